@@ -1,0 +1,246 @@
+"""CPU oracle of the CO3 gradient codec -- TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg may import
+this package.  The product (``paper_2203_09044_amd``) never does, and this
+package never imports the product.
+
+``co3_oracle.c`` is the scalar statement of every step of Algorithm 1's
+uplink path; this module is its ctypes binding plus the (numpy/scipy) model
+table of Sec. III (ii), where the Huffman code is designed from the GenNorm
+pdf instead of from data.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "co3_oracle.c")
+_LIB = os.path.join(_HERE, "libco3_oracle.so")
+
+OK, EINVAL, ECAP, ENOCODE, EBADSTREAM = 0, -1, -2, -3, -4
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (strict IEEE: no contraction, no fast-math)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + f".{os.getpid()}.tmp"
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared",
+             "-Wall", "-Wextra", "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = C.CDLL(build())
+        p = C.c_void_p
+        L.co3o_level.restype = C.c_double
+        L.co3o_level.argtypes = [C.c_int] * 5
+        L.co3o_quantize_value.restype = C.c_double
+        L.co3o_quantize_value.argtypes = [C.c_double, C.c_int, C.c_int, C.c_int]
+        L.co3o_quantize_values.restype = None
+        L.co3o_quantize_values.argtypes = [p, C.c_int64, C.c_int, C.c_int, C.c_int, p]
+        L.co3o_quantize_symbol.restype = C.c_int
+        L.co3o_quantize_symbol.argtypes = [C.c_float, C.c_int, C.c_int, C.c_int]
+        L.co3o_symbol_value.restype = C.c_float
+        L.co3o_symbol_value.argtypes = [C.c_int] * 4
+        L.co3o_anchor.argtypes = [p, C.c_int64, p, C.c_int, C.c_int, p]
+        L.co3o_convert_ef.argtypes = [p, p, p, C.c_int64, p, C.c_int, p, C.c_float, C.c_int, C.c_int]
+        L.co3o_histogram.argtypes = [p, C.c_int64, C.c_int, p]
+        L.co3o_huffman_lengths.argtypes = [p, C.c_int, p]
+        L.co3o_canonical_codes.argtypes = [p, C.c_int, p]
+        L.co3o_encode.argtypes = [p, C.c_int64, p, p, C.c_int, C.c_int64, p, C.c_int64, p, p]
+        L.co3o_decode.argtypes = [p, C.c_uint64, p, p, C.c_int, C.c_int64, p]
+        L.co3o_aggregate.argtypes = [p, C.c_int64, C.c_int, C.c_int64, p, C.c_int, p, C.c_int, C.c_int, p]
+        _lib = L
+    return _lib
+
+
+def _ptr(a: np.ndarray):
+    assert a.flags["C_CONTIGUOUS"]
+    return a.ctypes.data_as(C.c_void_p)
+
+
+class OracleError(RuntimeError):
+    def __init__(self, code):
+        super().__init__(f"oracle status {code}")
+        self.code = code
+
+
+def _check(rc):
+    if rc != OK:
+        raise OracleError(rc)
+
+
+@dataclass(frozen=True)
+class Fmt:
+    """Sign / exponent / mantissa format of Sec. III (i): 1 + E + M bits."""
+    E: int
+    M: int
+
+    @property
+    def K(self) -> int:
+        return 1 << (1 + self.E + self.M)
+
+    @property
+    def F(self) -> int:
+        return (1 << self.E) - 1
+
+
+def level(f, m, A, fmt: Fmt) -> float:
+    return lib().co3o_level(f, m, A, fmt.E, fmt.M)
+
+
+def quantize_value(x: float, A: int, E: int, M: int) -> float:
+    return lib().co3o_quantize_value(float(x), A, E, M)
+
+
+def quantize_values(x: np.ndarray, A: int, E: int, M: int) -> np.ndarray:
+    xs = np.ascontiguousarray(x, dtype=np.float32)
+    out = np.zeros(xs.shape, dtype=np.float64)
+    lib().co3o_quantize_values(_ptr(xs), xs.size, A, E, M, _ptr(out))
+    return out
+
+
+def quantize_symbol(x, A: int, fmt: Fmt) -> int:
+    return lib().co3o_quantize_symbol(np.float32(x), A, fmt.E, fmt.M)
+
+
+def symbol_value(sym: int, A: int, fmt: Fmt) -> np.float32:
+    return np.float32(lib().co3o_symbol_value(int(sym), A, fmt.E, fmt.M))
+
+
+def _seg(seg_off, n):
+    if seg_off is None:
+        seg_off = [0, n]
+    return np.ascontiguousarray(seg_off, dtype=np.int64)
+
+
+def anchor(g: np.ndarray, fmt: Fmt, seg_off=None) -> np.ndarray:
+    g = np.ascontiguousarray(g, dtype=np.float32)
+    so = _seg(seg_off, g.size)
+    out = np.zeros(so.size - 1, dtype=np.int32)
+    _check(lib().co3o_anchor(_ptr(g), g.size, _ptr(so), so.size - 1, fmt.E, _ptr(out)))
+    return out
+
+
+def convert_ef(g: np.ndarray, err: np.ndarray, anchors: np.ndarray, gamma: float, fmt: Fmt, seg_off=None):
+    """Returns (sym u8[n], new_err f32[n]); ``err`` is not modified."""
+    g = np.ascontiguousarray(g, dtype=np.float32)
+    e = np.array(err, dtype=np.float32, copy=True, order="C")
+    so = _seg(seg_off, g.size)
+    a = np.ascontiguousarray(anchors, dtype=np.int32)
+    assert a.size == so.size - 1 and e.size == g.size
+    sym = np.zeros(g.size, dtype=np.uint8)
+    _check(lib().co3o_convert_ef(_ptr(g), _ptr(e), _ptr(sym), g.size, _ptr(so), so.size - 1, _ptr(a),
+                                 C.c_float(gamma), fmt.E, fmt.M))
+    return sym, e
+
+
+def histogram(sym: np.ndarray, fmt: Fmt) -> np.ndarray:
+    sym = np.ascontiguousarray(sym, dtype=np.uint8)
+    cnt = np.zeros(fmt.K, dtype=np.uint32)
+    _check(lib().co3o_histogram(_ptr(sym), sym.size, fmt.K, _ptr(cnt)))
+    return cnt
+
+
+def huffman_lengths(weights: np.ndarray) -> np.ndarray:
+    w = np.ascontiguousarray(weights, dtype=np.uint32)
+    out = np.zeros(w.size, dtype=np.uint8)
+    _check(lib().co3o_huffman_lengths(_ptr(w), w.size, _ptr(out)))
+    return out
+
+
+def canonical_codes(lengths: np.ndarray) -> np.ndarray:
+    l = np.ascontiguousarray(lengths, dtype=np.uint8)
+    out = np.zeros(l.size, dtype=np.uint64)
+    _check(lib().co3o_canonical_codes(_ptr(l), l.size, _ptr(out)))
+    return out
+
+
+def encode(sym: np.ndarray, lengths: np.ndarray, codes: np.ndarray, chunk_syms: int, cap_words=None):
+    """Returns (words u64[cap], chunk_bitoff u64[nchunks+1], total_bits)."""
+    sym = np.ascontiguousarray(sym, dtype=np.uint8)
+    l = np.ascontiguousarray(lengths, dtype=np.uint8)
+    c = np.ascontiguousarray(codes, dtype=np.uint64)
+    n = sym.size
+    if cap_words is None:
+        cap_words = (int(l.max(initial=0)) * n + 63) // 64
+    nchunks = (n + chunk_syms - 1) // chunk_syms
+    words = np.zeros(max(cap_words, 1), dtype=np.uint64)
+    off = np.zeros(nchunks + 1, dtype=np.uint64)
+    total = C.c_uint64(0)
+    _check(lib().co3o_encode(_ptr(sym), n, _ptr(l), _ptr(c), l.size, chunk_syms, _ptr(words), cap_words,
+                             _ptr(off), C.byref(total)))
+    return words, off, int(total.value)
+
+
+def decode(words: np.ndarray, total_bits: int, lengths: np.ndarray, codes: np.ndarray, n: int) -> np.ndarray:
+    words = np.ascontiguousarray(words, dtype=np.uint64)
+    l = np.ascontiguousarray(lengths, dtype=np.uint8)
+    c = np.ascontiguousarray(codes, dtype=np.uint64)
+    out = np.zeros(n, dtype=np.uint8)
+    _check(lib().co3o_decode(_ptr(words), C.c_uint64(total_bits), _ptr(l), _ptr(c), l.size, n, _ptr(out)))
+    return out
+
+
+def aggregate(sym: np.ndarray, anchors: np.ndarray, fmt: Fmt, seg_off=None) -> np.ndarray:
+    """sym u8[U][n], anchors i32[U][nseg] -> mean f32[n] (users added in index order)."""
+    sym = np.ascontiguousarray(sym, dtype=np.uint8)
+    assert sym.ndim == 2
+    U, n = sym.shape
+    so = _seg(seg_off, n)
+    a = np.ascontiguousarray(anchors, dtype=np.int32).reshape(U, so.size - 1)
+    out = np.zeros(n, dtype=np.float32)
+    _check(lib().co3o_aggregate(_ptr(sym), n, U, n, _ptr(so), so.size - 1, _ptr(a), fmt.E, fmt.M, _ptr(out)))
+    return out
+
+
+# --------------------------------------------------------------------------
+# Sec. III (ii), model table: symbol probabilities of a quantised GenNorm
+# source.  Decision thresholds sit midway between adjacent levels; the zero
+# cell is symmetric; the top cell extends to infinity.  The negative-zero
+# pattern has probability 0.
+# --------------------------------------------------------------------------
+def gennorm_cdf(x, beta: float, alpha: float):
+    """CDF of the density proportional to exp(-(|x|/alpha)**beta)."""
+    from scipy.special import gammainc
+    x = np.asarray(x, dtype=np.float64)
+    with np.errstate(over="ignore"):
+        tail = gammainc(1.0 / beta, (np.abs(x) / alpha) ** beta)
+    return 0.5 + 0.5 * np.sign(x) * tail
+
+
+def model_pmf(A: int, fmt: Fmt, beta: float, alpha: float) -> np.ndarray:
+    half = fmt.K // 2
+    mags = np.array([level(c >> fmt.M, c & ((1 << fmt.M) - 1), A, fmt) for c in range(half)], dtype=np.float64)
+    mid = 0.5 * (mags[:-1] + mags[1:])
+    lo = np.concatenate([[0.0], mid])          # lower threshold of magnitude cell c
+    hi = np.concatenate([mid, [np.inf]])
+    cdf_lo = gennorm_cdf(lo, beta, alpha)
+    cdf_hi = gennorm_cdf(hi, beta, alpha)
+    p_mag = cdf_hi - cdf_lo                    # P(lo <= X < hi), X > 0 side
+    p = np.zeros(fmt.K, dtype=np.float64)
+    p[:half] = p_mag
+    p[half:] = p_mag
+    p[0] = 2.0 * p_mag[0]                      # symmetric zero cell
+    p[half] = 0.0                              # "-0" is never emitted
+    return p
+
+
+def model_weights(A: int, fmt: Fmt, beta: float, alpha: float) -> np.ndarray:
+    """Integer Huffman weights: round(p * 2^32) kept within [1, 2^32 - 1]."""
+    p = model_pmf(A, fmt, beta, alpha)
+    w = np.clip(np.rint(p * 4294967296.0), 1.0, 4294967295.0).astype(np.uint64).astype(np.uint32)
+    w[fmt.K // 2] = 0
+    return w
