@@ -1,0 +1,189 @@
+/*
+ * libco3 -- C ABI of the CO3 gradient codec hot path on one MI355X (gfx950).
+ *
+ * The calls follow one iteration of Algorithm 1 of "Convert, compress, correct":
+ * on the user side error correction + fp conversion (co3_convert_ef), the symbol
+ * statistics and the Huffman code (co3_histogram, co3_build_code), compression
+ * (co3_encode); on the parameter-server side decompression (co3_decode) and
+ * decompression + averaging over users (co3_ps_aggregate).  All U users of an
+ * iteration are batched in every call.
+ *
+ * Conventions for every call below, unless its comment says otherwise:
+ *   - every pointer is a DEVICE pointer owned by the caller; the library never
+ *     allocates, frees or keeps device memory, and keeps no state between calls;
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream); the
+ *     call only enqueues kernels on it and returns without waiting;
+ *   - batched arrays are laid out [U][stride] with `stride` in elements (>= n, and
+ *     a multiple of 16 when U > 1); float/word arrays must be 16-byte aligned;
+ *   - the return value is a host-side status: CO3_OK or a negative CO3_E* for
+ *     arguments rejected before anything was launched;
+ *   - conditions that only the device can see (capacity overrun, symbol without a
+ *     code, inconsistent stream) are reported through `status`, a caller-owned
+ *     device int32 that the caller zeroes once; kernels only ever lower it to a
+ *     negative CO3_E* value (the smallest wins) and never write out of bounds.
+ *     Read it with co3_poll_status.
+ *
+ * Format of the sign/exponent/mantissa representation (Sec. III (i)): 1 sign bit,
+ * E exponent bits, M mantissa bits, K = 2^(1+E+M) <= 256 symbols; symbol byte =
+ * sign << (E+M) | exponent field << M | mantissa field.  The exponent bias is an
+ * integer anchor A per (user, segment): exponent field f >= 1 is binade
+ * 2^(A - (2^E - 1) + f), field 0 holds the gradual-underflow levels (including 0),
+ * there are no Inf/NaN codes, and the negative-zero pattern is never produced.
+ *
+ * Format of a compressed stream (Sec. II-B: h is an invertible variable-length
+ * map; Sec. III (ii): element-wise Huffman): canonical Huffman codewords
+ * concatenated most-significant bit first; stream bit p is bit 63 - (p mod 64) of
+ * 64-bit word p / 64; the last word is zero padded.  chunk_bitoff[c] is the stream
+ * position of symbol c * chunk_syms, chunk_bitoff[nchunks] the stream length,
+ * nchunks = ceil(n / chunk_syms).  The wire header of a user is len[K] (the first K
+ * bytes of its code blob), its anchors and n.
+ */
+#ifndef CO3_H
+#define CO3_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct {
+    int32_t exp_bits;  /* E >= 1 */
+    int32_t mant_bits; /* M >= 0, 1 + E + M <= 8 */
+} co3_fmt;
+
+#define CO3_OK 0
+#define CO3_EINVAL (-1)     /* bad argument (format, size, alignment, null pointer) */
+#define CO3_ECAP (-2)       /* a stream would exceed cap_words; that user's stream is not written */
+#define CO3_ENOCODE (-3)    /* a symbol to encode has no codeword (possible with model tables) */
+#define CO3_EBADSTREAM (-4) /* decoder: a chunk did not end where the index says, or an invalid prefix */
+#define CO3_EHIP (-5)       /* a HIP runtime call failed */
+
+#define CO3_ANCHOR_GIVEN 0         /* anchor[] is an input */
+#define CO3_ANCHOR_FROM_ABSMAX_G 1 /* anchor[] is an output: binade of max|g| per (user, segment) */
+
+#define CO3_CODE_BYTES 12288 /* size of one user's code blob */
+
+/* ---- helpers (host only, no GPU work) ---------------------------------- */
+
+/* Human-readable name of a status code; never NULL. */
+const char *co3_strerror(int32_t status);
+
+/* Bytes of workspace co3_encode needs (one 64-bit partial sum per 2048 symbols and user). */
+size_t co3_encode_workspace_bytes(int64_t n, int32_t U);
+
+/* Bytes of workspace co3_ps_aggregate needs (the decoded symbols, U * stride bytes). */
+size_t co3_ps_aggregate_workspace_bytes(int64_t stride, int32_t U);
+
+/* Number of 64-bit words that always hold a stream coded with an empirical table built
+ * from the very symbols being coded (Huffman is then no longer than the fixed-length
+ * code): ceil(n * (1+E+M) / 64), rounded up to a multiple of 2. */
+int64_t co3_cap_words_empirical(int64_t n, co3_fmt fmt);
+
+/* Waits for `stream` and returns the device status word (CO3_OK if it is still 0),
+ * or CO3_EHIP.  status_dev: device int32. */
+int32_t co3_poll_status(const int32_t *status_dev, void *stream);
+
+/* ---- user side ---------------------------------------------------------- */
+
+/*
+ * Error correction + fp conversion + memory update (Algorithm 1: "fp-converts
+ * g + gamma*m" and "updates m"), for all users:
+ *     x = fl32(g + fl32(gamma * err));  sym = Q_A(x);  err = fl32(x - value_A(sym))
+ * Q_A rounds to the nearest level, ties to the even multiple of the local quantum;
+ * magnitudes above the top level saturate to it (the excess stays in err).
+ *
+ *   g      [U][stride] f32 in     gradients
+ *   err    [U][stride] f32 in/out memory m_{t-1} -> m_t (the only in/out buffer)
+ *   sym    [U][stride] u8  out    symbols
+ *   seg_off [nseg+1] i64 in       segment (tensor) boundaries, seg_off[0] = 0,
+ *                                 non-decreasing, seg_off[nseg] = n; NULL = one segment
+ *   anchor [U][nseg] i32          per anchor_mode; with FROM_ABSMAX_G it is computed as
+ *                                 floor(log2 max|g|) over the segment, clamped to
+ *                                 [2^E - 127, 127], from g (not from g + gamma*err)
+ *   counts [U][K] u32 out         optional (NULL to skip): symbol histogram of each user,
+ *                                 overwritten -- the fused form of co3_histogram
+ * n = 0 is allowed.  Non-finite inputs are not rejected: Inf saturates, NaN is unspecified.
+ */
+int32_t co3_convert_ef(const float *g, float *err, uint8_t *sym, int64_t n, int32_t U, int64_t stride,
+                       const int64_t *seg_off, int32_t nseg, int32_t *anchor, int32_t anchor_mode, float gamma,
+                       co3_fmt fmt, uint32_t *counts, void *stream);
+
+/*
+ * Empirical symbol counts per user (the stand-in for the symbol law that the Huffman
+ * design of Sec. III (ii) needs): counts[u][k] = #{i < n : sym[u][i] = k}, overwritten.
+ * Symbols >= K (cannot come from co3_convert_ef) are ignored.  n < 2^32.
+ */
+int32_t co3_histogram(const uint8_t *sym, int64_t n, int32_t U, int64_t stride, co3_fmt fmt, uint32_t *counts,
+                      void *stream);
+
+/*
+ * Huffman code per user from integer weights (Sec. III (ii)): empirical counts, or model
+ * weights of a quantised GenNorm law (co3_model_weights).  Symbols with weight 0 get no code.
+ * Lengths follow the two-queue construction on leaves sorted by (weight, symbol), a leaf
+ * winning a weight tie against a merged node; one active symbol gets the 1-bit code "0".
+ * Codewords are canonical: ordered by (length, symbol), first all zeros, each next one
+ * (previous + 1) << (length growth).
+ *
+ *   weights [U][K] u32 in
+ *   codes   [U][CO3_CODE_BYTES] out; bytes 0..K-1 of each blob are len[K]; the rest
+ *           (codewords, decoder tables) is private to the library.
+ */
+int32_t co3_build_code(const uint32_t *weights, int32_t U, co3_fmt fmt, void *codes, int32_t *status, void *stream);
+
+/*
+ * Compression h_Hf (Algorithm 1: "compresses ghat") of every user's symbols with its code.
+ *
+ *   words        [U][cap_words] u64 out  streams; words past ceil(total_bits/64) are untouched
+ *   chunk_syms   64, 128, ..., 2048 (power of two)
+ *   chunk_bitoff [U][nchunks+1] u64 out
+ *   total_bits   [U] u64 out
+ *   workspace    co3_encode_workspace_bytes(n, U) bytes, 8-byte aligned, contents unspecified
+ * Device-reported: CO3_ENOCODE, CO3_ECAP (nothing is written past cap_words).
+ */
+int32_t co3_encode(const uint8_t *sym, int64_t n, int32_t U, int64_t stride, co3_fmt fmt, const void *codes,
+                   uint64_t *words, int64_t cap_words, int32_t chunk_syms, uint64_t *chunk_bitoff,
+                   uint64_t *total_bits, void *workspace, size_t ws_bytes, int32_t *status, void *stream);
+
+/* ---- parameter-server side ---------------------------------------------- */
+
+/*
+ * Decompression (Algorithm 1: "PS decompresses all the users' gradients"): the inverse of
+ * co3_encode, chunk by chunk.  sym_out [U][stride] u8.  Device-reported: CO3_EBADSTREAM.
+ */
+int32_t co3_decode(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff, int32_t chunk_syms,
+                   const void *codes, co3_fmt fmt, int64_t n, int32_t U, uint8_t *sym_out, int64_t stride,
+                   int32_t *status, void *stream);
+
+/*
+ * Decompression + average over users (Sec. II-A, the aggregate (1/U) * sum_u ghat^(u); the
+ * learning-rate step on the model is the caller's):
+ *     avg[i] = fl32( (((0 + v_0) + v_1) + ... + v_{U-1}) / U ),  v_u = value_{A_u}(symbol i of user u)
+ * added in user-index order in fp32, one fp32 division.
+ *
+ *   anchor    [U][nseg] i32 in, seg_off as in co3_convert_ef
+ *   avg_out   [n] f32 out
+ *   workspace co3_ps_aggregate_workspace_bytes(stride16, U) bytes with stride16 = n rounded up
+ *             to a multiple of 16; holds the decoded symbols
+ */
+int32_t co3_ps_aggregate(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff, int32_t chunk_syms,
+                         const void *codes, co3_fmt fmt, int64_t n, int32_t U, const int32_t *anchor,
+                         const int64_t *seg_off, int32_t nseg, float *avg_out, void *workspace, size_t ws_bytes,
+                         int32_t *status, void *stream);
+
+/* ---- model table (host only) -------------------------------------------- */
+
+/*
+ * Integer Huffman weights of a GenNorm(beta, scale alpha) source quantised with anchor A
+ * (Sec. III (ii): the code is designed from the assumed GenNorm law, not from data).
+ * Cell boundaries are the midpoints between adjacent levels, the zero cell is symmetric, the
+ * top cell is unbounded; weight = round(p * 2^32) kept within [1, 2^32-1]; the negative-zero
+ * symbol gets 0.  weights_host: HOST pointer to K uint32.  Pure host arithmetic.
+ */
+int32_t co3_model_weights(int32_t A, co3_fmt fmt, double beta, double alpha, uint32_t *weights_host);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CO3_H */

@@ -1,0 +1,198 @@
+"""ctypes binding of libco3: argument marshalling only.
+
+Every function has the name and meaning of the C entry point in ``include/co3.h``.
+Tensors are torch CUDA tensors (PyTorch is used for device memory and streams only);
+all arithmetic of the codec runs in the HIP kernels of the library.  There is no
+fallback: if the library is missing, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libco3.so")
+
+OK, EINVAL, ECAP, ENOCODE, EBADSTREAM, EHIP = 0, -1, -2, -3, -4, -5
+ANCHOR_GIVEN, ANCHOR_FROM_ABSMAX_G = 0, 1
+CODE_BYTES = 12288
+PACK_SYMS = 2048
+
+EXPORTS = (
+    "co3_strerror", "co3_encode_workspace_bytes", "co3_ps_aggregate_workspace_bytes", "co3_cap_words_empirical",
+    "co3_poll_status", "co3_convert_ef", "co3_histogram", "co3_build_code", "co3_encode", "co3_decode",
+    "co3_ps_aggregate", "co3_model_weights",
+)
+
+
+class _Fmt(C.Structure):
+    _fields_ = [("exp_bits", C.c_int32), ("mant_bits", C.c_int32)]
+
+
+@dataclass(frozen=True)
+class Fmt:
+    """1 sign bit, E exponent bits, M mantissa bits."""
+    E: int
+    M: int
+
+    @property
+    def K(self) -> int:
+        return 1 << (1 + self.E + self.M)
+
+    @property
+    def bits(self) -> int:
+        return 1 + self.E + self.M
+
+    def c(self) -> _Fmt:
+        return _Fmt(self.E, self.M)
+
+
+class Co3Error(RuntimeError):
+    def __init__(self, code: int, where: str):
+        super().__init__(f"{where}: {strerror(code)} ({code})")
+        self.code = code
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'`")
+    L = C.CDLL(LIB_PATH)
+    p, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+    L.co3_strerror.restype = C.c_char_p
+    L.co3_strerror.argtypes = [i32]
+    L.co3_encode_workspace_bytes.restype = sz
+    L.co3_encode_workspace_bytes.argtypes = [i64, i32]
+    L.co3_ps_aggregate_workspace_bytes.restype = sz
+    L.co3_ps_aggregate_workspace_bytes.argtypes = [i64, i32]
+    L.co3_cap_words_empirical.restype = i64
+    L.co3_cap_words_empirical.argtypes = [i64, _Fmt]
+    L.co3_poll_status.restype = i32
+    L.co3_poll_status.argtypes = [p, p]
+    L.co3_convert_ef.restype = i32
+    L.co3_convert_ef.argtypes = [p, p, p, i64, i32, i64, p, i32, p, i32, C.c_float, _Fmt, p, p]
+    L.co3_histogram.restype = i32
+    L.co3_histogram.argtypes = [p, i64, i32, i64, _Fmt, p, p]
+    L.co3_build_code.restype = i32
+    L.co3_build_code.argtypes = [p, i32, _Fmt, p, p, p]
+    L.co3_encode.restype = i32
+    L.co3_encode.argtypes = [p, i64, i32, i64, _Fmt, p, p, i64, i32, p, p, p, sz, p, p]
+    L.co3_decode.restype = i32
+    L.co3_decode.argtypes = [p, i64, p, i32, p, _Fmt, i64, i32, p, i64, p, p]
+    L.co3_ps_aggregate.restype = i32
+    L.co3_ps_aggregate.argtypes = [p, i64, p, i32, p, _Fmt, i64, i32, p, p, i32, p, p, sz, p, p]
+    L.co3_model_weights.restype = i32
+    L.co3_model_weights.argtypes = [i32, _Fmt, C.c_double, C.c_double, p]
+    return L
+
+
+_lib = _load()
+
+
+def _dp(t, dtype=None):
+    """Device pointer of a contiguous CUDA tensor (None -> NULL)."""
+    if t is None:
+        return None
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous()):
+        raise TypeError("expected a contiguous CUDA tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"expected dtype {dtype}, got {t.dtype}")
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream(stream=None):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def _chk(rc: int, where: str):
+    if rc != OK:
+        raise Co3Error(rc, where)
+
+
+def _batch(t):
+    """(U, n_or_stride) of a [U][stride] tensor (1-D tensors are one user)."""
+    if t.dim() == 1:
+        return 1, t.shape[0]
+    if t.dim() != 2:
+        raise ValueError("expected a 1-D or 2-D tensor")
+    return t.shape[0], t.shape[1]
+
+
+def strerror(code: int) -> str:
+    return _lib.co3_strerror(code).decode()
+
+
+def encode_workspace_bytes(n: int, U: int) -> int:
+    return _lib.co3_encode_workspace_bytes(n, U)
+
+
+def ps_aggregate_workspace_bytes(stride: int, U: int) -> int:
+    return _lib.co3_ps_aggregate_workspace_bytes(stride, U)
+
+
+def cap_words_empirical(n: int, fmt: Fmt) -> int:
+    return _lib.co3_cap_words_empirical(n, fmt.c())
+
+
+def poll_status(status, stream=None) -> int:
+    return _lib.co3_poll_status(_dp(status, torch.int32), _stream(stream))
+
+
+def convert_ef(g, err, sym, n, anchor, anchor_mode, gamma, fmt: Fmt, seg_off=None, counts=None, stream=None):
+    U, stride = _batch(g)
+    nseg = 1 if seg_off is None else seg_off.numel() - 1
+    rc = _lib.co3_convert_ef(_dp(g, torch.float32), _dp(err, torch.float32), _dp(sym, torch.uint8), n, U, stride,
+                             _dp(seg_off, torch.int64), nseg, _dp(anchor, torch.int32), anchor_mode,
+                             C.c_float(gamma), fmt.c(), _dp(counts, torch.int32), _stream(stream))
+    _chk(rc, "co3_convert_ef")
+
+
+def histogram(sym, n, fmt: Fmt, counts, stream=None):
+    U, stride = _batch(sym)
+    _chk(_lib.co3_histogram(_dp(sym, torch.uint8), n, U, stride, fmt.c(), _dp(counts, torch.int32), _stream(stream)),
+         "co3_histogram")
+
+
+def build_code(weights, U, fmt: Fmt, codes, status, stream=None):
+    _chk(_lib.co3_build_code(_dp(weights, torch.int32), U, fmt.c(), _dp(codes, torch.uint8),
+                             _dp(status, torch.int32), _stream(stream)), "co3_build_code")
+
+
+def encode(sym, n, fmt: Fmt, codes, words, chunk_syms, chunk_bitoff, total_bits, workspace, status, stream=None):
+    U, stride = _batch(sym)
+    cap_words = words.shape[-1]
+    rc = _lib.co3_encode(_dp(sym, torch.uint8), n, U, stride, fmt.c(), _dp(codes, torch.uint8),
+                         _dp(words, torch.int64), cap_words, chunk_syms, _dp(chunk_bitoff, torch.int64),
+                         _dp(total_bits, torch.int64), _dp(workspace), workspace.numel() * workspace.element_size(),
+                         _dp(status, torch.int32), _stream(stream))
+    _chk(rc, "co3_encode")
+
+
+def decode(words, chunk_bitoff, chunk_syms, codes, fmt: Fmt, n, sym_out, status, stream=None):
+    U, stride = _batch(sym_out)
+    rc = _lib.co3_decode(_dp(words, torch.int64), words.shape[-1], _dp(chunk_bitoff, torch.int64), chunk_syms,
+                         _dp(codes, torch.uint8), fmt.c(), n, U, _dp(sym_out, torch.uint8), stride,
+                         _dp(status, torch.int32), _stream(stream))
+    _chk(rc, "co3_decode")
+
+
+def ps_aggregate(words, chunk_bitoff, chunk_syms, codes, fmt: Fmt, n, U, anchor, avg_out, workspace, status,
+                 seg_off=None, stream=None):
+    nseg = 1 if seg_off is None else seg_off.numel() - 1
+    rc = _lib.co3_ps_aggregate(_dp(words, torch.int64), words.shape[-1], _dp(chunk_bitoff, torch.int64), chunk_syms,
+                               _dp(codes, torch.uint8), fmt.c(), n, U, _dp(anchor, torch.int32),
+                               _dp(seg_off, torch.int64), nseg, _dp(avg_out, torch.float32), _dp(workspace),
+                               workspace.numel() * workspace.element_size(), _dp(status, torch.int32),
+                               _stream(stream))
+    _chk(rc, "co3_ps_aggregate")
+
+
+def model_weights(A: int, fmt: Fmt, beta: float, alpha: float):
+    """Host computation; returns a CPU int32 tensor holding the K uint32 weights bit-for-bit."""
+    import numpy as np
+    w = np.zeros(fmt.K, dtype=np.uint32)
+    _chk(_lib.co3_model_weights(A, fmt.c(), beta, alpha, w.ctypes.data_as(C.c_void_p)), "co3_model_weights")
+    return torch.from_numpy(w.view(np.int32).copy())

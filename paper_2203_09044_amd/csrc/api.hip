@@ -1,0 +1,224 @@
+// extern "C" boundary of libco3: argument validation and kernel sequencing only.
+#include <math.h>
+
+#include "co3_dev.h"
+#include "kernels.h"
+
+namespace {
+
+bool fmt_ok(co3_fmt f)
+{
+    return f.exp_bits >= 1 && f.mant_bits >= 0 && 1 + f.exp_bits + f.mant_bits <= 8;
+}
+
+bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+bool batch_ok(int64_t n, int32_t U, int64_t stride)
+{
+    if (n < 0 || U < 1 || n >= ((int64_t)1 << 32)) return false;
+    if (U > 1 && (stride < n || stride % 16 != 0)) return false;
+    return true;
+}
+
+bool chunk_ok(int32_t c) { return c >= 64 && c <= CO3_PACK_SYMS && (c & (c - 1)) == 0; }
+
+int32_t hip_rc(hipError_t e) { return e == hipSuccess ? CO3_OK : CO3_EHIP; }
+
+}  // namespace
+
+extern "C" {
+
+const char *co3_strerror(int32_t status)
+{
+    switch (status) {
+    case CO3_OK: return "ok";
+    case CO3_EINVAL: return "invalid argument";
+    case CO3_ECAP: return "stream capacity exceeded";
+    case CO3_ENOCODE: return "symbol without a codeword";
+    case CO3_EBADSTREAM: return "inconsistent stream";
+    case CO3_EHIP: return "HIP runtime error";
+    default: return "unknown status";
+    }
+}
+
+size_t co3_encode_workspace_bytes(int64_t n, int32_t U)
+{
+    if (n < 0 || U < 1) return 0;
+    int64_t nblk = (n + CO3_PACK_SYMS - 1) / CO3_PACK_SYMS;
+    return (size_t)(nblk > 0 ? nblk : 1) * (size_t)U * sizeof(uint64_t);
+}
+
+size_t co3_ps_aggregate_workspace_bytes(int64_t stride, int32_t U)
+{
+    if (stride < 0 || U < 1) return 0;
+    return (size_t)stride * (size_t)U;
+}
+
+int64_t co3_cap_words_empirical(int64_t n, co3_fmt fmt)
+{
+    if (n < 0 || !fmt_ok(fmt)) return 0;
+    int64_t w = (n * (1 + fmt.exp_bits + fmt.mant_bits) + 63) / 64;
+    return (w + 1) & ~(int64_t)1;
+}
+
+int32_t co3_poll_status(const int32_t *status_dev, void *stream)
+{
+    if (!status_dev) return CO3_EINVAL;
+    int32_t h = 0;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (hipMemcpyAsync(&h, status_dev, sizeof(h), hipMemcpyDeviceToHost, st) != hipSuccess) return CO3_EHIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return CO3_EHIP;
+    return h;
+}
+
+int32_t co3_convert_ef(const float *g, float *err, uint8_t *sym, int64_t n, int32_t U, int64_t stride,
+                       const int64_t *seg_off, int32_t nseg, int32_t *anchor, int32_t anchor_mode, float gamma,
+                       co3_fmt fmt, uint32_t *counts, void *stream)
+{
+    if (!fmt_ok(fmt) || !batch_ok(n, U, stride) || nseg < 1 || (seg_off == nullptr && nseg != 1)) return CO3_EINVAL;
+    if (!g || !err || !sym || !anchor) return CO3_EINVAL;
+    if (!aligned(g, 16) || !aligned(err, 16) || !aligned(sym, 16)) return CO3_EINVAL;
+    if (anchor_mode != CO3_ANCHOR_GIVEN && anchor_mode != CO3_ANCHOR_FROM_ABSMAX_G) return CO3_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const FmtC fc(fmt);
+    const bool from_g = anchor_mode == CO3_ANCHOR_FROM_ABSMAX_G;
+    hipError_t e = co3_launch_fill(from_g ? anchor : nullptr, from_g ? (int64_t)U * nseg : 0, fc.F - 126, counts,
+                                   counts ? (int64_t)U * fc.K : 0, st);
+    if (e != hipSuccess) return CO3_EHIP;
+    if (from_g) {
+        e = co3_launch_absmax(g, n, U, stride, seg_off, nseg, anchor, st);
+        if (e != hipSuccess) return CO3_EHIP;
+    }
+    return hip_rc(co3_launch_convert(g, err, sym, n, U, stride, seg_off, nseg, anchor, gamma, fmt, counts, st));
+}
+
+int32_t co3_histogram(const uint8_t *sym, int64_t n, int32_t U, int64_t stride, co3_fmt fmt, uint32_t *counts,
+                      void *stream)
+{
+    if (!fmt_ok(fmt) || !batch_ok(n, U, stride) || !sym || !counts || !aligned(sym, 16)) return CO3_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const FmtC fc(fmt);
+    hipError_t e = co3_launch_fill(nullptr, 0, 0, counts, (int64_t)U * fc.K, st);
+    if (e != hipSuccess) return CO3_EHIP;
+    return hip_rc(co3_launch_histogram(sym, n, U, stride, fc.K, counts, st));
+}
+
+int32_t co3_build_code(const uint32_t *weights, int32_t U, co3_fmt fmt, void *codes, int32_t *status, void *stream)
+{
+    if (!fmt_ok(fmt) || U < 1 || !weights || !codes || !aligned(codes, 8)) return CO3_EINVAL;
+    const FmtC fc(fmt);
+    return hip_rc(co3_launch_build_code(weights, U, fc.K, codes, status, static_cast<hipStream_t>(stream)));
+}
+
+int32_t co3_encode(const uint8_t *sym, int64_t n, int32_t U, int64_t stride, co3_fmt fmt, const void *codes,
+                   uint64_t *words, int64_t cap_words, int32_t chunk_syms, uint64_t *chunk_bitoff,
+                   uint64_t *total_bits, void *workspace, size_t ws_bytes, int32_t *status, void *stream)
+{
+    if (!fmt_ok(fmt) || !batch_ok(n, U, stride) || !chunk_ok(chunk_syms) || cap_words < 0) return CO3_EINVAL;
+    if (!sym || !codes || !words || !chunk_bitoff || !total_bits || !workspace) return CO3_EINVAL;
+    if (!aligned(sym, 16) || !aligned(words, 8) || !aligned(codes, 8) || !aligned(workspace, 8)) return CO3_EINVAL;
+    if (ws_bytes < co3_encode_workspace_bytes(n, U)) return CO3_EINVAL;
+    return hip_rc(co3_launch_encode(sym, n, U, stride, codes, words, cap_words, chunk_syms, chunk_bitoff, total_bits,
+                                    static_cast<uint64_t *>(workspace), status, static_cast<hipStream_t>(stream)));
+}
+
+int32_t co3_decode(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff, int32_t chunk_syms,
+                   const void *codes, co3_fmt fmt, int64_t n, int32_t U, uint8_t *sym_out, int64_t stride,
+                   int32_t *status, void *stream)
+{
+    if (!fmt_ok(fmt) || !batch_ok(n, U, stride) || !chunk_ok(chunk_syms) || cap_words < 0) return CO3_EINVAL;
+    if (!words || !chunk_bitoff || !codes || !sym_out) return CO3_EINVAL;
+    if (!aligned(sym_out, 16) || !aligned(words, 8) || !aligned(codes, 8)) return CO3_EINVAL;
+    return hip_rc(co3_launch_decode(words, cap_words, chunk_bitoff, chunk_syms, codes, n, U, sym_out, stride, status,
+                                    static_cast<hipStream_t>(stream)));
+}
+
+int32_t co3_ps_aggregate(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff, int32_t chunk_syms,
+                         const void *codes, co3_fmt fmt, int64_t n, int32_t U, const int32_t *anchor,
+                         const int64_t *seg_off, int32_t nseg, float *avg_out, void *workspace, size_t ws_bytes,
+                         int32_t *status, void *stream)
+{
+    if (!fmt_ok(fmt) || n < 0 || n >= ((int64_t)1 << 32) || U < 1 || !chunk_ok(chunk_syms) || cap_words < 0)
+        return CO3_EINVAL;
+    if (nseg < 1 || (seg_off == nullptr && nseg != 1)) return CO3_EINVAL;
+    if (!words || !chunk_bitoff || !codes || !anchor || !avg_out || !workspace) return CO3_EINVAL;
+    if (!aligned(avg_out, 16) || !aligned(workspace, 16) || !aligned(words, 8) || !aligned(codes, 8)) return CO3_EINVAL;
+    const int64_t stride = (n + 15) & ~(int64_t)15;
+    if (ws_bytes < co3_ps_aggregate_workspace_bytes(stride, U)) return CO3_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    uint8_t *symws = static_cast<uint8_t *>(workspace);
+    hipError_t e = co3_launch_decode(words, cap_words, chunk_bitoff, chunk_syms, codes, n, U, symws, stride, status, st);
+    if (e != hipSuccess) return CO3_EHIP;
+    return hip_rc(co3_launch_ps_sum(symws, n, U, stride, anchor, seg_off, nseg, fmt, avg_out, st));
+}
+
+// ---- model table (host arithmetic only) ---------------------------------------------------
+
+// Regularised lower incomplete gamma function P(a, x), a > 0, x >= 0: power series for x < a + 1,
+// continued fraction for the complement otherwise.
+static double reg_lower_gamma(double a, double x)
+{
+    if (!(x > 0.0)) return 0.0;
+    if (isinf(x)) return 1.0;
+    const double lg = lgamma(a);
+    if (x < a + 1.0) {
+        double term = 1.0 / a, sum = term, ap = a;
+        for (int it = 0; it < 100000; ++it) {
+            ap += 1.0;
+            term *= x / ap;
+            sum += term;
+            if (fabs(term) < fabs(sum) * 1e-17) break;
+        }
+        return sum * exp(-x + a * log(x) - lg);
+    }
+    const double tiny = 1e-300;
+    double b = x + 1.0 - a, c = 1.0 / tiny, d = 1.0 / b, h = d;
+    for (int it = 1; it < 100000; ++it) {
+        double an = -(double)it * ((double)it - a);
+        b += 2.0;
+        d = an * d + b;
+        if (fabs(d) < tiny) d = tiny;
+        c = b + an / c;
+        if (fabs(c) < tiny) c = tiny;
+        d = 1.0 / d;
+        double delta = d * c;
+        h *= delta;
+        if (fabs(delta - 1.0) < 1e-16) break;
+    }
+    double qv = exp(-x + a * log(x) - lg) * h;
+    return 1.0 - qv;
+}
+
+static double gennorm_cdf_pos(double x, double beta, double alpha)   // x >= 0
+{
+    return 0.5 + 0.5 * reg_lower_gamma(1.0 / beta, pow(x / alpha, beta));
+}
+
+int32_t co3_model_weights(int32_t A, co3_fmt fmt, double beta, double alpha, uint32_t *weights_host)
+{
+    if (!fmt_ok(fmt) || !weights_host || !(beta > 0.0) || !(alpha > 0.0)) return CO3_EINVAL;
+    const FmtC fc(fmt);
+    const int half = fc.K / 2;
+    const int e_min = A - fc.F + 1;
+    double mags[128];
+    for (int c = 0; c < half; ++c) {
+        int f = c >> fc.M, m = c & ((1 << fc.M) - 1);
+        double frac = (double)m / (double)(1 << fc.M);
+        mags[c] = f ? ldexp(1.0 + frac, e_min + f - 1) : ldexp(frac, e_min);
+    }
+    for (int c = 0; c < half; ++c) {
+        double lo = c ? 0.5 * (mags[c - 1] + mags[c]) : 0.0;
+        double cdf_lo = gennorm_cdf_pos(lo, beta, alpha);
+        double cdf_hi = (c + 1 < half) ? gennorm_cdf_pos(0.5 * (mags[c] + mags[c + 1]), beta, alpha) : 1.0;
+        double p = cdf_hi - cdf_lo;
+        if (c == 0) p *= 2.0;      // the zero cell is symmetric about 0
+        double w = nearbyint(p * 4294967296.0);
+        if (!(w >= 1.0)) w = 1.0;
+        if (w > 4294967295.0) w = 4294967295.0;
+        weights_host[c] = (uint32_t)w;
+        weights_host[half + c] = c ? (uint32_t)w : 0u;
+    }
+    return CO3_OK;
+}
+
+}  // extern "C"

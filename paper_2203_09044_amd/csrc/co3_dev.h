@@ -1,0 +1,94 @@
+// Shared device-side definitions of libco3 (gfx950, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/co3.h"
+
+#define CO3_WAVE 64
+#define CO3_LUT_BITS_MAX 12
+#define CO3_MAX_CODE_LEN 57     // (code << 6 | len) must fit 64 bits; u32 weights cannot reach it
+#define CO3_PACK_SYMS 2048      // symbols per encoder block (256 threads x 8)
+
+// Per-user code blob.  Bytes 0..K-1 (len) are the public wire header; the rest is private.
+struct Co3Code {
+    uint8_t len[256];          // code length per symbol, 0 = no code
+    uint64_t enc[256];         // (codeword << 6) | length
+    uint64_t first_code[65];   // right-aligned first codeword of each length (canonical order)
+    uint16_t count[66];        // number of codewords of each length
+    uint16_t base[66];         // index into sorted[] of the first symbol of each length
+    uint8_t sorted[256];       // symbols ordered by (length, symbol)
+    uint32_t nact;             // symbols that have a code
+    uint32_t maxlen;           // longest code length
+    uint32_t lut_bits;         // decoder table is indexed by this many leading bits
+    uint32_t reserved;
+    uint16_t lut[1 << CO3_LUT_BITS_MAX];   // (length << 8) | symbol, 0 = longer than lut_bits or invalid
+};
+static_assert(sizeof(Co3Code) <= CO3_CODE_BYTES, "code blob size");
+
+// Derived constants of a sign/exponent/mantissa format (Sec. III (i)).
+struct FmtC {
+    int E, M;
+    int F;          // top exponent field, 2^E - 1
+    int K;          // alphabet size
+    int codemax;    // largest magnitude code, 2^(E+M) - 1
+    __host__ __device__ FmtC(co3_fmt f)
+        : E(f.exp_bits), M(f.mant_bits), F((1 << f.exp_bits) - 1), K(1 << (1 + f.exp_bits + f.mant_bits)),
+          codemax((1 << (f.exp_bits + f.mant_bits)) - 1) {}
+};
+
+__device__ __forceinline__ void co3_raise(int32_t *status, int32_t code)
+{
+    if (status) atomicMin(status, code);
+}
+
+// Number of k in [1, nseg] with seg_off[k] <= i, kept below nseg: the segment that holds element i.
+__device__ __forceinline__ int co3_find_seg(const int64_t *seg_off, int nseg, int64_t i)
+{
+    if (seg_off == nullptr || nseg <= 1) return 0;
+    int lo = 1, hi = nseg + 1;   // first k in [1, nseg] with seg_off[k] > i, or nseg + 1
+    while (lo < hi) {
+        int mid = (lo + hi) >> 1;
+        if (seg_off[mid] <= i) lo = mid + 1; else hi = mid;
+    }
+    int s = lo - 1;
+    return s > nseg - 1 ? nseg - 1 : s;
+}
+
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
+{
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+        uint32_t t = (uint32_t)__shfl_xor((int)v, o, CO3_WAVE);
+        v = t > v ? t : v;
+    }
+    return v;
+}
+
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v)
+{
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v += (uint32_t)__shfl_xor((int)v, o, CO3_WAVE);
+    return v;
+}
+
+// inclusive prefix sum across the 64 lanes of a wavefront
+__device__ __forceinline__ uint32_t wave_scan_incl_u32(uint32_t v, int lane)
+{
+#pragma unroll
+    for (int o = 1; o < CO3_WAVE; o <<= 1) {
+        uint32_t t = (uint32_t)__shfl_up((int)v, o, CO3_WAVE);
+        if (lane >= o) v += t;
+    }
+    return v;
+}
+
+// Value of a magnitude code under e_min = A - F + 1 (Sec. III (i)): exponent field f >= 1 is
+// (1 + m/2^M) * 2^(e_min + f - 1); field 0 is (m/2^M) * 2^e_min.
+__device__ __forceinline__ float co3_code_value(uint32_t code, int e_min, int M)
+{
+    uint32_t f = code >> M;
+    uint32_t nbits = (code << (23 - M)) + ((uint32_t)(e_min - 1 + 127) << 23);
+    float sub = ldexpf((float)code, e_min - M);
+    return f ? __uint_as_float(nbits) : sub;
+}

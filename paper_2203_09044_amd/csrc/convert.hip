@@ -1,0 +1,309 @@
+// User side of Algorithm 1: exponent anchor, error correction + fp conversion + memory update,
+// symbol histogram.  Streaming kernels: every block owns a contiguous range of one user's vector.
+#include "co3_dev.h"
+#include "kernels.h"
+
+#define CV_BLOCK 256
+#define CV_VEC 4                       // elements per thread per step (one 16-byte load)
+#define CV_TILE (CV_BLOCK * CV_VEC)    // elements per block step
+#define HIST_SLOTS 1024                // LDS counters per wavefront
+
+// ------------------------------------------------------------------------------------------
+// initial values: anchors start at the lower clamp (so atomicMax applies it), counts at zero
+// ------------------------------------------------------------------------------------------
+__global__ void k_fill_i32(int32_t *a, int64_t na, int32_t va, uint32_t *b, int64_t nb)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t step = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t j = i; j < na; j += step) a[j] = va;
+    for (int64_t j = i; j < nb; j += step) b[j] = 0u;
+}
+
+// ------------------------------------------------------------------------------------------
+// anchor: A = floor(log2 max|g|) per (user, segment) = biased exponent of the largest magnitude
+// minus 127, at most 127; the lower clamp comes from the initial value.
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ void absmax_flush(uint32_t m, int32_t *anchor_us)
+{
+    m = wave_max_u32(m);
+    if ((threadIdx.x & (CO3_WAVE - 1)) == 0) {
+        int cand = (int)(m >> 23) - 127;
+        if (cand > 127) cand = 127;
+        atomicMax(anchor_us, cand);
+    }
+}
+
+__global__ __launch_bounds__(CV_BLOCK) void k_absmax(const float *__restrict__ g, int64_t n, int64_t stride,
+                                                      const int64_t *__restrict__ seg_off, int nseg,
+                                                      int32_t *__restrict__ anchor, int64_t per_block)
+{
+    const int u = blockIdx.y;
+    const float *gu = g + (int64_t)u * stride;
+    int32_t *anchor_u = anchor + (int64_t)u * nseg;
+    int64_t beg = (int64_t)blockIdx.x * per_block;
+    int64_t end = beg + per_block < n ? beg + per_block : n;
+    if (beg >= end) return;
+
+    int cur_seg = co3_find_seg(seg_off, nseg, beg);
+    uint32_t m = 0;
+    for (int64_t t0 = beg; t0 < end; t0 += CV_TILE) {
+        int64_t t1 = t0 + CV_TILE < end ? t0 + CV_TILE : end;
+        int s_lo = co3_find_seg(seg_off, nseg, t0);
+        int s_hi = co3_find_seg(seg_off, nseg, t1 - 1);
+        int64_t i = t0 + (int64_t)threadIdx.x * CV_VEC;
+        if (s_lo == s_hi) {
+            if (s_lo != cur_seg) {       // block-uniform branch
+                absmax_flush(m, anchor_u + cur_seg);
+                m = 0;
+                cur_seg = s_lo;
+            }
+            if (i + CV_VEC <= t1) {
+                float4 v = *reinterpret_cast<const float4 *>(gu + i);
+                uint32_t a0 = __float_as_uint(v.x) & 0x7fffffffu, a1 = __float_as_uint(v.y) & 0x7fffffffu;
+                uint32_t a2 = __float_as_uint(v.z) & 0x7fffffffu, a3 = __float_as_uint(v.w) & 0x7fffffffu;
+                a0 = a0 > a1 ? a0 : a1;
+                a2 = a2 > a3 ? a2 : a3;
+                a0 = a0 > a2 ? a0 : a2;
+                m = m > a0 ? m : a0;
+            } else {
+                for (int64_t j = i; j < t1; ++j) {
+                    uint32_t a = __float_as_uint(gu[j]) & 0x7fffffffu;
+                    m = m > a ? m : a;
+                }
+            }
+        } else {                         // tile straddles tensors: per element
+            for (int64_t j = i; j < i + CV_VEC && j < t1; ++j) {
+                uint32_t a = __float_as_uint(gu[j]) & 0x7fffffffu;
+                int cand = (int)(a >> 23) - 127;
+                if (cand > 127) cand = 127;
+                int s = co3_find_seg(seg_off, nseg, j);
+                atomicMax(anchor_u + s, cand);
+            }
+        }
+    }
+    absmax_flush(m, anchor_u + cur_seg);
+}
+
+// ------------------------------------------------------------------------------------------
+// Q_A on one value (Sec. III (i), nearest level, ties to even, saturating), returning the symbol
+// byte and its value.  All steps are exact: scaling by a power of two, rint, scaling back.
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ void co3_quantize(float x, int e_min, int A, int E, int M, int codemax, uint32_t &sym,
+                                             float &val)
+{
+    uint32_t bits = __float_as_uint(x);
+    uint32_t abits = bits & 0x7fffffffu;
+    float a = __uint_as_float(abits);
+    int ex = (int)(abits >> 23) - 127;          // fp32 subnormals read -127, below every e_min
+    int e = ex > e_min ? ex : e_min;            // clamped exponent
+    int qe = e - M;                             // exponent of the local quantum
+    float t = ldexpf(a, -qe);                   // |x| in quanta: exact, < 2^(M+1) for finite x
+    t = fminf(t, (float)(4 << M));              // Inf/NaN: keep the integer conversion defined
+    float r = rintf(t);                         // ties to even
+    int code = ((e - e_min) << M) + (int)r;     // a carry out of the mantissa lands in the next field
+    float mag = ldexpf(r, qe);
+    if (code > codemax) {                       // above the top binade
+        code = codemax;
+        mag = ldexpf((float)((2 << M) - 1), A - M);
+    }
+    uint32_t s = code ? (bits >> 31) : 0u;      // one zero only
+    sym = (s << (E + M)) | (uint32_t)code;
+    val = __uint_as_float(__float_as_uint(mag) | (s << 31));
+}
+
+template <bool HIST>
+__global__ __launch_bounds__(CV_BLOCK) void k_convert_ef(const float *__restrict__ g, float *__restrict__ err,
+                                                          uint8_t *__restrict__ sym, int64_t n, int64_t stride,
+                                                          const int64_t *__restrict__ seg_off, int nseg,
+                                                          const int32_t *__restrict__ anchor, float gamma, co3_fmt fmt,
+                                                          uint32_t *__restrict__ counts, int64_t per_block)
+{
+    const FmtC fc(fmt);
+    const int E = fc.E, M = fc.M, F = fc.F, K = fc.K, codemax = fc.codemax;
+    const int u = blockIdx.y;
+    const float *gu = g + (int64_t)u * stride;
+    float *eu = err + (int64_t)u * stride;
+    uint8_t *su = sym + (int64_t)u * stride;
+    const int32_t *anchor_u = anchor + (int64_t)u * nseg;
+    const int lane = threadIdx.x & (CO3_WAVE - 1);
+    const int wave = threadIdx.x / CO3_WAVE;
+
+    // per-wavefront private histogram: `copies` interleaved replicas of the K counters so that
+    // lanes hitting one popular symbol spread over banks
+    __shared__ uint32_t hist[CV_BLOCK / CO3_WAVE][HIST_SLOTS];
+    const int copies = HIST_SLOTS / K > 32 ? 32 : HIST_SLOTS / K;
+    uint32_t *myhist = hist[wave];
+    const int mycopy = lane & (copies - 1);
+    if (HIST) {
+        for (int j = threadIdx.x; j < (CV_BLOCK / CO3_WAVE) * HIST_SLOTS; j += CV_BLOCK) (&hist[0][0])[j] = 0;
+        __syncthreads();
+    }
+
+    int64_t beg = (int64_t)blockIdx.x * per_block;
+    int64_t end = beg + per_block < n ? beg + per_block : n;
+
+    for (int64_t t0 = beg; t0 < end; t0 += CV_TILE) {
+        int64_t t1 = t0 + CV_TILE < end ? t0 + CV_TILE : end;
+        int s_lo = co3_find_seg(seg_off, nseg, t0);
+        int s_hi = co3_find_seg(seg_off, nseg, t1 - 1);
+        int64_t i = t0 + (int64_t)threadIdx.x * CV_VEC;
+        if (s_lo == s_hi && i + CV_VEC <= t1) {
+            const int A = anchor_u[s_lo];
+            const int e_min = A - F + 1;
+            float4 gv = *reinterpret_cast<const float4 *>(gu + i);
+            float4 ev = *reinterpret_cast<const float4 *>(eu + i);
+            float x0 = gv.x + gamma * ev.x, x1 = gv.y + gamma * ev.y;   // no contraction (build flag):
+            float x2 = gv.z + gamma * ev.z, x3 = gv.w + gamma * ev.w;   // one rounding per operation
+            uint32_t q0, q1, q2, q3;
+            float v0, v1, v2, v3;
+            co3_quantize(x0, e_min, A, E, M, codemax, q0, v0);
+            co3_quantize(x1, e_min, A, E, M, codemax, q1, v1);
+            co3_quantize(x2, e_min, A, E, M, codemax, q2, v2);
+            co3_quantize(x3, e_min, A, E, M, codemax, q3, v3);
+            float4 en = make_float4(x0 - v0, x1 - v1, x2 - v2, x3 - v3);
+            *reinterpret_cast<float4 *>(eu + i) = en;
+            *reinterpret_cast<uint32_t *>(su + i) = q0 | (q1 << 8) | (q2 << 16) | (q3 << 24);
+            if (HIST) {
+                atomicAdd(&myhist[q0 * copies + mycopy], 1u);
+                atomicAdd(&myhist[q1 * copies + mycopy], 1u);
+                atomicAdd(&myhist[q2 * copies + mycopy], 1u);
+                atomicAdd(&myhist[q3 * copies + mycopy], 1u);
+            }
+        } else {                         // ragged tail, or a tile that straddles tensors
+            for (int64_t j = i; j < i + CV_VEC && j < t1; ++j) {
+                int s = (s_lo == s_hi) ? s_lo : co3_find_seg(seg_off, nseg, j);
+                const int A = anchor_u[s];
+                float x = gu[j] + gamma * eu[j];
+                uint32_t q;
+                float v;
+                co3_quantize(x, A - F + 1, A, E, M, codemax, q, v);
+                eu[j] = x - v;
+                su[j] = (uint8_t)q;
+                if (HIST) atomicAdd(&myhist[q * copies + mycopy], 1u);
+            }
+        }
+    }
+
+    if (HIST) {
+        __syncthreads();
+        for (int k = threadIdx.x; k < K; k += CV_BLOCK) {
+            uint32_t c = 0;
+            for (int w = 0; w < CV_BLOCK / CO3_WAVE; ++w)
+                for (int r = 0; r < copies; ++r) c += hist[w][k * copies + r];
+            if (c) atomicAdd(&counts[(int64_t)u * K + k], c);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// stand-alone histogram of symbol bytes (same LDS scheme), 16 symbols per thread per step
+// ------------------------------------------------------------------------------------------
+#define HS_VEC 16
+#define HS_TILE (CV_BLOCK * HS_VEC)
+
+__global__ __launch_bounds__(CV_BLOCK) void k_histogram(const uint8_t *__restrict__ sym, int64_t n, int64_t stride,
+                                                         int K, uint32_t *__restrict__ counts, int64_t per_block)
+{
+    const int u = blockIdx.y;
+    const uint8_t *su = sym + (int64_t)u * stride;
+    const int lane = threadIdx.x & (CO3_WAVE - 1);
+    const int wave = threadIdx.x / CO3_WAVE;
+    __shared__ uint32_t hist[CV_BLOCK / CO3_WAVE][HIST_SLOTS];
+    const int copies = HIST_SLOTS / K > 32 ? 32 : HIST_SLOTS / K;
+    uint32_t *myhist = hist[wave];
+    const int mycopy = lane & (copies - 1);
+    for (int j = threadIdx.x; j < (CV_BLOCK / CO3_WAVE) * HIST_SLOTS; j += CV_BLOCK) (&hist[0][0])[j] = 0;
+    __syncthreads();
+
+    int64_t beg = (int64_t)blockIdx.x * per_block;
+    int64_t end = beg + per_block < n ? beg + per_block : n;
+    for (int64_t t0 = beg; t0 < end; t0 += HS_TILE) {
+        int64_t i = t0 + (int64_t)threadIdx.x * HS_VEC;
+        if (i + HS_VEC <= end) {
+            uint4 v = *reinterpret_cast<const uint4 *>(su + i);
+            uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    uint32_t q = (w[a] >> (8 * b)) & 0xffu;
+                    if (q < (uint32_t)K) atomicAdd(&myhist[q * copies + mycopy], 1u);
+                }
+        } else {
+            for (int64_t j = i; j < end; ++j) {
+                uint32_t q = su[j];
+                if (q < (uint32_t)K) atomicAdd(&myhist[q * copies + mycopy], 1u);
+            }
+        }
+    }
+    __syncthreads();
+    for (int k = threadIdx.x; k < K; k += CV_BLOCK) {
+        uint32_t c = 0;
+        for (int w = 0; w < CV_BLOCK / CO3_WAVE; ++w)
+            for (int r = 0; r < copies; ++r) c += hist[w][k * copies + r];
+        if (c) atomicAdd(&counts[(int64_t)u * K + k], c);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// launchers
+// ------------------------------------------------------------------------------------------
+static int64_t per_block_for(int64_t n, int U, int64_t tile, int *blocks_out)
+{
+    // about 8 blocks per compute unit in total, each a whole number of tiles
+    int64_t target_blocks = 2048 / (U > 0 ? U : 1);
+    if (target_blocks < 1) target_blocks = 1;
+    int64_t tiles = (n + tile - 1) / tile;
+    int64_t tiles_per_block = (tiles + target_blocks - 1) / target_blocks;
+    if (tiles_per_block < 1) tiles_per_block = 1;
+    int64_t blocks = (tiles + tiles_per_block - 1) / tiles_per_block;
+    if (blocks < 1) blocks = 1;
+    *blocks_out = (int)blocks;
+    return tiles_per_block * tile;
+}
+
+hipError_t co3_launch_fill(int32_t *a, int64_t na, int32_t va, uint32_t *b, int64_t nb, hipStream_t st)
+{
+    int64_t m = na > nb ? na : nb;
+    if (m <= 0) return hipSuccess;
+    int blocks = (int)((m + 255) / 256);
+    if (blocks > 1024) blocks = 1024;
+    hipLaunchKernelGGL(k_fill_i32, dim3(blocks), dim3(256), 0, st, a, na, va, b, nb);
+    return hipGetLastError();
+}
+
+hipError_t co3_launch_absmax(const float *g, int64_t n, int U, int64_t stride, const int64_t *seg_off, int nseg,
+                             int32_t *anchor, hipStream_t st)
+{
+    if (n <= 0) return hipSuccess;
+    int blocks;
+    int64_t pb = per_block_for(n, U, CV_TILE, &blocks);
+    hipLaunchKernelGGL(k_absmax, dim3(blocks, U), dim3(CV_BLOCK), 0, st, g, n, stride, seg_off, nseg, anchor, pb);
+    return hipGetLastError();
+}
+
+hipError_t co3_launch_convert(const float *g, float *err, uint8_t *sym, int64_t n, int U, int64_t stride,
+                              const int64_t *seg_off, int nseg, const int32_t *anchor, float gamma, co3_fmt fmt,
+                              uint32_t *counts, hipStream_t st)
+{
+    if (n <= 0) return hipSuccess;
+    int blocks;
+    int64_t pb = per_block_for(n, U, CV_TILE, &blocks);
+    if (counts)
+        hipLaunchKernelGGL(k_convert_ef<true>, dim3(blocks, U), dim3(CV_BLOCK), 0, st, g, err, sym, n, stride, seg_off,
+                           nseg, anchor, gamma, fmt, counts, pb);
+    else
+        hipLaunchKernelGGL(k_convert_ef<false>, dim3(blocks, U), dim3(CV_BLOCK), 0, st, g, err, sym, n, stride,
+                           seg_off, nseg, anchor, gamma, fmt, counts, pb);
+    return hipGetLastError();
+}
+
+hipError_t co3_launch_histogram(const uint8_t *sym, int64_t n, int U, int64_t stride, int K, uint32_t *counts,
+                                hipStream_t st)
+{
+    if (n <= 0) return hipSuccess;
+    int blocks;
+    int64_t pb = per_block_for(n, U, HS_TILE, &blocks);
+    hipLaunchKernelGGL(k_histogram, dim3(blocks, U), dim3(CV_BLOCK), 0, st, sym, n, stride, K, counts, pb);
+    return hipGetLastError();
+}

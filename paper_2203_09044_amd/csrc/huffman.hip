@@ -1,0 +1,162 @@
+// Huffman code construction (Sec. III (ii)): one workgroup per user builds code lengths,
+// canonical codewords and the decoder tables from K <= 256 integer weights.
+#include "co3_dev.h"
+#include "kernels.h"
+
+#define HB_BLOCK 256
+
+__global__ __launch_bounds__(HB_BLOCK) void k_build_code(const uint32_t *__restrict__ weights, int K, char *codes,
+                                                          int32_t *status)
+{
+    const int u = blockIdx.x;
+    const int tid = threadIdx.x;
+    Co3Code *out = reinterpret_cast<Co3Code *>(codes + (size_t)u * CO3_CODE_BYTES);
+
+    __shared__ uint64_t key[HB_BLOCK];        // (weight << 8 | symbol), inactive symbols sort last
+    __shared__ uint64_t node_w[2 * HB_BLOCK]; // weights of merged nodes (index >= nact)
+    __shared__ uint16_t parent[2 * HB_BLOCK];
+    __shared__ uint8_t len_s[HB_BLOCK];
+    __shared__ uint32_t cnt_s[66];
+    __shared__ uint64_t first_s[66];
+    __shared__ uint32_t base_s[66];
+    __shared__ uint8_t sorted_s[HB_BLOCK];
+    __shared__ uint32_t maxlen_s;
+
+    uint32_t wt = tid < K ? weights[(size_t)u * K + tid] : 0u;
+    key[tid] = wt ? (((uint64_t)wt << 8) | (uint64_t)tid) : ~0ull;
+    len_s[tid] = 0;
+    sorted_s[tid] = 0;
+    if (tid < 66) {
+        cnt_s[tid] = 0;
+        first_s[tid] = 0;
+        base_s[tid] = 0;
+    }
+    if (tid == 0) maxlen_s = 0;
+    const int nact = __syncthreads_count(wt != 0u);
+
+    // leaves in (weight, symbol) order: bitonic sort of the 256 keys
+    for (int k = 2; k <= HB_BLOCK; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            int other = tid ^ j;
+            if (other > tid) {
+                uint64_t a = key[tid], b = key[other];
+                bool ascending = (tid & k) == 0;
+                if ((a > b) == ascending) {
+                    key[tid] = b;
+                    key[other] = a;
+                }
+            }
+            __syncthreads();
+        }
+    }
+
+    // two-queue merge: nodes 0..nact-1 are the sorted leaves, nact..2*nact-2 the merged nodes in
+    // creation order; a leaf wins a weight tie against a merged node
+    if (tid == 0 && nact >= 2) {
+        int q1 = 0, q2 = nact, next = nact;
+        for (int step = 0; step < nact - 1; ++step) {
+            uint64_t wsum = 0;
+            int pick[2];
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                uint64_t wl = q1 < nact ? (key[q1] >> 8) : ~0ull;
+                uint64_t wn = q2 < next ? node_w[q2] : ~0ull;
+                if (wl <= wn) {          // weights stay below 2^40, so ~0 never wins while a queue has entries
+                    pick[c] = q1++;
+                    wsum += wl;
+                } else {
+                    pick[c] = q2++;
+                    wsum += wn;
+                }
+            }
+            node_w[next] = wsum;
+            parent[pick[0]] = (uint16_t)next;
+            parent[pick[1]] = (uint16_t)next;
+            ++next;
+        }
+    }
+    __syncthreads();
+
+    // code length = depth of the leaf
+    if (tid < nact) {
+        int depth;
+        if (nact == 1) {
+            depth = 1;
+        } else {
+            const int root = 2 * nact - 2;
+            depth = 0;
+            for (int v = tid; v != root && depth < 255; v = parent[v]) ++depth;
+        }
+        int s = (int)(key[tid] & 0xffu);
+        int dl = depth > 64 ? 64 : depth;
+        len_s[s] = (uint8_t)dl;
+        atomicAdd(&cnt_s[dl], 1u);
+        atomicMax(&maxlen_s, (uint32_t)depth);
+    }
+    __syncthreads();
+    const uint32_t maxlen = maxlen_s;
+    if (tid == 0 && maxlen > CO3_MAX_CODE_LEN) co3_raise(status, CO3_EINVAL);
+
+    // canonical numbering: first code of length l is sum_{j<l} count[j] << (l - j)
+    if (tid >= 1 && tid <= 64) {
+        uint64_t first = 0;
+        uint32_t base = 0;
+        for (int j = 1; j < tid; ++j) {
+            first += (uint64_t)cnt_s[j] << (tid - j);
+            base += cnt_s[j];
+        }
+        first_s[tid] = first;
+        base_s[tid] = base;
+    }
+    __syncthreads();
+
+    {
+        uint32_t l = len_s[tid];
+        uint64_t enc = 0;
+        if (l) {
+            uint32_t rank = 0;
+            for (int j = 0; j < tid; ++j) rank += (len_s[j] == l) ? 1u : 0u;
+            uint64_t code = first_s[l] + rank;
+            sorted_s[base_s[l] + rank] = (uint8_t)tid;
+            enc = (code << 6) | (uint64_t)(l & 63u);
+        }
+        out->len[tid] = (uint8_t)l;
+        out->enc[tid] = enc;
+    }
+    __syncthreads();
+
+    if (tid < 65) out->first_code[tid] = first_s[tid];
+    if (tid < 66) {
+        out->count[tid] = (uint16_t)cnt_s[tid];
+        out->base[tid] = (uint16_t)base_s[tid];
+    }
+    out->sorted[tid] = sorted_s[tid];
+    uint32_t lut_bits = maxlen < 1 ? 1 : (maxlen > CO3_LUT_BITS_MAX ? CO3_LUT_BITS_MAX : maxlen);
+    if (tid == 0) {
+        out->nact = (uint32_t)nact;
+        out->maxlen = maxlen;
+        out->lut_bits = lut_bits;
+        out->reserved = 0;
+    }
+
+    // decoder table: entry i decodes the lut_bits-bit prefix i by the canonical rule
+    for (uint32_t i = tid; i < (1u << lut_bits); i += HB_BLOCK) {
+        uint16_t entry = 0;
+        for (uint32_t l = 1; l <= lut_bits; ++l) {
+            uint64_t off = (uint64_t)(i >> (lut_bits - l)) - first_s[l];
+            if (off < (uint64_t)cnt_s[l]) {
+                entry = (uint16_t)((l << 8) | sorted_s[base_s[l] + (uint32_t)off]);
+                break;
+            }
+        }
+        out->lut[i] = entry;
+    }
+}
+
+hipError_t co3_launch_build_code(const uint32_t *weights, int U, int K, void *codes, int32_t *status, hipStream_t st)
+{
+    if (U <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_build_code, dim3(U), dim3(HB_BLOCK), 0, st, weights, K, reinterpret_cast<char *>(codes),
+                       status);
+    return hipGetLastError();
+}

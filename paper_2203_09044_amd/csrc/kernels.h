@@ -1,0 +1,24 @@
+// Host-side launchers of the libco3 kernels (one per kernel; arguments already validated).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/co3.h"
+
+hipError_t co3_launch_fill(int32_t *a, int64_t na, int32_t va, uint32_t *b, int64_t nb, hipStream_t st);
+hipError_t co3_launch_absmax(const float *g, int64_t n, int U, int64_t stride, const int64_t *seg_off, int nseg,
+                             int32_t *anchor, hipStream_t st);
+hipError_t co3_launch_convert(const float *g, float *err, uint8_t *sym, int64_t n, int U, int64_t stride,
+                              const int64_t *seg_off, int nseg, const int32_t *anchor, float gamma, co3_fmt fmt,
+                              uint32_t *counts, hipStream_t st);
+hipError_t co3_launch_histogram(const uint8_t *sym, int64_t n, int U, int64_t stride, int K, uint32_t *counts,
+                                hipStream_t st);
+hipError_t co3_launch_build_code(const uint32_t *weights, int U, int K, void *codes, int32_t *status, hipStream_t st);
+hipError_t co3_launch_encode(const uint8_t *sym, int64_t n, int U, int64_t stride, const void *codes, uint64_t *words,
+                             int64_t cap_words, int chunk_syms, uint64_t *chunk_bitoff, uint64_t *total_bits,
+                             uint64_t *blocksum, int32_t *status, hipStream_t st);
+hipError_t co3_launch_decode(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff, int chunk_syms,
+                             const void *codes, int64_t n, int U, uint8_t *sym_out, int64_t stride, int32_t *status,
+                             hipStream_t st);
+hipError_t co3_launch_ps_sum(const uint8_t *sym, int64_t n, int U, int64_t stride, const int32_t *anchor,
+                             const int64_t *seg_off, int nseg, co3_fmt fmt, float *avg_out, hipStream_t st);

@@ -1,0 +1,82 @@
+"""Device buffers of one workload and the call sequence of one CO3 iteration.
+
+Plumbing only: allocation through torch, then the six library calls in the order of
+Algorithm 1 (user side: convert_ef [+ fused histogram] -> build_code -> encode; server
+side: ps_aggregate, or decode for the round-trip check).
+"""
+from __future__ import annotations
+
+from typing import Optional
+
+import torch
+
+from . import binding as B
+from .binding import Fmt
+
+
+def _round_up(x: int, m: int) -> int:
+    return (x + m - 1) // m * m
+
+
+class Co3Pipeline:
+    def __init__(self, U: int, n: int, fmt: Fmt, chunk_syms: int = 256, seg_off=None, gamma: float = 1.0,
+                 cap_words: Optional[int] = None, device="cuda:0", fused_histogram: bool = True):
+        self.U, self.n, self.fmt, self.chunk_syms, self.gamma = U, n, fmt, chunk_syms, gamma
+        self.fused_histogram = fused_histogram
+        dev = torch.device(device)
+        self.device = dev
+        self.stride = _round_up(max(n, 1), 16)
+        self.nchunks = (n + chunk_syms - 1) // chunk_syms
+        self.cap_words = B.cap_words_empirical(n, fmt) if cap_words is None else cap_words
+        self.seg_off = None if seg_off is None else torch.as_tensor(seg_off, dtype=torch.int64).to(dev)
+        self.nseg = 1 if seg_off is None else self.seg_off.numel() - 1
+        z = dict(device=dev)
+        self.err = torch.zeros((U, self.stride), dtype=torch.float32, **z)
+        self.sym = torch.zeros((U, self.stride), dtype=torch.uint8, **z)
+        self.anchor = torch.zeros((U, self.nseg), dtype=torch.int32, **z)
+        self.counts = torch.zeros((U, fmt.K), dtype=torch.int32, **z)
+        self.codes = torch.zeros((U, B.CODE_BYTES), dtype=torch.uint8, **z)
+        self.words = torch.zeros((U, max(self.cap_words, 2)), dtype=torch.int64, **z)
+        self.chunk_bitoff = torch.zeros((U, self.nchunks + 1), dtype=torch.int64, **z)
+        self.total_bits = torch.zeros((U,), dtype=torch.int64, **z)
+        self.enc_ws = torch.zeros((max(B.encode_workspace_bytes(n, U), 8) // 8,), dtype=torch.int64, **z)
+        self.agg_ws = torch.zeros((max(B.ps_aggregate_workspace_bytes(self.stride, U), 16),), dtype=torch.uint8, **z)
+        self.avg = torch.zeros((self.stride,), dtype=torch.float32, **z)
+        self.sym_dec = torch.zeros((U, self.stride), dtype=torch.uint8, **z)
+        self.status = torch.zeros((1,), dtype=torch.int32, **z)
+
+    def new_gradient_buffer(self) -> torch.Tensor:
+        return torch.zeros((self.U, self.stride), dtype=torch.float32, device=self.device)
+
+    # ---- user side
+    def convert(self, g: torch.Tensor, anchor_mode=B.ANCHOR_FROM_ABSMAX_G):
+        B.convert_ef(g, self.err, self.sym, self.n, self.anchor, anchor_mode, self.gamma, self.fmt,
+                     seg_off=self.seg_off, counts=self.counts if self.fused_histogram else None)
+        if not self.fused_histogram:
+            B.histogram(self.sym, self.n, self.fmt, self.counts)
+
+    def build(self, weights: Optional[torch.Tensor] = None):
+        B.build_code(self.counts if weights is None else weights, self.U, self.fmt, self.codes, self.status)
+
+    def encode(self):
+        B.encode(self.sym, self.n, self.fmt, self.codes, self.words, self.chunk_syms, self.chunk_bitoff,
+                 self.total_bits, self.enc_ws, self.status)
+
+    # ---- server side
+    def decode(self):
+        B.decode(self.words, self.chunk_bitoff, self.chunk_syms, self.codes, self.fmt, self.n, self.sym_dec,
+                 self.status)
+
+    def aggregate(self):
+        B.ps_aggregate(self.words, self.chunk_bitoff, self.chunk_syms, self.codes, self.fmt, self.n, self.U,
+                       self.anchor, self.avg, self.agg_ws, self.status, seg_off=self.seg_off)
+
+    def step(self, g: torch.Tensor, weights: Optional[torch.Tensor] = None):
+        """One whole iteration: users encode, the server decodes and averages."""
+        self.convert(g)
+        self.build(weights)
+        self.encode()
+        self.aggregate()
+
+    def poll(self) -> int:
+        return B.poll_status(self.status)
