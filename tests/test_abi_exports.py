@@ -1,0 +1,82 @@
+"""The C-ABI library loads and exports every function declared in include/co3.h (CPU only:
+no GPU work is issued; the host-only helpers are exercised)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "co3.h")
+LIB = os.path.join(ROOT, "paper_2203_09044_amd", "libco3.so")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(co3_[a-z0-9_]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        import __graft_entry__ as ge
+        ge.build()
+    return ctypes.CDLL(LIB)
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert {"co3_convert_ef", "co3_histogram", "co3_build_code", "co3_encode", "co3_decode",
+            "co3_ps_aggregate"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), name
+
+
+def test_binding_covers_header():
+    from paper_2203_09044_amd import binding
+    assert sorted(binding.EXPORTS) == declared_functions()
+    for name in binding.EXPORTS:
+        assert hasattr(binding, name[len("co3_"):]), name
+
+
+def test_host_helpers_without_gpu():
+    from paper_2203_09044_amd import binding as B
+    fmt = B.Fmt(3, 1)
+    assert B.strerror(0) == "ok" and B.strerror(B.ECAP) and B.strerror(-1234)
+    assert B.encode_workspace_bytes(0, 1) == 8
+    assert B.encode_workspace_bytes(2048, 3) == 24
+    assert B.encode_workspace_bytes(2049, 3) == 48
+    assert B.ps_aggregate_workspace_bytes(32, 4) == 128
+    assert B.cap_words_empirical(64, fmt) == 6          # 5 bits * 64 = 320 bits = 5 words, even -> 6
+    assert B.cap_words_empirical(0, fmt) == 0
+    assert B.CODE_BYTES == 12288
+
+
+def test_host_argument_checks_launch_nothing():
+    """Invalid arguments are rejected on the host before any HIP call (safe without a GPU)."""
+    from paper_2203_09044_amd import binding as B
+    L = B._lib
+    f = B.Fmt(6, 3).c()       # 10 bits: invalid
+    assert L.co3_convert_ef(None, None, None, 10, 1, 16, None, 1, None, 0, 1.0, f, None, None) == B.EINVAL
+    assert L.co3_histogram(None, 10, 1, 16, B.Fmt(3, 1).c(), None, None) == B.EINVAL
+    assert L.co3_build_code(None, 1, B.Fmt(3, 1).c(), None, None, None) == B.EINVAL
+    assert L.co3_encode(None, 10, 1, 16, B.Fmt(3, 1).c(), None, None, 1, 100, None, None, None, 0, None, None) == B.EINVAL
+    assert L.co3_decode(None, 1, None, 256, None, B.Fmt(3, 1).c(), 10, 1, None, 16, None, None) == B.EINVAL
+    assert L.co3_ps_aggregate(None, 1, None, 256, None, B.Fmt(3, 1).c(), 10, 1, None, None, 1, None, None, 0, None,
+                              None) == B.EINVAL
+    assert L.co3_poll_status(None, None) == B.EINVAL
+
+
+def test_model_weights_host_matches_oracle_model():
+    """The library's own GenNorm-CDF arithmetic against the oracle's scipy-based table."""
+    import oracle
+    from paper_2203_09044_amd import binding as B
+    for (E, M), beta, alpha, A in [((5, 2), 1.0, 1e-4, -7), ((3, 1), 1.0, 1e-3, -7), ((4, 3), 0.8, 1e-3, -5),
+                                   ((2, 0), 0.5, 1e-3, -3), ((3, 0), 1.5, 1e-3, -8), ((4, 3), 2.0, 1e-3, -8),
+                                   ((5, 2), 0.5, 1e-3, 2)]:
+        got = B.model_weights(A, B.Fmt(E, M), beta, alpha).numpy().view(np.uint32)
+        want = oracle.model_weights(A, oracle.Fmt(E, M), beta, alpha)
+        assert np.array_equal(got, want), (E, M, beta, A)
+        assert got[(1 << (E + M))] == 0 and got.min(initial=1, where=np.arange(got.size) != (1 << (E + M))) >= 1
