@@ -1,0 +1,202 @@
+#!/usr/bin/env python3
+"""Benchmark of the CO3 codec hot path on one MI355X.
+
+A step is one whole iteration of Algorithm 1's uplink for all clients of the workload:
+co3_convert_ef (anchor + error correction + fp conversion + histogram) -> co3_build_code ->
+co3_encode -> co3_ps_aggregate (decode + average), on synthetic GenNorm gradients that are
+resident in HBM before the timed region starts.
+
+Prints ONE JSON line: elements/s of the whole path, the roofline of the dominant kernel
+(k_convert_ef, timed live with HIP events on the launch stream), and the CPU oracle timed on a
+bounded sample of the same workload on this host.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+K_CONVERT = 2                  # kernel id of k_convert_ef in the library's timing facility
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def make_workload(name):
+    import co3_inputs as inp
+    if name == "C3":
+        w = inp.c3()
+        betas = [float(b) for b in inp.c3_client_betas(w.U)]
+        return w, betas, 1e-3, ("C3: 10 clients x 11,173,962 fp32, GenNorm beta~U(0.5,1.5) per client, scale 1e-3, "
+                                "E3M0, per-client empirical Huffman, PS decode+average")
+    if name == "C1":
+        w = inp.c1()
+        return w, [1.0], 1e-3, "C1: 1 client x 65,536 fp32, GenNorm beta=1 scale 1e-3, E3M1"
+    if name == "C5":
+        w = inp.c5(4)
+        return w, [1.0], 1e-3, "C5[E3M1,beta=1]: 16 clients x 25,000,000 fp32, scale 1e-3"
+    raise SystemExit(f"unknown workload {name}")
+
+
+def device_batches(w, betas, alpha, pool, pipe):
+    """`pool` gradient batches [U][stride] drawn on the device (seeded), one per iteration slot."""
+    import torch
+    import co3_inputs as inp
+    out = []
+    for t in range(pool):
+        g = pipe.new_gradient_buffer()
+        for u in range(w.U):
+            seed = inp.BASE_SEED * 1000003 + w.cfg * 10007 + u * 101 + t
+            g[u, :w.n] = inp.device_gennorm(w.n, betas[u % len(betas)], alpha, seed)
+        out.append(g)
+    torch.cuda.synchronize()
+    return out
+
+
+def cpu_baseline(w, betas, alpha, chunk_syms, n_sample, reps):
+    """The oracle as it stands, single thread, same call sequence, on `n_sample` elements per client of
+    `U_s` clients of the workload."""
+    import numpy as np
+    import oracle
+    import co3_inputs as inp
+    U_s = min(w.U, 2)
+    fmt = oracle.Fmt(w.E, w.M)
+    gs = [[inp.gennorm(inp.rng_for(w.cfg, 7, u, t), n_sample, betas[u % len(betas)], alpha) for u in range(U_s)]
+          for t in range(reps)]
+    errs = [np.zeros(n_sample, np.float32) for _ in range(U_s)]
+    oracle.lib()
+    t0 = time.perf_counter()
+    for t in range(reps):
+        syms, anchors = [], []
+        for u in range(U_s):
+            A = oracle.anchor(gs[t][u], fmt)
+            s, errs[u] = oracle.convert_ef(gs[t][u], errs[u], A, 1.0, fmt)
+            cnt = oracle.histogram(s, fmt)
+            l = oracle.huffman_lengths(cnt)
+            c = oracle.canonical_codes(l)
+            words, off, total = oracle.encode(s, l, c, chunk_syms)
+            d = oracle.decode(words, total, l, c, n_sample)
+            syms.append(d)
+            anchors.append(A)
+        oracle.aggregate(np.stack(syms), np.stack(anchors), fmt)
+    dt = time.perf_counter() - t0
+    elems = U_s * n_sample * reps
+    return {"value": elems / dt, "unit": "elements/s", "cores": 1, "kind": "oracle",
+            "sample": f"{U_s} clients x {n_sample} elements x {reps} iterations of the same workload "
+                      f"({dt:.1f} s, single thread)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="C3")
+    ap.add_argument("--chunk", type=int, default=256)
+    ap.add_argument("--pool", type=int, default=3, help="distinct gradient batches cycled through")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--breakdown", action="store_true", help="extra untimed pass timing every kernel (stderr)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1")
+
+    import torch
+    assert torch.cuda.is_available(), "bench.py needs an MI355X"
+    from paper_2203_09044_amd import Co3Pipeline, Fmt, binding as B
+
+    w, betas, alpha, desc = make_workload(args.workload)
+    fmt = Fmt(w.E, w.M)
+    pipe = Co3Pipeline(w.U, w.n, fmt, chunk_syms=args.chunk)
+    log(f"[bench] {desc}; generating {args.pool} device batches")
+    batches = device_batches(w, betas, alpha, args.pool, pipe)
+
+    for i in range(args.warmup):
+        pipe.step(batches[i % args.pool])
+    torch.cuda.synchronize()
+    assert pipe.poll() == 0, "device status after warmup"
+
+    B.timing_reset()
+    B.timing_enable(1 << K_CONVERT)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        pipe.step(batches[i % args.pool])
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    conv_ms, conv_launches = B.timing_read(K_CONVERT)
+    B.timing_enable(0)
+    assert pipe.poll() == 0, "device status after the timed region"
+
+    elems_step = w.U * w.n
+    value = elems_step * args.steps / dt
+    total_bits = pipe.total_bits.cpu().numpy().astype("float64")
+    payload_bpe = float(total_bits.sum()) / elems_step
+    index_bpe = 64.0 * (pipe.nchunks + 1) / w.n
+    header_bpe = (8.0 * fmt.K + 32 + 64) / w.n
+    b = payload_bpe + index_bpe + header_bpe
+    b_alg = 12.0 + b / 4.0 + 4.0 / w.U                 # algorithmic bytes per client-element, whole path
+    conv_avg_ms = conv_ms / max(conv_launches, 1)
+    conv_bytes = 12.0 * elems_step                     # k_convert_ef: read g, read m, write m
+    achieved = conv_bytes / (conv_avg_ms * 1e-3) / 1e9 if conv_avg_ms > 0 else 0.0
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic_k_convert_ef_C3.json")
+    if args.workload == "C3" and os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("traffic_bytes_per_launch")
+        except Exception:
+            traffic = None
+
+    if args.breakdown:
+        B.timing_reset()
+        B.timing_enable((1 << B.KERNEL_COUNT) - 1)
+        reps = 5
+        for i in range(reps):
+            pipe.step(batches[i % args.pool])
+        torch.cuda.synchronize()
+        tot = 0.0
+        for k in range(B.KERNEL_COUNT):
+            ms, cnt = B.timing_read(k)
+            if cnt:
+                log(f"[bench] {B.kernel_name(k):14s} {ms / reps:8.4f} ms/step  ({cnt // reps} launches/step)")
+                tot += ms / reps
+        log(f"[bench] sum of kernels {tot:.4f} ms/step")
+        B.timing_enable(0)
+
+    res = {
+        "metric": "gradient elements/s (encode+decode, 1 GPU)",
+        "value": value,
+        "unit": "elements/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": dt / args.steps * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": desc, "U": w.U, "n": w.n, "format": f"E{w.E}M{w.M}", "chunk_syms": args.chunk,
+                   "table": "empirical per client, rebuilt every step", "gamma": 1.0},
+        "bits_per_element": {"payload": payload_bpe, "index": index_bpe, "header": header_bpe},
+        "path_roofline": {"bound": "hbm", "algorithmic_bytes_per_element": b_alg,
+                          "achieved": b_alg * value / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                          "frac": b_alg * value / 1e9 / HBM_PEAK_GBS},
+        "roofline": {"bound": "hbm", "kernel": "k_convert_ef", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "avg_launch_ms": conv_avg_ms, "launches": conv_launches,
+                     "algorithmic_bytes_per_launch": conv_bytes},
+    }
+    if not args.no_cpu:
+        log("[bench] timing the CPU oracle on a bounded sample")
+        res["cpu_baseline"] = cpu_baseline(w, betas, alpha, args.chunk, n_sample=min(w.n, 1 << 24), reps=4)
+    print(json.dumps(res), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -14,7 +14,8 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream); the
  *     call only enqueues kernels on it and returns without waiting;
  *   - batched arrays are laid out [U][stride] with `stride` in elements (>= n, and
- *     a multiple of 16 when U > 1); float/word arrays must be 16-byte aligned;
+ *     a multiple of 16 when U > 1); float, symbol and word arrays must be 16-byte
+ *     aligned, and cap_words (the per-user stride of the word array) must be even;
  *   - the return value is a host-side status: CO3_OK or a negative CO3_E* for
  *     arguments rejected before anything was launched;
  *   - conditions that only the device can see (capacity overrun, symbol without a
@@ -73,8 +74,9 @@ const char *co3_strerror(int32_t status);
 /* Bytes of workspace co3_encode needs (one 64-bit partial sum per 2048 symbols and user). */
 size_t co3_encode_workspace_bytes(int64_t n, int32_t U);
 
-/* Bytes of workspace co3_ps_aggregate needs (the decoded symbols, U * stride bytes). */
-size_t co3_ps_aggregate_workspace_bytes(int64_t stride, int32_t U);
+/* Bytes of workspace co3_ps_aggregate needs (the decoded symbols of all users, whole tiles of
+ * 64 chunks). */
+size_t co3_ps_aggregate_workspace_bytes(int64_t n, int32_t U, int32_t chunk_syms);
 
 /* Number of 64-bit words that always hold a stream coded with an empirical table built
  * from the very symbols being coded (Huffman is then no longer than the fixed-length
@@ -164,13 +166,32 @@ int32_t co3_decode(const uint64_t *words, int64_t cap_words, const uint64_t *chu
  *
  *   anchor    [U][nseg] i32 in, seg_off as in co3_convert_ef
  *   avg_out   [n] f32 out
- *   workspace co3_ps_aggregate_workspace_bytes(stride16, U) bytes with stride16 = n rounded up
- *             to a multiple of 16; holds the decoded symbols
+ *   workspace co3_ps_aggregate_workspace_bytes(n, U, chunk_syms) bytes, 16-byte aligned; holds the
+ *             decoded symbols in a private interleaved order
  */
 int32_t co3_ps_aggregate(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff, int32_t chunk_syms,
                          const void *codes, co3_fmt fmt, int64_t n, int32_t U, const int32_t *anchor,
                          const int64_t *seg_off, int32_t nseg, float *avg_out, void *workspace, size_t ws_bytes,
                          int32_t *status, void *stream);
+
+/* ---- launch timing (diagnostic) ------------------------------------------ */
+
+/*
+ * Optional per-kernel timing with HIP events recorded on the launch stream, for benchmarks
+ * that must report one kernel's average duration.  Process-global and not thread-safe: the
+ * only state the library keeps, and only while enabled.  kernel ids: 0 k_fill_i32, 1 k_absmax,
+ * 2 k_convert_ef, 3 k_histogram, 4 k_build_code, 5 k_enc_sizes, 6 k_enc_scan, 7 k_enc_pack,
+ * 8 k_decode, 9 k_ps_sum (co3_kernel_name returns these names, "" for other ids).
+ *   co3_timing_enable(mask): bracket every later launch of kernel k with events iff bit k is set.
+ *   co3_timing_read(k, &ms, &count): waits for the recorded events, then returns the summed
+ *       duration and launch count of kernel k since the last reset.
+ *   co3_timing_reset(): waits likewise and clears all sums.
+ */
+#define CO3_KERNEL_COUNT 10
+int32_t co3_timing_enable(uint32_t kernel_mask);
+int32_t co3_timing_read(int32_t kernel, double *total_ms, int64_t *launches);
+int32_t co3_timing_reset(void);
+const char *co3_kernel_name(int32_t kernel);
 
 /* ---- model table (host only) -------------------------------------------- */
 

@@ -24,8 +24,10 @@ PACK_SYMS = 2048
 EXPORTS = (
     "co3_strerror", "co3_encode_workspace_bytes", "co3_ps_aggregate_workspace_bytes", "co3_cap_words_empirical",
     "co3_poll_status", "co3_convert_ef", "co3_histogram", "co3_build_code", "co3_encode", "co3_decode",
-    "co3_ps_aggregate", "co3_model_weights",
+    "co3_ps_aggregate", "co3_model_weights", "co3_timing_enable", "co3_timing_read", "co3_timing_reset",
+    "co3_kernel_name",
 )
+KERNEL_COUNT = 10
 
 
 class _Fmt(C.Structure):
@@ -66,7 +68,7 @@ def _load():
     L.co3_encode_workspace_bytes.restype = sz
     L.co3_encode_workspace_bytes.argtypes = [i64, i32]
     L.co3_ps_aggregate_workspace_bytes.restype = sz
-    L.co3_ps_aggregate_workspace_bytes.argtypes = [i64, i32]
+    L.co3_ps_aggregate_workspace_bytes.argtypes = [i64, i32, i32]
     L.co3_cap_words_empirical.restype = i64
     L.co3_cap_words_empirical.argtypes = [i64, _Fmt]
     L.co3_poll_status.restype = i32
@@ -85,6 +87,14 @@ def _load():
     L.co3_ps_aggregate.argtypes = [p, i64, p, i32, p, _Fmt, i64, i32, p, p, i32, p, p, sz, p, p]
     L.co3_model_weights.restype = i32
     L.co3_model_weights.argtypes = [i32, _Fmt, C.c_double, C.c_double, p]
+    L.co3_timing_enable.restype = i32
+    L.co3_timing_enable.argtypes = [C.c_uint32]
+    L.co3_timing_read.restype = i32
+    L.co3_timing_read.argtypes = [i32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+    L.co3_timing_reset.restype = i32
+    L.co3_timing_reset.argtypes = []
+    L.co3_kernel_name.restype = C.c_char_p
+    L.co3_kernel_name.argtypes = [i32]
     return L
 
 
@@ -129,8 +139,8 @@ def encode_workspace_bytes(n: int, U: int) -> int:
     return _lib.co3_encode_workspace_bytes(n, U)
 
 
-def ps_aggregate_workspace_bytes(stride: int, U: int) -> int:
-    return _lib.co3_ps_aggregate_workspace_bytes(stride, U)
+def ps_aggregate_workspace_bytes(n: int, U: int, chunk_syms: int) -> int:
+    return _lib.co3_ps_aggregate_workspace_bytes(n, U, chunk_syms)
 
 
 def cap_words_empirical(n: int, fmt: Fmt) -> int:
@@ -196,3 +206,22 @@ def model_weights(A: int, fmt: Fmt, beta: float, alpha: float):
     w = np.zeros(fmt.K, dtype=np.uint32)
     _chk(_lib.co3_model_weights(A, fmt.c(), beta, alpha, w.ctypes.data_as(C.c_void_p)), "co3_model_weights")
     return torch.from_numpy(w.view(np.int32).copy())
+
+
+def timing_enable(kernel_mask: int):
+    _chk(_lib.co3_timing_enable(kernel_mask), "co3_timing_enable")
+
+
+def timing_read(kernel: int):
+    """(total milliseconds, launches) of one kernel id since the last reset."""
+    ms, cnt = C.c_double(0), C.c_int64(0)
+    _chk(_lib.co3_timing_read(kernel, C.byref(ms), C.byref(cnt)), "co3_timing_read")
+    return ms.value, cnt.value
+
+
+def timing_reset():
+    _chk(_lib.co3_timing_reset(), "co3_timing_reset")
+
+
+def kernel_name(kernel: int) -> str:
+    return _lib.co3_kernel_name(kernel).decode()

@@ -4,7 +4,49 @@
 #include "co3_dev.h"
 #include "kernels.h"
 
+#include <vector>
+
 namespace {
+
+// ---- optional launch timing (diagnostic, process-global, not thread-safe) ------------------
+struct TimedLaunch {
+    hipEvent_t start, stop;
+    int kernel;
+    bool pending;
+};
+uint32_t g_timing_mask = 0;
+std::vector<TimedLaunch> g_timed;                 // event pairs, reused after each read
+size_t g_timed_used = 0;
+double g_total_ms[CO3_K_COUNT] = {0};
+int64_t g_launches[CO3_K_COUNT] = {0};
+
+int timing_acquire(int kernel)
+{
+    if (g_timed_used == g_timed.size()) {
+        TimedLaunch t{};
+        if (hipEventCreate(&t.start) != hipSuccess) return -1;
+        if (hipEventCreate(&t.stop) != hipSuccess) return -1;
+        g_timed.push_back(t);
+    }
+    g_timed[g_timed_used].kernel = kernel;
+    g_timed[g_timed_used].pending = true;
+    return (int)g_timed_used++;
+}
+
+void timing_collect()
+{
+    for (size_t i = 0; i < g_timed_used; ++i) {
+        TimedLaunch &t = g_timed[i];
+        if (!t.pending) continue;
+        float ms = 0.f;
+        if (hipEventSynchronize(t.stop) == hipSuccess && hipEventElapsedTime(&ms, t.start, t.stop) == hipSuccess) {
+            g_total_ms[t.kernel] += ms;
+            g_launches[t.kernel] += 1;
+        }
+        t.pending = false;
+    }
+    g_timed_used = 0;
+}
 
 bool fmt_ok(co3_fmt f)
 {
@@ -26,7 +68,52 @@ int32_t hip_rc(hipError_t e) { return e == hipSuccess ? CO3_OK : CO3_EHIP; }
 
 }  // namespace
 
+Co3LaunchTimer::Co3LaunchTimer(int kernel, hipStream_t st) : slot(-1), stream(st)
+{
+    if (g_timing_mask & (1u << kernel)) {
+        slot = timing_acquire(kernel);
+        if (slot >= 0) (void)hipEventRecord(g_timed[slot].start, stream);
+    }
+}
+
+Co3LaunchTimer::~Co3LaunchTimer()
+{
+    if (slot >= 0) (void)hipEventRecord(g_timed[slot].stop, stream);
+}
+
 extern "C" {
+
+int32_t co3_timing_enable(uint32_t kernel_mask)
+{
+    g_timing_mask = kernel_mask & ((1u << CO3_K_COUNT) - 1u);
+    return CO3_OK;
+}
+
+int32_t co3_timing_read(int32_t kernel, double *total_ms, int64_t *launches)
+{
+    if (kernel < 0 || kernel >= CO3_K_COUNT || !total_ms || !launches) return CO3_EINVAL;
+    timing_collect();
+    *total_ms = g_total_ms[kernel];
+    *launches = g_launches[kernel];
+    return CO3_OK;
+}
+
+int32_t co3_timing_reset(void)
+{
+    timing_collect();
+    for (int k = 0; k < CO3_K_COUNT; ++k) {
+        g_total_ms[k] = 0;
+        g_launches[k] = 0;
+    }
+    return CO3_OK;
+}
+
+const char *co3_kernel_name(int32_t kernel)
+{
+    static const char *names[CO3_K_COUNT] = {"k_fill_i32", "k_absmax",    "k_convert_ef", "k_histogram", "k_build_code",
+                                             "k_enc_sizes", "k_enc_scan", "k_enc_pack",   "k_decode",    "k_ps_sum"};
+    return (kernel >= 0 && kernel < CO3_K_COUNT) ? names[kernel] : "";
+}
 
 const char *co3_strerror(int32_t status)
 {
@@ -48,10 +135,13 @@ size_t co3_encode_workspace_bytes(int64_t n, int32_t U)
     return (size_t)(nblk > 0 ? nblk : 1) * (size_t)U * sizeof(uint64_t);
 }
 
-size_t co3_ps_aggregate_workspace_bytes(int64_t stride, int32_t U)
+size_t co3_ps_aggregate_workspace_bytes(int64_t n, int32_t U, int32_t chunk_syms)
 {
-    if (stride < 0 || U < 1) return 0;
-    return (size_t)stride * (size_t)U;
+    if (n < 0 || U < 1 || !chunk_ok(chunk_syms)) return 0;
+    int64_t nchunks = (n + chunk_syms - 1) / chunk_syms;
+    int64_t ntiles = (nchunks + CO3_WAVE - 1) / CO3_WAVE;
+    if (ntiles < 1) ntiles = 1;
+    return (size_t)ntiles * CO3_WAVE * (size_t)chunk_syms * (size_t)U;
 }
 
 int64_t co3_cap_words_empirical(int64_t n, co3_fmt fmt)
@@ -116,7 +206,8 @@ int32_t co3_encode(const uint8_t *sym, int64_t n, int32_t U, int64_t stride, co3
 {
     if (!fmt_ok(fmt) || !batch_ok(n, U, stride) || !chunk_ok(chunk_syms) || cap_words < 0) return CO3_EINVAL;
     if (!sym || !codes || !words || !chunk_bitoff || !total_bits || !workspace) return CO3_EINVAL;
-    if (!aligned(sym, 16) || !aligned(words, 8) || !aligned(codes, 8) || !aligned(workspace, 8)) return CO3_EINVAL;
+    if (!aligned(sym, 16) || !aligned(words, 16) || !aligned(codes, 8) || !aligned(workspace, 8)) return CO3_EINVAL;
+    if (cap_words % 2 != 0) return CO3_EINVAL;
     if (ws_bytes < co3_encode_workspace_bytes(n, U)) return CO3_EINVAL;
     return hip_rc(co3_launch_encode(sym, n, U, stride, codes, words, cap_words, chunk_syms, chunk_bitoff, total_bits,
                                     static_cast<uint64_t *>(workspace), status, static_cast<hipStream_t>(stream)));
@@ -128,8 +219,8 @@ int32_t co3_decode(const uint64_t *words, int64_t cap_words, const uint64_t *chu
 {
     if (!fmt_ok(fmt) || !batch_ok(n, U, stride) || !chunk_ok(chunk_syms) || cap_words < 0) return CO3_EINVAL;
     if (!words || !chunk_bitoff || !codes || !sym_out) return CO3_EINVAL;
-    if (!aligned(sym_out, 16) || !aligned(words, 8) || !aligned(codes, 8)) return CO3_EINVAL;
-    return hip_rc(co3_launch_decode(words, cap_words, chunk_bitoff, chunk_syms, codes, n, U, sym_out, stride, status,
+    if (!aligned(sym_out, 16) || !aligned(words, 16) || !aligned(codes, 8) || cap_words % 2 != 0) return CO3_EINVAL;
+    return hip_rc(co3_launch_decode(words, cap_words, chunk_bitoff, chunk_syms, codes, n, U, sym_out, stride, 0, status,
                                     static_cast<hipStream_t>(stream)));
 }
 
@@ -142,14 +233,18 @@ int32_t co3_ps_aggregate(const uint64_t *words, int64_t cap_words, const uint64_
         return CO3_EINVAL;
     if (nseg < 1 || (seg_off == nullptr && nseg != 1)) return CO3_EINVAL;
     if (!words || !chunk_bitoff || !codes || !anchor || !avg_out || !workspace) return CO3_EINVAL;
-    if (!aligned(avg_out, 16) || !aligned(workspace, 16) || !aligned(words, 8) || !aligned(codes, 8)) return CO3_EINVAL;
-    const int64_t stride = (n + 15) & ~(int64_t)15;
-    if (ws_bytes < co3_ps_aggregate_workspace_bytes(stride, U)) return CO3_EINVAL;
+    if (!aligned(avg_out, 16) || !aligned(workspace, 16) || !aligned(words, 16) || !aligned(codes, 8)) return CO3_EINVAL;
+    if (cap_words % 2 != 0) return CO3_EINVAL;
+    const size_t need = co3_ps_aggregate_workspace_bytes(n, U, chunk_syms);
+    if (ws_bytes < need) return CO3_EINVAL;
+    const int64_t ws_stride = (int64_t)(need / (size_t)U);
     hipStream_t st = static_cast<hipStream_t>(stream);
     uint8_t *symws = static_cast<uint8_t *>(workspace);
-    hipError_t e = co3_launch_decode(words, cap_words, chunk_bitoff, chunk_syms, codes, n, U, symws, stride, status, st);
+    hipError_t e =
+        co3_launch_decode(words, cap_words, chunk_bitoff, chunk_syms, codes, n, U, symws, ws_stride, 1, status, st);
     if (e != hipSuccess) return CO3_EHIP;
-    return hip_rc(co3_launch_ps_sum(symws, n, U, stride, anchor, seg_off, nseg, fmt, avg_out, st));
+    return hip_rc(
+        co3_launch_ps_sum_tiled(symws, n, U, ws_stride, chunk_syms, anchor, seg_off, nseg, fmt, avg_out, st));
 }
 
 // ---- model table (host arithmetic only) ---------------------------------------------------

@@ -268,6 +268,7 @@ hipError_t co3_launch_fill(int32_t *a, int64_t na, int32_t va, uint32_t *b, int6
     if (m <= 0) return hipSuccess;
     int blocks = (int)((m + 255) / 256);
     if (blocks > 1024) blocks = 1024;
+    Co3LaunchTimer tm(CO3_K_FILL, st);
     hipLaunchKernelGGL(k_fill_i32, dim3(blocks), dim3(256), 0, st, a, na, va, b, nb);
     return hipGetLastError();
 }
@@ -278,6 +279,7 @@ hipError_t co3_launch_absmax(const float *g, int64_t n, int U, int64_t stride, c
     if (n <= 0) return hipSuccess;
     int blocks;
     int64_t pb = per_block_for(n, U, CV_TILE, &blocks);
+    Co3LaunchTimer tm(CO3_K_ABSMAX, st);
     hipLaunchKernelGGL(k_absmax, dim3(blocks, U), dim3(CV_BLOCK), 0, st, g, n, stride, seg_off, nseg, anchor, pb);
     return hipGetLastError();
 }
@@ -289,6 +291,7 @@ hipError_t co3_launch_convert(const float *g, float *err, uint8_t *sym, int64_t 
     if (n <= 0) return hipSuccess;
     int blocks;
     int64_t pb = per_block_for(n, U, CV_TILE, &blocks);
+    Co3LaunchTimer tm(CO3_K_CONVERT, st);
     if (counts)
         hipLaunchKernelGGL(k_convert_ef<true>, dim3(blocks, U), dim3(CV_BLOCK), 0, st, g, err, sym, n, stride, seg_off,
                            nseg, anchor, gamma, fmt, counts, pb);
@@ -304,6 +307,7 @@ hipError_t co3_launch_histogram(const uint8_t *sym, int64_t n, int U, int64_t st
     if (n <= 0) return hipSuccess;
     int blocks;
     int64_t pb = per_block_for(n, U, HS_TILE, &blocks);
+    Co3LaunchTimer tm(CO3_K_HISTOGRAM, st);
     hipLaunchKernelGGL(k_histogram, dim3(blocks, U), dim3(CV_BLOCK), 0, st, sym, n, stride, K, counts, pb);
     return hipGetLastError();
 }

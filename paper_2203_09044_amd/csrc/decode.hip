@@ -3,48 +3,105 @@
 #include "co3_dev.h"
 #include "kernels.h"
 
-#define DE_BLOCK 256
+#define DE_BLOCK 1024
 
 __device__ __forceinline__ const Co3Code *dcode_of(const void *codes, int u)
 {
     return reinterpret_cast<const Co3Code *>(reinterpret_cast<const char *>(codes) + (size_t)u * CO3_CODE_BYTES);
 }
 
-// The stream as 32-bit pieces in stream order: piece q holds stream bits [32q, 32q+32), first bit
-// in its top bit.  In memory the words are little-endian u64, so piece q is 32-bit element q ^ 1.
-struct BitReader {
-    const uint32_t *w32;
-    int64_t npieces;     // 2 * cap_words: reads beyond are zeros
-    uint64_t buf;        // upcoming bits, left-justified
-    int avail;           // valid bits in buf
-    int64_t q;           // next piece to load
+// ------------------------------------------------------------------------------------------
+// Per-lane stream window in LDS.  The stream is read in 16-byte blocks (4 pieces of 32 bits; piece q
+// holds stream bits [32q, 32q+32), first bit on top; in memory the words are little-endian u64, so
+// the two pieces of a word are swapped).  Each lane keeps the 4 most recent blocks of its chunk in
+// a 16-dword ring, stored in descending piece order (piece q at ring index 16 - (q mod 16), and a
+// copy of the piece with q mod 16 == 0 at index 0) so that pieces q and q+1 are one two-dword read
+// that lands as a 64-bit register pair with piece q on top.  Blocks are requested one group of 8
+// symbols ahead of their use, at a cadence that is the same for all lanes of the wavefront, so the
+// global-load latency hides behind the decoding of the previous group.
+// ------------------------------------------------------------------------------------------
+#define RING_STRIDE 17
+#define DE_GROUP 8
+typedef uint64_t u64_align4 __attribute__((aligned(4)));
 
-    __device__ __forceinline__ uint32_t piece(int64_t k) const { return (k >= 0 && k < npieces) ? w32[k ^ 1] : 0u; }
-    __device__ __forceinline__ void seek(uint64_t p)
+struct LaneStream {
+    const uint4 *blocks;   // the user's stream as 16-byte blocks
+    int64_t nblocks;       // blocks inside the buffer; beyond read as zeros
+    int64_t base_blk;      // absolute index of relative block 0 (the block holding the chunk start)
+    uint32_t *slot;        // this lane's ring in LDS
+    uint32_t rel;          // current bit position relative to block base_blk
+    uint32_t loaded;       // relative blocks [loaded-4, loaded) are in the ring
+    bool inflight;         // block `loaded` has been requested and sits in `fl`
+    uint4 fl;
+
+    __device__ __forceinline__ uint4 fetch(uint32_t relblk) const
     {
-        int64_t k = (int64_t)(p >> 5);
-        int o = (int)(p & 31);
-        buf = (((uint64_t)piece(k) << 32) | (uint64_t)piece(k + 1)) << o;
-        avail = 64 - o;
-        q = k + 2;
+        int64_t b = base_blk + relblk;
+        return (b >= 0 && b < nblocks) ? blocks[b] : make_uint4(0u, 0u, 0u, 0u);
     }
-    __device__ __forceinline__ uint64_t pos() const { return (uint64_t)(q << 5) - (uint64_t)avail; }
-    __device__ __forceinline__ void refill()
+    __device__ __forceinline__ void put(uint32_t relblk, uint4 v)
     {
-        if (avail <= 32) {
-            buf |= (uint64_t)piece(q) << (32 - avail);
-            avail += 32;
-            ++q;
+        uint32_t top = 16u - (relblk & 3u) * 4u;   // ring index of the block's first piece
+        slot[top - 3] = v.z;
+        slot[top - 2] = v.w;
+        slot[top - 1] = v.x;
+        slot[top] = v.y;
+        if (top == 16u) slot[0] = v.y;
+    }
+    __device__ __forceinline__ void land()
+    {
+        if (inflight) {
+            put(loaded, fl);
+            ++loaded;
+            inflight = false;
         }
     }
-    // 64 stream bits starting at absolute position p
-    __device__ __forceinline__ uint64_t peek64(uint64_t p) const
+    // make pieces [.., need_dw) resident (synchronous; only used off the fast path)
+    __device__ __forceinline__ void ensure(uint32_t need_dw)
     {
-        int64_t k = (int64_t)(p >> 5);
-        int o = (int)(p & 31);
-        uint64_t hi = ((uint64_t)piece(k) << 32) | (uint64_t)piece(k + 1);
-        uint64_t lo = (uint64_t)piece(k + 2);
-        return o ? ((hi << o) | (lo >> (32 - o))) : hi;
+        land();
+        while (loaded * 4u < need_dw) {
+            put(loaded, fetch(loaded));
+            ++loaded;
+        }
+    }
+    __device__ __forceinline__ void open(uint64_t p0)
+    {
+        base_blk = (int64_t)(p0 >> 7);
+        rel = (uint32_t)(p0 & 127u);
+        inflight = false;
+        uint4 a = fetch(0), b = fetch(1), c = fetch(2);
+        put(0, a);
+        put(1, b);
+        put(2, c);
+        loaded = 3;
+    }
+    // Start of a group of DE_GROUP symbols.  On entry blocks cur .. cur+2 are resident or landing
+    // (a group whose codewords all fit the table prefix consumes at most 96 bits, less than a
+    // block); on exit block cur+3 is resident or requested.
+    __device__ __forceinline__ void group_boundary()
+    {
+        land();
+        if (loaded < (rel >> 7) + 4u) {
+            fl = fetch(loaded);
+            inflight = true;
+        }
+    }
+    __device__ __forceinline__ uint64_t pos() const { return ((uint64_t)base_blk << 7) + rel; }
+    // the 32 stream bits at the current position
+    __device__ __forceinline__ uint32_t peek32() const
+    {
+        uint64_t two = *reinterpret_cast<const u64_align4 *>(slot + (~(rel >> 5) & 15u));
+        return (uint32_t)((two << (rel & 31u)) >> 32);
+    }
+    __device__ __forceinline__ uint32_t piece(uint32_t d) const { return slot[16u - (d & 15u)]; }
+    __device__ __forceinline__ uint64_t peek64()
+    {
+        uint32_t d = rel >> 5, o = rel & 31u;
+        ensure(d + 3u);
+        uint64_t hi = ((uint64_t)piece(d) << 32) | (uint64_t)piece(d + 1u);
+        uint64_t lo = (uint64_t)piece(d + 2u);
+        return o ? ((hi << o) | (lo >> (32u - o))) : hi;
     }
 };
 
@@ -87,59 +144,95 @@ __device__ __forceinline__ int decode_long(const DecTables &t, uint64_t window, 
     return 0;
 }
 
-// One lane decodes the `nsym` symbols of one chunk and stores them at out[0..nsym).
-__device__ __forceinline__ bool decode_chunk(const DecTables &t, BitReader &br, uint64_t p0, uint64_t p1, int nsym,
-                                             uint8_t *out)
+// Careful decoding of `count` <= 8 symbols (any codeword length, any stream content): used for
+// groups that met a codeword longer than the table prefix and for the ragged end of a chunk.
+// Leaves blocks cur .. cur+2 resident.  Symbols are returned first-in-lowest-byte.
+__device__ __forceinline__ uint64_t decode_group_careful(const DecTables &t, LaneStream &ls, int shift, int count,
+                                                      bool &ok)
 {
-    bool ok = true;
-    const int shift = 64 - (int)t.lut_bits;
-    br.seek(p0);
-    int i = 0;
-    for (; i + 16 <= nsym; i += 16) {
-        uint32_t w[4];
-#pragma unroll
-        for (int a = 0; a < 4; ++a) {
-            uint32_t acc = 0;
-#pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                br.refill();
-                uint32_t e = t.lut[br.buf >> shift];
-                int l = (int)(e >> 8);
-                uint32_t s = e & 0xffu;
-                if (l == 0) {                       // rare: longer than the table prefix
-                    uint64_t p = br.pos();
-                    l = decode_long(t, br.peek64(p), &s);
-                    if (l == 0) { ok = false; l = 1; s = 0; }
-                    br.seek(p + l);
-                } else {
-                    br.buf <<= l;
-                    br.avail -= l;
-                }
-                acc |= s << (8 * b);
-            }
-            w[a] = acc;
-        }
-        *reinterpret_cast<uint4 *>(out + i) = make_uint4(w[0], w[1], w[2], w[3]);
-    }
-    for (; i < nsym; ++i) {
-        br.refill();
-        uint32_t e = t.lut[br.buf >> shift];
-        int l = (int)(e >> 8);
-        uint32_t s = e & 0xffu;
+    uint64_t out = 0;
+    for (int k = 0; k < count; ++k) {
+        ls.ensure((ls.rel >> 5) + 2u);
+        uint32_t e = t.lut[ls.peek32() >> shift];
+        uint32_t l = e >> 8, s = e & 0xffu;
         if (l == 0) {
-            uint64_t p = br.pos();
-            l = decode_long(t, br.peek64(p), &s);
-            if (l == 0) { ok = false; l = 1; s = 0; }
-            br.seek(p + l);
-        } else {
-            br.buf <<= l;
-            br.avail -= l;
+            l = (uint32_t)decode_long(t, ls.peek64(), &s);
+            if (l == 0) {
+                ok = false;
+                l = 1;
+                s = 0;
+            }
         }
-        out[i] = (uint8_t)s;
+        ls.rel += l;
+        out |= (uint64_t)s << (8 * k);
     }
-    return ok && br.pos() == p1;
+    ls.ensure(((ls.rel >> 7) + 3u) * 4u);
+    return out;
 }
 
+// One lane decodes the `nsym` symbols of one chunk.  Symbols leave in runs of 16: run r is stored at
+// out + r * run_step (run_step = 16 gives the plain contiguous layout; the tiled layout used between
+// decoding and averaging interleaves the runs of the 64 chunks of a wavefront so that each store
+// instruction of the wavefront covers one contiguous KiB).
+__device__ __forceinline__ bool decode_chunk(const DecTables &t, LaneStream &ls, uint64_t p0, uint64_t p1, int nsym,
+                                             uint8_t *out, int64_t run_step)
+{
+    bool ok = true;
+    const int shift = 32 - (int)t.lut_bits;
+    ls.open(p0);
+    int i = 0;
+#pragma unroll 1
+    for (; i + 2 * DE_GROUP <= nsym; i += 2 * DE_GROUP) {
+        uint32_t w0 = 0, w1 = 0, w2 = 0, w3 = 0;
+#pragma unroll 1
+        for (int h = 0; h < 2; ++h) {
+            ls.group_boundary();
+            const uint32_t rel0 = ls.rel;
+            uint32_t lo = 0, hi = 0, minlen = 255u;
+            uint32_t nrel = ~rel0;          // complement of the position: ring index and shift come cheaper
+#pragma unroll
+            for (int b = 0; b < DE_GROUP; ++b) {
+                uint64_t two = *reinterpret_cast<const u64_align4 *>(ls.slot + ((nrel >> 5) & 15u));
+                uint32_t w = (uint32_t)((two << (~nrel & 31u)) >> 32);
+                uint32_t e = t.lut[w >> shift];
+                uint32_t l = e >> 8;
+                minlen = min(minlen, l);
+                nrel -= l;
+                if (b < 4)
+                    lo = __builtin_amdgcn_alignbit(e, lo, 8);
+                else
+                    hi = __builtin_amdgcn_alignbit(e, hi, 8);
+            }
+            ls.rel = ~nrel;
+            if (minlen == 0) {          // rare: redo the group with the careful decoder
+                ls.rel = rel0;
+                uint64_t r = decode_group_careful(t, ls, shift, DE_GROUP, ok);
+                lo = (uint32_t)r;
+                hi = (uint32_t)(r >> 32);
+            }
+            if (h == 0) {
+                w0 = lo;
+                w1 = hi;
+            } else {
+                w2 = lo;
+                w3 = hi;
+            }
+        }
+        *reinterpret_cast<uint4 *>(out + (int64_t)(i >> 4) * run_step) = make_uint4(w0, w1, w2, w3);
+    }
+    for (int left = nsym - i; left > 0; left -= DE_GROUP) {      // ragged end of the last chunk
+        ls.group_boundary();
+        int cnt = left < DE_GROUP ? left : DE_GROUP;
+        uint64_t r = decode_group_careful(t, ls, shift, cnt, ok);
+        for (int k = 0; k < cnt; ++k, ++i) out[(int64_t)(i >> 4) * run_step + (i & 15)] = (uint8_t)(r >> (8 * k));
+    }
+    ls.land();
+    return ok && ls.pos() == p1;
+}
+
+// TILED = false: sym_out is [U][stride] symbols in order.  TILED = true: sym_out is the averaging
+// workspace, [U][tiles][chunk_syms/16][64 lanes][16 symbols] with tile = 64 consecutive chunks.
+template <bool TILED>
 __global__ __launch_bounds__(DE_BLOCK) void k_decode(const uint64_t *__restrict__ words, int64_t cap_words,
                                                       const uint64_t *__restrict__ chunk_bitoff, int chunk_syms,
                                                       int64_t nchunks, const void *__restrict__ codes, int64_t n,
@@ -147,18 +240,29 @@ __global__ __launch_bounds__(DE_BLOCK) void k_decode(const uint64_t *__restrict_
 {
     const int u = blockIdx.y;
     __shared__ DecTables t;
+    __shared__ uint32_t ring[DE_BLOCK * RING_STRIDE];
     load_tables(t, dcode_of(codes, u));
     __syncthreads();
 
     const int64_t c = (int64_t)blockIdx.x * DE_BLOCK + threadIdx.x;
     if (c >= nchunks) return;
     const uint64_t *off = chunk_bitoff + (int64_t)u * (nchunks + 1);
-    BitReader br;
-    br.w32 = reinterpret_cast<const uint32_t *>(words + (int64_t)u * cap_words);
-    br.npieces = 2 * cap_words;
+    LaneStream ls;
+    ls.blocks = reinterpret_cast<const uint4 *>(words + (int64_t)u * cap_words);
+    ls.nblocks = cap_words / 2;
+    ls.slot = ring + threadIdx.x * RING_STRIDE;
     int64_t first = c * chunk_syms;
     int nsym = (int)(n - first < chunk_syms ? n - first : chunk_syms);
-    bool ok = decode_chunk(t, br, off[c], off[c + 1], nsym, sym_out + (int64_t)u * stride + first);
+    uint8_t *out;
+    int64_t run_step;
+    if (TILED) {
+        out = sym_out + (int64_t)u * stride + (c >> 6) * ((int64_t)CO3_WAVE * chunk_syms) + (c & 63) * 16;
+        run_step = CO3_WAVE * 16;
+    } else {
+        out = sym_out + (int64_t)u * stride + first;
+        run_step = 16;
+    }
+    bool ok = decode_chunk(t, ls, off[c], off[c + 1], nsym, out, run_step);
     if (!ok) co3_raise(status, CO3_EBADSTREAM);
 }
 
@@ -211,15 +315,88 @@ __global__ __launch_bounds__(PS_BLOCK) void k_ps_sum(const uint8_t *__restrict__
     }
 }
 
+// Average from the tiled workspace: one thread owns a run of 16 consecutive elements.
+#define PT_BLOCK 256
+
+__global__ __launch_bounds__(PT_BLOCK) void k_ps_sum_tiled(const uint8_t *__restrict__ symt, int64_t n, int U,
+                                                            int64_t ws_stride, int chunk_syms, int64_t nruns,
+                                                            const int32_t *__restrict__ anchor,
+                                                            const int64_t *__restrict__ seg_off, int nseg, co3_fmt fmt,
+                                                            float *__restrict__ avg_out)
+{
+    const FmtC fc(fmt);
+    const int EM = fc.E + fc.M, M = fc.M, F = fc.F;
+    const uint32_t cmask = (uint32_t)fc.codemax;
+    const float fU = (float)U;
+    const int runs_per_chunk = chunk_syms >> 4;
+    for (int64_t r = (int64_t)blockIdx.x * PT_BLOCK + threadIdx.x; r < nruns; r += (int64_t)gridDim.x * PT_BLOCK) {
+        // r enumerates (tile, run within chunk, lane) with the lane fastest: the workspace order
+        const int lane = (int)(r & 63);
+        const int64_t q = r >> 6;
+        const int run = (int)(q % runs_per_chunk);
+        const int64_t tile = q / runs_per_chunk;
+        const int64_t i0 = (tile * CO3_WAVE + lane) * chunk_syms + (int64_t)run * 16;
+        if (i0 >= n) continue;
+        const uint8_t *src = symt + r * 16;
+        const int s_lo = co3_find_seg(seg_off, nseg, i0);
+        const int64_t i_last = i0 + 15 < n ? i0 + 15 : n - 1;
+        const int s_hi = co3_find_seg(seg_off, nseg, i_last);
+        float acc[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) acc[k] = 0.f;
+        if (s_lo == s_hi) {
+            for (int u = 0; u < U; ++u) {
+                const int e_min = anchor[(int64_t)u * nseg + s_lo] - F + 1;
+                uint4 v = *reinterpret_cast<const uint4 *>(src + (int64_t)u * ws_stride);
+                uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int k = 0; k < 16; ++k) {
+                    uint32_t s = (w[k >> 2] >> (8 * (k & 3))) & 0xffu;
+                    float val = co3_code_value(s & cmask, e_min, M);
+                    acc[k] += __uint_as_float(__float_as_uint(val) | ((s >> EM) << 31));
+                }
+            }
+        } else {                           // the run straddles tensors: anchor per element
+            for (int u = 0; u < U; ++u) {
+                uint4 v = *reinterpret_cast<const uint4 *>(src + (int64_t)u * ws_stride);
+                uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int k = 0; k < 16; ++k) {
+                    int sg = co3_find_seg(seg_off, nseg, i0 + k < n ? i0 + k : n - 1);
+                    const int e_min = anchor[(int64_t)u * nseg + sg] - F + 1;
+                    uint32_t s = (w[k >> 2] >> (8 * (k & 3))) & 0xffu;
+                    float val = co3_code_value(s & cmask, e_min, M);
+                    acc[k] += __uint_as_float(__float_as_uint(val) | ((s >> EM) << 31));
+                }
+            }
+        }
+        if (i0 + 16 <= n) {
+#pragma unroll
+            for (int k = 0; k < 16; k += 4)
+                *reinterpret_cast<float4 *>(avg_out + i0 + k) =
+                    make_float4(acc[k] / fU, acc[k + 1] / fU, acc[k + 2] / fU, acc[k + 3] / fU);
+        } else {
+#pragma unroll
+            for (int k = 0; k < 16; ++k)
+                if (i0 + k < n) avg_out[i0 + k] = acc[k] / fU;
+        }
+    }
+}
+
 hipError_t co3_launch_decode(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff, int chunk_syms,
-                             const void *codes, int64_t n, int U, uint8_t *sym_out, int64_t stride, int32_t *status,
-                             hipStream_t st)
+                             const void *codes, int64_t n, int U, uint8_t *sym_out, int64_t stride, int tiled,
+                             int32_t *status, hipStream_t st)
 {
     const int64_t nchunks = (n + chunk_syms - 1) / chunk_syms;
     if (nchunks <= 0) return hipSuccess;
     unsigned blocks = (unsigned)((nchunks + DE_BLOCK - 1) / DE_BLOCK);
-    hipLaunchKernelGGL(k_decode, dim3(blocks, U), dim3(DE_BLOCK), 0, st, words, cap_words, chunk_bitoff, chunk_syms,
-                       nchunks, codes, n, sym_out, stride, status);
+    Co3LaunchTimer tm(CO3_K_DECODE, st);
+    if (tiled)
+        hipLaunchKernelGGL(k_decode<true>, dim3(blocks, U), dim3(DE_BLOCK), 0, st, words, cap_words, chunk_bitoff,
+                           chunk_syms, nchunks, codes, n, sym_out, stride, status);
+    else
+        hipLaunchKernelGGL(k_decode<false>, dim3(blocks, U), dim3(DE_BLOCK), 0, st, words, cap_words, chunk_bitoff,
+                           chunk_syms, nchunks, codes, n, sym_out, stride, status);
     return hipGetLastError();
 }
 
@@ -229,7 +406,24 @@ hipError_t co3_launch_ps_sum(const uint8_t *sym, int64_t n, int U, int64_t strid
     if (n <= 0) return hipSuccess;
     int64_t tiles = (n + PS_TILE - 1) / PS_TILE;
     unsigned blocks = (unsigned)(tiles < 4096 ? tiles : 4096);
+    Co3LaunchTimer tm(CO3_K_PS_SUM, st);
     hipLaunchKernelGGL(k_ps_sum, dim3(blocks), dim3(PS_BLOCK), 0, st, sym, n, U, stride, anchor, seg_off, nseg, fmt,
                        avg_out);
+    return hipGetLastError();
+}
+
+hipError_t co3_launch_ps_sum_tiled(const uint8_t *symt, int64_t n, int U, int64_t ws_stride, int chunk_syms,
+                                   const int32_t *anchor, const int64_t *seg_off, int nseg, co3_fmt fmt,
+                                   float *avg_out, hipStream_t st)
+{
+    if (n <= 0) return hipSuccess;
+    const int64_t nchunks = (n + chunk_syms - 1) / chunk_syms;
+    const int64_t ntiles = (nchunks + CO3_WAVE - 1) / CO3_WAVE;
+    const int64_t nruns = ntiles * (chunk_syms >> 4) * CO3_WAVE;
+    int64_t b = (nruns + PT_BLOCK - 1) / PT_BLOCK;
+    unsigned blocks = (unsigned)(b < 8192 ? b : 8192);
+    Co3LaunchTimer tm(CO3_K_PS_SUM, st);
+    hipLaunchKernelGGL(k_ps_sum_tiled, dim3(blocks), dim3(PT_BLOCK), 0, st, symt, n, U, ws_stride, chunk_syms, nruns,
+                       anchor, seg_off, nseg, fmt, avg_out);
     return hipGetLastError();
 }

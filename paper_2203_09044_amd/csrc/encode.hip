@@ -258,11 +258,17 @@ hipError_t co3_launch_encode(const uint8_t *sym, int64_t n, int U, int64_t strid
 {
     const int64_t nblk = (n + CO3_PACK_SYMS - 1) / CO3_PACK_SYMS;
     const int64_t nchunks = (n + chunk_syms - 1) / chunk_syms;
-    if (nblk > 0)
+    if (nblk > 0) {
+        Co3LaunchTimer tm(CO3_K_ENC_SIZES, st);
         hipLaunchKernelGGL(k_enc_sizes, dim3((unsigned)nblk, U), dim3(EN_BLOCK), 0, st, sym, n, stride, codes, blocksum,
                            nblk, status);
-    hipLaunchKernelGGL(k_enc_scan, dim3(U), dim3(SC_BLOCK), 0, st, blocksum, nblk, words, cap_words, chunk_bitoff,
-                       nchunks, total_bits, status);
+    }
+    {
+        Co3LaunchTimer tm(CO3_K_ENC_SCAN, st);
+        hipLaunchKernelGGL(k_enc_scan, dim3(U), dim3(SC_BLOCK), 0, st, blocksum, nblk, words, cap_words, chunk_bitoff,
+                           nchunks, total_bits, status);
+    }
+    Co3LaunchTimer tm(CO3_K_ENC_PACK, st);
     if (nblk > 0)
         hipLaunchKernelGGL(k_enc_pack, dim3((unsigned)nblk, U), dim3(EN_BLOCK), 0, st, sym, n, stride, codes,
                            (const uint64_t *)blocksum, nblk, words, cap_words, chunk_syms, chunk_bitoff, nchunks,

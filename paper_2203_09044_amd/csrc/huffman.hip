@@ -156,6 +156,7 @@ __global__ __launch_bounds__(HB_BLOCK) void k_build_code(const uint32_t *__restr
 hipError_t co3_launch_build_code(const uint32_t *weights, int U, int K, void *codes, int32_t *status, hipStream_t st)
 {
     if (U <= 0) return hipSuccess;
+    Co3LaunchTimer tm(CO3_K_BUILD, st);
     hipLaunchKernelGGL(k_build_code, dim3(U), dim3(HB_BLOCK), 0, st, weights, K, reinterpret_cast<char *>(codes),
                        status);
     return hipGetLastError();

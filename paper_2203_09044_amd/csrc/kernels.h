@@ -5,6 +5,21 @@
 
 #include "../../include/co3.h"
 
+// Kernel ids for the optional launch timing (co3_timing_* in the public header).
+enum Co3Kernel {
+    CO3_K_FILL = 0, CO3_K_ABSMAX, CO3_K_CONVERT, CO3_K_HISTOGRAM, CO3_K_BUILD, CO3_K_ENC_SIZES, CO3_K_ENC_SCAN,
+    CO3_K_ENC_PACK, CO3_K_DECODE, CO3_K_PS_SUM, CO3_K_COUNT
+};
+
+// Brackets one kernel launch with a pair of HIP events on the launch stream when timing of that
+// kernel is enabled; otherwise does nothing.
+struct Co3LaunchTimer {
+    Co3LaunchTimer(int kernel, hipStream_t st);
+    ~Co3LaunchTimer();
+    int slot;
+    hipStream_t stream;
+};
+
 hipError_t co3_launch_fill(int32_t *a, int64_t na, int32_t va, uint32_t *b, int64_t nb, hipStream_t st);
 hipError_t co3_launch_absmax(const float *g, int64_t n, int U, int64_t stride, const int64_t *seg_off, int nseg,
                              int32_t *anchor, hipStream_t st);
@@ -18,7 +33,10 @@ hipError_t co3_launch_encode(const uint8_t *sym, int64_t n, int U, int64_t strid
                              int64_t cap_words, int chunk_syms, uint64_t *chunk_bitoff, uint64_t *total_bits,
                              uint64_t *blocksum, int32_t *status, hipStream_t st);
 hipError_t co3_launch_decode(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff, int chunk_syms,
-                             const void *codes, int64_t n, int U, uint8_t *sym_out, int64_t stride, int32_t *status,
-                             hipStream_t st);
+                             const void *codes, int64_t n, int U, uint8_t *sym_out, int64_t stride, int tiled,
+                             int32_t *status, hipStream_t st);
+hipError_t co3_launch_ps_sum_tiled(const uint8_t *symt, int64_t n, int U, int64_t ws_stride, int chunk_syms,
+                                   const int32_t *anchor, const int64_t *seg_off, int nseg, co3_fmt fmt,
+                                   float *avg_out, hipStream_t st);
 hipError_t co3_launch_ps_sum(const uint8_t *sym, int64_t n, int U, int64_t stride, const int32_t *anchor,
                              const int64_t *seg_off, int nseg, co3_fmt fmt, float *avg_out, hipStream_t st);

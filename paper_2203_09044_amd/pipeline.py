@@ -27,7 +27,7 @@ class Co3Pipeline:
         self.device = dev
         self.stride = _round_up(max(n, 1), 16)
         self.nchunks = (n + chunk_syms - 1) // chunk_syms
-        self.cap_words = B.cap_words_empirical(n, fmt) if cap_words is None else cap_words
+        self.cap_words = B.cap_words_empirical(n, fmt) if cap_words is None else _round_up(cap_words, 2)
         self.seg_off = None if seg_off is None else torch.as_tensor(seg_off, dtype=torch.int64).to(dev)
         self.nseg = 1 if seg_off is None else self.seg_off.numel() - 1
         z = dict(device=dev)
@@ -40,7 +40,7 @@ class Co3Pipeline:
         self.chunk_bitoff = torch.zeros((U, self.nchunks + 1), dtype=torch.int64, **z)
         self.total_bits = torch.zeros((U,), dtype=torch.int64, **z)
         self.enc_ws = torch.zeros((max(B.encode_workspace_bytes(n, U), 8) // 8,), dtype=torch.int64, **z)
-        self.agg_ws = torch.zeros((max(B.ps_aggregate_workspace_bytes(self.stride, U), 16),), dtype=torch.uint8, **z)
+        self.agg_ws = torch.zeros((max(B.ps_aggregate_workspace_bytes(n, U, chunk_syms), 16),), dtype=torch.uint8, **z)
         self.avg = torch.zeros((self.stride,), dtype=torch.float32, **z)
         self.sym_dec = torch.zeros((U, self.stride), dtype=torch.uint8, **z)
         self.status = torch.zeros((1,), dtype=torch.int32, **z)
