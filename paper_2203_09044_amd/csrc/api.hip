@@ -209,8 +209,10 @@ int32_t co3_encode(const uint8_t *sym, int64_t n, int32_t U, int64_t stride, co3
     if (!aligned(sym, 16) || !aligned(words, 16) || !aligned(codes, 8) || !aligned(workspace, 8)) return CO3_EINVAL;
     if (cap_words % 2 != 0) return CO3_EINVAL;
     if (ws_bytes < co3_encode_workspace_bytes(n, U)) return CO3_EINVAL;
-    return hip_rc(co3_launch_encode(sym, n, U, stride, codes, words, cap_words, chunk_syms, chunk_bitoff, total_bits,
-                                    static_cast<uint64_t *>(workspace), status, static_cast<hipStream_t>(stream)));
+    const FmtC fc(fmt);
+    return hip_rc(co3_launch_encode(sym, n, U, stride, codes, fc.K, words, cap_words, chunk_syms, chunk_bitoff,
+                                    total_bits, static_cast<uint64_t *>(workspace), status,
+                                    static_cast<hipStream_t>(stream)));
 }
 
 int32_t co3_decode(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff, int32_t chunk_syms,

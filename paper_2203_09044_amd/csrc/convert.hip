@@ -23,14 +23,34 @@ __global__ void k_fill_i32(int32_t *a, int64_t na, int32_t va, uint32_t *b, int6
 // anchor: A = floor(log2 max|g|) per (user, segment) = biased exponent of the largest magnitude
 // minus 127, at most 127; the lower clamp comes from the initial value.
 // ------------------------------------------------------------------------------------------
-__device__ __forceinline__ void absmax_flush(uint32_t m, int32_t *anchor_us)
+#define AM_UNROLL 4
+#define AM_TILE (CV_TILE * AM_UNROLL)   // elements per block step: four 16-byte loads in flight per thread
+
+// Block-wide maximum of the magnitude bit patterns, then at most one atomic per block (and none
+// when the anchor already holds a value at least as large).  Called under block-uniform conditions.
+__device__ __forceinline__ void absmax_flush(uint32_t m, int32_t *anchor_us, uint32_t *red)
 {
     m = wave_max_u32(m);
-    if ((threadIdx.x & (CO3_WAVE - 1)) == 0) {
-        int cand = (int)(m >> 23) - 127;
+    if ((threadIdx.x & (CO3_WAVE - 1)) == 0) red[threadIdx.x / CO3_WAVE] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t mm = red[0];
+        for (int w = 1; w < CV_BLOCK / CO3_WAVE; ++w) mm = mm > red[w] ? mm : red[w];
+        int cand = (int)(mm >> 23) - 127;
         if (cand > 127) cand = 127;
-        atomicMax(anchor_us, cand);
+        if (cand > *reinterpret_cast<volatile int32_t *>(anchor_us)) atomicMax(anchor_us, cand);
     }
+    __syncthreads();
+}
+
+__device__ __forceinline__ uint32_t absmax4(float4 v, uint32_t m)
+{
+    uint32_t a0 = __float_as_uint(v.x) & 0x7fffffffu, a1 = __float_as_uint(v.y) & 0x7fffffffu;
+    uint32_t a2 = __float_as_uint(v.z) & 0x7fffffffu, a3 = __float_as_uint(v.w) & 0x7fffffffu;
+    a0 = a0 > a1 ? a0 : a1;
+    a2 = a2 > a3 ? a2 : a3;
+    a0 = a0 > a2 ? a0 : a2;
+    return m > a0 ? m : a0;
 }
 
 __global__ __launch_bounds__(CV_BLOCK) void k_absmax(const float *__restrict__ g, int64_t n, int64_t stride,
@@ -40,48 +60,60 @@ __global__ __launch_bounds__(CV_BLOCK) void k_absmax(const float *__restrict__ g
     const int u = blockIdx.y;
     const float *gu = g + (int64_t)u * stride;
     int32_t *anchor_u = anchor + (int64_t)u * nseg;
+    __shared__ uint32_t red[CV_BLOCK / CO3_WAVE];
     int64_t beg = (int64_t)blockIdx.x * per_block;
     int64_t end = beg + per_block < n ? beg + per_block : n;
     if (beg >= end) return;
 
     int cur_seg = co3_find_seg(seg_off, nseg, beg);
     uint32_t m = 0;
-    for (int64_t t0 = beg; t0 < end; t0 += CV_TILE) {
-        int64_t t1 = t0 + CV_TILE < end ? t0 + CV_TILE : end;
+    for (int64_t t0 = beg; t0 < end; t0 += AM_TILE) {
+        int64_t t1 = t0 + AM_TILE < end ? t0 + AM_TILE : end;
         int s_lo = co3_find_seg(seg_off, nseg, t0);
         int s_hi = co3_find_seg(seg_off, nseg, t1 - 1);
         int64_t i = t0 + (int64_t)threadIdx.x * CV_VEC;
         if (s_lo == s_hi) {
             if (s_lo != cur_seg) {       // block-uniform branch
-                absmax_flush(m, anchor_u + cur_seg);
+                absmax_flush(m, anchor_u + cur_seg, red);
                 m = 0;
                 cur_seg = s_lo;
             }
-            if (i + CV_VEC <= t1) {
-                float4 v = *reinterpret_cast<const float4 *>(gu + i);
-                uint32_t a0 = __float_as_uint(v.x) & 0x7fffffffu, a1 = __float_as_uint(v.y) & 0x7fffffffu;
-                uint32_t a2 = __float_as_uint(v.z) & 0x7fffffffu, a3 = __float_as_uint(v.w) & 0x7fffffffu;
-                a0 = a0 > a1 ? a0 : a1;
-                a2 = a2 > a3 ? a2 : a3;
-                a0 = a0 > a2 ? a0 : a2;
-                m = m > a0 ? m : a0;
+            if (t1 - t0 == AM_TILE) {
+                float4 v0 = *reinterpret_cast<const float4 *>(gu + i);
+                float4 v1 = *reinterpret_cast<const float4 *>(gu + i + CV_TILE);
+                float4 v2 = *reinterpret_cast<const float4 *>(gu + i + 2 * CV_TILE);
+                float4 v3 = *reinterpret_cast<const float4 *>(gu + i + 3 * CV_TILE);
+                m = absmax4(v0, m);
+                m = absmax4(v1, m);
+                m = absmax4(v2, m);
+                m = absmax4(v3, m);
             } else {
-                for (int64_t j = i; j < t1; ++j) {
-                    uint32_t a = __float_as_uint(gu[j]) & 0x7fffffffu;
-                    m = m > a ? m : a;
+                for (int k = 0; k < AM_UNROLL; ++k) {
+                    int64_t j0 = i + (int64_t)k * CV_TILE;
+                    if (j0 + CV_VEC <= t1) {
+                        m = absmax4(*reinterpret_cast<const float4 *>(gu + j0), m);
+                    } else {
+                        for (int64_t j = j0; j < t1; ++j) {
+                            uint32_t a = __float_as_uint(gu[j]) & 0x7fffffffu;
+                            m = m > a ? m : a;
+                        }
+                    }
                 }
             }
         } else {                         // tile straddles tensors: per element
-            for (int64_t j = i; j < i + CV_VEC && j < t1; ++j) {
-                uint32_t a = __float_as_uint(gu[j]) & 0x7fffffffu;
-                int cand = (int)(a >> 23) - 127;
-                if (cand > 127) cand = 127;
-                int s = co3_find_seg(seg_off, nseg, j);
-                atomicMax(anchor_u + s, cand);
+            for (int k = 0; k < AM_UNROLL; ++k) {
+                int64_t j0 = i + (int64_t)k * CV_TILE;
+                for (int64_t j = j0; j < j0 + CV_VEC && j < t1; ++j) {
+                    uint32_t a = __float_as_uint(gu[j]) & 0x7fffffffu;
+                    int cand = (int)(a >> 23) - 127;
+                    if (cand > 127) cand = 127;
+                    int sg = co3_find_seg(seg_off, nseg, j);
+                    if (cand > *reinterpret_cast<volatile int32_t *>(anchor_u + sg)) atomicMax(anchor_u + sg, cand);
+                }
             }
         }
     }
-    absmax_flush(m, anchor_u + cur_seg);
+    absmax_flush(m, anchor_u + cur_seg, red);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -278,7 +310,7 @@ hipError_t co3_launch_absmax(const float *g, int64_t n, int U, int64_t stride, c
 {
     if (n <= 0) return hipSuccess;
     int blocks;
-    int64_t pb = per_block_for(n, U, CV_TILE, &blocks);
+    int64_t pb = per_block_for(n, U, AM_TILE, &blocks);
     Co3LaunchTimer tm(CO3_K_ABSMAX, st);
     hipLaunchKernelGGL(k_absmax, dim3(blocks, U), dim3(CV_BLOCK), 0, st, g, n, stride, seg_off, nseg, anchor, pb);
     return hipGetLastError();
