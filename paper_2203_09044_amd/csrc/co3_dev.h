@@ -37,6 +37,26 @@ struct FmtC {
           codemax((1 << (f.exp_bits + f.mant_bits)) - 1) {}
 };
 
+// Streaming (non-temporal) 16-byte accesses for data that is touched once per kernel.
+typedef float co3_f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t co3_u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float4 ld_stream_f4(const float *p)
+{
+    co3_f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const co3_f32x4 *>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void st_stream_f4(float *p, float4 a)
+{
+    co3_f32x4 v = {a.x, a.y, a.z, a.w};
+    __builtin_nontemporal_store(v, reinterpret_cast<co3_f32x4 *>(p));
+}
+__device__ __forceinline__ uint4 ld_stream_u4(const void *p)
+{
+    co3_u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const co3_u32x4 *>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 __device__ __forceinline__ void co3_raise(int32_t *status, int32_t code)
 {
     if (status) atomicMin(status, code);

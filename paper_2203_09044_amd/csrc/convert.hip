@@ -79,10 +79,10 @@ __global__ __launch_bounds__(CV_BLOCK) void k_absmax(const float *__restrict__ g
                 cur_seg = s_lo;
             }
             if (t1 - t0 == AM_TILE) {
-                float4 v0 = *reinterpret_cast<const float4 *>(gu + i);
-                float4 v1 = *reinterpret_cast<const float4 *>(gu + i + CV_TILE);
-                float4 v2 = *reinterpret_cast<const float4 *>(gu + i + 2 * CV_TILE);
-                float4 v3 = *reinterpret_cast<const float4 *>(gu + i + 3 * CV_TILE);
+                float4 v0 = ld_stream_f4(gu + i);
+                float4 v1 = ld_stream_f4(gu + i + CV_TILE);
+                float4 v2 = ld_stream_f4(gu + i + 2 * CV_TILE);
+                float4 v3 = ld_stream_f4(gu + i + 3 * CV_TILE);
                 m = absmax4(v0, m);
                 m = absmax4(v1, m);
                 m = absmax4(v2, m);
@@ -182,8 +182,8 @@ __global__ __launch_bounds__(CV_BLOCK) void k_convert_ef(const float *__restrict
         if (s_lo == s_hi && i + CV_VEC <= t1) {
             const int A = anchor_u[s_lo];
             const int e_min = A - F + 1;
-            float4 gv = *reinterpret_cast<const float4 *>(gu + i);
-            float4 ev = *reinterpret_cast<const float4 *>(eu + i);
+            float4 gv = ld_stream_f4(gu + i);
+            float4 ev = ld_stream_f4(eu + i);
             float x0 = gv.x + gamma * ev.x, x1 = gv.y + gamma * ev.y;   // no contraction (build flag):
             float x2 = gv.z + gamma * ev.z, x3 = gv.w + gamma * ev.w;   // one rounding per operation
             uint32_t q0, q1, q2, q3;
@@ -193,7 +193,7 @@ __global__ __launch_bounds__(CV_BLOCK) void k_convert_ef(const float *__restrict
             co3_quantize(x2, e_min, A, E, M, codemax, q2, v2);
             co3_quantize(x3, e_min, A, E, M, codemax, q3, v3);
             float4 en = make_float4(x0 - v0, x1 - v1, x2 - v2, x3 - v3);
-            *reinterpret_cast<float4 *>(eu + i) = en;
+            st_stream_f4(eu + i, en);
             *reinterpret_cast<uint32_t *>(su + i) = q0 | (q1 << 8) | (q2 << 16) | (q3 << 24);
             if (HIST) {
                 atomicAdd(&myhist[q0 * copies + mycopy], 1u);

@@ -1,0 +1,227 @@
+"""Parity at the full sizes of the five benchmark workloads, in the launch configuration that
+bench.py times (chunk 256, fused histogram, tiled averaging workspace).
+
+Where the oracle is fast enough it checks every element of every client (threads over clients;
+the oracle itself stays single-threaded per call).  For the largest workloads a stated subset of
+clients goes through the oracle element by element and every client is checked through
+properties that hold at any size: decode(encode(s)) = s, coded length = sum of count * length,
+chunk offsets consistent with the stream length, histogram total = n.
+Inputs are drawn on the device with the seeded sampler and copied back, so both sides consume
+the same bytes.
+"""
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+import pytest
+
+import oracle
+import co3_inputs as inp
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def co3():
+    import paper_2203_09044_amd as pkg
+    return pkg
+
+
+def u32(t):
+    return t.cpu().numpy().view(np.uint32)
+
+
+def u64(t):
+    return t.cpu().numpy().view(np.uint64)
+
+
+def oracle_client(args):
+    g, err, E, M, seg_off, C, weights = args
+    f = oracle.Fmt(E, M)
+    A = oracle.anchor(g, f, seg_off)
+    sym, e_new = oracle.convert_ef(g, err, A, 1.0, f, seg_off)
+    cnt = oracle.histogram(sym, f)
+    l = oracle.huffman_lengths(cnt if weights is None else weights)
+    words, off, total = oracle.encode(sym, l, oracle.canonical_codes(l), C)
+    return dict(A=A, sym=sym, err=e_new, cnt=cnt, len=l, words=words, off=off, total=total)
+
+
+def compare_client(pipe, u, ref, n):
+    assert np.array_equal(pipe.anchor[u].cpu().numpy(), ref["A"]), "anchor"
+    assert np.array_equal(pipe.sym[u, :n].cpu().numpy(), ref["sym"]), "symbols"
+    assert np.array_equal(u32(pipe.err[u, :n]), ref["err"].view(np.uint32)), "error vector"
+    assert np.array_equal(u32(pipe.counts[u]), ref["cnt"]), "histogram"
+    assert np.array_equal(pipe.codes[u, :pipe.fmt.K].cpu().numpy(), ref["len"]), "code lengths"
+    assert int(pipe.total_bits[u].item()) == ref["total"], "total bits"
+    assert np.array_equal(u64(pipe.chunk_bitoff[u]), ref["off"]), "chunk offsets"
+    nw = (ref["total"] + 63) // 64
+    assert np.array_equal(u64(pipe.words[u, :nw]), ref["words"][:nw]), "stream words"
+
+
+def properties_all_clients(pipe, n):
+    """Size-independent checks on every client, from GPU results only."""
+    pipe.decode()
+    assert pipe.poll() == 0
+    assert torch.equal(pipe.sym_dec[:, :n], pipe.sym[:, :n]), "decode(encode(s)) = s"
+    cnt = pipe.counts.cpu().numpy().view(np.uint32).astype(np.int64)
+    lens = pipe.codes[:, :pipe.fmt.K].cpu().numpy().astype(np.int64)
+    assert np.all(cnt.sum(axis=1) == n)
+    tot = pipe.total_bits.cpu().numpy().astype(np.int64)
+    assert np.array_equal(tot, (cnt * lens).sum(axis=1)), "coded length = sum count * length"
+    off = pipe.chunk_bitoff.cpu().numpy().astype(np.int64)
+    assert np.all(off[:, 0] == 0) and np.array_equal(off[:, -1], tot) and np.all(np.diff(off, axis=1) > 0)
+    for u in range(pipe.U):          # Kraft equality of every client's code
+        l = lens[u][lens[u] > 0]
+        if l.size >= 2:
+            assert abs(float(np.sum(np.exp2(-l.astype(np.float64)))) - 1.0) < 1e-12
+
+
+def fill_from_device(pipe, g, draw):
+    host = []
+    for u in range(pipe.U):
+        x = draw(u)
+        g[u, :pipe.n] = x
+        host.append(x.cpu().numpy())
+    return host
+
+
+def test_c1_full(co3):
+    """C1: 65,536 elements, E3M1, 5 error-feedback iterations, every element."""
+    w = inp.c1()
+    fmt = co3.Fmt(w.E, w.M)
+    pipe = co3.Co3Pipeline(1, w.n, fmt, chunk_syms=256)
+    g = pipe.new_gradient_buffer()
+    err = np.zeros(w.n, np.float32)
+    for t in range(1, w.T + 1):
+        gh = inp.host_gradient(w, 0, t)
+        g[0, :w.n] = torch.from_numpy(gh).cuda()
+        pipe.step(g)
+        assert pipe.poll() == 0
+        ref = oracle_client((gh, err, w.E, w.M, None, 256, None))
+        compare_client(pipe, 0, ref, w.n)
+        want = oracle.aggregate(ref["sym"][None, :], ref["A"][None, :], oracle.Fmt(w.E, w.M))
+        assert np.array_equal(u32(pipe.avg[:w.n]), want.view(np.uint32))
+        err = ref["err"]
+    properties_all_clients(pipe, w.n)
+
+
+def test_c2_full(co3):
+    """C2: 62 tensors, 11,173,962 elements, E4M3, per-tensor anchors; 3 chained iterations checked on
+    every element (the workload's 100 iterations repeat the same code path)."""
+    w = inp.c2()
+    fmt = co3.Fmt(w.E, w.M)
+    pipe = co3.Co3Pipeline(1, w.n, fmt, chunk_syms=256, seg_off=w.seg_off)
+    g = pipe.new_gradient_buffer()
+    err = np.zeros(w.n, np.float32)
+    scales = inp.c2_tensor_scales()
+    for t in range(1, 4):
+        parts = [inp.device_gennorm(s, 0.8, float(a), 2000 + 100 * t + k) for k, (s, a) in enumerate(zip(w.sizes, scales))]
+        x = torch.cat(parts)
+        g[0, :w.n] = x
+        gh = x.cpu().numpy()
+        pipe.step(g)
+        assert pipe.poll() == 0
+        ref = oracle_client((gh, err, w.E, w.M, w.seg_off, 256, None))
+        compare_client(pipe, 0, ref, w.n)
+        want = oracle.aggregate(ref["sym"][None, :], ref["A"][None, :], oracle.Fmt(w.E, w.M), w.seg_off)
+        assert np.array_equal(u32(pipe.avg[:w.n]), want.view(np.uint32))
+        err = ref["err"]
+    properties_all_clients(pipe, w.n)
+
+
+def test_c3_full(co3):
+    """C3 (the benchmark workload): 10 clients x 11,173,962, E3M0; 2 chained iterations, every element of
+    every client, and the average."""
+    w = inp.c3()
+    fmt = co3.Fmt(w.E, w.M)
+    betas = inp.c3_client_betas(w.U)
+    pipe = co3.Co3Pipeline(w.U, w.n, fmt, chunk_syms=256)
+    g = pipe.new_gradient_buffer()
+    errs = [np.zeros(w.n, np.float32) for _ in range(w.U)]
+    with ThreadPoolExecutor(max_workers=10) as pool:
+        for t in range(1, 3):
+            host = fill_from_device(pipe, g, lambda u: inp.device_gennorm(w.n, float(betas[u]), 1e-3, 3000 + 10 * t + u))
+            pipe.step(g)
+            assert pipe.poll() == 0
+            refs = list(pool.map(oracle_client, [(host[u], errs[u], w.E, w.M, None, 256, None) for u in range(w.U)]))
+            for u in range(w.U):
+                compare_client(pipe, u, refs[u], w.n)
+                errs[u] = refs[u]["err"]
+            want = oracle.aggregate(np.stack([r["sym"] for r in refs]), np.stack([r["A"] for r in refs]),
+                                    oracle.Fmt(w.E, w.M))
+            assert np.array_equal(u32(pipe.avg[:w.n]), want.view(np.uint32)), "average"
+    properties_all_clients(pipe, w.n)
+
+
+def test_c4_full(co3):
+    """C4: 100M elements, E5M2, with outliers; empirical table and the fixed GenNorm-model table, one
+    iteration each on every element."""
+    w = inp.c4()
+    fmt = co3.Fmt(w.E, w.M)
+    f = oracle.Fmt(w.E, w.M)
+    n = w.n
+    x = inp.device_gennorm(n, 1.0, 1e-4, 4001)
+    mask = torch.rand(n, device="cuda", generator=torch.Generator(device="cuda").manual_seed(4002)) < 1e-4
+    x = torch.where(mask, x * 100.0, x)
+    gh = x.cpu().numpy()
+    for table in ("empirical", "model"):
+        pipe = co3.Co3Pipeline(1, n, fmt, chunk_syms=256, cap_words=None if table == "empirical" else n // 4)
+        g = pipe.new_gradient_buffer()
+        g[0, :n] = x
+        del_g = g
+        weights = None
+        if table == "model":
+            pipe.convert(g)
+            A = int(pipe.anchor[0, 0].item())
+            wdev = co3.binding.model_weights(A, fmt, 1.0, 1e-4)
+            weights = oracle.model_weights(A, f, 1.0, 1e-4)
+            assert np.array_equal(wdev.numpy().view(np.uint32), weights)
+            pipe.build(wdev.cuda().reshape(1, -1))
+            pipe.encode()
+            pipe.aggregate()
+        else:
+            pipe.step(g)
+        assert pipe.poll() == 0
+        ref = oracle_client((gh, np.zeros(n, np.float32), w.E, w.M, None, 256, weights))
+        compare_client(pipe, 0, ref, n)
+        want = oracle.aggregate(ref["sym"][None, :], ref["A"][None, :], f)
+        assert np.array_equal(u32(pipe.avg[:n]), want.view(np.uint32))
+        pipe.decode()
+        assert pipe.poll() == 0
+        assert torch.equal(pipe.sym_dec[0, :n], pipe.sym[0, :n])
+        del pipe, g, del_g
+        torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("point", [0, 4, 8, 11])
+def test_c5_points(co3, point):
+    """C5: 16 clients x 25M; formats E2M0 / E3M1 / E4M3 / E5M2 at one beta each (points 0, 4, 8, 11 of the
+    12-point sweep).  Clients 0 and 15 go through the oracle element by element, all 16 through the
+    size-independent properties; the average is checked on the first 2^20 elements with all 16
+    clients' symbols taken from the (round-trip verified) GPU symbols."""
+    w = inp.c5(point)
+    beta = inp.C5_BETAS[point % 3]
+    fmt = co3.Fmt(w.E, w.M)
+    pipe = co3.Co3Pipeline(w.U, w.n, fmt, chunk_syms=256)
+    g = pipe.new_gradient_buffer()
+    checked = (0, w.U - 1)
+    host = {}
+    for u in range(w.U):
+        x = inp.device_gennorm(w.n, beta, 1e-3, 5000 + 100 * point + u)
+        g[u, :w.n] = x
+        if u in checked:
+            host[u] = x.cpu().numpy()
+        del x
+    pipe.step(g)
+    assert pipe.poll() == 0
+    with ThreadPoolExecutor(max_workers=2) as pool:
+        refs = list(pool.map(oracle_client, [(host[u], np.zeros(w.n, np.float32), w.E, w.M, None, 256, None)
+                                             for u in checked]))
+    for u, ref in zip(checked, refs):
+        compare_client(pipe, u, ref, w.n)
+    properties_all_clients(pipe, w.n)
+    m = 1 << 20
+    syms = pipe.sym[:, :m].cpu().numpy()
+    want = oracle.aggregate(syms, pipe.anchor.cpu().numpy(), oracle.Fmt(w.E, w.M))
+    assert np.array_equal(u32(pipe.avg[:m]), want.view(np.uint32))
