@@ -101,12 +101,23 @@ def main():
     ap.add_argument("--pool", type=int, default=3, help="distinct gradient batches cycled through")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--breakdown", action="store_true", help="extra untimed pass timing every kernel (stderr)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run only a plain elementwise copy of 1 GiB (reads 2^30 B, writes 2^30 B) three times: "
+                         "the known-size kernel that scales the rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1")
 
     import torch
     assert torch.cuda.is_available(), "bench.py needs an MI355X"
+    if args.calibrate_copy:
+        a = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        b = torch.empty_like(a)
+        for _ in range(3):
+            torch.add(a, 1.0, out=b)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": 1 << 30, "calibrate_copy_bytes_written": 1 << 30}))
+        return
     from paper_2203_09044_amd import Co3Pipeline, Fmt, binding as B
 
     w, betas, alpha, desc = make_workload(args.workload)

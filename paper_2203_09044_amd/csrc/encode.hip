@@ -186,10 +186,29 @@ __global__ __launch_bounds__(EN_BLOCK) void k_enc_pack(const uint8_t *__restrict
     uint32_t s[8];
     const int nvalid = i < n ? load_syms32(su, i, n, s) : 0;
 
+    // One table lookup per symbol: the codewords of every 4 symbols are concatenated into one run
+    // (kept in registers) as long as the run fits 64 bits, which it always does for codes of at most
+    // 16 bits; a lane that meets a longer run falls back to symbol-by-symbol packing below.
+    uint64_t run[EN_LSYM / 4];
+    uint32_t runbits[EN_LSYM / 4];
     uint32_t mybits = 0;
+    bool wide = false;
 #pragma unroll
-    for (int c = 0; c < EN_LSYM; ++c)
-        if (c < nvalid) mybits += (uint32_t)(enc_s[(s[c >> 2] >> (8 * (c & 3))) & 0xffu] & 63u);
+    for (int g = 0; g < EN_LSYM / 4; ++g) {
+        uint64_t acc = 0;
+        uint32_t nb = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            uint64_t e = (4 * g + k < nvalid) ? enc_s[(s[g] >> (8 * k)) & 0xffu] : 0ull;
+            uint32_t l = (uint32_t)(e & 63u);
+            acc = (acc << l) | (e >> 6);
+            nb += l;
+        }
+        wide |= nb > 64u;
+        run[g] = acc;
+        runbits[g] = nb;
+        mybits += nb;
+    }
     const uint32_t incl = wave_scan_incl_u32(mybits, lane);
     const uint32_t excl = incl - mybits;
     const uint32_t tilebits = (uint32_t)__shfl((int)incl, CO3_WAVE - 1, CO3_WAVE);
@@ -209,12 +228,18 @@ __global__ __launch_bounds__(EN_BLOCK) void k_enc_pack(const uint8_t *__restrict
 #pragma unroll
         for (int j = 0; j < EN_STAGE_WORDS / CO3_WAVE; ++j) stage[lane + j * CO3_WAVE] = 0ull;
         wave_lds_sync();
-        // concatenate this lane's codewords into runs of at most 64 bits and OR them in
-        uint64_t acc = 0, pos = rel0;
-        int accbits = 0;
+        if (!wide) {
+            uint64_t pos = rel0;
 #pragma unroll
-        for (int c = 0; c < EN_LSYM; ++c) {
-            if (c < nvalid) {
+            for (int g = 0; g < EN_LSYM / 4; ++g) {
+                if (runbits[g]) stage_bits(stage, win_w0, run[g], (int)runbits[g], pos);
+                pos += runbits[g];
+            }
+        } else {
+            // runs of at most 64 bits, symbol by symbol
+            uint64_t acc = 0, pos = rel0;
+            int accbits = 0;
+            for (int c = 0; c < nvalid; ++c) {
                 uint64_t e = enc_s[(s[c >> 2] >> (8 * (c & 3))) & 0xffu];
                 int l = (int)(e & 63u);
                 if (l) {
@@ -228,8 +253,8 @@ __global__ __launch_bounds__(EN_BLOCK) void k_enc_pack(const uint8_t *__restrict
                     accbits += l;
                 }
             }
+            if (accbits) stage_bits(stage, win_w0, acc, accbits, pos);
         }
-        if (accbits) stage_bits(stage, win_w0, acc, accbits, pos);
         wave_lds_sync();
 #pragma unroll
         for (int j = 0; j < EN_STAGE_WORDS / CO3_WAVE; ++j) {
