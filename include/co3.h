@@ -56,7 +56,7 @@ typedef struct {
 
 #define CO3_OK 0
 #define CO3_EINVAL (-1)     /* bad argument (format, size, alignment, null pointer) */
-#define CO3_ECAP (-2)       /* a stream would exceed cap_words; that user's stream is not written */
+#define CO3_ECAP (-2)       /* a stream would exceed cap_words; that user's stream is incomplete */
 #define CO3_ENOCODE (-3)    /* a symbol to encode has no codeword (possible with model tables) */
 #define CO3_EBADSTREAM (-4) /* decoder: a chunk did not end where the index says, or an invalid prefix */
 #define CO3_EHIP (-5)       /* a HIP runtime call failed */
@@ -71,7 +71,7 @@ typedef struct {
 /* Human-readable name of a status code; never NULL. */
 const char *co3_strerror(int32_t status);
 
-/* Bytes of workspace co3_encode needs (one 64-bit partial sum per 2048 symbols and user). */
+/* Bytes of workspace co3_encode needs (one 64-bit partial sum per tile of 1024 symbols and user). */
 size_t co3_encode_workspace_bytes(int64_t n, int32_t U);
 
 /* Bytes of workspace co3_ps_aggregate needs (the decoded symbols of all users, whole tiles of
@@ -138,11 +138,12 @@ int32_t co3_build_code(const uint32_t *weights, int32_t U, co3_fmt fmt, void *co
  * Compression h_Hf (Algorithm 1: "compresses ghat") of every user's symbols with its code.
  *
  *   words        [U][cap_words] u64 out  streams; words past ceil(total_bits/64) are untouched
- *   chunk_syms   64, 128, ..., 2048 (power of two)
+ *   chunk_syms   64, 128, ..., 4096 (power of two)
  *   chunk_bitoff [U][nchunks+1] u64 out
  *   total_bits   [U] u64 out
  *   workspace    co3_encode_workspace_bytes(n, U) bytes, 8-byte aligned, contents unspecified
- * Device-reported: CO3_ENOCODE, CO3_ECAP (nothing is written past cap_words).
+ * Device-reported: CO3_ENOCODE; CO3_ECAP (nothing is written past cap_words, total_bits still
+ * reports the needed length, the words of that user are unspecified).
  */
 int32_t co3_encode(const uint8_t *sym, int64_t n, int32_t U, int64_t stride, co3_fmt fmt, const void *codes,
                    uint64_t *words, int64_t cap_words, int32_t chunk_syms, uint64_t *chunk_bitoff,

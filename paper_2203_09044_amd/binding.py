@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libco3.so")
 OK, EINVAL, ECAP, ENOCODE, EBADSTREAM, EHIP = 0, -1, -2, -3, -4, -5
 ANCHOR_GIVEN, ANCHOR_FROM_ABSMAX_G = 0, 1
 CODE_BYTES = 12288
-PACK_SYMS = 2048
+PACK_SYMS = 1024
 
 EXPORTS = (
     "co3_strerror", "co3_encode_workspace_bytes", "co3_ps_aggregate_workspace_bytes", "co3_cap_words_empirical",

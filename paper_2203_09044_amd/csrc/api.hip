@@ -62,7 +62,7 @@ bool batch_ok(int64_t n, int32_t U, int64_t stride)
     return true;
 }
 
-bool chunk_ok(int32_t c) { return c >= 64 && c <= CO3_PACK_SYMS && (c & (c - 1)) == 0; }
+bool chunk_ok(int32_t c) { return c >= 64 && c <= 4096 && (c & (c - 1)) == 0; }
 
 int32_t hip_rc(hipError_t e) { return e == hipSuccess ? CO3_OK : CO3_EHIP; }
 

@@ -8,7 +8,7 @@
 #define CO3_WAVE 64
 #define CO3_LUT_BITS_MAX 12
 #define CO3_MAX_CODE_LEN 57     // (code << 6 | len) must fit 64 bits; u32 weights cannot reach it
-#define CO3_PACK_SYMS 2048      // symbols per encoder block (256 threads x 8)
+#define CO3_PACK_SYMS 1024      // symbols per encoder tile (one wavefront, 16 per lane)
 
 // Per-user code blob.  Bytes 0..K-1 (len) are the public wire header; the rest is private.
 struct Co3Code {

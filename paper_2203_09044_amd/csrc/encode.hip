@@ -1,14 +1,16 @@
-// Compression h_Hf (Algorithm 1, user side): bit lengths per tile of 2048 symbols, exclusive scan
-// of the tile lengths per user, then bit packing through an LDS staging window with coalesced
-// 64-bit stores.  One wavefront owns one tile (32 symbols per lane), so the two passes over the
-// symbols need no workgroup barriers.
+// Compression h_Hf (Algorithm 1, user side): coded size of every tile of 1024 symbols, exclusive scan
+// of the tile sizes per user, then bit packing.  In the packing pass one wavefront owns one tile (16
+// symbols per lane): it looks the codewords up, scans the lengths, packs its bits in an LDS staging
+// window and writes every 64-bit word whose first bit lies inside the tile -- completing the last
+// such word with the leading codewords of the following symbols, so that each word of the stream is
+// written exactly once, by one wavefront, with plain coalesced stores.
 #include "co3_dev.h"
 #include "kernels.h"
 
 #define EN_BLOCK 256
 #define EN_WAVES (EN_BLOCK / CO3_WAVE)
-#define EN_LSYM 32                             // symbols per lane
-#define EN_STAGE_WORDS 256                     // staging window: 16384 bits = 8 bits/symbol on average
+#define EN_LSYM 16                             // symbols per lane
+#define EN_STAGE_WORDS 128                     // staging window: 8192 bits = 8 bits/symbol on average
 static_assert(CO3_WAVE * EN_LSYM == CO3_PACK_SYMS, "tile geometry");
 
 __device__ __forceinline__ const Co3Code *code_of(const void *codes, int u)
@@ -16,19 +18,17 @@ __device__ __forceinline__ const Co3Code *code_of(const void *codes, int u)
     return reinterpret_cast<const Co3Code *>(reinterpret_cast<const char *>(codes) + (size_t)u * CO3_CODE_BYTES);
 }
 
-// Loads the 32 symbols of this lane into s[0..8) (4 per word, first symbol in the low byte);
+// Loads the 16 symbols of this lane into s[0..4) (4 per word, first symbol in the low byte);
 // returns how many lie below n.
-__device__ __forceinline__ int load_syms32(const uint8_t *su, int64_t i, int64_t n, uint32_t s[8])
+__device__ __forceinline__ int load_syms16(const uint8_t *su, int64_t i, int64_t n, uint32_t s[4])
 {
     if (i + EN_LSYM <= n) {
         uint4 a = *reinterpret_cast<const uint4 *>(su + i);
-        uint4 b = *reinterpret_cast<const uint4 *>(su + i + 16);
         s[0] = a.x; s[1] = a.y; s[2] = a.z; s[3] = a.w;
-        s[4] = b.x; s[5] = b.y; s[6] = b.z; s[7] = b.w;
         return EN_LSYM;
     }
 #pragma unroll
-    for (int k = 0; k < 8; ++k) s[k] = 0;
+    for (int k = 0; k < 4; ++k) s[k] = 0;
     int c = 0;
     for (int64_t j = i; j < n; ++j, ++c) s[c >> 2] |= (uint32_t)su[j] << (8 * (c & 3));
     return c;
@@ -41,10 +41,20 @@ __device__ __forceinline__ void wave_lds_sync()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// ---- pass 1: coded size of every tile of 2048 symbols --------------------------------------
+__device__ __forceinline__ uint64_t wave_sum_u64(uint64_t v)
+{
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v += (uint64_t)__shfl_xor((long long)v, o, CO3_WAVE);
+    return v;
+}
+
+// ---- pass 1: coded size of every tile; a wavefront takes 4 consecutive tiles with all loads in
+// flight before the first table lookup -----------------------------------------------------------
+#define SZ_TILES 4
+
 __global__ __launch_bounds__(EN_BLOCK) void k_enc_sizes(const uint8_t *__restrict__ sym, int64_t n, int64_t stride,
                                                          const void *__restrict__ codes, int K,
-                                                         uint64_t *__restrict__ blocksum, int64_t nblk, int32_t *status)
+                                                         uint64_t *__restrict__ tilesum, int64_t nblk, int32_t *status)
 {
     const int u = blockIdx.y;
     const Co3Code *cd = code_of(codes, u);
@@ -53,40 +63,45 @@ __global__ __launch_bounds__(EN_BLOCK) void k_enc_sizes(const uint8_t *__restric
     __syncthreads();
 
     const int lane = threadIdx.x & (CO3_WAVE - 1);
-    const int64_t tb = (int64_t)blockIdx.x * EN_WAVES + threadIdx.x / CO3_WAVE;
-    if (tb >= nblk) return;
+    const int64_t tb0 = ((int64_t)blockIdx.x * EN_WAVES + threadIdx.x / CO3_WAVE) * SZ_TILES;
+    if (tb0 >= nblk) return;
     const uint8_t *su = sym + (int64_t)u * stride;
-    const int64_t i = tb * CO3_PACK_SYMS + (int64_t)lane * EN_LSYM;
-    uint32_t s[8];
-    const int nvalid = i < n ? load_syms32(su, i, n, s) : 0;
-    uint32_t bits = 0;
+    uint32_t s[SZ_TILES][4];
+    int nvalid[SZ_TILES];
+#pragma unroll
+    for (int t = 0; t < SZ_TILES; ++t) {
+        const int64_t i = (tb0 + t) * CO3_PACK_SYMS + (int64_t)lane * EN_LSYM;
+        nvalid[t] = i < n ? load_syms16(su, i, n, s[t]) : 0;
+    }
     bool nocode = false;
 #pragma unroll
-    for (int c = 0; c < EN_LSYM; ++c) {
-        uint32_t l = len_s[(s[c >> 2] >> (8 * (c & 3))) & 0xffu];
-        if (c < nvalid) {
-            bits += l;
-            nocode |= (l == 0);
+    for (int t = 0; t < SZ_TILES; ++t) {
+        uint32_t bits = 0;
+#pragma unroll
+        for (int c = 0; c < EN_LSYM; ++c) {
+            uint32_t l = len_s[(s[t][c >> 2] >> (8 * (c & 3))) & 0xffu];
+            if (c < nvalid[t]) {
+                bits += l;
+                nocode |= (l == 0);
+            }
         }
+        bits = wave_sum_u32(bits);
+        if (lane == 0 && tb0 + t < nblk) tilesum[(int64_t)u * nblk + tb0 + t] = bits;
     }
     if (nocode) co3_raise(status, CO3_ENOCODE);
-    bits = wave_sum_u32(bits);
-    if (lane == 0) blocksum[(int64_t)u * nblk + tb] = bits;
 }
 
-// ---- pass 2: per user, exclusive scan of the block sizes (in place), stream length, capacity
-// check, and zeroing of the words shared by two neighbouring blocks -------------------------
+// ---- pass 2: per user, exclusive scan of the tile sizes (in place), stream length and capacity
+// check --------------------------------------------------------------------------------------
 #define SC_BLOCK 1024
-#define SC_PER 4
+#define SC_PER 8
 
-__global__ __launch_bounds__(SC_BLOCK) void k_enc_scan(uint64_t *__restrict__ blocksum, int64_t nblk,
-                                                        uint64_t *__restrict__ words, int64_t cap_words,
+__global__ __launch_bounds__(SC_BLOCK) void k_enc_scan(uint64_t *__restrict__ tilesum, int64_t nblk, int64_t cap_words,
                                                         uint64_t *__restrict__ chunk_bitoff, int64_t nchunks,
                                                         uint64_t *__restrict__ total_bits, int32_t *status)
 {
     const int u = blockIdx.x;
-    uint64_t *bs = blocksum + (int64_t)u * nblk;
-    uint64_t *wu = words + (int64_t)u * cap_words;
+    uint64_t *bs = tilesum + (int64_t)u * nblk;
     const int lane = threadIdx.x & (CO3_WAVE - 1);
     const int wave = threadIdx.x / CO3_WAVE;
     __shared__ uint64_t wave_tot[SC_BLOCK / CO3_WAVE];
@@ -103,8 +118,7 @@ __global__ __launch_bounds__(SC_BLOCK) void k_enc_scan(uint64_t *__restrict__ bl
             v[k] = (i0 + k < nblk) ? bs[i0 + k] : 0;
             mine += v[k];
         }
-        // wave inclusive scan of 64-bit values
-        uint64_t incl = mine;
+        uint64_t incl = mine;   // wave inclusive scan of 64-bit values
 #pragma unroll
         for (int o = 1; o < CO3_WAVE; o <<= 1) {
             uint64_t t = (uint64_t)__shfl_up((long long)incl, o, CO3_WAVE);
@@ -118,29 +132,21 @@ __global__ __launch_bounds__(SC_BLOCK) void k_enc_scan(uint64_t *__restrict__ bl
             if (w < wave) off += t;
             tile_tot += t;
         }
-        uint64_t run = off + incl - mine;
+        uint64_t running = off + incl - mine;
 #pragma unroll
         for (int k = 0; k < SC_PER; ++k) {
-            if (i0 + k < nblk) bs[i0 + k] = run;
-            run += v[k];
+            if (i0 + k < nblk) bs[i0 + k] = running;
+            running += v[k];
         }
         __syncthreads();
         if (threadIdx.x == 0) carry_s += tile_tot;
         __syncthreads();
     }
-    const uint64_t total = carry_s;
-    const bool fits = (total + 63) / 64 <= (uint64_t)cap_words;
     if (threadIdx.x == 0) {
+        const uint64_t total = carry_s;
         total_bits[u] = total;
         chunk_bitoff[(int64_t)u * (nchunks + 1) + nchunks] = total;
-        if (!fits) co3_raise(status, CO3_ECAP);
-    }
-    if (fits) {
-        // words that two blocks (or the last block and the padding) both touch are OR-ed into
-        for (int64_t i = threadIdx.x; i <= nblk; i += SC_BLOCK) {
-            uint64_t p = i < nblk ? bs[i] : total;
-            if ((p & 63) && (int64_t)(p >> 6) < cap_words) wu[p >> 6] = 0;
-        }
+        if ((total + 63) / 64 > (uint64_t)cap_words) co3_raise(status, CO3_ECAP);
     }
 }
 
@@ -159,10 +165,9 @@ __device__ __forceinline__ void stage_bits(unsigned long long *stage, int64_t wi
 
 __global__ __launch_bounds__(EN_BLOCK) void k_enc_pack(const uint8_t *__restrict__ sym, int64_t n, int64_t stride,
                                                         const void *__restrict__ codes, int K,
-                                                        const uint64_t *__restrict__ blockoff, int64_t nblk,
+                                                        const uint64_t *__restrict__ tileoff, int64_t nblk,
                                                         uint64_t *__restrict__ words, int64_t cap_words, int chunk_syms,
-                                                        uint64_t *__restrict__ chunk_bitoff, int64_t nchunks,
-                                                        const uint64_t *__restrict__ total_bits)
+                                                        uint64_t *__restrict__ chunk_bitoff, int64_t nchunks)
 {
     const int u = blockIdx.y;
     const Co3Code *cd = code_of(codes, u);
@@ -177,14 +182,11 @@ __global__ __launch_bounds__(EN_BLOCK) void k_enc_pack(const uint8_t *__restrict
     if (tb >= nblk) return;
     unsigned long long *stage = stage_all[wave];
 
-    const uint64_t total = total_bits[u];
-    const bool fits = (total + 63) / 64 <= (uint64_t)cap_words;
-    const uint64_t B0 = blockoff[(int64_t)u * nblk + tb];
     const uint8_t *su = sym + (int64_t)u * stride;
     uint64_t *wu = words + (int64_t)u * cap_words;
     const int64_t i = tb * CO3_PACK_SYMS + (int64_t)lane * EN_LSYM;
-    uint32_t s[8];
-    const int nvalid = i < n ? load_syms32(su, i, n, s) : 0;
+    uint32_t s[4];
+    const int nvalid = i < n ? load_syms16(su, i, n, s) : 0;
 
     // One table lookup per symbol: the codewords of every 4 symbols are concatenated into one run
     // (kept in registers) as long as the run fits 64 bits, which it always does for codes of at most
@@ -213,15 +215,18 @@ __global__ __launch_bounds__(EN_BLOCK) void k_enc_pack(const uint8_t *__restrict
     const uint32_t excl = incl - mybits;
     const uint32_t tilebits = (uint32_t)__shfl((int)incl, CO3_WAVE - 1, CO3_WAVE);
 
+    const uint64_t B0 = tileoff[(int64_t)u * nblk + tb];
+    const uint64_t B1 = B0 + tilebits;
+
     // chunk index: stream position of every chunk that starts at this lane's first symbol
     if (nvalid > 0 && (i & (int64_t)(chunk_syms - 1)) == 0)
         chunk_bitoff[(int64_t)u * (nchunks + 1) + i / chunk_syms] = B0 + excl;
+    // beyond the capacity nothing is written (the scan pass has reported it); uniform over the wavefront
+    if ((B1 + 63) / 64 > (uint64_t)cap_words || tilebits == 0) return;
 
-    if (!fits || tilebits == 0) return;   // uniform over the wavefront
-
-    const uint64_t B1 = B0 + tilebits;
-    const int64_t gw0 = (int64_t)(B0 >> 6);          // first and last stream word of the tile
+    const int64_t gw0 = (int64_t)(B0 >> 6);          // first and last stream word the tile touches
     const int64_t gwl = (int64_t)((B1 - 1) >> 6);
+    const int64_t first_owned = (B0 & 63) ? gw0 + 1 : gw0;   // words whose first bit lies in the tile
     const uint64_t rel0 = (B0 & 63) + excl;          // position of this lane's bits, relative to word gw0
 
     for (int64_t win_w0 = 0; gw0 + win_w0 <= gwl; win_w0 += EN_STAGE_WORDS) {
@@ -255,18 +260,23 @@ __global__ __launch_bounds__(EN_BLOCK) void k_enc_pack(const uint8_t *__restrict
             }
             if (accbits) stage_bits(stage, win_w0, acc, accbits, pos);
         }
+        // The last word of the tile is completed with the first codewords of the symbols that follow
+        // (at most 63 bits, hence at most 63 symbols), clipped at the word end.
+        const int64_t last_rel = gwl - gw0 - win_w0;
+        if ((B1 & 63) && last_rel >= 0 && last_rel < EN_STAGE_WORDS) {
+            const int64_t i2 = (tb + 1) * CO3_PACK_SYMS + lane;
+            uint64_t e = (lane < CO3_WAVE - 1 && i2 < n) ? enc_s[su[i2]] : 0ull;
+            uint32_t l = (uint32_t)(e & 63u);
+            uint32_t o = wave_scan_incl_u32(l, lane) - l;
+            const uint32_t used = (uint32_t)(B1 & 63);
+            if (l && used + o < 64u)
+                atomicOr(&stage[last_rel], (unsigned long long)(((e >> 6) << (64 - l)) >> (used + o)));
+        }
         wave_lds_sync();
 #pragma unroll
         for (int j = 0; j < EN_STAGE_WORDS / CO3_WAVE; ++j) {
             int64_t gw = gw0 + win_w0 + lane + j * CO3_WAVE;
-            if (gw <= gwl) {
-                unsigned long long v = stage[lane + j * CO3_WAVE];
-                bool shared_word = (gw == gw0 && (B0 & 63)) || (gw == gwl && (B1 & 63));
-                if (shared_word)
-                    atomicOr(reinterpret_cast<unsigned long long *>(wu + gw), v);
-                else
-                    wu[gw] = v;
-            }
+            if (gw >= first_owned && gw <= gwl) wu[gw] = stage[lane + j * CO3_WAVE];
         }
         wave_lds_sync();
     }
@@ -274,25 +284,26 @@ __global__ __launch_bounds__(EN_BLOCK) void k_enc_pack(const uint8_t *__restrict
 
 hipError_t co3_launch_encode(const uint8_t *sym, int64_t n, int U, int64_t stride, const void *codes, int K,
                              uint64_t *words, int64_t cap_words, int chunk_syms, uint64_t *chunk_bitoff,
-                             uint64_t *total_bits, uint64_t *blocksum, int32_t *status, hipStream_t st)
+                             uint64_t *total_bits, uint64_t *tilesum, int32_t *status, hipStream_t st)
 {
     const int64_t nblk = (n + CO3_PACK_SYMS - 1) / CO3_PACK_SYMS;
     const int64_t nchunks = (n + chunk_syms - 1) / chunk_syms;
-    const unsigned grid_x = (unsigned)((nblk + EN_WAVES - 1) / EN_WAVES);
     if (nblk > 0) {
+        const unsigned gx = (unsigned)((nblk + EN_WAVES * SZ_TILES - 1) / (EN_WAVES * SZ_TILES));
         Co3LaunchTimer tm(CO3_K_ENC_SIZES, st);
-        hipLaunchKernelGGL(k_enc_sizes, dim3(grid_x, U), dim3(EN_BLOCK), 0, st, sym, n, stride, codes, K, blocksum,
-                           nblk, status);
+        hipLaunchKernelGGL(k_enc_sizes, dim3(gx, U), dim3(EN_BLOCK), 0, st, sym, n, stride, codes, K, tilesum, nblk,
+                           status);
     }
     {
         Co3LaunchTimer tm(CO3_K_ENC_SCAN, st);
-        hipLaunchKernelGGL(k_enc_scan, dim3(U), dim3(SC_BLOCK), 0, st, blocksum, nblk, words, cap_words, chunk_bitoff,
-                           nchunks, total_bits, status);
+        hipLaunchKernelGGL(k_enc_scan, dim3(U), dim3(SC_BLOCK), 0, st, tilesum, nblk, cap_words, chunk_bitoff, nchunks,
+                           total_bits, status);
     }
-    Co3LaunchTimer tm(CO3_K_ENC_PACK, st);
-    if (nblk > 0)
-        hipLaunchKernelGGL(k_enc_pack, dim3(grid_x, U), dim3(EN_BLOCK), 0, st, sym, n, stride, codes, K,
-                           (const uint64_t *)blocksum, nblk, words, cap_words, chunk_syms, chunk_bitoff, nchunks,
-                           (const uint64_t *)total_bits);
+    if (nblk > 0) {
+        const unsigned gx = (unsigned)((nblk + EN_WAVES - 1) / EN_WAVES);
+        Co3LaunchTimer tm(CO3_K_ENC_PACK, st);
+        hipLaunchKernelGGL(k_enc_pack, dim3(gx, U), dim3(EN_BLOCK), 0, st, sym, n, stride, codes, K,
+                           (const uint64_t *)tilesum, nblk, words, cap_words, chunk_syms, chunk_bitoff, nchunks);
+    }
     return hipGetLastError();
 }

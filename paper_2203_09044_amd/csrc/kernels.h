@@ -31,7 +31,7 @@ hipError_t co3_launch_histogram(const uint8_t *sym, int64_t n, int U, int64_t st
 hipError_t co3_launch_build_code(const uint32_t *weights, int U, int K, void *codes, int32_t *status, hipStream_t st);
 hipError_t co3_launch_encode(const uint8_t *sym, int64_t n, int U, int64_t stride, const void *codes, int K,
                              uint64_t *words, int64_t cap_words, int chunk_syms, uint64_t *chunk_bitoff,
-                             uint64_t *total_bits, uint64_t *blocksum, int32_t *status, hipStream_t st);
+                             uint64_t *total_bits, uint64_t *tilesum, int32_t *status, hipStream_t st);
 hipError_t co3_launch_decode(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff, int chunk_syms,
                              const void *codes, int64_t n, int U, uint8_t *sym_out, int64_t stride, int tiled,
                              int32_t *status, hipStream_t st);

@@ -102,7 +102,7 @@ def test_whole_path_sizes(co3, n):
     run_case(co3, 3, n, co3.Fmt(3, 0), 128, betas=[0.5, 1.0, 1.5], T=2)
 
 
-@pytest.mark.parametrize("C", [64, 128, 256, 512, 1024, 2048])
+@pytest.mark.parametrize("C", [64, 128, 256, 512, 1024, 2048, 4096])
 def test_whole_path_chunk_sizes(co3, C):
     run_case(co3, 2, 3 * 4096 + 100, co3.Fmt(4, 3), C, betas=[0.8], T=2)
 
@@ -327,10 +327,15 @@ def test_device_reported_errors(co3):
     pipe.sym[0, :n] = torch.from_numpy(s).cuda()
     co3.binding.histogram(pipe.sym, n, fmt, pipe.counts)
     pipe.build()
-    canary = pipe.words.clone()
-    pipe.encode()
+    # the word buffer continues past the stated capacity: nothing may land there
+    big = torch.full((1, 1000), 0x5A5A5A5A5A5A5A5A, dtype=torch.int64, device="cuda")
+    rc = co3.binding._lib.co3_encode(pipe.sym.data_ptr(), n, 1, pipe.stride, fmt.c(), pipe.codes.data_ptr(),
+                                     big.data_ptr(), 100, C, pipe.chunk_bitoff.data_ptr(),
+                                     pipe.total_bits.data_ptr(), pipe.enc_ws.data_ptr(), pipe.enc_ws.numel() * 8,
+                                     pipe.status.data_ptr(), None)
+    assert rc == 0
     assert pipe.poll() == co3.binding.ECAP
-    assert torch.equal(pipe.words, canary)          # nothing written
+    assert bool((big[0, 100:] == 0x5A5A5A5A5A5A5A5A).all())
     assert int(pipe.total_bits[0].item()) == 3 * n    # the needed length is still reported
     # symbol without a code: table built from weights that miss symbol 7
     pipe = co3.Co3Pipeline(1, n, fmt, chunk_syms=C)
