@@ -174,33 +174,50 @@ __global__ __launch_bounds__(CV_BLOCK) void k_convert_ef(const float *__restrict
     int64_t beg = (int64_t)blockIdx.x * per_block;
     int64_t end = beg + per_block < n ? beg + per_block : n;
 
-    for (int64_t t0 = beg; t0 < end; t0 += CV_TILE) {
+    // four elements of one thread: correct, convert, update the memory, count
+    auto convert4 = [&](int64_t i, int A, int e_min, float4 gv, float4 ev) {
+        float x0 = gv.x + gamma * ev.x, x1 = gv.y + gamma * ev.y;   // no contraction (build flag):
+        float x2 = gv.z + gamma * ev.z, x3 = gv.w + gamma * ev.w;   // one rounding per operation
+        uint32_t q0, q1, q2, q3;
+        float v0, v1, v2, v3;
+        co3_quantize(x0, e_min, A, E, M, codemax, q0, v0);
+        co3_quantize(x1, e_min, A, E, M, codemax, q1, v1);
+        co3_quantize(x2, e_min, A, E, M, codemax, q2, v2);
+        co3_quantize(x3, e_min, A, E, M, codemax, q3, v3);
+        st_stream_f4(eu + i, make_float4(x0 - v0, x1 - v1, x2 - v2, x3 - v3));
+        *reinterpret_cast<uint32_t *>(su + i) = q0 | (q1 << 8) | (q2 << 16) | (q3 << 24);
+        if (HIST) {
+            atomicAdd(&myhist[q0 * copies + mycopy], 1u);
+            atomicAdd(&myhist[q1 * copies + mycopy], 1u);
+            atomicAdd(&myhist[q2 * copies + mycopy], 1u);
+            atomicAdd(&myhist[q3 * copies + mycopy], 1u);
+        }
+    };
+
+    int64_t t0 = beg;
+    while (t0 < end) {
+        if (t0 + 2 * CV_TILE <= end) {       // two full tiles inside one tensor: all four loads first
+            int s_a = co3_find_seg(seg_off, nseg, t0);
+            int s_b = co3_find_seg(seg_off, nseg, t0 + 2 * CV_TILE - 1);
+            if (s_a == s_b) {
+                const int A = anchor_u[s_a];
+                const int e_min = A - F + 1;
+                const int64_t i0 = t0 + (int64_t)threadIdx.x * CV_VEC, i1 = i0 + CV_TILE;
+                float4 g0 = ld_stream_f4(gu + i0), e0 = ld_stream_f4(eu + i0);
+                float4 g1 = ld_stream_f4(gu + i1), e1 = ld_stream_f4(eu + i1);
+                convert4(i0, A, e_min, g0, e0);
+                convert4(i1, A, e_min, g1, e1);
+                t0 += 2 * CV_TILE;
+                continue;
+            }
+        }
         int64_t t1 = t0 + CV_TILE < end ? t0 + CV_TILE : end;
         int s_lo = co3_find_seg(seg_off, nseg, t0);
         int s_hi = co3_find_seg(seg_off, nseg, t1 - 1);
         int64_t i = t0 + (int64_t)threadIdx.x * CV_VEC;
         if (s_lo == s_hi && i + CV_VEC <= t1) {
             const int A = anchor_u[s_lo];
-            const int e_min = A - F + 1;
-            float4 gv = ld_stream_f4(gu + i);
-            float4 ev = ld_stream_f4(eu + i);
-            float x0 = gv.x + gamma * ev.x, x1 = gv.y + gamma * ev.y;   // no contraction (build flag):
-            float x2 = gv.z + gamma * ev.z, x3 = gv.w + gamma * ev.w;   // one rounding per operation
-            uint32_t q0, q1, q2, q3;
-            float v0, v1, v2, v3;
-            co3_quantize(x0, e_min, A, E, M, codemax, q0, v0);
-            co3_quantize(x1, e_min, A, E, M, codemax, q1, v1);
-            co3_quantize(x2, e_min, A, E, M, codemax, q2, v2);
-            co3_quantize(x3, e_min, A, E, M, codemax, q3, v3);
-            float4 en = make_float4(x0 - v0, x1 - v1, x2 - v2, x3 - v3);
-            st_stream_f4(eu + i, en);
-            *reinterpret_cast<uint32_t *>(su + i) = q0 | (q1 << 8) | (q2 << 16) | (q3 << 24);
-            if (HIST) {
-                atomicAdd(&myhist[q0 * copies + mycopy], 1u);
-                atomicAdd(&myhist[q1 * copies + mycopy], 1u);
-                atomicAdd(&myhist[q2 * copies + mycopy], 1u);
-                atomicAdd(&myhist[q3 * copies + mycopy], 1u);
-            }
+            convert4(i, A, A - F + 1, ld_stream_f4(gu + i), ld_stream_f4(eu + i));
         } else {                         // ragged tail, or a tile that straddles tensors
             for (int64_t j = i; j < i + CV_VEC && j < t1; ++j) {
                 int s = (s_lo == s_hi) ? s_lo : co3_find_seg(seg_off, nseg, j);
@@ -214,6 +231,7 @@ __global__ __launch_bounds__(CV_BLOCK) void k_convert_ef(const float *__restrict
                 if (HIST) atomicAdd(&myhist[q * copies + mycopy], 1u);
             }
         }
+        t0 += CV_TILE;
     }
 
     if (HIST) {
