@@ -15,13 +15,17 @@ __device__ __forceinline__ const Co3Code *dcode_of(const void *codes, int u)
 // holds stream bits [32q, 32q+32), first bit on top; in memory the words are little-endian u64, so
 // the two pieces of a word are swapped).  Each lane keeps the 4 most recent blocks of its chunk in
 // a 16-dword ring, stored in descending piece order (piece q at ring index 16 - (q mod 16), and a
-// copy of the piece with q mod 16 == 0 at index 0) so that pieces q and q+1 are one two-dword read
-// that lands as a 64-bit register pair with piece q on top.  Blocks are requested one group of 8
-// symbols ahead of their use, at a cadence that is the same for all lanes of the wavefront, so the
+// copy of the piece with q mod 16 == 0 at index 0) so that pieces q+1 and q are ring entries j and
+// j+1 of one two-address LDS read.  The rings of a wavefront are interleaved: entry j of lane l is
+// dword j*64 + l of the wavefront's area, so the bank of an access depends on the lane only and
+// lanes at different ring positions never conflict.  Blocks are requested one group of 8 symbols
+// ahead of their use, at a cadence that is the same for all lanes of the wavefront, so the
 // global-load latency hides behind the decoding of the previous group.
 // ------------------------------------------------------------------------------------------
-#define RING_STRIDE 17
-#define DE_GROUP 8
+#define RING_ROWS 17
+#define RING_ROW_DW CO3_WAVE     // dwords between consecutive ring entries of one lane
+#define DE_GROUP 16          // symbols per run: one ring refill point, one 16-byte store
+#define DE_MISS_LEN 255u     // length field of a table entry that does not resolve a symbol
 typedef uint64_t u64_align4 __attribute__((aligned(4)));
 
 struct LaneStream {
@@ -31,8 +35,8 @@ struct LaneStream {
     uint32_t *slot;        // this lane's ring in LDS
     uint32_t rel;          // current bit position relative to block base_blk
     uint32_t loaded;       // relative blocks [loaded-4, loaded) are in the ring
-    bool inflight;         // block `loaded` has been requested and sits in `fl`
-    uint4 fl;
+    uint32_t nfly;         // blocks requested beyond `loaded`: fl0 holds block loaded, fl1 block loaded+1
+    uint4 fl0, fl1;
 
     __device__ __forceinline__ uint4 fetch(uint32_t relblk) const
     {
@@ -42,21 +46,21 @@ struct LaneStream {
     __device__ __forceinline__ void put(uint32_t relblk, uint4 v)
     {
         uint32_t top = 16u - (relblk & 3u) * 4u;   // ring index of the block's first piece
-        slot[top - 3] = v.z;
-        slot[top - 2] = v.w;
-        slot[top - 1] = v.x;
-        slot[top] = v.y;
+        slot[(top - 3) * RING_ROW_DW] = v.z;
+        slot[(top - 2) * RING_ROW_DW] = v.w;
+        slot[(top - 1) * RING_ROW_DW] = v.x;
+        slot[top * RING_ROW_DW] = v.y;
         if (top == 16u) slot[0] = v.y;
     }
     __device__ __forceinline__ void land()
     {
-        if (inflight) {
-            put(loaded, fl);
-            ++loaded;
-            inflight = false;
-        }
+        if (nfly >= 1u) put(loaded, fl0);
+        if (nfly == 2u) put(loaded + 1u, fl1);
+        loaded += nfly;
+        nfly = 0;
     }
-    // make pieces [.., need_dw) resident (synchronous; only used off the fast path)
+    // make pieces [.., need_dw) resident (synchronous; only used off the fast path).  Callers ask for
+    // at most block cur+2, so the block overwritten (loaded-4) always lies behind the position.
     __device__ __forceinline__ void ensure(uint32_t need_dw)
     {
         land();
@@ -69,32 +73,39 @@ struct LaneStream {
     {
         base_blk = (int64_t)(p0 >> 7);
         rel = (uint32_t)(p0 & 127u);
-        inflight = false;
-        uint4 a = fetch(0), b = fetch(1), c = fetch(2);
+        nfly = 0;
+        uint4 a = fetch(0), b = fetch(1), c = fetch(2), d = fetch(3);
         put(0, a);
         put(1, b);
         put(2, c);
-        loaded = 3;
+        put(3, d);
+        loaded = 4;
     }
-    // Start of a group of DE_GROUP symbols.  On entry blocks cur .. cur+2 are resident or landing
-    // (a group whose codewords all fit the table prefix consumes at most 96 bits, less than a
-    // block); on exit block cur+3 is resident or requested.
+    // Start of a run of DE_GROUP symbols: what was requested at the previous boundary enters the ring,
+    // and up to two further blocks are requested so that four blocks from the current one on are
+    // resident or on their way.  The blocks they will replace lie behind the position.
     __device__ __forceinline__ void group_boundary()
     {
         land();
-        if (loaded < (rel >> 7) + 4u) {
-            fl = fetch(loaded);
-            inflight = true;
+        const uint32_t want = (rel >> 7) + 4u;
+        if (loaded < want) {
+            fl0 = fetch(loaded);
+            nfly = 1;
+            if (loaded + 1u < want) {
+                fl1 = fetch(loaded + 1u);
+                nfly = 2;
+            }
         }
     }
     __device__ __forceinline__ uint64_t pos() const { return ((uint64_t)base_blk << 7) + rel; }
     // the 32 stream bits at the current position
     __device__ __forceinline__ uint32_t peek32() const
     {
-        uint64_t two = *reinterpret_cast<const u64_align4 *>(slot + (~(rel >> 5) & 15u));
+        const uint32_t *pc = slot + (~(rel >> 5) & 15u) * RING_ROW_DW;
+        uint64_t two = ((uint64_t)pc[RING_ROW_DW] << 32) | (uint64_t)pc[0];
         return (uint32_t)((two << (rel & 31u)) >> 32);
     }
-    __device__ __forceinline__ uint32_t piece(uint32_t d) const { return slot[16u - (d & 15u)]; }
+    __device__ __forceinline__ uint32_t piece(uint32_t d) const { return slot[(16u - (d & 15u)) * RING_ROW_DW]; }
     __device__ __forceinline__ uint64_t peek64()
     {
         uint32_t d = rel >> 5, o = rel & 31u;
@@ -117,7 +128,10 @@ struct DecTables {           // LDS-resident decoder tables of one user
 __device__ __forceinline__ void load_tables(DecTables &t, const Co3Code *cd)
 {
     const uint32_t lb = cd->lut_bits > CO3_LUT_BITS_MAX ? CO3_LUT_BITS_MAX : cd->lut_bits;
-    for (uint32_t i = threadIdx.x; i < (1u << lb); i += blockDim.x) t.lut[i] = cd->lut[i];
+    for (uint32_t i = threadIdx.x; i < (1u << lb); i += blockDim.x) {
+        uint16_t e = cd->lut[i];
+        t.lut[i] = (e >> 8) ? e : (uint16_t)(DE_MISS_LEN << 8);   // miss: longer than the prefix, or invalid
+    }
     for (int i = threadIdx.x; i < 65; i += blockDim.x) t.first_code[i] = cd->first_code[i];
     for (int i = threadIdx.x; i < 66; i += blockDim.x) {
         t.count[i] = cd->count[i];
@@ -144,18 +158,18 @@ __device__ __forceinline__ int decode_long(const DecTables &t, uint64_t window, 
     return 0;
 }
 
-// Careful decoding of `count` <= 8 symbols (any codeword length, any stream content): used for
-// groups that met a codeword longer than the table prefix and for the ragged end of a chunk.
-// Leaves blocks cur .. cur+2 resident.  Symbols are returned first-in-lowest-byte.
-__device__ __forceinline__ uint64_t decode_group_careful(const DecTables &t, LaneStream &ls, int shift, int count,
-                                                      bool &ok)
+// Careful decoding of `count` <= 16 symbols (any codeword length, any stream content): used for runs
+// that the fast path could not vouch for and for the ragged end of a chunk.  Leaves blocks
+// cur .. cur+2 resident.  Symbols are returned 4 per word, first in the lowest byte.
+__device__ __forceinline__ void decode_run_careful(const DecTables &t, LaneStream &ls, int shift, int count, bool &ok,
+                                                   uint32_t w[4])
 {
-    uint64_t out = 0;
+    w[0] = w[1] = w[2] = w[3] = 0;
     for (int k = 0; k < count; ++k) {
         ls.ensure((ls.rel >> 5) + 2u);
         uint32_t e = t.lut[ls.peek32() >> shift];
         uint32_t l = e >> 8, s = e & 0xffu;
-        if (l == 0) {
+        if (l == DE_MISS_LEN) {
             l = (uint32_t)decode_long(t, ls.peek64(), &s);
             if (l == 0) {
                 ok = false;
@@ -164,16 +178,24 @@ __device__ __forceinline__ uint64_t decode_group_careful(const DecTables &t, Lan
             }
         }
         ls.rel += l;
-        out |= (uint64_t)s << (8 * k);
+        uint32_t sh = s << (8 * (k & 3));
+        if ((k >> 2) == 0) w[0] |= sh;
+        else if ((k >> 2) == 1) w[1] |= sh;
+        else if ((k >> 2) == 2) w[2] |= sh;
+        else w[3] |= sh;
     }
     ls.ensure(((ls.rel >> 7) + 3u) * 4u);
-    return out;
 }
 
 // One lane decodes the `nsym` symbols of one chunk.  Symbols leave in runs of 16: run r is stored at
 // out + r * run_step (run_step = 16 gives the plain contiguous layout; the tiled layout used between
 // decoding and averaging interleaves the runs of the 64 chunks of a wavefront so that each store
 // instruction of the wavefront covers one contiguous KiB).
+//
+// The fast path decodes a run without any check per symbol and validates it afterwards: every
+// window it read lay inside the blocks that were resident when the run started, and no table
+// entry was a miss (a miss advances by DE_MISS_LEN, more than 16 hits can).  Otherwise the run is
+// decoded again by the careful path from the saved position.
 __device__ __forceinline__ bool decode_chunk(const DecTables &t, LaneStream &ls, uint64_t p0, uint64_t p1, int nsym,
                                              uint8_t *out, int64_t run_step)
 {
@@ -182,49 +204,39 @@ __device__ __forceinline__ bool decode_chunk(const DecTables &t, LaneStream &ls,
     ls.open(p0);
     int i = 0;
 #pragma unroll 1
-    for (; i + 2 * DE_GROUP <= nsym; i += 2 * DE_GROUP) {
-        uint32_t w0 = 0, w1 = 0, w2 = 0, w3 = 0;
-#pragma unroll 1
-        for (int h = 0; h < 2; ++h) {
-            ls.group_boundary();
-            const uint32_t rel0 = ls.rel;
-            uint32_t lo = 0, hi = 0, minlen = 255u;
-            uint32_t nrel = ~rel0;          // complement of the position: ring index and shift come cheaper
-#pragma unroll
-            for (int b = 0; b < DE_GROUP; ++b) {
-                uint64_t two = *reinterpret_cast<const u64_align4 *>(ls.slot + ((nrel >> 5) & 15u));
-                uint32_t w = (uint32_t)((two << (~nrel & 31u)) >> 32);
-                uint32_t e = t.lut[w >> shift];
-                uint32_t l = e >> 8;
-                minlen = min(minlen, l);
-                nrel -= l;
-                if (b < 4)
-                    lo = __builtin_amdgcn_alignbit(e, lo, 8);
-                else
-                    hi = __builtin_amdgcn_alignbit(e, hi, 8);
-            }
-            ls.rel = ~nrel;
-            if (minlen == 0) {          // rare: redo the group with the careful decoder
-                ls.rel = rel0;
-                uint64_t r = decode_group_careful(t, ls, shift, DE_GROUP, ok);
-                lo = (uint32_t)r;
-                hi = (uint32_t)(r >> 32);
-            }
-            if (h == 0) {
-                w0 = lo;
-                w1 = hi;
-            } else {
-                w2 = lo;
-                w3 = hi;
-            }
-        }
-        *reinterpret_cast<uint4 *>(out + (int64_t)(i >> 4) * run_step) = make_uint4(w0, w1, w2, w3);
-    }
-    for (int left = nsym - i; left > 0; left -= DE_GROUP) {      // ragged end of the last chunk
+    for (; i + DE_GROUP <= nsym; i += DE_GROUP) {
         ls.group_boundary();
-        int cnt = left < DE_GROUP ? left : DE_GROUP;
-        uint64_t r = decode_group_careful(t, ls, shift, cnt, ok);
-        for (int k = 0; k < cnt; ++k, ++i) out[(int64_t)(i >> 4) * run_step + (i & 15)] = (uint8_t)(r >> (8 * k));
+        const uint32_t rel0 = ls.rel;
+        uint32_t w[4] = {0u, 0u, 0u, 0u};
+        // Work with the negated position m = -rel.  The window of 32 stream bits at rel is
+        // ({piece d, piece d+1} >> (m mod 32)) with d = (rel - 1) / 32, whose ring index is
+        // bits 5..8 of m: one field extract, one two-address LDS read, one funnel shift.
+        uint32_t m = 0u - rel0;
+#pragma unroll
+        for (int b = 0; b < DE_GROUP; ++b) {
+            const uint32_t *pc = ls.slot + ((m >> 5) & 15u) * RING_ROW_DW;
+            uint32_t win = __builtin_amdgcn_alignbit(pc[RING_ROW_DW], pc[0], m);
+            uint32_t e = t.lut[win >> shift];
+            m -= e >> 8;
+            w[b >> 2] = __builtin_amdgcn_alignbit(e, w[b >> 2], 8);
+        }
+        ls.rel = 0u - m;
+        if (ls.rel - rel0 > DE_GROUP * CO3_LUT_BITS_MAX || ls.rel + 64u > ls.loaded * 128u) {   // rare
+            ls.rel = rel0;
+            decode_run_careful(t, ls, shift, DE_GROUP, ok, w);
+        }
+        *reinterpret_cast<uint4 *>(out + (int64_t)(i >> 4) * run_step) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+    if (i < nsym) {                         // ragged end of the last chunk
+        ls.group_boundary();
+        uint32_t w[4];
+        const int cnt = nsym - i;
+        decode_run_careful(t, ls, shift, cnt, ok, w);
+        uint8_t *dst = out + (int64_t)(i >> 4) * run_step;
+        for (int k = 0; k < cnt; ++k) {
+            uint32_t word = (k >> 2) == 0 ? w[0] : (k >> 2) == 1 ? w[1] : (k >> 2) == 2 ? w[2] : w[3];
+            dst[k] = (uint8_t)(word >> (8 * (k & 3)));
+        }
     }
     ls.land();
     return ok && ls.pos() == p1;
@@ -240,7 +252,7 @@ __global__ __launch_bounds__(DE_BLOCK) void k_decode(const uint64_t *__restrict_
 {
     const int u = blockIdx.y;
     __shared__ DecTables t;
-    __shared__ uint32_t ring[DE_BLOCK * RING_STRIDE];
+    __shared__ uint32_t ring[DE_BLOCK * RING_ROWS];
     load_tables(t, dcode_of(codes, u));
     __syncthreads();
 
@@ -250,7 +262,7 @@ __global__ __launch_bounds__(DE_BLOCK) void k_decode(const uint64_t *__restrict_
     LaneStream ls;
     ls.blocks = reinterpret_cast<const uint4 *>(words + (int64_t)u * cap_words);
     ls.nblocks = cap_words / 2;
-    ls.slot = ring + threadIdx.x * RING_STRIDE;
+    ls.slot = ring + (threadIdx.x / CO3_WAVE) * (RING_ROWS * RING_ROW_DW) + (threadIdx.x & (CO3_WAVE - 1));
     int64_t first = c * chunk_syms;
     int nsym = (int)(n - first < chunk_syms ? n - first : chunk_syms);
     uint8_t *out;
@@ -318,6 +330,9 @@ __global__ __launch_bounds__(PS_BLOCK) void k_ps_sum(const uint8_t *__restrict__
 // Average from the tiled workspace: one thread owns a run of 16 consecutive elements.
 #define PT_BLOCK 256
 
+// TABLE = true (one tensor, i.e. one anchor per user): the K values of every user are computed
+// once per block into LDS, and an element costs one LDS read and one add.
+template <bool TABLE>
 __global__ __launch_bounds__(PT_BLOCK) void k_ps_sum_tiled(const uint8_t *__restrict__ symt, int64_t n, int U,
                                                             int64_t ws_stride, int chunk_syms, int64_t nruns,
                                                             const int32_t *__restrict__ anchor,
@@ -329,6 +344,18 @@ __global__ __launch_bounds__(PT_BLOCK) void k_ps_sum_tiled(const uint8_t *__rest
     const uint32_t cmask = (uint32_t)fc.codemax;
     const float fU = (float)U;
     const int runs_per_chunk = chunk_syms >> 4;
+    extern __shared__ float value_of[];    // [U][K], TABLE only
+    if (TABLE) {
+        const int K = fc.K;
+        for (int j = threadIdx.x; j < U * K; j += PT_BLOCK) {
+            const int u = j / K;
+            const uint32_t s = (uint32_t)(j - u * K);
+            const int e_min = anchor[u] - F + 1;
+            float val = co3_code_value(s & cmask, e_min, M);
+            value_of[j] = __uint_as_float(__float_as_uint(val) | ((s >> EM) << 31));
+        }
+        __syncthreads();
+    }
     for (int64_t r = (int64_t)blockIdx.x * PT_BLOCK + threadIdx.x; r < nruns; r += (int64_t)gridDim.x * PT_BLOCK) {
         // r enumerates (tile, run within chunk, lane) with the lane fastest: the workspace order
         const int lane = (int)(r & 63);
@@ -344,7 +371,16 @@ __global__ __launch_bounds__(PT_BLOCK) void k_ps_sum_tiled(const uint8_t *__rest
         float acc[16];
 #pragma unroll
         for (int k = 0; k < 16; ++k) acc[k] = 0.f;
-        if (s_lo == s_hi) {
+        if (TABLE) {
+            const uint32_t kmask = (uint32_t)fc.K - 1u;
+            for (int u = 0; u < U; ++u) {
+                const float *vu = value_of + u * fc.K;
+                uint4 v = ld_stream_u4(src + (int64_t)u * ws_stride);
+                uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int k = 0; k < 16; ++k) acc[k] += vu[(w[k >> 2] >> (8 * (k & 3))) & kmask];
+            }
+        } else if (s_lo == s_hi) {
             for (int u = 0; u < U; ++u) {
                 const int e_min = anchor[(int64_t)u * nseg + s_lo] - F + 1;
                 uint4 v = *reinterpret_cast<const uint4 *>(src + (int64_t)u * ws_stride);
@@ -423,7 +459,12 @@ hipError_t co3_launch_ps_sum_tiled(const uint8_t *symt, int64_t n, int U, int64_
     int64_t b = (nruns + PT_BLOCK - 1) / PT_BLOCK;
     unsigned blocks = (unsigned)(b < 8192 ? b : 8192);
     Co3LaunchTimer tm(CO3_K_PS_SUM, st);
-    hipLaunchKernelGGL(k_ps_sum_tiled, dim3(blocks), dim3(PT_BLOCK), 0, st, symt, n, U, ws_stride, chunk_syms, nruns,
-                       anchor, seg_off, nseg, fmt, avg_out);
+    const size_t table_bytes = (size_t)U * (size_t)(1 << (1 + fmt.exp_bits + fmt.mant_bits)) * sizeof(float);
+    if (nseg == 1 && table_bytes <= 32768)
+        hipLaunchKernelGGL(k_ps_sum_tiled<true>, dim3(blocks), dim3(PT_BLOCK), table_bytes, st, symt, n, U, ws_stride,
+                           chunk_syms, nruns, anchor, seg_off, nseg, fmt, avg_out);
+    else
+        hipLaunchKernelGGL(k_ps_sum_tiled<false>, dim3(blocks), dim3(PT_BLOCK), 0, st, symt, n, U, ws_stride,
+                           chunk_syms, nruns, anchor, seg_off, nseg, fmt, avg_out);
     return hipGetLastError();
 }
