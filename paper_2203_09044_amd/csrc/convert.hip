@@ -23,8 +23,8 @@ __global__ void k_fill_i32(int32_t *a, int64_t na, int32_t va, uint32_t *b, int6
 // anchor: A = floor(log2 max|g|) per (user, segment) = biased exponent of the largest magnitude
 // minus 127, at most 127; the lower clamp comes from the initial value.
 // ------------------------------------------------------------------------------------------
-#define AM_UNROLL 4
-#define AM_TILE (CV_TILE * AM_UNROLL)   // elements per block step: four 16-byte loads in flight per thread
+#define AM_UNROLL 8
+#define AM_TILE (CV_TILE * AM_UNROLL)   // elements per block step: eight 16-byte loads in flight per thread
 
 // Block-wide maximum of the magnitude bit patterns, then at most one atomic per block (and none
 // when the anchor already holds a value at least as large).  Called under block-uniform conditions.
@@ -79,14 +79,11 @@ __global__ __launch_bounds__(CV_BLOCK) void k_absmax(const float *__restrict__ g
                 cur_seg = s_lo;
             }
             if (t1 - t0 == AM_TILE) {
-                float4 v0 = ld_stream_f4(gu + i);
-                float4 v1 = ld_stream_f4(gu + i + CV_TILE);
-                float4 v2 = ld_stream_f4(gu + i + 2 * CV_TILE);
-                float4 v3 = ld_stream_f4(gu + i + 3 * CV_TILE);
-                m = absmax4(v0, m);
-                m = absmax4(v1, m);
-                m = absmax4(v2, m);
-                m = absmax4(v3, m);
+                float4 v[AM_UNROLL];
+#pragma unroll
+                for (int k = 0; k < AM_UNROLL; ++k) v[k] = ld_stream_f4(gu + i + (int64_t)k * CV_TILE);
+#pragma unroll
+                for (int k = 0; k < AM_UNROLL; ++k) m = absmax4(v[k], m);
             } else {
                 for (int k = 0; k < AM_UNROLL; ++k) {
                     int64_t j0 = i + (int64_t)k * CV_TILE;

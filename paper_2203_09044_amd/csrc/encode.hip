@@ -67,26 +67,41 @@ __global__ __launch_bounds__(EN_BLOCK) void k_enc_sizes(const uint8_t *__restric
     if (tb0 >= nblk) return;
     const uint8_t *su = sym + (int64_t)u * stride;
     uint32_t s[SZ_TILES][4];
-    int nvalid[SZ_TILES];
-#pragma unroll
-    for (int t = 0; t < SZ_TILES; ++t) {
-        const int64_t i = (tb0 + t) * CO3_PACK_SYMS + (int64_t)lane * EN_LSYM;
-        nvalid[t] = i < n ? load_syms16(su, i, n, s[t]) : 0;
-    }
     bool nocode = false;
+    if ((tb0 + SZ_TILES) * CO3_PACK_SYMS <= n) {     // uniform: all four tiles are complete
 #pragma unroll
-    for (int t = 0; t < SZ_TILES; ++t) {
-        uint32_t bits = 0;
-#pragma unroll
-        for (int c = 0; c < EN_LSYM; ++c) {
-            uint32_t l = len_s[(s[t][c >> 2] >> (8 * (c & 3))) & 0xffu];
-            if (c < nvalid[t]) {
-                bits += l;
-                nocode |= (l == 0);
-            }
+        for (int t = 0; t < SZ_TILES; ++t) {
+            // ordinary (cached) loads: the packing pass reads the same symbols next
+            uint4 a = *reinterpret_cast<const uint4 *>(su + (tb0 + t) * CO3_PACK_SYMS + (int64_t)lane * EN_LSYM);
+            s[t][0] = a.x; s[t][1] = a.y; s[t][2] = a.z; s[t][3] = a.w;
         }
-        bits = wave_sum_u32(bits);
-        if (lane == 0 && tb0 + t < nblk) tilesum[(int64_t)u * nblk + tb0 + t] = bits;
+#pragma unroll
+        for (int t = 0; t < SZ_TILES; ++t) {
+            uint32_t bits = 0, minlen = 255u;
+#pragma unroll
+            for (int c = 0; c < EN_LSYM; ++c) {
+                uint32_t l = len_s[(s[t][c >> 2] >> (8 * (c & 3))) & 0xffu];
+                bits += l;
+                minlen = min(minlen, l);
+            }
+            nocode |= minlen == 0u;
+            bits = wave_sum_u32(bits);
+            if (lane == 0) tilesum[(int64_t)u * nblk + tb0 + t] = bits;
+        }
+    } else {                                          // the end of the vector
+        for (int t = 0; t < SZ_TILES && tb0 + t < nblk; ++t) {
+            const int64_t i = (tb0 + t) * CO3_PACK_SYMS + (int64_t)lane * EN_LSYM;
+            const int nvalid = i < n ? load_syms16(su, i, n, s[0]) : 0;
+            uint32_t bits = 0;
+#pragma unroll
+            for (int c = 0; c < EN_LSYM; ++c) {
+                uint32_t l = len_s[(s[0][c >> 2] >> (8 * (c & 3))) & 0xffu];
+                bits += c < nvalid ? l : 0u;
+                nocode |= c < nvalid && l == 0u;
+            }
+            bits = wave_sum_u32(bits);
+            if (lane == 0) tilesum[(int64_t)u * nblk + tb0 + t] = bits;
+        }
     }
     if (nocode) co3_raise(status, CO3_ENOCODE);
 }
@@ -151,6 +166,30 @@ __global__ __launch_bounds__(SC_BLOCK) void k_enc_scan(uint64_t *__restrict__ ti
 }
 
 // ---- pass 3: bit packing ------------------------------------------------------------------
+// Codewords of the lane's 16 symbols, concatenated four at a time.
+template <bool FULL>
+__device__ __forceinline__ void lookup_runs(const uint64_t *enc_s, const uint32_t s[4], int nvalid,
+                                            uint64_t run[EN_LSYM / 4], uint32_t runbits[EN_LSYM / 4], uint32_t &mybits,
+                                            bool &wide)
+{
+#pragma unroll
+    for (int g = 0; g < EN_LSYM / 4; ++g) {
+        uint64_t acc = 0;
+        uint32_t nb = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            uint64_t e = (FULL || 4 * g + k < nvalid) ? enc_s[(s[g] >> (8 * k)) & 0xffu] : 0ull;
+            uint32_t l = (uint32_t)(e & 63u);
+            acc = (acc << l) | (e >> 6);
+            nb += l;
+        }
+        wide |= nb > 64u;
+        run[g] = acc;
+        runbits[g] = nb;
+        mybits += nb;
+    }
+}
+
 // ORs `nb` bits (right-aligned in `acc`, 1 <= nb <= 64) into the staging window at stream position
 // `pos` (bits, relative to the first word of the tile); only words inside the window are touched.
 __device__ __forceinline__ void stage_bits(unsigned long long *stage, int64_t win_w0, uint64_t acc, int nb,
@@ -195,22 +234,10 @@ __global__ __launch_bounds__(EN_BLOCK) void k_enc_pack(const uint8_t *__restrict
     uint32_t runbits[EN_LSYM / 4];
     uint32_t mybits = 0;
     bool wide = false;
-#pragma unroll
-    for (int g = 0; g < EN_LSYM / 4; ++g) {
-        uint64_t acc = 0;
-        uint32_t nb = 0;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            uint64_t e = (4 * g + k < nvalid) ? enc_s[(s[g] >> (8 * k)) & 0xffu] : 0ull;
-            uint32_t l = (uint32_t)(e & 63u);
-            acc = (acc << l) | (e >> 6);
-            nb += l;
-        }
-        wide |= nb > 64u;
-        run[g] = acc;
-        runbits[g] = nb;
-        mybits += nb;
-    }
+    if ((tb + 1) * CO3_PACK_SYMS <= n)      // uniform: every symbol of the tile exists
+        lookup_runs<true>(enc_s, s, nvalid, run, runbits, mybits, wide);
+    else
+        lookup_runs<false>(enc_s, s, nvalid, run, runbits, mybits, wide);
     const uint32_t incl = wave_scan_incl_u32(mybits, lane);
     const uint32_t excl = incl - mybits;
     const uint32_t tilebits = (uint32_t)__shfl((int)incl, CO3_WAVE - 1, CO3_WAVE);
@@ -228,6 +255,43 @@ __global__ __launch_bounds__(EN_BLOCK) void k_enc_pack(const uint8_t *__restrict
     const int64_t gwl = (int64_t)((B1 - 1) >> 6);
     const int64_t first_owned = (B0 & 63) ? gw0 + 1 : gw0;   // words whose first bit lies in the tile
     const uint64_t rel0 = (B0 & 63) + excl;          // position of this lane's bits, relative to word gw0
+
+    if ((B0 & 63) + tilebits <= EN_STAGE_WORDS * 64u && !__any(wide)) {
+        // usual case: the tile fits one staging window and every run fits 64 bits
+#pragma unroll
+        for (int j = 0; j < EN_STAGE_WORDS / CO3_WAVE; ++j) stage[lane + j * CO3_WAVE] = 0ull;
+        wave_lds_sync();
+        uint32_t pos = (uint32_t)rel0;
+#pragma unroll
+        for (int g = 0; g < EN_LSYM / 4; ++g) {
+            const uint32_t nb = runbits[g];
+            if (nb) {
+                const uint64_t v = run[g] << (64u - nb);
+                const uint32_t w = pos >> 6, o = pos & 63u;
+                atomicOr(&stage[w], (unsigned long long)(v >> o));
+                if (o + nb > 64u) atomicOr(&stage[w + 1], (unsigned long long)(v << (64u - o)));
+            }
+            pos += nb;
+        }
+        const uint32_t last_rel = (uint32_t)(gwl - gw0);
+        if (B1 & 63) {          // complete the last word with the codewords that follow the tile
+            const int64_t i2 = (tb + 1) * CO3_PACK_SYMS + lane;
+            uint64_t e = (lane < CO3_WAVE - 1 && i2 < n) ? enc_s[su[i2]] : 0ull;
+            uint32_t l = (uint32_t)(e & 63u);
+            uint32_t o = wave_scan_incl_u32(l, lane) - l;
+            const uint32_t used = (uint32_t)(B1 & 63);
+            if (l && used + o < 64u)
+                atomicOr(&stage[last_rel], (unsigned long long)(((e >> 6) << (64 - l)) >> (used + o)));
+        }
+        wave_lds_sync();
+        const uint32_t first_rel = (uint32_t)(first_owned - gw0);
+#pragma unroll
+        for (int j = 0; j < EN_STAGE_WORDS / CO3_WAVE; ++j) {
+            const uint32_t r = lane + j * CO3_WAVE;
+            if (r >= first_rel && r <= last_rel) wu[gw0 + r] = stage[r];
+        }
+        return;
+    }
 
     for (int64_t win_w0 = 0; gw0 + win_w0 <= gwl; win_w0 += EN_STAGE_WORDS) {
 #pragma unroll
