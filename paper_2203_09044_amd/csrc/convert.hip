@@ -80,8 +80,10 @@ __global__ __launch_bounds__(CV_BLOCK) void k_absmax(const float *__restrict__ g
             }
             if (t1 - t0 == AM_TILE) {
                 float4 v[AM_UNROLL];
+                // ordinary (cached) loads: the conversion pass reads g again, last-read part first
 #pragma unroll
-                for (int k = 0; k < AM_UNROLL; ++k) v[k] = ld_stream_f4(gu + i + (int64_t)k * CV_TILE);
+                for (int k = 0; k < AM_UNROLL; ++k)
+                    v[k] = *reinterpret_cast<const float4 *>(gu + i + (int64_t)k * CV_TILE);
 #pragma unroll
                 for (int k = 0; k < AM_UNROLL; ++k) m = absmax4(v[k], m);
             } else {
@@ -149,7 +151,10 @@ __global__ __launch_bounds__(CV_BLOCK) void k_convert_ef(const float *__restrict
 {
     const FmtC fc(fmt);
     const int E = fc.E, M = fc.M, F = fc.F, K = fc.K, codemax = fc.codemax;
-    const int u = blockIdx.y;
+    // Users and ranges are taken in the reverse of the order in which the anchor pass read g, so that
+    // the part of g that pass left in the last-level cache is read first.
+    const int u = gridDim.y - 1 - blockIdx.y;
+    const int64_t range = gridDim.x - 1 - blockIdx.x;
     const float *gu = g + (int64_t)u * stride;
     float *eu = err + (int64_t)u * stride;
     uint8_t *su = sym + (int64_t)u * stride;
@@ -168,7 +173,7 @@ __global__ __launch_bounds__(CV_BLOCK) void k_convert_ef(const float *__restrict
         __syncthreads();
     }
 
-    int64_t beg = (int64_t)blockIdx.x * per_block;
+    int64_t beg = range * per_block;
     int64_t end = beg + per_block < n ? beg + per_block : n;
 
     // four elements of one thread: correct, convert, update the memory, count
