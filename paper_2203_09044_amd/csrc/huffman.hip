@@ -34,11 +34,11 @@ __global__ __launch_bounds__(HB_BLOCK) void k_build_code(const uint32_t *__restr
     if (tid == 0) maxlen_s = 0;
     const int nact = __syncthreads_count(wt != 0u);
 
-    // leaves in (weight, symbol) order: bitonic sort of the 256 keys
-    for (int k = 2; k <= HB_BLOCK; k <<= 1) {
+    // leaves in (weight, symbol) order: bitonic sort of the K keys (K is a power of two)
+    for (int k = 2; k <= K; k <<= 1) {
         for (int j = k >> 1; j > 0; j >>= 1) {
             int other = tid ^ j;
-            if (other > tid) {
+            if (other > tid && other < K) {
                 uint64_t a = key[tid], b = key[other];
                 bool ascending = (tid & k) == 0;
                 if ((a > b) == ascending) {
@@ -115,7 +115,7 @@ __global__ __launch_bounds__(HB_BLOCK) void k_build_code(const uint32_t *__restr
         uint64_t enc = 0;
         if (l) {
             uint32_t rank = 0;
-            for (int j = 0; j < tid; ++j) rank += (len_s[j] == l) ? 1u : 0u;
+            for (int j = 0; j < tid; ++j) rank += (len_s[j] == l) ? 1u : 0u;   // tid < K here
             uint64_t code = first_s[l] + rank;
             sorted_s[base_s[l] + rank] = (uint8_t)tid;
             enc = (code << 6) | (uint64_t)(l & 63u);
@@ -139,13 +139,22 @@ __global__ __launch_bounds__(HB_BLOCK) void k_build_code(const uint32_t *__restr
         out->reserved = 0;
     }
 
-    // decoder table: entry i decodes the lut_bits-bit prefix i by the canonical rule
+    // decoder table: entry i decodes the lut_bits-bit prefix i by the canonical rule.  Canonical
+    // codewords grow with their length, so the prefixes resolved by length <= l form the range
+    // [0, limit[l]) with limit[l] = (first_code[l] + count[l]) << (lut_bits - l): the entry's length is
+    // the first l whose limit exceeds i.
+    __shared__ uint32_t limit_s[CO3_LUT_BITS_MAX + 2];
+    if (tid >= 1 && tid <= (int)lut_bits) {
+        uint64_t lim = (first_s[tid] + cnt_s[tid]) << (lut_bits - tid);
+        limit_s[tid] = lim > (1ull << lut_bits) ? (1u << lut_bits) : (uint32_t)lim;
+    }
+    __syncthreads();
     for (uint32_t i = tid; i < (1u << lut_bits); i += HB_BLOCK) {
         uint16_t entry = 0;
         for (uint32_t l = 1; l <= lut_bits; ++l) {
-            uint64_t off = (uint64_t)(i >> (lut_bits - l)) - first_s[l];
-            if (off < (uint64_t)cnt_s[l]) {
-                entry = (uint16_t)((l << 8) | sorted_s[base_s[l] + (uint32_t)off]);
+            if (i < limit_s[l]) {
+                uint32_t off = (i >> (lut_bits - l)) - (uint32_t)first_s[l];
+                entry = (uint16_t)((l << 8) | sorted_s[base_s[l] + off]);
                 break;
             }
         }
