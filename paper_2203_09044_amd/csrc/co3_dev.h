@@ -85,22 +85,24 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
     return v;
 }
 
-__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v)
+// Inclusive prefix sum across the 64 lanes of a wavefront with data-parallel-primitive moves:
+// shifts by 1, 2, 4, 8 inside each row of 16 lanes, then the last lane of row 0/2 is added to row
+// 1/3 and the last lane of the lower half to the upper half.  Lanes without a source add 0.
+__device__ __forceinline__ uint32_t wave_scan_incl_u32(uint32_t v, int /*lane*/)
 {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) v += (uint32_t)__shfl_xor((int)v, o, CO3_WAVE);
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, false);   // row_shr:1
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, false);   // row_shr:2
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, false);   // row_shr:4
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, false);   // row_shr:8
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xa, 0xf, false);   // row_bcast:15 -> rows 1, 3
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xc, 0xf, false);   // row_bcast:31 -> rows 2, 3
     return v;
 }
 
-// inclusive prefix sum across the 64 lanes of a wavefront
-__device__ __forceinline__ uint32_t wave_scan_incl_u32(uint32_t v, int lane)
+// sum over the wavefront, returned in every lane
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v)
 {
-#pragma unroll
-    for (int o = 1; o < CO3_WAVE; o <<= 1) {
-        uint32_t t = (uint32_t)__shfl_up((int)v, o, CO3_WAVE);
-        if (lane >= o) v += t;
-    }
-    return v;
+    return (uint32_t)__builtin_amdgcn_readlane((int)wave_scan_incl_u32(v, 0), CO3_WAVE - 1);
 }
 
 // Value of a magnitude code under e_min = A - F + 1 (Sec. III (i)): exponent field f >= 1 is

@@ -240,7 +240,7 @@ __global__ __launch_bounds__(EN_BLOCK) void k_enc_pack(const uint8_t *__restrict
         lookup_runs<false>(enc_s, s, nvalid, run, runbits, mybits, wide);
     const uint32_t incl = wave_scan_incl_u32(mybits, lane);
     const uint32_t excl = incl - mybits;
-    const uint32_t tilebits = (uint32_t)__shfl((int)incl, CO3_WAVE - 1, CO3_WAVE);
+    const uint32_t tilebits = (uint32_t)__builtin_amdgcn_readlane((int)incl, CO3_WAVE - 1);
 
     const uint64_t B0 = tileoff[(int64_t)u * nblk + tb];
     const uint64_t B1 = B0 + tilebits;
