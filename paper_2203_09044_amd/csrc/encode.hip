@@ -190,6 +190,28 @@ __device__ __forceinline__ void lookup_runs(const uint64_t *enc_s, const uint32_
     }
 }
 
+// The same for codes of at most 16 bits (then (codeword << 6 | length) sits in the low dword of a
+// table entry and two codewords fit 32 bits): pairs are joined with 32-bit operations.
+__device__ __forceinline__ void lookup_runs_short(const uint64_t *enc_s, const uint32_t s[4],
+                                                  uint64_t run[EN_LSYM / 4], uint32_t runbits[EN_LSYM / 4],
+                                                  uint32_t &mybits)
+{
+    const uint32_t *enc32 = reinterpret_cast<const uint32_t *>(enc_s);
+#pragma unroll
+    for (int g = 0; g < EN_LSYM / 4; ++g) {
+        uint32_t e0 = enc32[2 * (s[g] & 0xffu)], e1 = enc32[2 * ((s[g] >> 8) & 0xffu)];
+        uint32_t e2 = enc32[2 * ((s[g] >> 16) & 0xffu)], e3 = enc32[2 * (s[g] >> 24)];
+        uint32_t l1 = e1 & 63u, l3 = e3 & 63u;
+        uint32_t p01 = ((e0 >> 6) << l1) | (e1 >> 6);
+        uint32_t p23 = ((e2 >> 6) << l3) | (e3 >> 6);
+        uint32_t n23 = (e2 & 63u) + l3;
+        uint32_t nb = (e0 & 63u) + l1 + n23;
+        run[g] = ((uint64_t)p01 << n23) | (uint64_t)p23;
+        runbits[g] = nb;
+        mybits += nb;
+    }
+}
+
 // ORs `nb` bits (right-aligned in `acc`, 1 <= nb <= 64) into the staging window at stream position
 // `pos` (bits, relative to the first word of the tile); only words inside the window are touched.
 __device__ __forceinline__ void stage_bits(unsigned long long *stage, int64_t win_w0, uint64_t acc, int nb,
@@ -213,6 +235,7 @@ __global__ __launch_bounds__(EN_BLOCK) void k_enc_pack(const uint8_t *__restrict
     __shared__ uint64_t enc_s[256];
     __shared__ unsigned long long stage_all[EN_WAVES][EN_STAGE_WORDS];
     enc_s[threadIdx.x] = (int)threadIdx.x < K ? cd->enc[threadIdx.x] : 0ull;
+    const uint32_t maxlen = cd->maxlen;
     __syncthreads();
 
     const int lane = threadIdx.x & (CO3_WAVE - 1);
@@ -234,9 +257,12 @@ __global__ __launch_bounds__(EN_BLOCK) void k_enc_pack(const uint8_t *__restrict
     uint32_t runbits[EN_LSYM / 4];
     uint32_t mybits = 0;
     bool wide = false;
-    if ((tb + 1) * CO3_PACK_SYMS <= n)      // uniform: every symbol of the tile exists
-        lookup_runs<true>(enc_s, s, nvalid, run, runbits, mybits, wide);
-    else
+    if ((tb + 1) * CO3_PACK_SYMS <= n) {    // uniform: every symbol of the tile exists
+        if (maxlen <= 16u)
+            lookup_runs_short(enc_s, s, run, runbits, mybits);
+        else
+            lookup_runs<true>(enc_s, s, nvalid, run, runbits, mybits, wide);
+    } else
         lookup_runs<false>(enc_s, s, nvalid, run, runbits, mybits, wide);
     const uint32_t incl = wave_scan_incl_u32(mybits, lane);
     const uint32_t excl = incl - mybits;
