@@ -28,6 +28,7 @@ def log(*a):
 
 
 def make_workload(name):
+    """(workload, per-user betas, scale, description, segmented) for a benchmark configuration."""
     import co3_inputs as inp
     if name == "C3":
         w = inp.c3()
@@ -37,10 +38,19 @@ def make_workload(name):
     if name == "C1":
         w = inp.c1()
         return w, [1.0], 1e-3, "C1: 1 client x 65,536 fp32, GenNorm beta=1 scale 1e-3, E3M1"
-    if name == "C5":
-        w = inp.c5(4)
-        return w, [1.0], 1e-3, "C5[E3M1,beta=1]: 16 clients x 25,000,000 fp32, scale 1e-3"
-    raise SystemExit(f"unknown workload {name}")
+    if name == "C2":
+        w = inp.c2()
+        return w, [0.8], 1e-3, ("C2: 1 client x 11,173,962 fp32 in 62 tensors (per-tensor anchors), GenNorm beta=0.8, "
+                                "E4M3 (the benchmark draws one scale for all tensors)")
+    if name == "C4":
+        w = inp.c4()
+        return w, [1.0], 1e-4, "C4: 1 client x 100,000,000 fp32, GenNorm beta=1 scale 1e-4, E5M2, empirical table"
+    if name.startswith("C5"):
+        point = int(name[3:]) if len(name) > 3 else 4
+        w = inp.c5(point)
+        beta = inp.C5_BETAS[point % 3]
+        return w, [beta], 1e-3, f"C5[{point}]: 16 clients x 25,000,000 fp32, E{w.E}M{w.M}, GenNorm beta={beta} scale 1e-3"
+    raise SystemExit(f"unknown workload {name} (C1, C2, C3, C4, C5.<point 0..11>)")
 
 
 def device_batches(w, betas, alpha, pool, pipe):
@@ -96,7 +106,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="C3")
+    ap.add_argument("--workload", default="C3", help="C3 (default, the headline configuration), C1, C2, C4, C5.<point>")
     ap.add_argument("--chunk", type=int, default=256)
     ap.add_argument("--pool", type=int, default=3, help="distinct gradient batches cycled through")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
@@ -122,7 +132,7 @@ def main():
 
     w, betas, alpha, desc = make_workload(args.workload)
     fmt = Fmt(w.E, w.M)
-    pipe = Co3Pipeline(w.U, w.n, fmt, chunk_syms=args.chunk)
+    pipe = Co3Pipeline(w.U, w.n, fmt, chunk_syms=args.chunk, seg_off=w.seg_off if w.sizes is not None else None)
     log(f"[bench] {desc}; generating {args.pool} device batches")
     batches = device_batches(w, betas, alpha, args.pool, pipe)
 

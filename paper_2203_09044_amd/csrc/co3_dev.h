@@ -75,6 +75,17 @@ __device__ __forceinline__ int co3_find_seg(const int64_t *seg_off, int nseg, in
     return s > nseg - 1 ? nseg - 1 : s;
 }
 
+// Tensor boundaries are looked up once or twice per tile; a block keeps them in LDS when they fit
+// (the lookups are chains of dependent loads).  Returns the pointer to search from then on.
+#define CO3_SEG_CACHE 512
+__device__ __forceinline__ const int64_t *co3_cache_segs(const int64_t *seg_off, int nseg, int64_t *cache)
+{
+    if (seg_off == nullptr || nseg <= 1 || nseg + 1 > CO3_SEG_CACHE) return seg_off;
+    for (int k = threadIdx.x; k <= nseg; k += blockDim.x) cache[k] = seg_off[k];
+    __syncthreads();
+    return cache;
+}
+
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
 {
 #pragma unroll

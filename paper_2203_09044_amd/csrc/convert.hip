@@ -54,13 +54,15 @@ __device__ __forceinline__ uint32_t absmax4(float4 v, uint32_t m)
 }
 
 __global__ __launch_bounds__(CV_BLOCK) void k_absmax(const float *__restrict__ g, int64_t n, int64_t stride,
-                                                      const int64_t *__restrict__ seg_off, int nseg,
+                                                      const int64_t *__restrict__ seg_off_g, int nseg,
                                                       int32_t *__restrict__ anchor, int64_t per_block)
 {
     const int u = blockIdx.y;
     const float *gu = g + (int64_t)u * stride;
     int32_t *anchor_u = anchor + (int64_t)u * nseg;
     __shared__ uint32_t red[CV_BLOCK / CO3_WAVE];
+    __shared__ int64_t seg_cache[CO3_SEG_CACHE];
+    const int64_t *seg_off = co3_cache_segs(seg_off_g, nseg, seg_cache);
     int64_t beg = (int64_t)blockIdx.x * per_block;
     int64_t end = beg + per_block < n ? beg + per_block : n;
     if (beg >= end) return;
@@ -99,17 +101,20 @@ __global__ __launch_bounds__(CV_BLOCK) void k_absmax(const float *__restrict__ g
                     }
                 }
             }
-        } else {                         // tile straddles tensors: per element
-            for (int k = 0; k < AM_UNROLL; ++k) {
-                int64_t j0 = i + (int64_t)k * CV_TILE;
-                for (int64_t j = j0; j < j0 + CV_VEC && j < t1; ++j) {
+        } else {                         // tile straddles tensors: one block reduction per tensor part
+            absmax_flush(m, anchor_u + cur_seg, red);
+            m = 0;
+            for (int sg = s_lo; sg <= s_hi; ++sg) {
+                const int64_t a0 = seg_off[sg] > t0 ? seg_off[sg] : t0;
+                const int64_t a1 = seg_off[sg + 1] < t1 ? seg_off[sg + 1] : t1;
+                uint32_t part = 0;
+                for (int64_t j = a0 + threadIdx.x; j < a1; j += CV_BLOCK) {
                     uint32_t a = __float_as_uint(gu[j]) & 0x7fffffffu;
-                    int cand = (int)(a >> 23) - 127;
-                    if (cand > 127) cand = 127;
-                    int sg = co3_find_seg(seg_off, nseg, j);
-                    if (cand > *reinterpret_cast<volatile int32_t *>(anchor_u + sg)) atomicMax(anchor_u + sg, cand);
+                    part = part > a ? part : a;
                 }
+                absmax_flush(part, anchor_u + sg, red);
             }
+            cur_seg = s_hi;
         }
     }
     absmax_flush(m, anchor_u + cur_seg, red);
@@ -145,11 +150,13 @@ __device__ __forceinline__ void co3_quantize(float x, int e_min, int A, int E, i
 template <bool HIST>
 __global__ __launch_bounds__(CV_BLOCK) void k_convert_ef(const float *__restrict__ g, float *__restrict__ err,
                                                           uint8_t *__restrict__ sym, int64_t n, int64_t stride,
-                                                          const int64_t *__restrict__ seg_off, int nseg,
+                                                          const int64_t *__restrict__ seg_off_g, int nseg,
                                                           const int32_t *__restrict__ anchor, float gamma, co3_fmt fmt,
                                                           uint32_t *__restrict__ counts, int64_t per_block)
 {
     const FmtC fc(fmt);
+    __shared__ int64_t seg_cache[CO3_SEG_CACHE];
+    const int64_t *seg_off = co3_cache_segs(seg_off_g, nseg, seg_cache);
     const int E = fc.E, M = fc.M, F = fc.F, K = fc.K, codemax = fc.codemax;
     // Users and ranges are taken in the reverse of the order in which the anchor pass read g, so that
     // the part of g that pass left in the last-level cache is read first.
@@ -220,10 +227,9 @@ __global__ __launch_bounds__(CV_BLOCK) void k_convert_ef(const float *__restrict
         if (s_lo == s_hi && i + CV_VEC <= t1) {
             const int A = anchor_u[s_lo];
             convert4(i, A, A - F + 1, ld_stream_f4(gu + i), ld_stream_f4(eu + i));
-        } else {                         // ragged tail, or a tile that straddles tensors
+        } else if (s_lo == s_hi) {       // ragged tail inside one tensor
+            const int A = anchor_u[s_lo];
             for (int64_t j = i; j < i + CV_VEC && j < t1; ++j) {
-                int s = (s_lo == s_hi) ? s_lo : co3_find_seg(seg_off, nseg, j);
-                const int A = anchor_u[s];
                 float x = gu[j] + gamma * eu[j];
                 uint32_t q;
                 float v;
@@ -231,6 +237,21 @@ __global__ __launch_bounds__(CV_BLOCK) void k_convert_ef(const float *__restrict
                 eu[j] = x - v;
                 su[j] = (uint8_t)q;
                 if (HIST) atomicAdd(&myhist[q * copies + mycopy], 1u);
+            }
+        } else {                         // a tile that straddles tensors: tensor part by tensor part
+            for (int sg = s_lo; sg <= s_hi; ++sg) {
+                const int64_t a0 = seg_off[sg] > t0 ? seg_off[sg] : t0;
+                const int64_t a1 = seg_off[sg + 1] < t1 ? seg_off[sg + 1] : t1;
+                const int A = anchor_u[sg];
+                for (int64_t j = a0 + threadIdx.x; j < a1; j += CV_BLOCK) {
+                    float x = gu[j] + gamma * eu[j];
+                    uint32_t q;
+                    float v;
+                    co3_quantize(x, A - F + 1, A, E, M, codemax, q, v);
+                    eu[j] = x - v;
+                    su[j] = (uint8_t)q;
+                    if (HIST) atomicAdd(&myhist[q * copies + mycopy], 1u);
+                }
             }
         }
         t0 += CV_TILE;

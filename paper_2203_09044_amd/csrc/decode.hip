@@ -336,14 +336,16 @@ template <bool TABLE>
 __global__ __launch_bounds__(PT_BLOCK) void k_ps_sum_tiled(const uint8_t *__restrict__ symt, int64_t n, int U,
                                                             int64_t ws_stride, int chunk_syms, int64_t nruns,
                                                             const int32_t *__restrict__ anchor,
-                                                            const int64_t *__restrict__ seg_off, int nseg, co3_fmt fmt,
-                                                            float *__restrict__ avg_out)
+                                                            const int64_t *__restrict__ seg_off_g, int nseg,
+                                                            co3_fmt fmt, float *__restrict__ avg_out)
 {
     const FmtC fc(fmt);
     const int EM = fc.E + fc.M, M = fc.M, F = fc.F;
     const uint32_t cmask = (uint32_t)fc.codemax;
     const float fU = (float)U;
     const int runs_per_chunk = chunk_syms >> 4;
+    __shared__ int64_t seg_cache[CO3_SEG_CACHE];
+    const int64_t *seg_off = co3_cache_segs(seg_off_g, nseg, seg_cache);
     extern __shared__ float value_of[];    // [U][K], TABLE only
     if (TABLE) {
         const int K = fc.K;
