@@ -108,9 +108,18 @@ __global__ __launch_bounds__(CV_BLOCK) void k_absmax(const float *__restrict__ g
                 const int64_t a0 = seg_off[sg] > t0 ? seg_off[sg] : t0;
                 const int64_t a1 = seg_off[sg + 1] < t1 ? seg_off[sg + 1] : t1;
                 uint32_t part = 0;
-                for (int64_t j = a0 + threadIdx.x; j < a1; j += CV_BLOCK) {
-                    uint32_t a = __float_as_uint(gu[j]) & 0x7fffffffu;
-                    part = part > a ? part : a;
+                for (int64_t j = a0 + threadIdx.x; j < a1; j += (int64_t)AM_UNROLL * CV_BLOCK) {
+                    float v[AM_UNROLL];      // independent loads, all in flight together
+#pragma unroll
+                    for (int k = 0; k < AM_UNROLL; ++k) {
+                        const int64_t jk = j + (int64_t)k * CV_BLOCK;
+                        v[k] = jk < a1 ? gu[jk] : 0.0f;
+                    }
+#pragma unroll
+                    for (int k = 0; k < AM_UNROLL; ++k) {
+                        uint32_t a = __float_as_uint(v[k]) & 0x7fffffffu;
+                        part = part > a ? part : a;
+                    }
                 }
                 absmax_flush(part, anchor_u + sg, red);
             }
@@ -321,10 +330,11 @@ __global__ __launch_bounds__(CV_BLOCK) void k_histogram(const uint8_t *__restric
 // ------------------------------------------------------------------------------------------
 // launchers
 // ------------------------------------------------------------------------------------------
-static int64_t per_block_for(int64_t n, int U, int64_t tile, int *blocks_out)
+static int64_t per_block_for(int64_t n, int U, int64_t tile, int *blocks_out, int K = 0)
 {
-    // about 8 blocks per compute unit in total, each a whole number of tiles
-    int64_t target_blocks = 2048 / (U > 0 ? U : 1);
+    // about 8 blocks per compute unit in total, each a whole number of tiles; half as many when every
+    // block ends by adding up to 256 counters into the same few cache lines
+    int64_t target_blocks = (K >= 128 ? 1024 : 2048) / (U > 0 ? U : 1);
     if (target_blocks < 1) target_blocks = 1;
     int64_t tiles = (n + tile - 1) / tile;
     int64_t tiles_per_block = (tiles + target_blocks - 1) / target_blocks;
@@ -363,7 +373,7 @@ hipError_t co3_launch_convert(const float *g, float *err, uint8_t *sym, int64_t 
 {
     if (n <= 0) return hipSuccess;
     int blocks;
-    int64_t pb = per_block_for(n, U, CV_TILE, &blocks);
+    int64_t pb = per_block_for(n, U, CV_TILE, &blocks, counts ? 1 << (1 + fmt.exp_bits + fmt.mant_bits) : 0);
     Co3LaunchTimer tm(CO3_K_CONVERT, st);
     if (counts)
         hipLaunchKernelGGL(k_convert_ef<true>, dim3(blocks, U), dim3(CV_BLOCK), 0, st, g, err, sym, n, stride, seg_off,
@@ -379,7 +389,7 @@ hipError_t co3_launch_histogram(const uint8_t *sym, int64_t n, int U, int64_t st
 {
     if (n <= 0) return hipSuccess;
     int blocks;
-    int64_t pb = per_block_for(n, U, HS_TILE, &blocks);
+    int64_t pb = per_block_for(n, U, HS_TILE, &blocks, K);
     Co3LaunchTimer tm(CO3_K_HISTOGRAM, st);
     hipLaunchKernelGGL(k_histogram, dim3(blocks, U), dim3(CV_BLOCK), 0, st, sym, n, stride, K, counts, pb);
     return hipGetLastError();
