@@ -62,6 +62,16 @@ def lib():
         L.co3o_encode.argtypes = [p, C.c_int64, p, p, C.c_int, C.c_int64, p, C.c_int64, p, p]
         L.co3o_decode.argtypes = [p, C.c_uint64, p, p, C.c_int, C.c_int64, p]
         L.co3o_aggregate.argtypes = [p, C.c_int64, C.c_int, C.c_int64, p, C.c_int, p, C.c_int, C.c_int, p]
+        L.co3o_moments.argtypes = [p, p, C.c_int64, p, C.c_int, C.c_float, p]
+        L.co3o_gennorm_ratio.restype = C.c_double
+        L.co3o_gennorm_ratio.argtypes = [C.c_double]
+        L.co3o_gennorm_fit.argtypes = [C.c_double, C.c_double, C.c_int64, p, p]
+        L.co3o_bias_poly.restype = C.c_double
+        L.co3o_bias_poly.argtypes = [C.c_double]
+        L.co3o_bias_scale.restype = C.c_float
+        L.co3o_bias_scale.argtypes = [C.c_double, C.c_double]
+        L.co3o_convert_ef_scaled.argtypes = [p, p, p, C.c_int64, p, C.c_int, p, p, C.c_float, C.c_int, C.c_int]
+        L.co3o_aggregate_scaled.argtypes = [p, C.c_int64, C.c_int, C.c_int64, p, C.c_int, p, p, C.c_int, C.c_int, p]
         _lib = L
     return _lib
 
@@ -134,17 +144,66 @@ def anchor(g: np.ndarray, fmt: Fmt, seg_off=None) -> np.ndarray:
     return out
 
 
-def convert_ef(g: np.ndarray, err: np.ndarray, anchors: np.ndarray, gamma: float, fmt: Fmt, seg_off=None):
-    """Returns (sym u8[n], new_err f32[n]); ``err`` is not modified."""
+def convert_ef(g: np.ndarray, err: np.ndarray, anchors: np.ndarray, gamma: float, fmt: Fmt, seg_off=None,
+               scale=None):
+    """Returns (sym u8[n], new_err f32[n]); ``err`` is not modified.  ``scale`` (f32 per tensor) selects the
+    multiplier form of the bias: the corrected gradient is multiplied by it before rounding onto the grid
+    of ``anchors`` and the level is divided by it afterwards."""
     g = np.ascontiguousarray(g, dtype=np.float32)
     e = np.array(err, dtype=np.float32, copy=True, order="C")
     so = _seg(seg_off, g.size)
     a = np.ascontiguousarray(anchors, dtype=np.int32)
     assert a.size == so.size - 1 and e.size == g.size
     sym = np.zeros(g.size, dtype=np.uint8)
-    _check(lib().co3o_convert_ef(_ptr(g), _ptr(e), _ptr(sym), g.size, _ptr(so), so.size - 1, _ptr(a),
-                                 C.c_float(gamma), fmt.E, fmt.M))
+    if scale is None:
+        _check(lib().co3o_convert_ef(_ptr(g), _ptr(e), _ptr(sym), g.size, _ptr(so), so.size - 1, _ptr(a),
+                                     C.c_float(gamma), fmt.E, fmt.M))
+    else:
+        c = np.ascontiguousarray(scale, dtype=np.float32)
+        assert c.size == so.size - 1
+        _check(lib().co3o_convert_ef_scaled(_ptr(g), _ptr(e), _ptr(sym), g.size, _ptr(so), so.size - 1, _ptr(a),
+                                            _ptr(c), C.c_float(gamma), fmt.E, fmt.M))
     return sym, e
+
+
+def moments(g: np.ndarray, err: np.ndarray, gamma: float, seg_off=None) -> np.ndarray:
+    """f64[nseg][2]: sum |x| and sum x^2 of x = g + gamma * err per tensor."""
+    g = np.ascontiguousarray(g, dtype=np.float32)
+    e = np.ascontiguousarray(err, dtype=np.float32)
+    so = _seg(seg_off, g.size)
+    out = np.zeros((so.size - 1, 2), dtype=np.float64)
+    _check(lib().co3o_moments(_ptr(g), _ptr(e), g.size, _ptr(so), so.size - 1, C.c_float(gamma), _ptr(out)))
+    return out
+
+
+def gennorm_ratio(beta: float) -> float:
+    return lib().co3o_gennorm_ratio(float(beta))
+
+
+def gennorm_fit(s1: float, s2: float, n: int):
+    """Moment-matching estimate (beta, alpha) from sum |x|, sum x^2 and the count."""
+    b, a = C.c_double(0), C.c_double(0)
+    _check(lib().co3o_gennorm_fit(float(s1), float(s2), int(n), C.byref(b), C.byref(a)))
+    return b.value, a.value
+
+
+def bias_poly(beta: float) -> float:
+    return lib().co3o_bias_poly(float(beta))
+
+
+def bias_scale(beta: float, alpha: float) -> np.float32:
+    return np.float32(lib().co3o_bias_scale(float(beta), float(alpha)))
+
+
+def bias_scales(g, err, gamma, seg_off=None) -> np.ndarray:
+    """The multiplier per tensor that the bias rule of Sec. V assigns to x = g + gamma * err."""
+    so = _seg(seg_off, np.asarray(g).size)
+    ms = moments(g, err, gamma, seg_off)
+    out = np.zeros(so.size - 1, dtype=np.float32)
+    for s in range(so.size - 1):
+        b, a = gennorm_fit(ms[s, 0], ms[s, 1], int(so[s + 1] - so[s]))
+        out[s] = bias_scale(b, a)
+    return out
 
 
 def histogram(sym: np.ndarray, fmt: Fmt) -> np.ndarray:
@@ -194,15 +253,21 @@ def decode(words: np.ndarray, total_bits: int, lengths: np.ndarray, codes: np.nd
     return out
 
 
-def aggregate(sym: np.ndarray, anchors: np.ndarray, fmt: Fmt, seg_off=None) -> np.ndarray:
-    """sym u8[U][n], anchors i32[U][nseg] -> mean f32[n] (users added in index order)."""
+def aggregate(sym: np.ndarray, anchors: np.ndarray, fmt: Fmt, seg_off=None, scale=None) -> np.ndarray:
+    """sym u8[U][n], anchors i32[U][nseg] (and multipliers f32[U][nseg]) -> mean f32[n], users added in
+    index order."""
     sym = np.ascontiguousarray(sym, dtype=np.uint8)
     assert sym.ndim == 2
     U, n = sym.shape
     so = _seg(seg_off, n)
     a = np.ascontiguousarray(anchors, dtype=np.int32).reshape(U, so.size - 1)
     out = np.zeros(n, dtype=np.float32)
-    _check(lib().co3o_aggregate(_ptr(sym), n, U, n, _ptr(so), so.size - 1, _ptr(a), fmt.E, fmt.M, _ptr(out)))
+    if scale is None:
+        _check(lib().co3o_aggregate(_ptr(sym), n, U, n, _ptr(so), so.size - 1, _ptr(a), fmt.E, fmt.M, _ptr(out)))
+    else:
+        c = np.ascontiguousarray(scale, dtype=np.float32).reshape(U, so.size - 1)
+        _check(lib().co3o_aggregate_scaled(_ptr(sym), n, U, n, _ptr(so), so.size - 1, _ptr(a), _ptr(c), fmt.E, fmt.M,
+                                           _ptr(out)))
     return out
 
 

@@ -440,3 +440,140 @@ int co3o_aggregate(const uint8_t *sym, int64_t n, int U, int64_t stride, const i
     (void)n;
     return CO3O_OK;
 }
+
+/* ---------------------------------------------------------------------- */
+/* Sec. V, "fp exponent bias": the bias of Sec. III (i) as a function of   */
+/* the GenNorm parameters of the tensor.  The bias is read as a real       */
+/* multiplier c applied to the corrected gradient before it is rounded     */
+/* onto a fixed grid (the printed approximation scales as 1/sigma, which   */
+/* only a multiplier does), and "sigma" as the GenNorm scale parameter     */
+/* alpha: under that reading the printed polynomial is the L2-optimal      */
+/* multiplier of a 4-bit grid to about one per cent (pinned by a test).    */
+/* ---------------------------------------------------------------------- */
+
+/* first absolute and second moment sums of x = g + gamma*m per tensor */
+int co3o_moments(const float *g, const float *err, int64_t n, const int64_t *seg_off, int nseg, float gamma,
+                 double *sums /* [nseg][2] */)
+{
+    if (nseg < 0 || (nseg > 0 && seg_off[nseg] > n))
+        return CO3O_EINVAL;
+    for (int s = 0; s < nseg; ++s) {
+        double s1 = 0.0, s2 = 0.0;
+        for (int64_t i = seg_off[s]; i < seg_off[s + 1]; ++i) {
+            volatile float decayed = gamma * err[i];
+            volatile float x = g[i] + decayed;
+            double xd = (double)x;
+            s1 += fabs(xd);
+            s2 += xd * xd;
+        }
+        sums[2 * s] = s1;
+        sums[2 * s + 1] = s2;
+    }
+    return CO3O_OK;
+}
+
+/* (E|X|)^2 / E[X^2] of GenNorm(beta): Gamma(2/b)^2 / (Gamma(1/b) Gamma(3/b)); rises from 0 to 3/4 */
+double co3o_gennorm_ratio(double beta)
+{
+    return exp(2.0 * lgamma(2.0 / beta) - lgamma(1.0 / beta) - lgamma(3.0 / beta));
+}
+
+#define CO3O_FIT_BETA_LO 0.05
+#define CO3O_FIT_BETA_HI 50.0
+
+/* Moment matching: the beta whose ratio equals s1^2 / (n s2), found by bisection, and the scale
+ * alpha that reproduces the second moment.  A tensor of zeros gives beta = 1, alpha = 0. */
+int co3o_gennorm_fit(double s1, double s2, int64_t n, double *beta, double *alpha)
+{
+    if (n <= 0 || !(s2 > 0.0)) {
+        *beta = 1.0;
+        *alpha = 0.0;
+        return CO3O_OK;
+    }
+    double rho = s1 * s1 / ((double)n * s2);
+    double lo = CO3O_FIT_BETA_LO, hi = CO3O_FIT_BETA_HI;
+    if (rho <= co3o_gennorm_ratio(lo)) {
+        hi = lo;
+    } else if (rho >= co3o_gennorm_ratio(hi)) {
+        lo = hi;
+    } else {
+        for (int it = 0; it < 200; ++it) {
+            double mid = 0.5 * (lo + hi);
+            if (co3o_gennorm_ratio(mid) < rho)
+                lo = mid;
+            else
+                hi = mid;
+        }
+    }
+    double b = 0.5 * (lo + hi);
+    *beta = b;
+    *alpha = sqrt(s2 / (double)n * exp(lgamma(1.0 / b) - lgamma(3.0 / b)));
+    return CO3O_OK;
+}
+
+/* the printed fourth-degree fit, beta clamped to the range over which the paper plots it */
+double co3o_bias_poly(double beta)
+{
+    double b = beta < 0.4 ? 0.4 : (beta > 1.6 ? 1.6 : beta);
+    return 0.46 - 2.85 * b + 5.37 * b * b - 2.85 * b * b * b + 0.52 * b * b * b * b;
+}
+
+/* multiplier c = poly(beta) / alpha as an fp32 number kept inside [2^-96, 2^96]; 1 for a zero tensor */
+float co3o_bias_scale(double beta, double alpha)
+{
+    if (!(alpha > 0.0))
+        return 1.0f;
+    double c = co3o_bias_poly(beta) / alpha;
+    const double lim = ldexp(1.0, 96);
+    if (!(c < lim))
+        c = lim;
+    if (!(c > 1.0 / lim))
+        c = 1.0 / lim;
+    return (float)c;
+}
+
+/* Algorithm 1 with the multiplier: x = g + gamma*m; y = c*x; ghat = Q_A(y) / c; m' = x - ghat.
+ * One fp32 rounding per stated operation.  scale is [nseg], anchor the fixed grid's anchor. */
+int co3o_convert_ef_scaled(const float *g, float *err, uint8_t *sym, int64_t n, const int64_t *seg_off, int nseg,
+                           const int32_t *anchor, const float *scale, float gamma, int E, int M)
+{
+    if (E < 1 || M < 0 || 1 + E + M > 8 || nseg < 0 || (nseg > 0 && seg_off[nseg] > n))
+        return CO3O_EINVAL;
+    for (int s = 0; s < nseg; ++s) {
+        int A = anchor[s];
+        float c = scale[s];
+        for (int64_t i = seg_off[s]; i < seg_off[s + 1]; ++i) {
+            volatile float decayed = gamma * err[i];
+            volatile float x = g[i] + decayed;
+            volatile float y = c * x;
+            int q = co3o_quantize_symbol(y, A, E, M);
+            volatile float ghat = co3o_symbol_value(q, A, E, M) / c;
+            volatile float e_new = x - ghat;
+            sym[i] = (uint8_t)q;
+            err[i] = e_new;
+        }
+    }
+    return CO3O_OK;
+}
+
+/* parameter server with multipliers: each user's level is divided by that user's c before the sum */
+int co3o_aggregate_scaled(const uint8_t *sym, int64_t n, int U, int64_t stride, const int64_t *seg_off, int nseg,
+                          const int32_t *anchor, const float *scale, int E, int M, float *avg)
+{
+    if (U < 1)
+        return CO3O_EINVAL;
+    for (int s = 0; s < nseg; ++s) {
+        for (int64_t i = seg_off[s]; i < seg_off[s + 1]; ++i) {
+            volatile float acc = 0.0f;
+            for (int u = 0; u < U; ++u) {
+                float v = co3o_symbol_value(sym[(int64_t)u * stride + i], anchor[(int64_t)u * nseg + s], E, M);
+                volatile float ghat = v / scale[(int64_t)u * nseg + s];
+                acc = acc + ghat;
+            }
+            volatile float mean = acc / (float)U;
+            avg[i] = mean;
+        }
+    }
+    (void)n;
+    return CO3O_OK;
+}
