@@ -108,6 +108,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="C3", help="C3 (default, the headline configuration), C1, C2, C4, C5.<point>")
     ap.add_argument("--chunk", type=int, default=256)
+    ap.add_argument("--bias", default="absmax", choices=("absmax", "moments"),
+                    help="absmax: integer anchor from max|g| (the headline configuration); moments: the paper's bias "
+                         "rule (moment sums, GenNorm fit, multiplier) on the fixed grid of anchor 2^(E-1)")
+    ap.add_argument("--format", default=None, help="override the workload's format, e.g. E1M2")
     ap.add_argument("--pool", type=int, default=3, help="distinct gradient batches cycled through")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--breakdown", action="store_true", help="extra untimed pass timing every kernel (stderr)")
@@ -131,8 +135,15 @@ def main():
     from paper_2203_09044_amd import Co3Pipeline, Fmt, binding as B
 
     w, betas, alpha, desc = make_workload(args.workload)
+    if args.format:
+        import dataclasses
+        w = dataclasses.replace(w, E=int(args.format[1]), M=int(args.format[3]))
+        desc += f", format overridden to {args.format}"
+    if args.bias == "moments":
+        desc += ", bias rule from moments"
     fmt = Fmt(w.E, w.M)
-    pipe = Co3Pipeline(w.U, w.n, fmt, chunk_syms=args.chunk, seg_off=w.seg_off if w.sizes is not None else None)
+    pipe = Co3Pipeline(w.U, w.n, fmt, chunk_syms=args.chunk, seg_off=w.seg_off if w.sizes is not None else None,
+                       bias=args.bias)
     log(f"[bench] {desc}; generating {args.pool} device batches")
     batches = device_batches(w, betas, alpha, args.pool, pipe)
 
@@ -203,7 +214,7 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": desc, "U": w.U, "n": w.n, "format": f"E{w.E}M{w.M}", "chunk_syms": args.chunk,
-                   "table": "empirical per client, rebuilt every step", "gamma": 1.0},
+                   "table": "empirical per client, rebuilt every step", "gamma": 1.0, "bias": args.bias},
         "bits_per_element": {"payload": payload_bpe, "index": index_bpe, "header": header_bpe},
         "path_roofline": {"bound": "hbm", "algorithmic_bytes_per_element": b_alg,
                           "achieved": b_alg * value / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -215,6 +226,8 @@ def main():
     }
     if not args.no_cpu:
         log("[bench] timing the CPU oracle on a bounded sample")
+        if args.bias != "absmax":
+            raise SystemExit("bench.py: the CPU leg times the headline path; use --no-cpu with --bias moments")
         res["cpu_baseline"] = cpu_baseline(w, betas, alpha, args.chunk, n_sample=min(w.n, 1 << 24), reps=4)
     print(json.dumps(res), flush=True)
 

@@ -113,6 +113,31 @@ int32_t co3_convert_ef(const float *g, float *err, uint8_t *sym, int64_t n, int3
                        co3_fmt fmt, uint32_t *counts, void *stream);
 
 /*
+ * The bias of Sec. III (i) in the form the approximation of Sec. V gives it: a real multiplier c per
+ * (user, tensor), c = (0.46 - 2.85 b + 5.37 b^2 - 2.85 b^3 + 0.52 b^4) / alpha with (b, alpha) the shape and
+ * scale of the GenNorm law fitted to the corrected gradient x = g + gamma*m, applied as
+ *     y = fl32(c * x);  sym = Q_A(y);  ghat = fl32(value_A(sym) / c);  err = fl32(x - ghat)
+ * on the fixed grid of the given anchor A (2^(E-1) is the IEEE-style choice; the 4-bit format of the
+ * paper is E = 1, M = 2, A = 1).  Three calls:
+ *
+ * co3_moments: sums[u][s] = (sum |x|, sum x^2) over tensor s of user u, accumulated in fp64 (the order of
+ *   the additions is unspecified: results agree with a sequential sum to about 1e-13 relative).
+ *     sums [U][nseg][2] f64 out, overwritten; g, err, seg_off, nseg, gamma as in co3_convert_ef
+ * co3_bias_scale: moment matching, (sum|x|)^2 / (count * sum x^2) = Gamma(2/b)^2 / (Gamma(1/b) Gamma(3/b))
+ *   solved for b in [0.05, 50], alpha from the second moment; b limited to [0.4, 1.6] (the range the paper
+ *   plots) inside the polynomial; c kept within [2^-96, 2^96]; a tensor of zeros gets c = 1.
+ *     scale [U][nseg] f32 out;  fit [U][nseg][2] f64 out, optional (NULL to skip): (b, alpha) before limiting
+ * co3_convert_ef_scaled: co3_convert_ef with anchor given (input) and the multipliers scale [U][nseg].
+ */
+int32_t co3_moments(const float *g, const float *err, int64_t n, int32_t U, int64_t stride, const int64_t *seg_off,
+                    int32_t nseg, float gamma, double *sums, void *stream);
+int32_t co3_bias_scale(const double *sums, int64_t n, int32_t U, const int64_t *seg_off, int32_t nseg, float *scale,
+                       double *fit, void *stream);
+int32_t co3_convert_ef_scaled(const float *g, float *err, uint8_t *sym, int64_t n, int32_t U, int64_t stride,
+                              const int64_t *seg_off, int32_t nseg, const int32_t *anchor, const float *scale,
+                              float gamma, co3_fmt fmt, uint32_t *counts, void *stream);
+
+/*
  * Empirical symbol counts per user (the stand-in for the symbol law that the Huffman
  * design of Sec. III (ii) needs): counts[u][k] = #{i < n : sym[u][i] = k}, overwritten.
  * Symbols >= K (cannot come from co3_convert_ef) are ignored.  n < 2^32.
@@ -175,6 +200,15 @@ int32_t co3_ps_aggregate(const uint64_t *words, int64_t cap_words, const uint64_
                          const int64_t *seg_off, int32_t nseg, float *avg_out, void *workspace, size_t ws_bytes,
                          int32_t *status, void *stream);
 
+/*
+ * co3_ps_aggregate for streams made with co3_convert_ef_scaled: v_u = fl32(value_{A_u}(symbol) / c_u) with
+ * the multipliers scale [U][nseg] of the users (Sec. III (i): the receiver undoes the bias).
+ */
+int32_t co3_ps_aggregate_scaled(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff,
+                                int32_t chunk_syms, const void *codes, co3_fmt fmt, int64_t n, int32_t U,
+                                const int32_t *anchor, const float *scale, const int64_t *seg_off, int32_t nseg,
+                                float *avg_out, void *workspace, size_t ws_bytes, int32_t *status, void *stream);
+
 /* ---- launch timing (diagnostic) ------------------------------------------ */
 
 /*
@@ -182,13 +216,14 @@ int32_t co3_ps_aggregate(const uint64_t *words, int64_t cap_words, const uint64_
  * that must report one kernel's average duration.  Process-global and not thread-safe: the
  * only state the library keeps, and only while enabled.  kernel ids: 0 k_fill_i32, 1 k_absmax,
  * 2 k_convert_ef, 3 k_histogram, 4 k_build_code, 5 k_enc_sizes, 6 k_enc_scan, 7 k_enc_pack,
- * 8 k_decode, 9 k_ps_sum (co3_kernel_name returns these names, "" for other ids).
+ * 8 k_decode, 9 k_ps_sum, 10 k_moments, 11 k_bias_scale (co3_kernel_name returns these names, ""
+ * for other ids).
  *   co3_timing_enable(mask): bracket every later launch of kernel k with events iff bit k is set.
  *   co3_timing_read(k, &ms, &count): waits for the recorded events, then returns the summed
  *       duration and launch count of kernel k since the last reset.
  *   co3_timing_reset(): waits likewise and clears all sums.
  */
-#define CO3_KERNEL_COUNT 10
+#define CO3_KERNEL_COUNT 12
 int32_t co3_timing_enable(uint32_t kernel_mask);
 int32_t co3_timing_read(int32_t kernel, double *total_ms, int64_t *launches);
 int32_t co3_timing_reset(void);

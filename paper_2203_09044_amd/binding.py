@@ -25,9 +25,9 @@ EXPORTS = (
     "co3_strerror", "co3_encode_workspace_bytes", "co3_ps_aggregate_workspace_bytes", "co3_cap_words_empirical",
     "co3_poll_status", "co3_convert_ef", "co3_histogram", "co3_build_code", "co3_encode", "co3_decode",
     "co3_ps_aggregate", "co3_model_weights", "co3_timing_enable", "co3_timing_read", "co3_timing_reset",
-    "co3_kernel_name",
+    "co3_kernel_name", "co3_moments", "co3_bias_scale", "co3_convert_ef_scaled", "co3_ps_aggregate_scaled",
 )
-KERNEL_COUNT = 10
+KERNEL_COUNT = 12
 
 
 class _Fmt(C.Structure):
@@ -75,6 +75,14 @@ def _load():
     L.co3_poll_status.argtypes = [p, p]
     L.co3_convert_ef.restype = i32
     L.co3_convert_ef.argtypes = [p, p, p, i64, i32, i64, p, i32, p, i32, C.c_float, _Fmt, p, p]
+    L.co3_convert_ef_scaled.restype = i32
+    L.co3_convert_ef_scaled.argtypes = [p, p, p, i64, i32, i64, p, i32, p, p, C.c_float, _Fmt, p, p]
+    L.co3_moments.restype = i32
+    L.co3_moments.argtypes = [p, p, i64, i32, i64, p, i32, C.c_float, p, p]
+    L.co3_bias_scale.restype = i32
+    L.co3_bias_scale.argtypes = [p, i64, i32, p, i32, p, p, p]
+    L.co3_ps_aggregate_scaled.restype = i32
+    L.co3_ps_aggregate_scaled.argtypes = [p, i64, p, i32, p, _Fmt, i64, i32, p, p, p, i32, p, p, sz, p, p]
     L.co3_histogram.restype = i32
     L.co3_histogram.argtypes = [p, i64, i32, i64, _Fmt, p, p]
     L.co3_build_code.restype = i32
@@ -160,6 +168,31 @@ def convert_ef(g, err, sym, n, anchor, anchor_mode, gamma, fmt: Fmt, seg_off=Non
     _chk(rc, "co3_convert_ef")
 
 
+def convert_ef_scaled(g, err, sym, n, anchor, scale, gamma, fmt: Fmt, seg_off=None, counts=None, stream=None):
+    U, stride = _batch(g)
+    nseg = 1 if seg_off is None else seg_off.numel() - 1
+    rc = _lib.co3_convert_ef_scaled(_dp(g, torch.float32), _dp(err, torch.float32), _dp(sym, torch.uint8), n, U,
+                                    stride, _dp(seg_off, torch.int64), nseg, _dp(anchor, torch.int32),
+                                    _dp(scale, torch.float32), C.c_float(gamma), fmt.c(), _dp(counts, torch.int32),
+                                    _stream(stream))
+    _chk(rc, "co3_convert_ef_scaled")
+
+
+def moments(g, err, n, gamma, sums, seg_off=None, stream=None):
+    U, stride = _batch(g)
+    nseg = 1 if seg_off is None else seg_off.numel() - 1
+    rc = _lib.co3_moments(_dp(g, torch.float32), _dp(err, torch.float32), n, U, stride, _dp(seg_off, torch.int64),
+                          nseg, C.c_float(gamma), _dp(sums, torch.float64), _stream(stream))
+    _chk(rc, "co3_moments")
+
+
+def bias_scale(sums, n, U, scale, fit=None, seg_off=None, stream=None):
+    nseg = 1 if seg_off is None else seg_off.numel() - 1
+    rc = _lib.co3_bias_scale(_dp(sums, torch.float64), n, U, _dp(seg_off, torch.int64), nseg,
+                             _dp(scale, torch.float32), _dp(fit, torch.float64), _stream(stream))
+    _chk(rc, "co3_bias_scale")
+
+
 def histogram(sym, n, fmt: Fmt, counts, stream=None):
     U, stride = _batch(sym)
     _chk(_lib.co3_histogram(_dp(sym, torch.uint8), n, U, stride, fmt.c(), _dp(counts, torch.int32), _stream(stream)),
@@ -225,3 +258,15 @@ def timing_reset():
 
 def kernel_name(kernel: int) -> str:
     return _lib.co3_kernel_name(kernel).decode()
+
+
+def ps_aggregate_scaled(words, chunk_bitoff, chunk_syms, codes, fmt: Fmt, n, U, anchor, scale, avg_out, workspace,
+                        status, seg_off=None, stream=None):
+    nseg = 1 if seg_off is None else seg_off.numel() - 1
+    rc = _lib.co3_ps_aggregate_scaled(_dp(words, torch.int64), words.shape[-1], _dp(chunk_bitoff, torch.int64),
+                                      chunk_syms, _dp(codes, torch.uint8), fmt.c(), n, U, _dp(anchor, torch.int32),
+                                      _dp(scale, torch.float32), _dp(seg_off, torch.int64), nseg,
+                                      _dp(avg_out, torch.float32), _dp(workspace),
+                                      workspace.numel() * workspace.element_size(), _dp(status, torch.int32),
+                                      _stream(stream))
+    _chk(rc, "co3_ps_aggregate_scaled")

@@ -111,7 +111,8 @@ int32_t co3_timing_reset(void)
 const char *co3_kernel_name(int32_t kernel)
 {
     static const char *names[CO3_K_COUNT] = {"k_fill_i32", "k_absmax",    "k_convert_ef", "k_histogram", "k_build_code",
-                                             "k_enc_sizes", "k_enc_scan", "k_enc_pack",   "k_decode",    "k_ps_sum"};
+                                             "k_enc_sizes", "k_enc_scan", "k_enc_pack",   "k_decode",    "k_ps_sum",
+                                             "k_moments",  "k_bias_scale"};
     return (kernel >= 0 && kernel < CO3_K_COUNT) ? names[kernel] : "";
 }
 
@@ -161,9 +162,9 @@ int32_t co3_poll_status(const int32_t *status_dev, void *stream)
     return h;
 }
 
-int32_t co3_convert_ef(const float *g, float *err, uint8_t *sym, int64_t n, int32_t U, int64_t stride,
-                       const int64_t *seg_off, int32_t nseg, int32_t *anchor, int32_t anchor_mode, float gamma,
-                       co3_fmt fmt, uint32_t *counts, void *stream)
+static int32_t convert_common(const float *g, float *err, uint8_t *sym, int64_t n, int32_t U, int64_t stride,
+                              const int64_t *seg_off, int32_t nseg, int32_t *anchor, int32_t anchor_mode,
+                              const float *scale, float gamma, co3_fmt fmt, uint32_t *counts, void *stream)
 {
     if (!fmt_ok(fmt) || !batch_ok(n, U, stride) || nseg < 1 || (seg_off == nullptr && nseg != 1)) return CO3_EINVAL;
     if (!g || !err || !sym || !anchor) return CO3_EINVAL;
@@ -179,7 +180,43 @@ int32_t co3_convert_ef(const float *g, float *err, uint8_t *sym, int64_t n, int3
         e = co3_launch_absmax(g, n, U, stride, seg_off, nseg, anchor, st);
         if (e != hipSuccess) return CO3_EHIP;
     }
-    return hip_rc(co3_launch_convert(g, err, sym, n, U, stride, seg_off, nseg, anchor, gamma, fmt, counts, st));
+    return hip_rc(co3_launch_convert(g, err, sym, n, U, stride, seg_off, nseg, anchor, scale, gamma, fmt, counts, st));
+}
+
+int32_t co3_convert_ef(const float *g, float *err, uint8_t *sym, int64_t n, int32_t U, int64_t stride,
+                       const int64_t *seg_off, int32_t nseg, int32_t *anchor, int32_t anchor_mode, float gamma,
+                       co3_fmt fmt, uint32_t *counts, void *stream)
+{
+    return convert_common(g, err, sym, n, U, stride, seg_off, nseg, anchor, anchor_mode, nullptr, gamma, fmt, counts,
+                          stream);
+}
+
+int32_t co3_convert_ef_scaled(const float *g, float *err, uint8_t *sym, int64_t n, int32_t U, int64_t stride,
+                              const int64_t *seg_off, int32_t nseg, const int32_t *anchor, const float *scale,
+                              float gamma, co3_fmt fmt, uint32_t *counts, void *stream)
+{
+    if (!scale) return CO3_EINVAL;
+    return convert_common(g, err, sym, n, U, stride, seg_off, nseg, const_cast<int32_t *>(anchor), CO3_ANCHOR_GIVEN,
+                          scale, gamma, fmt, counts, stream);
+}
+
+int32_t co3_moments(const float *g, const float *err, int64_t n, int32_t U, int64_t stride, const int64_t *seg_off,
+                    int32_t nseg, float gamma, double *sums, void *stream)
+{
+    if (!batch_ok(n, U, stride) || nseg < 1 || (seg_off == nullptr && nseg != 1)) return CO3_EINVAL;
+    if (!g || !err || !sums || !aligned(g, 16) || !aligned(err, 16) || !aligned(sums, 8)) return CO3_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // the sums start at +0.0: all-zero bits
+    hipError_t e = co3_launch_fill(reinterpret_cast<int32_t *>(sums), (int64_t)U * nseg * 4, 0, nullptr, 0, st);
+    if (e != hipSuccess) return CO3_EHIP;
+    return hip_rc(co3_launch_moments(g, err, n, U, stride, seg_off, nseg, gamma, sums, st));
+}
+
+int32_t co3_bias_scale(const double *sums, int64_t n, int32_t U, const int64_t *seg_off, int32_t nseg, float *scale,
+                       double *fit, void *stream)
+{
+    if (n < 0 || U < 1 || nseg < 1 || (seg_off == nullptr && nseg != 1) || !sums || !scale) return CO3_EINVAL;
+    return hip_rc(co3_launch_bias_scale(sums, n, U, seg_off, nseg, scale, fit, static_cast<hipStream_t>(stream)));
 }
 
 int32_t co3_histogram(const uint8_t *sym, int64_t n, int32_t U, int64_t stride, co3_fmt fmt, uint32_t *counts,
@@ -226,10 +263,10 @@ int32_t co3_decode(const uint64_t *words, int64_t cap_words, const uint64_t *chu
                                     static_cast<hipStream_t>(stream)));
 }
 
-int32_t co3_ps_aggregate(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff, int32_t chunk_syms,
-                         const void *codes, co3_fmt fmt, int64_t n, int32_t U, const int32_t *anchor,
-                         const int64_t *seg_off, int32_t nseg, float *avg_out, void *workspace, size_t ws_bytes,
-                         int32_t *status, void *stream)
+static int32_t aggregate_common(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff,
+                                int32_t chunk_syms, const void *codes, co3_fmt fmt, int64_t n, int32_t U,
+                                const int32_t *anchor, const float *scale, const int64_t *seg_off, int32_t nseg,
+                                float *avg_out, void *workspace, size_t ws_bytes, int32_t *status, void *stream)
 {
     if (!fmt_ok(fmt) || n < 0 || n >= ((int64_t)1 << 32) || U < 1 || !chunk_ok(chunk_syms) || cap_words < 0)
         return CO3_EINVAL;
@@ -246,7 +283,26 @@ int32_t co3_ps_aggregate(const uint64_t *words, int64_t cap_words, const uint64_
         co3_launch_decode(words, cap_words, chunk_bitoff, chunk_syms, codes, n, U, symws, ws_stride, 1, status, st);
     if (e != hipSuccess) return CO3_EHIP;
     return hip_rc(
-        co3_launch_ps_sum_tiled(symws, n, U, ws_stride, chunk_syms, anchor, seg_off, nseg, fmt, avg_out, st));
+        co3_launch_ps_sum_tiled(symws, n, U, ws_stride, chunk_syms, anchor, scale, seg_off, nseg, fmt, avg_out, st));
+}
+
+int32_t co3_ps_aggregate(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff, int32_t chunk_syms,
+                         const void *codes, co3_fmt fmt, int64_t n, int32_t U, const int32_t *anchor,
+                         const int64_t *seg_off, int32_t nseg, float *avg_out, void *workspace, size_t ws_bytes,
+                         int32_t *status, void *stream)
+{
+    return aggregate_common(words, cap_words, chunk_bitoff, chunk_syms, codes, fmt, n, U, anchor, nullptr, seg_off,
+                            nseg, avg_out, workspace, ws_bytes, status, stream);
+}
+
+int32_t co3_ps_aggregate_scaled(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff,
+                                int32_t chunk_syms, const void *codes, co3_fmt fmt, int64_t n, int32_t U,
+                                const int32_t *anchor, const float *scale, const int64_t *seg_off, int32_t nseg,
+                                float *avg_out, void *workspace, size_t ws_bytes, int32_t *status, void *stream)
+{
+    if (!scale) return CO3_EINVAL;
+    return aggregate_common(words, cap_words, chunk_bitoff, chunk_syms, codes, fmt, n, U, anchor, scale, seg_off, nseg,
+                            avg_out, workspace, ws_bytes, status, stream);
 }
 
 // ---- model table (host arithmetic only) ---------------------------------------------------

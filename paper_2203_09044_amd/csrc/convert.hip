@@ -156,11 +156,15 @@ __device__ __forceinline__ void co3_quantize(float x, int e_min, int A, int E, i
     val = __uint_as_float(__float_as_uint(mag) | (s << 31));
 }
 
-template <bool HIST>
+// SCALED: the bias in its multiplier form (Sec. III (i) with the approximation of Sec. V): the corrected
+// gradient is multiplied by c before it is rounded onto the grid of the given anchor, and the level
+// is divided by c again; one fp32 rounding per operation.
+template <bool HIST, bool SCALED>
 __global__ __launch_bounds__(CV_BLOCK) void k_convert_ef(const float *__restrict__ g, float *__restrict__ err,
                                                           uint8_t *__restrict__ sym, int64_t n, int64_t stride,
                                                           const int64_t *__restrict__ seg_off_g, int nseg,
-                                                          const int32_t *__restrict__ anchor, float gamma, co3_fmt fmt,
+                                                          const int32_t *__restrict__ anchor,
+                                                          const float *__restrict__ scale, float gamma, co3_fmt fmt,
                                                           uint32_t *__restrict__ counts, int64_t per_block)
 {
     const FmtC fc(fmt);
@@ -175,6 +179,7 @@ __global__ __launch_bounds__(CV_BLOCK) void k_convert_ef(const float *__restrict
     float *eu = err + (int64_t)u * stride;
     uint8_t *su = sym + (int64_t)u * stride;
     const int32_t *anchor_u = anchor + (int64_t)u * nseg;
+    const float *scale_u = SCALED ? scale + (int64_t)u * nseg : nullptr;
     const int lane = threadIdx.x & (CO3_WAVE - 1);
     const int wave = threadIdx.x / CO3_WAVE;
 
@@ -192,23 +197,41 @@ __global__ __launch_bounds__(CV_BLOCK) void k_convert_ef(const float *__restrict
     int64_t beg = range * per_block;
     int64_t end = beg + per_block < n ? beg + per_block : n;
 
-    // four elements of one thread: correct, convert, update the memory, count
-    auto convert4 = [&](int64_t i, int A, int e_min, float4 gv, float4 ev) {
-        float x0 = gv.x + gamma * ev.x, x1 = gv.y + gamma * ev.y;   // no contraction (build flag):
-        float x2 = gv.z + gamma * ev.z, x3 = gv.w + gamma * ev.w;   // one rounding per operation
+    // one element: correct, convert, new memory.  No contraction (build flag): one rounding per operation.
+    auto convert1 = [&](float gv, float ev, int A, int e_min, float c, uint32_t &q) -> float {
+        const float x = gv + gamma * ev;
+        float v;
+        co3_quantize(SCALED ? c * x : x, e_min, A, E, M, codemax, q, v);
+        if (SCALED) v = v / c;
+        return x - v;
+    };
+    // four elements of one thread, the symbols counted
+    auto convert4 = [&](int64_t i, int A, float c, float4 gv, float4 ev) {
+        const int e_min = A - F + 1;
         uint32_t q0, q1, q2, q3;
-        float v0, v1, v2, v3;
-        co3_quantize(x0, e_min, A, E, M, codemax, q0, v0);
-        co3_quantize(x1, e_min, A, E, M, codemax, q1, v1);
-        co3_quantize(x2, e_min, A, E, M, codemax, q2, v2);
-        co3_quantize(x3, e_min, A, E, M, codemax, q3, v3);
-        st_stream_f4(eu + i, make_float4(x0 - v0, x1 - v1, x2 - v2, x3 - v3));
+        float4 en;
+        en.x = convert1(gv.x, ev.x, A, e_min, c, q0);
+        en.y = convert1(gv.y, ev.y, A, e_min, c, q1);
+        en.z = convert1(gv.z, ev.z, A, e_min, c, q2);
+        en.w = convert1(gv.w, ev.w, A, e_min, c, q3);
+        st_stream_f4(eu + i, en);
         *reinterpret_cast<uint32_t *>(su + i) = q0 | (q1 << 8) | (q2 << 16) | (q3 << 24);
         if (HIST) {
             atomicAdd(&myhist[q0 * copies + mycopy], 1u);
             atomicAdd(&myhist[q1 * copies + mycopy], 1u);
             atomicAdd(&myhist[q2 * copies + mycopy], 1u);
             atomicAdd(&myhist[q3 * copies + mycopy], 1u);
+        }
+    };
+    // elements [a0, a1) of one tensor, one per thread and step
+    auto convert_part = [&](int64_t a0, int64_t a1, int64_t step, int sg) {
+        const int A = anchor_u[sg];
+        const float c = SCALED ? scale_u[sg] : 1.0f;
+        for (int64_t j = a0; j < a1; j += step) {
+            uint32_t q;
+            eu[j] = convert1(gu[j], eu[j], A, A - F + 1, c, q);
+            su[j] = (uint8_t)q;
+            if (HIST) atomicAdd(&myhist[q * copies + mycopy], 1u);
         }
     };
 
@@ -219,12 +242,12 @@ __global__ __launch_bounds__(CV_BLOCK) void k_convert_ef(const float *__restrict
             int s_b = co3_find_seg(seg_off, nseg, t0 + 2 * CV_TILE - 1);
             if (s_a == s_b) {
                 const int A = anchor_u[s_a];
-                const int e_min = A - F + 1;
+                const float c = SCALED ? scale_u[s_a] : 1.0f;
                 const int64_t i0 = t0 + (int64_t)threadIdx.x * CV_VEC, i1 = i0 + CV_TILE;
                 float4 g0 = ld_stream_f4(gu + i0), e0 = ld_stream_f4(eu + i0);
                 float4 g1 = ld_stream_f4(gu + i1), e1 = ld_stream_f4(eu + i1);
-                convert4(i0, A, e_min, g0, e0);
-                convert4(i1, A, e_min, g1, e1);
+                convert4(i0, A, c, g0, e0);
+                convert4(i1, A, c, g1, e1);
                 t0 += 2 * CV_TILE;
                 continue;
             }
@@ -234,33 +257,14 @@ __global__ __launch_bounds__(CV_BLOCK) void k_convert_ef(const float *__restrict
         int s_hi = co3_find_seg(seg_off, nseg, t1 - 1);
         int64_t i = t0 + (int64_t)threadIdx.x * CV_VEC;
         if (s_lo == s_hi && i + CV_VEC <= t1) {
-            const int A = anchor_u[s_lo];
-            convert4(i, A, A - F + 1, ld_stream_f4(gu + i), ld_stream_f4(eu + i));
+            convert4(i, anchor_u[s_lo], SCALED ? scale_u[s_lo] : 1.0f, ld_stream_f4(gu + i), ld_stream_f4(eu + i));
         } else if (s_lo == s_hi) {       // ragged tail inside one tensor
-            const int A = anchor_u[s_lo];
-            for (int64_t j = i; j < i + CV_VEC && j < t1; ++j) {
-                float x = gu[j] + gamma * eu[j];
-                uint32_t q;
-                float v;
-                co3_quantize(x, A - F + 1, A, E, M, codemax, q, v);
-                eu[j] = x - v;
-                su[j] = (uint8_t)q;
-                if (HIST) atomicAdd(&myhist[q * copies + mycopy], 1u);
-            }
+            convert_part(i, (i + CV_VEC < t1 ? i + CV_VEC : t1), 1, s_lo);
         } else {                         // a tile that straddles tensors: tensor part by tensor part
             for (int sg = s_lo; sg <= s_hi; ++sg) {
                 const int64_t a0 = seg_off[sg] > t0 ? seg_off[sg] : t0;
                 const int64_t a1 = seg_off[sg + 1] < t1 ? seg_off[sg + 1] : t1;
-                const int A = anchor_u[sg];
-                for (int64_t j = a0 + threadIdx.x; j < a1; j += CV_BLOCK) {
-                    float x = gu[j] + gamma * eu[j];
-                    uint32_t q;
-                    float v;
-                    co3_quantize(x, A - F + 1, A, E, M, codemax, q, v);
-                    eu[j] = x - v;
-                    su[j] = (uint8_t)q;
-                    if (HIST) atomicAdd(&myhist[q * copies + mycopy], 1u);
-                }
+                convert_part(a0 + threadIdx.x, a1, CV_BLOCK, sg);
             }
         }
         t0 += CV_TILE;
@@ -368,19 +372,22 @@ hipError_t co3_launch_absmax(const float *g, int64_t n, int U, int64_t stride, c
 }
 
 hipError_t co3_launch_convert(const float *g, float *err, uint8_t *sym, int64_t n, int U, int64_t stride,
-                              const int64_t *seg_off, int nseg, const int32_t *anchor, float gamma, co3_fmt fmt,
-                              uint32_t *counts, hipStream_t st)
+                              const int64_t *seg_off, int nseg, const int32_t *anchor, const float *scale, float gamma,
+                              co3_fmt fmt, uint32_t *counts, hipStream_t st)
 {
     if (n <= 0) return hipSuccess;
     int blocks;
     int64_t pb = per_block_for(n, U, CV_TILE, &blocks, counts ? 1 << (1 + fmt.exp_bits + fmt.mant_bits) : 0);
     Co3LaunchTimer tm(CO3_K_CONVERT, st);
-    if (counts)
-        hipLaunchKernelGGL(k_convert_ef<true>, dim3(blocks, U), dim3(CV_BLOCK), 0, st, g, err, sym, n, stride, seg_off,
-                           nseg, anchor, gamma, fmt, counts, pb);
-    else
-        hipLaunchKernelGGL(k_convert_ef<false>, dim3(blocks, U), dim3(CV_BLOCK), 0, st, g, err, sym, n, stride,
-                           seg_off, nseg, anchor, gamma, fmt, counts, pb);
+    const dim3 grid(blocks, U), block(CV_BLOCK);
+#define CO3_CONVERT_LAUNCH(H, S)                                                                                     \
+    hipLaunchKernelGGL((k_convert_ef<H, S>), grid, block, 0, st, g, err, sym, n, stride, seg_off, nseg, anchor, scale, \
+                       gamma, fmt, counts, pb)
+    if (counts && scale) CO3_CONVERT_LAUNCH(true, true);
+    else if (counts) CO3_CONVERT_LAUNCH(true, false);
+    else if (scale) CO3_CONVERT_LAUNCH(false, true);
+    else CO3_CONVERT_LAUNCH(false, false);
+#undef CO3_CONVERT_LAUNCH
     return hipGetLastError();
 }
 

@@ -279,54 +279,6 @@ __global__ __launch_bounds__(DE_BLOCK) void k_decode(const uint64_t *__restrict_
 }
 
 // ---- average of the reconstructed gradients: users added in index order, one division -----
-#define PS_BLOCK 256
-#define PS_VEC 4
-#define PS_TILE (PS_BLOCK * PS_VEC)
-
-__global__ __launch_bounds__(PS_BLOCK) void k_ps_sum(const uint8_t *__restrict__ sym, int64_t n, int U, int64_t stride,
-                                                      const int32_t *__restrict__ anchor,
-                                                      const int64_t *__restrict__ seg_off, int nseg, co3_fmt fmt,
-                                                      float *__restrict__ avg_out)
-{
-    const FmtC fc(fmt);
-    const int EM = fc.E + fc.M, M = fc.M, F = fc.F;
-    const uint32_t cmask = (uint32_t)fc.codemax;
-    const float fU = (float)U;
-    for (int64_t t0 = (int64_t)blockIdx.x * PS_TILE; t0 < n; t0 += (int64_t)gridDim.x * PS_TILE) {
-        int64_t t1 = t0 + PS_TILE < n ? t0 + PS_TILE : n;
-        int s_lo = co3_find_seg(seg_off, nseg, t0);
-        int s_hi = co3_find_seg(seg_off, nseg, t1 - 1);
-        int64_t i = t0 + (int64_t)threadIdx.x * PS_VEC;
-        if (s_lo == s_hi && i + PS_VEC <= t1) {
-            float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-            for (int u = 0; u < U; ++u) {
-                const int e_min = anchor[(int64_t)u * nseg + s_lo] - F + 1;
-                uint32_t q = *reinterpret_cast<const uint32_t *>(sym + (int64_t)u * stride + i);
-                uint32_t q0 = q & 0xffu, q1 = (q >> 8) & 0xffu, q2 = (q >> 16) & 0xffu, q3 = q >> 24;
-                float v0 = co3_code_value(q0 & cmask, e_min, M), v1 = co3_code_value(q1 & cmask, e_min, M);
-                float v2 = co3_code_value(q2 & cmask, e_min, M), v3 = co3_code_value(q3 & cmask, e_min, M);
-                a0 += __uint_as_float(__float_as_uint(v0) | ((q0 >> EM) << 31));
-                a1 += __uint_as_float(__float_as_uint(v1) | ((q1 >> EM) << 31));
-                a2 += __uint_as_float(__float_as_uint(v2) | ((q2 >> EM) << 31));
-                a3 += __uint_as_float(__float_as_uint(v3) | ((q3 >> EM) << 31));
-            }
-            *reinterpret_cast<float4 *>(avg_out + i) = make_float4(a0 / fU, a1 / fU, a2 / fU, a3 / fU);
-        } else {
-            for (int64_t j = i; j < i + PS_VEC && j < t1; ++j) {
-                int s = (s_lo == s_hi) ? s_lo : co3_find_seg(seg_off, nseg, j);
-                float a = 0.f;
-                for (int u = 0; u < U; ++u) {
-                    const int e_min = anchor[(int64_t)u * nseg + s] - F + 1;
-                    uint32_t q = sym[(int64_t)u * stride + j];
-                    float v = co3_code_value(q & cmask, e_min, M);
-                    a += __uint_as_float(__float_as_uint(v) | ((q >> EM) << 31));
-                }
-                avg_out[j] = a / fU;
-            }
-        }
-    }
-}
-
 // Average from the tiled workspace: one thread owns a run of 16 consecutive elements.
 #define PT_BLOCK 256
 
@@ -336,6 +288,7 @@ template <bool TABLE>
 __global__ __launch_bounds__(PT_BLOCK) void k_ps_sum_tiled(const uint8_t *__restrict__ symt, int64_t n, int U,
                                                             int64_t ws_stride, int chunk_syms, int64_t nruns,
                                                             const int32_t *__restrict__ anchor,
+                                                            const float *__restrict__ scale,
                                                             const int64_t *__restrict__ seg_off_g, int nseg,
                                                             co3_fmt fmt, float *__restrict__ avg_out)
 {
@@ -344,6 +297,14 @@ __global__ __launch_bounds__(PT_BLOCK) void k_ps_sum_tiled(const uint8_t *__rest
     const uint32_t cmask = (uint32_t)fc.codemax;
     const float fU = (float)U;
     const int runs_per_chunk = chunk_syms >> 4;
+    // value of symbol s of user u in tensor sg; with multipliers (scale != NULL) the level is divided by
+    // the user's multiplier, one fp32 rounding
+    auto value = [&](uint32_t s, int u, int sg) -> float {
+        const int e_min = anchor[(int64_t)u * nseg + sg] - F + 1;
+        float v = __uint_as_float(__float_as_uint(co3_code_value(s & cmask, e_min, M)) | ((s >> EM) << 31));
+        if (scale) v = v / scale[(int64_t)u * nseg + sg];
+        return v;
+    };
     __shared__ int64_t seg_cache[CO3_SEG_CACHE];
     const int64_t *seg_off = co3_cache_segs(seg_off_g, nseg, seg_cache);
     extern __shared__ float value_of[];    // [U][K], TABLE only
@@ -351,10 +312,7 @@ __global__ __launch_bounds__(PT_BLOCK) void k_ps_sum_tiled(const uint8_t *__rest
         const int K = fc.K;
         for (int j = threadIdx.x; j < U * K; j += PT_BLOCK) {
             const int u = j / K;
-            const uint32_t s = (uint32_t)(j - u * K);
-            const int e_min = anchor[u] - F + 1;
-            float val = co3_code_value(s & cmask, e_min, M);
-            value_of[j] = __uint_as_float(__float_as_uint(val) | ((s >> EM) << 31));
+            value_of[j] = value((uint32_t)(j - u * K), u, 0);
         }
         __syncthreads();
     }
@@ -385,13 +343,15 @@ __global__ __launch_bounds__(PT_BLOCK) void k_ps_sum_tiled(const uint8_t *__rest
         } else if (s_lo == s_hi) {
             for (int u = 0; u < U; ++u) {
                 const int e_min = anchor[(int64_t)u * nseg + s_lo] - F + 1;
+                const float c = scale ? scale[(int64_t)u * nseg + s_lo] : 1.0f;
                 uint4 v = *reinterpret_cast<const uint4 *>(src + (int64_t)u * ws_stride);
                 uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
                 for (int k = 0; k < 16; ++k) {
                     uint32_t s = (w[k >> 2] >> (8 * (k & 3))) & 0xffu;
                     float val = co3_code_value(s & cmask, e_min, M);
-                    acc[k] += __uint_as_float(__float_as_uint(val) | ((s >> EM) << 31));
+                    val = __uint_as_float(__float_as_uint(val) | ((s >> EM) << 31));
+                    acc[k] += scale ? val / c : val;
                 }
             }
         } else {                           // the run straddles tensors: anchor per element
@@ -401,10 +361,7 @@ __global__ __launch_bounds__(PT_BLOCK) void k_ps_sum_tiled(const uint8_t *__rest
 #pragma unroll
                 for (int k = 0; k < 16; ++k) {
                     int sg = co3_find_seg(seg_off, nseg, i0 + k < n ? i0 + k : n - 1);
-                    const int e_min = anchor[(int64_t)u * nseg + sg] - F + 1;
-                    uint32_t s = (w[k >> 2] >> (8 * (k & 3))) & 0xffu;
-                    float val = co3_code_value(s & cmask, e_min, M);
-                    acc[k] += __uint_as_float(__float_as_uint(val) | ((s >> EM) << 31));
+                    acc[k] += value((w[k >> 2] >> (8 * (k & 3))) & 0xffu, u, sg);
                 }
             }
         }
@@ -438,21 +395,9 @@ hipError_t co3_launch_decode(const uint64_t *words, int64_t cap_words, const uin
     return hipGetLastError();
 }
 
-hipError_t co3_launch_ps_sum(const uint8_t *sym, int64_t n, int U, int64_t stride, const int32_t *anchor,
-                             const int64_t *seg_off, int nseg, co3_fmt fmt, float *avg_out, hipStream_t st)
-{
-    if (n <= 0) return hipSuccess;
-    int64_t tiles = (n + PS_TILE - 1) / PS_TILE;
-    unsigned blocks = (unsigned)(tiles < 4096 ? tiles : 4096);
-    Co3LaunchTimer tm(CO3_K_PS_SUM, st);
-    hipLaunchKernelGGL(k_ps_sum, dim3(blocks), dim3(PS_BLOCK), 0, st, sym, n, U, stride, anchor, seg_off, nseg, fmt,
-                       avg_out);
-    return hipGetLastError();
-}
-
 hipError_t co3_launch_ps_sum_tiled(const uint8_t *symt, int64_t n, int U, int64_t ws_stride, int chunk_syms,
-                                   const int32_t *anchor, const int64_t *seg_off, int nseg, co3_fmt fmt,
-                                   float *avg_out, hipStream_t st)
+                                   const int32_t *anchor, const float *scale, const int64_t *seg_off, int nseg,
+                                   co3_fmt fmt, float *avg_out, hipStream_t st)
 {
     if (n <= 0) return hipSuccess;
     const int64_t nchunks = (n + chunk_syms - 1) / chunk_syms;
@@ -464,9 +409,9 @@ hipError_t co3_launch_ps_sum_tiled(const uint8_t *symt, int64_t n, int U, int64_
     const size_t table_bytes = (size_t)U * (size_t)(1 << (1 + fmt.exp_bits + fmt.mant_bits)) * sizeof(float);
     if (nseg == 1 && table_bytes <= 32768)
         hipLaunchKernelGGL(k_ps_sum_tiled<true>, dim3(blocks), dim3(PT_BLOCK), table_bytes, st, symt, n, U, ws_stride,
-                           chunk_syms, nruns, anchor, seg_off, nseg, fmt, avg_out);
+                           chunk_syms, nruns, anchor, scale, seg_off, nseg, fmt, avg_out);
     else
         hipLaunchKernelGGL(k_ps_sum_tiled<false>, dim3(blocks), dim3(PT_BLOCK), 0, st, symt, n, U, ws_stride,
-                           chunk_syms, nruns, anchor, seg_off, nseg, fmt, avg_out);
+                           chunk_syms, nruns, anchor, scale, seg_off, nseg, fmt, avg_out);
     return hipGetLastError();
 }

@@ -8,7 +8,7 @@
 // Kernel ids for the optional launch timing (co3_timing_* in the public header).
 enum Co3Kernel {
     CO3_K_FILL = 0, CO3_K_ABSMAX, CO3_K_CONVERT, CO3_K_HISTOGRAM, CO3_K_BUILD, CO3_K_ENC_SIZES, CO3_K_ENC_SCAN,
-    CO3_K_ENC_PACK, CO3_K_DECODE, CO3_K_PS_SUM, CO3_K_COUNT
+    CO3_K_ENC_PACK, CO3_K_DECODE, CO3_K_PS_SUM, CO3_K_MOMENTS, CO3_K_BIAS_SCALE, CO3_K_COUNT
 };
 
 // Brackets one kernel launch with a pair of HIP events on the launch stream when timing of that
@@ -24,8 +24,8 @@ hipError_t co3_launch_fill(int32_t *a, int64_t na, int32_t va, uint32_t *b, int6
 hipError_t co3_launch_absmax(const float *g, int64_t n, int U, int64_t stride, const int64_t *seg_off, int nseg,
                              int32_t *anchor, hipStream_t st);
 hipError_t co3_launch_convert(const float *g, float *err, uint8_t *sym, int64_t n, int U, int64_t stride,
-                              const int64_t *seg_off, int nseg, const int32_t *anchor, float gamma, co3_fmt fmt,
-                              uint32_t *counts, hipStream_t st);
+                              const int64_t *seg_off, int nseg, const int32_t *anchor, const float *scale, float gamma,
+                              co3_fmt fmt, uint32_t *counts, hipStream_t st);
 hipError_t co3_launch_histogram(const uint8_t *sym, int64_t n, int U, int64_t stride, int K, uint32_t *counts,
                                 hipStream_t st);
 hipError_t co3_launch_build_code(const uint32_t *weights, int U, int K, void *codes, int32_t *status, hipStream_t st);
@@ -36,7 +36,9 @@ hipError_t co3_launch_decode(const uint64_t *words, int64_t cap_words, const uin
                              const void *codes, int64_t n, int U, uint8_t *sym_out, int64_t stride, int tiled,
                              int32_t *status, hipStream_t st);
 hipError_t co3_launch_ps_sum_tiled(const uint8_t *symt, int64_t n, int U, int64_t ws_stride, int chunk_syms,
-                                   const int32_t *anchor, const int64_t *seg_off, int nseg, co3_fmt fmt,
-                                   float *avg_out, hipStream_t st);
-hipError_t co3_launch_ps_sum(const uint8_t *sym, int64_t n, int U, int64_t stride, const int32_t *anchor,
-                             const int64_t *seg_off, int nseg, co3_fmt fmt, float *avg_out, hipStream_t st);
+                                   const int32_t *anchor, const float *scale, const int64_t *seg_off, int nseg,
+                                   co3_fmt fmt, float *avg_out, hipStream_t st);
+hipError_t co3_launch_moments(const float *g, const float *err, int64_t n, int U, int64_t stride,
+                              const int64_t *seg_off, int nseg, float gamma, double *sums, hipStream_t st);
+hipError_t co3_launch_bias_scale(const double *sums, int64_t n, int U, const int64_t *seg_off, int nseg, float *scale,
+                                 double *fit, hipStream_t st);

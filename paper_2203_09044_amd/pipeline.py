@@ -2,7 +2,9 @@
 
 Plumbing only: allocation through torch, then the six library calls in the order of
 Algorithm 1 (user side: convert_ef [+ fused histogram] -> build_code -> encode; server
-side: ps_aggregate, or decode for the round-trip check).
+side: ps_aggregate, or decode for the round-trip check).  With ``bias="moments"`` the grid is
+fixed (anchor ``grid_anchor``) and the paper's bias rule supplies a multiplier per (user,
+tensor): moments -> bias_scale -> convert_ef_scaled ... ps_aggregate_scaled.
 """
 from __future__ import annotations
 
@@ -20,9 +22,13 @@ def _round_up(x: int, m: int) -> int:
 
 class Co3Pipeline:
     def __init__(self, U: int, n: int, fmt: Fmt, chunk_syms: int = 256, seg_off=None, gamma: float = 1.0,
-                 cap_words: Optional[int] = None, device="cuda:0", fused_histogram: bool = True):
+                 cap_words: Optional[int] = None, device="cuda:0", fused_histogram: bool = True,
+                 bias: str = "absmax", grid_anchor: Optional[int] = None):
+        if bias not in ("absmax", "moments"):
+            raise ValueError("bias must be 'absmax' or 'moments'")
         self.U, self.n, self.fmt, self.chunk_syms, self.gamma = U, n, fmt, chunk_syms, gamma
         self.fused_histogram = fused_histogram
+        self.bias = bias
         dev = torch.device(device)
         self.device = dev
         self.stride = _round_up(max(n, 1), 16)
@@ -44,14 +50,28 @@ class Co3Pipeline:
         self.avg = torch.zeros((self.stride,), dtype=torch.float32, **z)
         self.sym_dec = torch.zeros((U, self.stride), dtype=torch.uint8, **z)
         self.status = torch.zeros((1,), dtype=torch.int32, **z)
+        if bias == "moments":
+            self.anchor.fill_((1 << (fmt.E - 1)) if grid_anchor is None else grid_anchor)
+            self.sums = torch.zeros((U, self.nseg, 2), dtype=torch.float64, **z)
+            self.fit = torch.zeros((U, self.nseg, 2), dtype=torch.float64, **z)
+            self.scale = torch.ones((U, self.nseg), dtype=torch.float32, **z)
 
     def new_gradient_buffer(self) -> torch.Tensor:
         return torch.zeros((self.U, self.stride), dtype=torch.float32, device=self.device)
 
     # ---- user side
+    def fit_bias(self, g: torch.Tensor):
+        B.moments(g, self.err, self.n, self.gamma, self.sums, seg_off=self.seg_off)
+        B.bias_scale(self.sums, self.n, self.U, self.scale, fit=self.fit, seg_off=self.seg_off)
+
     def convert(self, g: torch.Tensor, anchor_mode=B.ANCHOR_FROM_ABSMAX_G):
-        B.convert_ef(g, self.err, self.sym, self.n, self.anchor, anchor_mode, self.gamma, self.fmt,
-                     seg_off=self.seg_off, counts=self.counts if self.fused_histogram else None)
+        counts = self.counts if self.fused_histogram else None
+        if self.bias == "moments":
+            B.convert_ef_scaled(g, self.err, self.sym, self.n, self.anchor, self.scale, self.gamma, self.fmt,
+                                seg_off=self.seg_off, counts=counts)
+        else:
+            B.convert_ef(g, self.err, self.sym, self.n, self.anchor, anchor_mode, self.gamma, self.fmt,
+                         seg_off=self.seg_off, counts=counts)
         if not self.fused_histogram:
             B.histogram(self.sym, self.n, self.fmt, self.counts)
 
@@ -68,11 +88,18 @@ class Co3Pipeline:
                  self.status)
 
     def aggregate(self):
-        B.ps_aggregate(self.words, self.chunk_bitoff, self.chunk_syms, self.codes, self.fmt, self.n, self.U,
-                       self.anchor, self.avg, self.agg_ws, self.status, seg_off=self.seg_off)
+        if self.bias == "moments":
+            B.ps_aggregate_scaled(self.words, self.chunk_bitoff, self.chunk_syms, self.codes, self.fmt, self.n,
+                                  self.U, self.anchor, self.scale, self.avg, self.agg_ws, self.status,
+                                  seg_off=self.seg_off)
+        else:
+            B.ps_aggregate(self.words, self.chunk_bitoff, self.chunk_syms, self.codes, self.fmt, self.n, self.U,
+                           self.anchor, self.avg, self.agg_ws, self.status, seg_off=self.seg_off)
 
     def step(self, g: torch.Tensor, weights: Optional[torch.Tensor] = None):
         """One whole iteration: users encode, the server decodes and averages."""
+        if self.bias == "moments":
+            self.fit_bias(g)
         self.convert(g)
         self.build(weights)
         self.encode()

@@ -154,6 +154,55 @@ def test_c3_full(co3):
     properties_all_clients(pipe, w.n)
 
 
+def test_c3_bias_rule_full(co3):
+    """The C3 shape (10 clients x 11,173,962) on the paper's 4-bit format E1M2 with the bias rule: moment
+    sums and multipliers against the oracle (1e-12 relative / 2 units in the last place), then one whole
+    iteration with the oracle's multipliers installed on both sides, every element of every client bit for
+    bit, and the average."""
+    w = inp.c3()
+    fmt = co3.Fmt(1, 2)
+    f = oracle.Fmt(1, 2)
+    betas = inp.c3_client_betas(w.U)
+    pipe = co3.Co3Pipeline(w.U, w.n, fmt, chunk_syms=256, bias="moments")
+    g = pipe.new_gradient_buffer()
+    host = fill_from_device(pipe, g, lambda u: inp.device_gennorm(w.n, float(betas[u]), 1e-3, 3500 + u))
+    errs = [inp.gennorm(inp.rng_for(35, u), w.n, 1.0, 1e-4) for u in range(w.U)]
+    for u in range(w.U):
+        pipe.err[u, :w.n] = torch.from_numpy(errs[u]).cuda()
+    pipe.fit_bias(g)
+    with ThreadPoolExecutor(max_workers=10) as pool:
+        sums_o = np.stack(list(pool.map(lambda u: oracle.moments(host[u], errs[u], 1.0), range(w.U))))
+        assert np.allclose(pipe.sums.cpu().numpy(), sums_o, rtol=1e-12, atol=0.0)
+        scale_o = np.zeros((w.U, 1), np.float32)
+        for u in range(w.U):
+            b, a = oracle.gennorm_fit(sums_o[u, 0, 0], sums_o[u, 0, 1], w.n)
+            scale_o[u, 0] = oracle.bias_scale(b, a)
+            assert abs(b - betas[u]) < 0.35          # the memory term is Laplace: the mixture's shape moves a little
+        got = pipe.scale.cpu().numpy()
+        assert np.all(np.abs(got.view(np.int32).astype(np.int64) - scale_o.view(np.int32).astype(np.int64)) <= 2)
+        pipe.scale.copy_(torch.from_numpy(scale_o).cuda())
+        pipe.convert(g)
+        pipe.build()
+        pipe.encode()
+        pipe.aggregate()
+        assert pipe.poll() == 0
+        A = np.array([1], np.int32)
+
+        def client(u):
+            sym, e_new = oracle.convert_ef(host[u], errs[u], A, 1.0, f, scale=scale_o[u])
+            cnt = oracle.histogram(sym, f)
+            l = oracle.huffman_lengths(cnt)
+            words, off, total = oracle.encode(sym, l, oracle.canonical_codes(l), 256)
+            return dict(A=A, sym=sym, err=e_new, cnt=cnt, len=l, words=words, off=off, total=total)
+
+        refs = list(pool.map(client, range(w.U)))
+    for u in range(w.U):
+        compare_client(pipe, u, refs[u], w.n)
+    want = oracle.aggregate(np.stack([r["sym"] for r in refs]), np.tile(A, (w.U, 1)), f, scale=scale_o)
+    assert np.array_equal(u32(pipe.avg[:w.n]), want.view(np.uint32)), "average"
+    properties_all_clients(pipe, w.n)
+
+
 def test_c4_full(co3):
     """C4: 100M elements, E5M2, with outliers; empirical table and the fixed GenNorm-model table, one
     iteration each on every element."""
