@@ -122,6 +122,7 @@ struct DecTables {           // LDS-resident decoder tables of one user
     uint16_t count[66];
     uint16_t base[66];
     uint8_t sorted[256];
+    uint64_t lim_incl[65];   // largest 64-bit window (codeword left-aligned, ones below) of a codeword of length <= l
     uint32_t maxlen, lut_bits;
 };
 
@@ -141,6 +142,19 @@ __device__ __forceinline__ void load_tables(DecTables &t, const Co3Code *cd)
     if (threadIdx.x == 0) {
         t.maxlen = cd->maxlen > 64 ? 64 : cd->maxlen;
         t.lut_bits = lb < 1 ? 1 : lb;
+    }
+    __syncthreads();
+    if (t.maxlen > t.lut_bits) {      // only codes with codewords beyond the table prefix use the limits
+        for (int l = threadIdx.x; l < 65; l += blockDim.x) {
+            int j = l;
+            while (j >= 1 && t.count[j] == 0) --j;     // canonical order: shorter codewords are numerically below
+            uint64_t lim = 0;
+            if (j >= 1) {
+                const uint64_t last = t.first_code[j] + t.count[j] - 1;
+                lim = j == 64 ? last : (last << (64 - j)) | ((~0ull) >> j);
+            }
+            t.lim_incl[l] = lim;
+        }
     }
 }
 
@@ -192,10 +206,17 @@ __device__ __forceinline__ void decode_run_careful(const DecTables &t, LaneStrea
 // decoding and averaging interleaves the runs of the 64 chunks of a wavefront so that each store
 // instruction of the wavefront covers one contiguous KiB).
 //
-// The fast path decodes a run without any check per symbol and validates it afterwards: every
-// window it read lay inside the blocks that were resident when the run started, and no table
-// entry was a miss (a miss advances by DE_MISS_LEN, more than 16 hits can).  Otherwise the run is
-// decoded again by the careful path from the saved position.
+// The fast path decodes a run without a residency check per symbol and validates it afterwards:
+// every window it read must lie inside the blocks that were resident when the run started, and
+// every window must have started a codeword.  Otherwise the run is decoded again by the careful
+// path from the saved position.  Codewords longer than the table prefix are resolved in place by a
+// canonical search (the lengths' upper limits are ordered), in a branch the wavefront skips when
+// no lane needs it.
+//
+// LONG = false is the instance for codes whose longest codeword fits the table prefix: there a miss can
+// only come from an invalid stream; it advances by DE_MISS_LEN, more than 16 hits can, which the
+// validation catches.
+template <bool LONG>
 __device__ __forceinline__ bool decode_chunk(const DecTables &t, LaneStream &ls, uint64_t p0, uint64_t p1, int nsym,
                                              uint8_t *out, int64_t run_step)
 {
@@ -212,16 +233,43 @@ __device__ __forceinline__ bool decode_chunk(const DecTables &t, LaneStream &ls,
         // ({piece d, piece d+1} >> (m mod 32)) with d = (rel - 1) / 32, whose ring index is
         // bits 5..8 of m: one field extract, one two-address LDS read, one funnel shift.
         uint32_t m = 0u - rel0;
+        bool bad = false;
 #pragma unroll
         for (int b = 0; b < DE_GROUP; ++b) {
-            const uint32_t *pc = ls.slot + ((m >> 5) & 15u) * RING_ROW_DW;
-            uint32_t win = __builtin_amdgcn_alignbit(pc[RING_ROW_DW], pc[0], m);
+            const uint32_t row = (m >> 5) & 15u;
+            const uint32_t *pc = ls.slot + row * RING_ROW_DW;
+            const uint32_t d0 = pc[0];
+            uint32_t win = __builtin_amdgcn_alignbit(pc[RING_ROW_DW], d0, m);
             uint32_t e = t.lut[win >> shift];
+            if (LONG && (e >> 8) == DE_MISS_LEN) {
+                // Codeword longer than the table prefix (skipped by the wavefront when no lane is here):
+                // 64-bit window, then the first length whose largest left-aligned codeword is not below it.
+                const uint32_t d2 = ls.slot[((row - 1u) & 15u) * RING_ROW_DW];
+                const uint64_t w64 = ((uint64_t)win << 32) | (uint64_t)__builtin_amdgcn_alignbit(d0, d2, m);
+                // (the limits do not decrease with the length and stay put beyond the longest codeword, so
+                // counting the limits below the window gives the length; nearly all long codewords end
+                // within four bits of the prefix: those limits are compared without a loop)
+                const uint32_t l0 = t.lut_bits + 1u;
+                uint32_t l = l0;
+#pragma unroll
+                for (uint32_t k = 0; k < 4u; ++k) l += w64 > t.lim_incl[l0 + k] ? 1u : 0u;
+                if (l == l0 + 4u)
+                    for (uint32_t j = l0 + 4u; j < t.maxlen; ++j) l += w64 > t.lim_incl[j] ? 1u : 0u;
+                const uint64_t off = (w64 >> (64u - l)) - t.first_code[l];
+                if (off < (uint64_t)t.count[l]) {
+                    e = (l << 8) | t.sorted[(t.base[l] + (uint32_t)off) & 255u];
+                } else {          // no codeword starts here
+                    bad = true;
+                    e = 1u << 8;
+                }
+            }
             m -= e >> 8;
             w[b >> 2] = __builtin_amdgcn_alignbit(e, w[b >> 2], 8);
         }
         ls.rel = 0u - m;
-        if (ls.rel - rel0 > DE_GROUP * CO3_LUT_BITS_MAX || ls.rel + 64u > ls.loaded * 128u) {   // rare
+        // every window read above (up to three dwords from the current one) must have been resident
+        if (LONG ? (bad || ls.rel + 96u > ls.loaded * 128u)
+                 : (ls.rel - rel0 > DE_GROUP * CO3_LUT_BITS_MAX || ls.rel + 64u > ls.loaded * 128u)) {   // rare
             ls.rel = rel0;
             decode_run_careful(t, ls, shift, DE_GROUP, ok, w);
         }
@@ -274,7 +322,8 @@ __global__ __launch_bounds__(DE_BLOCK) void k_decode(const uint64_t *__restrict_
         out = sym_out + (int64_t)u * stride + first;
         run_step = 16;
     }
-    bool ok = decode_chunk(t, ls, off[c], off[c + 1], nsym, out, run_step);
+    const bool ok = t.maxlen > t.lut_bits ? decode_chunk<true>(t, ls, off[c], off[c + 1], nsym, out, run_step)
+                                          : decode_chunk<false>(t, ls, off[c], off[c + 1], nsym, out, run_step);
     if (!ok) co3_raise(status, CO3_EBADSTREAM);
 }
 
