@@ -331,9 +331,11 @@ __global__ __launch_bounds__(DE_BLOCK) void k_decode(const uint64_t *__restrict_
 // Average from the tiled workspace: one thread owns a run of 16 consecutive elements.
 #define PT_BLOCK 256
 
-// TABLE = true (one tensor, i.e. one anchor per user): the K values of every user are computed
-// once per block into LDS, and an element costs one LDS read and one add.
-template <bool TABLE>
+// TABLE != 0 (one tensor, i.e. one anchor per user): the values of every user's symbols are computed
+// once per block into LDS, and an element costs one LDS read and one add.  TABLE = 1 keeps all K
+// values; TABLE = 2 (larger alphabets) keeps the K/2 magnitudes and applies the sign bit after the
+// read, halving the LDS footprint.
+template <int TABLE>
 __global__ __launch_bounds__(PT_BLOCK) void k_ps_sum_tiled(const uint8_t *__restrict__ symt, int64_t n, int U,
                                                             int64_t ws_stride, int chunk_syms, int64_t nruns,
                                                             const int32_t *__restrict__ anchor,
@@ -354,40 +356,51 @@ __global__ __launch_bounds__(PT_BLOCK) void k_ps_sum_tiled(const uint8_t *__rest
         if (scale) v = v / scale[(int64_t)u * nseg + sg];
         return v;
     };
-    __shared__ int64_t seg_cache[CO3_SEG_CACHE];
-    const int64_t *seg_off = co3_cache_segs(seg_off_g, nseg, seg_cache);
-    extern __shared__ float value_of[];    // [U][K], TABLE only
+    __shared__ int64_t seg_cache[TABLE ? 1 : CO3_SEG_CACHE];     // TABLE: one tensor, nothing to look up
+    const int64_t *seg_off = TABLE ? seg_off_g : co3_cache_segs(seg_off_g, nseg, seg_cache);
+    extern __shared__ float value_of[];    // [U][K] or [U][K/2], TABLE only
     if (TABLE) {
-        const int K = fc.K;
-        for (int j = threadIdx.x; j < U * K; j += PT_BLOCK) {
-            const int u = j / K;
-            value_of[j] = value((uint32_t)(j - u * K), u, 0);
+        const int H = TABLE == 1 ? fc.K : fc.K >> 1;
+        for (int j = threadIdx.x; j < U * H; j += PT_BLOCK) {
+            const int u = j / H;
+            value_of[j] = value((uint32_t)(j - u * H), u, 0);
         }
         __syncthreads();
     }
-    for (int64_t r = (int64_t)blockIdx.x * PT_BLOCK + threadIdx.x; r < nruns; r += (int64_t)gridDim.x * PT_BLOCK) {
+    // One block step covers one tile (64 chunks) x 4 consecutive runs: each wavefront one run, each lane
+    // one chunk (nruns is a multiple of 256 and a chunk has a multiple of 4 runs).  The 64 results per
+    // chunk are contiguous in the output; they pass through LDS so that every store instruction of a
+    // wavefront writes 256 contiguous bytes.
+    __shared__ float out_s[CO3_WAVE][CO3_WAVE + 1];
+    for (int64_t rb = (int64_t)blockIdx.x * PT_BLOCK; rb < nruns; rb += (int64_t)gridDim.x * PT_BLOCK) {
         // r enumerates (tile, run within chunk, lane) with the lane fastest: the workspace order
+        const int64_t r = rb + threadIdx.x;
         const int lane = (int)(r & 63);
+        const int wr = threadIdx.x >> 6;
         const int64_t q = r >> 6;
         const int run = (int)(q % runs_per_chunk);
         const int64_t tile = q / runs_per_chunk;
         const int64_t i0 = (tile * CO3_WAVE + lane) * chunk_syms + (int64_t)run * 16;
-        if (i0 >= n) continue;
         const uint8_t *src = symt + r * 16;
-        const int s_lo = co3_find_seg(seg_off, nseg, i0);
-        const int64_t i_last = i0 + 15 < n ? i0 + 15 : n - 1;
-        const int s_hi = co3_find_seg(seg_off, nseg, i_last);
         float acc[16];
 #pragma unroll
         for (int k = 0; k < 16; ++k) acc[k] = 0.f;
-        if (TABLE) {
-            const uint32_t kmask = (uint32_t)fc.K - 1u;
+        const int64_t i_first = i0 < n ? i0 : n - 1;       // lanes past the end compute on the last element's
+        const int s_lo = co3_find_seg(seg_off, nseg, i_first);   // tensor and store nothing
+        const int64_t i_last = i0 + 15 < n ? i0 + 15 : n - 1;
+        const int s_hi = co3_find_seg(seg_off, nseg, i_last);
+        if (i0 >= n) {
+        } else if (TABLE) {
             for (int u = 0; u < U; ++u) {
-                const float *vu = value_of + u * fc.K;
+                const float *vu = value_of + u * (TABLE == 1 ? fc.K : fc.K >> 1);
                 uint4 v = ld_stream_u4(src + (int64_t)u * ws_stride);
                 uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-                for (int k = 0; k < 16; ++k) acc[k] += vu[(w[k >> 2] >> (8 * (k & 3))) & kmask];
+                for (int k = 0; k < 16; ++k) {
+                    const uint32_t sy = w[k >> 2] >> (8 * (k & 3));
+                    if (TABLE == 1) acc[k] += vu[sy & ((uint32_t)fc.K - 1u)];
+                    else acc[k] += __uint_as_float(__float_as_uint(vu[sy & cmask]) | (((sy >> EM) & 1u) << 31));
+                }
             }
         } else if (s_lo == s_hi) {
             for (int u = 0; u < U; ++u) {
@@ -414,16 +427,18 @@ __global__ __launch_bounds__(PT_BLOCK) void k_ps_sum_tiled(const uint8_t *__rest
                 }
             }
         }
-        if (i0 + 16 <= n) {
 #pragma unroll
-            for (int k = 0; k < 16; k += 4)
-                *reinterpret_cast<float4 *>(avg_out + i0 + k) =
-                    make_float4(acc[k] / fU, acc[k + 1] / fU, acc[k + 2] / fU, acc[k + 3] / fU);
-        } else {
-#pragma unroll
-            for (int k = 0; k < 16; ++k)
-                if (i0 + k < n) avg_out[i0 + k] = acc[k] / fU;
+        for (int k = 0; k < 16; ++k) out_s[lane][wr * 16 + k] = acc[k] / fU;
+        __syncthreads();
+        const int64_t run0 = (int64_t)(run - wr) * 16;       // first element (within a chunk) of the block's 4 runs
+        const int e = threadIdx.x & 63;
+#pragma unroll 4
+        for (int j = 0; j < 16; ++j) {
+            const int cc = j * 4 + wr;
+            const int64_t i = (tile * CO3_WAVE + cc) * chunk_syms + run0 + e;
+            if (i < n) avg_out[i] = out_s[cc][e];
         }
+        __syncthreads();
     }
 }
 
@@ -455,12 +470,13 @@ hipError_t co3_launch_ps_sum_tiled(const uint8_t *symt, int64_t n, int U, int64_
     int64_t b = (nruns + PT_BLOCK - 1) / PT_BLOCK;
     unsigned blocks = (unsigned)(b < 8192 ? b : 8192);
     Co3LaunchTimer tm(CO3_K_PS_SUM, st);
-    const size_t table_bytes = (size_t)U * (size_t)(1 << (1 + fmt.exp_bits + fmt.mant_bits)) * sizeof(float);
-    if (nseg == 1 && table_bytes <= 32768)
-        hipLaunchKernelGGL(k_ps_sum_tiled<true>, dim3(blocks), dim3(PT_BLOCK), table_bytes, st, symt, n, U, ws_stride,
-                           chunk_syms, nruns, anchor, scale, seg_off, nseg, fmt, avg_out);
-    else
-        hipLaunchKernelGGL(k_ps_sum_tiled<false>, dim3(blocks), dim3(PT_BLOCK), 0, st, symt, n, U, ws_stride,
-                           chunk_syms, nruns, anchor, scale, seg_off, nseg, fmt, avg_out);
+    const size_t full_bytes = (size_t)U * (size_t)(1 << (1 + fmt.exp_bits + fmt.mant_bits)) * sizeof(float);
+#define CO3_SUM_LAUNCH(T, BYTES)                                                                                   \
+    hipLaunchKernelGGL(k_ps_sum_tiled<T>, dim3(blocks), dim3(PT_BLOCK), BYTES, st, symt, n, U, ws_stride, chunk_syms, \
+                       nruns, anchor, scale, seg_off, nseg, fmt, avg_out)
+    if (nseg == 1 && full_bytes <= 4096) CO3_SUM_LAUNCH(1, full_bytes);
+    else if (nseg == 1 && full_bytes / 2 <= 32768) CO3_SUM_LAUNCH(2, full_bytes / 2);
+    else CO3_SUM_LAUNCH(0, 0);
+#undef CO3_SUM_LAUNCH
     return hipGetLastError();
 }

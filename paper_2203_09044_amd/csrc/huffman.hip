@@ -52,26 +52,39 @@ __global__ __launch_bounds__(HB_BLOCK) void k_build_code(const uint32_t *__restr
 
     // two-queue merge: nodes 0..nact-1 are the sorted leaves, nact..2*nact-2 the merged nodes in
     // creation order; a leaf wins a weight tie against a merged node
+    // One lane runs the merge.  The fronts of both queues are kept in registers: the next four leaf
+    // weights (reloaded four picks ahead of their use) and the next two node weights (a node that is
+    // created when the node queue is nearly empty is forwarded without a trip through LDS), so the
+    // chain of dependent picks does not wait for LDS.
     if (tid == 0 && nact >= 2) {
+        const uint64_t INF = ~0ull;     // weights stay below 2^40, so INF never wins while a queue has entries
+        auto leaf_w = [&](int q) -> uint64_t { return q < nact ? (key[q] >> 8) : INF; };
         int q1 = 0, q2 = nact, next = nact;
+        uint64_t L0 = leaf_w(0), L1 = leaf_w(1), L2 = leaf_w(2), L3 = leaf_w(3);
+        uint64_t N0 = INF, N1 = INF;
         for (int step = 0; step < nact - 1; ++step) {
             uint64_t wsum = 0;
-            int pick[2];
 #pragma unroll
             for (int c = 0; c < 2; ++c) {
-                uint64_t wl = q1 < nact ? (key[q1] >> 8) : ~0ull;
-                uint64_t wn = q2 < next ? node_w[q2] : ~0ull;
-                if (wl <= wn) {          // weights stay below 2^40, so ~0 never wins while a queue has entries
-                    pick[c] = q1++;
-                    wsum += wl;
+                if (L0 <= N0) {
+                    wsum += L0;
+                    parent[q1] = (uint16_t)next;
+                    ++q1;
+                    L0 = L1;
+                    L1 = L2;
+                    L2 = L3;
+                    L3 = leaf_w(q1 + 3);
                 } else {
-                    pick[c] = q2++;
-                    wsum += wn;
+                    wsum += N0;
+                    parent[q2] = (uint16_t)next;
+                    ++q2;
+                    N0 = N1;
+                    N1 = q2 + 1 < next ? node_w[q2 + 1] : INF;
                 }
             }
             node_w[next] = wsum;
-            parent[pick[0]] = (uint16_t)next;
-            parent[pick[1]] = (uint16_t)next;
+            if (next == q2) N0 = wsum;
+            else if (next == q2 + 1) N1 = wsum;
             ++next;
         }
     }
