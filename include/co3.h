@@ -71,7 +71,8 @@ typedef struct {
 /* Human-readable name of a status code; never NULL. */
 const char *co3_strerror(int32_t status);
 
-/* Bytes of workspace co3_encode needs (one 64-bit partial sum per tile of 1024 symbols and user). */
+/* Bytes of workspace co3_encode needs (per user one 64-bit partial sum per tile of 1024 symbols and
+ * one per group of 16 tiles). */
 size_t co3_encode_workspace_bytes(int64_t n, int32_t U);
 
 /* Bytes of workspace co3_ps_aggregate needs (the decoded symbols of all users, whole tiles of

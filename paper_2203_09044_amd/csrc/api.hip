@@ -133,7 +133,8 @@ size_t co3_encode_workspace_bytes(int64_t n, int32_t U)
 {
     if (n < 0 || U < 1) return 0;
     int64_t nblk = (n + CO3_PACK_SYMS - 1) / CO3_PACK_SYMS;
-    return (size_t)(nblk > 0 ? nblk : 1) * (size_t)U * sizeof(uint64_t);
+    int64_t ngrp = (nblk + CO3_PACK_GROUP - 1) / CO3_PACK_GROUP;
+    return (size_t)((nblk > 0 ? nblk : 1) + (ngrp > 0 ? ngrp : 1)) * (size_t)U * sizeof(uint64_t);
 }
 
 size_t co3_ps_aggregate_workspace_bytes(int64_t n, int32_t U, int32_t chunk_syms)

@@ -9,6 +9,7 @@
 #define CO3_LUT_BITS_MAX 12
 #define CO3_MAX_CODE_LEN 57     // (code << 6 | len) must fit 64 bits; u32 weights cannot reach it
 #define CO3_PACK_SYMS 1024      // symbols per encoder tile (one wavefront, 16 per lane)
+#define CO3_PACK_GROUP 16       // tiles whose sizes one workgroup of the sizes pass adds up
 
 // Per-user code blob.  Bytes 0..K-1 (len) are the public wire header; the rest is private.
 struct Co3Code {

@@ -49,26 +49,34 @@ __device__ __forceinline__ uint64_t wave_sum_u64(uint64_t v)
 }
 
 // ---- pass 1: coded size of every tile; a wavefront takes 4 consecutive tiles with all loads in
-// flight before the first table lookup -----------------------------------------------------------
+// flight before the first table lookup.  The 16 tiles of a workgroup form a group: the kernel
+// leaves each tile's offset within its group in tilesum[] and the group's size in groupsum[], so
+// the serial scan of pass 2 runs over 16 times fewer entries. ------------------------------------
 #define SZ_TILES 4
+#define SZ_GROUP (EN_WAVES * SZ_TILES)        // tiles per workgroup = CO3_PACK_GROUP
 
 __global__ __launch_bounds__(EN_BLOCK) void k_enc_sizes(const uint8_t *__restrict__ sym, int64_t n, int64_t stride,
                                                          const void *__restrict__ codes, int K,
-                                                         uint64_t *__restrict__ tilesum, int64_t nblk, int32_t *status)
+                                                         uint64_t *__restrict__ tilesum, int64_t nblk,
+                                                         uint64_t *__restrict__ groupsum, int64_t ngrp,
+                                                         int32_t *status)
 {
     const int u = blockIdx.y;
     const Co3Code *cd = code_of(codes, u);
     __shared__ uint8_t len_s[256];
+    __shared__ uint32_t tile_bits[SZ_GROUP];
     len_s[threadIdx.x] = (int)threadIdx.x < K ? cd->len[threadIdx.x] : (uint8_t)0;
+    if (threadIdx.x < SZ_GROUP) tile_bits[threadIdx.x] = 0;
     __syncthreads();
 
     const int lane = threadIdx.x & (CO3_WAVE - 1);
-    const int64_t tb0 = ((int64_t)blockIdx.x * EN_WAVES + threadIdx.x / CO3_WAVE) * SZ_TILES;
-    if (tb0 >= nblk) return;
+    const int wave = threadIdx.x / CO3_WAVE;
+    const int64_t tb0 = ((int64_t)blockIdx.x * EN_WAVES + wave) * SZ_TILES;
     const uint8_t *su = sym + (int64_t)u * stride;
     uint32_t s[SZ_TILES][4];
     bool nocode = false;
-    if ((tb0 + SZ_TILES) * CO3_PACK_SYMS <= n) {     // uniform: all four tiles are complete
+    if (tb0 >= nblk) {                                // uniform: nothing for this wavefront
+    } else if ((tb0 + SZ_TILES) * CO3_PACK_SYMS <= n) {     // uniform: all four tiles are complete
 #pragma unroll
         for (int t = 0; t < SZ_TILES; ++t) {
             // ordinary (cached) loads: the packing pass reads the same symbols next
@@ -86,7 +94,7 @@ __global__ __launch_bounds__(EN_BLOCK) void k_enc_sizes(const uint8_t *__restric
             }
             nocode |= minlen == 0u;
             bits = wave_sum_u32(bits);
-            if (lane == 0) tilesum[(int64_t)u * nblk + tb0 + t] = bits;
+            if (lane == 0) tile_bits[wave * SZ_TILES + t] = bits;
         }
     } else {                                          // the end of the vector
         for (int t = 0; t < SZ_TILES && tb0 + t < nblk; ++t) {
@@ -100,13 +108,26 @@ __global__ __launch_bounds__(EN_BLOCK) void k_enc_sizes(const uint8_t *__restric
                 nocode |= c < nvalid && l == 0u;
             }
             bits = wave_sum_u32(bits);
-            if (lane == 0) tilesum[(int64_t)u * nblk + tb0 + t] = bits;
+            if (lane == 0) tile_bits[wave * SZ_TILES + t] = bits;
         }
     }
     if (nocode) co3_raise(status, CO3_ENOCODE);
+    __syncthreads();
+    if (threadIdx.x < SZ_GROUP) {
+        const int64_t tb = (int64_t)blockIdx.x * SZ_GROUP + threadIdx.x;
+        uint32_t before = 0, all = 0;
+#pragma unroll
+        for (int k = 0; k < SZ_GROUP; ++k) {
+            const uint32_t b = tile_bits[k];
+            before += k < (int)threadIdx.x ? b : 0u;
+            all += b;
+        }
+        if (tb < nblk) tilesum[(int64_t)u * nblk + tb] = before;
+        if (threadIdx.x == 0) groupsum[(int64_t)u * ngrp + blockIdx.x] = all;
+    }
 }
 
-// ---- pass 2: per user, exclusive scan of the tile sizes (in place), stream length and capacity
+// ---- pass 2: per user, exclusive scan of the group sizes (in place), stream length and capacity
 // check --------------------------------------------------------------------------------------
 #define SC_BLOCK 1024
 #define SC_PER 8
@@ -124,14 +145,26 @@ __global__ __launch_bounds__(SC_BLOCK) void k_enc_scan(uint64_t *__restrict__ ti
     if (threadIdx.x == 0) carry_s = 0;
     __syncthreads();
 
+    // the sizes of the next step are requested before the current step is scanned
+    uint64_t nxt[SC_PER];
+#pragma unroll
+    for (int k = 0; k < SC_PER; ++k) {
+        const int64_t i = (int64_t)threadIdx.x * SC_PER + k;
+        nxt[k] = i < nblk ? bs[i] : 0;
+    }
     for (int64_t base = 0; base < nblk; base += SC_BLOCK * SC_PER) {
         int64_t i0 = base + (int64_t)threadIdx.x * SC_PER;
         uint64_t v[SC_PER];
         uint64_t mine = 0;
 #pragma unroll
         for (int k = 0; k < SC_PER; ++k) {
-            v[k] = (i0 + k < nblk) ? bs[i0 + k] : 0;
+            v[k] = nxt[k];
             mine += v[k];
+        }
+#pragma unroll
+        for (int k = 0; k < SC_PER; ++k) {
+            const int64_t i = i0 + (int64_t)SC_BLOCK * SC_PER + k;
+            nxt[k] = i < nblk ? bs[i] : 0;
         }
         uint64_t incl = mine;   // wave inclusive scan of 64-bit values
 #pragma unroll
@@ -227,6 +260,7 @@ __device__ __forceinline__ void stage_bits(unsigned long long *stage, int64_t wi
 __global__ __launch_bounds__(EN_BLOCK) void k_enc_pack(const uint8_t *__restrict__ sym, int64_t n, int64_t stride,
                                                         const void *__restrict__ codes, int K,
                                                         const uint64_t *__restrict__ tileoff, int64_t nblk,
+                                                        const uint64_t *__restrict__ groupoff, int64_t ngrp,
                                                         uint64_t *__restrict__ words, int64_t cap_words, int chunk_syms,
                                                         uint64_t *__restrict__ chunk_bitoff, int64_t nchunks)
 {
@@ -268,7 +302,7 @@ __global__ __launch_bounds__(EN_BLOCK) void k_enc_pack(const uint8_t *__restrict
     const uint32_t excl = incl - mybits;
     const uint32_t tilebits = (uint32_t)__builtin_amdgcn_readlane((int)incl, CO3_WAVE - 1);
 
-    const uint64_t B0 = tileoff[(int64_t)u * nblk + tb];
+    const uint64_t B0 = groupoff[(int64_t)u * ngrp + tb / CO3_PACK_GROUP] + tileoff[(int64_t)u * nblk + tb];
     const uint64_t B1 = B0 + tilebits;
 
     // chunk index: stream position of every chunk that starts at this lane's first symbol
@@ -376,24 +410,27 @@ hipError_t co3_launch_encode(const uint8_t *sym, int64_t n, int U, int64_t strid
                              uint64_t *words, int64_t cap_words, int chunk_syms, uint64_t *chunk_bitoff,
                              uint64_t *total_bits, uint64_t *tilesum, int32_t *status, hipStream_t st)
 {
+    static_assert(SZ_GROUP == CO3_PACK_GROUP, "group size of the sizes pass");
     const int64_t nblk = (n + CO3_PACK_SYMS - 1) / CO3_PACK_SYMS;
+    const int64_t ngrp = (nblk + CO3_PACK_GROUP - 1) / CO3_PACK_GROUP;
     const int64_t nchunks = (n + chunk_syms - 1) / chunk_syms;
+    uint64_t *groupsum = tilesum + (int64_t)U * (nblk > 0 ? nblk : 1);     // workspace: [U][nblk] then [U][ngrp]
     if (nblk > 0) {
-        const unsigned gx = (unsigned)((nblk + EN_WAVES * SZ_TILES - 1) / (EN_WAVES * SZ_TILES));
         Co3LaunchTimer tm(CO3_K_ENC_SIZES, st);
-        hipLaunchKernelGGL(k_enc_sizes, dim3(gx, U), dim3(EN_BLOCK), 0, st, sym, n, stride, codes, K, tilesum, nblk,
-                           status);
+        hipLaunchKernelGGL(k_enc_sizes, dim3((unsigned)ngrp, U), dim3(EN_BLOCK), 0, st, sym, n, stride, codes, K,
+                           tilesum, nblk, groupsum, ngrp, status);
     }
     {
         Co3LaunchTimer tm(CO3_K_ENC_SCAN, st);
-        hipLaunchKernelGGL(k_enc_scan, dim3(U), dim3(SC_BLOCK), 0, st, tilesum, nblk, cap_words, chunk_bitoff, nchunks,
+        hipLaunchKernelGGL(k_enc_scan, dim3(U), dim3(SC_BLOCK), 0, st, groupsum, ngrp, cap_words, chunk_bitoff, nchunks,
                            total_bits, status);
     }
     if (nblk > 0) {
         const unsigned gx = (unsigned)((nblk + EN_WAVES - 1) / EN_WAVES);
         Co3LaunchTimer tm(CO3_K_ENC_PACK, st);
         hipLaunchKernelGGL(k_enc_pack, dim3(gx, U), dim3(EN_BLOCK), 0, st, sym, n, stride, codes, K,
-                           (const uint64_t *)tilesum, nblk, words, cap_words, chunk_syms, chunk_bitoff, nchunks);
+                           (const uint64_t *)tilesum, nblk, (const uint64_t *)groupsum, ngrp, words, cap_words,
+                           chunk_syms, chunk_bitoff, nchunks);
     }
     return hipGetLastError();
 }

@@ -45,9 +45,9 @@ def test_host_helpers_without_gpu():
     from paper_2203_09044_amd import binding as B
     fmt = B.Fmt(3, 1)
     assert B.strerror(0) == "ok" and B.strerror(B.ECAP) and B.strerror(-1234)
-    assert B.encode_workspace_bytes(0, 1) == 8
-    assert B.encode_workspace_bytes(1024, 3) == 24
-    assert B.encode_workspace_bytes(1025, 3) == 48
+    assert B.encode_workspace_bytes(0, 1) == 16
+    assert B.encode_workspace_bytes(1024, 3) == 48
+    assert B.encode_workspace_bytes(1025, 3) == 72
     assert B.ps_aggregate_workspace_bytes(32, 4, 256) == 4 * 64 * 256      # one tile of 64 chunks per user
     assert B.ps_aggregate_workspace_bytes(64 * 256 + 1, 1, 256) == 2 * 64 * 256
     assert B.cap_words_empirical(64, fmt) == 6          # 5 bits * 64 = 320 bits = 5 words, even -> 6
