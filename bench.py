@@ -111,6 +111,7 @@ def main():
     ap.add_argument("--bias", default="absmax", choices=("absmax", "moments"),
                     help="absmax: integer anchor from max|g| (the headline configuration); moments: the paper's bias "
                          "rule (moment sums, GenNorm fit, multiplier) on the fixed grid of anchor 2^(E-1)")
+    ap.add_argument("--gamma", type=float, default=1.0, help="memory decay coefficient (1.0 in all five configurations)")
     ap.add_argument("--format", default=None, help="override the workload's format, e.g. E1M2")
     ap.add_argument("--pool", type=int, default=3, help="distinct gradient batches cycled through")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
@@ -143,7 +144,7 @@ def main():
         desc += ", bias rule from moments"
     fmt = Fmt(w.E, w.M)
     pipe = Co3Pipeline(w.U, w.n, fmt, chunk_syms=args.chunk, seg_off=w.seg_off if w.sizes is not None else None,
-                       bias=args.bias)
+                       bias=args.bias, gamma=args.gamma)
     log(f"[bench] {desc}; generating {args.pool} device batches")
     batches = device_batches(w, betas, alpha, args.pool, pipe)
 
@@ -214,7 +215,7 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": desc, "U": w.U, "n": w.n, "format": f"E{w.E}M{w.M}", "chunk_syms": args.chunk,
-                   "table": "empirical per client, rebuilt every step", "gamma": 1.0, "bias": args.bias},
+                   "table": "empirical per client, rebuilt every step", "gamma": args.gamma, "bias": args.bias},
         "bits_per_element": {"payload": payload_bpe, "index": index_bpe, "header": header_bpe},
         "path_roofline": {"bound": "hbm", "algorithmic_bytes_per_element": b_alg,
                           "achieved": b_alg * value / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -226,8 +227,8 @@ def main():
     }
     if not args.no_cpu:
         log("[bench] timing the CPU oracle on a bounded sample")
-        if args.bias != "absmax":
-            raise SystemExit("bench.py: the CPU leg times the headline path; use --no-cpu with --bias moments")
+        if args.bias != "absmax" or args.gamma != 1.0:
+            raise SystemExit("bench.py: the CPU leg times the headline path; use --no-cpu with --bias moments / --gamma")
         res["cpu_baseline"] = cpu_baseline(w, betas, alpha, args.chunk, n_sample=min(w.n, 1 << 24), reps=4)
     print(json.dumps(res), flush=True)
 
