@@ -72,6 +72,9 @@ def lib():
         L.co3o_bias_scale.argtypes = [C.c_double, C.c_double]
         L.co3o_convert_ef_scaled.argtypes = [p, p, p, C.c_int64, p, C.c_int, p, p, C.c_float, C.c_int, C.c_int]
         L.co3o_aggregate_scaled.argtypes = [p, C.c_int64, C.c_int, C.c_int64, p, C.c_int, p, p, C.c_int, C.c_int, p]
+        L.co3o_histogram_layers.argtypes = [p, C.c_int64, p, C.c_int, C.c_int, p]
+        L.co3o_encode_layers.argtypes = [p, C.c_int64, p, C.c_int, p, p, C.c_int, C.c_int64, p, C.c_int64, p, p]
+        L.co3o_decode_layers.argtypes = [p, C.c_uint64, p, C.c_int, p, p, C.c_int, C.c_int64, p]
         _lib = L
     return _lib
 
@@ -250,6 +253,48 @@ def decode(words: np.ndarray, total_bits: int, lengths: np.ndarray, codes: np.nd
     c = np.ascontiguousarray(codes, dtype=np.uint64)
     out = np.zeros(n, dtype=np.uint8)
     _check(lib().co3o_decode(_ptr(words), C.c_uint64(total_bits), _ptr(l), _ptr(c), l.size, n, _ptr(out)))
+    return out
+
+
+# --------------------------------------------------------------------------
+# Sec. III (ii) as stated: one code per tensor (layer), shared by all users.
+# lengths / codes are [nseg][K].
+# --------------------------------------------------------------------------
+def histogram_layers(sym: np.ndarray, fmt: Fmt, seg_off) -> np.ndarray:
+    sym = np.ascontiguousarray(sym, dtype=np.uint8)
+    so = _seg(seg_off, sym.size)
+    cnt = np.zeros((so.size - 1, fmt.K), dtype=np.uint32)
+    _check(lib().co3o_histogram_layers(_ptr(sym), sym.size, _ptr(so), so.size - 1, fmt.K, _ptr(cnt)))
+    return cnt
+
+
+def encode_layers(sym: np.ndarray, lengths: np.ndarray, codes: np.ndarray, seg_off, chunk_syms: int, cap_words=None):
+    """Returns (words u64[cap], chunk_bitoff u64[nchunks+1], total_bits); lengths/codes are [nseg][K]."""
+    sym = np.ascontiguousarray(sym, dtype=np.uint8)
+    l = np.ascontiguousarray(lengths, dtype=np.uint8)
+    c = np.ascontiguousarray(codes, dtype=np.uint64)
+    n = sym.size
+    so = _seg(seg_off, n)
+    assert l.shape == c.shape and l.shape[0] == so.size - 1
+    if cap_words is None:
+        cap_words = (int(l.max(initial=0)) * n + 63) // 64
+    nchunks = (n + chunk_syms - 1) // chunk_syms
+    words = np.zeros(max(cap_words, 1), dtype=np.uint64)
+    off = np.zeros(nchunks + 1, dtype=np.uint64)
+    total = C.c_uint64(0)
+    _check(lib().co3o_encode_layers(_ptr(sym), n, _ptr(so), so.size - 1, _ptr(l), _ptr(c), l.shape[1], chunk_syms,
+                                    _ptr(words), cap_words, _ptr(off), C.byref(total)))
+    return words, off, int(total.value)
+
+
+def decode_layers(words: np.ndarray, total_bits: int, lengths: np.ndarray, codes: np.ndarray, seg_off, n: int):
+    words = np.ascontiguousarray(words, dtype=np.uint64)
+    l = np.ascontiguousarray(lengths, dtype=np.uint8)
+    c = np.ascontiguousarray(codes, dtype=np.uint64)
+    so = _seg(seg_off, n)
+    out = np.zeros(n, dtype=np.uint8)
+    _check(lib().co3o_decode_layers(_ptr(words), C.c_uint64(total_bits), _ptr(so), so.size - 1, _ptr(l), _ptr(c),
+                                    l.shape[1], n, _ptr(out)))
     return out
 
 

@@ -577,3 +577,94 @@ int co3o_aggregate_scaled(const uint8_t *sym, int64_t n, int U, int64_t stride, 
     (void)n;
     return CO3O_OK;
 }
+
+/* ---------------------------------------------------------------------- */
+/* Sec. III (ii), as the paper states it: "a different code is used at     */
+/* each DNN layer, but the same code is used across all users at a given   */
+/* layer".  A user's stream is still one concatenation of codewords over   */
+/* all its elements; the codeword of element i comes from the code of the  */
+/* tensor (layer) that holds i.  len and code are [nseg][K].               */
+/* ---------------------------------------------------------------------- */
+
+/* symbol counts per tensor: counts is [nseg][K] */
+int co3o_histogram_layers(const uint8_t *sym, int64_t n, const int64_t *seg_off, int nseg, int K, uint32_t *counts)
+{
+    if (nseg < 0 || (nseg > 0 && seg_off[nseg] > n))
+        return CO3O_EINVAL;
+    for (int64_t j = 0; j < (int64_t)nseg * K; ++j)
+        counts[j] = 0;
+    for (int s = 0; s < nseg; ++s)
+        for (int64_t i = seg_off[s]; i < seg_off[s + 1]; ++i)
+            if (sym[i] < K)
+                counts[(int64_t)s * K + sym[i]] += 1;
+    return CO3O_OK;
+}
+
+int co3o_encode_layers(const uint8_t *sym, int64_t n, const int64_t *seg_off, int nseg, const uint8_t *len,
+                       const uint64_t *code, int K, int64_t chunk_syms, uint64_t *words, int64_t cap_words,
+                       uint64_t *chunk_bitoff, uint64_t *total_bits)
+{
+    if (chunk_syms < 1 || n < 0 || nseg < 1 || seg_off[0] != 0 || seg_off[nseg] != n)
+        return CO3O_EINVAL;
+    uint64_t total = 0;
+    for (int s = 0; s < nseg; ++s)
+        for (int64_t i = seg_off[s]; i < seg_off[s + 1]; ++i) {
+            if (sym[i] >= K || len[(int64_t)s * K + sym[i]] == 0)
+                return CO3O_ENOCODE;
+            total += len[(int64_t)s * K + sym[i]];
+        }
+    if ((total + 63) / 64 > (uint64_t)cap_words)
+        return CO3O_ECAP;
+    for (uint64_t wdx = 0; wdx < (total + 63) / 64; ++wdx)
+        words[wdx] = 0;
+    uint64_t p = 0;
+    for (int s = 0; s < nseg; ++s)
+        for (int64_t i = seg_off[s]; i < seg_off[s + 1]; ++i) {
+            if (i % chunk_syms == 0)
+                chunk_bitoff[i / chunk_syms] = p;
+            int l = len[(int64_t)s * K + sym[i]];
+            uint64_t c = code[(int64_t)s * K + sym[i]];
+            for (int b = l - 1; b >= 0; --b) {
+                if ((c >> b) & 1)
+                    words[p / 64] |= (uint64_t)1 << (63 - (p % 64));
+                ++p;
+            }
+        }
+    int64_t nchunks = (n + chunk_syms - 1) / chunk_syms;
+    chunk_bitoff[nchunks] = p;
+    *total_bits = p;
+    return CO3O_OK;
+}
+
+/* inverse: for each element, extend the read prefix one stream bit at a time until it equals a
+ * codeword of the element's tensor (codes are prefix-free, so the first match is the symbol) */
+int co3o_decode_layers(const uint64_t *words, uint64_t total_bits, const int64_t *seg_off, int nseg,
+                       const uint8_t *len, const uint64_t *code, int K, int64_t n, uint8_t *sym_out)
+{
+    if (nseg < 1 || seg_off[0] != 0 || seg_off[nseg] != n)
+        return CO3O_EINVAL;
+    uint64_t p = 0;
+    for (int s = 0; s < nseg; ++s) {
+        const uint8_t *ls = len + (int64_t)s * K;
+        const uint64_t *cs = code + (int64_t)s * K;
+        for (int64_t i = seg_off[s]; i < seg_off[s + 1]; ++i) {
+            uint64_t prefix = 0;
+            int found = -1;
+            for (int l = 1; l <= 64 && found < 0; ++l) {
+                if (p >= total_bits)
+                    return CO3O_EBADSTREAM;
+                prefix = (prefix << 1) | ((words[p / 64] >> (63 - (p % 64))) & 1);
+                ++p;
+                for (int k = 0; k < K; ++k)
+                    if (ls[k] == l && cs[k] == prefix) {
+                        found = k;
+                        break;
+                    }
+            }
+            if (found < 0)
+                return CO3O_EBADSTREAM;
+            sym_out[i] = (uint8_t)found;
+        }
+    }
+    return p == total_bits ? CO3O_OK : CO3O_EBADSTREAM;
+}
