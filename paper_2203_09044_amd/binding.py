@@ -26,6 +26,7 @@ EXPORTS = (
     "co3_poll_status", "co3_convert_ef", "co3_histogram", "co3_build_code", "co3_encode", "co3_decode",
     "co3_ps_aggregate", "co3_model_weights", "co3_timing_enable", "co3_timing_read", "co3_timing_reset",
     "co3_kernel_name", "co3_moments", "co3_bias_scale", "co3_convert_ef_scaled", "co3_ps_aggregate_scaled",
+    "co3_histogram_layers", "co3_encode_layers", "co3_decode_layers", "co3_ps_aggregate_layers",
 )
 KERNEL_COUNT = 12
 
@@ -93,6 +94,14 @@ def _load():
     L.co3_decode.argtypes = [p, i64, p, i32, p, _Fmt, i64, i32, p, i64, p, p]
     L.co3_ps_aggregate.restype = i32
     L.co3_ps_aggregate.argtypes = [p, i64, p, i32, p, _Fmt, i64, i32, p, p, i32, p, p, sz, p, p]
+    L.co3_histogram_layers.restype = i32
+    L.co3_histogram_layers.argtypes = [p, i64, i32, i64, p, i32, _Fmt, p, p]
+    L.co3_encode_layers.restype = i32
+    L.co3_encode_layers.argtypes = [p, i64, i32, i64, _Fmt, p, p, i32, p, i64, i32, p, p, p, sz, p, p]
+    L.co3_decode_layers.restype = i32
+    L.co3_decode_layers.argtypes = [p, i64, p, i32, p, p, i32, _Fmt, i64, i32, p, i64, p, p]
+    L.co3_ps_aggregate_layers.restype = i32
+    L.co3_ps_aggregate_layers.argtypes = [p, i64, p, i32, p, _Fmt, i64, i32, p, p, p, i32, p, p, sz, p, p]
     L.co3_model_weights.restype = i32
     L.co3_model_weights.argtypes = [i32, _Fmt, C.c_double, C.c_double, p]
     L.co3_timing_enable.restype = i32
@@ -270,3 +279,42 @@ def ps_aggregate_scaled(words, chunk_bitoff, chunk_syms, codes, fmt: Fmt, n, U, 
                                       workspace.numel() * workspace.element_size(), _dp(status, torch.int32),
                                       _stream(stream))
     _chk(rc, "co3_ps_aggregate_scaled")
+
+
+# ---- one code per tensor, shared by all users -------------------------------------------------
+def histogram_layers(sym, n, fmt: Fmt, seg_off, counts, stream=None):
+    U, stride = _batch(sym)
+    _chk(_lib.co3_histogram_layers(_dp(sym, torch.uint8), n, U, stride, _dp(seg_off, torch.int64),
+                                   seg_off.numel() - 1, fmt.c(), _dp(counts, torch.int32), _stream(stream)),
+         "co3_histogram_layers")
+
+
+def encode_layers(sym, n, fmt: Fmt, codes, seg_off, words, chunk_syms, chunk_bitoff, total_bits, workspace, status,
+                  stream=None):
+    U, stride = _batch(sym)
+    rc = _lib.co3_encode_layers(_dp(sym, torch.uint8), n, U, stride, fmt.c(), _dp(codes, torch.uint8),
+                                _dp(seg_off, torch.int64), seg_off.numel() - 1, _dp(words, torch.int64),
+                                words.shape[-1], chunk_syms, _dp(chunk_bitoff, torch.int64),
+                                _dp(total_bits, torch.int64), _dp(workspace),
+                                workspace.numel() * workspace.element_size(), _dp(status, torch.int32),
+                                _stream(stream))
+    _chk(rc, "co3_encode_layers")
+
+
+def decode_layers(words, chunk_bitoff, chunk_syms, codes, seg_off, fmt: Fmt, n, sym_out, status, stream=None):
+    U, stride = _batch(sym_out)
+    rc = _lib.co3_decode_layers(_dp(words, torch.int64), words.shape[-1], _dp(chunk_bitoff, torch.int64), chunk_syms,
+                                _dp(codes, torch.uint8), _dp(seg_off, torch.int64), seg_off.numel() - 1, fmt.c(), n,
+                                U, _dp(sym_out, torch.uint8), stride, _dp(status, torch.int32), _stream(stream))
+    _chk(rc, "co3_decode_layers")
+
+
+def ps_aggregate_layers(words, chunk_bitoff, chunk_syms, codes, fmt: Fmt, n, U, anchor, avg_out, workspace, status,
+                        seg_off, scale=None, stream=None):
+    rc = _lib.co3_ps_aggregate_layers(_dp(words, torch.int64), words.shape[-1], _dp(chunk_bitoff, torch.int64),
+                                      chunk_syms, _dp(codes, torch.uint8), fmt.c(), n, U, _dp(anchor, torch.int32),
+                                      _dp(scale, torch.float32), _dp(seg_off, torch.int64), seg_off.numel() - 1,
+                                      _dp(avg_out, torch.float32), _dp(workspace),
+                                      workspace.numel() * workspace.element_size(), _dp(status, torch.int32),
+                                      _stream(stream))
+    _chk(rc, "co3_ps_aggregate_layers")

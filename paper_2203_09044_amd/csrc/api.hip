@@ -238,9 +238,10 @@ int32_t co3_build_code(const uint32_t *weights, int32_t U, co3_fmt fmt, void *co
     return hip_rc(co3_launch_build_code(weights, U, fc.K, codes, status, static_cast<hipStream_t>(stream)));
 }
 
-int32_t co3_encode(const uint8_t *sym, int64_t n, int32_t U, int64_t stride, co3_fmt fmt, const void *codes,
-                   uint64_t *words, int64_t cap_words, int32_t chunk_syms, uint64_t *chunk_bitoff,
-                   uint64_t *total_bits, void *workspace, size_t ws_bytes, int32_t *status, void *stream)
+static int32_t encode_common(const uint8_t *sym, int64_t n, int32_t U, int64_t stride, co3_fmt fmt, const void *codes,
+                             const int64_t *seg_off, int32_t nseg, uint64_t *words, int64_t cap_words,
+                             int32_t chunk_syms, uint64_t *chunk_bitoff, uint64_t *total_bits, void *workspace,
+                             size_t ws_bytes, int32_t *status, void *stream)
 {
     if (!fmt_ok(fmt) || !batch_ok(n, U, stride) || !chunk_ok(chunk_syms) || cap_words < 0) return CO3_EINVAL;
     if (!sym || !codes || !words || !chunk_bitoff || !total_bits || !workspace) return CO3_EINVAL;
@@ -248,27 +249,79 @@ int32_t co3_encode(const uint8_t *sym, int64_t n, int32_t U, int64_t stride, co3
     if (cap_words % 2 != 0) return CO3_EINVAL;
     if (ws_bytes < co3_encode_workspace_bytes(n, U)) return CO3_EINVAL;
     const FmtC fc(fmt);
-    return hip_rc(co3_launch_encode(sym, n, U, stride, codes, fc.K, words, cap_words, chunk_syms, chunk_bitoff,
-                                    total_bits, static_cast<uint64_t *>(workspace), status,
+    return hip_rc(co3_launch_encode(sym, n, U, stride, codes, fc.K, seg_off, nseg, words, cap_words, chunk_syms,
+                                    chunk_bitoff, total_bits, static_cast<uint64_t *>(workspace), status,
                                     static_cast<hipStream_t>(stream)));
+}
+
+int32_t co3_encode(const uint8_t *sym, int64_t n, int32_t U, int64_t stride, co3_fmt fmt, const void *codes,
+                   uint64_t *words, int64_t cap_words, int32_t chunk_syms, uint64_t *chunk_bitoff,
+                   uint64_t *total_bits, void *workspace, size_t ws_bytes, int32_t *status, void *stream)
+{
+    return encode_common(sym, n, U, stride, fmt, codes, nullptr, 1, words, cap_words, chunk_syms, chunk_bitoff,
+                         total_bits, workspace, ws_bytes, status, stream);
+}
+
+int32_t co3_encode_layers(const uint8_t *sym, int64_t n, int32_t U, int64_t stride, co3_fmt fmt, const void *codes,
+                          const int64_t *seg_off, int32_t nseg, uint64_t *words, int64_t cap_words,
+                          int32_t chunk_syms, uint64_t *chunk_bitoff, uint64_t *total_bits, void *workspace,
+                          size_t ws_bytes, int32_t *status, void *stream)
+{
+    if (!seg_off || nseg < 1) return CO3_EINVAL;
+    return encode_common(sym, n, U, stride, fmt, codes, seg_off, nseg, words, cap_words, chunk_syms, chunk_bitoff,
+                         total_bits, workspace, ws_bytes, status, stream);
+}
+
+int32_t co3_histogram_layers(const uint8_t *sym, int64_t n, int32_t U, int64_t stride, const int64_t *seg_off,
+                             int32_t nseg, co3_fmt fmt, uint32_t *counts, void *stream)
+{
+    if (!fmt_ok(fmt) || !batch_ok(n, U, stride) || !sym || !counts || !aligned(sym, 16)) return CO3_EINVAL;
+    if (!seg_off || nseg < 1) return CO3_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const FmtC fc(fmt);
+    hipError_t e = co3_launch_fill(nullptr, 0, 0, counts, (int64_t)U * nseg * fc.K, st);
+    if (e != hipSuccess) return CO3_EHIP;
+    return hip_rc(co3_launch_histogram_layers(sym, n, U, stride, fc.K, seg_off, nseg, counts, st));
+}
+
+static int32_t decode_common(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff, int32_t chunk_syms,
+                             const void *codes, const int64_t *code_seg_off, int32_t code_nseg, co3_fmt fmt, int64_t n,
+                             int32_t U, uint8_t *sym_out, int64_t stride, int32_t *status, void *stream)
+{
+    if (!fmt_ok(fmt) || !batch_ok(n, U, stride) || !chunk_ok(chunk_syms) || cap_words < 0) return CO3_EINVAL;
+    if (!words || !chunk_bitoff || !codes || !sym_out) return CO3_EINVAL;
+    if (!aligned(sym_out, 16) || !aligned(words, 16) || !aligned(codes, 8) || cap_words % 2 != 0) return CO3_EINVAL;
+    return hip_rc(co3_launch_decode(words, cap_words, chunk_bitoff, chunk_syms, codes, code_seg_off, code_nseg, n, U,
+                                    sym_out, stride, 0, status, static_cast<hipStream_t>(stream)));
 }
 
 int32_t co3_decode(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff, int32_t chunk_syms,
                    const void *codes, co3_fmt fmt, int64_t n, int32_t U, uint8_t *sym_out, int64_t stride,
                    int32_t *status, void *stream)
 {
-    if (!fmt_ok(fmt) || !batch_ok(n, U, stride) || !chunk_ok(chunk_syms) || cap_words < 0) return CO3_EINVAL;
-    if (!words || !chunk_bitoff || !codes || !sym_out) return CO3_EINVAL;
-    if (!aligned(sym_out, 16) || !aligned(words, 16) || !aligned(codes, 8) || cap_words % 2 != 0) return CO3_EINVAL;
-    return hip_rc(co3_launch_decode(words, cap_words, chunk_bitoff, chunk_syms, codes, n, U, sym_out, stride, 0, status,
-                                    static_cast<hipStream_t>(stream)));
+    return decode_common(words, cap_words, chunk_bitoff, chunk_syms, codes, nullptr, 1, fmt, n, U, sym_out, stride,
+                         status, stream);
 }
 
-static int32_t aggregate_common(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff,
-                                int32_t chunk_syms, const void *codes, co3_fmt fmt, int64_t n, int32_t U,
-                                const int32_t *anchor, const float *scale, const int64_t *seg_off, int32_t nseg,
-                                float *avg_out, void *workspace, size_t ws_bytes, int32_t *status, void *stream)
+int32_t co3_decode_layers(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff, int32_t chunk_syms,
+                          const void *codes, const int64_t *seg_off, int32_t nseg, co3_fmt fmt, int64_t n, int32_t U,
+                          uint8_t *sym_out, int64_t stride, int32_t *status, void *stream)
 {
+    if (!seg_off || nseg < 1) return CO3_EINVAL;
+    return decode_common(words, cap_words, chunk_bitoff, chunk_syms, codes, seg_off, nseg, fmt, n, U, sym_out, stride,
+                         status, stream);
+}
+
+// layer_codes: codes holds one code per tensor (shared by the users) instead of one per user
+static int32_t aggregate_common(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff,
+                                int32_t chunk_syms, const void *codes, bool layer_codes, co3_fmt fmt, int64_t n,
+                                int32_t U, const int32_t *anchor, const float *scale, const int64_t *seg_off,
+                                int32_t nseg, float *avg_out, void *workspace, size_t ws_bytes, int32_t *status,
+                                void *stream)
+{
+    if (layer_codes && !seg_off) return CO3_EINVAL;
+    const int64_t *code_seg_off = layer_codes ? seg_off : nullptr;
+    const int32_t code_nseg = layer_codes ? nseg : 1;
     if (!fmt_ok(fmt) || n < 0 || n >= ((int64_t)1 << 32) || U < 1 || !chunk_ok(chunk_syms) || cap_words < 0)
         return CO3_EINVAL;
     if (nseg < 1 || (seg_off == nullptr && nseg != 1)) return CO3_EINVAL;
@@ -281,7 +334,7 @@ static int32_t aggregate_common(const uint64_t *words, int64_t cap_words, const 
     hipStream_t st = static_cast<hipStream_t>(stream);
     uint8_t *symws = static_cast<uint8_t *>(workspace);
     hipError_t e =
-        co3_launch_decode(words, cap_words, chunk_bitoff, chunk_syms, codes, n, U, symws, ws_stride, 1, status, st);
+        co3_launch_decode(words, cap_words, chunk_bitoff, chunk_syms, codes, code_seg_off, code_nseg, n, U, symws, ws_stride, 1, status, st);
     if (e != hipSuccess) return CO3_EHIP;
     return hip_rc(
         co3_launch_ps_sum_tiled(symws, n, U, ws_stride, chunk_syms, anchor, scale, seg_off, nseg, fmt, avg_out, st));
@@ -292,8 +345,8 @@ int32_t co3_ps_aggregate(const uint64_t *words, int64_t cap_words, const uint64_
                          const int64_t *seg_off, int32_t nseg, float *avg_out, void *workspace, size_t ws_bytes,
                          int32_t *status, void *stream)
 {
-    return aggregate_common(words, cap_words, chunk_bitoff, chunk_syms, codes, fmt, n, U, anchor, nullptr, seg_off,
-                            nseg, avg_out, workspace, ws_bytes, status, stream);
+    return aggregate_common(words, cap_words, chunk_bitoff, chunk_syms, codes, false, fmt, n, U, anchor, nullptr,
+                            seg_off, nseg, avg_out, workspace, ws_bytes, status, stream);
 }
 
 int32_t co3_ps_aggregate_scaled(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff,
@@ -302,8 +355,17 @@ int32_t co3_ps_aggregate_scaled(const uint64_t *words, int64_t cap_words, const 
                                 float *avg_out, void *workspace, size_t ws_bytes, int32_t *status, void *stream)
 {
     if (!scale) return CO3_EINVAL;
-    return aggregate_common(words, cap_words, chunk_bitoff, chunk_syms, codes, fmt, n, U, anchor, scale, seg_off, nseg,
-                            avg_out, workspace, ws_bytes, status, stream);
+    return aggregate_common(words, cap_words, chunk_bitoff, chunk_syms, codes, false, fmt, n, U, anchor, scale, seg_off,
+                            nseg, avg_out, workspace, ws_bytes, status, stream);
+}
+
+int32_t co3_ps_aggregate_layers(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff,
+                                int32_t chunk_syms, const void *codes, co3_fmt fmt, int64_t n, int32_t U,
+                                const int32_t *anchor, const float *scale, const int64_t *seg_off, int32_t nseg,
+                                float *avg_out, void *workspace, size_t ws_bytes, int32_t *status, void *stream)
+{
+    return aggregate_common(words, cap_words, chunk_bitoff, chunk_syms, codes, true, fmt, n, U, anchor, scale, seg_off,
+                            nseg, avg_out, workspace, ws_bytes, status, stream);
 }
 
 // ---- model table (host arithmetic only) ---------------------------------------------------

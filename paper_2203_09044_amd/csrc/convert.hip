@@ -332,6 +332,84 @@ __global__ __launch_bounds__(CV_BLOCK) void k_histogram(const uint8_t *__restric
 }
 
 // ------------------------------------------------------------------------------------------
+// symbol counts per (user, tensor) -- the statistics behind one code per layer (Sec. III (ii)):
+// the same LDS scheme, emptied into counts[u][tensor] whenever the block moves to another tensor
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(CV_BLOCK) void k_histogram_layers(const uint8_t *__restrict__ sym, int64_t n,
+                                                                int64_t stride, int K,
+                                                                const int64_t *__restrict__ seg_off_g, int nseg,
+                                                                uint32_t *__restrict__ counts, int64_t per_block)
+{
+    const int u = blockIdx.y;
+    const uint8_t *su = sym + (int64_t)u * stride;
+    const int lane = threadIdx.x & (CO3_WAVE - 1);
+    const int wave = threadIdx.x / CO3_WAVE;
+    __shared__ uint32_t hist[CV_BLOCK / CO3_WAVE][HIST_SLOTS];
+    __shared__ int64_t seg_cache[CO3_SEG_CACHE];
+    const int64_t *seg_off = co3_cache_segs(seg_off_g, nseg, seg_cache);
+    const int copies = HIST_SLOTS / K > 32 ? 32 : HIST_SLOTS / K;
+    uint32_t *myhist = hist[wave];
+    const int mycopy = lane & (copies - 1);
+    for (int j = threadIdx.x; j < (CV_BLOCK / CO3_WAVE) * HIST_SLOTS; j += CV_BLOCK) (&hist[0][0])[j] = 0;
+    __syncthreads();
+
+    // adds the block's counters to tensor sg of this user and clears them (block-uniform call)
+    auto flush = [&](int sg) {
+        __syncthreads();
+        uint32_t *dst = counts + ((int64_t)u * nseg + sg) * K;
+        for (int k = threadIdx.x; k < K; k += CV_BLOCK) {
+            uint32_t c = 0;
+            for (int w = 0; w < CV_BLOCK / CO3_WAVE; ++w)
+                for (int r = 0; r < copies; ++r) {
+                    c += hist[w][k * copies + r];
+                    hist[w][k * copies + r] = 0;
+                }
+            if (c) atomicAdd(&dst[k], c);
+        }
+        __syncthreads();
+    };
+    auto count1 = [&](uint32_t q) {
+        if (q < (uint32_t)K) atomicAdd(&myhist[q * copies + mycopy], 1u);
+    };
+
+    int64_t beg = (int64_t)blockIdx.x * per_block;
+    int64_t end = beg + per_block < n ? beg + per_block : n;
+    if (beg >= end) return;
+    int cur_seg = co3_find_seg(seg_off, nseg, beg);
+    for (int64_t t0 = beg; t0 < end; t0 += HS_TILE) {
+        const int64_t t1 = t0 + HS_TILE < end ? t0 + HS_TILE : end;
+        const int s_lo = co3_find_seg(seg_off, nseg, t0), s_hi = co3_find_seg(seg_off, nseg, t1 - 1);
+        if (s_lo == s_hi) {
+            if (s_lo != cur_seg) {
+                flush(cur_seg);
+                cur_seg = s_lo;
+            }
+            const int64_t i = t0 + (int64_t)threadIdx.x * HS_VEC;
+            if (i + HS_VEC <= t1) {
+                uint4 v = *reinterpret_cast<const uint4 *>(su + i);
+                uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int a = 0; a < 4; ++a)
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) count1((w[a] >> (8 * b)) & 0xffu);
+            } else {
+                for (int64_t j = i; j < t1; ++j) count1(su[j]);
+            }
+        } else {
+            flush(cur_seg);
+            for (int sg = s_lo; sg <= s_hi; ++sg) {
+                const int64_t a0 = seg_off[sg] > t0 ? seg_off[sg] : t0;
+                const int64_t a1 = seg_off[sg + 1] < t1 ? seg_off[sg + 1] : t1;
+                for (int64_t j = a0 + threadIdx.x; j < a1; j += CV_BLOCK) count1(su[j]);
+                flush(sg);
+            }
+            cur_seg = s_hi;
+        }
+    }
+    flush(cur_seg);
+}
+
+// ------------------------------------------------------------------------------------------
 // launchers
 // ------------------------------------------------------------------------------------------
 static int64_t per_block_for(int64_t n, int U, int64_t tile, int *blocks_out, int K = 0)
@@ -399,5 +477,17 @@ hipError_t co3_launch_histogram(const uint8_t *sym, int64_t n, int U, int64_t st
     int64_t pb = per_block_for(n, U, HS_TILE, &blocks, K);
     Co3LaunchTimer tm(CO3_K_HISTOGRAM, st);
     hipLaunchKernelGGL(k_histogram, dim3(blocks, U), dim3(CV_BLOCK), 0, st, sym, n, stride, K, counts, pb);
+    return hipGetLastError();
+}
+
+hipError_t co3_launch_histogram_layers(const uint8_t *sym, int64_t n, int U, int64_t stride, int K,
+                                       const int64_t *seg_off, int nseg, uint32_t *counts, hipStream_t st)
+{
+    if (n <= 0) return hipSuccess;
+    int blocks;
+    int64_t pb = per_block_for(n, U, HS_TILE, &blocks, K);
+    Co3LaunchTimer tm(CO3_K_HISTOGRAM, st);
+    hipLaunchKernelGGL(k_histogram_layers, dim3(blocks, U), dim3(CV_BLOCK), 0, st, sym, n, stride, K, seg_off, nseg,
+                       counts, pb);
     return hipGetLastError();
 }

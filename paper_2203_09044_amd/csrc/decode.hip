@@ -160,7 +160,8 @@ __device__ __forceinline__ void load_tables(DecTables &t, const Co3Code *cd)
 
 // Canonical decoding of a codeword longer than the table prefix: the first length l whose l-bit
 // prefix lies within that length's codeword range.  Returns the length, 0 if there is none.
-__device__ __forceinline__ int decode_long(const DecTables &t, uint64_t window, uint32_t *sym)
+template <class Tables>
+__device__ __forceinline__ int decode_long(const Tables &t, uint64_t window, uint32_t *sym)
 {
     for (uint32_t l = t.lut_bits + 1; l <= t.maxlen; ++l) {
         uint64_t off = (window >> (64 - l)) - t.first_code[l];
@@ -327,6 +328,115 @@ __global__ __launch_bounds__(DE_BLOCK) void k_decode(const uint64_t *__restrict_
     if (!ok) co3_raise(status, CO3_EBADSTREAM);
 }
 
+// One chunk whose symbols lie in more than one tensor, with one code per tensor: symbol by symbol, the
+// tables read from the code blobs (a table entry with length 0 there means "longer than the prefix
+// or invalid").  Rare: at most one chunk per tensor boundary.
+// (Not inlined, with a stream object of its own, so that its registers do not weigh on the main path.)
+__device__ __noinline__ bool decode_chunk_mixed(const void *codes, const int64_t *seg_off, int nseg,
+                                                const uint4 *blocks, int64_t nblocks, uint32_t *slot, uint64_t p0,
+                                                uint64_t p1, int64_t first, int nsym, uint8_t *out, int64_t run_step)
+{
+    bool ok = true;
+    LaneStream ls;
+    ls.blocks = blocks;
+    ls.nblocks = nblocks;
+    ls.slot = slot;
+    ls.open(p0);
+    for (int i = 0; i < nsym; i += DE_GROUP) {
+        const int cnt = nsym - i < DE_GROUP ? nsym - i : DE_GROUP;
+        uint32_t w[4] = {0u, 0u, 0u, 0u};
+        for (int k = 0; k < cnt; ++k) {
+            const Co3Code &cd = *dcode_of(codes, co3_find_seg(seg_off, nseg, first + i + k));
+            const uint32_t lb = cd.lut_bits < 1u ? 1u : (cd.lut_bits > CO3_LUT_BITS_MAX ? CO3_LUT_BITS_MAX : cd.lut_bits);
+            ls.ensure((ls.rel >> 5) + 2u);
+            const uint32_t e = cd.lut[ls.peek32() >> (32u - lb)];
+            uint32_t l = e >> 8, sy = e & 0xffu;
+            if (l == 0u) {
+                l = (uint32_t)decode_long(cd, ls.peek64(), &sy);
+                if (l == 0u) {
+                    ok = false;
+                    l = 1;
+                    sy = 0;
+                }
+            }
+            ls.rel += l;
+            const uint32_t sh = sy << (8 * (k & 3));
+            if ((k >> 2) == 0) w[0] |= sh;
+            else if ((k >> 2) == 1) w[1] |= sh;
+            else if ((k >> 2) == 2) w[2] |= sh;
+            else w[3] |= sh;
+        }
+        uint8_t *dst = out + (int64_t)(i >> 4) * run_step;
+        if (cnt == DE_GROUP) {
+            *reinterpret_cast<uint4 *>(dst) = make_uint4(w[0], w[1], w[2], w[3]);
+        } else {
+            for (int k = 0; k < cnt; ++k) {
+                uint32_t word = (k >> 2) == 0 ? w[0] : (k >> 2) == 1 ? w[1] : (k >> 2) == 2 ? w[2] : w[3];
+                dst[k] = (uint8_t)(word >> (8 * (k & 3)));
+            }
+        }
+    }
+    ls.land();
+    return ok && ls.pos() == p1;
+}
+
+// Decompression with one code per tensor shared by all users (Sec. III (ii) as stated).  The workgroup
+// walks the tensors that hold whole chunks of its range: it loads that tensor's tables, and the lanes
+// whose chunk lies inside the tensor decode as in k_decode; chunks that straddle tensors follow.
+template <bool TILED>
+__global__ __launch_bounds__(DE_BLOCK, 8) void k_decode_layers(const uint64_t *__restrict__ words, int64_t cap_words,
+                                                             const uint64_t *__restrict__ chunk_bitoff, int chunk_syms,
+                                                             int64_t nchunks, const void *__restrict__ codes,
+                                                             const int64_t *__restrict__ seg_off_g, int nseg, int64_t n,
+                                                             uint8_t *__restrict__ sym_out, int64_t stride,
+                                                             int32_t *status)
+{
+    const int u = blockIdx.y;
+    __shared__ DecTables t;
+    __shared__ uint32_t ring[DE_BLOCK * RING_ROWS];
+    const int64_t *seg_off = seg_off_g;      // a handful of look-ups per lane: not worth LDS here
+
+    const int64_t c = (int64_t)blockIdx.x * DE_BLOCK + threadIdx.x;
+    const bool active = c < nchunks;
+    const uint64_t *off = chunk_bitoff + (int64_t)u * (nchunks + 1);
+    LaneStream ls;
+    ls.blocks = reinterpret_cast<const uint4 *>(words + (int64_t)u * cap_words);
+    ls.nblocks = cap_words / 2;
+    ls.slot = ring + (threadIdx.x / CO3_WAVE) * (RING_ROWS * RING_ROW_DW) + (threadIdx.x & (CO3_WAVE - 1));
+    const int64_t first = c * chunk_syms;
+    const int nsym = active ? (int)(n - first < chunk_syms ? n - first : chunk_syms) : 0;
+    uint8_t *out;
+    int64_t run_step;
+    if (TILED) {
+        out = sym_out + (int64_t)u * stride + (c >> 6) * ((int64_t)CO3_WAVE * chunk_syms) + (c & 63) * 16;
+        run_step = CO3_WAVE * 16;
+    } else {
+        out = sym_out + (int64_t)u * stride + first;
+        run_step = 16;
+    }
+    const int my_lo = active ? co3_find_seg(seg_off, nseg, first) : -1;
+    const int my_hi = active ? co3_find_seg(seg_off, nseg, first + nsym - 1) : -2;
+    // tensors touched by the workgroup's range of elements (uniform)
+    const int64_t b_first = (int64_t)blockIdx.x * DE_BLOCK * chunk_syms;
+    int64_t b_last = b_first + (int64_t)DE_BLOCK * chunk_syms;
+    b_last = (b_last < n ? b_last : n) - 1;
+    const int b_lo = co3_find_seg(seg_off, nseg, b_first), b_hi = co3_find_seg(seg_off, nseg, b_last);
+    bool ok = true;
+    for (int sg = b_lo; sg <= b_hi; ++sg) {
+        const bool mine = my_lo == sg && my_hi == sg;
+        if (!__syncthreads_or(mine)) continue;        // no whole chunk of this range lies in tensor sg (uniform)
+        load_tables(t, dcode_of(codes, sg));
+        __syncthreads();
+        if (mine)
+            ok = t.maxlen > t.lut_bits ? decode_chunk<true>(t, ls, off[c], off[c + 1], nsym, out, run_step)
+                                       : decode_chunk<false>(t, ls, off[c], off[c + 1], nsym, out, run_step);
+    }
+    if (active && my_lo != my_hi)
+        ok = decode_chunk_mixed(codes, seg_off, nseg, ls.blocks, ls.nblocks, ls.slot, off[c], off[c + 1], first, nsym,
+                                out, run_step);
+    if (!ok) co3_raise(status, CO3_EBADSTREAM);
+}
+
 // ---- average of the reconstructed gradients: users added in index order, one division -----
 // Average from the tiled workspace: one thread owns a run of 16 consecutive elements.
 #define PT_BLOCK 256
@@ -442,15 +552,22 @@ __global__ __launch_bounds__(PT_BLOCK) void k_ps_sum_tiled(const uint8_t *__rest
     }
 }
 
+// seg_off != NULL selects one code per tensor (codes[tensor], shared by the users) instead of codes[user]
 hipError_t co3_launch_decode(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff, int chunk_syms,
-                             const void *codes, int64_t n, int U, uint8_t *sym_out, int64_t stride, int tiled,
-                             int32_t *status, hipStream_t st)
+                             const void *codes, const int64_t *seg_off, int nseg, int64_t n, int U, uint8_t *sym_out,
+                             int64_t stride, int tiled, int32_t *status, hipStream_t st)
 {
     const int64_t nchunks = (n + chunk_syms - 1) / chunk_syms;
     if (nchunks <= 0) return hipSuccess;
     unsigned blocks = (unsigned)((nchunks + DE_BLOCK - 1) / DE_BLOCK);
     Co3LaunchTimer tm(CO3_K_DECODE, st);
-    if (tiled)
+    if (seg_off && tiled)
+        hipLaunchKernelGGL(k_decode_layers<true>, dim3(blocks, U), dim3(DE_BLOCK), 0, st, words, cap_words, chunk_bitoff,
+                           chunk_syms, nchunks, codes, seg_off, nseg, n, sym_out, stride, status);
+    else if (seg_off)
+        hipLaunchKernelGGL(k_decode_layers<false>, dim3(blocks, U), dim3(DE_BLOCK), 0, st, words, cap_words,
+                           chunk_bitoff, chunk_syms, nchunks, codes, seg_off, nseg, n, sym_out, stride, status);
+    else if (tiled)
         hipLaunchKernelGGL(k_decode<true>, dim3(blocks, U), dim3(DE_BLOCK), 0, st, words, cap_words, chunk_bitoff,
                            chunk_syms, nchunks, codes, n, sym_out, stride, status);
     else

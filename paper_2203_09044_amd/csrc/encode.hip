@@ -127,6 +127,80 @@ __global__ __launch_bounds__(EN_BLOCK) void k_enc_sizes(const uint8_t *__restric
     }
 }
 
+// The same pass for one code per tensor shared by all users (Sec. III (ii) as stated): a wavefront keeps
+// the length table of the tensor it is in, reloading it when a tile lies in another tensor; symbols of
+// a tile that straddles tensors read their lengths from the code blobs directly.
+__global__ __launch_bounds__(EN_BLOCK) void k_enc_sizes_layers(const uint8_t *__restrict__ sym, int64_t n,
+                                                                int64_t stride, const void *__restrict__ codes, int K,
+                                                                const int64_t *__restrict__ seg_off_g, int nseg,
+                                                                uint64_t *__restrict__ tilesum, int64_t nblk,
+                                                                uint64_t *__restrict__ groupsum, int64_t ngrp,
+                                                                int32_t *status)
+{
+    const int u = blockIdx.y;
+    __shared__ uint32_t len_w[EN_WAVES][256 / 4];
+    __shared__ uint32_t tile_bits[SZ_GROUP];
+    __shared__ int64_t seg_cache[CO3_SEG_CACHE];
+    if (threadIdx.x < SZ_GROUP) tile_bits[threadIdx.x] = 0;
+    const int64_t *seg_off = co3_cache_segs(seg_off_g, nseg, seg_cache);
+    __syncthreads();
+
+    const int lane = threadIdx.x & (CO3_WAVE - 1);
+    const int wave = threadIdx.x / CO3_WAVE;
+    const int64_t tb0 = ((int64_t)blockIdx.x * EN_WAVES + wave) * SZ_TILES;
+    const uint8_t *su = sym + (int64_t)u * stride;
+    const uint8_t *len_b = reinterpret_cast<const uint8_t *>(len_w[wave]);
+    bool nocode = false;
+    int cached = -1;
+    for (int t = 0; t < SZ_TILES && tb0 + t < nblk; ++t) {
+        const int64_t t_lo = (tb0 + t) * CO3_PACK_SYMS;
+        const int64_t t_hi = (t_lo + CO3_PACK_SYMS < n ? t_lo + CO3_PACK_SYMS : n) - 1;
+        const int s_lo = co3_find_seg(seg_off, nseg, t_lo), s_hi = co3_find_seg(seg_off, nseg, t_hi);
+        const int64_t i = t_lo + (int64_t)lane * EN_LSYM;
+        uint32_t s[4];
+        const int nvalid = i < n ? load_syms16(su, i, n, s) : 0;
+        uint32_t bits = 0;
+        if (s_lo == s_hi) {              // uniform
+            if (cached != s_lo) {
+                wave_lds_sync();
+                len_w[wave][lane] = reinterpret_cast<const uint32_t *>(code_of(codes, s_lo)->len)[lane];
+                wave_lds_sync();
+                cached = s_lo;
+            }
+#pragma unroll
+            for (int c = 0; c < EN_LSYM; ++c) {
+                const uint32_t sy = (s[c >> 2] >> (8 * (c & 3))) & 0xffu;
+                const uint32_t l = (int)sy < K ? len_b[sy] : 0u;
+                bits += c < nvalid ? l : 0u;
+                nocode |= c < nvalid && l == 0u;
+            }
+        } else {
+            for (int c = 0; c < nvalid; ++c) {
+                const uint32_t sy = (s[c >> 2] >> (8 * (c & 3))) & 0xffu;
+                const uint32_t l = (int)sy < K ? code_of(codes, co3_find_seg(seg_off, nseg, i + c))->len[sy] : 0u;
+                bits += l;
+                nocode |= l == 0u;
+            }
+        }
+        bits = wave_sum_u32(bits);
+        if (lane == 0) tile_bits[wave * SZ_TILES + t] = bits;
+    }
+    if (nocode) co3_raise(status, CO3_ENOCODE);
+    __syncthreads();
+    if (threadIdx.x < SZ_GROUP) {
+        const int64_t tb = (int64_t)blockIdx.x * SZ_GROUP + threadIdx.x;
+        uint32_t before = 0, all = 0;
+#pragma unroll
+        for (int k = 0; k < SZ_GROUP; ++k) {
+            const uint32_t b = tile_bits[k];
+            before += k < (int)threadIdx.x ? b : 0u;
+            all += b;
+        }
+        if (tb < nblk) tilesum[(int64_t)u * nblk + tb] = before;
+        if (threadIdx.x == 0) groupsum[(int64_t)u * ngrp + blockIdx.x] = all;
+    }
+}
+
 // ---- pass 2: per user, exclusive scan of the group sizes (in place), stream length and capacity
 // check --------------------------------------------------------------------------------------
 #define SC_BLOCK 1024
@@ -200,8 +274,9 @@ __global__ __launch_bounds__(SC_BLOCK) void k_enc_scan(uint64_t *__restrict__ ti
 
 // ---- pass 3: bit packing ------------------------------------------------------------------
 // Codewords of the lane's 16 symbols, concatenated four at a time.
-template <bool FULL>
-__device__ __forceinline__ void lookup_runs(const uint64_t *enc_s, const uint32_t s[4], int nvalid,
+// `entry(symbol, k)` returns the packed (codeword << 6 | length) of the lane's k-th symbol.
+template <bool FULL, class Entry>
+__device__ __forceinline__ void lookup_runs(Entry entry, const uint32_t s[4], int nvalid,
                                             uint64_t run[EN_LSYM / 4], uint32_t runbits[EN_LSYM / 4], uint32_t &mybits,
                                             bool &wide)
 {
@@ -211,7 +286,7 @@ __device__ __forceinline__ void lookup_runs(const uint64_t *enc_s, const uint32_
         uint32_t nb = 0;
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            uint64_t e = (FULL || 4 * g + k < nvalid) ? enc_s[(s[g] >> (8 * k)) & 0xffu] : 0ull;
+            uint64_t e = (FULL || 4 * g + k < nvalid) ? entry((s[g] >> (8 * k)) & 0xffu, 4 * g + k) : 0ull;
             uint32_t l = (uint32_t)(e & 63u);
             acc = (acc << l) | (e >> 6);
             nb += l;
@@ -257,25 +332,58 @@ __device__ __forceinline__ void stage_bits(unsigned long long *stage, int64_t wi
     if (o + nb > 64 && w + 1 >= 0 && w + 1 < EN_STAGE_WORDS) atomicOr(&stage[w + 1], (unsigned long long)(v << (64 - o)));
 }
 
+// LAYERS = false: one code per user (codes[u]), its table shared by the workgroup.  LAYERS = true: one
+// code per tensor shared by all users (codes[tensor]); each wavefront keeps the table of its tile's
+// tensor, and a tile that straddles tensors (look-ahead included) reads its entries from the code
+// blobs, tensor by element.
+template <bool LAYERS>
 __global__ __launch_bounds__(EN_BLOCK) void k_enc_pack(const uint8_t *__restrict__ sym, int64_t n, int64_t stride,
                                                         const void *__restrict__ codes, int K,
+                                                        const int64_t *__restrict__ seg_off_g, int nseg,
                                                         const uint64_t *__restrict__ tileoff, int64_t nblk,
                                                         const uint64_t *__restrict__ groupoff, int64_t ngrp,
                                                         uint64_t *__restrict__ words, int64_t cap_words, int chunk_syms,
                                                         uint64_t *__restrict__ chunk_bitoff, int64_t nchunks)
 {
     const int u = blockIdx.y;
-    const Co3Code *cd = code_of(codes, u);
-    __shared__ uint64_t enc_s[256];
+    __shared__ uint64_t enc_all[LAYERS ? EN_WAVES * 256 : 256];
     __shared__ unsigned long long stage_all[EN_WAVES][EN_STAGE_WORDS];
-    enc_s[threadIdx.x] = (int)threadIdx.x < K ? cd->enc[threadIdx.x] : 0ull;
-    const uint32_t maxlen = cd->maxlen;
-    __syncthreads();
-
+    __shared__ int64_t seg_cache[LAYERS ? CO3_SEG_CACHE : 1];
     const int lane = threadIdx.x & (CO3_WAVE - 1);
     const int wave = threadIdx.x / CO3_WAVE;
     const int64_t tb = (int64_t)blockIdx.x * EN_WAVES + wave;
-    if (tb >= nblk) return;
+    const uint64_t *enc_s = LAYERS ? enc_all + wave * 256 : enc_all;
+    const int64_t *seg_off = seg_off_g;
+    uint32_t maxlen;
+    bool one_tensor = true;
+    if (!LAYERS) {
+        const Co3Code *cd = code_of(codes, u);
+        enc_all[threadIdx.x] = (int)threadIdx.x < K ? cd->enc[threadIdx.x] : 0ull;
+        maxlen = cd->maxlen;
+        __syncthreads();
+        if (tb >= nblk) return;
+    } else {
+        seg_off = co3_cache_segs(seg_off_g, nseg, seg_cache);
+        __syncthreads();
+        if (tb >= nblk) return;
+        // tensors of the tile and of the at most 63 following symbols whose codewords complete its last word
+        const int64_t t_lo = tb * CO3_PACK_SYMS;
+        int64_t t_hi = t_lo + CO3_PACK_SYMS + CO3_WAVE - 1;
+        t_hi = (t_hi < n ? t_hi : n) - 1;
+        const int s_lo = co3_find_seg(seg_off, nseg, t_lo), s_hi = co3_find_seg(seg_off, nseg, t_hi);
+        one_tensor = s_lo == s_hi;
+        maxlen = 64u;                    // a mixed tile takes the general path
+        if (one_tensor) {
+            const Co3Code *cd = code_of(codes, s_lo);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int q = lane + k * CO3_WAVE;
+                enc_all[wave * 256 + q] = q < K ? cd->enc[q] : 0ull;
+            }
+            maxlen = cd->maxlen;
+            wave_lds_sync();
+        }
+    }
     unsigned long long *stage = stage_all[wave];
 
     const uint8_t *su = sym + (int64_t)u * stride;
@@ -283,6 +391,12 @@ __global__ __launch_bounds__(EN_BLOCK) void k_enc_pack(const uint8_t *__restrict
     const int64_t i = tb * CO3_PACK_SYMS + (int64_t)lane * EN_LSYM;
     uint32_t s[4];
     const int nvalid = i < n ? load_syms16(su, i, n, s) : 0;
+    // packed (codeword << 6 | length) of symbol sy at element idx
+    auto entry_at = [&](uint32_t sy, int64_t idx) -> uint64_t {
+        if (!LAYERS || one_tensor) return enc_s[sy];
+        return (int)sy < K ? code_of(codes, co3_find_seg(seg_off, nseg, idx))->enc[sy] : 0ull;
+    };
+    auto entry = [&](uint32_t sy, int k) -> uint64_t { return entry_at(sy, i + k); };
 
     // One table lookup per symbol: the codewords of every 4 symbols are concatenated into one run
     // (kept in registers) as long as the run fits 64 bits, which it always does for codes of at most
@@ -295,9 +409,9 @@ __global__ __launch_bounds__(EN_BLOCK) void k_enc_pack(const uint8_t *__restrict
         if (maxlen <= 16u)
             lookup_runs_short(enc_s, s, run, runbits, mybits);
         else
-            lookup_runs<true>(enc_s, s, nvalid, run, runbits, mybits, wide);
+            lookup_runs<true>(entry, s, nvalid, run, runbits, mybits, wide);
     } else
-        lookup_runs<false>(enc_s, s, nvalid, run, runbits, mybits, wide);
+        lookup_runs<false>(entry, s, nvalid, run, runbits, mybits, wide);
     const uint32_t incl = wave_scan_incl_u32(mybits, lane);
     const uint32_t excl = incl - mybits;
     const uint32_t tilebits = (uint32_t)__builtin_amdgcn_readlane((int)incl, CO3_WAVE - 1);
@@ -336,7 +450,7 @@ __global__ __launch_bounds__(EN_BLOCK) void k_enc_pack(const uint8_t *__restrict
         const uint32_t last_rel = (uint32_t)(gwl - gw0);
         if (B1 & 63) {          // complete the last word with the codewords that follow the tile
             const int64_t i2 = (tb + 1) * CO3_PACK_SYMS + lane;
-            uint64_t e = (lane < CO3_WAVE - 1 && i2 < n) ? enc_s[su[i2]] : 0ull;
+            uint64_t e = (lane < CO3_WAVE - 1 && i2 < n) ? entry_at(su[i2], i2) : 0ull;
             uint32_t l = (uint32_t)(e & 63u);
             uint32_t o = wave_scan_incl_u32(l, lane) - l;
             const uint32_t used = (uint32_t)(B1 & 63);
@@ -369,7 +483,7 @@ __global__ __launch_bounds__(EN_BLOCK) void k_enc_pack(const uint8_t *__restrict
             uint64_t acc = 0, pos = rel0;
             int accbits = 0;
             for (int c = 0; c < nvalid; ++c) {
-                uint64_t e = enc_s[(s[c >> 2] >> (8 * (c & 3))) & 0xffu];
+                uint64_t e = entry((s[c >> 2] >> (8 * (c & 3))) & 0xffu, c);
                 int l = (int)(e & 63u);
                 if (l) {
                     if (accbits + l > 64) {
@@ -389,7 +503,7 @@ __global__ __launch_bounds__(EN_BLOCK) void k_enc_pack(const uint8_t *__restrict
         const int64_t last_rel = gwl - gw0 - win_w0;
         if ((B1 & 63) && last_rel >= 0 && last_rel < EN_STAGE_WORDS) {
             const int64_t i2 = (tb + 1) * CO3_PACK_SYMS + lane;
-            uint64_t e = (lane < CO3_WAVE - 1 && i2 < n) ? enc_s[su[i2]] : 0ull;
+            uint64_t e = (lane < CO3_WAVE - 1 && i2 < n) ? entry_at(su[i2], i2) : 0ull;
             uint32_t l = (uint32_t)(e & 63u);
             uint32_t o = wave_scan_incl_u32(l, lane) - l;
             const uint32_t used = (uint32_t)(B1 & 63);
@@ -406,9 +520,11 @@ __global__ __launch_bounds__(EN_BLOCK) void k_enc_pack(const uint8_t *__restrict
     }
 }
 
+// seg_off != NULL selects one code per tensor (codes[tensor], shared by the users) instead of codes[user]
 hipError_t co3_launch_encode(const uint8_t *sym, int64_t n, int U, int64_t stride, const void *codes, int K,
-                             uint64_t *words, int64_t cap_words, int chunk_syms, uint64_t *chunk_bitoff,
-                             uint64_t *total_bits, uint64_t *tilesum, int32_t *status, hipStream_t st)
+                             const int64_t *seg_off, int nseg, uint64_t *words, int64_t cap_words, int chunk_syms,
+                             uint64_t *chunk_bitoff, uint64_t *total_bits, uint64_t *tilesum, int32_t *status,
+                             hipStream_t st)
 {
     static_assert(SZ_GROUP == CO3_PACK_GROUP, "group size of the sizes pass");
     const int64_t nblk = (n + CO3_PACK_SYMS - 1) / CO3_PACK_SYMS;
@@ -417,8 +533,12 @@ hipError_t co3_launch_encode(const uint8_t *sym, int64_t n, int U, int64_t strid
     uint64_t *groupsum = tilesum + (int64_t)U * (nblk > 0 ? nblk : 1);     // workspace: [U][nblk] then [U][ngrp]
     if (nblk > 0) {
         Co3LaunchTimer tm(CO3_K_ENC_SIZES, st);
-        hipLaunchKernelGGL(k_enc_sizes, dim3((unsigned)ngrp, U), dim3(EN_BLOCK), 0, st, sym, n, stride, codes, K,
-                           tilesum, nblk, groupsum, ngrp, status);
+        if (seg_off)
+            hipLaunchKernelGGL(k_enc_sizes_layers, dim3((unsigned)ngrp, U), dim3(EN_BLOCK), 0, st, sym, n, stride, codes,
+                               K, seg_off, nseg, tilesum, nblk, groupsum, ngrp, status);
+        else
+            hipLaunchKernelGGL(k_enc_sizes, dim3((unsigned)ngrp, U), dim3(EN_BLOCK), 0, st, sym, n, stride, codes, K,
+                               tilesum, nblk, groupsum, ngrp, status);
     }
     {
         Co3LaunchTimer tm(CO3_K_ENC_SCAN, st);
@@ -428,9 +548,14 @@ hipError_t co3_launch_encode(const uint8_t *sym, int64_t n, int U, int64_t strid
     if (nblk > 0) {
         const unsigned gx = (unsigned)((nblk + EN_WAVES - 1) / EN_WAVES);
         Co3LaunchTimer tm(CO3_K_ENC_PACK, st);
-        hipLaunchKernelGGL(k_enc_pack, dim3(gx, U), dim3(EN_BLOCK), 0, st, sym, n, stride, codes, K,
-                           (const uint64_t *)tilesum, nblk, (const uint64_t *)groupsum, ngrp, words, cap_words,
-                           chunk_syms, chunk_bitoff, nchunks);
+        if (seg_off)
+            hipLaunchKernelGGL(k_enc_pack<true>, dim3(gx, U), dim3(EN_BLOCK), 0, st, sym, n, stride, codes, K, seg_off,
+                               nseg, (const uint64_t *)tilesum, nblk, (const uint64_t *)groupsum, ngrp, words,
+                               cap_words, chunk_syms, chunk_bitoff, nchunks);
+        else
+            hipLaunchKernelGGL(k_enc_pack<false>, dim3(gx, U), dim3(EN_BLOCK), 0, st, sym, n, stride, codes, K, seg_off,
+                               nseg, (const uint64_t *)tilesum, nblk, (const uint64_t *)groupsum, ngrp, words,
+                               cap_words, chunk_syms, chunk_bitoff, nchunks);
     }
     return hipGetLastError();
 }

@@ -30,11 +30,12 @@ hipError_t co3_launch_histogram(const uint8_t *sym, int64_t n, int U, int64_t st
                                 hipStream_t st);
 hipError_t co3_launch_build_code(const uint32_t *weights, int U, int K, void *codes, int32_t *status, hipStream_t st);
 hipError_t co3_launch_encode(const uint8_t *sym, int64_t n, int U, int64_t stride, const void *codes, int K,
-                             uint64_t *words, int64_t cap_words, int chunk_syms, uint64_t *chunk_bitoff,
-                             uint64_t *total_bits, uint64_t *tilesum, int32_t *status, hipStream_t st);
+                             const int64_t *seg_off, int nseg, uint64_t *words, int64_t cap_words, int chunk_syms,
+                             uint64_t *chunk_bitoff, uint64_t *total_bits, uint64_t *tilesum, int32_t *status,
+                             hipStream_t st);
 hipError_t co3_launch_decode(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff, int chunk_syms,
-                             const void *codes, int64_t n, int U, uint8_t *sym_out, int64_t stride, int tiled,
-                             int32_t *status, hipStream_t st);
+                             const void *codes, const int64_t *seg_off, int nseg, int64_t n, int U, uint8_t *sym_out,
+                             int64_t stride, int tiled, int32_t *status, hipStream_t st);
 hipError_t co3_launch_ps_sum_tiled(const uint8_t *symt, int64_t n, int U, int64_t ws_stride, int chunk_syms,
                                    const int32_t *anchor, const float *scale, const int64_t *seg_off, int nseg,
                                    co3_fmt fmt, float *avg_out, hipStream_t st);
@@ -42,3 +43,5 @@ hipError_t co3_launch_moments(const float *g, const float *err, int64_t n, int U
                               const int64_t *seg_off, int nseg, float gamma, double *sums, hipStream_t st);
 hipError_t co3_launch_bias_scale(const double *sums, int64_t n, int U, const int64_t *seg_off, int nseg, float *scale,
                                  double *fit, hipStream_t st);
+hipError_t co3_launch_histogram_layers(const uint8_t *sym, int64_t n, int U, int64_t stride, int K,
+                                       const int64_t *seg_off, int nseg, uint32_t *counts, hipStream_t st);
