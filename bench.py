@@ -111,6 +111,11 @@ def main():
     ap.add_argument("--bias", default="absmax", choices=("absmax", "moments"),
                     help="absmax: integer anchor from max|g| (the headline configuration); moments: the paper's bias "
                          "rule (moment sums, GenNorm fit, multiplier) on the fixed grid of anchor 2^(E-1)")
+    ap.add_argument("--codes", default="user", choices=("user", "layer", "layer-model"),
+                    help="user: one empirical code per client, rebuilt every step (the headline configuration); "
+                         "layer: one code per tensor shared by the clients, rebuilt every step from the pooled "
+                         "per-tensor counts; layer-model: one fixed code per tensor designed once from the GenNorm "
+                         "law of the tensor (no histogram, no code build inside the step)")
     ap.add_argument("--gamma", type=float, default=1.0, help="memory decay coefficient (1.0 in all five configurations)")
     ap.add_argument("--format", default=None, help="override the workload's format, e.g. E1M2")
     ap.add_argument("--pool", type=int, default=3, help="distinct gradient batches cycled through")
@@ -143,13 +148,41 @@ def main():
     if args.bias == "moments":
         desc += ", bias rule from moments"
     fmt = Fmt(w.E, w.M)
+    code_seg_off = None
+    if args.codes != "user" and w.sizes is not None:
+        import co3_inputs as inp
+        groups = inp.group_small_tensors(w.sizes)
+        code_seg_off = inp.seg_offsets(groups)
+        desc += f", {len(groups)} code groups (tensors under 16,384 elements share the code of the large tensor before them)"
     pipe = Co3Pipeline(w.U, w.n, fmt, chunk_syms=args.chunk, seg_off=w.seg_off if w.sizes is not None else None,
-                       bias=args.bias, gamma=args.gamma)
+                       bias=args.bias, gamma=args.gamma, codes="user" if args.codes == "user" else "layer",
+                       code_seg_off=code_seg_off)
     log(f"[bench] {desc}; generating {args.pool} device batches")
     batches = device_batches(w, betas, alpha, args.pool, pipe)
 
+    rebuild = args.codes != "layer-model"
+    if not rebuild:
+        # fixed tables: the GenNorm law of each tensor (workload parameters) on the grid of client 0's anchors
+        # of the first batch; every emit-able symbol has a codeword, so the tables serve all clients and steps
+        import numpy as np
+        pipe.convert(batches[0])
+        A0 = pipe.anchor[0].cpu().numpy()
+        pipe.err.zero_()
+        model_beta = sum(betas) / len(betas)
+        model_alpha = alpha
+        # anchor of the first tensor of each code group
+        cso = pipe.code_seg_off.cpu().numpy()
+        aso = [0, w.n] if pipe.seg_off is None else pipe.seg_off.cpu().numpy()
+        first_tensor = [int(np.searchsorted(aso, cso[k], side="right") - 1) for k in range(pipe.ncodes)]
+        wts = np.zeros((pipe.ncodes, fmt.K), np.uint32)
+        for k in range(pipe.ncodes):
+            wts[k] = B.model_weights(int(A0[first_tensor[k]]), fmt, float(model_beta), float(model_alpha)).numpy().view(np.uint32)
+        pipe.build(torch.from_numpy(wts.view(np.int32)).cuda())
+        desc += ", fixed per-tensor model tables"
+    elif args.codes == "layer":
+        desc += ", per-tensor codes shared by the clients"
     for i in range(args.warmup):
-        pipe.step(batches[i % args.pool])
+        pipe.step(batches[i % args.pool], rebuild=rebuild)
     torch.cuda.synchronize()
     assert pipe.poll() == 0, "device status after warmup"
 
@@ -158,7 +191,7 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        pipe.step(batches[i % args.pool])
+        pipe.step(batches[i % args.pool], rebuild=rebuild)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     conv_ms, conv_launches = B.timing_read(K_CONVERT)
@@ -190,7 +223,7 @@ def main():
         B.timing_enable((1 << B.KERNEL_COUNT) - 1)
         reps = 5
         for i in range(reps):
-            pipe.step(batches[i % args.pool])
+            pipe.step(batches[i % args.pool], rebuild=rebuild)
         torch.cuda.synchronize()
         tot = 0.0
         for k in range(B.KERNEL_COUNT):
@@ -215,7 +248,7 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": desc, "U": w.U, "n": w.n, "format": f"E{w.E}M{w.M}", "chunk_syms": args.chunk,
-                   "table": "empirical per client, rebuilt every step", "gamma": args.gamma, "bias": args.bias},
+                   "table": "empirical per client, rebuilt every step", "gamma": args.gamma, "bias": args.bias, "codes": args.codes},
         "bits_per_element": {"payload": payload_bpe, "index": index_bpe, "header": header_bpe},
         "path_roofline": {"bound": "hbm", "algorithmic_bytes_per_element": b_alg,
                           "achieved": b_alg * value / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -227,7 +260,7 @@ def main():
     }
     if not args.no_cpu:
         log("[bench] timing the CPU oracle on a bounded sample")
-        if args.bias != "absmax" or args.gamma != 1.0:
+        if args.bias != "absmax" or args.gamma != 1.0 or args.codes != "user":
             raise SystemExit("bench.py: the CPU leg times the headline path; use --no-cpu with --bias moments / --gamma")
         res["cpu_baseline"] = cpu_baseline(w, betas, alpha, args.chunk, n_sample=min(w.n, 1 << 24), reps=4)
     print(json.dumps(res), flush=True)

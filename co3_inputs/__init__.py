@@ -57,6 +57,25 @@ def seg_offsets(sizes: Sequence[int]) -> np.ndarray:
     return np.concatenate([[0], np.cumsum(np.asarray(sizes, dtype=np.int64))]).astype(np.int64)
 
 
+def group_small_tensors(sizes: Sequence[int], min_elems: int = 16384) -> Tuple[int, ...]:
+    """Sizes of groups of consecutive tensors in which every tensor below ``min_elems`` elements joins the
+    large tensor before it (leading small tensors join the first large one): the groups that share a code
+    when one code per tensor would give tables to tensors of a few hundred elements."""
+    groups = []
+    pending = 0
+    for s in sizes:
+        if s >= min_elems:
+            groups.append(s + pending)
+            pending = 0
+        elif groups:
+            groups[-1] += s
+        else:
+            pending += s
+    if pending:
+        groups.append(pending)
+    return tuple(groups)
+
+
 @dataclass(frozen=True)
 class Workload:
     """One benchmark configuration: U clients x n elements, format E/M, T iterations."""

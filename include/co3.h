@@ -214,21 +214,26 @@ int32_t co3_ps_aggregate_scaled(const uint64_t *words, int64_t cap_words, const 
 
 /*
  * Sec. III (ii) as the paper states it: "a different code is used at each DNN layer, but the same code
- * is used across all users at a given layer".  codes is [nseg][CO3_CODE_BYTES], code s serving tensor s
- * (elements seg_off[s] .. seg_off[s+1]) of every user; build the nseg codes with one call
- * co3_build_code(weights [nseg][K], nseg, ...), the weights being model weights (co3_model_weights per
- * tensor) or per-tensor counts.  The stream of a user is still one concatenation over all its elements,
- * with the same word layout and the same chunk index as co3_encode; only the table that gives element i
- * its codeword changes at tensor boundaries.  seg_off (device, [nseg+1]) is required.
+ * is used across all users at a given layer".  codes is [nseg][CO3_CODE_BYTES], code s serving the
+ * elements seg_off[s] .. seg_off[s+1] of every user; build the nseg codes with one call
+ * co3_build_code(weights [nseg][K], nseg, ...), the weights being model weights (co3_model_weights) or
+ * pooled counts.  The stream of a user is still one concatenation over all its elements, with the same
+ * word layout and the same chunk index as co3_encode; only the table that gives element i its codeword
+ * changes at the boundaries.  seg_off (device, [nseg+1]) is required.  The boundaries of the codes need
+ * not be those of the anchors: a tensor of a few hundred elements cannot pay for a table of its own and
+ * is better grouped with a neighbour (the decoder also keeps only four tables resident per workgroup,
+ * so runs of tiny groups slow it down); co3_ps_aggregate_layers takes both sets of boundaries.
  *
  * co3_histogram_layers: counts[u][s][k] = #{i in tensor s : sym[u][i] = k}; counts [U][nseg][K] u32 out,
- *   overwritten (add over u for the statistics of a shared code).
+ *   overwritten.  With pool_users != 0 the users are added up: counts [nseg][K], the statistics of the
+ *   shared codes (n * U < 2^32).
  * co3_encode_layers / co3_decode_layers: as co3_encode / co3_decode.
- * co3_ps_aggregate_layers: as co3_ps_aggregate; scale may be NULL (no multipliers) or [U][nseg] as in
+ * co3_ps_aggregate_layers: as co3_ps_aggregate, with code_seg_off [code_nseg+1] the boundaries of the codes
+ *   and seg_off [nseg+1] those of the anchors; scale may be NULL (no multipliers) or [U][nseg] as in
  *   co3_ps_aggregate_scaled.
  */
 int32_t co3_histogram_layers(const uint8_t *sym, int64_t n, int32_t U, int64_t stride, const int64_t *seg_off,
-                             int32_t nseg, co3_fmt fmt, uint32_t *counts, void *stream);
+                             int32_t nseg, co3_fmt fmt, int32_t pool_users, uint32_t *counts, void *stream);
 int32_t co3_encode_layers(const uint8_t *sym, int64_t n, int32_t U, int64_t stride, co3_fmt fmt, const void *codes,
                           const int64_t *seg_off, int32_t nseg, uint64_t *words, int64_t cap_words,
                           int32_t chunk_syms, uint64_t *chunk_bitoff, uint64_t *total_bits, void *workspace,
@@ -237,9 +242,10 @@ int32_t co3_decode_layers(const uint64_t *words, int64_t cap_words, const uint64
                           const void *codes, const int64_t *seg_off, int32_t nseg, co3_fmt fmt, int64_t n, int32_t U,
                           uint8_t *sym_out, int64_t stride, int32_t *status, void *stream);
 int32_t co3_ps_aggregate_layers(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff,
-                                int32_t chunk_syms, const void *codes, co3_fmt fmt, int64_t n, int32_t U,
-                                const int32_t *anchor, const float *scale, const int64_t *seg_off, int32_t nseg,
-                                float *avg_out, void *workspace, size_t ws_bytes, int32_t *status, void *stream);
+                                int32_t chunk_syms, const void *codes, const int64_t *code_seg_off, int32_t code_nseg,
+                                co3_fmt fmt, int64_t n, int32_t U, const int32_t *anchor, const float *scale,
+                                const int64_t *seg_off, int32_t nseg, float *avg_out, void *workspace, size_t ws_bytes,
+                                int32_t *status, void *stream);
 
 /* ---- launch timing (diagnostic) ------------------------------------------ */
 

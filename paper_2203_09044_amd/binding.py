@@ -95,13 +95,13 @@ def _load():
     L.co3_ps_aggregate.restype = i32
     L.co3_ps_aggregate.argtypes = [p, i64, p, i32, p, _Fmt, i64, i32, p, p, i32, p, p, sz, p, p]
     L.co3_histogram_layers.restype = i32
-    L.co3_histogram_layers.argtypes = [p, i64, i32, i64, p, i32, _Fmt, p, p]
+    L.co3_histogram_layers.argtypes = [p, i64, i32, i64, p, i32, _Fmt, i32, p, p]
     L.co3_encode_layers.restype = i32
     L.co3_encode_layers.argtypes = [p, i64, i32, i64, _Fmt, p, p, i32, p, i64, i32, p, p, p, sz, p, p]
     L.co3_decode_layers.restype = i32
     L.co3_decode_layers.argtypes = [p, i64, p, i32, p, p, i32, _Fmt, i64, i32, p, i64, p, p]
     L.co3_ps_aggregate_layers.restype = i32
-    L.co3_ps_aggregate_layers.argtypes = [p, i64, p, i32, p, _Fmt, i64, i32, p, p, p, i32, p, p, sz, p, p]
+    L.co3_ps_aggregate_layers.argtypes = [p, i64, p, i32, p, p, i32, _Fmt, i64, i32, p, p, p, i32, p, p, sz, p, p]
     L.co3_model_weights.restype = i32
     L.co3_model_weights.argtypes = [i32, _Fmt, C.c_double, C.c_double, p]
     L.co3_timing_enable.restype = i32
@@ -282,11 +282,11 @@ def ps_aggregate_scaled(words, chunk_bitoff, chunk_syms, codes, fmt: Fmt, n, U, 
 
 
 # ---- one code per tensor, shared by all users -------------------------------------------------
-def histogram_layers(sym, n, fmt: Fmt, seg_off, counts, stream=None):
+def histogram_layers(sym, n, fmt: Fmt, seg_off, counts, pool_users=False, stream=None):
     U, stride = _batch(sym)
     _chk(_lib.co3_histogram_layers(_dp(sym, torch.uint8), n, U, stride, _dp(seg_off, torch.int64),
-                                   seg_off.numel() - 1, fmt.c(), _dp(counts, torch.int32), _stream(stream)),
-         "co3_histogram_layers")
+                                   seg_off.numel() - 1, fmt.c(), int(bool(pool_users)), _dp(counts, torch.int32),
+                                   _stream(stream)), "co3_histogram_layers")
 
 
 def encode_layers(sym, n, fmt: Fmt, codes, seg_off, words, chunk_syms, chunk_bitoff, total_bits, workspace, status,
@@ -309,11 +309,14 @@ def decode_layers(words, chunk_bitoff, chunk_syms, codes, seg_off, fmt: Fmt, n, 
     _chk(rc, "co3_decode_layers")
 
 
-def ps_aggregate_layers(words, chunk_bitoff, chunk_syms, codes, fmt: Fmt, n, U, anchor, avg_out, workspace, status,
-                        seg_off, scale=None, stream=None):
+def ps_aggregate_layers(words, chunk_bitoff, chunk_syms, codes, code_seg_off, fmt: Fmt, n, U, anchor, avg_out,
+                        workspace, status, seg_off=None, scale=None, stream=None):
+    """code_seg_off: boundaries of the codes; seg_off: boundaries of the anchors (None: one anchor per user)."""
+    nseg = 1 if seg_off is None else seg_off.numel() - 1
     rc = _lib.co3_ps_aggregate_layers(_dp(words, torch.int64), words.shape[-1], _dp(chunk_bitoff, torch.int64),
-                                      chunk_syms, _dp(codes, torch.uint8), fmt.c(), n, U, _dp(anchor, torch.int32),
-                                      _dp(scale, torch.float32), _dp(seg_off, torch.int64), seg_off.numel() - 1,
+                                      chunk_syms, _dp(codes, torch.uint8), _dp(code_seg_off, torch.int64),
+                                      code_seg_off.numel() - 1, fmt.c(), n, U, _dp(anchor, torch.int32),
+                                      _dp(scale, torch.float32), _dp(seg_off, torch.int64), nseg,
                                       _dp(avg_out, torch.float32), _dp(workspace),
                                       workspace.numel() * workspace.element_size(), _dp(status, torch.int32),
                                       _stream(stream))

@@ -273,15 +273,15 @@ int32_t co3_encode_layers(const uint8_t *sym, int64_t n, int32_t U, int64_t stri
 }
 
 int32_t co3_histogram_layers(const uint8_t *sym, int64_t n, int32_t U, int64_t stride, const int64_t *seg_off,
-                             int32_t nseg, co3_fmt fmt, uint32_t *counts, void *stream)
+                             int32_t nseg, co3_fmt fmt, int32_t pool_users, uint32_t *counts, void *stream)
 {
     if (!fmt_ok(fmt) || !batch_ok(n, U, stride) || !sym || !counts || !aligned(sym, 16)) return CO3_EINVAL;
     if (!seg_off || nseg < 1) return CO3_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const FmtC fc(fmt);
-    hipError_t e = co3_launch_fill(nullptr, 0, 0, counts, (int64_t)U * nseg * fc.K, st);
+    hipError_t e = co3_launch_fill(nullptr, 0, 0, counts, (int64_t)(pool_users ? 1 : U) * nseg * fc.K, st);
     if (e != hipSuccess) return CO3_EHIP;
-    return hip_rc(co3_launch_histogram_layers(sym, n, U, stride, fc.K, seg_off, nseg, counts, st));
+    return hip_rc(co3_launch_histogram_layers(sym, n, U, stride, fc.K, seg_off, nseg, pool_users != 0, counts, st));
 }
 
 static int32_t decode_common(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff, int32_t chunk_syms,
@@ -312,19 +312,17 @@ int32_t co3_decode_layers(const uint64_t *words, int64_t cap_words, const uint64
                          status, stream);
 }
 
-// layer_codes: codes holds one code per tensor (shared by the users) instead of one per user
+// code_seg_off != NULL: codes holds one code per code group [code_seg_off[s], code_seg_off[s+1]) shared by the
+// users, instead of one code per user
 static int32_t aggregate_common(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff,
-                                int32_t chunk_syms, const void *codes, bool layer_codes, co3_fmt fmt, int64_t n,
-                                int32_t U, const int32_t *anchor, const float *scale, const int64_t *seg_off,
-                                int32_t nseg, float *avg_out, void *workspace, size_t ws_bytes, int32_t *status,
-                                void *stream)
+                                int32_t chunk_syms, const void *codes, const int64_t *code_seg_off, int32_t code_nseg,
+                                co3_fmt fmt, int64_t n, int32_t U, const int32_t *anchor, const float *scale,
+                                const int64_t *seg_off, int32_t nseg, float *avg_out, void *workspace, size_t ws_bytes,
+                                int32_t *status, void *stream)
 {
-    if (layer_codes && !seg_off) return CO3_EINVAL;
-    const int64_t *code_seg_off = layer_codes ? seg_off : nullptr;
-    const int32_t code_nseg = layer_codes ? nseg : 1;
     if (!fmt_ok(fmt) || n < 0 || n >= ((int64_t)1 << 32) || U < 1 || !chunk_ok(chunk_syms) || cap_words < 0)
         return CO3_EINVAL;
-    if (nseg < 1 || (seg_off == nullptr && nseg != 1)) return CO3_EINVAL;
+    if (nseg < 1 || (seg_off == nullptr && nseg != 1) || code_nseg < 1) return CO3_EINVAL;
     if (!words || !chunk_bitoff || !codes || !anchor || !avg_out || !workspace) return CO3_EINVAL;
     if (!aligned(avg_out, 16) || !aligned(workspace, 16) || !aligned(words, 16) || !aligned(codes, 8)) return CO3_EINVAL;
     if (cap_words % 2 != 0) return CO3_EINVAL;
@@ -333,8 +331,8 @@ static int32_t aggregate_common(const uint64_t *words, int64_t cap_words, const 
     const int64_t ws_stride = (int64_t)(need / (size_t)U);
     hipStream_t st = static_cast<hipStream_t>(stream);
     uint8_t *symws = static_cast<uint8_t *>(workspace);
-    hipError_t e =
-        co3_launch_decode(words, cap_words, chunk_bitoff, chunk_syms, codes, code_seg_off, code_nseg, n, U, symws, ws_stride, 1, status, st);
+    hipError_t e = co3_launch_decode(words, cap_words, chunk_bitoff, chunk_syms, codes, code_seg_off, code_nseg, n, U,
+                                     symws, ws_stride, 1, status, st);
     if (e != hipSuccess) return CO3_EHIP;
     return hip_rc(
         co3_launch_ps_sum_tiled(symws, n, U, ws_stride, chunk_syms, anchor, scale, seg_off, nseg, fmt, avg_out, st));
@@ -345,7 +343,7 @@ int32_t co3_ps_aggregate(const uint64_t *words, int64_t cap_words, const uint64_
                          const int64_t *seg_off, int32_t nseg, float *avg_out, void *workspace, size_t ws_bytes,
                          int32_t *status, void *stream)
 {
-    return aggregate_common(words, cap_words, chunk_bitoff, chunk_syms, codes, false, fmt, n, U, anchor, nullptr,
+    return aggregate_common(words, cap_words, chunk_bitoff, chunk_syms, codes, nullptr, 1, fmt, n, U, anchor, nullptr,
                             seg_off, nseg, avg_out, workspace, ws_bytes, status, stream);
 }
 
@@ -355,17 +353,19 @@ int32_t co3_ps_aggregate_scaled(const uint64_t *words, int64_t cap_words, const 
                                 float *avg_out, void *workspace, size_t ws_bytes, int32_t *status, void *stream)
 {
     if (!scale) return CO3_EINVAL;
-    return aggregate_common(words, cap_words, chunk_bitoff, chunk_syms, codes, false, fmt, n, U, anchor, scale, seg_off,
-                            nseg, avg_out, workspace, ws_bytes, status, stream);
+    return aggregate_common(words, cap_words, chunk_bitoff, chunk_syms, codes, nullptr, 1, fmt, n, U, anchor, scale,
+                            seg_off, nseg, avg_out, workspace, ws_bytes, status, stream);
 }
 
 int32_t co3_ps_aggregate_layers(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff,
-                                int32_t chunk_syms, const void *codes, co3_fmt fmt, int64_t n, int32_t U,
-                                const int32_t *anchor, const float *scale, const int64_t *seg_off, int32_t nseg,
-                                float *avg_out, void *workspace, size_t ws_bytes, int32_t *status, void *stream)
+                                int32_t chunk_syms, const void *codes, const int64_t *code_seg_off, int32_t code_nseg,
+                                co3_fmt fmt, int64_t n, int32_t U, const int32_t *anchor, const float *scale,
+                                const int64_t *seg_off, int32_t nseg, float *avg_out, void *workspace, size_t ws_bytes,
+                                int32_t *status, void *stream)
 {
-    return aggregate_common(words, cap_words, chunk_bitoff, chunk_syms, codes, true, fmt, n, U, anchor, scale, seg_off,
-                            nseg, avg_out, workspace, ws_bytes, status, stream);
+    if (!code_seg_off) return CO3_EINVAL;
+    return aggregate_common(words, cap_words, chunk_bitoff, chunk_syms, codes, code_seg_off, code_nseg, fmt, n, U,
+                            anchor, scale, seg_off, nseg, avg_out, workspace, ws_bytes, status, stream);
 }
 
 // ---- model table (host arithmetic only) ---------------------------------------------------

@@ -338,9 +338,11 @@ __global__ __launch_bounds__(CV_BLOCK) void k_histogram(const uint8_t *__restric
 __global__ __launch_bounds__(CV_BLOCK) void k_histogram_layers(const uint8_t *__restrict__ sym, int64_t n,
                                                                 int64_t stride, int K,
                                                                 const int64_t *__restrict__ seg_off_g, int nseg,
-                                                                uint32_t *__restrict__ counts, int64_t per_block)
+                                                                int pool_users, uint32_t *__restrict__ counts,
+                                                                int64_t per_block)
 {
     const int u = blockIdx.y;
+    const int row = pool_users ? 0 : u;       // pooled: all users add into one [nseg][K] table
     const uint8_t *su = sym + (int64_t)u * stride;
     const int lane = threadIdx.x & (CO3_WAVE - 1);
     const int wave = threadIdx.x / CO3_WAVE;
@@ -356,7 +358,7 @@ __global__ __launch_bounds__(CV_BLOCK) void k_histogram_layers(const uint8_t *__
     // adds the block's counters to tensor sg of this user and clears them (block-uniform call)
     auto flush = [&](int sg) {
         __syncthreads();
-        uint32_t *dst = counts + ((int64_t)u * nseg + sg) * K;
+        uint32_t *dst = counts + ((int64_t)row * nseg + sg) * K;
         for (int k = threadIdx.x; k < K; k += CV_BLOCK) {
             uint32_t c = 0;
             for (int w = 0; w < CV_BLOCK / CO3_WAVE; ++w)
@@ -481,13 +483,14 @@ hipError_t co3_launch_histogram(const uint8_t *sym, int64_t n, int U, int64_t st
 }
 
 hipError_t co3_launch_histogram_layers(const uint8_t *sym, int64_t n, int U, int64_t stride, int K,
-                                       const int64_t *seg_off, int nseg, uint32_t *counts, hipStream_t st)
+                                       const int64_t *seg_off, int nseg, int pool_users, uint32_t *counts,
+                                       hipStream_t st)
 {
     if (n <= 0) return hipSuccess;
     int blocks;
     int64_t pb = per_block_for(n, U, HS_TILE, &blocks, K);
     Co3LaunchTimer tm(CO3_K_HISTOGRAM, st);
     hipLaunchKernelGGL(k_histogram_layers, dim3(blocks, U), dim3(CV_BLOCK), 0, st, sym, n, stride, K, seg_off, nseg,
-                       counts, pb);
+                       pool_users, counts, pb);
     return hipGetLastError();
 }

@@ -202,10 +202,12 @@ __device__ __forceinline__ void decode_run_careful(const DecTables &t, LaneStrea
     ls.ensure(((ls.rel >> 7) + 3u) * 4u);
 }
 
-// One lane decodes the `nsym` symbols of one chunk.  Symbols leave in runs of 16: run r is stored at
-// out + r * run_step (run_step = 16 gives the plain contiguous layout; the tiled layout used between
-// decoding and averaging interleaves the runs of the 64 chunks of a wavefront so that each store
-// instruction of the wavefront covers one contiguous KiB).
+// One lane decodes symbols [i0, i1) of its chunk; the stream is open at symbol i0.  Symbols leave in
+// runs of 16: run r is stored at out + r * run_step (run_step = 16 gives the plain contiguous layout;
+// the tiled layout used between decoding and averaging interleaves the runs of the 64 chunks of a
+// wavefront so that each store instruction of the wavefront covers one contiguous KiB).  A range
+// that does not start or end on a run boundary (tensor boundaries with one code per tensor, the end
+// of the vector) takes the careful path for the partial runs and stores them byte by byte.
 //
 // The fast path decodes a run without a residency check per symbol and validates it afterwards:
 // every window it read must lie inside the blocks that were resident when the run started, and
@@ -218,15 +220,26 @@ __device__ __forceinline__ void decode_run_careful(const DecTables &t, LaneStrea
 // only come from an invalid stream; it advances by DE_MISS_LEN, more than 16 hits can, which the
 // validation catches.
 template <bool LONG>
-__device__ __forceinline__ bool decode_chunk(const DecTables &t, LaneStream &ls, uint64_t p0, uint64_t p1, int nsym,
-                                             uint8_t *out, int64_t run_step)
+__device__ __forceinline__ void decode_range(const DecTables &t, LaneStream &ls, int i0, int i1, uint8_t *out,
+                                             int64_t run_step, bool &ok)
 {
-    bool ok = true;
     const int shift = 32 - (int)t.lut_bits;
-    ls.open(p0);
-    int i = 0;
+    int i = i0;
+    // cnt < 16 symbols from symbol i on, inside one run
+    auto partial = [&](int cnt) {
+        ls.group_boundary();
+        uint32_t w[4];
+        decode_run_careful(t, ls, shift, cnt, ok, w);
+        uint8_t *dst = out + (int64_t)(i >> 4) * run_step + (i & 15);
+        for (int k = 0; k < cnt; ++k) {
+            uint32_t word = (k >> 2) == 0 ? w[0] : (k >> 2) == 1 ? w[1] : (k >> 2) == 2 ? w[2] : w[3];
+            dst[k] = (uint8_t)(word >> (8 * (k & 3)));
+        }
+        i += cnt;
+    };
+    if ((i & 15) != 0 && i < i1) partial(16 - (i & 15) < i1 - i ? 16 - (i & 15) : i1 - i);
 #pragma unroll 1
-    for (; i + DE_GROUP <= nsym; i += DE_GROUP) {
+    for (; i + DE_GROUP <= i1; i += DE_GROUP) {
         ls.group_boundary();
         const uint32_t rel0 = ls.rel;
         uint32_t w[4] = {0u, 0u, 0u, 0u};
@@ -276,17 +289,17 @@ __device__ __forceinline__ bool decode_chunk(const DecTables &t, LaneStream &ls,
         }
         *reinterpret_cast<uint4 *>(out + (int64_t)(i >> 4) * run_step) = make_uint4(w[0], w[1], w[2], w[3]);
     }
-    if (i < nsym) {                         // ragged end of the last chunk
-        ls.group_boundary();
-        uint32_t w[4];
-        const int cnt = nsym - i;
-        decode_run_careful(t, ls, shift, cnt, ok, w);
-        uint8_t *dst = out + (int64_t)(i >> 4) * run_step;
-        for (int k = 0; k < cnt; ++k) {
-            uint32_t word = (k >> 2) == 0 ? w[0] : (k >> 2) == 1 ? w[1] : (k >> 2) == 2 ? w[2] : w[3];
-            dst[k] = (uint8_t)(word >> (8 * (k & 3)));
-        }
-    }
+    if (i < i1) partial(i1 - i);
+}
+
+// One lane decodes the `nsym` symbols of one chunk with one table.
+template <bool LONG>
+__device__ __forceinline__ bool decode_chunk(const DecTables &t, LaneStream &ls, uint64_t p0, uint64_t p1, int nsym,
+                                             uint8_t *out, int64_t run_step)
+{
+    bool ok = true;
+    ls.open(p0);
+    decode_range<LONG>(t, ls, 0, nsym, out, run_step, ok);
     ls.land();
     return ok && ls.pos() == p1;
 }
@@ -328,75 +341,34 @@ __global__ __launch_bounds__(DE_BLOCK) void k_decode(const uint64_t *__restrict_
     if (!ok) co3_raise(status, CO3_EBADSTREAM);
 }
 
-// One chunk whose symbols lie in more than one tensor, with one code per tensor: symbol by symbol, the
-// tables read from the code blobs (a table entry with length 0 there means "longer than the prefix
-// or invalid").  Rare: at most one chunk per tensor boundary.
-// (Not inlined, with a stream object of its own, so that its registers do not weigh on the main path.)
-__device__ __noinline__ bool decode_chunk_mixed(const void *codes, const int64_t *seg_off, int nseg,
-                                                const uint4 *blocks, int64_t nblocks, uint32_t *slot, uint64_t p0,
-                                                uint64_t p1, int64_t first, int nsym, uint8_t *out, int64_t run_step)
-{
-    bool ok = true;
-    LaneStream ls;
-    ls.blocks = blocks;
-    ls.nblocks = nblocks;
-    ls.slot = slot;
-    ls.open(p0);
-    for (int i = 0; i < nsym; i += DE_GROUP) {
-        const int cnt = nsym - i < DE_GROUP ? nsym - i : DE_GROUP;
-        uint32_t w[4] = {0u, 0u, 0u, 0u};
-        for (int k = 0; k < cnt; ++k) {
-            const Co3Code &cd = *dcode_of(codes, co3_find_seg(seg_off, nseg, first + i + k));
-            const uint32_t lb = cd.lut_bits < 1u ? 1u : (cd.lut_bits > CO3_LUT_BITS_MAX ? CO3_LUT_BITS_MAX : cd.lut_bits);
-            ls.ensure((ls.rel >> 5) + 2u);
-            const uint32_t e = cd.lut[ls.peek32() >> (32u - lb)];
-            uint32_t l = e >> 8, sy = e & 0xffu;
-            if (l == 0u) {
-                l = (uint32_t)decode_long(cd, ls.peek64(), &sy);
-                if (l == 0u) {
-                    ok = false;
-                    l = 1;
-                    sy = 0;
-                }
-            }
-            ls.rel += l;
-            const uint32_t sh = sy << (8 * (k & 3));
-            if ((k >> 2) == 0) w[0] |= sh;
-            else if ((k >> 2) == 1) w[1] |= sh;
-            else if ((k >> 2) == 2) w[2] |= sh;
-            else w[3] |= sh;
-        }
-        uint8_t *dst = out + (int64_t)(i >> 4) * run_step;
-        if (cnt == DE_GROUP) {
-            *reinterpret_cast<uint4 *>(dst) = make_uint4(w[0], w[1], w[2], w[3]);
-        } else {
-            for (int k = 0; k < cnt; ++k) {
-                uint32_t word = (k >> 2) == 0 ? w[0] : (k >> 2) == 1 ? w[1] : (k >> 2) == 2 ? w[2] : w[3];
-                dst[k] = (uint8_t)(word >> (8 * (k & 3)));
-            }
-        }
-    }
-    ls.land();
-    return ok && ls.pos() == p1;
-}
-
 // Decompression with one code per tensor shared by all users (Sec. III (ii) as stated).  The workgroup
-// walks the tensors that hold whole chunks of its range: it loads that tensor's tables, and the lanes
-// whose chunk lies inside the tensor decode as in k_decode; chunks that straddle tensors follow.
+// walks the tensors of its range of elements with the tables of four neighbouring tensors resident
+// (tensor s in slot s mod 4): a lane decodes the part of its chunk that lies in the tensor at its
+// position as soon as that tensor's tables are there, so the chunks on both sides of a tensor
+// boundary are decoded at the same time, each lane reading the table of its own tensor; a chunk that
+// straddles tensors continues in the next step.  Lanes whose tensor is more than three tensors away
+// from the first one of the range wait for the window: tensors much smaller than a workgroup's range
+// (512 chunks) are better given a code together with a neighbour.
+#define DL_BLOCK 512
+#define DL_SLOTS 4
+
 template <bool TILED>
-__global__ __launch_bounds__(DE_BLOCK, 8) void k_decode_layers(const uint64_t *__restrict__ words, int64_t cap_words,
+__global__ __launch_bounds__(DL_BLOCK) void k_decode_layers(const uint64_t *__restrict__ words, int64_t cap_words,
                                                              const uint64_t *__restrict__ chunk_bitoff, int chunk_syms,
                                                              int64_t nchunks, const void *__restrict__ codes,
-                                                             const int64_t *__restrict__ seg_off_g, int nseg, int64_t n,
+                                                             const int64_t *__restrict__ seg_off, int nseg, int64_t n,
                                                              uint8_t *__restrict__ sym_out, int64_t stride,
                                                              int32_t *status)
 {
     const int u = blockIdx.y;
-    __shared__ DecTables t;
-    __shared__ uint32_t ring[DE_BLOCK * RING_ROWS];
-    const int64_t *seg_off = seg_off_g;      // a handful of look-ups per lane: not worth LDS here
+    __shared__ DecTables t[DL_SLOTS];
+    __shared__ uint32_t ring[DL_BLOCK * RING_ROWS];
+    if (threadIdx.x < DL_SLOTS) {
+        t[threadIdx.x].maxlen = 0;
+        t[threadIdx.x].lut_bits = 1;
+    }
 
-    const int64_t c = (int64_t)blockIdx.x * DE_BLOCK + threadIdx.x;
+    const int64_t c = (int64_t)blockIdx.x * DL_BLOCK + threadIdx.x;
     const bool active = c < nchunks;
     const uint64_t *off = chunk_bitoff + (int64_t)u * (nchunks + 1);
     LaneStream ls;
@@ -414,26 +386,41 @@ __global__ __launch_bounds__(DE_BLOCK, 8) void k_decode_layers(const uint64_t *_
         out = sym_out + (int64_t)u * stride + first;
         run_step = 16;
     }
-    const int my_lo = active ? co3_find_seg(seg_off, nseg, first) : -1;
-    const int my_hi = active ? co3_find_seg(seg_off, nseg, first + nsym - 1) : -2;
     // tensors touched by the workgroup's range of elements (uniform)
-    const int64_t b_first = (int64_t)blockIdx.x * DE_BLOCK * chunk_syms;
-    int64_t b_last = b_first + (int64_t)DE_BLOCK * chunk_syms;
+    const int64_t b_first = (int64_t)blockIdx.x * DL_BLOCK * chunk_syms;
+    int64_t b_last = b_first + (int64_t)DL_BLOCK * chunk_syms;
     b_last = (b_last < n ? b_last : n) - 1;
     const int b_lo = co3_find_seg(seg_off, nseg, b_first), b_hi = co3_find_seg(seg_off, nseg, b_last);
+
     bool ok = true;
+    int cur = 0;                                                        // next symbol of the chunk to decode
+    int cur_seg = nsym > 0 ? co3_find_seg(seg_off, nseg, first) : -1;   // the tensor that holds it
+    if (nsym > 0) ls.open(off[c]);
     for (int sg = b_lo; sg <= b_hi; ++sg) {
-        const bool mine = my_lo == sg && my_hi == sg;
-        if (!__syncthreads_or(mine)) continue;        // no whole chunk of this range lies in tensor sg (uniform)
-        load_tables(t, dcode_of(codes, sg));
+        __syncthreads();                 // nobody reads the slot that is replaced any more
+        if (sg == b_lo) {
+            for (int k = 0; k < DL_SLOTS - 1 && sg + k <= b_hi; ++k)
+                load_tables(t[(sg + k) & (DL_SLOTS - 1)], dcode_of(codes, sg + k));
+        }
+        if (sg + DL_SLOTS - 1 <= b_hi)
+            load_tables(t[(sg + DL_SLOTS - 1) & (DL_SLOTS - 1)], dcode_of(codes, sg + DL_SLOTS - 1));
         __syncthreads();
-        if (mine)
-            ok = t.maxlen > t.lut_bits ? decode_chunk<true>(t, ls, off[c], off[c + 1], nsym, out, run_step)
-                                       : decode_chunk<false>(t, ls, off[c], off[c + 1], nsym, out, run_step);
+        bool any_long = false;           // uniform
+        for (int k = 0; k < DL_SLOTS; ++k) any_long |= t[k].maxlen > t[k].lut_bits;
+        if (cur < nsym && cur_seg >= sg && cur_seg < sg + DL_SLOTS) {
+            const DecTables &tl = t[cur_seg & (DL_SLOTS - 1)];
+            const int64_t seg_end = seg_off[cur_seg + 1] - first;
+            const int i1 = seg_end < nsym ? (int)seg_end : nsym;
+            if (any_long) decode_range<true>(tl, ls, cur, i1, out, run_step, ok);
+            else decode_range<false>(tl, ls, cur, i1, out, run_step, ok);
+            cur = i1;
+            if (cur < nsym) cur_seg = co3_find_seg(seg_off, nseg, first + cur);
+        }
     }
-    if (active && my_lo != my_hi)
-        ok = decode_chunk_mixed(codes, seg_off, nseg, ls.blocks, ls.nblocks, ls.slot, off[c], off[c + 1], first, nsym,
-                                out, run_step);
+    if (nsym > 0) {
+        ls.land();
+        ok = ok && cur == nsym && ls.pos() == off[c + 1];
+    }
     if (!ok) co3_raise(status, CO3_EBADSTREAM);
 }
 
@@ -560,12 +547,13 @@ hipError_t co3_launch_decode(const uint64_t *words, int64_t cap_words, const uin
     const int64_t nchunks = (n + chunk_syms - 1) / chunk_syms;
     if (nchunks <= 0) return hipSuccess;
     unsigned blocks = (unsigned)((nchunks + DE_BLOCK - 1) / DE_BLOCK);
+    const unsigned lblocks = (unsigned)((nchunks + DL_BLOCK - 1) / DL_BLOCK);
     Co3LaunchTimer tm(CO3_K_DECODE, st);
     if (seg_off && tiled)
-        hipLaunchKernelGGL(k_decode_layers<true>, dim3(blocks, U), dim3(DE_BLOCK), 0, st, words, cap_words, chunk_bitoff,
-                           chunk_syms, nchunks, codes, seg_off, nseg, n, sym_out, stride, status);
+        hipLaunchKernelGGL(k_decode_layers<true>, dim3(lblocks, U), dim3(DL_BLOCK), 0, st, words, cap_words,
+                           chunk_bitoff, chunk_syms, nchunks, codes, seg_off, nseg, n, sym_out, stride, status);
     else if (seg_off)
-        hipLaunchKernelGGL(k_decode_layers<false>, dim3(blocks, U), dim3(DE_BLOCK), 0, st, words, cap_words,
+        hipLaunchKernelGGL(k_decode_layers<false>, dim3(lblocks, U), dim3(DL_BLOCK), 0, st, words, cap_words,
                            chunk_bitoff, chunk_syms, nchunks, codes, seg_off, nseg, n, sym_out, stride, status);
     else if (tiled)
         hipLaunchKernelGGL(k_decode<true>, dim3(blocks, U), dim3(DE_BLOCK), 0, st, words, cap_words, chunk_bitoff,

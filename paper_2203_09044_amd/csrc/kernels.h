@@ -44,4 +44,5 @@ hipError_t co3_launch_moments(const float *g, const float *err, int64_t n, int U
 hipError_t co3_launch_bias_scale(const double *sums, int64_t n, int U, const int64_t *seg_off, int nseg, float *scale,
                                  double *fit, hipStream_t st);
 hipError_t co3_launch_histogram_layers(const uint8_t *sym, int64_t n, int U, int64_t stride, int K,
-                                       const int64_t *seg_off, int nseg, uint32_t *counts, hipStream_t st);
+                                       const int64_t *seg_off, int nseg, int pool_users, uint32_t *counts,
+                                       hipStream_t st);

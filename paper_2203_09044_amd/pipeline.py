@@ -4,7 +4,9 @@ Plumbing only: allocation through torch, then the six library calls in the order
 Algorithm 1 (user side: convert_ef [+ fused histogram] -> build_code -> encode; server
 side: ps_aggregate, or decode for the round-trip check).  With ``bias="moments"`` the grid is
 fixed (anchor ``grid_anchor``) and the paper's bias rule supplies a multiplier per (user,
-tensor): moments -> bias_scale -> convert_ef_scaled ... ps_aggregate_scaled.
+tensor): moments -> bias_scale -> convert_ef_scaled ... ps_aggregate_scaled.  With
+``codes="layer"`` there is one code per tensor shared by all users (built from the pooled
+per-tensor counts of the iteration, or once from model weights handed to ``build``).
 """
 from __future__ import annotations
 
@@ -23,9 +25,12 @@ def _round_up(x: int, m: int) -> int:
 class Co3Pipeline:
     def __init__(self, U: int, n: int, fmt: Fmt, chunk_syms: int = 256, seg_off=None, gamma: float = 1.0,
                  cap_words: Optional[int] = None, device="cuda:0", fused_histogram: bool = True,
-                 bias: str = "absmax", grid_anchor: Optional[int] = None):
+                 bias: str = "absmax", grid_anchor: Optional[int] = None, codes: str = "user", code_seg_off=None):
         if bias not in ("absmax", "moments"):
             raise ValueError("bias must be 'absmax' or 'moments'")
+        if codes not in ("user", "layer"):
+            raise ValueError("codes must be 'user' or 'layer'")
+        self.code_mode = codes
         self.U, self.n, self.fmt, self.chunk_syms, self.gamma = U, n, fmt, chunk_syms, gamma
         self.fused_histogram = fused_histogram
         self.bias = bias
@@ -33,7 +38,10 @@ class Co3Pipeline:
         self.device = dev
         self.stride = _round_up(max(n, 1), 16)
         self.nchunks = (n + chunk_syms - 1) // chunk_syms
-        self.cap_words = B.cap_words_empirical(n, fmt) if cap_words is None else _round_up(cap_words, 2)
+        # a user's own empirical code never exceeds the fixed-length size; a shared or model code can
+        if cap_words is None:
+            cap_words = B.cap_words_empirical(n, fmt) * (2 if codes == "layer" else 1)
+        self.cap_words = _round_up(cap_words, 2)
         self.seg_off = None if seg_off is None else torch.as_tensor(seg_off, dtype=torch.int64).to(dev)
         self.nseg = 1 if seg_off is None else self.seg_off.numel() - 1
         z = dict(device=dev)
@@ -50,6 +58,13 @@ class Co3Pipeline:
         self.avg = torch.zeros((self.stride,), dtype=torch.float32, **z)
         self.sym_dec = torch.zeros((U, self.stride), dtype=torch.uint8, **z)
         self.status = torch.zeros((1,), dtype=torch.int32, **z)
+        if codes == "layer":
+            # boundaries of the shared codes: given, else those of the anchors, else one code for everything
+            cso = code_seg_off if code_seg_off is not None else (seg_off if seg_off is not None else [0, n])
+            self.code_seg_off = torch.as_tensor(cso, dtype=torch.int64).to(dev)
+            self.ncodes = self.code_seg_off.numel() - 1
+            self.layer_counts = torch.zeros((self.ncodes, fmt.K), dtype=torch.int32, **z)
+            self.codes = torch.zeros((self.ncodes, B.CODE_BYTES), dtype=torch.uint8, **z)
         if bias == "moments":
             self.anchor.fill_((1 << (fmt.E - 1)) if grid_anchor is None else grid_anchor)
             self.sums = torch.zeros((U, self.nseg, 2), dtype=torch.float64, **z)
@@ -65,30 +80,50 @@ class Co3Pipeline:
         B.bias_scale(self.sums, self.n, self.U, self.scale, fit=self.fit, seg_off=self.seg_off)
 
     def convert(self, g: torch.Tensor, anchor_mode=B.ANCHOR_FROM_ABSMAX_G):
-        counts = self.counts if self.fused_histogram else None
+        counts = self.counts if self.fused_histogram and self.code_mode == "user" else None
         if self.bias == "moments":
             B.convert_ef_scaled(g, self.err, self.sym, self.n, self.anchor, self.scale, self.gamma, self.fmt,
                                 seg_off=self.seg_off, counts=counts)
         else:
             B.convert_ef(g, self.err, self.sym, self.n, self.anchor, anchor_mode, self.gamma, self.fmt,
                          seg_off=self.seg_off, counts=counts)
-        if not self.fused_histogram:
+        if not self.fused_histogram and self.code_mode == "user":
             B.histogram(self.sym, self.n, self.fmt, self.counts)
 
     def build(self, weights: Optional[torch.Tensor] = None):
-        B.build_code(self.counts if weights is None else weights, self.U, self.fmt, self.codes, self.status)
+        """Per-user codes from the users' counts (or given weights [U][K]); per-tensor codes from the pooled
+        per-tensor counts of this iteration (or given weights [nseg][K], e.g. model weights)."""
+        if self.code_mode == "layer":
+            if weights is None:
+                B.histogram_layers(self.sym, self.n, self.fmt, self.code_seg_off, self.layer_counts, pool_users=True)
+                weights = self.layer_counts
+            B.build_code(weights, self.ncodes, self.fmt, self.codes, self.status)
+        else:
+            B.build_code(self.counts if weights is None else weights, self.U, self.fmt, self.codes, self.status)
 
     def encode(self):
-        B.encode(self.sym, self.n, self.fmt, self.codes, self.words, self.chunk_syms, self.chunk_bitoff,
-                 self.total_bits, self.enc_ws, self.status)
+        if self.code_mode == "layer":
+            B.encode_layers(self.sym, self.n, self.fmt, self.codes, self.code_seg_off, self.words, self.chunk_syms,
+                            self.chunk_bitoff, self.total_bits, self.enc_ws, self.status)
+        else:
+            B.encode(self.sym, self.n, self.fmt, self.codes, self.words, self.chunk_syms, self.chunk_bitoff,
+                     self.total_bits, self.enc_ws, self.status)
 
     # ---- server side
     def decode(self):
-        B.decode(self.words, self.chunk_bitoff, self.chunk_syms, self.codes, self.fmt, self.n, self.sym_dec,
-                 self.status)
+        if self.code_mode == "layer":
+            B.decode_layers(self.words, self.chunk_bitoff, self.chunk_syms, self.codes, self.code_seg_off, self.fmt,
+                            self.n, self.sym_dec, self.status)
+        else:
+            B.decode(self.words, self.chunk_bitoff, self.chunk_syms, self.codes, self.fmt, self.n, self.sym_dec,
+                     self.status)
 
     def aggregate(self):
-        if self.bias == "moments":
+        if self.code_mode == "layer":
+            B.ps_aggregate_layers(self.words, self.chunk_bitoff, self.chunk_syms, self.codes, self.code_seg_off,
+                                  self.fmt, self.n, self.U, self.anchor, self.avg, self.agg_ws, self.status,
+                                  seg_off=self.seg_off, scale=self.scale if self.bias == "moments" else None)
+        elif self.bias == "moments":
             B.ps_aggregate_scaled(self.words, self.chunk_bitoff, self.chunk_syms, self.codes, self.fmt, self.n,
                                   self.U, self.anchor, self.scale, self.avg, self.agg_ws, self.status,
                                   seg_off=self.seg_off)
@@ -96,12 +131,14 @@ class Co3Pipeline:
             B.ps_aggregate(self.words, self.chunk_bitoff, self.chunk_syms, self.codes, self.fmt, self.n, self.U,
                            self.anchor, self.avg, self.agg_ws, self.status, seg_off=self.seg_off)
 
-    def step(self, g: torch.Tensor, weights: Optional[torch.Tensor] = None):
-        """One whole iteration: users encode, the server decodes and averages."""
+    def step(self, g: torch.Tensor, weights: Optional[torch.Tensor] = None, rebuild: bool = True):
+        """One whole iteration: users encode, the server decodes and averages.  ``rebuild=False`` keeps the
+        codes of the previous call (fixed tables designed from a model)."""
         if self.bias == "moments":
             self.fit_bias(g)
         self.convert(g)
-        self.build(weights)
+        if rebuild:
+            self.build(weights)
         self.encode()
         self.aggregate()
 

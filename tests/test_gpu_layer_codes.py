@@ -90,8 +90,8 @@ def run_layers(co3, U, sizes, E, M, C, table, seed=0):
     assert pipe.poll() == 0
     assert torch.equal(pipe.sym_dec[:, :n], pipe.sym[:, :n]), "decode(encode(s)) = s"
 
-    B.ps_aggregate_layers(words, pipe.chunk_bitoff, C, codes, fmt, n, U, pipe.anchor, pipe.avg, pipe.agg_ws,
-                          pipe.status, pipe.seg_off)
+    B.ps_aggregate_layers(words, pipe.chunk_bitoff, C, codes, pipe.seg_off, fmt, n, U, pipe.anchor, pipe.avg,
+                          pipe.agg_ws, pipe.status, seg_off=pipe.seg_off)
     assert pipe.poll() == 0
     want = oracle.aggregate(np.stack(syms), A, f, seg)
     assert np.array_equal(u32(pipe.avg[:n]), want.view(np.uint32)), "average"
@@ -118,6 +118,44 @@ def test_layer_codes_from_model(co3):
     the rare symbols, every emit-able symbol has one."""
     run_layers(co3, 2, SHAPES["resnet_head"], 4, 3, 256, "model", seed=5)
     run_layers(co3, 2, SHAPES["two_big"], 3, 1, 256, "model", seed=6)
+
+
+def test_code_groups_differ_from_anchor_tensors(co3):
+    """Anchors per tensor, codes per group of tensors (each small tensor grouped with the large one before
+    it), pooled over 3 users, through the pipeline class; two chained iterations."""
+    sizes = [1728, 64, 64, 36864, 64, 64, 73728, 128, 128, 5120, 10]
+    groups = [1728 + 64 + 64, 36864 + 64 + 64, 73728 + 128 + 128, 5120 + 10]
+    seg, cseg = inp.seg_offsets(sizes), inp.seg_offsets(groups)
+    n, U, C = int(seg[-1]), 3, 256
+    fmt, f = co3.Fmt(4, 3), oracle.Fmt(4, 3)
+    pipe = co3.Co3Pipeline(U, n, fmt, chunk_syms=C, seg_off=seg, codes="layer", code_seg_off=cseg)
+    g = pipe.new_gradient_buffer()
+    errs = [np.zeros(n, np.float32) for _ in range(U)]
+    for t in range(2):
+        gh = [np.concatenate([inp.gennorm(inp.rng_for(89, t, u, k), m, 0.9, 10.0 ** -(2 + k % 3))
+                              for k, m in enumerate(sizes)]).astype(np.float32) for u in range(U)]
+        g[:, :n] = torch.from_numpy(np.stack(gh)).cuda()
+        pipe.step(g)
+        pipe.decode()
+        assert pipe.poll() == 0
+        A = np.stack([oracle.anchor(gh[u], f, seg) for u in range(U)])
+        syms = []
+        for u in range(U):
+            sym, errs[u] = oracle.convert_ef(gh[u], errs[u], A[u], 1.0, f, seg)
+            syms.append(sym)
+        w = np.stack([oracle.histogram_layers(s_, f, cseg) for s_ in syms]).astype(np.int64).sum(axis=0).astype(np.uint32)
+        assert np.array_equal(u32(pipe.layer_counts), w), "pooled counts per code group"
+        lens = np.stack([oracle.huffman_lengths(w[k]) for k in range(len(groups))])
+        cods = np.stack([oracle.canonical_codes(lens[k]) for k in range(len(groups))])
+        for u in range(U):
+            wo, off, total = oracle.encode_layers(syms[u], lens, cods, cseg, C)
+            assert int(pipe.total_bits[u].item()) == total
+            assert np.array_equal(u64(pipe.chunk_bitoff[u]), off)
+            assert np.array_equal(u64(pipe.words[u, :(total + 63) // 64]), wo[:(total + 63) // 64])
+            assert np.array_equal(pipe.sym_dec[u, :n].cpu().numpy(), syms[u])
+            assert np.array_equal(u32(pipe.err[u, :n]), errs[u].view(np.uint32))
+        want = oracle.aggregate(np.stack(syms), A, f, seg)
+        assert np.array_equal(u32(pipe.avg[:n]), want.view(np.uint32))
 
 
 def test_layer_codes_errors(co3):
