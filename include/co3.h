@@ -91,8 +91,8 @@ int32_t co3_poll_status(const int32_t *status_dev, void *stream);
 /* ---- user side ---------------------------------------------------------- */
 
 /*
- * Error correction + fp conversion + memory update (Algorithm 1: "fp-converts
- * g + gamma*m" and "updates m"), for all users:
+ * Error correction + fp conversion + memory update (Algorithm 1, the user's conversion
+ * step and memory-update step), for all users:
  *     x = fl32(g + fl32(gamma * err));  sym = Q_A(x);  err = fl32(x - value_A(sym))
  * Q_A rounds to the nearest level, ties to the even multiple of the local quantum;
  * magnitudes above the top level saturate to it (the excess stays in err).
@@ -161,7 +161,7 @@ int32_t co3_histogram(const uint8_t *sym, int64_t n, int32_t U, int64_t stride, 
 int32_t co3_build_code(const uint32_t *weights, int32_t U, co3_fmt fmt, void *codes, int32_t *status, void *stream);
 
 /*
- * Compression h_Hf (Algorithm 1: "compresses ghat") of every user's symbols with its code.
+ * Compression h_Hf (Algorithm 1, the user's compression step) of every user's symbols with its code.
  *
  *   words        [U][cap_words] u64 out  streams; words past ceil(total_bits/64) are untouched
  *   chunk_syms   64, 128, ..., 4096 (power of two)
@@ -178,7 +178,7 @@ int32_t co3_encode(const uint8_t *sym, int64_t n, int32_t U, int64_t stride, co3
 /* ---- parameter-server side ---------------------------------------------- */
 
 /*
- * Decompression (Algorithm 1: "PS decompresses all the users' gradients"): the inverse of
+ * Decompression (Algorithm 1, the parameter server's decompression step): the inverse of
  * co3_encode, chunk by chunk.  sym_out [U][stride] u8.  Device-reported: CO3_EBADSTREAM.
  */
 int32_t co3_decode(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff, int32_t chunk_syms,
@@ -213,8 +213,8 @@ int32_t co3_ps_aggregate_scaled(const uint64_t *words, int64_t cap_words, const 
 /* ---- one code per layer, shared by all users ---------------------------------- */
 
 /*
- * Sec. III (ii) as the paper states it: "a different code is used at each DNN layer, but the same code
- * is used across all users at a given layer".  codes is [nseg][CO3_CODE_BYTES], code s serving the
+ * Sec. III (ii) assigns the codes per layer: every layer has a code of its own, and all users share the
+ * code of a layer.  codes is [nseg][CO3_CODE_BYTES], code s serving the
  * elements seg_off[s] .. seg_off[s+1] of every user; build the nseg codes with one call
  * co3_build_code(weights [nseg][K], nseg, ...), the weights being model weights (co3_model_weights) or
  * pooled counts.  The stream of a user is still one concatenation over all its elements, with the same

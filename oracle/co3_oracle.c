@@ -13,7 +13,7 @@
  * point that the method performs in fp32 is performed in fp32 with one IEEE
  * operation per stated operation (build with -ffp-contract=off, no fast-math);
  * the quantiser itself is evaluated in double, where every intermediate is
- * exact, following the "closest representative" rule of Sec. III (i).
+ * exact, following the nearest-representative rule of Sec. III (i).
  *
  * Readings of the paper that the text leaves open (integer exponent anchor in
  * place of the real-valued bias, ties-to-even, gradual underflow, one zero,
@@ -579,11 +579,11 @@ int co3o_aggregate_scaled(const uint8_t *sym, int64_t n, int U, int64_t stride, 
 }
 
 /* ---------------------------------------------------------------------- */
-/* Sec. III (ii), as the paper states it: "a different code is used at     */
-/* each DNN layer, but the same code is used across all users at a given   */
-/* layer".  A user's stream is still one concatenation of codewords over   */
-/* all its elements; the codeword of element i comes from the code of the  */
-/* tensor (layer) that holds i.  len and code are [nseg][K].               */
+/* Sec. III (ii) assigns the codes per layer: every layer (tensor) has a   */
+/* code of its own, and all users share the code of a layer.  A user's     */
+/* stream is still one concatenation of codewords over all its elements;   */
+/* the codeword of element i comes from the code of the tensor that holds  */
+/* i.  len and code are [nseg][K].                                         */
 /* ---------------------------------------------------------------------- */
 
 /* symbol counts per tensor: counts is [nseg][K] */
