@@ -119,6 +119,8 @@ def main():
     ap.add_argument("--gamma", type=float, default=1.0, help="memory decay coefficient (1.0 in all five configurations)")
     ap.add_argument("--format", default=None, help="override the workload's format, e.g. E1M2")
     ap.add_argument("--pool", type=int, default=3, help="distinct gradient batches cycled through")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one iteration per batch buffer in a HIP graph and time replays (launch-bound workloads)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--breakdown", action="store_true", help="extra untimed pass timing every kernel (stderr)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -185,15 +187,36 @@ def main():
         pipe.step(batches[i % args.pool], rebuild=rebuild)
     torch.cuda.synchronize()
     assert pipe.poll() == 0, "device status after warmup"
+    graphs = None
+    if args.graph:
+        graphs = []
+        for b in batches:
+            gr = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gr):
+                pipe.step(b, rebuild=rebuild)
+            graphs.append(gr)
+        torch.cuda.synchronize()
+        desc += ", HIP graph replay"
 
     B.timing_reset()
-    B.timing_enable(1 << K_CONVERT)
+    if graphs is None:
+        B.timing_enable(1 << K_CONVERT)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
-        pipe.step(batches[i % args.pool], rebuild=rebuild)
+    if graphs is None:
+        for i in range(args.steps):
+            pipe.step(batches[i % args.pool], rebuild=rebuild)
+    else:
+        for i in range(args.steps):
+            graphs[i % args.pool].replay()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    if graphs is not None:
+        # the event timing of the dominant kernel cannot be recorded inside a graph: a separate eager pass
+        B.timing_enable(1 << K_CONVERT)
+        for i in range(min(args.steps, 10)):
+            pipe.step(batches[i % args.pool], rebuild=rebuild)
+        torch.cuda.synchronize()
     conv_ms, conv_launches = B.timing_read(K_CONVERT)
     B.timing_enable(0)
     assert pipe.poll() == 0, "device status after the timed region"
