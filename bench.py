@@ -28,7 +28,7 @@ def log(*a):
 
 
 def make_workload(name):
-    """(workload, per-user betas, scale, description, segmented) for a benchmark configuration."""
+    """(workload, per-user betas, scale, description) of one of the five benchmark configurations."""
     import co3_inputs as inp
     if name == "C3":
         w = inp.c3()

@@ -532,7 +532,7 @@ def _entropy(p):
     return float(-(p * np.log2(p)).sum())
 
 
-def test_model_table_matches_survey_estimates(golden_dir):
+def test_model_table_matches_independent_estimates(golden_dir):
     """Model pmf -> weights -> Huffman reproduces the independently computed rate table."""
     for line in _read_cases(os.path.join(golden_dir, "model_rate_estimates.txt")):
         lhs, nact, p0, H, Lbar = [p.strip() for p in line.split("|")]
@@ -556,7 +556,7 @@ def test_model_table_matches_survey_estimates(golden_dir):
         assert int((w > 0).sum()) == int(nact)
         l = oracle.huffman_lengths(w)
         got_L = float((p * l).sum())
-        # the anchor estimate may sit one binade off the survey's expected-maximum anchor; accept the
+        # the anchor estimate may sit one binade off the table's expected-maximum anchor; accept the
         # printed figures at either neighbouring anchor
         ok = False
         for dA in (0, 1, -1):
