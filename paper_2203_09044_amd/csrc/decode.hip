@@ -18,15 +18,14 @@ __device__ __forceinline__ const Co3Code *dcode_of(const void *codes, int u)
 // copy of the piece with q mod 16 == 0 at index 0) so that pieces q+1 and q are ring entries j and
 // j+1 of one two-address LDS read.  The rings of a wavefront are interleaved: entry j of lane l is
 // dword j*64 + l of the wavefront's area, so the bank of an access depends on the lane only and
-// lanes at different ring positions never conflict.  Blocks are requested one group of 8 symbols
+// lanes at different ring positions never conflict.  Blocks are requested one run of 16 symbols
 // ahead of their use, at a cadence that is the same for all lanes of the wavefront, so the
-// global-load latency hides behind the decoding of the previous group.
+// global-load latency hides behind the decoding of the previous run.
 // ------------------------------------------------------------------------------------------
 #define RING_ROWS 17
 #define RING_ROW_DW CO3_WAVE     // dwords between consecutive ring entries of one lane
 #define DE_GROUP 16          // symbols per run: one ring refill point, one 16-byte store
 #define DE_MISS_LEN 255u     // length field of a table entry that does not resolve a symbol
-typedef uint64_t u64_align4 __attribute__((aligned(4)));
 
 struct LaneStream {
     const uint4 *blocks;   // the user's stream as 16-byte blocks
