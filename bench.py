@@ -121,6 +121,9 @@ def main():
     ap.add_argument("--pool", type=int, default=3, help="distinct gradient batches cycled through")
     ap.add_argument("--graph", action="store_true",
                     help="capture one iteration per batch buffer in a HIP graph and time replays (launch-bound workloads)")
+    ap.add_argument("--sweep-c5", action="store_true",
+                    help="run the 12 points of C5 (4 formats x 3 shapes) one after the other, each in a child process, "
+                         "and print one line with elements/s and bits/element per point")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--breakdown", action="store_true", help="extra untimed pass timing every kernel (stderr)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -129,6 +132,28 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1")
+
+    if args.sweep_c5:
+        import subprocess
+        points, total_elems, total_s = [], 0.0, 0.0
+        for pt in range(12):
+            out = subprocess.run([sys.executable, os.path.abspath(__file__), "--workload", f"C5.{pt}", "--no-cpu",
+                                  "--steps", str(min(args.steps, 10)), "--warmup", "2", "--chunk", str(args.chunk)],
+                                 capture_output=True, text=True, check=True).stdout
+            r = json.loads([l for l in out.splitlines() if l.startswith("{")][-1])
+            points.append({"point": pt, "format": r["config"]["format"], "workload": r["config"]["workload"],
+                           "elements_per_s": r["value"], "ms_per_step": r["ms_per_step"],
+                           "bits_per_element": sum(r["bits_per_element"].values()),
+                           "path_roofline_frac": r["path_roofline"]["frac"]})
+            total_elems += r["config"]["U"] * r["config"]["n"] * r["steps"]
+            total_s += r["ms_per_step"] * 1e-3 * r["steps"]
+            log(f"[bench] C5.{pt} {r['config']['format']}: {r['value'] / 1e9:.1f} G elements/s, "
+                f"{points[-1]['bits_per_element']:.3f} bit/element")
+        print(json.dumps({"metric": "gradient elements/s (encode+decode, 1 GPU)", "value": total_elems / total_s,
+                          "unit": "elements/s", "n_gpus": 1, "higher_is_better": True, "data": "synthetic",
+                          "dtype": "f32", "config": {"workload": "C5 sweep: 16 clients x 25,000,000, 12 points"},
+                          "points": points}), flush=True)
+        return
 
     import torch
     assert torch.cuda.is_available(), "bench.py needs an MI355X"
