@@ -274,3 +274,44 @@ def test_c5_points(co3, point):
     syms = pipe.sym[:, :m].cpu().numpy()
     want = oracle.aggregate(syms, pipe.anchor.cpu().numpy(), oracle.Fmt(w.E, w.M))
     assert np.array_equal(u32(pipe.avg[:m]), want.view(np.uint32))
+
+
+def test_beyond_2_to_the_31_elements(co3):
+    """One client with 2^31 + 2^20 + 13 elements (the interface admits n < 2^32): every index computation must
+    be 64-bit.  Inputs are drawn on the device in pieces; the anchor is checked against torch's own maximum;
+    windows at the start, across element 2^31 and at the ragged end go through the oracle element by element
+    (symbols, memory, average); all elements through the size-independent properties."""
+    n = (1 << 31) + (1 << 20) + 13
+    fmt = co3.Fmt(3, 0)
+    f = oracle.Fmt(3, 0)
+    pipe = co3.Co3Pipeline(1, n, fmt, chunk_syms=256)
+    g = pipe.new_gradient_buffer()
+    piece = 1 << 28
+    for k, a in enumerate(range(0, n, piece)):
+        b = min(n, a + piece)
+        g[0, a:b] = inp.device_gennorm(b - a, 1.0, 1e-3, 8100 + k)
+    pipe.step(g)
+    assert pipe.poll() == 0
+    amax = float(g[0, :n].abs().max().item())
+    A = int(np.floor(np.log2(amax)))
+    assert int(pipe.anchor[0, 0].item()) == A
+    windows = [(0, 70_000), ((1 << 31) - 50_001, (1 << 31) + 50_003), (n - 66_001, n)]
+    for a, b in windows:
+        gh = g[0, a:b].cpu().numpy()
+        sym, e_new = oracle.convert_ef(gh, np.zeros(b - a, np.float32), np.array([A], np.int32), 1.0, f)
+        assert np.array_equal(pipe.sym[0, a:b].cpu().numpy(), sym), (a, b)
+        assert np.array_equal(u32(pipe.err[0, a:b]), e_new.view(np.uint32)), (a, b)
+        want = oracle.aggregate(sym[None, :], np.array([[A]], np.int32), f)
+        assert np.array_equal(u32(pipe.avg[a:b]), want.view(np.uint32)), (a, b)
+    # stream of the first window against the oracle's encoder (the code comes from the device histogram,
+    # itself checked against the symbols by the properties below)
+    cnt = u32(pipe.counts[0])
+    lens = oracle.huffman_lengths(cnt)
+    assert np.array_equal(pipe.codes[0, :fmt.K].cpu().numpy(), lens)
+    m = 65_536
+    words, off, total = oracle.encode(pipe.sym[0, :m].cpu().numpy(), lens, oracle.canonical_codes(lens), 256)
+    assert np.array_equal(u64(pipe.chunk_bitoff[0, :m // 256 + 1]), off)
+    assert np.array_equal(u64(pipe.words[0, :total // 64]), words[:total // 64])
+    hist = torch.bincount(pipe.sym[0, :n].to(torch.int32), minlength=fmt.K).cpu().numpy()
+    assert np.array_equal(hist, cnt.astype(np.int64))
+    properties_all_clients(pipe, n)
