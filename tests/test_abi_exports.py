@@ -68,6 +68,30 @@ def test_host_argument_checks_launch_nothing():
     assert L.co3_ps_aggregate(None, 1, None, 256, None, B.Fmt(3, 1).c(), 10, 1, None, None, 1, None, None, 0, None,
                               None) == B.EINVAL
     assert L.co3_poll_status(None, None) == B.EINVAL
+    ok = B.Fmt(3, 1).c()
+    assert L.co3_moments(None, None, 10, 1, 16, None, 1, 1.0, None, None) == B.EINVAL
+    assert L.co3_bias_scale(None, 10, 1, None, 1, None, None, None) == B.EINVAL
+    assert L.co3_convert_ef_scaled(None, None, None, 10, 1, 16, None, 1, None, None, 1.0, ok, None, None) == B.EINVAL
+    assert L.co3_ps_aggregate_scaled(None, 2, None, 256, None, ok, 10, 1, None, None, None, 1, None, None, 0, None,
+                                     None) == B.EINVAL
+    assert L.co3_histogram_layers(None, 10, 1, 16, None, 1, ok, 0, None, None) == B.EINVAL
+    assert L.co3_encode_layers(None, 10, 1, 16, ok, None, None, 1, None, 2, 256, None, None, None, 0, None,
+                               None) == B.EINVAL
+    assert L.co3_decode_layers(None, 2, None, 256, None, None, 1, ok, 10, 1, None, 16, None, None) == B.EINVAL
+    assert L.co3_ps_aggregate_layers(None, 2, None, 256, None, None, 1, ok, 10, 1, None, None, None, 1, None, None, 0,
+                                     None, None) == B.EINVAL
+    # sizes at and beyond the interface's limit (n < 2^32), with plausible non-null pointers: rejected before
+    # anything is launched
+    import ctypes as C
+    fake = C.c_void_p(1 << 20)
+    big = 1 << 32
+    assert L.co3_histogram(fake, big, 1, big, ok, fake, None) == B.EINVAL
+    assert L.co3_convert_ef(fake, fake, fake, big, 1, big, None, 1, fake, 0, 1.0, ok, None, None) == B.EINVAL
+    assert L.co3_moments(fake, fake, big, 1, big, None, 1, 1.0, fake, None) == B.EINVAL
+    assert L.co3_decode(fake, 2, fake, 256, fake, ok, big, 1, fake, big, None, None) == B.EINVAL
+    # users of a batch must be 16-element aligned rows at least n long
+    assert L.co3_histogram(fake, 100, 2, 100, ok, fake, None) == B.EINVAL
+    assert L.co3_histogram(fake, 100, 2, 96, ok, fake, None) == B.EINVAL
 
 
 def test_model_weights_host_matches_oracle_model():
