@@ -258,13 +258,17 @@ def main():
     conv_bytes = 12.0 * elems_step                     # k_convert_ef: read g, read m, write m
     achieved = conv_bytes / (conv_avg_ms * 1e-3) / 1e9 if conv_avg_ms > 0 else 0.0
 
+    # HBM traffic of the dominant kernel from the committed rocprofv3 counter summary (fetched + written MB)
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic_k_convert_ef_C3.json")
-    if args.workload == "C3" and os.path.exists(tpath):
-        try:
-            traffic = json.load(open(tpath)).get("traffic_bytes_per_launch")
-        except Exception:
-            traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_C3.txt")
+    if args.workload == "C3" and args.bias == "absmax" and args.codes == "user" and os.path.exists(tpath):
+        for line in open(tpath):
+            if line.startswith("k_convert_ef"):
+                try:
+                    traffic = float(line.split()[-1]) * 1e6
+                except ValueError:
+                    traffic = None
+                break
 
     if args.breakdown:
         B.timing_reset()

@@ -38,7 +38,8 @@ def kernel_stats(args):
     ours = [r for r in rows if re.search(r"\bk_[a-z0-9_]+", r["Name"])]
     total = sum(float(r["TotalDurationNs"]) for r in ours)
     print(f"# rocprofv3 --kernel-trace --stats, kernels of libco3 only (torch's input-generation kernels omitted)")
-    print(f"# command: {args.command}")
+    for line in args.command.split(";"):
+        print(f"# command: {line.strip()}")
     print(f"{'kernel':24s} {'calls':>6s} {'avg us':>10s} {'min us':>10s} {'max us':>10s} {'share of path':>14s}")
     for r in sorted(ours, key=lambda r: -float(r["TotalDurationNs"])):
         print(f"{short(r['Name']):24s} {int(r['Calls']):6d} {float(r['AverageNs']) / 1e3:10.2f} "
@@ -72,7 +73,8 @@ def traffic(args):
     print("# rocprofv3 --pmc FETCH_SIZE and --pmc WRITE_SIZE (one run each), per launch, scaled by the readings of a")
     print(f"# plain 1 GiB elementwise copy: FETCH_SIZE {f_read:.0f} -> x{f_scale / 1024:.3f} KiB per unit, "
           f"WRITE_SIZE {w_read:.0f} -> x{w_scale / 1024:.3f} KiB per unit")
-    print(f"# command: {args.command}")
+    for line in args.command.split(";"):
+        print(f"# command: {line.strip()}")
     print(f"{'kernel':24s} {'fetched MB':>12s} {'written MB':>12s} {'total MB':>10s}")
     res = {}
     for k in sorted(set(fetch) | set(write), key=lambda k: -(fetch.get(k, 0) * f_scale + write.get(k, 0) * w_scale)):
