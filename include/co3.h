@@ -114,7 +114,7 @@ int32_t co3_convert_ef(const float *g, float *err, uint8_t *sym, int64_t n, int3
                        co3_fmt fmt, uint32_t *counts, void *stream);
 
 /*
- * The bias of Sec. III (i) in the form the approximation of Sec. V gives it: a real multiplier c per
+ * The bias of Sec. III (i) in the form the approximation of Sec. IV-B gives it: a real multiplier c per
  * (user, tensor), c = (0.46 - 2.85 b + 5.37 b^2 - 2.85 b^3 + 0.52 b^4) / alpha with (b, alpha) the shape and
  * scale of the GenNorm law fitted to the corrected gradient x = g + gamma*m, applied as
  *     y = fl32(c * x);  sym = Q_A(y);  ghat = fl32(value_A(sym) / c);  err = fl32(x - ghat)

@@ -199,7 +199,7 @@ def bias_scale(beta: float, alpha: float) -> np.float32:
 
 
 def bias_scales(g, err, gamma, seg_off=None) -> np.ndarray:
-    """The multiplier per tensor that the bias rule of Sec. V assigns to x = g + gamma * err."""
+    """The multiplier per tensor that the bias rule of Sec. IV-B assigns to x = g + gamma * err."""
     so = _seg(seg_off, np.asarray(g).size)
     ms = moments(g, err, gamma, seg_off)
     out = np.zeros(so.size - 1, dtype=np.float32)

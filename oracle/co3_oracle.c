@@ -442,8 +442,8 @@ int co3o_aggregate(const uint8_t *sym, int64_t n, int U, int64_t stride, const i
 }
 
 /* ---------------------------------------------------------------------- */
-/* Sec. V, "fp exponent bias": the bias of Sec. III (i) as a function of   */
-/* the GenNorm parameters of the tensor.  The bias is read as a real       */
+/* Sec. IV-B, "fp exponent bias": the bias of Sec. III (i) as a function   */
+/* of the GenNorm parameters of the tensor.  The bias is read as a real    */
 /* multiplier c applied to the corrected gradient before it is rounded     */
 /* onto a fixed grid (the printed approximation scales as 1/sigma, which   */
 /* only a multiplier does), and "sigma" as the GenNorm scale parameter     */

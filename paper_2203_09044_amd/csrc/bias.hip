@@ -1,4 +1,4 @@
-// The bias rule of the paper in its multiplier form (Sec. III (i), Eq. (exp bias); Sec. V, "fp exponent
+// The bias rule of the paper in its multiplier form (Sec. III (i), Eq. (exp bias); Sec. IV-B, "fp exponent
 // bias", Eq. (approximate)): statistics of the corrected gradient per (user, tensor), a GenNorm fit
 // by moment matching, and the printed fourth-degree polynomial in the fitted shape divided by the
 // fitted scale.

@@ -156,7 +156,7 @@ __device__ __forceinline__ void co3_quantize(float x, int e_min, int A, int E, i
     val = __uint_as_float(__float_as_uint(mag) | (s << 31));
 }
 
-// SCALED: the bias in its multiplier form (Sec. III (i) with the approximation of Sec. V): the corrected
+// SCALED: the bias in its multiplier form (Sec. III (i) with the approximation of Sec. IV-B): the corrected
 // gradient is multiplied by c before it is rounded onto the grid of the given anchor, and the level
 // is divided by c again; one fp32 rounding per operation.
 template <bool HIST, bool SCALED>

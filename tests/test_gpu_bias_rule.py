@@ -1,4 +1,4 @@
-"""HIP path vs CPU oracle for the paper's bias rule (Sec. III (i), Eq. (exp bias); Sec. V,
+"""HIP path vs CPU oracle for the paper's bias rule (Sec. III (i), Eq. (exp bias); Sec. IV-B,
 Eq. (approximate)), through the C ABI (GPU only).
 
 Bars.  Moment sums: fp64 sums whose order of additions differs from the oracle's sequential order:

@@ -1,8 +1,8 @@
-"""Memory decay sweep on the paper's 4-bit format (Sec. III (iii); Sec. V "Error correction": format
-[sign mantissa exponent] = [1 2 1], i.e. E1M2, and decay values up to the paper's best 0.9): for
-gamma in {0, 0.1, 0.5, 0.9, 1} a chain of iterations is compared with the oracle bit for bit, and the
-diagnostic of that section (L1 norm of the memory relative to the L1 norm of the gradient) and the
-rate are read from the device and compared with the oracle's.
+"""Memory decay sweep (Sec. III (iii)) on the 4-bit format of Sec. IV-C ([sign mantissa exponent] =
+[1 2 1], i.e. E1M2; the best decay there is 0.9): for gamma in {0, 0.1, 0.5, 0.9, 1} a chain of
+iterations is compared with the oracle bit for bit, and the diagnostic of Sec. IV-B (L1 norm of the
+memory relative to the L1 norm of the gradient) and the rate are read from the device and compared
+with the oracle's.
 
 The two-rounding form x = fl32(g + fl32(gamma * m)) matters for every gamma that is not 0 or 1.
 """

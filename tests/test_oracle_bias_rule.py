@@ -1,4 +1,4 @@
-"""Pins for the oracle's statement of the paper's bias rule (Sec. III (i), Eq. (exp bias); Sec. V,
+"""Pins for the oracle's statement of the paper's bias rule (Sec. III (i), Eq. (exp bias); Sec. IV-B,
 Eq. (approximate)): moment sums, the GenNorm fit by moment matching, the printed polynomial, and the
 conversion / averaging with a real multiplier.
 
