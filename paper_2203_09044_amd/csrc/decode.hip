@@ -532,7 +532,7 @@ __global__ __launch_bounds__(PT_BLOCK) void k_ps_sum_tiled(const uint8_t *__rest
         for (int j = 0; j < 16; ++j) {
             const int cc = j * 4 + wr;
             const int64_t i = (tile * CO3_WAVE + cc) * chunk_syms + run0 + e;
-            if (i < n) avg_out[i] = out_s[cc][e];
+            if (i < n) __builtin_nontemporal_store(out_s[cc][e], avg_out + i);   // not read again here
         }
         __syncthreads();
     }
