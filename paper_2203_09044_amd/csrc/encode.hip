@@ -391,6 +391,12 @@ __global__ __launch_bounds__(EN_BLOCK) void k_enc_pack(const uint8_t *__restrict
     const int64_t i = tb * CO3_PACK_SYMS + (int64_t)lane * EN_LSYM;
     uint32_t s[4];
     const int nvalid = i < n ? load_syms16(su, i, n, s) : 0;
+    // the symbols that follow the tile (their codewords complete its last word): requested now, used at the end
+    const int64_t i2 = (tb + 1) * CO3_PACK_SYMS + lane;
+    const bool has_next = lane < CO3_WAVE - 1 && i2 < n;
+    const uint32_t next_sym = has_next ? su[i2] : 0u;
+    const uint64_t group_base = groupoff[(int64_t)u * ngrp + tb / CO3_PACK_GROUP];     // likewise
+    const uint64_t tile_base = tileoff[(int64_t)u * nblk + tb];
     // packed (codeword << 6 | length) of symbol sy at element idx
     auto entry_at = [&](uint32_t sy, int64_t idx) -> uint64_t {
         if (!LAYERS || one_tensor) return enc_s[sy];
@@ -416,7 +422,7 @@ __global__ __launch_bounds__(EN_BLOCK) void k_enc_pack(const uint8_t *__restrict
     const uint32_t excl = incl - mybits;
     const uint32_t tilebits = (uint32_t)__builtin_amdgcn_readlane((int)incl, CO3_WAVE - 1);
 
-    const uint64_t B0 = groupoff[(int64_t)u * ngrp + tb / CO3_PACK_GROUP] + tileoff[(int64_t)u * nblk + tb];
+    const uint64_t B0 = group_base + tile_base;
     const uint64_t B1 = B0 + tilebits;
 
     // chunk index: stream position of every chunk that starts at this lane's first symbol
@@ -449,8 +455,7 @@ __global__ __launch_bounds__(EN_BLOCK) void k_enc_pack(const uint8_t *__restrict
         }
         const uint32_t last_rel = (uint32_t)(gwl - gw0);
         if (B1 & 63) {          // complete the last word with the codewords that follow the tile
-            const int64_t i2 = (tb + 1) * CO3_PACK_SYMS + lane;
-            uint64_t e = (lane < CO3_WAVE - 1 && i2 < n) ? entry_at(su[i2], i2) : 0ull;
+            uint64_t e = has_next ? entry_at(next_sym, i2) : 0ull;
             uint32_t l = (uint32_t)(e & 63u);
             uint32_t o = wave_scan_incl_u32(l, lane) - l;
             const uint32_t used = (uint32_t)(B1 & 63);
@@ -502,8 +507,7 @@ __global__ __launch_bounds__(EN_BLOCK) void k_enc_pack(const uint8_t *__restrict
         // (at most 63 bits, hence at most 63 symbols), clipped at the word end.
         const int64_t last_rel = gwl - gw0 - win_w0;
         if ((B1 & 63) && last_rel >= 0 && last_rel < EN_STAGE_WORDS) {
-            const int64_t i2 = (tb + 1) * CO3_PACK_SYMS + lane;
-            uint64_t e = (lane < CO3_WAVE - 1 && i2 < n) ? entry_at(su[i2], i2) : 0ull;
+            uint64_t e = has_next ? entry_at(next_sym, i2) : 0ull;
             uint32_t l = (uint32_t)(e & 63u);
             uint32_t o = wave_scan_incl_u32(l, lane) - l;
             const uint32_t used = (uint32_t)(B1 & 63);
