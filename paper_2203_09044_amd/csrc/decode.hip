@@ -291,18 +291,6 @@ __device__ __forceinline__ void decode_range(const DecTables &t, LaneStream &ls,
     if (i < i1) partial(i1 - i);
 }
 
-// One lane decodes the `nsym` symbols of one chunk with one table.
-template <bool LONG>
-__device__ __forceinline__ bool decode_chunk(const DecTables &t, LaneStream &ls, uint64_t p0, uint64_t p1, int nsym,
-                                             uint8_t *out, int64_t run_step)
-{
-    bool ok = true;
-    ls.open(p0);
-    decode_range<LONG>(t, ls, 0, nsym, out, run_step, ok);
-    ls.land();
-    return ok && ls.pos() == p1;
-}
-
 // TILED = false: sym_out is [U][stride] symbols in order.  TILED = true: sym_out is the averaging
 // workspace, [U][tiles][chunk_syms/16][64 lanes][16 symbols] with tile = 64 consecutive chunks.
 template <bool TILED>
@@ -314,16 +302,22 @@ __global__ __launch_bounds__(DE_BLOCK) void k_decode(const uint64_t *__restrict_
     const int u = blockIdx.y;
     __shared__ DecTables t;
     __shared__ uint32_t ring[DE_BLOCK * RING_ROWS];
-    load_tables(t, dcode_of(codes, u));
-    __syncthreads();
 
+    // The chunk's stream position and its first blocks are requested before the tables are loaded, so
+    // that the three memory latencies at the start of a workgroup overlap.
     const int64_t c = (int64_t)blockIdx.x * DE_BLOCK + threadIdx.x;
-    if (c >= nchunks) return;
+    const bool active = c < nchunks;
     const uint64_t *off = chunk_bitoff + (int64_t)u * (nchunks + 1);
+    const uint64_t p0 = active ? off[c] : 0, p1 = active ? off[c + 1] : 0;
     LaneStream ls;
     ls.blocks = reinterpret_cast<const uint4 *>(words + (int64_t)u * cap_words);
     ls.nblocks = cap_words / 2;
     ls.slot = ring + (threadIdx.x / CO3_WAVE) * (RING_ROWS * RING_ROW_DW) + (threadIdx.x & (CO3_WAVE - 1));
+    if (active) ls.open(p0);
+    load_tables(t, dcode_of(codes, u));
+    __syncthreads();
+    if (!active) return;
+
     int64_t first = c * chunk_syms;
     int nsym = (int)(n - first < chunk_syms ? n - first : chunk_syms);
     uint8_t *out;
@@ -335,9 +329,11 @@ __global__ __launch_bounds__(DE_BLOCK) void k_decode(const uint64_t *__restrict_
         out = sym_out + (int64_t)u * stride + first;
         run_step = 16;
     }
-    const bool ok = t.maxlen > t.lut_bits ? decode_chunk<true>(t, ls, off[c], off[c + 1], nsym, out, run_step)
-                                          : decode_chunk<false>(t, ls, off[c], off[c + 1], nsym, out, run_step);
-    if (!ok) co3_raise(status, CO3_EBADSTREAM);
+    bool ok = true;
+    if (t.maxlen > t.lut_bits) decode_range<true>(t, ls, 0, nsym, out, run_step, ok);
+    else decode_range<false>(t, ls, 0, nsym, out, run_step, ok);
+    ls.land();
+    if (!(ok && ls.pos() == p1)) co3_raise(status, CO3_EBADSTREAM);
 }
 
 // Decompression with one code per tensor shared by all users (Sec. III (ii) as stated).  The workgroup
