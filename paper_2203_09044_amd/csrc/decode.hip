@@ -568,7 +568,7 @@ hipError_t co3_launch_ps_sum_tiled(const uint8_t *symt, int64_t n, int U, int64_
     const int64_t ntiles = (nchunks + CO3_WAVE - 1) / CO3_WAVE;
     const int64_t nruns = ntiles * (chunk_syms >> 4) * CO3_WAVE;
     int64_t b = (nruns + PT_BLOCK - 1) / PT_BLOCK;
-    unsigned blocks = (unsigned)(b < 8192 ? b : 8192);
+    unsigned blocks = (unsigned)(b < 16384 ? b : 16384);
     Co3LaunchTimer tm(CO3_K_PS_SUM, st);
     const size_t full_bytes = (size_t)U * (size_t)(1 << (1 + fmt.exp_bits + fmt.mant_bits)) * sizeof(float);
 #define CO3_SUM_LAUNCH(T, BYTES)                                                                                   \
