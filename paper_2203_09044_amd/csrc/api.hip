@@ -291,8 +291,8 @@ static int32_t decode_common(const uint64_t *words, int64_t cap_words, const uin
     if (!fmt_ok(fmt) || !batch_ok(n, U, stride) || !chunk_ok(chunk_syms) || cap_words < 0) return CO3_EINVAL;
     if (!words || !chunk_bitoff || !codes || !sym_out) return CO3_EINVAL;
     if (!aligned(sym_out, 16) || !aligned(words, 16) || !aligned(codes, 8) || cap_words % 2 != 0) return CO3_EINVAL;
-    return hip_rc(co3_launch_decode(words, cap_words, chunk_bitoff, chunk_syms, codes, code_seg_off, code_nseg, n, U,
-                                    sym_out, stride, 0, status, static_cast<hipStream_t>(stream)));
+    return hip_rc(co3_launch_decode(words, cap_words, chunk_bitoff, chunk_syms, codes, code_seg_off, code_nseg,
+                                    FmtC(fmt).K, n, U, sym_out, stride, 0, status, static_cast<hipStream_t>(stream)));
 }
 
 int32_t co3_decode(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff, int32_t chunk_syms,
@@ -331,8 +331,8 @@ static int32_t aggregate_common(const uint64_t *words, int64_t cap_words, const 
     const int64_t ws_stride = (int64_t)(need / (size_t)U);
     hipStream_t st = static_cast<hipStream_t>(stream);
     uint8_t *symws = static_cast<uint8_t *>(workspace);
-    hipError_t e = co3_launch_decode(words, cap_words, chunk_bitoff, chunk_syms, codes, code_seg_off, code_nseg, n, U,
-                                     symws, ws_stride, 1, status, st);
+    hipError_t e = co3_launch_decode(words, cap_words, chunk_bitoff, chunk_syms, codes, code_seg_off, code_nseg,
+                                     FmtC(fmt).K, n, U, symws, ws_stride, 1, status, st);
     if (e != hipSuccess) return CO3_EHIP;
     return hip_rc(
         co3_launch_ps_sum_tiled(symws, n, U, ws_stride, chunk_syms, anchor, scale, seg_off, nseg, fmt, avg_out, st));

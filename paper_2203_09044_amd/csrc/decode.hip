@@ -26,6 +26,9 @@ __device__ __forceinline__ const Co3Code *dcode_of(const void *codes, int u)
 #define RING_ROW_DW CO3_WAVE     // dwords between consecutive ring entries of one lane
 #define DE_GROUP 16          // symbols per run: one ring refill point, one 16-byte store
 #define DE_MISS_LEN 255u     // length field of a table entry that does not resolve a symbol
+#define DE_PAIR_BITS 12      // prefix length of the two-symbol table used for small alphabets
+#define DE_PAIR_MAX_K 16     // alphabets up to this size are decoded two symbols per lookup
+enum { DE_SHORT = 0, DE_LONG = 1, DE_PAIRS = 2 };   // fast-path variants of decode_range
 
 struct LaneStream {
     const uint4 *blocks;   // the user's stream as 16-byte blocks
@@ -157,6 +160,31 @@ __device__ __forceinline__ void load_tables(DecTables &t, const Co3Code *cd)
     }
 }
 
+// Two-symbol table for small alphabets (most pairs of codewords fit DE_PAIR_BITS bits there): entry i
+// describes the stream that starts with the DE_PAIR_BITS-bit prefix i.
+//   bits 0..7 first symbol, 8..15 second symbol, 16..23 length of the first codeword (DE_MISS_LEN when
+//   the prefix does not resolve it), 24..31 length of both codewords together, 0 when the prefix does
+//   not hold the whole second codeword.
+// The second codeword is looked up with the bits after the first one, zero-filled: a codeword that
+// ends inside the prefix is determined by its own bits alone (prefix-free code).
+__device__ __forceinline__ void build_pairs(const DecTables &t, uint32_t *pairs)
+{
+    const uint32_t down = DE_PAIR_BITS - t.lut_bits;
+    for (uint32_t i = threadIdx.x; i < (1u << DE_PAIR_BITS); i += blockDim.x) {
+        const uint32_t e1 = t.lut[i >> down];
+        const uint32_t l1 = e1 >> 8;
+        uint32_t entry = DE_MISS_LEN << 16;
+        if (l1 != DE_MISS_LEN) {
+            entry = (e1 & 0xffu) | (l1 << 16);
+            const uint32_t i2 = (i << l1) & ((1u << DE_PAIR_BITS) - 1u);
+            const uint32_t e2 = t.lut[i2 >> down];
+            const uint32_t l2 = e2 >> 8;
+            if (l2 != DE_MISS_LEN && l1 + l2 <= DE_PAIR_BITS) entry |= ((e2 & 0xffu) << 8) | ((l1 + l2) << 24);
+        }
+        pairs[i] = entry;
+    }
+}
+
 // Canonical decoding of a codeword longer than the table prefix: the first length l whose l-bit
 // prefix lies within that length's codeword range.  Returns the length, 0 if there is none.
 template <class Tables>
@@ -215,13 +243,17 @@ __device__ __forceinline__ void decode_run_careful(const DecTables &t, LaneStrea
 // canonical search (the lengths' upper limits are ordered), in a branch the wavefront skips when
 // no lane needs it.
 //
-// LONG = false is the instance for codes whose longest codeword fits the table prefix: there a miss can
+// DE_SHORT is the instance for codes whose longest codeword fits the table prefix: there a miss can
 // only come from an invalid stream; it advances by DE_MISS_LEN, more than 16 hits can, which the
-// validation catches.
-template <bool LONG>
+// validation catches.  DE_PAIRS reads the two-symbol table `pairs`: eight lookups per run; a lookup
+// whose prefix does not hold both codewords takes the second one from a lookup of its own (in a branch
+// the wavefront skips when no lane needs it), and a codeword longer than the prefix sends the run to
+// the careful path.
+template <int MODE>
 __device__ __forceinline__ void decode_range(const DecTables &t, LaneStream &ls, int i0, int i1, uint8_t *out,
-                                             int64_t run_step, bool &ok)
+                                             int64_t run_step, bool &ok, const uint32_t *pairs = nullptr)
 {
+    constexpr bool LONG = MODE == DE_LONG;
     const int shift = 32 - (int)t.lut_bits;
     int i = i0;
     // cnt < 16 symbols from symbol i on, inside one run
@@ -247,6 +279,36 @@ __device__ __forceinline__ void decode_range(const DecTables &t, LaneStream &ls,
         // bits 5..8 of m: one field extract, one two-address LDS read, one funnel shift.
         uint32_t m = 0u - rel0;
         bool bad = false;
+        if (MODE == DE_PAIRS) {
+#pragma unroll
+            for (int b = 0; b < DE_GROUP / 2; ++b) {
+                const uint32_t *pc = ls.slot + ((m >> 5) & 15u) * RING_ROW_DW;
+                const uint32_t win = __builtin_amdgcn_alignbit(pc[RING_ROW_DW], pc[0], m);
+                uint32_t e = pairs[win >> (32 - DE_PAIR_BITS)];
+                uint32_t adv = e >> 24;
+                if (adv == 0u) {      // the prefix does not hold two codewords (rare)
+                    const uint32_t l1 = (e >> 16) & 0xffu;
+                    if (l1 == DE_MISS_LEN) {
+                        bad = true;
+                        adv = 2u;
+                    } else {
+                        const uint32_t m1 = m - l1;
+                        const uint32_t *pc1 = ls.slot + ((m1 >> 5) & 15u) * RING_ROW_DW;
+                        const uint32_t win1 = __builtin_amdgcn_alignbit(pc1[RING_ROW_DW], pc1[0], m1);
+                        const uint32_t e2 = pairs[win1 >> (32 - DE_PAIR_BITS)];
+                        uint32_t l2 = (e2 >> 16) & 0xffu;
+                        if (l2 == DE_MISS_LEN) {
+                            bad = true;
+                            l2 = 1u;
+                        }
+                        adv = l1 + l2;
+                        e = (e & 0xffu) | ((e2 & 0xffu) << 8);
+                    }
+                }
+                m -= adv;
+                w[b >> 1] = __builtin_amdgcn_alignbit(e, w[b >> 1], 16);
+            }
+        } else {
 #pragma unroll
         for (int b = 0; b < DE_GROUP; ++b) {
             const uint32_t row = (m >> 5) & 15u;
@@ -279,10 +341,13 @@ __device__ __forceinline__ void decode_range(const DecTables &t, LaneStream &ls,
             m -= e >> 8;
             w[b >> 2] = __builtin_amdgcn_alignbit(e, w[b >> 2], 8);
         }
+        }
         ls.rel = 0u - m;
         // every window read above (up to three dwords from the current one) must have been resident
-        if (LONG ? (bad || ls.rel + 96u > ls.loaded * 128u)
-                 : (ls.rel - rel0 > DE_GROUP * CO3_LUT_BITS_MAX || ls.rel + 64u > ls.loaded * 128u)) {   // rare
+        if (MODE == DE_LONG    ? (bad || ls.rel + 96u > ls.loaded * 128u)
+            : MODE == DE_PAIRS ? (bad || ls.rel + 64u > ls.loaded * 128u)
+                               : (ls.rel - rel0 > DE_GROUP * CO3_LUT_BITS_MAX ||
+                                  ls.rel + 64u > ls.loaded * 128u)) {   // rare
             ls.rel = rel0;
             decode_run_careful(t, ls, shift, DE_GROUP, ok, w);
         }
@@ -293,7 +358,8 @@ __device__ __forceinline__ void decode_range(const DecTables &t, LaneStream &ls,
 
 // TILED = false: sym_out is [U][stride] symbols in order.  TILED = true: sym_out is the averaging
 // workspace, [U][tiles][chunk_syms/16][64 lanes][16 symbols] with tile = 64 consecutive chunks.
-template <bool TILED>
+// PAIRS: the workgroup also builds the two-symbol table (launched for alphabets of at most DE_PAIR_MAX_K symbols).
+template <bool TILED, bool PAIRS>
 __global__ __launch_bounds__(DE_BLOCK) void k_decode(const uint64_t *__restrict__ words, int64_t cap_words,
                                                       const uint64_t *__restrict__ chunk_bitoff, int chunk_syms,
                                                       int64_t nchunks, const void *__restrict__ codes, int64_t n,
@@ -302,6 +368,7 @@ __global__ __launch_bounds__(DE_BLOCK) void k_decode(const uint64_t *__restrict_
     const int u = blockIdx.y;
     __shared__ DecTables t;
     __shared__ uint32_t ring[DE_BLOCK * RING_ROWS];
+    __shared__ uint32_t pairs[PAIRS ? (1 << DE_PAIR_BITS) : 1];
 
     // The chunk's stream position and its first blocks are requested before the tables are loaded, so
     // that the three memory latencies at the start of a workgroup overlap.
@@ -316,6 +383,10 @@ __global__ __launch_bounds__(DE_BLOCK) void k_decode(const uint64_t *__restrict_
     if (active) ls.open(p0);
     load_tables(t, dcode_of(codes, u));
     __syncthreads();
+    if (PAIRS) {
+        build_pairs(t, pairs);
+        __syncthreads();
+    }
     if (!active) return;
 
     int64_t first = c * chunk_syms;
@@ -330,8 +401,9 @@ __global__ __launch_bounds__(DE_BLOCK) void k_decode(const uint64_t *__restrict_
         run_step = 16;
     }
     bool ok = true;
-    if (t.maxlen > t.lut_bits) decode_range<true>(t, ls, 0, nsym, out, run_step, ok);
-    else decode_range<false>(t, ls, 0, nsym, out, run_step, ok);
+    if (PAIRS) decode_range<DE_PAIRS>(t, ls, 0, nsym, out, run_step, ok, pairs);
+    else if (t.maxlen > t.lut_bits) decode_range<DE_LONG>(t, ls, 0, nsym, out, run_step, ok);
+    else decode_range<DE_SHORT>(t, ls, 0, nsym, out, run_step, ok);
     ls.land();
     if (!(ok && ls.pos() == p1)) co3_raise(status, CO3_EBADSTREAM);
 }
@@ -406,8 +478,8 @@ __global__ __launch_bounds__(DL_BLOCK) void k_decode_layers(const uint64_t *__re
             const DecTables &tl = t[cur_seg & (DL_SLOTS - 1)];
             const int64_t seg_end = seg_off[cur_seg + 1] - first;
             const int i1 = seg_end < nsym ? (int)seg_end : nsym;
-            if (any_long) decode_range<true>(tl, ls, cur, i1, out, run_step, ok);
-            else decode_range<false>(tl, ls, cur, i1, out, run_step, ok);
+            if (any_long) decode_range<DE_LONG>(tl, ls, cur, i1, out, run_step, ok);
+            else decode_range<DE_SHORT>(tl, ls, cur, i1, out, run_step, ok);
             cur = i1;
             if (cur < nsym) cur_seg = co3_find_seg(seg_off, nseg, first + cur);
         }
@@ -536,13 +608,16 @@ __global__ __launch_bounds__(PT_BLOCK) void k_ps_sum_tiled(const uint8_t *__rest
 
 // seg_off != NULL selects one code per tensor (codes[tensor], shared by the users) instead of codes[user]
 hipError_t co3_launch_decode(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff, int chunk_syms,
-                             const void *codes, const int64_t *seg_off, int nseg, int64_t n, int U, uint8_t *sym_out,
-                             int64_t stride, int tiled, int32_t *status, hipStream_t st)
+                             const void *codes, const int64_t *seg_off, int nseg, int K, int64_t n, int U,
+                             uint8_t *sym_out, int64_t stride, int tiled, int32_t *status, hipStream_t st)
 {
     const int64_t nchunks = (n + chunk_syms - 1) / chunk_syms;
     if (nchunks <= 0) return hipSuccess;
     unsigned blocks = (unsigned)((nchunks + DE_BLOCK - 1) / DE_BLOCK);
     const unsigned lblocks = (unsigned)((nchunks + DL_BLOCK - 1) / DL_BLOCK);
+#define CO3_DECODE_LAUNCH(T, P)                                                                                    \
+    hipLaunchKernelGGL((k_decode<T, P>), dim3(blocks, U), dim3(DE_BLOCK), 0, st, words, cap_words, chunk_bitoff,   \
+                       chunk_syms, nchunks, codes, n, sym_out, stride, status)
     Co3LaunchTimer tm(CO3_K_DECODE, st);
     if (seg_off && tiled)
         hipLaunchKernelGGL(k_decode_layers<true>, dim3(lblocks, U), dim3(DL_BLOCK), 0, st, words, cap_words,
@@ -550,12 +625,14 @@ hipError_t co3_launch_decode(const uint64_t *words, int64_t cap_words, const uin
     else if (seg_off)
         hipLaunchKernelGGL(k_decode_layers<false>, dim3(lblocks, U), dim3(DL_BLOCK), 0, st, words, cap_words,
                            chunk_bitoff, chunk_syms, nchunks, codes, seg_off, nseg, n, sym_out, stride, status);
-    else if (tiled)
-        hipLaunchKernelGGL(k_decode<true>, dim3(blocks, U), dim3(DE_BLOCK), 0, st, words, cap_words, chunk_bitoff,
-                           chunk_syms, nchunks, codes, n, sym_out, stride, status);
-    else
-        hipLaunchKernelGGL(k_decode<false>, dim3(blocks, U), dim3(DE_BLOCK), 0, st, words, cap_words, chunk_bitoff,
-                           chunk_syms, nchunks, codes, n, sym_out, stride, status);
+    else if (K <= DE_PAIR_MAX_K && chunk_syms >= DE_GROUP) {
+        if (tiled) CO3_DECODE_LAUNCH(true, true);
+        else CO3_DECODE_LAUNCH(false, true);
+    } else {
+        if (tiled) CO3_DECODE_LAUNCH(true, false);
+        else CO3_DECODE_LAUNCH(false, false);
+    }
+#undef CO3_DECODE_LAUNCH
     return hipGetLastError();
 }
 

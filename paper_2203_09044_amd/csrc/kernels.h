@@ -34,8 +34,8 @@ hipError_t co3_launch_encode(const uint8_t *sym, int64_t n, int U, int64_t strid
                              uint64_t *chunk_bitoff, uint64_t *total_bits, uint64_t *tilesum, int32_t *status,
                              hipStream_t st);
 hipError_t co3_launch_decode(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff, int chunk_syms,
-                             const void *codes, const int64_t *seg_off, int nseg, int64_t n, int U, uint8_t *sym_out,
-                             int64_t stride, int tiled, int32_t *status, hipStream_t st);
+                             const void *codes, const int64_t *seg_off, int nseg, int K, int64_t n, int U,
+                             uint8_t *sym_out, int64_t stride, int tiled, int32_t *status, hipStream_t st);
 hipError_t co3_launch_ps_sum_tiled(const uint8_t *symt, int64_t n, int U, int64_t ws_stride, int chunk_syms,
                                    const int32_t *anchor, const float *scale, const int64_t *seg_off, int nseg,
                                    co3_fmt fmt, float *avg_out, hipStream_t st);
