@@ -165,8 +165,11 @@ __device__ __forceinline__ void load_tables(DecTables &t, const Co3Code *cd)
 //   bits 0..7 first symbol, 8..15 second symbol, 16..23 length of the first codeword (DE_MISS_LEN when
 //   the prefix does not resolve it), 24..31 length of both codewords together, 0 when the prefix does
 //   not hold the whole second codeword.
+// NIB (symbols of at most four bits): both symbols share the low byte instead, the second one in its
+// upper half, the form in which the averaging workspace stores them.
 // The second codeword is looked up with the bits after the first one, zero-filled: a codeword that
 // ends inside the prefix is determined by its own bits alone (prefix-free code).
+template <bool NIB>
 __device__ __forceinline__ void build_pairs(const DecTables &t, uint32_t *pairs)
 {
     const uint32_t down = DE_PAIR_BITS - t.lut_bits;
@@ -179,7 +182,8 @@ __device__ __forceinline__ void build_pairs(const DecTables &t, uint32_t *pairs)
             const uint32_t i2 = (i << l1) & ((1u << DE_PAIR_BITS) - 1u);
             const uint32_t e2 = t.lut[i2 >> down];
             const uint32_t l2 = e2 >> 8;
-            if (l2 != DE_MISS_LEN && l1 + l2 <= DE_PAIR_BITS) entry |= ((e2 & 0xffu) << 8) | ((l1 + l2) << 24);
+            if (l2 != DE_MISS_LEN && l1 + l2 <= DE_PAIR_BITS)
+                entry |= ((e2 & 0xffu) << (NIB ? 4 : 8)) | ((l1 + l2) << 24);
         }
         pairs[i] = entry;
     }
@@ -229,6 +233,28 @@ __device__ __forceinline__ void decode_run_careful(const DecTables &t, LaneStrea
     ls.ensure(((ls.rel >> 7) + 3u) * 4u);
 }
 
+// Two-symbol entry e read at position m holds only its first codeword: the entry completed with the
+// second codeword from a lookup of its own (the combined length in the top byte).
+template <bool NIB>
+__device__ __forceinline__ uint32_t pair_second(const LaneStream &ls, const uint32_t *pairs, uint32_t e, uint32_t m,
+                                                bool &bad)
+{
+    const uint32_t l1 = (e >> 16) & 0xffu;
+    if (l1 == DE_MISS_LEN) {     // not even the first codeword: the careful path takes the run
+        bad = true;
+        return 2u << 24;
+    }
+    const uint32_t m1 = m - l1;
+    const uint32_t *pc1 = ls.slot + ((m1 >> 5) & 15u) * RING_ROW_DW;
+    const uint32_t e2 = pairs[__builtin_amdgcn_alignbit(pc1[RING_ROW_DW], pc1[0], m1) >> (32 - DE_PAIR_BITS)];
+    uint32_t l2 = (e2 >> 16) & 0xffu;
+    if (l2 == DE_MISS_LEN) {
+        bad = true;
+        l2 = 1u;
+    }
+    return (e & 0xffu) | ((e2 & 0xffu) << (NIB ? 4 : 8)) | ((l1 + l2) << 24);
+}
+
 // One lane decodes symbols [i0, i1) of its chunk; the stream is open at symbol i0.  Symbols leave in
 // runs of 16: run r is stored at out + r * run_step (run_step = 16 gives the plain contiguous layout;
 // the tiled layout used between decoding and averaging interleaves the runs of the 64 chunks of a
@@ -269,6 +295,36 @@ __device__ __forceinline__ void decode_range(const DecTables &t, LaneStream &ls,
         i += cnt;
     };
     if ((i & 15) != 0 && i < i1) partial(16 - (i & 15) < i1 - i ? 16 - (i & 15) : i1 - i);
+    if (MODE == DE_PAIRS) {
+        // two runs per refill point: with at most four bits per symbol on average the blocks requested
+        // at one boundary cover the 32 symbols up to the next one
+#pragma unroll 1
+        for (; i + 2 * DE_GROUP <= i1; i += 2 * DE_GROUP) {
+            ls.group_boundary();
+            const uint32_t rel0 = ls.rel;
+            uint32_t w[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
+            uint32_t m = 0u - rel0;
+            bool bad = false;
+#pragma unroll
+            for (int b = 0; b < DE_GROUP; ++b) {
+                const uint32_t *pc = ls.slot + ((m >> 5) & 15u) * RING_ROW_DW;
+                const uint32_t win = __builtin_amdgcn_alignbit(pc[RING_ROW_DW], pc[0], m);
+                uint32_t e = pairs[win >> (32 - DE_PAIR_BITS)];
+                if ((e >> 24) == 0u) e = pair_second<false>(ls, pairs, e, m, bad);
+                m -= e >> 24;
+                w[b >> 1] = __builtin_amdgcn_alignbit(e, w[b >> 1], 16);
+            }
+            ls.rel = 0u - m;
+            if (bad || ls.rel + 64u > ls.loaded * 128u) {   // rare
+                ls.rel = rel0;
+                decode_run_careful(t, ls, shift, DE_GROUP, ok, w);
+                decode_run_careful(t, ls, shift, DE_GROUP, ok, w + 4);
+            }
+            uint8_t *dst = out + (int64_t)(i >> 4) * run_step;
+            *reinterpret_cast<uint4 *>(dst) = make_uint4(w[0], w[1], w[2], w[3]);
+            *reinterpret_cast<uint4 *>(dst + run_step) = make_uint4(w[4], w[5], w[6], w[7]);
+        }
+    }
 #pragma unroll 1
     for (; i + DE_GROUP <= i1; i += DE_GROUP) {
         ls.group_boundary();
@@ -285,27 +341,8 @@ __device__ __forceinline__ void decode_range(const DecTables &t, LaneStream &ls,
                 const uint32_t *pc = ls.slot + ((m >> 5) & 15u) * RING_ROW_DW;
                 const uint32_t win = __builtin_amdgcn_alignbit(pc[RING_ROW_DW], pc[0], m);
                 uint32_t e = pairs[win >> (32 - DE_PAIR_BITS)];
-                uint32_t adv = e >> 24;
-                if (adv == 0u) {      // the prefix does not hold two codewords (rare)
-                    const uint32_t l1 = (e >> 16) & 0xffu;
-                    if (l1 == DE_MISS_LEN) {
-                        bad = true;
-                        adv = 2u;
-                    } else {
-                        const uint32_t m1 = m - l1;
-                        const uint32_t *pc1 = ls.slot + ((m1 >> 5) & 15u) * RING_ROW_DW;
-                        const uint32_t win1 = __builtin_amdgcn_alignbit(pc1[RING_ROW_DW], pc1[0], m1);
-                        const uint32_t e2 = pairs[win1 >> (32 - DE_PAIR_BITS)];
-                        uint32_t l2 = (e2 >> 16) & 0xffu;
-                        if (l2 == DE_MISS_LEN) {
-                            bad = true;
-                            l2 = 1u;
-                        }
-                        adv = l1 + l2;
-                        e = (e & 0xffu) | ((e2 & 0xffu) << 8);
-                    }
-                }
-                m -= adv;
+                if ((e >> 24) == 0u) e = pair_second<false>(ls, pairs, e, m, bad);   // rare
+                m -= e >> 24;
                 w[b >> 1] = __builtin_amdgcn_alignbit(e, w[b >> 1], 16);
             }
         } else {
@@ -356,9 +393,64 @@ __device__ __forceinline__ void decode_range(const DecTables &t, LaneStream &ls,
     if (i < i1) partial(i1 - i);
 }
 
+// A whole chunk of an alphabet of at most 16 symbols, written in the packed form of the averaging
+// workspace: two symbols per byte (the earlier one in the low half), 32 symbols per 16-byte store, run r
+// of 32 symbols at out + r * run_step.  One refill point per 32 symbols: with at most four bits per
+// symbol on average the blocks requested at one boundary cover the symbols up to the next one.
+__device__ __forceinline__ void decode_chunk_packed(const DecTables &t, LaneStream &ls, int nsym, uint8_t *out,
+                                                    int64_t run_step, bool &ok, const uint32_t *pairs)
+{
+    const int shift = 32 - (int)t.lut_bits;
+    // cnt <= 32 symbols by the careful path, packed; the rest of the 16 bytes is zero
+    auto careful = [&](int cnt, uint32_t w[4]) {
+        uint32_t b[8];
+        decode_run_careful(t, ls, shift, cnt < DE_GROUP ? cnt : DE_GROUP, ok, b);
+        if (cnt > DE_GROUP) decode_run_careful(t, ls, shift, cnt - DE_GROUP, ok, b + 4);
+        else b[4] = b[5] = b[6] = b[7] = 0u;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {      // bytes 0x0d0c0b0a, 0x0h0g0f0e -> nibbles 0xhgfedcba
+            const uint32_t lo = b[2 * k], hi = b[2 * k + 1];
+            const uint32_t l2 = (lo | (lo >> 4)) & 0x00ff00ffu, h2 = (hi | (hi >> 4)) & 0x00ff00ffu;
+            w[k] = ((l2 | (l2 >> 8)) & 0xffffu) | (((h2 | (h2 >> 8)) & 0xffffu) << 16);
+        }
+    };
+    int i = 0;
+#pragma unroll 1
+    for (; i + 2 * DE_GROUP <= nsym; i += 2 * DE_GROUP) {
+        ls.group_boundary();
+        const uint32_t rel0 = ls.rel;
+        uint32_t w[4] = {0u, 0u, 0u, 0u};
+        uint32_t m = 0u - rel0;
+        bool bad = false;
+#pragma unroll
+        for (int b = 0; b < DE_GROUP; ++b) {
+            const uint32_t *pc = ls.slot + ((m >> 5) & 15u) * RING_ROW_DW;
+            const uint32_t win = __builtin_amdgcn_alignbit(pc[RING_ROW_DW], pc[0], m);
+            uint32_t e = pairs[win >> (32 - DE_PAIR_BITS)];
+            if ((e >> 24) == 0u) e = pair_second<true>(ls, pairs, e, m, bad);   // rare
+            m -= e >> 24;
+            w[b >> 2] = __builtin_amdgcn_alignbit(e, w[b >> 2], 8);
+        }
+        ls.rel = 0u - m;
+        if (bad || ls.rel + 64u > ls.loaded * 128u) {   // rare: see decode_range
+            ls.rel = rel0;
+            careful(2 * DE_GROUP, w);
+        }
+        *reinterpret_cast<uint4 *>(out + (int64_t)(i >> 5) * run_step) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+    if (i < nsym) {                        // ragged end of the vector
+        ls.group_boundary();
+        uint32_t w[4];
+        careful(nsym - i, w);
+        *reinterpret_cast<uint4 *>(out + (int64_t)(i >> 5) * run_step) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+}
+
 // TILED = false: sym_out is [U][stride] symbols in order.  TILED = true: sym_out is the averaging
 // workspace, [U][tiles][chunk_syms/16][64 lanes][16 symbols] with tile = 64 consecutive chunks.
-// PAIRS: the workgroup also builds the two-symbol table (launched for alphabets of at most DE_PAIR_MAX_K symbols).
+// PAIRS: the workgroup also builds the two-symbol table (launched for alphabets of at most DE_PAIR_MAX_K
+// symbols and chunks of at least 32); with TILED the workspace then holds two symbols per byte,
+// [U][tiles][chunk_syms/32][64 lanes][32 symbols in 16 bytes].
 template <bool TILED, bool PAIRS>
 __global__ __launch_bounds__(DE_BLOCK) void k_decode(const uint64_t *__restrict__ words, int64_t cap_words,
                                                       const uint64_t *__restrict__ chunk_bitoff, int chunk_syms,
@@ -366,9 +458,15 @@ __global__ __launch_bounds__(DE_BLOCK) void k_decode(const uint64_t *__restrict_
                                                       uint8_t *__restrict__ sym_out, int64_t stride, int32_t *status)
 {
     const int u = blockIdx.y;
-    __shared__ DecTables t;
-    __shared__ uint32_t ring[DE_BLOCK * RING_ROWS];
-    __shared__ uint32_t pairs[PAIRS ? (1 << DE_PAIR_BITS) : 1];
+    // tables first: their LDS offsets then fit the immediate field of the read instructions
+    __shared__ struct {
+        uint32_t pairs[PAIRS ? (1 << DE_PAIR_BITS) : 1];
+        DecTables t;
+        alignas(256) uint32_t ring[DE_BLOCK * RING_ROWS];   // a multiple of the ring row: row offsets stay immediates
+    } lds;
+    DecTables &t = lds.t;
+    uint32_t *const ring = lds.ring;
+    uint32_t *const pairs = lds.pairs;
 
     // The chunk's stream position and its first blocks are requested before the tables are loaded, so
     // that the three memory latencies at the start of a workgroup overlap.
@@ -384,7 +482,7 @@ __global__ __launch_bounds__(DE_BLOCK) void k_decode(const uint64_t *__restrict_
     load_tables(t, dcode_of(codes, u));
     __syncthreads();
     if (PAIRS) {
-        build_pairs(t, pairs);
+        build_pairs<TILED>(t, pairs);
         __syncthreads();
     }
     if (!active) return;
@@ -394,14 +492,16 @@ __global__ __launch_bounds__(DE_BLOCK) void k_decode(const uint64_t *__restrict_
     uint8_t *out;
     int64_t run_step;
     if (TILED) {
-        out = sym_out + (int64_t)u * stride + (c >> 6) * ((int64_t)CO3_WAVE * chunk_syms) + (c & 63) * 16;
+        const int64_t tile_bytes = (int64_t)CO3_WAVE * (PAIRS ? chunk_syms >> 1 : chunk_syms);
+        out = sym_out + (int64_t)u * stride + (c >> 6) * tile_bytes + (c & 63) * 16;
         run_step = CO3_WAVE * 16;
     } else {
         out = sym_out + (int64_t)u * stride + first;
         run_step = 16;
     }
     bool ok = true;
-    if (PAIRS) decode_range<DE_PAIRS>(t, ls, 0, nsym, out, run_step, ok, pairs);
+    if (PAIRS && TILED) decode_chunk_packed(t, ls, nsym, out, run_step, ok, pairs);
+    else if (PAIRS) decode_range<DE_PAIRS>(t, ls, 0, nsym, out, run_step, ok, pairs);
     else if (t.maxlen > t.lut_bits) decode_range<DE_LONG>(t, ls, 0, nsym, out, run_step, ok);
     else decode_range<DE_SHORT>(t, ls, 0, nsym, out, run_step, ok);
     ls.land();
@@ -492,26 +592,30 @@ __global__ __launch_bounds__(DL_BLOCK) void k_decode_layers(const uint64_t *__re
 }
 
 // ---- average of the reconstructed gradients: users added in index order, one division -----
-// Average from the tiled workspace: one thread owns a run of 16 consecutive elements.
-#define PT_BLOCK 256
+// Average from the tiled workspace: one thread owns the 16 bytes of one run, 16 consecutive elements
+// (NIB, two symbols per byte: 32).  A workgroup of PT_WAVES wavefronts takes that many consecutive runs
+// of one tile of 64 chunks.
+#define PT_WAVES(NIB) ((NIB) ? 2 : 4)
 
 // TABLE != 0 (one tensor, i.e. one anchor per user): the values of every user's symbols are computed
 // once per block into LDS, and an element costs one LDS read and one add.  TABLE = 1 keeps all K
 // values; TABLE = 2 (larger alphabets) keeps the K/2 magnitudes and applies the sign bit after the
 // read, halving the LDS footprint.
-template <int TABLE>
-__global__ __launch_bounds__(PT_BLOCK) void k_ps_sum_tiled(const uint8_t *__restrict__ symt, int64_t n, int U,
+template <int TABLE, bool NIB>
+__global__ __launch_bounds__(PT_WAVES(NIB) * CO3_WAVE) void k_ps_sum_tiled(const uint8_t *__restrict__ symt, int64_t n, int U,
                                                             int64_t ws_stride, int chunk_syms, int64_t nruns,
                                                             const int32_t *__restrict__ anchor,
                                                             const float *__restrict__ scale,
                                                             const int64_t *__restrict__ seg_off_g, int nseg,
                                                             co3_fmt fmt, float *__restrict__ avg_out)
 {
+    constexpr int EPT = NIB ? 32 : 16;     // elements per thread
+    constexpr int WAVES = PT_WAVES(NIB), PT_BLOCK = WAVES * CO3_WAVE;
     const FmtC fc(fmt);
     const int EM = fc.E + fc.M, M = fc.M, F = fc.F;
     const uint32_t cmask = (uint32_t)fc.codemax;
     const float fU = (float)U;
-    const int runs_per_chunk = chunk_syms >> 4;
+    const int runs_per_chunk = chunk_syms / EPT;
     // value of symbol s of user u in tensor sg; with multipliers (scale != NULL) the level is divided by
     // the user's multiplier, one fp32 rounding
     auto value = [&](uint32_t s, int u, int sg) -> float {
@@ -519,6 +623,10 @@ __global__ __launch_bounds__(PT_BLOCK) void k_ps_sum_tiled(const uint8_t *__rest
         float v = __uint_as_float(__float_as_uint(co3_code_value(s & cmask, e_min, M)) | ((s >> EM) << 31));
         if (scale) v = v / scale[(int64_t)u * nseg + sg];
         return v;
+    };
+    // symbol k of the 16 bytes w
+    auto symbol = [&](const uint32_t (&w)[4], int k) -> uint32_t {
+        return NIB ? (w[k >> 3] >> (4 * (k & 7))) & 0xfu : (w[k >> 2] >> (8 * (k & 3))) & 0xffu;
     };
     __shared__ int64_t seg_cache[TABLE ? 1 : CO3_SEG_CACHE];     // TABLE: one tensor, nothing to look up
     const int64_t *seg_off = TABLE ? seg_off_g : co3_cache_segs(seg_off_g, nseg, seg_cache);
@@ -531,11 +639,12 @@ __global__ __launch_bounds__(PT_BLOCK) void k_ps_sum_tiled(const uint8_t *__rest
         }
         __syncthreads();
     }
-    // One block step covers one tile (64 chunks) x 4 consecutive runs: each wavefront one run, each lane
-    // one chunk (nruns is a multiple of 256 and a chunk has a multiple of 4 runs).  The 64 results per
-    // chunk are contiguous in the output; they pass through LDS so that every store instruction of a
-    // wavefront writes 256 contiguous bytes.
-    __shared__ float out_s[CO3_WAVE][CO3_WAVE + 1];
+    // One block step covers one tile (64 chunks) x WAVES consecutive runs: each wavefront one run, each
+    // lane one chunk (a chunk has a multiple of WAVES runs).  The WAVES * EPT results per chunk are
+    // contiguous in the output; they pass through LDS so that every store instruction of a wavefront
+    // writes 256 contiguous bytes.
+    constexpr int ROW = WAVES * EPT;       // 64 elements in both layouts
+    __shared__ float out_s[CO3_WAVE][ROW + 1];
     for (int64_t rb = (int64_t)blockIdx.x * PT_BLOCK; rb < nruns; rb += (int64_t)gridDim.x * PT_BLOCK) {
         // r enumerates (tile, run within chunk, lane) with the lane fastest: the workspace order
         const int64_t r = rb + threadIdx.x;
@@ -544,14 +653,14 @@ __global__ __launch_bounds__(PT_BLOCK) void k_ps_sum_tiled(const uint8_t *__rest
         const int64_t q = r >> 6;
         const int run = (int)(q % runs_per_chunk);
         const int64_t tile = q / runs_per_chunk;
-        const int64_t i0 = (tile * CO3_WAVE + lane) * chunk_syms + (int64_t)run * 16;
+        const int64_t i0 = (tile * CO3_WAVE + lane) * chunk_syms + (int64_t)run * EPT;
         const uint8_t *src = symt + r * 16;
-        float acc[16];
+        float acc[EPT];
 #pragma unroll
-        for (int k = 0; k < 16; ++k) acc[k] = 0.f;
+        for (int k = 0; k < EPT; ++k) acc[k] = 0.f;
         const int64_t i_first = i0 < n ? i0 : n - 1;       // lanes past the end compute on the last element's
         const int s_lo = co3_find_seg(seg_off, nseg, i_first);   // tensor and store nothing
-        const int64_t i_last = i0 + 15 < n ? i0 + 15 : n - 1;
+        const int64_t i_last = i0 + EPT - 1 < n ? i0 + EPT - 1 : n - 1;
         const int s_hi = co3_find_seg(seg_off, nseg, i_last);
         if (i0 >= n) {
         } else if (TABLE) {
@@ -560,8 +669,8 @@ __global__ __launch_bounds__(PT_BLOCK) void k_ps_sum_tiled(const uint8_t *__rest
                 uint4 v = ld_stream_u4(src + (int64_t)u * ws_stride);
                 uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-                for (int k = 0; k < 16; ++k) {
-                    const uint32_t sy = w[k >> 2] >> (8 * (k & 3));
+                for (int k = 0; k < EPT; ++k) {
+                    const uint32_t sy = symbol(w, k);
                     if (TABLE == 1) acc[k] += vu[sy & ((uint32_t)fc.K - 1u)];
                     else acc[k] += __uint_as_float(__float_as_uint(vu[sy & cmask]) | (((sy >> EM) & 1u) << 31));
                 }
@@ -573,8 +682,8 @@ __global__ __launch_bounds__(PT_BLOCK) void k_ps_sum_tiled(const uint8_t *__rest
                 uint4 v = *reinterpret_cast<const uint4 *>(src + (int64_t)u * ws_stride);
                 uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-                for (int k = 0; k < 16; ++k) {
-                    uint32_t s = (w[k >> 2] >> (8 * (k & 3))) & 0xffu;
+                for (int k = 0; k < EPT; ++k) {
+                    uint32_t s = symbol(w, k);
                     float val = co3_code_value(s & cmask, e_min, M);
                     val = __uint_as_float(__float_as_uint(val) | ((s >> EM) << 31));
                     acc[k] += scale ? val / c : val;
@@ -585,20 +694,20 @@ __global__ __launch_bounds__(PT_BLOCK) void k_ps_sum_tiled(const uint8_t *__rest
                 uint4 v = *reinterpret_cast<const uint4 *>(src + (int64_t)u * ws_stride);
                 uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-                for (int k = 0; k < 16; ++k) {
+                for (int k = 0; k < EPT; ++k) {
                     int sg = co3_find_seg(seg_off, nseg, i0 + k < n ? i0 + k : n - 1);
-                    acc[k] += value((w[k >> 2] >> (8 * (k & 3))) & 0xffu, u, sg);
+                    acc[k] += value(symbol(w, k), u, sg);
                 }
             }
         }
 #pragma unroll
-        for (int k = 0; k < 16; ++k) out_s[lane][wr * 16 + k] = acc[k] / fU;
+        for (int k = 0; k < EPT; ++k) out_s[lane][wr * EPT + k] = acc[k] / fU;
         __syncthreads();
-        const int64_t run0 = (int64_t)(run - wr) * 16;       // first element (within a chunk) of the block's 4 runs
-        const int e = threadIdx.x & 63;
+        const int64_t run0 = (int64_t)(run - wr) * EPT;      // first element (within a chunk) of the block's runs
 #pragma unroll 4
-        for (int j = 0; j < 16; ++j) {
-            const int cc = j * 4 + wr;
+        for (int j = 0; j < CO3_WAVE; j += WAVES) {
+            const int idx = (j + wr) * CO3_WAVE + (threadIdx.x & 63);   // element of the [64][ROW] tile, row-major
+            const int cc = idx / ROW, e = idx % ROW;
             const int64_t i = (tile * CO3_WAVE + cc) * chunk_syms + run0 + e;
             if (i < n) __builtin_nontemporal_store(out_s[cc][e], avg_out + i);   // not read again here
         }
@@ -625,7 +734,7 @@ hipError_t co3_launch_decode(const uint64_t *words, int64_t cap_words, const uin
     else if (seg_off)
         hipLaunchKernelGGL(k_decode_layers<false>, dim3(lblocks, U), dim3(DL_BLOCK), 0, st, words, cap_words,
                            chunk_bitoff, chunk_syms, nchunks, codes, seg_off, nseg, n, sym_out, stride, status);
-    else if (K <= DE_PAIR_MAX_K && chunk_syms >= DE_GROUP) {
+    else if (co3_ws_packed(K, chunk_syms, false)) {
         if (tiled) CO3_DECODE_LAUNCH(true, true);
         else CO3_DECODE_LAUNCH(false, true);
     } else {
@@ -638,22 +747,26 @@ hipError_t co3_launch_decode(const uint64_t *words, int64_t cap_words, const uin
 
 hipError_t co3_launch_ps_sum_tiled(const uint8_t *symt, int64_t n, int U, int64_t ws_stride, int chunk_syms,
                                    const int32_t *anchor, const float *scale, const int64_t *seg_off, int nseg,
-                                   co3_fmt fmt, float *avg_out, hipStream_t st)
+                                   co3_fmt fmt, int packed, float *avg_out, hipStream_t st)
 {
     if (n <= 0) return hipSuccess;
     const int64_t nchunks = (n + chunk_syms - 1) / chunk_syms;
     const int64_t ntiles = (nchunks + CO3_WAVE - 1) / CO3_WAVE;
-    const int64_t nruns = ntiles * (chunk_syms >> 4) * CO3_WAVE;
-    int64_t b = (nruns + PT_BLOCK - 1) / PT_BLOCK;
+    const int64_t nruns = ntiles * (chunk_syms >> (packed ? 5 : 4)) * CO3_WAVE;   // 16-byte pieces of one user
+    const int threads = PT_WAVES(packed) * CO3_WAVE;
+    int64_t b = (nruns + threads - 1) / threads;
     unsigned blocks = (unsigned)(b < 16384 ? b : 16384);
     Co3LaunchTimer tm(CO3_K_PS_SUM, st);
     const size_t full_bytes = (size_t)U * (size_t)(1 << (1 + fmt.exp_bits + fmt.mant_bits)) * sizeof(float);
-#define CO3_SUM_LAUNCH(T, BYTES)                                                                                   \
-    hipLaunchKernelGGL(k_ps_sum_tiled<T>, dim3(blocks), dim3(PT_BLOCK), BYTES, st, symt, n, U, ws_stride, chunk_syms, \
-                       nruns, anchor, scale, seg_off, nseg, fmt, avg_out)
-    if (nseg == 1 && full_bytes <= 4096) CO3_SUM_LAUNCH(1, full_bytes);
-    else if (nseg == 1 && full_bytes / 2 <= 32768) CO3_SUM_LAUNCH(2, full_bytes / 2);
-    else CO3_SUM_LAUNCH(0, 0);
+#define CO3_SUM_LAUNCH(T, P, BYTES)                                                                                \
+    hipLaunchKernelGGL((k_ps_sum_tiled<T, P>), dim3(blocks), dim3(threads), BYTES, st, symt, n, U, ws_stride,     \
+                       chunk_syms, nruns, anchor, scale, seg_off, nseg, fmt, avg_out)
+    if (packed) {       // alphabets of at most 16 symbols: the full table is 64 bytes per user
+        if (nseg == 1 && full_bytes <= 4096) CO3_SUM_LAUNCH(1, true, full_bytes);
+        else CO3_SUM_LAUNCH(0, true, 0);
+    } else if (nseg == 1 && full_bytes <= 4096) CO3_SUM_LAUNCH(1, false, full_bytes);
+    else if (nseg == 1 && full_bytes / 2 <= 32768) CO3_SUM_LAUNCH(2, false, full_bytes / 2);
+    else CO3_SUM_LAUNCH(0, false, 0);
 #undef CO3_SUM_LAUNCH
     return hipGetLastError();
 }

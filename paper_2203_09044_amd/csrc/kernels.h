@@ -36,9 +36,15 @@ hipError_t co3_launch_encode(const uint8_t *sym, int64_t n, int U, int64_t strid
 hipError_t co3_launch_decode(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff, int chunk_syms,
                              const void *codes, const int64_t *seg_off, int nseg, int K, int64_t n, int U,
                              uint8_t *sym_out, int64_t stride, int tiled, int32_t *status, hipStream_t st);
+// The averaging workspace holds two symbols per byte when this is true (user codes only): alphabets of at
+// most 16 symbols, chunks of at least two runs of 32.  The decoder then also reads two symbols per lookup.
+static inline bool co3_ws_packed(int K, int chunk_syms, bool layer_codes)
+{
+    return !layer_codes && K <= 16 && chunk_syms >= 64;
+}
 hipError_t co3_launch_ps_sum_tiled(const uint8_t *symt, int64_t n, int U, int64_t ws_stride, int chunk_syms,
                                    const int32_t *anchor, const float *scale, const int64_t *seg_off, int nseg,
-                                   co3_fmt fmt, float *avg_out, hipStream_t st);
+                                   co3_fmt fmt, int packed, float *avg_out, hipStream_t st);
 hipError_t co3_launch_moments(const float *g, const float *err, int64_t n, int U, int64_t stride,
                               const int64_t *seg_off, int nseg, float gamma, double *sums, hipStream_t st);
 hipError_t co3_launch_bias_scale(const double *sums, int64_t n, int U, const int64_t *seg_off, int nseg, float *scale,

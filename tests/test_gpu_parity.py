@@ -316,6 +316,61 @@ def test_very_long_codewords_model_style_table(co3):
     assert np.array_equal(pipe.sym_dec[0, :n].cpu().numpy(), s)
 
 
+# ------------------------------ alphabets of at most 16 symbols: two symbols per lookup, packed workspace
+@pytest.mark.parametrize("E,M,C", [(3, 0, 64), (3, 0, 512), (3, 0, 4096), (2, 0, 64), (1, 2, 1024), (2, 1, 128), (1, 0, 64)])
+def test_small_alphabet_chunk_sizes(co3, E, M, C):
+    # several tiles of 64 chunks where the chunk is small, a ragged last chunk and a ragged last run
+    run_case(co3, 3, 70 * C + 45 if C <= 512 else 5 * C + 45, co3.Fmt(E, M), C, betas=[0.5, 1.0, 2.0], T=2)
+
+
+@pytest.mark.parametrize("C", [64, 256])
+def test_small_alphabet_long_codewords(co3, C):
+    """K = 16 with a table of Fibonacci weights (codewords of 1..14 bits) and data in which the rare
+    symbols are frequent: pairs that do not fit the table prefix, codewords longer than it, and runs
+    that fall back to the careful decoder, in the plain and in the averaging path."""
+    fmt = co3.Fmt(3, 0)
+    f = ofmt(fmt)
+    fib = [1, 1]
+    while len(fib) < 15:
+        fib.append(fib[-1] + fib[-2])
+    w = np.zeros((1, 16), np.uint32)
+    order = np.random.default_rng(3).permutation(16)[:15]
+    w[0, order] = fib
+    l = oracle.huffman_lengths(w[0])
+    assert int(l.max()) == 14
+    U, n = 2, 40 * 64 * C // 16 + 21
+    rng = np.random.default_rng(12)
+    syms = []
+    for u in range(U):
+        # user 0: all active symbols equally likely (about 8 bits per symbol); user 1: the table's own law
+        p = np.full(15, 1 / 15) if u == 0 else np.asarray(fib, float) / sum(fib)
+        syms.append(order[rng.choice(15, size=n, p=p)].astype(np.uint8))
+    cap = 2 * ((max(int(l[s].astype(np.int64).sum()) for s in syms) + 127) // 128) + 2
+    pipe = co3.Co3Pipeline(U, n, fmt, chunk_syms=C, cap_words=cap)
+    pipe.sym[:, :n] = torch.from_numpy(np.stack(syms)).cuda()
+    pipe.build(torch.from_numpy(np.repeat(w, U, 0).view(np.int32)).cuda())
+    pipe.anchor[:, 0] = torch.tensor([-3, 2], dtype=torch.int32)
+    pipe.encode()
+    pipe.decode()
+    pipe.aggregate()
+    assert pipe.poll() == 0
+    for u in range(U):
+        words, off, total = oracle.encode(syms[u], l, oracle.canonical_codes(l), C)
+        assert int(pipe.total_bits[u].item()) == total
+        assert np.array_equal(host_u64(pipe.chunk_bitoff[u]), off)
+        assert np.array_equal(host_u64(pipe.words[u, :(total + 63) // 64]), words[:(total + 63) // 64])
+        assert np.array_equal(pipe.sym_dec[u, :n].cpu().numpy(), syms[u])
+    want = oracle.aggregate(np.stack(syms), np.array([[-3], [2]], np.int32), f)
+    assert np.array_equal(pipe.avg[:n].cpu().numpy().view(np.uint32), want.view(np.uint32))
+    # a flipped stream bit: the decoders run to the end and report the stream unless it still parses
+    pipe.words[0, 5] ^= 1 << 17
+    pipe.status.zero_()
+    pipe.aggregate()
+    pipe.decode()
+    rc = pipe.poll()
+    assert rc in (0, co3.binding.EBADSTREAM)
+
+
 # ----------------------------------------------------------------------------- error paths
 def test_device_reported_errors(co3):
     fmt = co3.Fmt(3, 0)
