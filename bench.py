@@ -314,7 +314,10 @@ def main():
         log("[bench] timing the CPU oracle on a bounded sample")
         if args.bias != "absmax" or args.gamma != 1.0 or args.codes != "user":
             raise SystemExit("bench.py: the CPU leg times the headline path; use --no-cpu with --bias moments / --gamma")
-        res["cpu_baseline"] = cpu_baseline(w, betas, alpha, args.chunk, n_sample=min(w.n, 1 << 24), reps=4)
+        # about 12 s of oracle time at its usual 15-20 M elements/s
+        n_sample = min(w.n, 1 << 24)
+        reps = max(4, min(200, -(-220_000_000 // (min(w.U, 2) * n_sample))))
+        res["cpu_baseline"] = cpu_baseline(w, betas, alpha, args.chunk, n_sample=n_sample, reps=reps)
     print(json.dumps(res), flush=True)
 
 
