@@ -18,16 +18,15 @@ __device__ __forceinline__ const Co3Code *dcode_of(const void *codes, int u)
 // copy of the piece with q mod 16 == 0 at index 0) so that pieces q+1 and q are ring entries j and
 // j+1 of one two-address LDS read.  The rings of a wavefront are interleaved: entry j of lane l is
 // dword j*64 + l of the wavefront's area, so the bank of an access depends on the lane only and
-// lanes at different ring positions never conflict.  Blocks are requested one run of 16 symbols
-// ahead of their use, at a cadence that is the same for all lanes of the wavefront, so the
-// global-load latency hides behind the decoding of the previous run.
+// lanes at different ring positions never conflict.  Blocks are requested one run (16 symbols, 32
+// with the two-symbol table) ahead of their use, at a cadence that is the same for all lanes of the
+// wavefront, so the global-load latency hides behind the decoding of the previous run.
 // ------------------------------------------------------------------------------------------
 #define RING_ROWS 17
 #define RING_ROW_DW CO3_WAVE     // dwords between consecutive ring entries of one lane
 #define DE_GROUP 16          // symbols per run: one ring refill point, one 16-byte store
 #define DE_MISS_LEN 255u     // length field of a table entry that does not resolve a symbol
-#define DE_PAIR_BITS 12      // prefix length of the two-symbol table used for small alphabets
-#define DE_PAIR_MAX_K 16     // alphabets up to this size are decoded two symbols per lookup
+#define DE_PAIR_BITS 12      // prefix length of the two-symbol table used for alphabets of at most 16 symbols
 enum { DE_SHORT = 0, DE_LONG = 1, DE_PAIRS = 2 };   // fast-path variants of decode_range
 
 struct LaneStream {
@@ -271,10 +270,11 @@ __device__ __forceinline__ uint32_t pair_second(const LaneStream &ls, const uint
 //
 // DE_SHORT is the instance for codes whose longest codeword fits the table prefix: there a miss can
 // only come from an invalid stream; it advances by DE_MISS_LEN, more than 16 hits can, which the
-// validation catches.  DE_PAIRS reads the two-symbol table `pairs`: eight lookups per run; a lookup
-// whose prefix does not hold both codewords takes the second one from a lookup of its own (in a branch
-// the wavefront skips when no lane needs it), and a codeword longer than the prefix sends the run to
-// the careful path.
+// validation catches.  DE_PAIRS reads the two-symbol table `pairs`: one lookup per two symbols and one
+// refill point per 32 symbols (with at most four bits per symbol on average the blocks requested at one
+// boundary cover the symbols up to the next one); a lookup whose prefix does not hold both codewords
+// takes the second one from a lookup of its own (in a branch the wavefront skips when no lane needs
+// it), and a codeword longer than the prefix sends the run to the careful path.
 template <int MODE>
 __device__ __forceinline__ void decode_range(const DecTables &t, LaneStream &ls, int i0, int i1, uint8_t *out,
                                              int64_t run_step, bool &ok, const uint32_t *pairs = nullptr)
@@ -296,8 +296,6 @@ __device__ __forceinline__ void decode_range(const DecTables &t, LaneStream &ls,
     };
     if ((i & 15) != 0 && i < i1) partial(16 - (i & 15) < i1 - i ? 16 - (i & 15) : i1 - i);
     if (MODE == DE_PAIRS) {
-        // two runs per refill point: with at most four bits per symbol on average the blocks requested
-        // at one boundary cover the 32 symbols up to the next one
 #pragma unroll 1
         for (; i + 2 * DE_GROUP <= i1; i += 2 * DE_GROUP) {
             ls.group_boundary();
@@ -448,7 +446,7 @@ __device__ __forceinline__ void decode_chunk_packed(const DecTables &t, LaneStre
 
 // TILED = false: sym_out is [U][stride] symbols in order.  TILED = true: sym_out is the averaging
 // workspace, [U][tiles][chunk_syms/16][64 lanes][16 symbols] with tile = 64 consecutive chunks.
-// PAIRS: the workgroup also builds the two-symbol table (launched for alphabets of at most DE_PAIR_MAX_K
+// PAIRS: the workgroup also builds the two-symbol table (launched for alphabets of at most 16
 // symbols and chunks of at least 32); with TILED the workspace then holds two symbols per byte,
 // [U][tiles][chunk_syms/32][64 lanes][32 symbols in 16 bytes].
 template <bool TILED, bool PAIRS>
