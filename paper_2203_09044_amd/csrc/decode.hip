@@ -117,8 +117,14 @@ struct LaneStream {
     }
 };
 
-struct DecTables {           // LDS-resident decoder tables of one user
-    uint16_t lut[1 << CO3_LUT_BITS_MAX];
+// LDS-resident decoder tables of one code.  BITS: longest prefix the lookup table resolves.  The code
+// blob stores a table of at most CO3_LUT_BITS_MAX bits; a workgroup that has LDS to spare widens it
+// (DE_WIDE_BITS) while loading, so that fewer codewords take the canonical search.
+#define DE_WIDE_BITS 14
+template <int BITS>
+struct DecTablesT {
+    static constexpr int kBits = BITS;
+    uint16_t lut[1 << BITS];
     uint64_t first_code[65];
     uint16_t count[66];
     uint16_t base[66];
@@ -126,14 +132,16 @@ struct DecTables {           // LDS-resident decoder tables of one user
     uint64_t lim_incl[65];   // largest 64-bit window (codeword left-aligned, ones below) of a codeword of length <= l
     uint32_t maxlen, lut_bits;
 };
+typedef DecTablesT<CO3_LUT_BITS_MAX> DecTables;
 
-__device__ __forceinline__ void load_tables(DecTables &t, const Co3Code *cd)
+template <class Tables>
+__device__ __forceinline__ void load_tables(Tables &t, const Co3Code *cd)
 {
-    const uint32_t lb = cd->lut_bits > CO3_LUT_BITS_MAX ? CO3_LUT_BITS_MAX : cd->lut_bits;
-    for (uint32_t i = threadIdx.x; i < (1u << lb); i += blockDim.x) {
-        uint16_t e = cd->lut[i];
-        t.lut[i] = (e >> 8) ? e : (uint16_t)(DE_MISS_LEN << 8);   // miss: longer than the prefix, or invalid
-    }
+    constexpr uint32_t BITS = Tables::kBits;
+    const uint32_t lb = cd->lut_bits > CO3_LUT_BITS_MAX ? CO3_LUT_BITS_MAX : (cd->lut_bits < 1 ? 1 : cd->lut_bits);
+    const uint32_t ml = cd->maxlen > 64 ? 64 : cd->maxlen;
+    // table prefix here: the stored one, widened up to BITS when the code has longer codewords
+    const uint32_t nb = (BITS > CO3_LUT_BITS_MAX && ml > lb) ? (ml < BITS ? ml : BITS) : lb;
     for (int i = threadIdx.x; i < 65; i += blockDim.x) t.first_code[i] = cd->first_code[i];
     for (int i = threadIdx.x; i < 66; i += blockDim.x) {
         t.count[i] = cd->count[i];
@@ -141,10 +149,33 @@ __device__ __forceinline__ void load_tables(DecTables &t, const Co3Code *cd)
     }
     for (int i = threadIdx.x; i < 256; i += blockDim.x) t.sorted[i] = cd->sorted[i];
     if (threadIdx.x == 0) {
-        t.maxlen = cd->maxlen > 64 ? 64 : cd->maxlen;
-        t.lut_bits = lb < 1 ? 1 : lb;
+        t.maxlen = ml;
+        t.lut_bits = nb;
     }
-    __syncthreads();
+    if (nb == lb) {
+        for (uint32_t i = threadIdx.x; i < (1u << lb); i += blockDim.x) {
+            uint16_t e = cd->lut[i];
+            t.lut[i] = (e >> 8) ? e : (uint16_t)(DE_MISS_LEN << 8);   // miss: longer than the prefix, or invalid
+        }
+        __syncthreads();
+    } else {
+        __syncthreads();                 // the canonical tables are read below
+        for (uint32_t i = threadIdx.x; i < (1u << nb); i += blockDim.x) {
+            uint32_t e = cd->lut[i >> (nb - lb)];
+            if ((e >> 8) == 0u) {        // not resolved by the stored prefix: lengths lb+1 .. nb by the canonical rule
+                e = DE_MISS_LEN << 8;
+                for (uint32_t l = lb + 1; l <= nb; ++l) {
+                    const uint64_t off = (uint64_t)(i >> (nb - l)) - t.first_code[l];
+                    if (off < (uint64_t)t.count[l]) {
+                        e = (l << 8) | t.sorted[(t.base[l] + (uint32_t)off) & 255u];
+                        break;
+                    }
+                }
+            }
+            t.lut[i] = (uint16_t)e;
+        }
+        __syncthreads();
+    }
     if (t.maxlen > t.lut_bits) {      // only codes with codewords beyond the table prefix use the limits
         for (int l = threadIdx.x; l < 65; l += blockDim.x) {
             int j = l;
@@ -206,7 +237,8 @@ __device__ __forceinline__ int decode_long(const Tables &t, uint64_t window, uin
 // Careful decoding of `count` <= 16 symbols (any codeword length, any stream content): used for runs
 // that the fast path could not vouch for and for the ragged end of a chunk.  Leaves blocks
 // cur .. cur+2 resident.  Symbols are returned 4 per word, first in the lowest byte.
-__device__ __forceinline__ void decode_run_careful(const DecTables &t, LaneStream &ls, int shift, int count, bool &ok,
+template <class Tables>
+__device__ __forceinline__ void decode_run_careful(const Tables &t, LaneStream &ls, int shift, int count, bool &ok,
                                                    uint32_t w[4])
 {
     w[0] = w[1] = w[2] = w[3] = 0;
@@ -275,10 +307,11 @@ __device__ __forceinline__ uint32_t pair_second(const LaneStream &ls, const uint
 // boundary cover the symbols up to the next one); a lookup whose prefix does not hold both codewords
 // takes the second one from a lookup of its own (in a branch the wavefront skips when no lane needs
 // it), and a codeword longer than the prefix sends the run to the careful path.
-template <int MODE>
-__device__ __forceinline__ void decode_range(const DecTables &t, LaneStream &ls, int i0, int i1, uint8_t *out,
+template <int MODE, class Tables>
+__device__ __forceinline__ void decode_range(const Tables &t, LaneStream &ls, int i0, int i1, uint8_t *out,
                                              int64_t run_step, bool &ok, const uint32_t *pairs = nullptr)
 {
+    static_assert(DE_GROUP * Tables::kBits < DE_MISS_LEN, "a miss must advance more than a run of hits can");
     constexpr bool LONG = MODE == DE_LONG;
     const int shift = 32 - (int)t.lut_bits;
     int i = i0;
@@ -381,7 +414,7 @@ __device__ __forceinline__ void decode_range(const DecTables &t, LaneStream &ls,
         // every window read above (up to three dwords from the current one) must have been resident
         if (MODE == DE_LONG    ? (bad || ls.rel + 96u > ls.loaded * 128u)
             : MODE == DE_PAIRS ? (bad || ls.rel + 64u > ls.loaded * 128u)
-                               : (ls.rel - rel0 > DE_GROUP * CO3_LUT_BITS_MAX ||
+                               : (ls.rel - rel0 > DE_GROUP * Tables::kBits ||
                                   ls.rel + 64u > ls.loaded * 128u)) {   // rare
             ls.rel = rel0;
             decode_run_careful(t, ls, shift, DE_GROUP, ok, w);
@@ -459,10 +492,10 @@ __global__ __launch_bounds__(DE_BLOCK) void k_decode(const uint64_t *__restrict_
     // tables first: their LDS offsets then fit the immediate field of the read instructions
     __shared__ struct {
         uint32_t pairs[PAIRS ? (1 << DE_PAIR_BITS) : 1];
-        DecTables t;
+        DecTablesT<PAIRS ? CO3_LUT_BITS_MAX : DE_WIDE_BITS> t;   // one symbol per lookup: the widened table
         alignas(256) uint32_t ring[DE_BLOCK * RING_ROWS];   // a multiple of the ring row: row offsets stay immediates
     } lds;
-    DecTables &t = lds.t;
+    auto &t = lds.t;
     uint32_t *const ring = lds.ring;
     uint32_t *const pairs = lds.pairs;
 
@@ -479,7 +512,7 @@ __global__ __launch_bounds__(DE_BLOCK) void k_decode(const uint64_t *__restrict_
     if (active) ls.open(p0);
     load_tables(t, dcode_of(codes, u));
     __syncthreads();
-    if (PAIRS) {
+    if constexpr (PAIRS) {
         build_pairs<TILED>(t, pairs);
         __syncthreads();
     }
@@ -498,8 +531,8 @@ __global__ __launch_bounds__(DE_BLOCK) void k_decode(const uint64_t *__restrict_
         run_step = 16;
     }
     bool ok = true;
-    if (PAIRS && TILED) decode_chunk_packed(t, ls, nsym, out, run_step, ok, pairs);
-    else if (PAIRS) decode_range<DE_PAIRS>(t, ls, 0, nsym, out, run_step, ok, pairs);
+    if constexpr (PAIRS && TILED) decode_chunk_packed(t, ls, nsym, out, run_step, ok, pairs);
+    else if constexpr (PAIRS) decode_range<DE_PAIRS>(t, ls, 0, nsym, out, run_step, ok, pairs);
     else if (t.maxlen > t.lut_bits) decode_range<DE_LONG>(t, ls, 0, nsym, out, run_step, ok);
     else decode_range<DE_SHORT>(t, ls, 0, nsym, out, run_step, ok);
     ls.land();
