@@ -503,6 +503,31 @@ def test_average_exact_and_float64():
     for x in v:
         acc = np.float32(acc + x)
     assert got[0] == np.float32(acc / np.float32(3))
+    # the one division is a correctly rounded quotient, not a product with a rounded reciprocal: exact
+    # rational arithmetic for user counts whose reciprocal is not an fp32 number
+    from fractions import Fraction
+
+    def to_f32(q):                       # nearest fp32 to the positive rational q, ties to even (normal range)
+        e = q.numerator.bit_length() - q.denominator.bit_length()
+        if Fraction(2) ** e > q:
+            e -= 1
+        scaled = q / Fraction(2) ** (e - 23)          # in [2^23, 2^24)
+        lo = scaled.numerator // scaled.denominator
+        rem = scaled - lo
+        r = lo + (1 if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and lo % 2 == 1) else 0)
+        return np.float32(float(Fraction(r) * Fraction(2) ** (e - 23)))
+
+    fmt6 = Fmt(1, 6)
+    differs = 0
+    for U3 in (3, 7):
+        sy = rng.integers(1, fmt6.K // 2, (U3, 400)).astype(np.uint8)      # positive levels, 7-bit significands
+        got = oracle.aggregate(sy, np.full((U3, 1), 3, np.int32), fmt6)
+        for i in range(sy.shape[1]):
+            total = sum(Fraction(float(oracle.symbol_value(int(sy[u, i]), 3, fmt6))) for u in range(U3))
+            assert float(np.float32(float(total))) == float(total)          # the fp32 partial sums were exact
+            assert got[i] == to_f32(total / U3), (U3, i)
+            differs += int(np.float32(np.float32(float(total)) * (np.float32(1) / np.float32(U3))) != got[i])
+    assert differs > 0          # the sample does separate the two ways of dividing
     # per-segment anchors
     so = [0, 3, 5]
     A4 = np.array([[0, 4], [1, 5]], np.int32)
