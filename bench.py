@@ -44,7 +44,7 @@ def make_workload(name):
                                 "E4M3 (the benchmark draws one scale for all tensors)")
     if name == "C4":
         w = inp.c4()
-        return w, [1.0], 1e-4, "C4: 1 client x 100,000,000 fp32, GenNorm beta=1 scale 1e-4, E5M2, empirical table"
+        return w, [1.0], 1e-4, "C4: 1 client x 100,000,000 fp32, GenNorm beta=1 scale 1e-4 (1e-4 of the samples at 100x), E5M2"
     if name.startswith("C5"):
         point = int(name[3:]) if len(name) > 3 else 4
         w = inp.c5(point)
@@ -111,10 +111,12 @@ def main():
     ap.add_argument("--bias", default="absmax", choices=("absmax", "moments"),
                     help="absmax: integer anchor from max|g| (the headline configuration); moments: the paper's bias "
                          "rule (moment sums, GenNorm fit, multiplier) on the fixed grid of anchor 2^(E-1)")
-    ap.add_argument("--codes", default="user", choices=("user", "layer", "layer-model"),
+    ap.add_argument("--codes", default="user", choices=("user", "user-model", "layer", "layer-model"),
                     help="user: one empirical code per client, rebuilt every step (the headline configuration); "
                          "layer: one code per tensor shared by the clients, rebuilt every step from the pooled "
-                         "per-tensor counts; layer-model: one fixed code per tensor designed once from the GenNorm "
+                         "per-tensor counts; user-model: one fixed code per client designed once from the GenNorm law "
+                         "of the workload (C4's model table; no histogram, no code build inside the step); "
+                         "layer-model: one fixed code per tensor designed once from the GenNorm "
                          "law of the tensor (no histogram, no code build inside the step)")
     ap.add_argument("--gamma", type=float, default=1.0, help="memory decay coefficient (1.0 in all five configurations)")
     ap.add_argument("--format", default=None, help="override the workload's format, e.g. E1M2")
@@ -176,19 +178,32 @@ def main():
         desc += ", bias rule from moments"
     fmt = Fmt(w.E, w.M)
     code_seg_off = None
-    if args.codes != "user" and w.sizes is not None:
+    if args.codes in ("layer", "layer-model") and w.sizes is not None:
         import co3_inputs as inp
         groups = inp.group_small_tensors(w.sizes)
         code_seg_off = inp.seg_offsets(groups)
         desc += f", {len(groups)} code groups (tensors under 16,384 elements share the code of the large tensor before them)"
+    fixed_user_tables = args.codes == "user-model"
     pipe = Co3Pipeline(w.U, w.n, fmt, chunk_syms=args.chunk, seg_off=w.seg_off if w.sizes is not None else None,
-                       bias=args.bias, gamma=args.gamma, codes="user" if args.codes == "user" else "layer",
-                       code_seg_off=code_seg_off)
+                       bias=args.bias, gamma=args.gamma, codes="user" if args.codes.startswith("user") else "layer",
+                       code_seg_off=code_seg_off, statistics=not fixed_user_tables,
+                       cap_words=2 * B.cap_words_empirical(w.n, fmt) if fixed_user_tables else None)
     log(f"[bench] {desc}; generating {args.pool} device batches")
     batches = device_batches(w, betas, alpha, args.pool, pipe)
 
-    rebuild = args.codes != "layer-model"
-    if not rebuild:
+    rebuild = args.codes in ("user", "layer")
+    if fixed_user_tables:
+        # one table per client from the law the client's gradients are drawn from, on the grid of the client's
+        # anchor of the first batch (every emit-able symbol has a codeword, so the table serves every step)
+        import numpy as np
+        pipe.convert(batches[0])
+        A0 = pipe.anchor[:, 0].cpu().numpy()
+        pipe.err.zero_()
+        wts = np.stack([B.model_weights(int(A0[u]), fmt, float(betas[u % len(betas)]), float(alpha)).numpy().view(np.uint32)
+                        for u in range(w.U)])
+        pipe.build(torch.from_numpy(wts.view(np.int32)).cuda())
+        desc += ", fixed per-client model tables"
+    elif not rebuild:
         # fixed tables: the GenNorm law of each tensor (workload parameters) on the grid of client 0's anchors
         # of the first batch; every emit-able symbol has a codeword, so the tables serve all clients and steps
         import numpy as np
@@ -300,7 +315,11 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": desc, "U": w.U, "n": w.n, "format": f"E{w.E}M{w.M}", "chunk_syms": args.chunk,
-                   "table": "empirical per client, rebuilt every step", "gamma": args.gamma, "bias": args.bias, "codes": args.codes},
+                   "table": {"user": "empirical per client, rebuilt every step",
+                             "user-model": "fixed per client, designed from the GenNorm law of the workload",
+                             "layer": "empirical per tensor, pooled over the clients, rebuilt every step",
+                             "layer-model": "fixed per tensor, designed from the GenNorm law of the workload"}[args.codes],
+                   "gamma": args.gamma, "bias": args.bias, "codes": args.codes},
         "bits_per_element": {"payload": payload_bpe, "index": index_bpe, "header": header_bpe},
         "path_roofline": {"bound": "hbm", "algorithmic_bytes_per_element": b_alg,
                           "achieved": b_alg * value / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",

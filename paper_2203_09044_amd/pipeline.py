@@ -25,7 +25,8 @@ def _round_up(x: int, m: int) -> int:
 class Co3Pipeline:
     def __init__(self, U: int, n: int, fmt: Fmt, chunk_syms: int = 256, seg_off=None, gamma: float = 1.0,
                  cap_words: Optional[int] = None, device="cuda:0", fused_histogram: bool = True,
-                 bias: str = "absmax", grid_anchor: Optional[int] = None, codes: str = "user", code_seg_off=None):
+                 bias: str = "absmax", grid_anchor: Optional[int] = None, codes: str = "user", code_seg_off=None,
+                 statistics: bool = True):
         if bias not in ("absmax", "moments"):
             raise ValueError("bias must be 'absmax' or 'moments'")
         if codes not in ("user", "layer"):
@@ -33,6 +34,7 @@ class Co3Pipeline:
         self.code_mode = codes
         self.U, self.n, self.fmt, self.chunk_syms, self.gamma = U, n, fmt, chunk_syms, gamma
         self.fused_histogram = fused_histogram
+        self.statistics = statistics      # False: fixed tables (designed from a model), no symbol counts are gathered
         self.bias = bias
         dev = torch.device(device)
         self.device = dev
@@ -80,14 +82,14 @@ class Co3Pipeline:
         B.bias_scale(self.sums, self.n, self.U, self.scale, fit=self.fit, seg_off=self.seg_off)
 
     def convert(self, g: torch.Tensor, anchor_mode=B.ANCHOR_FROM_ABSMAX_G):
-        counts = self.counts if self.fused_histogram and self.code_mode == "user" else None
+        counts = self.counts if self.statistics and self.fused_histogram and self.code_mode == "user" else None
         if self.bias == "moments":
             B.convert_ef_scaled(g, self.err, self.sym, self.n, self.anchor, self.scale, self.gamma, self.fmt,
                                 seg_off=self.seg_off, counts=counts)
         else:
             B.convert_ef(g, self.err, self.sym, self.n, self.anchor, anchor_mode, self.gamma, self.fmt,
                          seg_off=self.seg_off, counts=counts)
-        if not self.fused_histogram and self.code_mode == "user":
+        if self.statistics and not self.fused_histogram and self.code_mode == "user":
             B.histogram(self.sym, self.n, self.fmt, self.counts)
 
     def build(self, weights: Optional[torch.Tensor] = None):
