@@ -55,12 +55,18 @@ __global__ __launch_bounds__(HB_BLOCK) void k_build_code(const uint32_t *__restr
     // One lane runs the merge.  The fronts of both queues are kept in registers: the next four leaf
     // weights (reloaded four picks ahead of their use) and the next two node weights (a node that is
     // created when the node queue is nearly empty is forwarded without a trip through LDS), so the
-    // chain of dependent picks does not wait for LDS.
+    // chain of dependent picks does not wait for LDS.  Both queues are padded with an unreachable
+    // weight, so the reloads need neither a bounds test nor arithmetic on what they return.
+    const uint64_t INF = ~0ull;     // weights stay below 2^40, so INF never wins while a queue has entries
+    __shared__ uint64_t leaf_q[HB_BLOCK + 4];
+    leaf_q[tid] = tid < nact ? (key[tid] >> 8) : INF;
+    if (tid < 4) leaf_q[HB_BLOCK + tid] = INF;
+    node_w[tid] = INF;
+    node_w[HB_BLOCK + tid] = INF;
+    __syncthreads();
     if (tid == 0 && nact >= 2) {
-        const uint64_t INF = ~0ull;     // weights stay below 2^40, so INF never wins while a queue has entries
-        auto leaf_w = [&](int q) -> uint64_t { return q < nact ? (key[q] >> 8) : INF; };
         int q1 = 0, q2 = nact, next = nact;
-        uint64_t L0 = leaf_w(0), L1 = leaf_w(1), L2 = leaf_w(2), L3 = leaf_w(3);
+        uint64_t L0 = leaf_q[0], L1 = leaf_q[1], L2 = leaf_q[2], L3 = leaf_q[3];
         uint64_t N0 = INF, N1 = INF;
         for (int step = 0; step < nact - 1; ++step) {
             uint64_t wsum = 0;
@@ -73,13 +79,13 @@ __global__ __launch_bounds__(HB_BLOCK) void k_build_code(const uint32_t *__restr
                     L0 = L1;
                     L1 = L2;
                     L2 = L3;
-                    L3 = leaf_w(q1 + 3);
+                    L3 = leaf_q[q1 + 3];
                 } else {
                     wsum += N0;
                     parent[q2] = (uint16_t)next;
                     ++q2;
                     N0 = N1;
-                    N1 = q2 + 1 < next ? node_w[q2 + 1] : INF;
+                    N1 = node_w[q2 + 1];          // INF beyond the nodes created so far
                 }
             }
             node_w[next] = wsum;
