@@ -168,14 +168,19 @@ __global__ __launch_bounds__(HB_BLOCK) void k_build_code(const uint32_t *__restr
         limit_s[tid] = lim > (1ull << lut_bits) ? (1u << lut_bits) : (uint32_t)lim;
     }
     __syncthreads();
+    // (the limits do not decrease with the length: counting the limits at or below i gives the length;
+    // they are held in registers, so an entry costs no chain of LDS reads)
+    uint32_t lim[CO3_LUT_BITS_MAX + 1];
+#pragma unroll
+    for (uint32_t l = 1; l <= CO3_LUT_BITS_MAX; ++l) lim[l] = l <= lut_bits ? limit_s[l] : 0xffffffffu;
     for (uint32_t i = tid; i < (1u << lut_bits); i += HB_BLOCK) {
+        uint32_t l = 1;
+#pragma unroll
+        for (uint32_t j = 1; j <= CO3_LUT_BITS_MAX; ++j) l += i >= lim[j] ? 1u : 0u;
         uint16_t entry = 0;
-        for (uint32_t l = 1; l <= lut_bits; ++l) {
-            if (i < limit_s[l]) {
-                uint32_t off = (i >> (lut_bits - l)) - (uint32_t)first_s[l];
-                entry = (uint16_t)((l << 8) | sorted_s[base_s[l] + off]);
-                break;
-            }
+        if (l <= lut_bits) {
+            uint32_t off = (i >> (lut_bits - l)) - (uint32_t)first_s[l];
+            entry = (uint16_t)((l << 8) | sorted_s[base_s[l] + off]);
         }
         out->lut[i] = entry;
     }
