@@ -52,11 +52,11 @@ __global__ __launch_bounds__(HB_BLOCK) void k_build_code(const uint32_t *__restr
 
     // two-queue merge: nodes 0..nact-1 are the sorted leaves, nact..2*nact-2 the merged nodes in
     // creation order; a leaf wins a weight tie against a merged node
-    // One lane runs the merge.  The fronts of both queues are kept in registers: the next four leaf
-    // weights (reloaded four picks ahead of their use) and the next two node weights (a node that is
-    // created when the node queue is nearly empty is forwarded without a trip through LDS), so the
-    // chain of dependent picks does not wait for LDS.  Both queues are padded with an unreachable
-    // weight, so the reloads need neither a bounds test nor arithmetic on what they return.
+    // One lane runs the merge.  A step reads the two front entries of each queue and takes one of three
+    // outcomes: two leaves (the second leaf is not above the first node), two nodes (the second node is
+    // below the first leaf), or the first leaf with the first node (their order does not matter to the
+    // sum or to the parent links).  Both queues are padded with an unreachable weight, so no bounds
+    // test is needed; the node created by a step is written before the next step reads the fronts.
     const uint64_t INF = ~0ull;     // weights stay below 2^40, so INF never wins while a queue has entries
     __shared__ uint64_t leaf_q[HB_BLOCK + 4];
     leaf_q[tid] = tid < nact ? (key[tid] >> 8) : INF;
@@ -65,33 +65,29 @@ __global__ __launch_bounds__(HB_BLOCK) void k_build_code(const uint32_t *__restr
     node_w[HB_BLOCK + tid] = INF;
     __syncthreads();
     if (tid == 0 && nact >= 2) {
-        int q1 = 0, q2 = nact, next = nact;
-        uint64_t L0 = leaf_q[0], L1 = leaf_q[1], L2 = leaf_q[2], L3 = leaf_q[3];
-        uint64_t N0 = INF, N1 = INF;
-        for (int step = 0; step < nact - 1; ++step) {
-            uint64_t wsum = 0;
-#pragma unroll
-            for (int c = 0; c < 2; ++c) {
-                if (L0 <= N0) {
-                    wsum += L0;
-                    parent[q1] = (uint16_t)next;
-                    ++q1;
-                    L0 = L1;
-                    L1 = L2;
-                    L2 = L3;
-                    L3 = leaf_q[q1 + 3];
-                } else {
-                    wsum += N0;
-                    parent[q2] = (uint16_t)next;
-                    ++q2;
-                    N0 = N1;
-                    N1 = node_w[q2 + 1];          // INF beyond the nodes created so far
-                }
+        int q1 = 0, q2 = nact;
+        for (int next = nact; next < 2 * nact - 1; ++next) {
+            const uint64_t L0 = leaf_q[q1], L1 = leaf_q[q1 + 1];
+            const uint64_t N0 = node_w[q2], N1 = node_w[q2 + 1];
+            uint64_t wsum;
+            if (L1 <= N0) {
+                wsum = L0 + L1;
+                parent[q1] = (uint16_t)next;
+                parent[q1 + 1] = (uint16_t)next;
+                q1 += 2;
+            } else if (N1 < L0) {
+                wsum = N0 + N1;
+                parent[q2] = (uint16_t)next;
+                parent[q2 + 1] = (uint16_t)next;
+                q2 += 2;
+            } else {
+                wsum = L0 + N0;
+                parent[q1] = (uint16_t)next;
+                parent[q2] = (uint16_t)next;
+                ++q1;
+                ++q2;
             }
             node_w[next] = wsum;
-            if (next == q2) N0 = wsum;
-            else if (next == q2 + 1) N1 = wsum;
-            ++next;
         }
     }
     __syncthreads();
