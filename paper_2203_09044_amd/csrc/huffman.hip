@@ -15,7 +15,7 @@ __global__ __launch_bounds__(HB_BLOCK) void k_build_code(const uint32_t *__restr
     __shared__ uint64_t key[HB_BLOCK];        // (weight << 8 | symbol), inactive symbols sort last
     __shared__ uint64_t node_w[2 * HB_BLOCK]; // weights of merged nodes (index >= nact)
     __shared__ uint16_t parent[2 * HB_BLOCK];
-    __shared__ uint8_t len_s[HB_BLOCK];
+    __shared__ __attribute__((aligned(4))) uint8_t len_s[HB_BLOCK];   // also read as words
     __shared__ uint32_t cnt_s[66];
     __shared__ uint64_t first_s[66];
     __shared__ uint32_t base_s[66];
@@ -23,7 +23,8 @@ __global__ __launch_bounds__(HB_BLOCK) void k_build_code(const uint32_t *__restr
     __shared__ uint32_t maxlen_s;
 
     uint32_t wt = tid < K ? weights[(size_t)u * K + tid] : 0u;
-    key[tid] = wt ? (((uint64_t)wt << 8) | (uint64_t)tid) : ~0ull;
+    const uint64_t mykey = wt ? (((uint64_t)wt << 8) | (uint64_t)tid) : ~0ull;
+    key[tid] = mykey;
     len_s[tid] = 0;
     sorted_s[tid] = 0;
     if (tid < 66) {
@@ -34,20 +35,19 @@ __global__ __launch_bounds__(HB_BLOCK) void k_build_code(const uint32_t *__restr
     if (tid == 0) maxlen_s = 0;
     const int nact = __syncthreads_count(wt != 0u);
 
-    // leaves in (weight, symbol) order: bitonic sort of the K keys (K is a power of two)
-    for (int k = 2; k <= K; k <<= 1) {
-        for (int j = k >> 1; j > 0; j >>= 1) {
-            int other = tid ^ j;
-            if (other > tid && other < K) {
-                uint64_t a = key[tid], b = key[other];
-                bool ascending = (tid & k) == 0;
-                if ((a > b) == ascending) {
-                    key[tid] = b;
-                    key[other] = a;
-                }
-            }
-            __syncthreads();
+    // leaves in (weight, symbol) order: every thread counts the keys below its own (all threads read the
+    // same entry at the same time, a broadcast) and stores its key at that position; the symbols without
+    // a weight share one key and are ordered among themselves by their index
+    {
+        int below = 0;
+        for (int j = 0; j < K; ++j) {        // entries from K on hold the no-weight key and stay where they are
+            const uint64_t kj = key[j];
+            below += (kj < mykey || (kj == mykey && j < tid)) ? 1 : 0;
         }
+        if (tid >= K) below = tid;
+        __syncthreads();
+        key[below] = mykey;
+        __syncthreads();
     }
 
     // two-queue merge: nodes 0..nact-1 are the sorted leaves, nact..2*nact-2 the merged nodes in
@@ -129,8 +129,16 @@ __global__ __launch_bounds__(HB_BLOCK) void k_build_code(const uint32_t *__restr
         uint32_t l = len_s[tid];
         uint64_t enc = 0;
         if (l) {
+            // symbols below this one with the same length, four length bytes per LDS word
             uint32_t rank = 0;
-            for (int j = 0; j < tid; ++j) rank += (len_s[j] == l) ? 1u : 0u;   // tid < K here
+            const uint32_t *len_w = reinterpret_cast<const uint32_t *>(len_s);
+            const uint32_t pat = l * 0x01010101u;
+            for (int j = 0; j <= tid >> 2; ++j) {
+                uint32_t x = len_w[j] ^ pat;                       // zero bytes where the length matches
+                if (j == tid >> 2) x |= ~0u << (8 * (tid & 3));    // only the symbols below this one
+                const uint32_t z = ~(((x & 0x7f7f7f7fu) + 0x7f7f7f7fu) | x | 0x7f7f7f7fu);   // 0x80 per zero byte
+                rank += (uint32_t)__builtin_popcount(z);
+            }
             uint64_t code = first_s[l] + rank;
             sorted_s[base_s[l] + rank] = (uint8_t)tid;
             enc = (code << 6) | (uint64_t)(l & 63u);
