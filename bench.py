@@ -118,6 +118,9 @@ def main():
                          "of the workload (C4's model table; no histogram, no code build inside the step); "
                          "layer-model: one fixed code per tensor designed once from the GenNorm "
                          "law of the tensor (no histogram, no code build inside the step)")
+    ap.add_argument("--single-pass", action="store_true",
+                    help="with --codes user-model: conversion and compression in one pass (co3_convert_encode), no "
+                         "symbol array")
     ap.add_argument("--gamma", type=float, default=1.0, help="memory decay coefficient (1.0 in all five configurations)")
     ap.add_argument("--format", default=None, help="override the workload's format, e.g. E1M2")
     ap.add_argument("--pool", type=int, default=3, help="distinct gradient batches cycled through")
@@ -184,9 +187,12 @@ def main():
         code_seg_off = inp.seg_offsets(groups)
         desc += f", {len(groups)} code groups (tensors under 16,384 elements share the code of the large tensor before them)"
     fixed_user_tables = args.codes == "user-model"
+    if args.single_pass and not fixed_user_tables:
+        raise SystemExit("--single-pass needs --codes user-model (the codes must be known before the step)")
     pipe = Co3Pipeline(w.U, w.n, fmt, chunk_syms=args.chunk, seg_off=w.seg_off if w.sizes is not None else None,
                        bias=args.bias, gamma=args.gamma, codes="user" if args.codes.startswith("user") else "layer",
                        code_seg_off=code_seg_off, statistics=not fixed_user_tables,
+                       single_pass=fixed_user_tables and args.single_pass,
                        cap_words=2 * B.cap_words_empirical(w.n, fmt) if fixed_user_tables else None)
     log(f"[bench] {desc}; generating {args.pool} device batches")
     batches = device_batches(w, betas, alpha, args.pool, pipe)
@@ -202,7 +208,7 @@ def main():
         wts = np.stack([B.model_weights(int(A0[u]), fmt, float(betas[u % len(betas)]), float(alpha)).numpy().view(np.uint32)
                         for u in range(w.U)])
         pipe.build(torch.from_numpy(wts.view(np.int32)).cuda())
-        desc += ", fixed per-client model tables"
+        desc += ", fixed per-client model tables" + (", single pass" if args.single_pass else "")
     elif not rebuild:
         # fixed tables: the GenNorm law of each tensor (workload parameters) on the grid of client 0's anchors
         # of the first batch; every emit-able symbol has a codeword, so the tables serve all clients and steps

@@ -247,6 +247,30 @@ int32_t co3_ps_aggregate_layers(const uint64_t *words, int64_t cap_words, const 
                                 const int64_t *seg_off, int32_t nseg, float *avg_out, void *workspace, size_t ws_bytes,
                                 int32_t *status, void *stream);
 
+/* ---- fixed codes: conversion and compression in one pass ------------------- */
+
+/*
+ * Sec. III (ii) designs the code from a model of the gradients, before the gradients are seen.  With
+ * such a code (or one kept from an earlier iteration) the user's three steps of Algorithm 1 need no
+ * pass over the symbols of their own: co3_convert_encode gives the results of co3_convert_ef
+ * followed by co3_encode with codes[u] -- err, anchor, words, chunk_bitoff, total_bits, bit for
+ * bit -- without producing the symbol array or the counts.
+ *
+ *   arguments  as in co3_convert_ef (g, err, n, U, stride, seg_off, nseg, anchor, anchor_mode, gamma,
+ *              fmt) and co3_encode (codes [U], words, cap_words, chunk_syms, chunk_bitoff,
+ *              total_bits, status)
+ *   workspace  co3_convert_encode_workspace_bytes(n, U, chunk_syms) bytes, 16-byte aligned, contents
+ *              unspecified: every 256 elements pack into a slot of 2 KiB of their own (room for 256
+ *              codewords of any length) before they are moved into the stream, 8 bytes per element
+ *              of address space of which a codeword's worth is touched
+ *   errors     as the two calls: CO3_EINVAL on the host; CO3_ENOCODE, CO3_ECAP through status
+ */
+size_t co3_convert_encode_workspace_bytes(int64_t n, int32_t U, int32_t chunk_syms);
+int32_t co3_convert_encode(const float *g, float *err, int64_t n, int32_t U, int64_t stride, const int64_t *seg_off,
+                           int32_t nseg, int32_t *anchor, int32_t anchor_mode, float gamma, co3_fmt fmt, const void *codes,
+                           uint64_t *words, int64_t cap_words, int32_t chunk_syms, uint64_t *chunk_bitoff,
+                           uint64_t *total_bits, void *workspace, size_t ws_bytes, int32_t *status, void *stream);
+
 /* ---- launch timing (diagnostic) ------------------------------------------ */
 
 /*

@@ -137,6 +137,12 @@ size_t co3_encode_workspace_bytes(int64_t n, int32_t U)
     return (size_t)((nblk > 0 ? nblk : 1) + (ngrp > 0 ? ngrp : 1)) * (size_t)U * sizeof(uint64_t);
 }
 
+size_t co3_convert_encode_workspace_bytes(int64_t n, int32_t U, int32_t chunk_syms)
+{
+    if (n < 0 || U < 1 || !chunk_ok(chunk_syms)) return 0;
+    return co3_fused_workspace_bytes_impl(n, U, chunk_syms);
+}
+
 size_t co3_ps_aggregate_workspace_bytes(int64_t n, int32_t U, int32_t chunk_syms)
 {
     if (n < 0 || U < 1 || !chunk_ok(chunk_syms)) return 0;
@@ -199,6 +205,30 @@ int32_t co3_convert_ef_scaled(const float *g, float *err, uint8_t *sym, int64_t 
     if (!scale) return CO3_EINVAL;
     return convert_common(g, err, sym, n, U, stride, seg_off, nseg, const_cast<int32_t *>(anchor), CO3_ANCHOR_GIVEN,
                           scale, gamma, fmt, counts, stream);
+}
+
+int32_t co3_convert_encode(const float *g, float *err, int64_t n, int32_t U, int64_t stride, const int64_t *seg_off,
+                           int32_t nseg, int32_t *anchor, int32_t anchor_mode, float gamma, co3_fmt fmt, const void *codes,
+                           uint64_t *words, int64_t cap_words, int32_t chunk_syms, uint64_t *chunk_bitoff,
+                           uint64_t *total_bits, void *workspace, size_t ws_bytes, int32_t *status, void *stream)
+{
+    if (!fmt_ok(fmt) || !batch_ok(n, U, stride) || nseg < 1 || (seg_off == nullptr && nseg != 1)) return CO3_EINVAL;
+    if (!chunk_ok(chunk_syms) || cap_words < 0 || cap_words % 2 != 0) return CO3_EINVAL;
+    if (!g || !err || !anchor || !codes || !words || !chunk_bitoff || !total_bits || !workspace) return CO3_EINVAL;
+    if (!aligned(g, 16) || !aligned(err, 16) || !aligned(words, 16) || !aligned(codes, 8) || !aligned(workspace, 16))
+        return CO3_EINVAL;
+    if (anchor_mode != CO3_ANCHOR_GIVEN && anchor_mode != CO3_ANCHOR_FROM_ABSMAX_G) return CO3_EINVAL;
+    if (ws_bytes < co3_convert_encode_workspace_bytes(n, U, chunk_syms)) return CO3_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const FmtC fc(fmt);
+    if (anchor_mode == CO3_ANCHOR_FROM_ABSMAX_G) {
+        hipError_t e = co3_launch_fill(anchor, (int64_t)U * nseg, fc.F - 126, nullptr, 0, st);
+        if (e != hipSuccess) return CO3_EHIP;
+        e = co3_launch_absmax(g, n, U, stride, seg_off, nseg, anchor, st);
+        if (e != hipSuccess) return CO3_EHIP;
+    }
+    return hip_rc(co3_launch_convert_encode(g, err, n, U, stride, seg_off, nseg, anchor, gamma, fmt, codes, words, cap_words,
+                                            chunk_syms, chunk_bitoff, total_bits, workspace, status, st));
 }
 
 int32_t co3_moments(const float *g, const float *err, int64_t n, int32_t U, int64_t stride, const int64_t *seg_off,

@@ -10,6 +10,9 @@
 #define CO3_MAX_CODE_LEN 57     // (code << 6 | len) must fit 64 bits; u32 weights cannot reach it
 #define CO3_PACK_SYMS 1024      // symbols per encoder tile (one wavefront, 16 per lane)
 #define CO3_PACK_GROUP 16       // tiles whose sizes one workgroup of the sizes pass adds up
+#define CO3_FUSED_UNIT 256       // elements that one wavefront of the single-pass path converts and packs together
+#define CO3_FUSED_SLOT_WORDS 256 // 64-bit words of workspace per unit: room for 256 codewords of any length
+#define CO3_FUSED_GROUP 64       // units per group of the offset scan (= lanes of a wavefront)
 
 // Per-user code blob.  Bytes 0..K-1 (len) are the public wire header; the rest is private.
 struct Co3Code {
@@ -125,4 +128,39 @@ __device__ __forceinline__ float co3_code_value(uint32_t code, int e_min, int M)
     uint32_t nbits = (code << (23 - M)) + ((uint32_t)(e_min - 1 + 127) << 23);
     float sub = ldexpf((float)code, e_min - M);
     return f ? __uint_as_float(nbits) : sub;
+}
+
+// ------------------------------------------------------------------------------------------
+// Q_A on one value (Sec. III (i), nearest level, ties to even, saturating), returning the symbol
+// byte and its value.  All steps are exact: scaling by a power of two, rint, scaling back.
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ void co3_quantize(float x, int e_min, int A, int E, int M, int codemax, uint32_t &sym,
+                                             float &val)
+{
+    uint32_t bits = __float_as_uint(x);
+    uint32_t abits = bits & 0x7fffffffu;
+    float a = __uint_as_float(abits);
+    int ex = (int)(abits >> 23) - 127;          // fp32 subnormals read -127, below every e_min
+    int e = ex > e_min ? ex : e_min;            // clamped exponent
+    int qe = e - M;                             // exponent of the local quantum
+    float t = ldexpf(a, -qe);                   // |x| in quanta: exact, < 2^(M+1) for finite x
+    t = fminf(t, (float)(4 << M));              // Inf/NaN: keep the integer conversion defined
+    float r = rintf(t);                         // ties to even
+    int code = ((e - e_min) << M) + (int)r;     // a carry out of the mantissa lands in the next field
+    float mag = ldexpf(r, qe);
+    if (code > codemax) {                       // above the top binade
+        code = codemax;
+        mag = ldexpf((float)((2 << M) - 1), A - M);
+    }
+    uint32_t s = code ? (bits >> 31) : 0u;      // one zero only
+    sym = (s << (E + M)) | (uint32_t)code;
+    val = __uint_as_float(__float_as_uint(mag) | (s << 31));
+}
+
+// release/acquire fence at wavefront scope around a wavefront barrier: LDS written by some lanes is read by others
+__device__ __forceinline__ void co3_wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }

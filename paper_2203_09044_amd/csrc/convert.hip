@@ -129,33 +129,6 @@ __global__ __launch_bounds__(CV_BLOCK) void k_absmax(const float *__restrict__ g
     absmax_flush(m, anchor_u + cur_seg, red);
 }
 
-// ------------------------------------------------------------------------------------------
-// Q_A on one value (Sec. III (i), nearest level, ties to even, saturating), returning the symbol
-// byte and its value.  All steps are exact: scaling by a power of two, rint, scaling back.
-// ------------------------------------------------------------------------------------------
-__device__ __forceinline__ void co3_quantize(float x, int e_min, int A, int E, int M, int codemax, uint32_t &sym,
-                                             float &val)
-{
-    uint32_t bits = __float_as_uint(x);
-    uint32_t abits = bits & 0x7fffffffu;
-    float a = __uint_as_float(abits);
-    int ex = (int)(abits >> 23) - 127;          // fp32 subnormals read -127, below every e_min
-    int e = ex > e_min ? ex : e_min;            // clamped exponent
-    int qe = e - M;                             // exponent of the local quantum
-    float t = ldexpf(a, -qe);                   // |x| in quanta: exact, < 2^(M+1) for finite x
-    t = fminf(t, (float)(4 << M));              // Inf/NaN: keep the integer conversion defined
-    float r = rintf(t);                         // ties to even
-    int code = ((e - e_min) << M) + (int)r;     // a carry out of the mantissa lands in the next field
-    float mag = ldexpf(r, qe);
-    if (code > codemax) {                       // above the top binade
-        code = codemax;
-        mag = ldexpf((float)((2 << M) - 1), A - M);
-    }
-    uint32_t s = code ? (bits >> 31) : 0u;      // one zero only
-    sym = (s << (E + M)) | (uint32_t)code;
-    val = __uint_as_float(__float_as_uint(mag) | (s << 31));
-}
-
 // SCALED: the bias in its multiplier form (Sec. III (i) with the approximation of Sec. IV-B): the corrected
 // gradient is multiplied by c before it is rounded onto the grid of the given anchor, and the level
 // is divided by c again; one fp32 rounding per operation.

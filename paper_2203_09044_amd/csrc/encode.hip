@@ -524,6 +524,15 @@ __global__ __launch_bounds__(EN_BLOCK) void k_enc_pack(const uint8_t *__restrict
     }
 }
 
+hipError_t co3_launch_enc_scan(uint64_t *sizes, int64_t nsizes, int U, int64_t cap_words, uint64_t *chunk_bitoff,
+                               int64_t nchunks, uint64_t *total_bits, int32_t *status, hipStream_t st)
+{
+    Co3LaunchTimer tm(CO3_K_ENC_SCAN, st);
+    hipLaunchKernelGGL(k_enc_scan, dim3(U), dim3(SC_BLOCK), 0, st, sizes, nsizes, cap_words, chunk_bitoff, nchunks,
+                       total_bits, status);
+    return hipGetLastError();
+}
+
 // seg_off != NULL selects one code per tensor (codes[tensor], shared by the users) instead of codes[user]
 hipError_t co3_launch_encode(const uint8_t *sym, int64_t n, int U, int64_t stride, const void *codes, int K,
                              const int64_t *seg_off, int nseg, uint64_t *words, int64_t cap_words, int chunk_syms,
@@ -544,11 +553,8 @@ hipError_t co3_launch_encode(const uint8_t *sym, int64_t n, int U, int64_t strid
             hipLaunchKernelGGL(k_enc_sizes, dim3((unsigned)ngrp, U), dim3(EN_BLOCK), 0, st, sym, n, stride, codes, K,
                                tilesum, nblk, groupsum, ngrp, status);
     }
-    {
-        Co3LaunchTimer tm(CO3_K_ENC_SCAN, st);
-        hipLaunchKernelGGL(k_enc_scan, dim3(U), dim3(SC_BLOCK), 0, st, groupsum, ngrp, cap_words, chunk_bitoff, nchunks,
-                           total_bits, status);
-    }
+    if (co3_launch_enc_scan(groupsum, ngrp, U, cap_words, chunk_bitoff, nchunks, total_bits, status, st) != hipSuccess)
+        return hipGetLastError();
     if (nblk > 0) {
         const unsigned gx = (unsigned)((nblk + EN_WAVES - 1) / EN_WAVES);
         Co3LaunchTimer tm(CO3_K_ENC_PACK, st);

@@ -26,7 +26,7 @@ class Co3Pipeline:
     def __init__(self, U: int, n: int, fmt: Fmt, chunk_syms: int = 256, seg_off=None, gamma: float = 1.0,
                  cap_words: Optional[int] = None, device="cuda:0", fused_histogram: bool = True,
                  bias: str = "absmax", grid_anchor: Optional[int] = None, codes: str = "user", code_seg_off=None,
-                 statistics: bool = True):
+                 statistics: bool = True, single_pass: bool = False):
         if bias not in ("absmax", "moments"):
             raise ValueError("bias must be 'absmax' or 'moments'")
         if codes not in ("user", "layer"):
@@ -35,6 +35,10 @@ class Co3Pipeline:
         self.U, self.n, self.fmt, self.chunk_syms, self.gamma = U, n, fmt, chunk_syms, gamma
         self.fused_histogram = fused_histogram
         self.statistics = statistics      # False: fixed tables (designed from a model), no symbol counts are gathered
+        # fixed per-user tables only: conversion and compression in one pass, no symbol array (co3_convert_encode)
+        self.single_pass = single_pass
+        if single_pass and (codes != "user" or bias != "absmax"):
+            raise ValueError("single_pass needs per-user codes and the integer anchor")
         self.bias = bias
         dev = torch.device(device)
         self.device = dev
@@ -57,6 +61,8 @@ class Co3Pipeline:
         self.total_bits = torch.zeros((U,), dtype=torch.int64, **z)
         self.enc_ws = torch.zeros((max(B.encode_workspace_bytes(n, U), 8) // 8,), dtype=torch.int64, **z)
         self.agg_ws = torch.zeros((max(B.ps_aggregate_workspace_bytes(n, U, chunk_syms), 16),), dtype=torch.uint8, **z)
+        self.fused_ws = (torch.empty((B.convert_encode_workspace_bytes(n, U, chunk_syms),), dtype=torch.uint8, **z)
+                         if single_pass else None)
         self.avg = torch.zeros((self.stride,), dtype=torch.float32, **z)
         self.sym_dec = torch.zeros((U, self.stride), dtype=torch.uint8, **z)
         self.status = torch.zeros((1,), dtype=torch.int32, **z)
@@ -91,6 +97,12 @@ class Co3Pipeline:
                          seg_off=self.seg_off, counts=counts)
         if self.statistics and not self.fused_histogram and self.code_mode == "user":
             B.histogram(self.sym, self.n, self.fmt, self.counts)
+
+    def convert_encode(self, g: torch.Tensor, anchor_mode=B.ANCHOR_FROM_ABSMAX_G):
+        """Conversion and compression in one pass with the codes already in ``self.codes`` (single_pass)."""
+        B.convert_encode(g, self.err, self.n, self.anchor, anchor_mode, self.gamma, self.fmt, self.codes, self.words,
+                         self.chunk_syms, self.chunk_bitoff, self.total_bits, self.fused_ws, self.status,
+                         seg_off=self.seg_off)
 
     def build(self, weights: Optional[torch.Tensor] = None):
         """Per-user codes from the users' counts (or given weights [U][K]); per-tensor codes from the pooled
@@ -136,6 +148,10 @@ class Co3Pipeline:
     def step(self, g: torch.Tensor, weights: Optional[torch.Tensor] = None, rebuild: bool = True):
         """One whole iteration: users encode, the server decodes and averages.  ``rebuild=False`` keeps the
         codes of the previous call (fixed tables designed from a model)."""
+        if self.single_pass and not rebuild:
+            self.convert_encode(g)
+            self.aggregate()
+            return
         if self.bias == "moments":
             self.fit_bias(g)
         self.convert(g)

@@ -154,6 +154,38 @@ def test_c3_full(co3):
     properties_all_clients(pipe, w.n)
 
 
+def test_c3_single_pass_full(co3):
+    """The C3 shape with tables fixed before the iteration (designed from a GenNorm model, one per client) and
+    conversion + compression in one pass: 2 chained iterations, memory, stream words, chunk offsets and
+    the average of every client against the oracle's convert_ef followed by encode, bit for bit."""
+    w = inp.c3()
+    fmt = co3.Fmt(w.E, w.M)
+    f = oracle.Fmt(w.E, w.M)
+    betas = inp.c3_client_betas(w.U)
+    pipe = co3.Co3Pipeline(w.U, w.n, fmt, chunk_syms=256, statistics=False, single_pass=True, cap_words=w.n // 4)
+    g = pipe.new_gradient_buffer()
+    weights = np.stack([oracle.model_weights(-7, f, float(betas[u]), 1e-3) for u in range(w.U)])
+    pipe.build(torch.from_numpy(weights.view(np.int32)).cuda())
+    errs = [np.zeros(w.n, np.float32) for _ in range(w.U)]
+    with ThreadPoolExecutor(max_workers=10) as pool:
+        for t in range(1, 3):
+            host = fill_from_device(pipe, g, lambda u: inp.device_gennorm(w.n, float(betas[u]), 1e-3, 3700 + 10 * t + u))
+            pipe.step(g, rebuild=False)
+            assert pipe.poll() == 0
+            refs = list(pool.map(oracle_client, [(host[u], errs[u], w.E, w.M, None, 256, weights[u]) for u in range(w.U)]))
+            for u in range(w.U):
+                ref = refs[u]
+                assert np.array_equal(pipe.anchor[u].cpu().numpy(), ref["A"]), "anchor"
+                assert np.array_equal(u32(pipe.err[u, :w.n]), ref["err"].view(np.uint32)), "error vector"
+                assert int(pipe.total_bits[u].item()) == ref["total"], "total bits"
+                assert np.array_equal(u64(pipe.chunk_bitoff[u]), ref["off"]), "chunk offsets"
+                nw = (ref["total"] + 63) // 64
+                assert np.array_equal(u64(pipe.words[u, :nw]), ref["words"][:nw]), "stream words"
+                errs[u] = ref["err"]
+            want = oracle.aggregate(np.stack([r["sym"] for r in refs]), np.stack([r["A"] for r in refs]), f)
+            assert np.array_equal(u32(pipe.avg[:w.n]), want.view(np.uint32)), "average"
+
+
 def test_c3_bias_rule_full(co3):
     """The C3 shape (10 clients x 11,173,962) on the paper's 4-bit format E1M2 with the bias rule: moment
     sums and multipliers against the oracle (1e-12 relative / 2 units in the last place), then one whole
