@@ -10,8 +10,8 @@
 #define CO3_MAX_CODE_LEN 57     // (code << 6 | len) must fit 64 bits; u32 weights cannot reach it
 #define CO3_PACK_SYMS 1024      // symbols per encoder tile (one wavefront, 16 per lane)
 #define CO3_PACK_GROUP 16       // tiles whose sizes one workgroup of the sizes pass adds up
-#define CO3_FUSED_UNIT 256       // elements that one wavefront of the single-pass path converts and packs together
-#define CO3_FUSED_SLOT_WORDS 256 // 64-bit words of workspace per unit: room for 256 codewords of any length
+#define CO3_FUSED_UNIT 1024      // elements that one wavefront of the single-pass path converts and packs together
+#define CO3_FUSED_SLOT_WORDS 1024 // 64-bit words of workspace per unit: room for 1024 codewords of any length
 #define CO3_FUSED_GROUP 64       // units per group of the offset scan (= lanes of a wavefront)
 
 // Per-user code blob.  Bytes 0..K-1 (len) are the public wire header; the rest is private.

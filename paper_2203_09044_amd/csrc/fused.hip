@@ -15,8 +15,11 @@
 #define FU_BLOCK 256
 #define FU_WAVES (FU_BLOCK / CO3_WAVE)
 #define FU_VEC 4
-#define FU_TILE (FU_BLOCK * FU_VEC)             // elements of one block step: four units, one per wavefront
-static_assert(CO3_FUSED_UNIT == CO3_WAVE * FU_VEC, "unit geometry");
+#define FU_RUN (CO3_WAVE * FU_VEC)              // consecutive elements that one load of a wavefront covers
+#define FU_SUB (CO3_FUSED_UNIT / FU_RUN)        // runs per unit
+#define FU_TILE (FU_WAVES * CO3_FUSED_UNIT)     // elements of one block step: four units, one per wavefront
+static_assert(CO3_FUSED_UNIT % (2 * FU_RUN) == 0, "unit geometry: an even number of runs");
+static_assert(FU_RUN * CO3_MAX_CODE_LEN < 65536, "the bits of a run fit 16 bits");
 static_assert(CO3_FUSED_SLOT_WORDS * 64 >= CO3_FUSED_UNIT * CO3_MAX_CODE_LEN, "a slot holds any unit");
 
 __device__ __forceinline__ const Co3Code *fcode_of(const void *codes, int u)
@@ -34,6 +37,10 @@ __device__ __forceinline__ void fused_stage(unsigned long long *stage, uint64_t 
 }
 
 // ---- pass 1: conversion with error correction, codeword lookup, unit-local packing -----------
+// A unit is FU_SUB runs of 256 elements; lane l holds elements 4l..4l+3 of every run, so each load is
+// one contiguous KiB per wavefront.  The bit position of a lane's codewords inside the unit comes from
+// one scan over the lanes for all runs at once: the lane totals of two runs share a 32-bit word (a run
+// has at most 256 * 57 < 2^16 bits).
 __global__ __launch_bounds__(FU_BLOCK) void k_convert_stage(const float *__restrict__ g, float *__restrict__ err,
                                                              int64_t n, int64_t stride,
                                                              const int64_t *__restrict__ seg_off_g, int nseg,
@@ -50,10 +57,12 @@ __global__ __launch_bounds__(FU_BLOCK) void k_convert_stage(const float *__restr
     __shared__ uint64_t enc_s[256];
     __shared__ unsigned long long stage_all[FU_WAVES][CO3_FUSED_SLOT_WORDS + 1];
     const int64_t *seg_off = co3_cache_segs(seg_off_g, nseg, seg_cache);
-    const int u = blockIdx.y;
+    // users and ranges in the reverse of the anchor pass's order: what that pass left in the last-level
+    // cache is read first
+    const int u = gridDim.y - 1 - blockIdx.y;
+    const int64_t range = gridDim.x - 1 - blockIdx.x;
     const Co3Code *cd = fcode_of(codes, u);
     enc_s[threadIdx.x] = (int)threadIdx.x < K ? cd->enc[threadIdx.x] : 0ull;
-    const bool short_code = cd->maxlen <= 16u;       // four codewords of a lane fit 64 bits
     __syncthreads();
 
     const float *gu = g + (int64_t)u * stride;
@@ -67,75 +76,109 @@ __global__ __launch_bounds__(FU_BLOCK) void k_convert_stage(const float *__restr
     uint32_t *chunk_local_u = chunk_local + (int64_t)u * nchunks;
     bool nocode = false;
 
-    const int64_t beg = (int64_t)blockIdx.x * per_block;                 // a multiple of FU_TILE
+    const int64_t beg = range * per_block;                               // a multiple of FU_TILE
     const int64_t end = beg + per_block < n ? beg + per_block : n;
     for (int64_t t0 = beg; t0 < end; t0 += FU_TILE) {
         const int64_t unit = t0 / CO3_FUSED_UNIT + wave;
         const int64_t u0 = unit * CO3_FUSED_UNIT;                         // first element of the wavefront's unit
         if (u0 >= n) continue;                                            // uniform over the wavefront
-        const int64_t i = u0 + (int64_t)lane * FU_VEC;
-        const int64_t left = n - i;
-        const int nvalid = left >= FU_VEC ? FU_VEC : (left > 0 ? (int)left : 0);
-        float gv[FU_VEC], ev[FU_VEC];
-        if (nvalid == FU_VEC) {
-            const float4 a = ld_stream_f4(gu + i), b = ld_stream_f4(eu + i);
-            gv[0] = a.x; gv[1] = a.y; gv[2] = a.z; gv[3] = a.w;
-            ev[0] = b.x; ev[1] = b.y; ev[2] = b.z; ev[3] = b.w;
+        const bool whole = u0 + CO3_FUSED_UNIT <= n;                      // uniform
+        float4 gv[FU_SUB], ev[FU_SUB];
+        if (whole) {
+#pragma unroll
+            for (int r = 0; r < FU_SUB; ++r) {
+                const int64_t i = u0 + r * FU_RUN + lane * FU_VEC;
+                gv[r] = ld_stream_f4(gu + i);
+                ev[r] = ld_stream_f4(eu + i);
+            }
         } else {
 #pragma unroll
-            for (int k = 0; k < FU_VEC; ++k) {
-                gv[k] = k < nvalid ? gu[i + k] : 0.0f;
-                ev[k] = k < nvalid ? eu[i + k] : 0.0f;
+            for (int r = 0; r < FU_SUB; ++r) {
+                const int64_t i = u0 + r * FU_RUN + lane * FU_VEC;
+                gv[r].x = i + 0 < n ? gu[i + 0] : 0.0f; ev[r].x = i + 0 < n ? eu[i + 0] : 0.0f;
+                gv[r].y = i + 1 < n ? gu[i + 1] : 0.0f; ev[r].y = i + 1 < n ? eu[i + 1] : 0.0f;
+                gv[r].z = i + 2 < n ? gu[i + 2] : 0.0f; ev[r].z = i + 2 < n ? eu[i + 2] : 0.0f;
+                gv[r].w = i + 3 < n ? gu[i + 3] : 0.0f; ev[r].w = i + 3 < n ? eu[i + 3] : 0.0f;
             }
         }
         // anchor: one tensor for the whole unit (the usual case), else looked up per element
-        const int64_t u_last = (u0 + CO3_FUSED_UNIT < n ? u0 + CO3_FUSED_UNIT : n) - 1;
+        const int64_t u_last = (whole ? u0 + CO3_FUSED_UNIT : n) - 1;
         const int s_lo = co3_find_seg(seg_off, nseg, u0), s_hi = co3_find_seg(seg_off, nseg, u_last);
-        uint64_t ent[FU_VEC];
-        uint32_t nb = 0;
-        float en[FU_VEC];
+        const int A_unit = anchor_u[s_lo];
+
+        uint64_t acc[FU_SUB];            // the lane's four codewords of a run, joined (whole if they fit 64 bits)
+        uint32_t qpack[FU_SUB];          // the four symbols of a run (looked up again if they do not)
+        uint32_t nb[FU_SUB];             // bits of the lane's four codewords of a run
 #pragma unroll
-        for (int k = 0; k < FU_VEC; ++k) {
-            const int sg = s_lo == s_hi ? s_lo : co3_find_seg(seg_off, nseg, i + k < n ? i + k : n - 1);
-            const int A = anchor_u[sg];
-            const float x = gv[k] + gamma * ev[k];       // no contraction (build flag): one rounding per operation
-            uint32_t q;
-            float v;
-            co3_quantize(x, A - F + 1, A, E, M, codemax, q, v);
-            en[k] = x - v;
-            const uint64_t e = k < nvalid ? enc_s[q] : 0ull;
-            nocode |= k < nvalid && (e & 63u) == 0u;
-            ent[k] = e;
-            nb += (uint32_t)(e & 63u);
-        }
-        if (nvalid == FU_VEC) {
-            st_stream_f4(eu + i, make_float4(en[0], en[1], en[2], en[3]));
-        } else {
+        for (int r = 0; r < FU_SUB; ++r) {
+            const int64_t i = u0 + r * FU_RUN + lane * FU_VEC;
+            const float ga[FU_VEC] = {gv[r].x, gv[r].y, gv[r].z, gv[r].w};
+            const float ea[FU_VEC] = {ev[r].x, ev[r].y, ev[r].z, ev[r].w};
+            float en[FU_VEC];
+            acc[r] = 0;
+            qpack[r] = 0;
+            nb[r] = 0;
 #pragma unroll
-            for (int k = 0; k < FU_VEC; ++k)
-                if (k < nvalid) eu[i + k] = en[k];
+            for (int k = 0; k < FU_VEC; ++k) {
+                const bool valid = whole || i + k < n;
+                const int A = s_lo == s_hi ? A_unit : anchor_u[co3_find_seg(seg_off, nseg, valid ? i + k : n - 1)];
+                const float x = ga[k] + gamma * ea[k];   // no contraction (build flag): one rounding per operation
+                uint32_t q;
+                float v;
+                co3_quantize(x, A - F + 1, A, E, M, codemax, q, v);
+                en[k] = x - v;
+                const uint64_t e = valid ? enc_s[q] : 0ull;
+                const uint32_t l = (uint32_t)(e & 63u);
+                nocode |= valid && l == 0u;
+                acc[r] = (acc[r] << l) | (e >> 6);
+                qpack[r] |= q << (8 * k);
+                nb[r] += l;
+            }
+            if (whole) {
+                st_stream_f4(eu + i, make_float4(en[0], en[1], en[2], en[3]));
+            } else {
+#pragma unroll
+                for (int k = 0; k < FU_VEC; ++k)
+                    if (i + k < n) eu[i + k] = en[k];
+            }
         }
-        const uint32_t incl = wave_scan_incl_u32(nb, lane);
-        const uint32_t excl = incl - nb;
-        const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)incl, CO3_WAVE - 1);
-        if (nvalid > 0 && (i & (int64_t)(chunk_syms - 1)) == 0) chunk_local_u[i / chunk_syms] = excl;
+        // positions: one scan per pair of runs
+        uint32_t pos[FU_SUB], total = 0;
+#pragma unroll
+        for (int r = 0; r < FU_SUB; r += 2) {
+            const uint32_t both = nb[r] | (nb[r + 1] << 16);
+            const uint32_t incl = wave_scan_incl_u32(both, lane);
+            const uint32_t tot = (uint32_t)__builtin_amdgcn_readlane((int)incl, CO3_WAVE - 1);
+            pos[r] = total + (incl & 0xffffu) - nb[r];
+            total += tot & 0xffffu;
+            pos[r + 1] = total + (incl >> 16) - nb[r + 1];
+            total += tot >> 16;
+        }
+        // chunk index: position, inside the unit, of every chunk's first symbol (chunks start at multiples of 64)
+#pragma unroll
+        for (int r = 0; r < FU_SUB; ++r) {
+            const int64_t i = u0 + r * FU_RUN + lane * FU_VEC;
+            if (i < n && (i & (int64_t)(chunk_syms - 1)) == 0) chunk_local_u[i / chunk_syms] = pos[r];
+        }
 
         // the unit's bits, packed from bit 0 of the wavefront's LDS window, then copied to the unit's slot
         const uint32_t nwords = (total + 63u) >> 6;                       // uniform; <= CO3_FUSED_SLOT_WORDS
         for (uint32_t w = lane; w <= nwords; w += CO3_WAVE) stage[w] = 0ull;    // one word of slack for the straddle test
         co3_wave_lds_sync();
-        if (short_code) {
-            uint64_t acc = 0;
 #pragma unroll
-            for (int k = 0; k < FU_VEC; ++k) acc = (acc << (ent[k] & 63u)) | (ent[k] >> 6);
-            if (nb) fused_stage(stage, acc, nb, excl);
-        } else {
-            uint32_t pos = excl;
+        for (int r = 0; r < FU_SUB; ++r) {
+            if (nb[r] <= 64u) {                      // the usual case: the lane's four codewords as one piece
+                if (nb[r]) fused_stage(stage, acc[r], nb[r], pos[r]);
+            } else {                                 // codeword by codeword, looked up again
+                uint32_t p = pos[r];
 #pragma unroll
-            for (int k = 0; k < FU_VEC; ++k) {
-                const uint32_t l = (uint32_t)(ent[k] & 63u);
-                if (l) fused_stage(stage, ent[k] >> 6, l, pos);
-                pos += l;
+                for (int k = 0; k < FU_VEC; ++k) {
+                    const bool valid = whole || u0 + r * FU_RUN + lane * FU_VEC + k < n;
+                    const uint64_t e = enc_s[(qpack[r] >> (8 * k)) & 0xffu];
+                    const uint32_t l = valid ? (uint32_t)(e & 63u) : 0u;
+                    if (l) fused_stage(stage, e >> 6, l, p);
+                    p += l;
+                }
             }
         }
         co3_wave_lds_sync();
@@ -161,9 +204,25 @@ __global__ __launch_bounds__(CO3_WAVE) void k_unit_groups(const uint32_t *__rest
 }
 
 // ---- pass 4: every slot to its place in the stream; chunk index -------------------------------
-// One wavefront per four consecutive units.  Stream word gw belongs to the unit that holds its first
-// bit; its content is 64 bits of the unit's slot from local bit 64*gw - D on (D = stream position of
-// the unit), and where the unit ends inside the word, the leading bits of the next unit's slot.
+// One wavefront per CP_UNITS consecutive units (all in one group of the scan).  Stream word gw belongs
+// to the unit that holds its first bit; its content is 64 bits of the unit's slot from local bit
+// 64*gw - D on (D = stream position of the unit), and where the unit ends inside the word, the leading
+// bits of the next unit's slot.  The first 64 owned words of all units are loaded before any is stored.
+#define CP_UNITS 4
+static_assert(CO3_FUSED_GROUP % CP_UNITS == 0, "the units of a wavefront share a group");
+
+__device__ __forceinline__ uint64_t compact_word(uint64_t s0, uint64_t s1, uint32_t sh, uint32_t a, uint32_t size,
+                                                 uint64_t next0)
+{
+    uint64_t v = sh ? (s0 << sh) | (s1 >> (64u - sh)) : s0;
+    const uint32_t rem = size - (a * 64u + sh);                          // bits of this unit from the word's first bit on
+    if (rem < 64u) {                                                     // the unit ends inside this word
+        v &= ~0ull << (64u - rem);
+        v |= next0 >> rem;
+    }
+    return v;
+}
+
 __global__ __launch_bounds__(FU_BLOCK) void k_compact(const uint64_t *__restrict__ slots,
                                                        const uint32_t *__restrict__ unit_bits,
                                                        const uint32_t *__restrict__ unit_off,
@@ -174,65 +233,67 @@ __global__ __launch_bounds__(FU_BLOCK) void k_compact(const uint64_t *__restrict
 {
     const int u = blockIdx.y;
     const int lane = threadIdx.x & (CO3_WAVE - 1);
-    const int64_t tile = (int64_t)blockIdx.x * FU_WAVES + threadIdx.x / CO3_WAVE;
-    const int64_t unit0 = tile * 4;
+    const int64_t unit0 = ((int64_t)blockIdx.x * FU_WAVES + threadIdx.x / CO3_WAVE) * CP_UNITS;
     if (unit0 >= nunits) return;
-    const uint64_t *slots_u = slots + (int64_t)u * nunits * CO3_FUSED_SLOT_WORDS;
     const uint32_t *bits_u = unit_bits + (int64_t)u * nunits;
     const uint32_t *off_u = unit_off + (int64_t)u * nunits;
-    const uint64_t gbase = groupoff[(int64_t)u * ngrp + unit0 / CO3_FUSED_GROUP];    // the four units share a group
-    uint64_t D[4];
-    uint32_t size[4];
+    const uint64_t gbase = groupoff[(int64_t)u * ngrp + unit0 / CO3_FUSED_GROUP];
+    // sizes of the wavefront's units and of the one after them (lane k holds unit0 + k), offsets likewise
+    const bool have = lane <= CP_UNITS && unit0 + lane < nunits;
+    const uint32_t my_size = have ? bits_u[unit0 + lane] : 0u;
+    const uint32_t my_off = have ? off_u[unit0 + lane] : 0u;
+    uint32_t size[CP_UNITS + 1], sh[CP_UNITS];
+    uint64_t d[CP_UNITS];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const bool have = unit0 + k < nunits;
-        size[k] = have ? bits_u[unit0 + k] : 0u;
-        D[k] = gbase + (have ? off_u[unit0 + k] : 0u);
+    for (int k = 0; k <= CP_UNITS; ++k) size[k] = (uint32_t)__builtin_amdgcn_readlane((int)my_size, k);
+#pragma unroll
+    for (int k = 0; k < CP_UNITS; ++k) {
+        d[k] = gbase + (uint32_t)__builtin_amdgcn_readlane((int)my_off, k);
+        // every owned word of a unit starts at the same bit of a slot word (64 * gw - d is the same modulo
+        // 64); the amount is uniform and kept in a scalar register
+        sh[k] = (0u - (uint32_t)d[k]) & 63u;
     }
-#pragma unroll
-    for (int k = 1; k < 4; ++k)
-        if (unit0 + k >= nunits) D[k] = D[k - 1] + size[k - 1];
 
-    // chunk index: chunks whose first element lies in this tile (at most 16: chunks have at least 64 symbols)
+    // chunk index: chunks whose first element lies in these units (chunks have at least 64 symbols)
     {
         const int64_t e0 = unit0 * CO3_FUSED_UNIT;
-        const int64_t c0 = (e0 + chunk_syms - 1) / chunk_syms;
-        const int64_t c = c0 + lane;
+        const int64_t c = (e0 + chunk_syms - 1) / chunk_syms + lane;
         const int64_t e = c * chunk_syms;
-        if (e < n && e < e0 + 4 * CO3_FUSED_UNIT) {
+        if (e < n && e < e0 + (int64_t)CP_UNITS * CO3_FUSED_UNIT) {
             const int k = (int)((e - e0) / CO3_FUSED_UNIT);
-            const uint64_t d = k == 0 ? D[0] : k == 1 ? D[1] : k == 2 ? D[2] : D[3];
-            chunk_bitoff[(int64_t)u * (nchunks + 1) + c] = d + chunk_local[(int64_t)u * nchunks + c];
+            uint64_t dk = d[0];
+#pragma unroll
+            for (int j = 1; j < CP_UNITS; ++j) dk = k == j ? d[j] : dk;
+            chunk_bitoff[(int64_t)u * (nchunks + 1) + c] = dk + chunk_local[(int64_t)u * nchunks + c];
         }
     }
-    // beyond the capacity nothing is written (the scan pass has reported it); uniform over the wavefront
-    if ((D[3] + size[3] + 63) / 64 > (uint64_t)cap_words) return;
+    static_assert(CP_UNITS * CO3_FUSED_UNIT / 64 <= CO3_WAVE, "one lane per possible chunk start");
+
     uint64_t *wu = words + (int64_t)u * cap_words;
+    const uint64_t *slot0 = slots + ((int64_t)u * nunits + unit0) * CO3_FUSED_SLOT_WORDS;
+    uint64_t s0[CP_UNITS], s1[CP_UNITS], next0[CP_UNITS], gw0[CP_UNITS];
+    uint32_t nown[CP_UNITS];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        if (size[k] == 0u) continue;                                     // uniform
-        const uint64_t d = D[k];
-        const uint64_t gw0 = (d + 63) >> 6, gw1 = (d + size[k] + 63) >> 6;     // owned words [gw0, gw1)
+    for (int k = 0; k < CP_UNITS; ++k) {
+        const uint64_t *slot = slot0 + (int64_t)k * CO3_FUSED_SLOT_WORDS;
+        gw0[k] = (d[k] + 63) >> 6;                                       // owned words [gw0, gw0 + nown)
+        const uint64_t gw1 = (d[k] + size[k] + 63) >> 6;
+        // beyond the capacity nothing is written (the scan pass has reported it)
+        nown[k] = size[k] == 0u || gw1 > (uint64_t)cap_words ? 0u : (uint32_t)(gw1 - gw0[k]);
         const uint32_t nw = (size[k] + 63u) >> 6;                        // words of the slot that hold bits
-        const uint64_t *slot = slots_u + (unit0 + k) * CO3_FUSED_SLOT_WORDS;
-        const bool has_next = unit0 + k + 1 < nunits;
-        const uint64_t next0 = has_next ? slot[CO3_FUSED_SLOT_WORDS] : 0ull;   // first word of the next unit's slot
-        const bool next_empty = !has_next || bits_u[unit0 + k + 1] == 0u;
-        // every owned word starts at the same bit of a slot word: 64 * gw - d is the same modulo 64
-        const uint32_t sh = (uint32_t)__builtin_amdgcn_readfirstlane((int)((0u - (uint32_t)d) & 63u));
-        for (uint64_t gw = gw0 + lane; gw < gw1; gw += CO3_WAVE) {
-            const uint32_t l = (uint32_t)((gw << 6) - d);                // local bit of the word's first bit
-            const uint32_t a = l >> 6;
-            const uint64_t s0 = slot[a];
-            const uint64_t s1 = slot[a + 1u < nw ? a + 1u : a];
-            uint64_t v = sh ? (s0 << sh) | ((a + 1u < nw ? s1 : 0ull) >> (64u - sh)) : s0;
-            const uint32_t rem = size[k] - l;                            // bits of this unit from l on
-            if (rem < 64u) {                                             // the unit ends inside this word
-                v &= ~0ull << (64u - rem);
-                if (!next_empty) v |= next0 >> rem;
-            }
-            wu[gw] = v;
-        }
+        s0[k] = (uint32_t)lane < nown[k] ? slot[lane] : 0ull;
+        s1[k] = (uint32_t)lane < nown[k] && (uint32_t)lane + 1u < nw ? slot[lane + 1] : 0ull;
+        next0[k] = nown[k] && size[k + 1] ? slot[CO3_FUSED_SLOT_WORDS] : 0ull;   // first word of the next unit's slot
+    }
+#pragma unroll
+    for (int k = 0; k < CP_UNITS; ++k)
+        if ((uint32_t)lane < nown[k]) wu[gw0[k] + lane] = compact_word(s0[k], s1[k], sh[k], lane, size[k], next0[k]);
+#pragma unroll
+    for (int k = 0; k < CP_UNITS; ++k) {                                 // units of more than 64 words
+        const uint64_t *slot = slot0 + (int64_t)k * CO3_FUSED_SLOT_WORDS;
+        const uint32_t nw = (size[k] + 63u) >> 6;
+        for (uint32_t a = lane + CO3_WAVE; a < nown[k]; a += CO3_WAVE)
+            wu[gw0[k] + a] = compact_word(slot[a], a + 1u < nw ? slot[a + 1u] : 0ull, sh[k], a, size[k], next0[k]);
     }
 }
 
@@ -293,9 +354,9 @@ hipError_t co3_launch_convert_encode(const float *g, float *err, int64_t n, int 
     hipError_t e = co3_launch_enc_scan(groupsum, ngrp, U, cap_words, chunk_bitoff, nchunks, total_bits, status, st);
     if (e != hipSuccess) return e;
     if (nunits > 0) {
-        const int64_t ntiles = (nunits + 3) / 4;
         Co3LaunchTimer tm(CO3_K_ENC_PACK, st);
-        hipLaunchKernelGGL(k_compact, dim3((unsigned)((ntiles + FU_WAVES - 1) / FU_WAVES), U), dim3(FU_BLOCK), 0, st,
+        const int64_t per_block = (int64_t)FU_WAVES * CP_UNITS;
+        hipLaunchKernelGGL(k_compact, dim3((unsigned)((nunits + per_block - 1) / per_block), U), dim3(FU_BLOCK), 0, st,
                            (const uint64_t *)slots, (const uint32_t *)unit_bits, (const uint32_t *)unit_off,
                            (const uint64_t *)groupsum, (const uint32_t *)chunk_local, n, nunits, ngrp, words, cap_words,
                            chunk_syms, chunk_bitoff, nchunks);

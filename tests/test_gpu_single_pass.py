@@ -64,7 +64,8 @@ def test_formats(co3, E, M):
     run(co3, 2, 5 * 2048 + 1237, E, M, 256, betas=[0.7, 1.4], T=3)
 
 
-@pytest.mark.parametrize("n", [0, 1, 3, 4, 5, 255, 256, 257, 1023, 1024, 1025, 4096 + 8, 65_536 + 5, 300_001])
+@pytest.mark.parametrize("n", [0, 1, 3, 4, 5, 255, 256, 257, 1023, 1024, 1025, 2047, 4095, 4096, 4096 + 8, 65_535, 65_536,
+                               65_536 + 5, 2 * 65_536 + 1024, 300_001])
 def test_sizes(co3, n):
     run(co3, 3, n, 3, 1, 64, betas=[0.5, 1.0, 1.5])
 
@@ -80,8 +81,8 @@ def test_tensors_and_decay(co3):
 
 
 def test_long_codewords(co3):
-    """Fibonacci weights: codewords up to 45 bits, so a lane's four codewords need more than one staging
-    operation and a unit's bits spread over many words of its slot."""
+    """Fibonacci weights: codewords up to 45 bits, so a lane's four codewords often exceed 64 bits (staged one by
+    one) and a unit's bits fill several hundred words of its slot."""
     fib = [1, 1]
     while len(fib) < 46:
         fib.append(fib[-1] + fib[-2])
