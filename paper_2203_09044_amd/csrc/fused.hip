@@ -3,7 +3,7 @@
 // error correction, fp conversion and compression without the symbol array in between.
 //
 // The stream position of a codeword depends on all symbols before it, so the pass cannot write the
-// stream itself.  Each wavefront converts a unit of 256 consecutive elements (four per lane), packs the
+// stream itself.  Each wavefront converts a unit of 1024 consecutive elements (sixteen per lane), packs the
 // unit's codewords from bit 0 of a private slot of the workspace and records the unit's length; a
 // small kernel turns the lengths into offsets within groups of 64 units, the packer's scan kernel into
 // stream offsets of the groups, and a last kernel moves every slot to its place in the stream (a funnel
@@ -34,6 +34,79 @@ __device__ __forceinline__ void fused_stage(unsigned long long *stage, uint64_t 
     const uint32_t w = pos >> 6, o = pos & 63u;
     atomicOr(&stage[w], (unsigned long long)(v >> o));
     if (o + nb > 64u) atomicOr(&stage[w + 1], (unsigned long long)(v << (64u - o)));
+}
+
+// One unit's elements: error correction, conversion, new memory, codeword lookup.  PLAIN: all 1024
+// elements exist and lie in one tensor (vector loads and stores, one anchor, no branches between the
+// elements, so that the table reads of a lane overlap); otherwise every access is guarded and the
+// anchor is looked up per element.  Returns whether a symbol without a codeword was met.
+struct Fu_unit_args {
+    const float *gu;
+    float *eu;
+    int64_t n, u0;
+    int lane;
+    const int64_t *seg_off;
+    int nseg;
+    const int32_t *anchor_u;
+    int A_unit;
+    float gamma;
+    int E, M, F, codemax;
+    const uint64_t *enc_s;
+};
+
+template <bool PLAIN>
+__device__ __forceinline__ bool fused_convert_unit(const Fu_unit_args &a, uint64_t (&acc)[FU_SUB], uint32_t (&qpack)[FU_SUB],
+                                                   uint32_t (&nb)[FU_SUB])
+{
+    float4 gv[FU_SUB], ev[FU_SUB];
+#pragma unroll
+    for (int r = 0; r < FU_SUB; ++r) {
+        const int64_t i = a.u0 + r * FU_RUN + a.lane * FU_VEC;
+        if (PLAIN) {
+            gv[r] = ld_stream_f4(a.gu + i);
+            ev[r] = ld_stream_f4(a.eu + i);
+        } else {
+            gv[r].x = i + 0 < a.n ? a.gu[i + 0] : 0.0f; ev[r].x = i + 0 < a.n ? a.eu[i + 0] : 0.0f;
+            gv[r].y = i + 1 < a.n ? a.gu[i + 1] : 0.0f; ev[r].y = i + 1 < a.n ? a.eu[i + 1] : 0.0f;
+            gv[r].z = i + 2 < a.n ? a.gu[i + 2] : 0.0f; ev[r].z = i + 2 < a.n ? a.eu[i + 2] : 0.0f;
+            gv[r].w = i + 3 < a.n ? a.gu[i + 3] : 0.0f; ev[r].w = i + 3 < a.n ? a.eu[i + 3] : 0.0f;
+        }
+    }
+    bool nocode = false;
+#pragma unroll
+    for (int r = 0; r < FU_SUB; ++r) {
+        const int64_t i = a.u0 + r * FU_RUN + a.lane * FU_VEC;
+        const float ga[FU_VEC] = {gv[r].x, gv[r].y, gv[r].z, gv[r].w};
+        const float ea[FU_VEC] = {ev[r].x, ev[r].y, ev[r].z, ev[r].w};
+        float en[FU_VEC];
+        acc[r] = 0;
+        qpack[r] = 0;
+        nb[r] = 0;
+#pragma unroll
+        for (int k = 0; k < FU_VEC; ++k) {
+            const bool valid = PLAIN || i + k < a.n;
+            const int A = PLAIN ? a.A_unit : a.anchor_u[co3_find_seg(a.seg_off, a.nseg, valid ? i + k : a.n - 1)];
+            const float x = ga[k] + a.gamma * ea[k];     // no contraction (build flag): one rounding per operation
+            uint32_t q;
+            float v;
+            co3_quantize(x, A - a.F + 1, A, a.E, a.M, a.codemax, q, v);
+            en[k] = x - v;
+            const uint64_t e = valid ? a.enc_s[q] : 0ull;
+            const uint32_t l = (uint32_t)(e & 63u);
+            nocode |= valid && l == 0u;
+            acc[r] = (acc[r] << l) | (e >> 6);
+            qpack[r] |= q << (8 * k);
+            nb[r] += l;
+        }
+        if (PLAIN) {
+            st_stream_f4(a.eu + i, make_float4(en[0], en[1], en[2], en[3]));
+        } else {
+#pragma unroll
+            for (int k = 0; k < FU_VEC; ++k)
+                if (i + k < a.n) a.eu[i + k] = en[k];
+        }
+    }
+    return nocode;
 }
 
 // ---- pass 1: conversion with error correction, codeword lookup, unit-local packing -----------
@@ -83,65 +156,15 @@ __global__ __launch_bounds__(FU_BLOCK) void k_convert_stage(const float *__restr
         const int64_t u0 = unit * CO3_FUSED_UNIT;                         // first element of the wavefront's unit
         if (u0 >= n) continue;                                            // uniform over the wavefront
         const bool whole = u0 + CO3_FUSED_UNIT <= n;                      // uniform
-        float4 gv[FU_SUB], ev[FU_SUB];
-        if (whole) {
-#pragma unroll
-            for (int r = 0; r < FU_SUB; ++r) {
-                const int64_t i = u0 + r * FU_RUN + lane * FU_VEC;
-                gv[r] = ld_stream_f4(gu + i);
-                ev[r] = ld_stream_f4(eu + i);
-            }
-        } else {
-#pragma unroll
-            for (int r = 0; r < FU_SUB; ++r) {
-                const int64_t i = u0 + r * FU_RUN + lane * FU_VEC;
-                gv[r].x = i + 0 < n ? gu[i + 0] : 0.0f; ev[r].x = i + 0 < n ? eu[i + 0] : 0.0f;
-                gv[r].y = i + 1 < n ? gu[i + 1] : 0.0f; ev[r].y = i + 1 < n ? eu[i + 1] : 0.0f;
-                gv[r].z = i + 2 < n ? gu[i + 2] : 0.0f; ev[r].z = i + 2 < n ? eu[i + 2] : 0.0f;
-                gv[r].w = i + 3 < n ? gu[i + 3] : 0.0f; ev[r].w = i + 3 < n ? eu[i + 3] : 0.0f;
-            }
-        }
         // anchor: one tensor for the whole unit (the usual case), else looked up per element
         const int64_t u_last = (whole ? u0 + CO3_FUSED_UNIT : n) - 1;
         const int s_lo = co3_find_seg(seg_off, nseg, u0), s_hi = co3_find_seg(seg_off, nseg, u_last);
-        const int A_unit = anchor_u[s_lo];
-
         uint64_t acc[FU_SUB];            // the lane's four codewords of a run, joined (whole if they fit 64 bits)
         uint32_t qpack[FU_SUB];          // the four symbols of a run (looked up again if they do not)
         uint32_t nb[FU_SUB];             // bits of the lane's four codewords of a run
-#pragma unroll
-        for (int r = 0; r < FU_SUB; ++r) {
-            const int64_t i = u0 + r * FU_RUN + lane * FU_VEC;
-            const float ga[FU_VEC] = {gv[r].x, gv[r].y, gv[r].z, gv[r].w};
-            const float ea[FU_VEC] = {ev[r].x, ev[r].y, ev[r].z, ev[r].w};
-            float en[FU_VEC];
-            acc[r] = 0;
-            qpack[r] = 0;
-            nb[r] = 0;
-#pragma unroll
-            for (int k = 0; k < FU_VEC; ++k) {
-                const bool valid = whole || i + k < n;
-                const int A = s_lo == s_hi ? A_unit : anchor_u[co3_find_seg(seg_off, nseg, valid ? i + k : n - 1)];
-                const float x = ga[k] + gamma * ea[k];   // no contraction (build flag): one rounding per operation
-                uint32_t q;
-                float v;
-                co3_quantize(x, A - F + 1, A, E, M, codemax, q, v);
-                en[k] = x - v;
-                const uint64_t e = valid ? enc_s[q] : 0ull;
-                const uint32_t l = (uint32_t)(e & 63u);
-                nocode |= valid && l == 0u;
-                acc[r] = (acc[r] << l) | (e >> 6);
-                qpack[r] |= q << (8 * k);
-                nb[r] += l;
-            }
-            if (whole) {
-                st_stream_f4(eu + i, make_float4(en[0], en[1], en[2], en[3]));
-            } else {
-#pragma unroll
-                for (int k = 0; k < FU_VEC; ++k)
-                    if (i + k < n) eu[i + k] = en[k];
-            }
-        }
+        const Fu_unit_args ua = {gu, eu, n, u0, lane, seg_off, nseg, anchor_u, anchor_u[s_lo], gamma, E, M, F, codemax, enc_s};
+        if (whole && s_lo == s_hi) nocode |= fused_convert_unit<true>(ua, acc, qpack, nb);
+        else nocode |= fused_convert_unit<false>(ua, acc, qpack, nb);
         // positions: one scan per pair of runs
         uint32_t pos[FU_SUB], total = 0;
 #pragma unroll
