@@ -119,8 +119,8 @@ def main():
                          "layer-model: one fixed code per tensor designed once from the GenNorm "
                          "law of the tensor (no histogram, no code build inside the step)")
     ap.add_argument("--single-pass", action="store_true",
-                    help="with --codes user-model: conversion and compression in one pass (co3_convert_encode), no "
-                         "symbol array")
+                    help="with --codes user-model or layer-model: conversion and compression in one pass "
+                         "(co3_convert_encode, co3_convert_encode_layers), no symbol array")
     ap.add_argument("--gamma", type=float, default=1.0, help="memory decay coefficient (1.0 in all five configurations)")
     ap.add_argument("--format", default=None, help="override the workload's format, e.g. E1M2")
     ap.add_argument("--pool", type=int, default=3, help="distinct gradient batches cycled through")
@@ -187,12 +187,14 @@ def main():
         code_seg_off = inp.seg_offsets(groups)
         desc += f", {len(groups)} code groups (tensors under 16,384 elements share the code of the large tensor before them)"
     fixed_user_tables = args.codes == "user-model"
-    if args.single_pass and not fixed_user_tables:
-        raise SystemExit("--single-pass needs --codes user-model (the codes must be known before the step)")
+    if args.single_pass and args.codes not in ("user-model", "layer-model"):
+        raise SystemExit("--single-pass needs --codes user-model or layer-model (the codes must be known before the step)")
+    if args.single_pass and fixed_user_tables and args.bias != "absmax":
+        raise SystemExit("--single-pass with --bias moments needs --codes layer-model")
     pipe = Co3Pipeline(w.U, w.n, fmt, chunk_syms=args.chunk, seg_off=w.seg_off if w.sizes is not None else None,
                        bias=args.bias, gamma=args.gamma, codes="user" if args.codes.startswith("user") else "layer",
                        code_seg_off=code_seg_off, statistics=not fixed_user_tables,
-                       single_pass=fixed_user_tables and args.single_pass,
+                       single_pass=args.single_pass,
                        cap_words=2 * B.cap_words_empirical(w.n, fmt) if fixed_user_tables else None)
     log(f"[bench] {desc}; generating {args.pool} device batches")
     batches = device_batches(w, betas, alpha, args.pool, pipe)
@@ -213,6 +215,11 @@ def main():
         # fixed tables: the GenNorm law of each tensor (workload parameters) on the grid of client 0's anchors
         # of the first batch; every emit-able symbol has a codeword, so the tables serve all clients and steps
         import numpy as np
+        if args.bias == "moments":       # the multiplier c of the first batch: c * x follows GenNorm(beta, c * alpha)
+            pipe.fit_bias(batches[0])
+            c0 = pipe.scale[0].cpu().numpy()
+        else:
+            c0 = np.ones(pipe.nseg, np.float32)
         pipe.convert(batches[0])
         A0 = pipe.anchor[0].cpu().numpy()
         pipe.err.zero_()
@@ -224,9 +231,10 @@ def main():
         first_tensor = [int(np.searchsorted(aso, cso[k], side="right") - 1) for k in range(pipe.ncodes)]
         wts = np.zeros((pipe.ncodes, fmt.K), np.uint32)
         for k in range(pipe.ncodes):
-            wts[k] = B.model_weights(int(A0[first_tensor[k]]), fmt, float(model_beta), float(model_alpha)).numpy().view(np.uint32)
+            wts[k] = B.model_weights(int(A0[first_tensor[k]]), fmt, float(model_beta),
+                                     float(model_alpha) * float(c0[first_tensor[k]])).numpy().view(np.uint32)
         pipe.build(torch.from_numpy(wts.view(np.int32)).cuda())
-        desc += ", fixed per-tensor model tables"
+        desc += ", fixed per-tensor model tables" + (", single pass" if args.single_pass else "")
     elif args.codes == "layer":
         desc += ", per-tensor codes shared by the clients"
     for i in range(args.warmup):

@@ -260,16 +260,30 @@ int32_t co3_ps_aggregate_layers(const uint64_t *words, int64_t cap_words, const 
  *              fmt) and co3_encode (codes [U], words, cap_words, chunk_syms, chunk_bitoff,
  *              total_bits, status)
  *   workspace  co3_convert_encode_workspace_bytes(n, U, chunk_syms) bytes, 16-byte aligned, contents
- *              unspecified: every 256 elements pack into a slot of 2 KiB of their own (room for 256
+ *              unspecified: every 1024 elements pack into a slot of 8 KiB of their own (room for 1024
  *              codewords of any length) before they are moved into the stream, 8 bytes per element
  *              of address space of which a codeword's worth is touched
- *   errors     as the two calls: CO3_EINVAL on the host; CO3_ENOCODE, CO3_ECAP through status
+ *   errors     as the two calls: CO3_EINVAL on the host; CO3_ENOCODE, CO3_ECAP through status (after
+ *              CO3_ENOCODE the stream is unspecified)
+ *
+ * co3_convert_encode_layers is the same pass for one code per layer shared by all users (codes
+ * [code_nseg], code_seg_off [code_nseg+1] device, as in co3_encode_layers; the boundaries of the codes
+ * need not be those of the anchors), with or without the multipliers of the bias rule: scale NULL gives
+ * co3_convert_ef followed by co3_encode_layers; scale [U][nseg] gives co3_convert_ef_scaled followed by
+ * co3_encode_layers, and then the anchors are inputs (anchor_mode must be CO3_ANCHOR_GIVEN).  Model
+ * codes per layer, the multiplier and one pass together are the scheme of Sec. III as the paper states it.
  */
 size_t co3_convert_encode_workspace_bytes(int64_t n, int32_t U, int32_t chunk_syms);
 int32_t co3_convert_encode(const float *g, float *err, int64_t n, int32_t U, int64_t stride, const int64_t *seg_off,
                            int32_t nseg, int32_t *anchor, int32_t anchor_mode, float gamma, co3_fmt fmt, const void *codes,
                            uint64_t *words, int64_t cap_words, int32_t chunk_syms, uint64_t *chunk_bitoff,
                            uint64_t *total_bits, void *workspace, size_t ws_bytes, int32_t *status, void *stream);
+int32_t co3_convert_encode_layers(const float *g, float *err, int64_t n, int32_t U, int64_t stride,
+                                  const int64_t *seg_off, int32_t nseg, int32_t *anchor, int32_t anchor_mode,
+                                  const float *scale, float gamma, co3_fmt fmt, const void *codes,
+                                  const int64_t *code_seg_off, int32_t code_nseg, uint64_t *words, int64_t cap_words,
+                                  int32_t chunk_syms, uint64_t *chunk_bitoff, uint64_t *total_bits, void *workspace,
+                                  size_t ws_bytes, int32_t *status, void *stream);
 
 /* ---- launch timing (diagnostic) ------------------------------------------ */
 

@@ -27,7 +27,7 @@ EXPORTS = (
     "co3_ps_aggregate", "co3_model_weights", "co3_timing_enable", "co3_timing_read", "co3_timing_reset",
     "co3_kernel_name", "co3_moments", "co3_bias_scale", "co3_convert_ef_scaled", "co3_ps_aggregate_scaled",
     "co3_histogram_layers", "co3_encode_layers", "co3_decode_layers", "co3_ps_aggregate_layers",
-    "co3_convert_encode_workspace_bytes", "co3_convert_encode",
+    "co3_convert_encode_workspace_bytes", "co3_convert_encode", "co3_convert_encode_layers",
 )
 KERNEL_COUNT = 12
 
@@ -107,6 +107,9 @@ def _load():
     L.co3_convert_encode_workspace_bytes.argtypes = [i64, i32, i32]
     L.co3_convert_encode.restype = i32
     L.co3_convert_encode.argtypes = [p, p, i64, i32, i64, p, i32, p, i32, C.c_float, _Fmt, p, p, i64, i32, p, p, p, sz, p, p]
+    L.co3_convert_encode_layers.restype = i32
+    L.co3_convert_encode_layers.argtypes = [p, p, i64, i32, i64, p, i32, p, i32, p, C.c_float, _Fmt, p, p, i32, p, i64, i32, p,
+                                            p, p, sz, p, p]
     L.co3_model_weights.restype = i32
     L.co3_model_weights.argtypes = [i32, _Fmt, C.c_double, C.c_double, p]
     L.co3_timing_enable.restype = i32
@@ -197,6 +200,22 @@ def convert_encode(g, err, n, anchor, anchor_mode, gamma, fmt: Fmt, codes, words
                                  _dp(workspace), workspace.numel() * workspace.element_size(), _dp(status, torch.int32),
                                  _stream(stream))
     _chk(rc, "co3_convert_encode")
+
+
+def convert_encode_layers(g, err, n, anchor, anchor_mode, gamma, fmt: Fmt, codes, code_seg_off, words, chunk_syms,
+                          chunk_bitoff, total_bits, workspace, status, seg_off=None, scale=None, stream=None):
+    """code_seg_off: boundaries of the codes; seg_off: boundaries of the anchors; scale: None or [U][nseg]."""
+    U, stride = _batch(g)
+    nseg = 1 if seg_off is None else seg_off.numel() - 1
+    rc = _lib.co3_convert_encode_layers(_dp(g, torch.float32), _dp(err, torch.float32), n, U, stride,
+                                        _dp(seg_off, torch.int64), nseg, _dp(anchor, torch.int32), anchor_mode,
+                                        _dp(scale, torch.float32), C.c_float(gamma), fmt.c(), _dp(codes, torch.uint8),
+                                        _dp(code_seg_off, torch.int64), code_seg_off.numel() - 1,
+                                        _dp(words, torch.int64), words.shape[-1], chunk_syms,
+                                        _dp(chunk_bitoff, torch.int64), _dp(total_bits, torch.int64), _dp(workspace),
+                                        workspace.numel() * workspace.element_size(), _dp(status, torch.int32),
+                                        _stream(stream))
+    _chk(rc, "co3_convert_encode_layers")
 
 
 def convert_ef_scaled(g, err, sym, n, anchor, scale, gamma, fmt: Fmt, seg_off=None, counts=None, stream=None):

@@ -37,9 +37,13 @@ __device__ __forceinline__ void fused_stage(unsigned long long *stage, uint64_t 
 }
 
 // One unit's elements: error correction, conversion, new memory, codeword lookup.  PLAIN: all 1024
-// elements exist and lie in one tensor (vector loads and stores, one anchor, no branches between the
-// elements, so that the table reads of a lane overlap); otherwise every access is guarded and the
-// anchor is looked up per element.  Returns whether a symbol without a codeword was met.
+// elements exist and lie in one tensor and under one code (vector loads and stores, one anchor, one
+// multiplier, the table in LDS, no branches between the elements, so that the table reads of a lane
+// overlap); otherwise every access is guarded and anchor, multiplier and code are looked up per element.
+// SCALED: the bias in its multiplier form (Sec. III (i), Sec. IV-B), as in the two-pass conversion: the
+// corrected gradient times c is rounded onto the grid, the level divided by c.  LAYERS: one code per
+// group of tensors (Sec. III (ii)), codes[group], the wavefront's LDS table holding the code of the
+// unit's first element.  Returns whether a symbol without a codeword was met.
 struct Fu_unit_args {
     const float *gu;
     float *eu;
@@ -48,13 +52,26 @@ struct Fu_unit_args {
     const int64_t *seg_off;
     int nseg;
     const int32_t *anchor_u;
+    const float *scale_u;
     int A_unit;
+    float c_unit;
     float gamma;
-    int E, M, F, codemax;
+    int E, M, F, K, codemax;
     const uint64_t *enc_s;
+    const void *codes;
+    const int64_t *code_seg_off;
+    int ncodes;
+    bool one_code;
 };
 
-template <bool PLAIN>
+template <bool LAYERS>
+__device__ __forceinline__ uint64_t fused_entry(const Fu_unit_args &a, uint32_t q, int64_t idx)
+{
+    if (!LAYERS || a.one_code) return a.enc_s[q];
+    return (int)q < a.K ? fcode_of(a.codes, co3_find_seg(a.code_seg_off, a.ncodes, idx))->enc[q] : 0ull;
+}
+
+template <bool PLAIN, bool LAYERS, bool SCALED>
 __device__ __forceinline__ bool fused_convert_unit(const Fu_unit_args &a, uint64_t (&acc)[FU_SUB], uint32_t (&qpack)[FU_SUB],
                                                    uint32_t (&nb)[FU_SUB])
 {
@@ -85,13 +102,17 @@ __device__ __forceinline__ bool fused_convert_unit(const Fu_unit_args &a, uint64
 #pragma unroll
         for (int k = 0; k < FU_VEC; ++k) {
             const bool valid = PLAIN || i + k < a.n;
-            const int A = PLAIN ? a.A_unit : a.anchor_u[co3_find_seg(a.seg_off, a.nseg, valid ? i + k : a.n - 1)];
+            const int64_t idx = valid ? i + k : a.n - 1;
+            const int sg = PLAIN ? 0 : co3_find_seg(a.seg_off, a.nseg, idx);
+            const int A = PLAIN ? a.A_unit : a.anchor_u[sg];
+            const float c = !SCALED ? 1.0f : PLAIN ? a.c_unit : a.scale_u[sg];
             const float x = ga[k] + a.gamma * ea[k];     // no contraction (build flag): one rounding per operation
             uint32_t q;
             float v;
-            co3_quantize(x, A - a.F + 1, A, a.E, a.M, a.codemax, q, v);
+            co3_quantize(SCALED ? c * x : x, A - a.F + 1, A, a.E, a.M, a.codemax, q, v);
+            if (SCALED) v = v / c;
             en[k] = x - v;
-            const uint64_t e = valid ? a.enc_s[q] : 0ull;
+            const uint64_t e = !valid ? 0ull : PLAIN ? a.enc_s[q] : fused_entry<LAYERS>(a, q, idx);
             const uint32_t l = (uint32_t)(e & 63u);
             nocode |= valid && l == 0u;
             acc[r] = (acc[r] << l) | (e >> 6);
@@ -114,11 +135,14 @@ __device__ __forceinline__ bool fused_convert_unit(const Fu_unit_args &a, uint64
 // one contiguous KiB per wavefront.  The bit position of a lane's codewords inside the unit comes from
 // one scan over the lanes for all runs at once: the lane totals of two runs share a 32-bit word (a run
 // has at most 256 * 57 < 2^16 bits).
+template <bool LAYERS, bool SCALED>
 __global__ __launch_bounds__(FU_BLOCK) void k_convert_stage(const float *__restrict__ g, float *__restrict__ err,
                                                              int64_t n, int64_t stride,
                                                              const int64_t *__restrict__ seg_off_g, int nseg,
-                                                             const int32_t *__restrict__ anchor, float gamma, co3_fmt fmt,
+                                                             const int32_t *__restrict__ anchor,
+                                                             const float *__restrict__ scale, float gamma, co3_fmt fmt,
                                                              const void *__restrict__ codes,
+                                                             const int64_t *__restrict__ code_seg_off_g, int ncodes,
                                                              uint64_t *__restrict__ slots, uint32_t *__restrict__ unit_bits,
                                                              uint32_t *__restrict__ chunk_local, int chunk_syms,
                                                              int64_t nchunks, int64_t nunits, int64_t per_block,
@@ -127,20 +151,24 @@ __global__ __launch_bounds__(FU_BLOCK) void k_convert_stage(const float *__restr
     const FmtC fc(fmt);
     const int E = fc.E, M = fc.M, F = fc.F, K = fc.K, codemax = fc.codemax;
     __shared__ int64_t seg_cache[CO3_SEG_CACHE];
-    __shared__ uint64_t enc_s[256];
+    __shared__ int64_t code_seg_cache[LAYERS ? CO3_SEG_CACHE : 1];
+    __shared__ uint64_t enc_all[LAYERS ? FU_WAVES * 256 : 256];
     __shared__ unsigned long long stage_all[FU_WAVES][CO3_FUSED_SLOT_WORDS + 1];
     const int64_t *seg_off = co3_cache_segs(seg_off_g, nseg, seg_cache);
+    const int64_t *code_seg_off = LAYERS ? co3_cache_segs(code_seg_off_g, ncodes, code_seg_cache) : nullptr;
     // users and ranges in the reverse of the anchor pass's order: what that pass left in the last-level
     // cache is read first
     const int u = gridDim.y - 1 - blockIdx.y;
     const int64_t range = gridDim.x - 1 - blockIdx.x;
-    const Co3Code *cd = fcode_of(codes, u);
-    enc_s[threadIdx.x] = (int)threadIdx.x < K ? cd->enc[threadIdx.x] : 0ull;
+    if (!LAYERS) enc_all[threadIdx.x] = (int)threadIdx.x < K ? fcode_of(codes, u)->enc[threadIdx.x] : 0ull;
     __syncthreads();
+    uint64_t *enc_s = LAYERS ? enc_all + (threadIdx.x / CO3_WAVE) * 256 : enc_all;
+    int cur_code = -1;                   // LAYERS: the code whose table the wavefront holds
 
     const float *gu = g + (int64_t)u * stride;
     float *eu = err + (int64_t)u * stride;
     const int32_t *anchor_u = anchor + (int64_t)u * nseg;
+    const float *scale_u = SCALED ? scale + (int64_t)u * nseg : nullptr;
     const int lane = threadIdx.x & (CO3_WAVE - 1);
     const int wave = threadIdx.x / CO3_WAVE;
     unsigned long long *stage = stage_all[wave];
@@ -162,9 +190,27 @@ __global__ __launch_bounds__(FU_BLOCK) void k_convert_stage(const float *__restr
         uint64_t acc[FU_SUB];            // the lane's four codewords of a run, joined (whole if they fit 64 bits)
         uint32_t qpack[FU_SUB];          // the four symbols of a run (looked up again if they do not)
         uint32_t nb[FU_SUB];             // bits of the lane's four codewords of a run
-        const Fu_unit_args ua = {gu, eu, n, u0, lane, seg_off, nseg, anchor_u, anchor_u[s_lo], gamma, E, M, F, codemax, enc_s};
-        if (whole && s_lo == s_hi) nocode |= fused_convert_unit<true>(ua, acc, qpack, nb);
-        else nocode |= fused_convert_unit<false>(ua, acc, qpack, nb);
+        bool one_code = true;
+        if (LAYERS) {                    // the table of the unit's first element, reloaded when it changes
+            const int c_lo = co3_find_seg(code_seg_off, ncodes, u0), c_hi = co3_find_seg(code_seg_off, ncodes, u_last);
+            one_code = c_lo == c_hi;
+            if (c_lo != cur_code) {      // uniform
+                co3_wave_lds_sync();
+                const Co3Code *cd = fcode_of(codes, c_lo);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int q = lane + k * CO3_WAVE;
+                    enc_s[q] = q < K ? cd->enc[q] : 0ull;
+                }
+                co3_wave_lds_sync();
+                cur_code = c_lo;
+            }
+        }
+        const Fu_unit_args ua = {gu, eu, n, u0, lane, seg_off, nseg, anchor_u, scale_u, anchor_u[s_lo],
+                                 SCALED ? scale_u[s_lo] : 1.0f, gamma, E, M, F, K, codemax, enc_s, codes, code_seg_off,
+                                 ncodes, one_code};
+        if (whole && s_lo == s_hi && one_code) nocode |= fused_convert_unit<true, LAYERS, SCALED>(ua, acc, qpack, nb);
+        else nocode |= fused_convert_unit<false, LAYERS, SCALED>(ua, acc, qpack, nb);
         // positions: one scan per pair of runs
         uint32_t pos[FU_SUB], total = 0;
 #pragma unroll
@@ -196,8 +242,9 @@ __global__ __launch_bounds__(FU_BLOCK) void k_convert_stage(const float *__restr
                 uint32_t p = pos[r];
 #pragma unroll
                 for (int k = 0; k < FU_VEC; ++k) {
-                    const bool valid = whole || u0 + r * FU_RUN + lane * FU_VEC + k < n;
-                    const uint64_t e = enc_s[(qpack[r] >> (8 * k)) & 0xffu];
+                    const int64_t idx = u0 + r * FU_RUN + lane * FU_VEC + k;
+                    const bool valid = whole || idx < n;
+                    const uint64_t e = fused_entry<LAYERS>(ua, (qpack[r] >> (8 * k)) & 0xffu, valid ? idx : n - 1);
                     const uint32_t l = valid ? (uint32_t)(e & 63u) : 0u;
                     if (l) fused_stage(stage, e >> 6, l, p);
                     p += l;
@@ -343,9 +390,10 @@ static FusedWs fused_layout(int64_t n, int U, int chunk_syms)
 size_t co3_fused_workspace_bytes_impl(int64_t n, int U, int chunk_syms) { return fused_layout(n, U, chunk_syms).total; }
 
 hipError_t co3_launch_convert_encode(const float *g, float *err, int64_t n, int U, int64_t stride, const int64_t *seg_off,
-                                     int nseg, const int32_t *anchor, float gamma, co3_fmt fmt, const void *codes,
-                                     uint64_t *words, int64_t cap_words, int chunk_syms, uint64_t *chunk_bitoff,
-                                     uint64_t *total_bits, void *workspace, int32_t *status, hipStream_t st)
+                                     int nseg, const int32_t *anchor, const float *scale, float gamma, co3_fmt fmt,
+                                     const void *codes, const int64_t *code_seg_off, int ncodes, uint64_t *words,
+                                     int64_t cap_words, int chunk_syms, uint64_t *chunk_bitoff, uint64_t *total_bits,
+                                     void *workspace, int32_t *status, hipStream_t st)
 {
     const int64_t nunits = (n + CO3_FUSED_UNIT - 1) / CO3_FUSED_UNIT;
     const int64_t ngrp = (nunits + CO3_FUSED_GROUP - 1) / CO3_FUSED_GROUP;
@@ -361,12 +409,18 @@ hipError_t co3_launch_convert_encode(const float *g, float *err, int64_t n, int 
         // about 2048 workgroups in all, each a whole number of block steps
         int64_t per_user = 2048 / U > 0 ? 2048 / U : 1;
         int64_t per_block = ((n + per_user - 1) / per_user + FU_TILE - 1) / FU_TILE * FU_TILE;
-        const unsigned gx = (unsigned)((n + per_block - 1) / per_block);
+        const dim3 grid((unsigned)((n + per_block - 1) / per_block), U), block(FU_BLOCK);
         {
             Co3LaunchTimer tm(CO3_K_CONVERT, st);
-            hipLaunchKernelGGL(k_convert_stage, dim3(gx, U), dim3(FU_BLOCK), 0, st, g, err, n, stride, seg_off, nseg, anchor,
-                               gamma, fmt, codes, slots, unit_bits, chunk_local, chunk_syms, nchunks, nunits, per_block,
-                               status);
+#define CO3_STAGE_LAUNCH(L_, S_)                                                                                        \
+    hipLaunchKernelGGL((k_convert_stage<L_, S_>), grid, block, 0, st, g, err, n, stride, seg_off, nseg, anchor, scale,   \
+                       gamma, fmt, codes, code_seg_off, ncodes, slots, unit_bits, chunk_local, chunk_syms, nchunks,     \
+                       nunits, per_block, status)
+            if (code_seg_off && scale) CO3_STAGE_LAUNCH(true, true);
+            else if (code_seg_off) CO3_STAGE_LAUNCH(true, false);
+            else if (scale) CO3_STAGE_LAUNCH(false, true);
+            else CO3_STAGE_LAUNCH(false, false);
+#undef CO3_STAGE_LAUNCH
         }
         {
             Co3LaunchTimer tm(CO3_K_ENC_SIZES, st);

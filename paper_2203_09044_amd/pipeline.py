@@ -35,10 +35,10 @@ class Co3Pipeline:
         self.U, self.n, self.fmt, self.chunk_syms, self.gamma = U, n, fmt, chunk_syms, gamma
         self.fused_histogram = fused_histogram
         self.statistics = statistics      # False: fixed tables (designed from a model), no symbol counts are gathered
-        # fixed per-user tables only: conversion and compression in one pass, no symbol array (co3_convert_encode)
+        # fixed tables only: conversion and compression in one pass, no symbol array (co3_convert_encode[_layers])
         self.single_pass = single_pass
-        if single_pass and (codes != "user" or bias != "absmax"):
-            raise ValueError("single_pass needs per-user codes and the integer anchor")
+        if single_pass and codes == "user" and bias != "absmax":
+            raise ValueError("single_pass with the bias rule needs codes='layer'")
         self.bias = bias
         dev = torch.device(device)
         self.device = dev
@@ -100,9 +100,16 @@ class Co3Pipeline:
 
     def convert_encode(self, g: torch.Tensor, anchor_mode=B.ANCHOR_FROM_ABSMAX_G):
         """Conversion and compression in one pass with the codes already in ``self.codes`` (single_pass)."""
-        B.convert_encode(g, self.err, self.n, self.anchor, anchor_mode, self.gamma, self.fmt, self.codes, self.words,
-                         self.chunk_syms, self.chunk_bitoff, self.total_bits, self.fused_ws, self.status,
-                         seg_off=self.seg_off)
+        if self.code_mode == "layer":
+            scaled = self.bias == "moments"
+            B.convert_encode_layers(g, self.err, self.n, self.anchor, B.ANCHOR_GIVEN if scaled else anchor_mode, self.gamma,
+                                    self.fmt, self.codes, self.code_seg_off, self.words, self.chunk_syms,
+                                    self.chunk_bitoff, self.total_bits, self.fused_ws, self.status, seg_off=self.seg_off,
+                                    scale=self.scale if scaled else None)
+        else:
+            B.convert_encode(g, self.err, self.n, self.anchor, anchor_mode, self.gamma, self.fmt, self.codes, self.words,
+                             self.chunk_syms, self.chunk_bitoff, self.total_bits, self.fused_ws, self.status,
+                             seg_off=self.seg_off)
 
     def build(self, weights: Optional[torch.Tensor] = None):
         """Per-user codes from the users' counts (or given weights [U][K]); per-tensor codes from the pooled
@@ -149,6 +156,8 @@ class Co3Pipeline:
         """One whole iteration: users encode, the server decodes and averages.  ``rebuild=False`` keeps the
         codes of the previous call (fixed tables designed from a model)."""
         if self.single_pass and not rebuild:
+            if self.bias == "moments":
+                self.fit_bias(g)
             self.convert_encode(g)
             self.aggregate()
             return

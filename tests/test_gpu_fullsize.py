@@ -235,6 +235,52 @@ def test_c3_bias_rule_full(co3):
     properties_all_clients(pipe, w.n)
 
 
+def test_c3_paper_scheme_single_pass_full(co3):
+    """The scheme as Sec. III states it, at the C3 shape: the 4-bit format E1M2, the bias rule's multiplier
+    on a fixed grid, one code designed from the GenNorm model and shared by all users, and the user side in
+    one pass (co3_convert_encode_layers).  One iteration from a non-zero memory, the oracle's multipliers
+    on both sides; memory, stream words, chunk offsets of every user and the average, bit for bit."""
+    w = inp.c3()
+    fmt = co3.Fmt(1, 2)
+    f = oracle.Fmt(1, 2)
+    betas = inp.c3_client_betas(w.U)
+    pipe = co3.Co3Pipeline(w.U, w.n, fmt, chunk_syms=256, bias="moments", codes="layer", statistics=False,
+                           single_pass=True, cap_words=w.n // 4)
+    g = pipe.new_gradient_buffer()
+    host = fill_from_device(pipe, g, lambda u: inp.device_gennorm(w.n, float(betas[u]), 1e-3, 3900 + u))
+    errs = [inp.gennorm(inp.rng_for(39, u), w.n, 1.0, 1e-4) for u in range(w.U)]
+    for u in range(w.U):
+        pipe.err[u, :w.n] = torch.from_numpy(errs[u]).cuda()
+    A = np.array([1], np.int32)
+    assert np.all(pipe.anchor.cpu().numpy() == 1)
+    with ThreadPoolExecutor(max_workers=10) as pool:
+        scale_o = np.stack(list(pool.map(lambda u: oracle.bias_scales(host[u], errs[u], 1.0), range(w.U))))
+        pipe.scale.copy_(torch.from_numpy(scale_o).cuda())
+        weights = oracle.model_weights(1, f, 1.0, 1e-3 * float(scale_o.mean()))[None, :]
+        pipe.build(torch.from_numpy(weights.view(np.int32)).cuda())
+        lens = oracle.huffman_lengths(weights[0])[None, :]
+        cods = oracle.canonical_codes(lens[0])[None, :]
+        assert np.array_equal(pipe.codes[:, :fmt.K].cpu().numpy(), lens)
+        pipe.convert_encode(g)
+        pipe.aggregate()
+        assert pipe.poll() == 0
+
+        def client(u):
+            sym, e_new = oracle.convert_ef(host[u], errs[u], A, 1.0, f, scale=scale_o[u])
+            words, off, total = oracle.encode_layers(sym, lens, cods, [0, w.n], 256)
+            return sym, e_new, words, off, total
+
+        refs = list(pool.map(client, range(w.U)))
+    for u, (sym, e_new, words, off, total) in enumerate(refs):
+        assert np.array_equal(u32(pipe.err[u, :w.n]), e_new.view(np.uint32)), "error vector"
+        assert int(pipe.total_bits[u].item()) == total, "total bits"
+        assert np.array_equal(u64(pipe.chunk_bitoff[u]), off), "chunk offsets"
+        nw = (total + 63) // 64
+        assert np.array_equal(u64(pipe.words[u, :nw]), words[:nw]), "stream words"
+    want = oracle.aggregate(np.stack([r[0] for r in refs]), np.tile(A, (w.U, 1)), f, scale=scale_o)
+    assert np.array_equal(u32(pipe.avg[:w.n]), want.view(np.uint32)), "average"
+
+
 def test_c4_full(co3):
     """C4: 100M elements, E5M2, with outliers; empirical table and the fixed GenNorm-model table, one
     iteration each on every element."""

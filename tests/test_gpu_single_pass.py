@@ -117,3 +117,99 @@ def test_capacity_is_respected(co3):
     pipe.convert_encode(g)
     assert pipe.poll() == co3.binding.ECAP
     assert int(pipe.total_bits[0].item()) == 4 * n          # the needed length is still reported
+
+
+# ---- one code per layer shared by the users, with and without the multiplier of the bias rule ----
+
+LAYER_SHAPES = {
+    "odd": [10, 0, 4086, 1, 33000, 12903],
+    "resnet_head": [1728, 64, 64, 36864, 64, 64, 73728, 128, 128, 5120, 10],
+    "single": [70001],
+    "tiny_many": [5] * 300 + [2000] + [1] * 70 + [9000],
+    "two_big": [300000, 300001],
+    "aligned": [4096, 8192, 1024, 1024],
+}
+
+
+def run_layers(co3, U, sizes, E, M, C, scaled=False, grouped=False, T=2, gamma=1.0, seed=0):
+    fmt, f = co3.Fmt(E, M), oracle.Fmt(E, M)
+    seg = inp.seg_offsets(sizes)
+    nseg = len(sizes)
+    n = int(seg[-1])
+    code_seg = inp.seg_offsets(inp.group_small_tensors(sizes, 3000)) if grouped else seg
+    ncodes = len(code_seg) - 1
+    pipe = co3.Co3Pipeline(U, n, fmt, chunk_syms=C, seg_off=seg, gamma=gamma, codes="layer", code_seg_off=code_seg,
+                           statistics=False, single_pass=True, bias="moments" if scaled else "absmax",
+                           cap_words=2 * ((n * 57 + 127) // 128 + 1))
+    rng = np.random.default_rng(seed + 11)
+    weights = rng.integers(1, 1000, (ncodes, fmt.K)).astype(np.uint32) ** 2
+    weights[:, 1 << (E + M)] = 0                                   # the negative zero is never emitted
+    pipe.build(torch.from_numpy(weights.view(np.int32)).cuda())
+    lens = np.stack([oracle.huffman_lengths(weights[k]) for k in range(ncodes)])
+    cods = np.stack([oracle.canonical_codes(lens[k]) for k in range(ncodes)])
+    alphas = 10.0 ** inp.rng_for(97 + seed).uniform(-4, -2, nseg)
+    errs = [np.zeros(n, np.float32) for _ in range(U)]
+    g = pipe.new_gradient_buffer()
+    for t in range(1, T + 1):
+        gh = [np.concatenate([inp.gennorm(inp.rng_for(97 + seed, u, t, k), m, 0.9, a)
+                              for k, (m, a) in enumerate(zip(sizes, alphas))]).astype(np.float32) for u in range(U)]
+        g[:, :n] = torch.from_numpy(np.stack(gh)).cuda()
+        scale = None
+        if scaled:
+            # the oracle's multipliers on both sides (the device's own fit is compared elsewhere, to 2 ulp)
+            scale = np.stack([oracle.bias_scales(gh[u], errs[u], gamma, seg) for u in range(U)])
+            pipe.scale.copy_(torch.from_numpy(scale).cuda())
+        pipe.convert_encode(g)
+        pipe.aggregate()
+        assert pipe.poll() == 0
+        syms, anchors = [], []
+        for u in range(U):
+            A = pipe.anchor[u].cpu().numpy() if scaled else oracle.anchor(gh[u], f, seg)
+            if scaled:
+                assert np.all(A == 1 << (E - 1))                   # the fixed grid of the bias rule
+            s, errs[u] = oracle.convert_ef(gh[u], errs[u], A, gamma, f, seg, scale=None if scale is None else scale[u])
+            words, off, total = oracle.encode_layers(s, lens, cods, code_seg, C)
+            assert np.array_equal(pipe.anchor[u].cpu().numpy(), A), "anchor"
+            assert np.array_equal(pipe.err[u, :n].cpu().numpy().view(np.uint32), errs[u].view(np.uint32)), "memory"
+            assert int(pipe.total_bits[u].item()) == total, "total bits"
+            assert np.array_equal(u64(pipe.chunk_bitoff[u]), off), "chunk offsets"
+            nw = (total + 63) // 64
+            assert np.array_equal(u64(pipe.words[u, :nw]), words[:nw]), "stream words"
+            syms.append(s)
+            anchors.append(A)
+        want = oracle.aggregate(np.stack(syms), np.stack(anchors), f, seg, scale=scale)
+        assert np.array_equal(pipe.avg[:n].cpu().numpy().view(np.uint32), want.view(np.uint32)), "average"
+
+
+@pytest.mark.parametrize("shape", sorted(LAYER_SHAPES))
+@pytest.mark.parametrize("scaled", [False, True])
+def test_layer_codes_shapes(co3, shape, scaled):
+    run_layers(co3, 2, LAYER_SHAPES[shape], 4, 3, 256, scaled=scaled)
+
+
+@pytest.mark.parametrize("E,M", [(3, 0), (3, 1), (5, 2), (1, 2)])
+def test_layer_codes_formats(co3, E, M):
+    run_layers(co3, 2, LAYER_SHAPES["odd"], E, M, 64, scaled=(E, M) == (1, 2), T=3, gamma=0.9)
+
+
+@pytest.mark.parametrize("C", [64, 1024, 4096])
+def test_layer_codes_grouped_boundaries(co3, C):
+    """Code groups that differ from the anchors' tensors (small tensors share the code of a neighbour)."""
+    run_layers(co3, 3, LAYER_SHAPES["resnet_head"], 4, 3, C, grouped=True)
+    run_layers(co3, 2, LAYER_SHAPES["tiny_many"], 3, 1, C, grouped=True, scaled=True)
+
+
+def test_layer_entry_rejects_bad_arguments(co3):
+    B = co3.binding
+    fmt = co3.Fmt(3, 0)
+    pipe = co3.Co3Pipeline(1, 1000, fmt, codes="layer", statistics=False, single_pass=True)
+    g = pipe.new_gradient_buffer()
+    scale = torch.ones((1, 1), dtype=torch.float32, device="cuda")
+    with pytest.raises(B.Co3Error):          # a multiplier with anchors taken from max|g|
+        B.convert_encode_layers(g, pipe.err, pipe.n, pipe.anchor, B.ANCHOR_FROM_ABSMAX_G, 1.0, fmt, pipe.codes,
+                                pipe.code_seg_off, pipe.words, 256, pipe.chunk_bitoff, pipe.total_bits, pipe.fused_ws,
+                                pipe.status, scale=scale)
+    small = torch.empty((16,), dtype=torch.uint8, device="cuda")
+    with pytest.raises(B.Co3Error):          # workspace too small
+        B.convert_encode_layers(g, pipe.err, pipe.n, pipe.anchor, B.ANCHOR_FROM_ABSMAX_G, 1.0, fmt, pipe.codes,
+                                pipe.code_seg_off, pipe.words, 256, pipe.chunk_bitoff, pipe.total_bits, small, pipe.status)
