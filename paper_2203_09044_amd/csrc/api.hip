@@ -391,7 +391,7 @@ static int32_t aggregate_common(const uint64_t *words, int64_t cap_words, const 
     hipError_t e = co3_launch_decode(words, cap_words, chunk_bitoff, chunk_syms, codes, code_seg_off, code_nseg,
                                      FmtC(fmt).K, n, U, symws, ws_stride, 1, status, st);
     if (e != hipSuccess) return CO3_EHIP;
-    const int packed = co3_ws_packed(FmtC(fmt).K, chunk_syms, code_seg_off != nullptr) ? 1 : 0;
+    const int packed = co3_ws_packed(FmtC(fmt).K, chunk_syms, code_seg_off ? code_nseg : 0) ? 1 : 0;
     return hip_rc(co3_launch_ps_sum_tiled(symws, n, U, ws_stride, chunk_syms, anchor, scale, seg_off, nseg, fmt, packed,
                                           avg_out, st));
 }

@@ -485,8 +485,9 @@ __device__ __forceinline__ void decode_chunk_packed(const DecTables &t, LaneStre
 template <bool TILED, bool PAIRS>
 __global__ __launch_bounds__(DE_BLOCK) void k_decode(const uint64_t *__restrict__ words, int64_t cap_words,
                                                       const uint64_t *__restrict__ chunk_bitoff, int chunk_syms,
-                                                      int64_t nchunks, const void *__restrict__ codes, int64_t n,
-                                                      uint8_t *__restrict__ sym_out, int64_t stride, int32_t *status)
+                                                      int64_t nchunks, const void *__restrict__ codes,
+                                                      int code_per_user, int64_t n, uint8_t *__restrict__ sym_out,
+                                                      int64_t stride, int32_t *status)
 {
     const int u = blockIdx.y;
     // tables first: their LDS offsets then fit the immediate field of the read instructions
@@ -510,7 +511,7 @@ __global__ __launch_bounds__(DE_BLOCK) void k_decode(const uint64_t *__restrict_
     ls.nblocks = cap_words / 2;
     ls.slot = ring + (threadIdx.x / CO3_WAVE) * (RING_ROWS * RING_ROW_DW) + (threadIdx.x & (CO3_WAVE - 1));
     if (active) ls.open(p0);
-    load_tables(t, dcode_of(codes, u));
+    load_tables(t, dcode_of(codes, code_per_user ? u : 0));        // else one code shared by all users
     __syncthreads();
     if constexpr (PAIRS) {
         build_pairs<TILED>(t, pairs);
@@ -757,15 +758,18 @@ hipError_t co3_launch_decode(const uint64_t *words, int64_t cap_words, const uin
     const unsigned lblocks = (unsigned)((nchunks + DL_BLOCK - 1) / DL_BLOCK);
 #define CO3_DECODE_LAUNCH(T, P)                                                                                    \
     hipLaunchKernelGGL((k_decode<T, P>), dim3(blocks, U), dim3(DE_BLOCK), 0, st, words, cap_words, chunk_bitoff,   \
-                       chunk_syms, nchunks, codes, n, sym_out, stride, status)
+                       chunk_syms, nchunks, codes, code_per_user, n, sym_out, stride, status)
     Co3LaunchTimer tm(CO3_K_DECODE, st);
+    // one code for everything, shared by the users: the per-user kernels with every user reading codes[0]
+    const int code_per_user = seg_off == nullptr;
+    if (seg_off && nseg == 1) seg_off = nullptr;
     if (seg_off && tiled)
         hipLaunchKernelGGL(k_decode_layers<true>, dim3(lblocks, U), dim3(DL_BLOCK), 0, st, words, cap_words,
                            chunk_bitoff, chunk_syms, nchunks, codes, seg_off, nseg, n, sym_out, stride, status);
     else if (seg_off)
         hipLaunchKernelGGL(k_decode_layers<false>, dim3(lblocks, U), dim3(DL_BLOCK), 0, st, words, cap_words,
                            chunk_bitoff, chunk_syms, nchunks, codes, seg_off, nseg, n, sym_out, stride, status);
-    else if (co3_ws_packed(K, chunk_syms, false)) {
+    else if (co3_ws_packed(K, chunk_syms, 0)) {
         if (tiled) CO3_DECODE_LAUNCH(true, true);
         else CO3_DECODE_LAUNCH(false, true);
     } else {

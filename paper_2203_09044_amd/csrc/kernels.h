@@ -45,11 +45,13 @@ hipError_t co3_launch_convert_encode(const float *g, float *err, int64_t n, int 
 hipError_t co3_launch_decode(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff, int chunk_syms,
                              const void *codes, const int64_t *seg_off, int nseg, int K, int64_t n, int U,
                              uint8_t *sym_out, int64_t stride, int tiled, int32_t *status, hipStream_t st);
-// The averaging workspace holds two symbols per byte when this is true (user codes only): alphabets of at
-// most 16 symbols, chunks of at least two runs of 32.  The decoder then also reads two symbols per lookup.
-static inline bool co3_ws_packed(int K, int chunk_syms, bool layer_codes)
+// The averaging workspace holds two symbols per byte when this is true: alphabets of at most 16 symbols,
+// chunks of at least two runs of 32, and one code per user or one code shared by everything
+// (code_groups = 0 for per-user codes, else the number of shared per-layer codes).  The decoder then
+// also reads two symbols per lookup.
+static inline bool co3_ws_packed(int K, int chunk_syms, int code_groups)
 {
-    return !layer_codes && K <= 16 && chunk_syms >= 64;
+    return code_groups <= 1 && K <= 16 && chunk_syms >= 64;
 }
 hipError_t co3_launch_ps_sum_tiled(const uint8_t *symt, int64_t n, int U, int64_t ws_stride, int chunk_syms,
                                    const int32_t *anchor, const float *scale, const int64_t *seg_off, int nseg,

@@ -213,3 +213,11 @@ def test_layer_entry_rejects_bad_arguments(co3):
     with pytest.raises(B.Co3Error):          # workspace too small
         B.convert_encode_layers(g, pipe.err, pipe.n, pipe.anchor, B.ANCHOR_FROM_ABSMAX_G, 1.0, fmt, pipe.codes,
                                 pipe.code_seg_off, pipe.words, 256, pipe.chunk_bitoff, pipe.total_bits, small, pipe.status)
+
+
+@pytest.mark.parametrize("E,M,scaled", [(3, 0, False), (1, 2, True), (4, 3, False)])
+def test_one_code_shared_by_everything(co3, E, M, scaled):
+    """A single code group: the server side then runs the decoder of the per-user codes with every user
+    reading the one table (two symbols per lookup and per workspace byte for alphabets of 16)."""
+    run_layers(co3, 3, [70001], E, M, 256, scaled=scaled, T=2)
+    run_layers(co3, 2, [5000, 3, 60000], E, M, 64, scaled=scaled, grouped=False, T=1)
