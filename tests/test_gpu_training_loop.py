@@ -66,15 +66,17 @@ def test_average_is_the_oracles_over_chained_iterations(co3):
             assert torch.equal(p.detach(), torch.add(b, upd, alpha=-0.05))
 
 
-@pytest.mark.parametrize("E,M,bias,codes", [(3, 1, "absmax", "user"), (1, 2, "moments", "user"), (4, 3, "absmax", "layer")])
-def test_training_converges_like_plain_sgd(co3, E, M, bias, codes):
+@pytest.mark.parametrize("E,M,bias,codes,tables", [(3, 1, "absmax", "user", "empirical"), (1, 2, "moments", "user", "empirical"),
+                                                   (4, 3, "absmax", "layer", "empirical"),
+                                                   (1, 2, "moments", "layer", "model"), (3, 1, "moments", "layer", "model")])
+def test_training_converges_like_plain_sgd(co3, E, M, bias, codes, tables):
     from paper_2203_09044_amd.training import Co3SGD
     U, T, lr = 4, 80, 0.1
     sample, model = make_problem(11, U, 64)
     loss_fn = torch.nn.functional.cross_entropy
 
     net = model()
-    opt = Co3SGD(net, U, co3.Fmt(E, M), lr=lr, bias=bias, codes=codes, code_group_min=10000)
+    opt = Co3SGD(net, U, co3.Fmt(E, M), lr=lr, bias=bias, codes=codes, code_group_min=10000, tables=tables, refresh=10)
     losses = [opt.step([sample(t, u) for u in range(U)], loss_fn) for t in range(T)]
     assert opt.pipe.poll() == 0
 
@@ -96,8 +98,8 @@ def test_training_converges_like_plain_sgd(co3, E, M, bias, codes):
         ref_losses.append(tot / U)
 
     first, last, ref_last = np.mean(losses[:5]), np.mean(losses[-10:]), np.mean(ref_losses[-10:])
-    print(f"\n[training E{E}M{M} bias={bias} codes={codes}] loss {first:.3f} -> {last:.3f} (plain SGD {ref_last:.3f}), "
+    print(f"\n[training E{E}M{M} bias={bias} codes={codes} tables={tables}] loss {first:.3f} -> {last:.3f} (plain SGD {ref_last:.3f}), "
           f"{opt.bits_per_element():.2f} payload bits per gradient element")
     assert last < 0.5 * first
     assert last < 1.35 * ref_last + 0.05
-    assert opt.bits_per_element() < 1 + E + M
+    assert opt.bits_per_element() < 1 + E + M + (1 if tables == "model" else 0)     # a model table has no such bound
