@@ -44,7 +44,7 @@ __device__ __forceinline__ void fused_stage(unsigned long long *stage, uint64_t 
 // corrected gradient times c is rounded onto the grid, the level divided by c.  LAYERS: one code per
 // group of tensors (Sec. III (ii)), codes[group], the wavefront's LDS table holding the code of the
 // unit's first element.  Returns whether a symbol without a codeword was met.
-struct Fu_unit_args {
+struct FusedUnit {
     const float *gu;
     float *eu;
     int64_t n, u0;
@@ -65,14 +65,14 @@ struct Fu_unit_args {
 };
 
 template <bool LAYERS>
-__device__ __forceinline__ uint64_t fused_entry(const Fu_unit_args &a, uint32_t q, int64_t idx)
+__device__ __forceinline__ uint64_t fused_entry(const FusedUnit &a, uint32_t q, int64_t idx)
 {
     if (!LAYERS || a.one_code) return a.enc_s[q];
     return (int)q < a.K ? fcode_of(a.codes, co3_find_seg(a.code_seg_off, a.ncodes, idx))->enc[q] : 0ull;
 }
 
 template <bool PLAIN, bool LAYERS, bool SCALED>
-__device__ __forceinline__ bool fused_convert_unit(const Fu_unit_args &a, uint64_t (&acc)[FU_SUB], uint32_t (&qpack)[FU_SUB],
+__device__ __forceinline__ bool fused_convert_unit(const FusedUnit &a, uint64_t (&acc)[FU_SUB], uint32_t (&qpack)[FU_SUB],
                                                    uint32_t (&nb)[FU_SUB])
 {
     float4 gv[FU_SUB], ev[FU_SUB];
@@ -206,7 +206,7 @@ __global__ __launch_bounds__(FU_BLOCK) void k_convert_stage(const float *__restr
                 cur_code = c_lo;
             }
         }
-        const Fu_unit_args ua = {gu, eu, n, u0, lane, seg_off, nseg, anchor_u, scale_u, anchor_u[s_lo],
+        const FusedUnit ua = {gu, eu, n, u0, lane, seg_off, nseg, anchor_u, scale_u, anchor_u[s_lo],
                                  SCALED ? scale_u[s_lo] : 1.0f, gamma, E, M, F, K, codemax, enc_s, codes, code_seg_off,
                                  ncodes, one_code};
         if (whole && s_lo == s_hi && one_code) nocode |= fused_convert_unit<true, LAYERS, SCALED>(ua, acc, qpack, nb);
