@@ -393,3 +393,44 @@ def test_beyond_2_to_the_31_elements(co3):
     hist = torch.bincount(pipe.sym[0, :n].to(torch.int32), minlength=fmt.K).cpu().numpy()
     assert np.array_equal(hist, cnt.astype(np.int64))
     properties_all_clients(pipe, n)
+
+
+def test_single_pass_beyond_2_to_the_31_elements(co3):
+    """The one-pass user side at 2^31 + 2^20 + 13 elements (64-bit indices everywhere): with the code that
+    the two-pass path built from the same gradients, memory, stream words, chunk offsets and total must
+    equal the two-pass results over the whole length (those are checked against the oracle in the test
+    above); windows of the memory across element 2^31 and at the ragged end, and the stream of the first
+    65,536 symbols, go through the oracle directly."""
+    n = (1 << 31) + (1 << 20) + 13
+    fmt = co3.Fmt(3, 0)
+    f = oracle.Fmt(3, 0)
+    two = co3.Co3Pipeline(1, n, fmt, chunk_syms=256)
+    g = two.new_gradient_buffer()
+    piece = 1 << 28
+    for k, a in enumerate(range(0, n, piece)):
+        b = min(n, a + piece)
+        g[0, a:b] = inp.device_gennorm(b - a, 1.0, 1e-3, 8300 + k)
+    two.convert(g)
+    two.build()
+    two.encode()
+    assert two.poll() == 0
+    one = co3.Co3Pipeline(1, n, fmt, chunk_syms=256, statistics=False, single_pass=True)
+    one.codes.copy_(two.codes)
+    one.convert_encode(g)
+    assert one.poll() == 0
+    assert torch.equal(one.anchor, two.anchor)
+    assert torch.equal(one.total_bits, two.total_bits)
+    assert torch.equal(one.chunk_bitoff, two.chunk_bitoff), "chunk offsets"
+    nw = (int(two.total_bits[0].item()) + 63) // 64
+    assert torch.equal(one.words[0, :nw], two.words[0, :nw]), "stream words"
+    assert torch.equal(one.err.view(torch.int32), two.err.view(torch.int32)), "memory"
+    A = one.anchor[0].cpu().numpy()
+    for a, b in [((1 << 31) - 50_001, (1 << 31) + 50_003), (n - 66_001, n)]:
+        sym, e_new = oracle.convert_ef(g[0, a:b].cpu().numpy(), np.zeros(b - a, np.float32), A, 1.0, f)
+        assert np.array_equal(u32(one.err[0, a:b]), e_new.view(np.uint32)), (a, b)
+    lens = one.codes[0, :fmt.K].cpu().numpy()
+    m = 65_536
+    sym, _ = oracle.convert_ef(g[0, :m].cpu().numpy(), np.zeros(m, np.float32), A, 1.0, f)
+    words, off, total = oracle.encode(sym, lens, oracle.canonical_codes(lens), 256)
+    assert np.array_equal(u64(one.chunk_bitoff[0, :m // 256 + 1]), off)
+    assert np.array_equal(u64(one.words[0, :total // 64]), words[:total // 64])
