@@ -221,3 +221,33 @@ def test_one_code_shared_by_everything(co3, E, M, scaled):
     reading the one table (two symbols per lookup and per workspace byte for alphabets of 16)."""
     run_layers(co3, 3, [70001], E, M, 256, scaled=scaled, T=2)
     run_layers(co3, 2, [5000, 3, 60000], E, M, 64, scaled=scaled, grouped=False, T=1)
+
+
+def test_degenerate_one_symbol_table_and_zero_gradient(co3):
+    """A table with a single codeword (length 1) and a gradient of zeros: n one-bit codewords; then a gradient
+    with one non-zero element, whose symbol has no codeword."""
+    fmt, f = co3.Fmt(3, 1), oracle.Fmt(3, 1)
+    n = 70_001
+    pipe = co3.Co3Pipeline(2, n, fmt, chunk_syms=128, statistics=False, single_pass=True)
+    w = np.zeros((2, fmt.K), np.uint32)
+    w[:, 0] = 5
+    pipe.build(torch.from_numpy(w.view(np.int32)).cuda())
+    lens = oracle.huffman_lengths(w[0])
+    assert lens[0] == 1 and lens[1:].sum() == 0
+    g = pipe.new_gradient_buffer()
+    pipe.step(g, rebuild=False)
+    assert pipe.poll() == 0
+    zeros = np.zeros(n, np.float32)
+    A = oracle.anchor(zeros, f)
+    sym, e_new = oracle.convert_ef(zeros, zeros, A, 1.0, f)
+    words, off, total = oracle.encode(sym, lens, oracle.canonical_codes(lens), 128)
+    assert total == n
+    for u in range(2):
+        assert np.array_equal(pipe.anchor[u].cpu().numpy(), A)
+        assert int(pipe.total_bits[u].item()) == total
+        assert np.array_equal(u64(pipe.chunk_bitoff[u]), off)
+        assert np.array_equal(u64(pipe.words[u, :(total + 63) // 64]), words[:(total + 63) // 64])
+    assert not pipe.avg[:n].any()
+    g[1, 12_345] = 1.0
+    pipe.convert_encode(g)
+    assert pipe.poll() == co3.binding.ENOCODE
