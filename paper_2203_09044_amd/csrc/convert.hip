@@ -25,9 +25,11 @@ __global__ void k_fill_i32(int32_t *a, int64_t na, int32_t va, uint32_t *b, int6
 // ------------------------------------------------------------------------------------------
 #define AM_UNROLL 8
 #define AM_TILE (CV_TILE * AM_UNROLL)   // elements per block step: eight 16-byte loads in flight per thread
+#define AM_PARTS 8                      // tensor parts of a straddling tile reduced per pair of block barriers
 
-// Block-wide maximum of the magnitude bit patterns, then at most one atomic per block (and none
-// when the anchor already holds a value at least as large).  Called under block-uniform conditions.
+// Block-wide maximum of the magnitude bit patterns, then one atomic per block, fired without a result
+// (reading the anchor first, to skip the atomic when it is already large enough, was measured slower:
+// the line is contended while the blocks finish).  Called under block-uniform conditions.
 __device__ __forceinline__ void absmax_flush(uint32_t m, int32_t *anchor_us, uint32_t *red)
 {
     m = wave_max_u32(m);
@@ -38,7 +40,7 @@ __device__ __forceinline__ void absmax_flush(uint32_t m, int32_t *anchor_us, uin
         for (int w = 1; w < CV_BLOCK / CO3_WAVE; ++w) mm = mm > red[w] ? mm : red[w];
         int cand = (int)(mm >> 23) - 127;
         if (cand > 127) cand = 127;
-        if (cand > *reinterpret_cast<volatile int32_t *>(anchor_us)) atomicMax(anchor_us, cand);
+        atomicMax(anchor_us, cand);
     }
     __syncthreads();
 }
@@ -61,6 +63,7 @@ __global__ __launch_bounds__(CV_BLOCK) void k_absmax(const float *__restrict__ g
     const float *gu = g + (int64_t)u * stride;
     int32_t *anchor_u = anchor + (int64_t)u * nseg;
     __shared__ uint32_t red[CV_BLOCK / CO3_WAVE];
+    __shared__ uint32_t parts[CV_BLOCK / CO3_WAVE][AM_PARTS];
     __shared__ int64_t seg_cache[CO3_SEG_CACHE];
     const int64_t *seg_off = co3_cache_segs(seg_off_g, nseg, seg_cache);
     int64_t beg = (int64_t)blockIdx.x * per_block;
@@ -101,27 +104,54 @@ __global__ __launch_bounds__(CV_BLOCK) void k_absmax(const float *__restrict__ g
                     }
                 }
             }
-        } else {                         // tile straddles tensors: one block reduction per tensor part
+        } else {
+            // The tile straddles tensors.  Its elements are loaded once, all loads in flight together as in
+            // the plain case (a loop per tensor part would put one memory latency per part into this block,
+            // and the kernel ends with its slowest block); then the parts are reduced from registers, up
+            // to AM_PARTS of them per pair of block barriers.
             absmax_flush(m, anchor_u + cur_seg, red);
             m = 0;
-            for (int sg = s_lo; sg <= s_hi; ++sg) {
-                const int64_t a0 = seg_off[sg] > t0 ? seg_off[sg] : t0;
-                const int64_t a1 = seg_off[sg + 1] < t1 ? seg_off[sg + 1] : t1;
-                uint32_t part = 0;
-                for (int64_t j = a0 + threadIdx.x; j < a1; j += (int64_t)AM_UNROLL * CV_BLOCK) {
-                    float v[AM_UNROLL];      // independent loads, all in flight together
+            uint32_t a[AM_UNROLL][CV_VEC];
 #pragma unroll
-                    for (int k = 0; k < AM_UNROLL; ++k) {
-                        const int64_t jk = j + (int64_t)k * CV_BLOCK;
-                        v[k] = jk < a1 ? gu[jk] : 0.0f;
-                    }
+            for (int k = 0; k < AM_UNROLL; ++k) {
+                const int64_t j0 = i + (int64_t)k * CV_TILE;
+                if (j0 + CV_VEC <= t1) {
+                    const float4 v = *reinterpret_cast<const float4 *>(gu + j0);
+                    a[k][0] = __float_as_uint(v.x); a[k][1] = __float_as_uint(v.y);
+                    a[k][2] = __float_as_uint(v.z); a[k][3] = __float_as_uint(v.w);
+                } else {
 #pragma unroll
-                    for (int k = 0; k < AM_UNROLL; ++k) {
-                        uint32_t a = __float_as_uint(v[k]) & 0x7fffffffu;
-                        part = part > a ? part : a;
-                    }
+                    for (int c = 0; c < CV_VEC; ++c) a[k][c] = j0 + c < t1 ? __float_as_uint(gu[j0 + c]) : 0u;
                 }
-                absmax_flush(part, anchor_u + sg, red);
+#pragma unroll
+                for (int c = 0; c < CV_VEC; ++c) a[k][c] &= 0x7fffffffu;
+            }
+            for (int sg0 = s_lo; sg0 <= s_hi; sg0 += AM_PARTS) {
+                const int np = s_hi - sg0 + 1 < AM_PARTS ? s_hi - sg0 + 1 : AM_PARTS;
+                for (int p = 0; p < np; ++p) {
+                    const int64_t a0 = seg_off[sg0 + p], a1 = seg_off[sg0 + p + 1];
+                    uint32_t part = 0;
+#pragma unroll
+                    for (int k = 0; k < AM_UNROLL; ++k)
+#pragma unroll
+                        for (int c = 0; c < CV_VEC; ++c) {
+                            const int64_t j = i + (int64_t)k * CV_TILE + c;
+                            const uint32_t v = j >= a0 && j < a1 ? a[k][c] : 0u;
+                            part = part > v ? part : v;
+                        }
+                    part = wave_max_u32(part);
+                    if ((threadIdx.x & (CO3_WAVE - 1)) == 0) parts[threadIdx.x / CO3_WAVE][p] = part;
+                }
+                __syncthreads();
+                if ((int)threadIdx.x < np) {
+                    uint32_t mm = 0;
+                    for (int w = 0; w < CV_BLOCK / CO3_WAVE; ++w) mm = mm > parts[w][threadIdx.x] ? mm : parts[w][threadIdx.x];
+                    int cand = (int)(mm >> 23) - 127;
+                    if (cand > 127) cand = 127;
+                    if (seg_off[sg0 + threadIdx.x + 1] > seg_off[sg0 + threadIdx.x])       // an empty tensor keeps the clamp
+                        atomicMax(anchor_u + sg0 + threadIdx.x, cand);
+                }
+                __syncthreads();
             }
             cur_seg = s_hi;
         }
@@ -233,12 +263,30 @@ __global__ __launch_bounds__(CV_BLOCK) void k_convert_ef(const float *__restrict
             convert4(i, anchor_u[s_lo], SCALED ? scale_u[s_lo] : 1.0f, ld_stream_f4(gu + i), ld_stream_f4(eu + i));
         } else if (s_lo == s_hi) {       // ragged tail inside one tensor
             convert_part(i, (i + CV_VEC < t1 ? i + CV_VEC : t1), 1, s_lo);
-        } else {                         // a tile that straddles tensors: tensor part by tensor part
-            for (int sg = s_lo; sg <= s_hi; ++sg) {
-                const int64_t a0 = seg_off[sg] > t0 ? seg_off[sg] : t0;
-                const int64_t a1 = seg_off[sg + 1] < t1 ? seg_off[sg + 1] : t1;
-                convert_part(a0 + threadIdx.x, a1, CV_BLOCK, sg);
+        } else if (i + CV_VEC <= t1) {
+            // a tile that straddles tensors: the same loads and stores as a plain tile (a loop per tensor
+            // part would put one memory latency per part into this block), each element under the anchor
+            // of its own tensor
+            const float4 gv = ld_stream_f4(gu + i), ev = ld_stream_f4(eu + i);
+            const int sa = co3_find_seg(seg_off, nseg, i), sb = co3_find_seg(seg_off, nseg, i + CV_VEC - 1);
+            if (sa == sb) {
+                convert4(i, anchor_u[sa], SCALED ? scale_u[sa] : 1.0f, gv, ev);
+            } else {
+                const float ga[CV_VEC] = {gv.x, gv.y, gv.z, gv.w}, ea[CV_VEC] = {ev.x, ev.y, ev.z, ev.w};
+                float en[CV_VEC];
+                uint32_t q[CV_VEC];
+#pragma unroll
+                for (int k = 0; k < CV_VEC; ++k) {
+                    const int sg = co3_find_seg(seg_off, nseg, i + k);
+                    const int A = anchor_u[sg];
+                    en[k] = convert1(ga[k], ea[k], A, A - F + 1, SCALED ? scale_u[sg] : 1.0f, q[k]);
+                    if (HIST) atomicAdd(&myhist[q[k] * copies + mycopy], 1u);
+                }
+                st_stream_f4(eu + i, make_float4(en[0], en[1], en[2], en[3]));
+                *reinterpret_cast<uint32_t *>(su + i) = q[0] | (q[1] << 8) | (q[2] << 16) | (q[3] << 24);
             }
+        } else {                         // its ragged end, element by element
+            for (int64_t j = i; j < t1; ++j) convert_part(j, j + 1, 1, co3_find_seg(seg_off, nseg, j));
         }
         t0 += CV_TILE;
     }
@@ -387,13 +435,15 @@ __global__ __launch_bounds__(CV_BLOCK) void k_histogram_layers(const uint8_t *__
 // ------------------------------------------------------------------------------------------
 // launchers
 // ------------------------------------------------------------------------------------------
-static int64_t per_block_for(int64_t n, int U, int64_t tile, int *blocks_out, int K = 0)
+static int64_t per_block_for(int64_t n, int U, int64_t tile, int *blocks_out, int K = 0, bool few = false)
 {
     // about 8 blocks per compute unit in total, each a whole number of tiles; half as many when every
-    // block ends by adding up to 256 counters into the same few cache lines
+    // block ends by adding up to 256 counters into the same few cache lines; (few) at least two tiles per
+    // block where every block ends with an atomic on one word per tensor
     int64_t target_blocks = (K >= 128 ? 1024 : 2048) / (U > 0 ? U : 1);
-    if (target_blocks < 1) target_blocks = 1;
     int64_t tiles = (n + tile - 1) / tile;
+    if (few && target_blocks > tiles / 2) target_blocks = tiles / 2;
+    if (target_blocks < 1) target_blocks = 1;
     int64_t tiles_per_block = (tiles + target_blocks - 1) / target_blocks;
     if (tiles_per_block < 1) tiles_per_block = 1;
     int64_t blocks = (tiles + tiles_per_block - 1) / tiles_per_block;
@@ -418,7 +468,7 @@ hipError_t co3_launch_absmax(const float *g, int64_t n, int U, int64_t stride, c
 {
     if (n <= 0) return hipSuccess;
     int blocks;
-    int64_t pb = per_block_for(n, U, AM_TILE, &blocks);
+    int64_t pb = per_block_for(n, U, AM_TILE, &blocks, 0, true);
     Co3LaunchTimer tm(CO3_K_ABSMAX, st);
     hipLaunchKernelGGL(k_absmax, dim3(blocks, U), dim3(CV_BLOCK), 0, st, g, n, stride, seg_off, nseg, anchor, pb);
     return hipGetLastError();
