@@ -94,13 +94,42 @@ __global__ __launch_bounds__(MO_BLOCK) void k_moments(const float *__restrict__ 
             } else {
                 for (int64_t j = t0 + threadIdx.x; j < t1; j += MO_BLOCK) add1(gu[j], eu[j]);
             }
-        } else {                         // tile straddles tensors: one block reduction per tensor part
+        } else {
+            // The tile straddles tensors.  Its elements are loaded once, all loads in flight together as in
+            // the plain case (a loop per tensor part would put one memory latency per part into this block,
+            // and the kernel ends with its slowest block); then every part is summed from registers.
             moments_flush(s1, s2, sums_u + 2 * cur_seg, red);
+            float x[MO_UNROLL][MO_VEC];
+#pragma unroll
+            for (int k = 0; k < MO_UNROLL; ++k) {
+                const int64_t j0 = i + (int64_t)k * (MO_BLOCK * MO_VEC);
+                float gq[MO_VEC], eq[MO_VEC];
+                if (j0 + MO_VEC <= t1) {
+                    const float4 gv = *reinterpret_cast<const float4 *>(gu + j0), ev = *reinterpret_cast<const float4 *>(eu + j0);
+                    gq[0] = gv.x; gq[1] = gv.y; gq[2] = gv.z; gq[3] = gv.w;
+                    eq[0] = ev.x; eq[1] = ev.y; eq[2] = ev.z; eq[3] = ev.w;
+                } else {
+#pragma unroll
+                    for (int c = 0; c < MO_VEC; ++c) {
+                        gq[c] = j0 + c < t1 ? gu[j0 + c] : 0.0f;
+                        eq[c] = j0 + c < t1 ? eu[j0 + c] : 0.0f;
+                    }
+                }
+#pragma unroll
+                for (int c = 0; c < MO_VEC; ++c) x[k][c] = gq[c] + gamma * eq[c];   // as the conversion computes it
+            }
             for (int sg = s_lo; sg <= s_hi; ++sg) {
-                const int64_t a0 = seg_off[sg] > t0 ? seg_off[sg] : t0;
-                const int64_t a1 = seg_off[sg + 1] < t1 ? seg_off[sg + 1] : t1;
+                const int64_t a0 = seg_off[sg], a1 = seg_off[sg + 1];
                 s1 = s2 = 0.0;
-                for (int64_t j = a0 + threadIdx.x; j < a1; j += MO_BLOCK) add1(gu[j], eu[j]);
+#pragma unroll
+                for (int k = 0; k < MO_UNROLL; ++k)
+#pragma unroll
+                    for (int c = 0; c < MO_VEC; ++c) {
+                        const int64_t j = i + (int64_t)k * (MO_BLOCK * MO_VEC) + c;
+                        const double xd = j >= a0 && j < a1 && j < t1 ? (double)x[k][c] : 0.0;
+                        s1 += fabs(xd);
+                        s2 += xd * xd;
+                    }
                 moments_flush(s1, s2, sums_u + 2 * sg, red);
             }
             s1 = s2 = 0.0;
@@ -180,8 +209,9 @@ hipError_t co3_launch_moments(const float *g, const float *err, int64_t n, int U
 {
     if (n <= 0) return hipSuccess;
     int64_t target_blocks = 2048 / U;
-    if (target_blocks < 1) target_blocks = 1;
     const int64_t tiles = (n + MO_TILE - 1) / MO_TILE;
+    if (target_blocks > tiles / 4) target_blocks = tiles / 4;   // every block ends with two atomics per tensor: few blocks end at once
+    if (target_blocks < 1) target_blocks = 1;
     int64_t tiles_per_block = (tiles + target_blocks - 1) / target_blocks;
     if (tiles_per_block < 1) tiles_per_block = 1;
     const int64_t blocks = (tiles + tiles_per_block - 1) / tiles_per_block;
