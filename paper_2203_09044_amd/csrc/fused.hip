@@ -36,10 +36,11 @@ __device__ __forceinline__ void fused_stage(unsigned long long *stage, uint64_t 
     if (o + nb > 64u) atomicOr(&stage[w + 1], (unsigned long long)(v << (64u - o)));
 }
 
-// One unit's elements: error correction, conversion, new memory, codeword lookup.  PLAIN: all 1024
-// elements exist and lie in one tensor and under one code (vector loads and stores, one anchor, one
-// multiplier, the table in LDS, no branches between the elements, so that the table reads of a lane
-// overlap); otherwise every access is guarded and anchor, multiplier and code are looked up per element.
+// One unit's elements: error correction, conversion, new memory, codeword lookup.  WHOLE: all 1024
+// elements exist (vector loads and stores), else every access is guarded.  PLAIN (with WHOLE): they lie
+// in one tensor and under one code (one anchor, one multiplier, the table in LDS, no branches between the
+// elements, so that the table reads of a lane overlap); else anchor, multiplier and code are looked up
+// per element.
 // SCALED: the bias in its multiplier form (Sec. III (i), Sec. IV-B), as in the two-pass conversion: the
 // corrected gradient times c is rounded onto the grid, the level divided by c.  LAYERS: one code per
 // group of tensors (Sec. III (ii)), codes[group], the wavefront's LDS table holding the code of the
@@ -70,8 +71,16 @@ __device__ __forceinline__ uint64_t fused_entry(const FusedUnit &a, uint32_t q, 
     if (!LAYERS || a.one_code) return a.enc_s[q];
     return (int)q < a.K ? fcode_of(a.codes, co3_find_seg(a.code_seg_off, a.ncodes, idx))->enc[q] : 0ull;
 }
+// the same with the code groups of the first and the last of the lane's four consecutive elements known
+template <bool LAYERS>
+__device__ __forceinline__ uint64_t fused_entry4(const FusedUnit &a, uint32_t q, int64_t idx, int cg_first, int cg_last)
+{
+    if (!LAYERS || a.one_code) return a.enc_s[q];
+    const int cg = cg_first == cg_last ? cg_first : co3_find_seg(a.code_seg_off, a.ncodes, idx);
+    return (int)q < a.K ? fcode_of(a.codes, cg)->enc[q] : 0ull;
+}
 
-template <bool PLAIN, bool LAYERS, bool SCALED>
+template <bool WHOLE, bool PLAIN, bool LAYERS, bool SCALED>
 __device__ __forceinline__ bool fused_convert_unit(const FusedUnit &a, uint64_t (&acc)[FU_SUB], uint32_t (&qpack)[FU_SUB],
                                                    uint32_t (&nb)[FU_SUB])
 {
@@ -79,7 +88,7 @@ __device__ __forceinline__ bool fused_convert_unit(const FusedUnit &a, uint64_t 
 #pragma unroll
     for (int r = 0; r < FU_SUB; ++r) {
         const int64_t i = a.u0 + r * FU_RUN + a.lane * FU_VEC;
-        if (PLAIN) {
+        if (WHOLE) {
             gv[r] = ld_stream_f4(a.gu + i);
             ev[r] = ld_stream_f4(a.eu + i);
         } else {
@@ -99,11 +108,22 @@ __device__ __forceinline__ bool fused_convert_unit(const FusedUnit &a, uint64_t 
         acc[r] = 0;
         qpack[r] = 0;
         nb[r] = 0;
+        // tensors and code groups of the lane's first and last element of the run: mostly the same
+        int sg_first = 0, sg_last = 0, cg_first = 0, cg_last = 0;
+        if (!PLAIN) {
+            const int64_t j0 = i < a.n ? i : a.n - 1, j3 = i + FU_VEC - 1 < a.n ? i + FU_VEC - 1 : a.n - 1;
+            sg_first = co3_find_seg(a.seg_off, a.nseg, j0);
+            sg_last = co3_find_seg(a.seg_off, a.nseg, j3);
+            if (LAYERS && !a.one_code) {
+                cg_first = co3_find_seg(a.code_seg_off, a.ncodes, j0);
+                cg_last = co3_find_seg(a.code_seg_off, a.ncodes, j3);
+            }
+        }
 #pragma unroll
         for (int k = 0; k < FU_VEC; ++k) {
-            const bool valid = PLAIN || i + k < a.n;
+            const bool valid = WHOLE || i + k < a.n;
             const int64_t idx = valid ? i + k : a.n - 1;
-            const int sg = PLAIN ? 0 : co3_find_seg(a.seg_off, a.nseg, idx);
+            const int sg = PLAIN ? 0 : sg_first == sg_last ? sg_first : co3_find_seg(a.seg_off, a.nseg, idx);
             const int A = PLAIN ? a.A_unit : a.anchor_u[sg];
             const float c = !SCALED ? 1.0f : PLAIN ? a.c_unit : a.scale_u[sg];
             const float x = ga[k] + a.gamma * ea[k];     // no contraction (build flag): one rounding per operation
@@ -112,14 +132,14 @@ __device__ __forceinline__ bool fused_convert_unit(const FusedUnit &a, uint64_t 
             co3_quantize(SCALED ? c * x : x, A - a.F + 1, A, a.E, a.M, a.codemax, q, v);
             if (SCALED) v = v / c;
             en[k] = x - v;
-            const uint64_t e = !valid ? 0ull : PLAIN ? a.enc_s[q] : fused_entry<LAYERS>(a, q, idx);
+            const uint64_t e = !valid ? 0ull : PLAIN ? a.enc_s[q] : fused_entry4<LAYERS>(a, q, idx, cg_first, cg_last);
             const uint32_t l = (uint32_t)(e & 63u);
             nocode |= valid && l == 0u;
             acc[r] = (acc[r] << l) | (e >> 6);
             qpack[r] |= q << (8 * k);
             nb[r] += l;
         }
-        if (PLAIN) {
+        if (WHOLE) {
             st_stream_f4(a.eu + i, make_float4(en[0], en[1], en[2], en[3]));
         } else {
 #pragma unroll
@@ -209,8 +229,9 @@ __global__ __launch_bounds__(FU_BLOCK) void k_convert_stage(const float *__restr
         const FusedUnit ua = {gu, eu, n, u0, lane, seg_off, nseg, anchor_u, scale_u, anchor_u[s_lo],
                                  SCALED ? scale_u[s_lo] : 1.0f, gamma, E, M, F, K, codemax, enc_s, codes, code_seg_off,
                                  ncodes, one_code};
-        if (whole && s_lo == s_hi && one_code) nocode |= fused_convert_unit<true, LAYERS, SCALED>(ua, acc, qpack, nb);
-        else nocode |= fused_convert_unit<false, LAYERS, SCALED>(ua, acc, qpack, nb);
+        if (whole && s_lo == s_hi && one_code) nocode |= fused_convert_unit<true, true, LAYERS, SCALED>(ua, acc, qpack, nb);
+        else if (whole) nocode |= fused_convert_unit<true, false, LAYERS, SCALED>(ua, acc, qpack, nb);
+        else nocode |= fused_convert_unit<false, false, LAYERS, SCALED>(ua, acc, qpack, nb);
         // positions: one scan per pair of runs
         uint32_t pos[FU_SUB], total = 0;
 #pragma unroll
