@@ -174,12 +174,21 @@ __global__ __launch_bounds__(EN_BLOCK) void k_enc_sizes_layers(const uint8_t *__
                 bits += c < nvalid ? l : 0u;
                 nocode |= c < nvalid && l == 0u;
             }
-        } else {
-            for (int c = 0; c < nvalid; ++c) {
+        } else if (nvalid > 0) {
+            // a tile that straddles tensors: lengths from the code blobs.  The lane's 16 symbols mostly lie in
+            // one tensor: then one lookup of the tensor and 16 independent loads (a lookup and a load per
+            // symbol in turn put 16 memory latencies into this wavefront, and the kernel ends with its
+            // slowest one)
+            const int c_first = co3_find_seg(seg_off, nseg, i), c_last = co3_find_seg(seg_off, nseg, i + nvalid - 1);
+            const uint8_t *len_first = code_of(codes, c_first)->len;
+#pragma unroll
+            for (int c = 0; c < EN_LSYM; ++c) {
                 const uint32_t sy = (s[c >> 2] >> (8 * (c & 3))) & 0xffu;
-                const uint32_t l = (int)sy < K ? code_of(codes, co3_find_seg(seg_off, nseg, i + c))->len[sy] : 0u;
+                const uint8_t *lp = c_first == c_last ? len_first
+                                                      : code_of(codes, co3_find_seg(seg_off, nseg, c < nvalid ? i + c : i))->len;
+                const uint32_t l = c < nvalid && (int)sy < K ? lp[sy] : 0u;
                 bits += l;
-                nocode |= l == 0u;
+                nocode |= c < nvalid && l == 0u;
             }
         }
         bits = wave_sum_u32(bits);
@@ -402,7 +411,19 @@ __global__ __launch_bounds__(EN_BLOCK) void k_enc_pack(const uint8_t *__restrict
         if (!LAYERS || one_tensor) return enc_s[sy];
         return (int)sy < K ? code_of(codes, co3_find_seg(seg_off, nseg, idx))->enc[sy] : 0ull;
     };
-    auto entry = [&](uint32_t sy, int k) -> uint64_t { return entry_at(sy, i + k); };
+    // the lane's own symbols in a tile that straddles tensors: mostly one tensor, looked up once, so that the
+    // 16 reads from its code blob are independent
+    int c_first = 0, c_last = 0;
+    if (LAYERS && !one_tensor && nvalid > 0) {
+        c_first = co3_find_seg(seg_off, nseg, i);
+        c_last = co3_find_seg(seg_off, nseg, i + nvalid - 1);
+    }
+    const uint64_t *enc_first = LAYERS ? code_of(codes, c_first)->enc : nullptr;
+    auto entry = [&](uint32_t sy, int k) -> uint64_t {
+        if (!LAYERS || one_tensor) return enc_s[sy];
+        if (c_first == c_last) return (int)sy < K ? enc_first[sy] : 0ull;
+        return entry_at(sy, i + k);
+    };
 
     // One table lookup per symbol: the codewords of every 4 symbols are concatenated into one run
     // (kept in registers) as long as the run fits 64 bits, which it always does for codes of at most
