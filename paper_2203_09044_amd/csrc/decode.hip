@@ -606,10 +606,14 @@ __global__ __launch_bounds__(DL_BLOCK) void k_decode_layers(const uint64_t *__re
         __syncthreads();
         bool any_long = false;           // uniform
         for (int k = 0; k < DL_SLOTS; ++k) any_long |= t[k].maxlen > t[k].lut_bits;
-        if (cur < nsym && cur_seg >= sg && cur_seg < sg + DL_SLOTS) {
+        // a chunk that straddles tensors goes on at once while the next tensor's tables are in the window
+        // (if it waited for the next step it would start its second part when all other lanes have finished
+        // their whole chunks)
+        while (cur < nsym && cur_seg >= sg && cur_seg < sg + DL_SLOTS) {
             const DecTables &tl = t[cur_seg & (DL_SLOTS - 1)];
             const int64_t seg_end = seg_off[cur_seg + 1] - first;
             const int i1 = seg_end < nsym ? (int)seg_end : nsym;
+            if (i1 <= cur) break;        // boundaries that do not increase: the chunk stays unfinished and is reported
             if (any_long) decode_range<DE_LONG>(tl, ls, cur, i1, out, run_step, ok);
             else decode_range<DE_SHORT>(tl, ls, cur, i1, out, run_step, ok);
             cur = i1;
