@@ -545,7 +545,7 @@ __global__ __launch_bounds__(DE_BLOCK) void k_decode(const uint64_t *__restrict_
 // (tensor s in slot s mod 4): a lane decodes the part of its chunk that lies in the tensor at its
 // position as soon as that tensor's tables are there, so the chunks on both sides of a tensor
 // boundary are decoded at the same time, each lane reading the table of its own tensor; a chunk that
-// straddles tensors continues in the next step.  Lanes whose tensor is more than three tensors away
+// straddles tensors goes on into the next tensor while that tensor's tables are in the window.  Lanes whose tensor is more than three tensors away
 // from the first one of the range wait for the window: tensors much smaller than a workgroup's range
 // (512 chunks) are better given a code together with a neighbour.
 #define DL_BLOCK 512
