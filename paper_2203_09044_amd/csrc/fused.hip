@@ -341,7 +341,7 @@ __global__ __launch_bounds__(FU_BLOCK) void k_compact(const uint64_t *__restrict
     for (int k = 0; k < CP_UNITS; ++k) {
         d[k] = gbase + (uint32_t)__builtin_amdgcn_readlane((int)my_off, k);
         // every owned word of a unit starts at the same bit of a slot word (64 * gw - d is the same modulo
-        // 64); the amount is uniform and kept in a scalar register
+        // 64); the amount is uniform over the wavefront
         sh[k] = (0u - (uint32_t)d[k]) & 63u;
     }
 
