@@ -300,6 +300,7 @@ __global__ __launch_bounds__(CO3_WAVE) void k_unit_groups(const uint32_t *__rest
 // 64*gw - D on (D = stream position of the unit), and where the unit ends inside the word, the leading
 // bits of the next unit's slot.  The first 64 owned words of all units are loaded before any is stored.
 #define CP_UNITS 4
+#define CP_ROUNDS 2
 static_assert(CO3_FUSED_GROUP % CP_UNITS == 0, "the units of a wavefront share a group");
 
 __device__ __forceinline__ uint64_t compact_word(uint64_t s0, uint64_t s1, uint32_t sh, uint32_t a, uint32_t size,
@@ -362,7 +363,9 @@ __global__ __launch_bounds__(FU_BLOCK) void k_compact(const uint64_t *__restrict
 
     uint64_t *wu = words + (int64_t)u * cap_words;
     const uint64_t *slot0 = slots + ((int64_t)u * nunits + unit0) * CO3_FUSED_SLOT_WORDS;
-    uint64_t s0[CP_UNITS], s1[CP_UNITS], next0[CP_UNITS], gw0[CP_UNITS];
+    // the first CP_ROUNDS * 64 owned words of every unit are loaded before any is stored (two rounds cover
+    // units of up to 8 bits per element); longer units finish in a loop
+    uint64_t s0[CP_UNITS][CP_ROUNDS], s1[CP_UNITS][CP_ROUNDS], next0[CP_UNITS], gw0[CP_UNITS];
     uint32_t nown[CP_UNITS];
 #pragma unroll
     for (int k = 0; k < CP_UNITS; ++k) {
@@ -372,18 +375,26 @@ __global__ __launch_bounds__(FU_BLOCK) void k_compact(const uint64_t *__restrict
         // beyond the capacity nothing is written (the scan pass has reported it)
         nown[k] = size[k] == 0u || gw1 > (uint64_t)cap_words ? 0u : (uint32_t)(gw1 - gw0[k]);
         const uint32_t nw = (size[k] + 63u) >> 6;                        // words of the slot that hold bits
-        s0[k] = (uint32_t)lane < nown[k] ? slot[lane] : 0ull;
-        s1[k] = (uint32_t)lane < nown[k] && (uint32_t)lane + 1u < nw ? slot[lane + 1] : 0ull;
+#pragma unroll
+        for (int r = 0; r < CP_ROUNDS; ++r) {
+            const uint32_t a = (uint32_t)lane + r * CO3_WAVE;
+            s0[k][r] = a < nown[k] ? slot[a] : 0ull;
+            s1[k][r] = a < nown[k] && a + 1u < nw ? slot[a + 1u] : 0ull;
+        }
         next0[k] = nown[k] && size[k + 1] ? slot[CO3_FUSED_SLOT_WORDS] : 0ull;   // first word of the next unit's slot
     }
 #pragma unroll
     for (int k = 0; k < CP_UNITS; ++k)
-        if ((uint32_t)lane < nown[k]) wu[gw0[k] + lane] = compact_word(s0[k], s1[k], sh[k], lane, size[k], next0[k]);
 #pragma unroll
-    for (int k = 0; k < CP_UNITS; ++k) {                                 // units of more than 64 words
+        for (int r = 0; r < CP_ROUNDS; ++r) {
+            const uint32_t a = (uint32_t)lane + r * CO3_WAVE;
+            if (a < nown[k]) wu[gw0[k] + a] = compact_word(s0[k][r], s1[k][r], sh[k], a, size[k], next0[k]);
+        }
+#pragma unroll
+    for (int k = 0; k < CP_UNITS; ++k) {                                 // units of more words than that
         const uint64_t *slot = slot0 + (int64_t)k * CO3_FUSED_SLOT_WORDS;
         const uint32_t nw = (size[k] + 63u) >> 6;
-        for (uint32_t a = lane + CO3_WAVE; a < nown[k]; a += CO3_WAVE)
+        for (uint32_t a = lane + CP_ROUNDS * CO3_WAVE; a < nown[k]; a += CO3_WAVE)
             wu[gw0[k] + a] = compact_word(slot[a], a + 1u < nw ? slot[a + 1u] : 0ull, sh[k], a, size[k], next0[k]);
     }
 }
