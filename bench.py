@@ -111,11 +111,13 @@ def main():
     ap.add_argument("--bias", default="absmax", choices=("absmax", "moments"),
                     help="absmax: integer anchor from max|g| (the headline configuration); moments: the paper's bias "
                          "rule (moment sums, GenNorm fit, multiplier) on the fixed grid of anchor 2^(E-1)")
-    ap.add_argument("--codes", default="user", choices=("user", "user-model", "layer", "layer-model"),
+    ap.add_argument("--codes", default="user", choices=("user", "user-model", "user-lagged", "layer", "layer-model"),
                     help="user: one empirical code per client, rebuilt every step (the headline configuration); "
                          "layer: one code per tensor shared by the clients, rebuilt every step from the pooled "
                          "per-tensor counts; user-model: one fixed code per client designed once from the GenNorm law "
                          "of the workload (C4's model table; no histogram, no code build inside the step); "
+                         "user-lagged: one empirical code per client built from the counts of the previous step, "
+                         "gathered by the one-pass user side (conversion + compression in one pass every step); "
                          "layer-model: one fixed code per tensor designed once from the GenNorm "
                          "law of the tensor (no histogram, no code build inside the step)")
     ap.add_argument("--single-pass", action="store_true",
@@ -187,6 +189,9 @@ def main():
         code_seg_off = inp.seg_offsets(groups)
         desc += f", {len(groups)} code groups (tensors under 16,384 elements share the code of the large tensor before them)"
     fixed_user_tables = args.codes == "user-model"
+    lagged = args.codes == "user-lagged"
+    if lagged and args.bias != "absmax":
+        raise SystemExit("--codes user-lagged goes with the integer anchor")
     if args.single_pass and args.codes not in ("user-model", "layer-model"):
         raise SystemExit("--single-pass needs --codes user-model or layer-model (the codes must be known before the step)")
     if args.single_pass and fixed_user_tables and args.bias != "absmax":
@@ -194,12 +199,12 @@ def main():
     pipe = Co3Pipeline(w.U, w.n, fmt, chunk_syms=args.chunk, seg_off=w.seg_off if w.sizes is not None else None,
                        bias=args.bias, gamma=args.gamma, codes="user" if args.codes.startswith("user") else "layer",
                        code_seg_off=code_seg_off, statistics=not fixed_user_tables,
-                       single_pass=args.single_pass,
-                       cap_words=2 * B.cap_words_empirical(w.n, fmt) if fixed_user_tables else None)
+                       single_pass=args.single_pass or lagged, lagged_codes=lagged,
+                       cap_words=2 * B.cap_words_empirical(w.n, fmt) if fixed_user_tables or lagged else None)
     log(f"[bench] {desc}; generating {args.pool} device batches")
     batches = device_batches(w, betas, alpha, args.pool, pipe)
 
-    rebuild = args.codes in ("user", "layer")
+    rebuild = args.codes in ("user", "layer", "user-lagged")      # user-lagged: the step builds the next step's codes
     if fixed_user_tables:
         # one table per client from the law the client's gradients are drawn from, on the grid of the client's
         # anchor of the first batch (every emit-able symbol has a codeword, so the table serves every step)
@@ -237,6 +242,8 @@ def main():
         desc += ", fixed per-tensor model tables" + (", single pass" if args.single_pass else "")
     elif args.codes == "layer":
         desc += ", per-tensor codes shared by the clients"
+    elif lagged:
+        desc += ", codes from the counts of the previous step (one-pass user side)"
     for i in range(args.warmup):
         pipe.step(batches[i % args.pool], rebuild=rebuild)
     torch.cuda.synchronize()
@@ -331,6 +338,7 @@ def main():
         "config": {"workload": desc, "U": w.U, "n": w.n, "format": f"E{w.E}M{w.M}", "chunk_syms": args.chunk,
                    "table": {"user": "empirical per client, rebuilt every step",
                              "user-model": "fixed per client, designed from the GenNorm law of the workload",
+                             "user-lagged": "empirical per client from the previous step's counts (+1), rebuilt every step",
                              "layer": "empirical per tensor, pooled over the clients, rebuilt every step",
                              "layer-model": "fixed per tensor, designed from the GenNorm law of the workload"}[args.codes],
                    "gamma": args.gamma, "bias": args.bias, "codes": args.codes},

@@ -263,6 +263,10 @@ int32_t co3_ps_aggregate_layers(const uint64_t *words, int64_t cap_words, const 
  *              unspecified: every 1024 elements pack into a slot of 8 KiB of their own (room for 1024
  *              codewords of any length) before they are moved into the stream, 8 bytes per element
  *              of address space of which a codeword's worth is touched
+ *   counts     NULL, or [U][K] u32 out, overwritten: 1 + the number of occurrences of every symbol in this
+ *              call.  A code built from them (co3_build_code) has a codeword for every symbol, so it can
+ *              serve the next iteration: empirical codes that follow the gradients one iteration behind,
+ *              at the cost of one pass (Sec. III (ii) leaves the model of the distribution open)
  *   errors     as the two calls: CO3_EINVAL on the host; CO3_ENOCODE, CO3_ECAP through status (after
  *              CO3_ENOCODE the stream is unspecified)
  *
@@ -276,8 +280,9 @@ int32_t co3_ps_aggregate_layers(const uint64_t *words, int64_t cap_words, const 
 size_t co3_convert_encode_workspace_bytes(int64_t n, int32_t U, int32_t chunk_syms);
 int32_t co3_convert_encode(const float *g, float *err, int64_t n, int32_t U, int64_t stride, const int64_t *seg_off,
                            int32_t nseg, int32_t *anchor, int32_t anchor_mode, float gamma, co3_fmt fmt, const void *codes,
-                           uint64_t *words, int64_t cap_words, int32_t chunk_syms, uint64_t *chunk_bitoff,
-                           uint64_t *total_bits, void *workspace, size_t ws_bytes, int32_t *status, void *stream);
+                           uint32_t *counts, uint64_t *words, int64_t cap_words, int32_t chunk_syms,
+                           uint64_t *chunk_bitoff, uint64_t *total_bits, void *workspace, size_t ws_bytes, int32_t *status,
+                           void *stream);
 int32_t co3_convert_encode_layers(const float *g, float *err, int64_t n, int32_t U, int64_t stride,
                                   const int64_t *seg_off, int32_t nseg, int32_t *anchor, int32_t anchor_mode,
                                   const float *scale, float gamma, co3_fmt fmt, const void *codes,

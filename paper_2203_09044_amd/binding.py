@@ -106,7 +106,7 @@ def _load():
     L.co3_convert_encode_workspace_bytes.restype = sz
     L.co3_convert_encode_workspace_bytes.argtypes = [i64, i32, i32]
     L.co3_convert_encode.restype = i32
-    L.co3_convert_encode.argtypes = [p, p, i64, i32, i64, p, i32, p, i32, C.c_float, _Fmt, p, p, i64, i32, p, p, p, sz, p, p]
+    L.co3_convert_encode.argtypes = [p, p, i64, i32, i64, p, i32, p, i32, C.c_float, _Fmt, p, p, p, i64, i32, p, p, p, sz, p, p]
     L.co3_convert_encode_layers.restype = i32
     L.co3_convert_encode_layers.argtypes = [p, p, i64, i32, i64, p, i32, p, i32, p, C.c_float, _Fmt, p, p, i32, p, i64, i32, p,
                                             p, p, sz, p, p]
@@ -190,12 +190,14 @@ def convert_ef(g, err, sym, n, anchor, anchor_mode, gamma, fmt: Fmt, seg_off=Non
 
 
 def convert_encode(g, err, n, anchor, anchor_mode, gamma, fmt: Fmt, codes, words, chunk_syms, chunk_bitoff, total_bits,
-                   workspace, status, seg_off=None, stream=None):
+                   workspace, status, seg_off=None, counts=None, stream=None):
+    """counts: None, or [U][K] int32 out: 1 + occurrences of every symbol (weights of the next iteration's codes)."""
     U, stride = _batch(g)
     nseg = 1 if seg_off is None else seg_off.numel() - 1
     rc = _lib.co3_convert_encode(_dp(g, torch.float32), _dp(err, torch.float32), n, U, stride,
                                  _dp(seg_off, torch.int64), nseg, _dp(anchor, torch.int32), anchor_mode,
-                                 C.c_float(gamma), fmt.c(), _dp(codes, torch.uint8), _dp(words, torch.int64),
+                                 C.c_float(gamma), fmt.c(), _dp(codes, torch.uint8), _dp(counts, torch.int32),
+                                 _dp(words, torch.int64),
                                  words.shape[-1], chunk_syms, _dp(chunk_bitoff, torch.int64), _dp(total_bits, torch.int64),
                                  _dp(workspace), workspace.numel() * workspace.element_size(), _dp(status, torch.int32),
                                  _stream(stream))

@@ -210,9 +210,9 @@ int32_t co3_convert_ef_scaled(const float *g, float *err, uint8_t *sym, int64_t 
 static int32_t convert_encode_common(const float *g, float *err, int64_t n, int32_t U, int64_t stride,
                                      const int64_t *seg_off, int32_t nseg, int32_t *anchor, int32_t anchor_mode,
                                      const float *scale, float gamma, co3_fmt fmt, const void *codes,
-                                     const int64_t *code_seg_off, int32_t ncodes, uint64_t *words, int64_t cap_words,
-                                     int32_t chunk_syms, uint64_t *chunk_bitoff, uint64_t *total_bits, void *workspace,
-                                     size_t ws_bytes, int32_t *status, void *stream)
+                                     const int64_t *code_seg_off, int32_t ncodes, uint32_t *counts, uint64_t *words,
+                                     int64_t cap_words, int32_t chunk_syms, uint64_t *chunk_bitoff, uint64_t *total_bits,
+                                     void *workspace, size_t ws_bytes, int32_t *status, void *stream)
 {
     if (!fmt_ok(fmt) || !batch_ok(n, U, stride) || nseg < 1 || (seg_off == nullptr && nseg != 1)) return CO3_EINVAL;
     if (!chunk_ok(chunk_syms) || cap_words < 0 || cap_words % 2 != 0) return CO3_EINVAL;
@@ -224,25 +224,30 @@ static int32_t convert_encode_common(const float *g, float *err, int64_t n, int3
     if (ws_bytes < co3_convert_encode_workspace_bytes(n, U, chunk_syms)) return CO3_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const FmtC fc(fmt);
-    if (anchor_mode == CO3_ANCHOR_FROM_ABSMAX_G) {
-        hipError_t e = co3_launch_fill(anchor, (int64_t)U * nseg, fc.F - 126, nullptr, 0, st);
+    const bool from_g = anchor_mode == CO3_ANCHOR_FROM_ABSMAX_G;
+    if (from_g || counts) {          // anchors start at the lower clamp, the counts at one
+        hipError_t e = co3_launch_fill(from_g ? anchor : nullptr, from_g ? (int64_t)U * nseg : 0, fc.F - 126, counts,
+                                       counts ? (int64_t)U * fc.K : 0, st, 1u);
         if (e != hipSuccess) return CO3_EHIP;
-        e = co3_launch_absmax(g, n, U, stride, seg_off, nseg, anchor, st);
+    }
+    if (from_g) {
+        hipError_t e = co3_launch_absmax(g, n, U, stride, seg_off, nseg, anchor, st);
         if (e != hipSuccess) return CO3_EHIP;
     }
     return hip_rc(co3_launch_convert_encode(g, err, n, U, stride, seg_off, nseg, anchor, scale, gamma, fmt, codes,
-                                            code_seg_off, ncodes, words, cap_words, chunk_syms, chunk_bitoff, total_bits,
-                                            workspace, status, st));
+                                            code_seg_off, ncodes, counts, words, cap_words, chunk_syms, chunk_bitoff,
+                                            total_bits, workspace, status, st));
 }
 
 int32_t co3_convert_encode(const float *g, float *err, int64_t n, int32_t U, int64_t stride, const int64_t *seg_off,
                            int32_t nseg, int32_t *anchor, int32_t anchor_mode, float gamma, co3_fmt fmt, const void *codes,
-                           uint64_t *words, int64_t cap_words, int32_t chunk_syms, uint64_t *chunk_bitoff,
-                           uint64_t *total_bits, void *workspace, size_t ws_bytes, int32_t *status, void *stream)
+                           uint32_t *counts, uint64_t *words, int64_t cap_words, int32_t chunk_syms,
+                           uint64_t *chunk_bitoff, uint64_t *total_bits, void *workspace, size_t ws_bytes, int32_t *status,
+                           void *stream)
 {
     return convert_encode_common(g, err, n, U, stride, seg_off, nseg, anchor, anchor_mode, nullptr, gamma, fmt, codes,
-                                 nullptr, 0, words, cap_words, chunk_syms, chunk_bitoff, total_bits, workspace, ws_bytes,
-                                 status, stream);
+                                 nullptr, 0, counts, words, cap_words, chunk_syms, chunk_bitoff, total_bits, workspace,
+                                 ws_bytes, status, stream);
 }
 
 int32_t co3_convert_encode_layers(const float *g, float *err, int64_t n, int32_t U, int64_t stride,
@@ -254,8 +259,8 @@ int32_t co3_convert_encode_layers(const float *g, float *err, int64_t n, int32_t
 {
     if (!code_seg_off || code_nseg < 1) return CO3_EINVAL;
     return convert_encode_common(g, err, n, U, stride, seg_off, nseg, anchor, anchor_mode, scale, gamma, fmt, codes,
-                                 code_seg_off, code_nseg, words, cap_words, chunk_syms, chunk_bitoff, total_bits, workspace,
-                                 ws_bytes, status, stream);
+                                 code_seg_off, code_nseg, nullptr, words, cap_words, chunk_syms, chunk_bitoff, total_bits,
+                                 workspace, ws_bytes, status, stream);
 }
 
 int32_t co3_moments(const float *g, const float *err, int64_t n, int32_t U, int64_t stride, const int64_t *seg_off,

@@ -9,14 +9,15 @@
 #define HIST_SLOTS 1024                // LDS counters per wavefront
 
 // ------------------------------------------------------------------------------------------
-// initial values: anchors start at the lower clamp (so atomicMax applies it), counts at zero
+// initial values: anchors start at the lower clamp (so atomicMax applies it), counts at zero (or at one,
+// where the counts are to give every symbol a codeword)
 // ------------------------------------------------------------------------------------------
-__global__ void k_fill_i32(int32_t *a, int64_t na, int32_t va, uint32_t *b, int64_t nb)
+__global__ void k_fill_i32(int32_t *a, int64_t na, int32_t va, uint32_t *b, int64_t nb, uint32_t vb)
 {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     int64_t step = (int64_t)gridDim.x * blockDim.x;
     for (int64_t j = i; j < na; j += step) a[j] = va;
-    for (int64_t j = i; j < nb; j += step) b[j] = 0u;
+    for (int64_t j = i; j < nb; j += step) b[j] = vb;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -452,14 +453,14 @@ static int64_t per_block_for(int64_t n, int U, int64_t tile, int *blocks_out, in
     return tiles_per_block * tile;
 }
 
-hipError_t co3_launch_fill(int32_t *a, int64_t na, int32_t va, uint32_t *b, int64_t nb, hipStream_t st)
+hipError_t co3_launch_fill(int32_t *a, int64_t na, int32_t va, uint32_t *b, int64_t nb, hipStream_t st, uint32_t vb)
 {
     int64_t m = na > nb ? na : nb;
     if (m <= 0) return hipSuccess;
     int blocks = (int)((m + 255) / 256);
     if (blocks > 1024) blocks = 1024;
     Co3LaunchTimer tm(CO3_K_FILL, st);
-    hipLaunchKernelGGL(k_fill_i32, dim3(blocks), dim3(256), 0, st, a, na, va, b, nb);
+    hipLaunchKernelGGL(k_fill_i32, dim3(blocks), dim3(256), 0, st, a, na, va, b, nb, vb);
     return hipGetLastError();
 }
 

@@ -15,6 +15,7 @@
 #define FU_BLOCK 256
 #define FU_WAVES (FU_BLOCK / CO3_WAVE)
 #define FU_VEC 4
+#define FU_HIST_SLOTS 512                      // LDS counters per wavefront (optional symbol counts)
 #define FU_RUN (CO3_WAVE * FU_VEC)              // consecutive elements that one load of a wavefront covers
 #define FU_SUB (CO3_FUSED_UNIT / FU_RUN)        // runs per unit
 #define FU_TILE (FU_WAVES * CO3_FUSED_UNIT)     // elements of one block step: four units, one per wavefront
@@ -63,6 +64,8 @@ struct FusedUnit {
     const int64_t *code_seg_off;
     int ncodes;
     bool one_code;
+    uint32_t *hist;      // the wavefront's LDS counters (HIST), slot of symbol q: q * copies + mycopy
+    int copies, mycopy;
 };
 
 template <bool LAYERS>
@@ -80,7 +83,7 @@ __device__ __forceinline__ uint64_t fused_entry4(const FusedUnit &a, uint32_t q,
     return (int)q < a.K ? fcode_of(a.codes, cg)->enc[q] : 0ull;
 }
 
-template <bool WHOLE, bool PLAIN, bool LAYERS, bool SCALED>
+template <bool WHOLE, bool PLAIN, bool LAYERS, bool SCALED, bool HIST>
 __device__ __forceinline__ bool fused_convert_unit(const FusedUnit &a, uint64_t (&acc)[FU_SUB], uint32_t (&qpack)[FU_SUB],
                                                    uint32_t (&nb)[FU_SUB])
 {
@@ -132,6 +135,7 @@ __device__ __forceinline__ bool fused_convert_unit(const FusedUnit &a, uint64_t 
             co3_quantize(SCALED ? c * x : x, A - a.F + 1, A, a.E, a.M, a.codemax, q, v);
             if (SCALED) v = v / c;
             en[k] = x - v;
+            if (HIST && valid) atomicAdd(&a.hist[q * a.copies + a.mycopy], 1u);
             const uint64_t e = !valid ? 0ull : PLAIN ? a.enc_s[q] : fused_entry4<LAYERS>(a, q, idx, cg_first, cg_last);
             const uint32_t l = (uint32_t)(e & 63u);
             nocode |= valid && l == 0u;
@@ -155,7 +159,7 @@ __device__ __forceinline__ bool fused_convert_unit(const FusedUnit &a, uint64_t 
 // one contiguous KiB per wavefront.  The bit position of a lane's codewords inside the unit comes from
 // one scan over the lanes for all runs at once: the lane totals of two runs share a 32-bit word (a run
 // has at most 256 * 57 < 2^16 bits).
-template <bool LAYERS, bool SCALED>
+template <bool LAYERS, bool SCALED, bool HIST>
 __global__ __launch_bounds__(FU_BLOCK) void k_convert_stage(const float *__restrict__ g, float *__restrict__ err,
                                                              int64_t n, int64_t stride,
                                                              const int64_t *__restrict__ seg_off_g, int nseg,
@@ -163,6 +167,7 @@ __global__ __launch_bounds__(FU_BLOCK) void k_convert_stage(const float *__restr
                                                              const float *__restrict__ scale, float gamma, co3_fmt fmt,
                                                              const void *__restrict__ codes,
                                                              const int64_t *__restrict__ code_seg_off_g, int ncodes,
+                                                             uint32_t *__restrict__ counts,
                                                              uint64_t *__restrict__ slots, uint32_t *__restrict__ unit_bits,
                                                              uint32_t *__restrict__ chunk_local, int chunk_syms,
                                                              int64_t nchunks, int64_t nunits, int64_t per_block,
@@ -174,6 +179,13 @@ __global__ __launch_bounds__(FU_BLOCK) void k_convert_stage(const float *__restr
     __shared__ int64_t code_seg_cache[LAYERS ? CO3_SEG_CACHE : 1];
     __shared__ uint64_t enc_all[LAYERS ? FU_WAVES * 256 : 256];
     __shared__ unsigned long long stage_all[FU_WAVES][CO3_FUSED_SLOT_WORDS + 1];
+    // HIST: per-wavefront counters, `copies` interleaved replicas per symbol so that lanes that meet one
+    // popular symbol spread over banks (as in the two-pass conversion)
+    __shared__ uint32_t hist_all[HIST ? FU_WAVES * FU_HIST_SLOTS : 1];
+    if (HIST) {
+        for (int j = threadIdx.x; j < FU_WAVES * FU_HIST_SLOTS; j += FU_BLOCK) hist_all[j] = 0u;
+    }
+    const int copies = FU_HIST_SLOTS / K > 32 ? 32 : FU_HIST_SLOTS / K;
     const int64_t *seg_off = co3_cache_segs(seg_off_g, nseg, seg_cache);
     const int64_t *code_seg_off = LAYERS ? co3_cache_segs(code_seg_off_g, ncodes, code_seg_cache) : nullptr;
     // users and ranges in the reverse of the anchor pass's order: what that pass left in the last-level
@@ -228,10 +240,10 @@ __global__ __launch_bounds__(FU_BLOCK) void k_convert_stage(const float *__restr
         }
         const FusedUnit ua = {gu, eu, n, u0, lane, seg_off, nseg, anchor_u, scale_u, anchor_u[s_lo],
                                  SCALED ? scale_u[s_lo] : 1.0f, gamma, E, M, F, K, codemax, enc_s, codes, code_seg_off,
-                                 ncodes, one_code};
-        if (whole && s_lo == s_hi && one_code) nocode |= fused_convert_unit<true, true, LAYERS, SCALED>(ua, acc, qpack, nb);
-        else if (whole) nocode |= fused_convert_unit<true, false, LAYERS, SCALED>(ua, acc, qpack, nb);
-        else nocode |= fused_convert_unit<false, false, LAYERS, SCALED>(ua, acc, qpack, nb);
+                                 ncodes, one_code, hist_all + wave * FU_HIST_SLOTS, copies, lane & (copies - 1)};
+        if (whole && s_lo == s_hi && one_code) nocode |= fused_convert_unit<true, true, LAYERS, SCALED, HIST>(ua, acc, qpack, nb);
+        else if (whole) nocode |= fused_convert_unit<true, false, LAYERS, SCALED, HIST>(ua, acc, qpack, nb);
+        else nocode |= fused_convert_unit<false, false, LAYERS, SCALED, HIST>(ua, acc, qpack, nb);
         // positions: one scan per pair of runs
         uint32_t pos[FU_SUB], total = 0;
 #pragma unroll
@@ -279,6 +291,15 @@ __global__ __launch_bounds__(FU_BLOCK) void k_convert_stage(const float *__restr
         co3_wave_lds_sync();                                              // the window is reused by the next unit
     }
     if (nocode) co3_raise(status, CO3_ENOCODE);
+    if (HIST) {
+        __syncthreads();
+        for (int k = threadIdx.x; k < K; k += FU_BLOCK) {
+            uint32_t c = 0;
+            for (int w = 0; w < FU_WAVES; ++w)
+                for (int r = 0; r < copies; ++r) c += hist_all[w * FU_HIST_SLOTS + k * copies + r];
+            if (c) atomicAdd(&counts[(int64_t)u * K + k], c);
+        }
+    }
 }
 
 // ---- pass 2: offsets of the units within groups of 64, group sizes -----------------------------
@@ -423,9 +444,9 @@ size_t co3_fused_workspace_bytes_impl(int64_t n, int U, int chunk_syms) { return
 
 hipError_t co3_launch_convert_encode(const float *g, float *err, int64_t n, int U, int64_t stride, const int64_t *seg_off,
                                      int nseg, const int32_t *anchor, const float *scale, float gamma, co3_fmt fmt,
-                                     const void *codes, const int64_t *code_seg_off, int ncodes, uint64_t *words,
-                                     int64_t cap_words, int chunk_syms, uint64_t *chunk_bitoff, uint64_t *total_bits,
-                                     void *workspace, int32_t *status, hipStream_t st)
+                                     const void *codes, const int64_t *code_seg_off, int ncodes, uint32_t *counts,
+                                     uint64_t *words, int64_t cap_words, int chunk_syms, uint64_t *chunk_bitoff,
+                                     uint64_t *total_bits, void *workspace, int32_t *status, hipStream_t st)
 {
     const int64_t nunits = (n + CO3_FUSED_UNIT - 1) / CO3_FUSED_UNIT;
     const int64_t ngrp = (nunits + CO3_FUSED_GROUP - 1) / CO3_FUSED_GROUP;
@@ -444,14 +465,15 @@ hipError_t co3_launch_convert_encode(const float *g, float *err, int64_t n, int 
         const dim3 grid((unsigned)((n + per_block - 1) / per_block), U), block(FU_BLOCK);
         {
             Co3LaunchTimer tm(CO3_K_CONVERT, st);
-#define CO3_STAGE_LAUNCH(L_, S_)                                                                                        \
-    hipLaunchKernelGGL((k_convert_stage<L_, S_>), grid, block, 0, st, g, err, n, stride, seg_off, nseg, anchor, scale,   \
-                       gamma, fmt, codes, code_seg_off, ncodes, slots, unit_bits, chunk_local, chunk_syms, nchunks,     \
-                       nunits, per_block, status)
-            if (code_seg_off && scale) CO3_STAGE_LAUNCH(true, true);
-            else if (code_seg_off) CO3_STAGE_LAUNCH(true, false);
-            else if (scale) CO3_STAGE_LAUNCH(false, true);
-            else CO3_STAGE_LAUNCH(false, false);
+#define CO3_STAGE_LAUNCH(L_, S_, H_)                                                                                    \
+    hipLaunchKernelGGL((k_convert_stage<L_, S_, H_>), grid, block, 0, st, g, err, n, stride, seg_off, nseg, anchor,      \
+                       scale, gamma, fmt, codes, code_seg_off, ncodes, counts, slots, unit_bits, chunk_local,           \
+                       chunk_syms, nchunks, nunits, per_block, status)
+            if (code_seg_off && scale) CO3_STAGE_LAUNCH(true, true, false);
+            else if (code_seg_off) CO3_STAGE_LAUNCH(true, false, false);
+            else if (scale) CO3_STAGE_LAUNCH(false, true, false);
+            else if (counts) CO3_STAGE_LAUNCH(false, false, true);
+            else CO3_STAGE_LAUNCH(false, false, false);
 #undef CO3_STAGE_LAUNCH
         }
         {

@@ -20,7 +20,7 @@ struct Co3LaunchTimer {
     hipStream_t stream;
 };
 
-hipError_t co3_launch_fill(int32_t *a, int64_t na, int32_t va, uint32_t *b, int64_t nb, hipStream_t st);
+hipError_t co3_launch_fill(int32_t *a, int64_t na, int32_t va, uint32_t *b, int64_t nb, hipStream_t st, uint32_t vb = 0u);
 hipError_t co3_launch_absmax(const float *g, int64_t n, int U, int64_t stride, const int64_t *seg_off, int nseg,
                              int32_t *anchor, hipStream_t st);
 hipError_t co3_launch_convert(const float *g, float *err, uint8_t *sym, int64_t n, int U, int64_t stride,
@@ -39,9 +39,9 @@ hipError_t co3_launch_enc_scan(uint64_t *sizes, int64_t nsizes, int U, int64_t c
 size_t co3_fused_workspace_bytes_impl(int64_t n, int U, int chunk_syms);
 hipError_t co3_launch_convert_encode(const float *g, float *err, int64_t n, int U, int64_t stride, const int64_t *seg_off,
                                      int nseg, const int32_t *anchor, const float *scale, float gamma, co3_fmt fmt,
-                                     const void *codes, const int64_t *code_seg_off, int ncodes, uint64_t *words,
-                                     int64_t cap_words, int chunk_syms, uint64_t *chunk_bitoff, uint64_t *total_bits,
-                                     void *workspace, int32_t *status, hipStream_t st);
+                                     const void *codes, const int64_t *code_seg_off, int ncodes, uint32_t *counts,
+                                     uint64_t *words, int64_t cap_words, int chunk_syms, uint64_t *chunk_bitoff,
+                                     uint64_t *total_bits, void *workspace, int32_t *status, hipStream_t st);
 hipError_t co3_launch_decode(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff, int chunk_syms,
                              const void *codes, const int64_t *seg_off, int nseg, int K, int64_t n, int U,
                              uint8_t *sym_out, int64_t stride, int tiled, int32_t *status, hipStream_t st);

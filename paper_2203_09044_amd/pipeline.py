@@ -26,7 +26,7 @@ class Co3Pipeline:
     def __init__(self, U: int, n: int, fmt: Fmt, chunk_syms: int = 256, seg_off=None, gamma: float = 1.0,
                  cap_words: Optional[int] = None, device="cuda:0", fused_histogram: bool = True,
                  bias: str = "absmax", grid_anchor: Optional[int] = None, codes: str = "user", code_seg_off=None,
-                 statistics: bool = True, single_pass: bool = False):
+                 statistics: bool = True, single_pass: bool = False, lagged_codes: bool = False):
         if bias not in ("absmax", "moments"):
             raise ValueError("bias must be 'absmax' or 'moments'")
         if codes not in ("user", "layer"):
@@ -39,6 +39,12 @@ class Co3Pipeline:
         self.single_pass = single_pass
         if single_pass and codes == "user" and bias != "absmax":
             raise ValueError("single_pass with the bias rule needs codes='layer'")
+        # per-user empirical codes that follow the gradients one iteration behind: the one-pass user side also
+        # counts the symbols (+1 each), and the codes of the next iteration are built from those counts
+        self.lagged_codes = lagged_codes
+        if lagged_codes and not (single_pass and codes == "user"):
+            raise ValueError("lagged_codes needs single_pass and per-user codes")
+        self.have_codes = False
         self.bias = bias
         dev = torch.device(device)
         self.device = dev
@@ -109,7 +115,7 @@ class Co3Pipeline:
         else:
             B.convert_encode(g, self.err, self.n, self.anchor, anchor_mode, self.gamma, self.fmt, self.codes, self.words,
                              self.chunk_syms, self.chunk_bitoff, self.total_bits, self.fused_ws, self.status,
-                             seg_off=self.seg_off)
+                             seg_off=self.seg_off, counts=self.counts if self.lagged_codes else None)
 
     def build(self, weights: Optional[torch.Tensor] = None):
         """Per-user codes from the users' counts (or given weights [U][K]); per-tensor codes from the pooled
@@ -155,6 +161,15 @@ class Co3Pipeline:
     def step(self, g: torch.Tensor, weights: Optional[torch.Tensor] = None, rebuild: bool = True):
         """One whole iteration: users encode, the server decodes and averages.  ``rebuild=False`` keeps the
         codes of the previous call (fixed tables designed from a model)."""
+        if self.lagged_codes:
+            if not self.have_codes:          # first iteration: nothing is known yet, every symbol weighs the same
+                self.build(torch.ones((self.U, self.fmt.K), dtype=torch.int32, device=self.device)
+                           if weights is None else weights)
+                self.have_codes = True
+            self.convert_encode(g)
+            self.aggregate()                 # the server decodes with the codes this iteration was coded with
+            self.build()                     # ... and the counts of this iteration code the next one
+            return
         if self.single_pass and not rebuild:
             if self.bias == "moments":
                 self.fit_bias(g)

@@ -251,3 +251,44 @@ def test_degenerate_one_symbol_table_and_zero_gradient(co3):
     g[1, 12_345] = 1.0
     pipe.convert_encode(g)
     assert pipe.poll() == co3.binding.ENOCODE
+
+
+# ---- empirical codes one iteration behind: the one-pass user side also counts the symbols ----
+
+@pytest.mark.parametrize("E,M,n,C", [(3, 0, 70_001, 256), (4, 3, 5 * 4096 + 77, 64), (3, 1, 1023, 128)])
+def test_codes_from_the_previous_iterations_counts(co3, E, M, n, C):
+    """Iteration 1 is coded with the flat code (all weights one); from then on iteration t is coded with the
+    Huffman code of 1 + the counts of iteration t-1, which the one-pass call of iteration t-1 gathered.
+    Counts, code lengths, memory, streams and the average against the oracle, bit for bit."""
+    fmt, f = co3.Fmt(E, M), oracle.Fmt(E, M)
+    U = 3
+    pipe = co3.Co3Pipeline(U, n, fmt, chunk_syms=C, single_pass=True, lagged_codes=True,
+                           cap_words=2 * ((n * 57 + 127) // 128 + 1))
+    g = pipe.new_gradient_buffer()
+    errs = [np.zeros(n, np.float32) for _ in range(U)]
+    weights = [np.ones(fmt.K, np.uint32) for _ in range(U)]   # what the codes of the current iteration were built from
+    for t in range(1, 5):
+        gh = [inp.gennorm(inp.rng_for(96, u, t), n, [0.6, 1.0, 1.5][u], 1e-3 * (1 + 0.3 * t)) for u in range(U)]
+        g[:, :n] = torch.from_numpy(np.stack(gh)).cuda()
+        pipe.step(g)
+        assert pipe.poll() == 0
+        syms, anchors = [], []
+        for u in range(U):
+            A = oracle.anchor(gh[u], f)
+            s, errs[u] = oracle.convert_ef(gh[u], errs[u], A, 1.0, f)
+            cnt = oracle.histogram(s, f)
+            lens = oracle.huffman_lengths(weights[u])
+            words, off, total = oracle.encode(s, lens, oracle.canonical_codes(lens), C)
+            assert np.array_equal(pipe.anchor[u].cpu().numpy(), A), "anchor"
+            assert np.array_equal(pipe.err[u, :n].cpu().numpy().view(np.uint32), errs[u].view(np.uint32)), "memory"
+            assert int(pipe.total_bits[u].item()) == total, (t, "total bits")
+            assert np.array_equal(u64(pipe.chunk_bitoff[u]), off), "chunk offsets"
+            nw = (total + 63) // 64
+            assert np.array_equal(u64(pipe.words[u, :nw]), words[:nw]), "stream words"
+            assert np.array_equal(pipe.counts[u].cpu().numpy().view(np.uint32), cnt + 1), "counts + 1"
+            weights[u] = cnt + 1                          # ... code the next iteration
+            assert np.array_equal(pipe.codes[u, :fmt.K].cpu().numpy(), oracle.huffman_lengths(weights[u])), "next code"
+            syms.append(s)
+            anchors.append(A)
+        want = oracle.aggregate(np.stack(syms), np.stack(anchors), f)
+        assert np.array_equal(pipe.avg[:n].cpu().numpy().view(np.uint32), want.view(np.uint32)), "average"
