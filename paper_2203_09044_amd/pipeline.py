@@ -50,9 +50,9 @@ class Co3Pipeline:
         self.device = dev
         self.stride = _round_up(max(n, 1), 16)
         self.nchunks = (n + chunk_syms - 1) // chunk_syms
-        # a user's own empirical code never exceeds the fixed-length size; a shared or model code can
+        # a user's own empirical code never exceeds the fixed-length size; a shared, model or lagged code can
         if cap_words is None:
-            cap_words = B.cap_words_empirical(n, fmt) * (2 if codes == "layer" else 1)
+            cap_words = B.cap_words_empirical(n, fmt) * (2 if codes == "layer" or single_pass else 1)
         self.cap_words = _round_up(cap_words, 2)
         self.seg_off = None if seg_off is None else torch.as_tensor(seg_off, dtype=torch.int64).to(dev)
         self.nseg = 1 if seg_off is None else self.seg_off.numel() - 1

@@ -11,6 +11,8 @@ arithmetic of the codec happens here.
 one code per layer shared by the users and designed from the GenNorm law fitted to the layer's
 corrected gradients (no symbol statistics), refreshed every ``refresh`` iterations; between
 refreshes the user side runs in one pass (conversion and compression without a symbol array).
+``tables="lagged"``: per-user Huffman codes from the previous iteration's symbol counts, which the
+one-pass user side gathers on the way.
 """
 from __future__ import annotations
 
@@ -27,10 +29,12 @@ class Co3SGD:
     def __init__(self, model: torch.nn.Module, users: int, fmt: Fmt, lr: float, gamma: float = 1.0,
                  chunk_syms: int = 256, bias: str = "absmax", codes: str = "user", code_group_min: int = 16384,
                  tables: str = "empirical", refresh: int = 10):
-        if tables not in ("empirical", "model"):
-            raise ValueError("tables must be 'empirical' or 'model'")
+        if tables not in ("empirical", "model", "lagged"):
+            raise ValueError("tables must be 'empirical', 'model' or 'lagged'")
         if tables == "model" and (bias != "moments" or codes != "layer"):
             raise ValueError("model tables go with bias='moments' and codes='layer'")
+        if tables == "lagged" and (bias != "absmax" or codes != "user"):
+            raise ValueError("lagged tables go with bias='absmax' and codes='user'")
         self.tables, self.refresh, self.t = tables, max(1, refresh), 0
         self.model = model
         self.params = [p for p in model.parameters() if p.requires_grad]
@@ -64,7 +68,8 @@ class Co3SGD:
                 code_seg_off.append(code_seg_off[-1] + gsz)
         self.pipe = Co3Pipeline(users, self.n, fmt, chunk_syms=chunk_syms, seg_off=self.seg_off, gamma=gamma,
                                 device=dev, bias=bias, codes=codes, code_seg_off=code_seg_off,
-                                statistics=tables == "empirical", single_pass=tables == "model")
+                                statistics=tables != "model", single_pass=tables != "empirical",
+                                lagged_codes=tables == "lagged")
         self.g = self.pipe.new_gradient_buffer()
         if tables == "model":
             # the tensor that designs each group's table: the largest one of the group
