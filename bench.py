@@ -111,13 +111,14 @@ def main():
     ap.add_argument("--bias", default="absmax", choices=("absmax", "moments"),
                     help="absmax: integer anchor from max|g| (the headline configuration); moments: the paper's bias "
                          "rule (moment sums, GenNorm fit, multiplier) on the fixed grid of anchor 2^(E-1)")
-    ap.add_argument("--codes", default="user", choices=("user", "user-model", "user-lagged", "layer", "layer-model"),
+    ap.add_argument("--codes", default="user", choices=("user", "user-model", "user-lagged", "layer", "layer-model", "layer-lagged"),
                     help="user: one empirical code per client, rebuilt every step (the headline configuration); "
                          "layer: one code per tensor shared by the clients, rebuilt every step from the pooled "
                          "per-tensor counts; user-model: one fixed code per client designed once from the GenNorm law "
                          "of the workload (C4's model table; no histogram, no code build inside the step); "
                          "user-lagged: one empirical code per client built from the counts of the previous step, "
                          "gathered by the one-pass user side (conversion + compression in one pass every step); "
+                         "layer-lagged: the same for one code per tensor shared by the clients (pooled counts); "
                          "layer-model: one fixed code per tensor designed once from the GenNorm "
                          "law of the tensor (no histogram, no code build inside the step)")
     ap.add_argument("--single-pass", action="store_true",
@@ -183,14 +184,14 @@ def main():
         desc += ", bias rule from moments"
     fmt = Fmt(w.E, w.M)
     code_seg_off = None
-    if args.codes in ("layer", "layer-model") and w.sizes is not None:
+    if args.codes in ("layer", "layer-model", "layer-lagged") and w.sizes is not None:
         import co3_inputs as inp
         groups = inp.group_small_tensors(w.sizes)
         code_seg_off = inp.seg_offsets(groups)
         desc += f", {len(groups)} code groups (tensors under 16,384 elements share the code of the large tensor before them)"
     fixed_user_tables = args.codes == "user-model"
-    lagged = args.codes == "user-lagged"
-    if lagged and args.bias != "absmax":
+    lagged = args.codes in ("user-lagged", "layer-lagged")
+    if args.codes == "user-lagged" and args.bias != "absmax":
         raise SystemExit("--codes user-lagged goes with the integer anchor")
     if args.single_pass and args.codes not in ("user-model", "layer-model"):
         raise SystemExit("--single-pass needs --codes user-model or layer-model (the codes must be known before the step)")
@@ -204,7 +205,7 @@ def main():
     log(f"[bench] {desc}; generating {args.pool} device batches")
     batches = device_batches(w, betas, alpha, args.pool, pipe)
 
-    rebuild = args.codes in ("user", "layer", "user-lagged")      # user-lagged: the step builds the next step's codes
+    rebuild = args.codes in ("user", "layer", "user-lagged", "layer-lagged")   # lagged: the step builds the next step's codes
     if fixed_user_tables:
         # one table per client from the law the client's gradients are drawn from, on the grid of the client's
         # anchor of the first batch (every emit-able symbol has a codeword, so the table serves every step)
@@ -339,6 +340,7 @@ def main():
                    "table": {"user": "empirical per client, rebuilt every step",
                              "user-model": "fixed per client, designed from the GenNorm law of the workload",
                              "user-lagged": "empirical per client from the previous step's counts (+1), rebuilt every step",
+                             "layer-lagged": "empirical per tensor from the previous step's pooled counts (+1), rebuilt every step",
                              "layer": "empirical per tensor, pooled over the clients, rebuilt every step",
                              "layer-model": "fixed per tensor, designed from the GenNorm law of the workload"}[args.codes],
                    "gamma": args.gamma, "bias": args.bias, "codes": args.codes},

@@ -276,6 +276,8 @@ int32_t co3_ps_aggregate_layers(const uint64_t *words, int64_t cap_words, const 
  * co3_convert_ef followed by co3_encode_layers; scale [U][nseg] gives co3_convert_ef_scaled followed by
  * co3_encode_layers, and then the anchors are inputs (anchor_mode must be CO3_ANCHOR_GIVEN).  Model
  * codes per layer, the multiplier and one pass together are the scheme of Sec. III as the paper states it.
+ * counts: NULL, or [code_nseg][K] u32 out, overwritten: 1 + the occurrences of every symbol in the
+ * elements of a code, added up over the users (n * U < 2^32): the weights of the next iteration's codes.
  */
 size_t co3_convert_encode_workspace_bytes(int64_t n, int32_t U, int32_t chunk_syms);
 int32_t co3_convert_encode(const float *g, float *err, int64_t n, int32_t U, int64_t stride, const int64_t *seg_off,
@@ -286,9 +288,9 @@ int32_t co3_convert_encode(const float *g, float *err, int64_t n, int32_t U, int
 int32_t co3_convert_encode_layers(const float *g, float *err, int64_t n, int32_t U, int64_t stride,
                                   const int64_t *seg_off, int32_t nseg, int32_t *anchor, int32_t anchor_mode,
                                   const float *scale, float gamma, co3_fmt fmt, const void *codes,
-                                  const int64_t *code_seg_off, int32_t code_nseg, uint64_t *words, int64_t cap_words,
-                                  int32_t chunk_syms, uint64_t *chunk_bitoff, uint64_t *total_bits, void *workspace,
-                                  size_t ws_bytes, int32_t *status, void *stream);
+                                  const int64_t *code_seg_off, int32_t code_nseg, uint32_t *counts, uint64_t *words,
+                                  int64_t cap_words, int32_t chunk_syms, uint64_t *chunk_bitoff, uint64_t *total_bits,
+                                  void *workspace, size_t ws_bytes, int32_t *status, void *stream);
 
 /* ---- launch timing (diagnostic) ------------------------------------------ */
 

@@ -108,8 +108,8 @@ def _load():
     L.co3_convert_encode.restype = i32
     L.co3_convert_encode.argtypes = [p, p, i64, i32, i64, p, i32, p, i32, C.c_float, _Fmt, p, p, p, i64, i32, p, p, p, sz, p, p]
     L.co3_convert_encode_layers.restype = i32
-    L.co3_convert_encode_layers.argtypes = [p, p, i64, i32, i64, p, i32, p, i32, p, C.c_float, _Fmt, p, p, i32, p, i64, i32, p,
-                                            p, p, sz, p, p]
+    L.co3_convert_encode_layers.argtypes = [p, p, i64, i32, i64, p, i32, p, i32, p, C.c_float, _Fmt, p, p, i32, p, p, i64, i32,
+                                            p, p, p, sz, p, p]
     L.co3_model_weights.restype = i32
     L.co3_model_weights.argtypes = [i32, _Fmt, C.c_double, C.c_double, p]
     L.co3_timing_enable.restype = i32
@@ -205,15 +205,16 @@ def convert_encode(g, err, n, anchor, anchor_mode, gamma, fmt: Fmt, codes, words
 
 
 def convert_encode_layers(g, err, n, anchor, anchor_mode, gamma, fmt: Fmt, codes, code_seg_off, words, chunk_syms,
-                          chunk_bitoff, total_bits, workspace, status, seg_off=None, scale=None, stream=None):
-    """code_seg_off: boundaries of the codes; seg_off: boundaries of the anchors; scale: None or [U][nseg]."""
+                          chunk_bitoff, total_bits, workspace, status, seg_off=None, scale=None, counts=None, stream=None):
+    """code_seg_off: boundaries of the codes; seg_off: boundaries of the anchors; scale: None or [U][nseg];
+    counts: None or [ncodes][K] int32 out (1 + occurrences, users added up)."""
     U, stride = _batch(g)
     nseg = 1 if seg_off is None else seg_off.numel() - 1
     rc = _lib.co3_convert_encode_layers(_dp(g, torch.float32), _dp(err, torch.float32), n, U, stride,
                                         _dp(seg_off, torch.int64), nseg, _dp(anchor, torch.int32), anchor_mode,
                                         _dp(scale, torch.float32), C.c_float(gamma), fmt.c(), _dp(codes, torch.uint8),
                                         _dp(code_seg_off, torch.int64), code_seg_off.numel() - 1,
-                                        _dp(words, torch.int64), words.shape[-1], chunk_syms,
+                                        _dp(counts, torch.int32), _dp(words, torch.int64), words.shape[-1], chunk_syms,
                                         _dp(chunk_bitoff, torch.int64), _dp(total_bits, torch.int64), _dp(workspace),
                                         workspace.numel() * workspace.element_size(), _dp(status, torch.int32),
                                         _stream(stream))

@@ -226,8 +226,9 @@ static int32_t convert_encode_common(const float *g, float *err, int64_t n, int3
     const FmtC fc(fmt);
     const bool from_g = anchor_mode == CO3_ANCHOR_FROM_ABSMAX_G;
     if (from_g || counts) {          // anchors start at the lower clamp, the counts at one
+        const int64_t ncounts = (int64_t)(code_seg_off ? ncodes : U) * fc.K;      // per code group, else per user
         hipError_t e = co3_launch_fill(from_g ? anchor : nullptr, from_g ? (int64_t)U * nseg : 0, fc.F - 126, counts,
-                                       counts ? (int64_t)U * fc.K : 0, st, 1u);
+                                       counts ? ncounts : 0, st, 1u);
         if (e != hipSuccess) return CO3_EHIP;
     }
     if (from_g) {
@@ -253,13 +254,13 @@ int32_t co3_convert_encode(const float *g, float *err, int64_t n, int32_t U, int
 int32_t co3_convert_encode_layers(const float *g, float *err, int64_t n, int32_t U, int64_t stride,
                                   const int64_t *seg_off, int32_t nseg, int32_t *anchor, int32_t anchor_mode,
                                   const float *scale, float gamma, co3_fmt fmt, const void *codes,
-                                  const int64_t *code_seg_off, int32_t code_nseg, uint64_t *words, int64_t cap_words,
-                                  int32_t chunk_syms, uint64_t *chunk_bitoff, uint64_t *total_bits, void *workspace,
-                                  size_t ws_bytes, int32_t *status, void *stream)
+                                  const int64_t *code_seg_off, int32_t code_nseg, uint32_t *counts, uint64_t *words,
+                                  int64_t cap_words, int32_t chunk_syms, uint64_t *chunk_bitoff, uint64_t *total_bits,
+                                  void *workspace, size_t ws_bytes, int32_t *status, void *stream)
 {
     if (!code_seg_off || code_nseg < 1) return CO3_EINVAL;
     return convert_encode_common(g, err, n, U, stride, seg_off, nseg, anchor, anchor_mode, scale, gamma, fmt, codes,
-                                 code_seg_off, code_nseg, nullptr, words, cap_words, chunk_syms, chunk_bitoff, total_bits,
+                                 code_seg_off, code_nseg, counts, words, cap_words, chunk_syms, chunk_bitoff, total_bits,
                                  workspace, ws_bytes, status, stream);
 }
 

@@ -66,6 +66,7 @@ struct FusedUnit {
     bool one_code;
     uint32_t *hist;      // the wavefront's LDS counters (HIST), slot of symbol q: q * copies + mycopy
     int copies, mycopy;
+    uint32_t *counts;    // HIST with LAYERS: the pooled counters [ncodes][K] in global memory
 };
 
 template <bool LAYERS>
@@ -135,7 +136,14 @@ __device__ __forceinline__ bool fused_convert_unit(const FusedUnit &a, uint64_t 
             co3_quantize(SCALED ? c * x : x, A - a.F + 1, A, a.E, a.M, a.codemax, q, v);
             if (SCALED) v = v / c;
             en[k] = x - v;
-            if (HIST && valid) atomicAdd(&a.hist[q * a.copies + a.mycopy], 1u);
+            if (HIST && valid) {
+                if (!LAYERS || a.one_code) {
+                    atomicAdd(&a.hist[q * a.copies + a.mycopy], 1u);
+                } else {                 // a unit that straddles code groups: straight to the group's counters
+                    const int cg = cg_first == cg_last ? cg_first : co3_find_seg(a.code_seg_off, a.ncodes, idx);
+                    atomicAdd(&a.counts[(int64_t)cg * a.K + q], 1u);
+                }
+            }
             const uint64_t e = !valid ? 0ull : PLAIN ? a.enc_s[q] : fused_entry4<LAYERS>(a, q, idx, cg_first, cg_last);
             const uint32_t l = (uint32_t)(e & 63u);
             nocode |= valid && l == 0u;
@@ -152,6 +160,20 @@ __device__ __forceinline__ bool fused_convert_unit(const FusedUnit &a, uint64_t 
         }
     }
     return nocode;
+}
+
+// Adds a wavefront's LDS counters (all replicas of every symbol) to K global counters and clears them.
+__device__ __forceinline__ void flush_wave_counts(uint32_t *hist, int copies, int K, int lane, uint32_t *dst)
+{
+    for (int k = lane; k < K; k += CO3_WAVE) {
+        uint32_t c = 0;
+        for (int r = 0; r < copies; ++r) {
+            c += hist[k * copies + r];
+            hist[k * copies + r] = 0u;
+        }
+        if (c) atomicAdd(&dst[k], c);
+    }
+    co3_wave_lds_sync();
 }
 
 // ---- pass 1: conversion with error correction, codeword lookup, unit-local packing -----------
@@ -228,6 +250,8 @@ __global__ __launch_bounds__(FU_BLOCK) void k_convert_stage(const float *__restr
             one_code = c_lo == c_hi;
             if (c_lo != cur_code) {      // uniform
                 co3_wave_lds_sync();
+                if (HIST && cur_code >= 0) flush_wave_counts(hist_all + wave * FU_HIST_SLOTS, copies, K, lane,
+                                                             counts + (int64_t)cur_code * K);
                 const Co3Code *cd = fcode_of(codes, c_lo);
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
@@ -240,7 +264,7 @@ __global__ __launch_bounds__(FU_BLOCK) void k_convert_stage(const float *__restr
         }
         const FusedUnit ua = {gu, eu, n, u0, lane, seg_off, nseg, anchor_u, scale_u, anchor_u[s_lo],
                                  SCALED ? scale_u[s_lo] : 1.0f, gamma, E, M, F, K, codemax, enc_s, codes, code_seg_off,
-                                 ncodes, one_code, hist_all + wave * FU_HIST_SLOTS, copies, lane & (copies - 1)};
+                                 ncodes, one_code, hist_all + wave * FU_HIST_SLOTS, copies, lane & (copies - 1), counts};
         if (whole && s_lo == s_hi && one_code) nocode |= fused_convert_unit<true, true, LAYERS, SCALED, HIST>(ua, acc, qpack, nb);
         else if (whole) nocode |= fused_convert_unit<true, false, LAYERS, SCALED, HIST>(ua, acc, qpack, nb);
         else nocode |= fused_convert_unit<false, false, LAYERS, SCALED, HIST>(ua, acc, qpack, nb);
@@ -291,7 +315,27 @@ __global__ __launch_bounds__(FU_BLOCK) void k_convert_stage(const float *__restr
         co3_wave_lds_sync();                                              // the window is reused by the next unit
     }
     if (nocode) co3_raise(status, CO3_ENOCODE);
-    if (HIST) {
+    if (HIST && LAYERS) {
+        // the wavefronts of a block mostly end in the same code group: then one sum per block and symbol
+        // (the pooled counters take an atomic from every block of every user)
+        __shared__ int end_code[FU_WAVES];
+        if (lane == 0) end_code[wave] = cur_code;
+        __syncthreads();
+        bool same = true;
+        for (int w = 1; w < FU_WAVES; ++w) same &= end_code[w] == end_code[0];
+        if (same) {
+            if (end_code[0] >= 0) {
+                for (int k = threadIdx.x; k < K; k += FU_BLOCK) {
+                    uint32_t c = 0;
+                    for (int w = 0; w < FU_WAVES; ++w)
+                        for (int r = 0; r < copies; ++r) c += hist_all[w * FU_HIST_SLOTS + k * copies + r];
+                    if (c) atomicAdd(&counts[(int64_t)end_code[0] * K + k], c);
+                }
+            }
+        } else if (cur_code >= 0) {
+            flush_wave_counts(hist_all + wave * FU_HIST_SLOTS, copies, K, lane, counts + (int64_t)cur_code * K);
+        }
+    } else if (HIST) {
         __syncthreads();
         for (int k = threadIdx.x; k < K; k += FU_BLOCK) {
             uint32_t c = 0;
@@ -469,7 +513,9 @@ hipError_t co3_launch_convert_encode(const float *g, float *err, int64_t n, int 
     hipLaunchKernelGGL((k_convert_stage<L_, S_, H_>), grid, block, 0, st, g, err, n, stride, seg_off, nseg, anchor,      \
                        scale, gamma, fmt, codes, code_seg_off, ncodes, counts, slots, unit_bits, chunk_local,           \
                        chunk_syms, nchunks, nunits, per_block, status)
-            if (code_seg_off && scale) CO3_STAGE_LAUNCH(true, true, false);
+            if (code_seg_off && scale && counts) CO3_STAGE_LAUNCH(true, true, true);
+            else if (code_seg_off && scale) CO3_STAGE_LAUNCH(true, true, false);
+            else if (code_seg_off && counts) CO3_STAGE_LAUNCH(true, false, true);
             else if (code_seg_off) CO3_STAGE_LAUNCH(true, false, false);
             else if (scale) CO3_STAGE_LAUNCH(false, true, false);
             else if (counts) CO3_STAGE_LAUNCH(false, false, true);

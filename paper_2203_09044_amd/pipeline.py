@@ -42,8 +42,8 @@ class Co3Pipeline:
         # per-user empirical codes that follow the gradients one iteration behind: the one-pass user side also
         # counts the symbols (+1 each), and the codes of the next iteration are built from those counts
         self.lagged_codes = lagged_codes
-        if lagged_codes and not (single_pass and codes == "user"):
-            raise ValueError("lagged_codes needs single_pass and per-user codes")
+        if lagged_codes and not single_pass:
+            raise ValueError("lagged_codes needs single_pass")
         self.have_codes = False
         self.bias = bias
         dev = torch.device(device)
@@ -111,7 +111,8 @@ class Co3Pipeline:
             B.convert_encode_layers(g, self.err, self.n, self.anchor, B.ANCHOR_GIVEN if scaled else anchor_mode, self.gamma,
                                     self.fmt, self.codes, self.code_seg_off, self.words, self.chunk_syms,
                                     self.chunk_bitoff, self.total_bits, self.fused_ws, self.status, seg_off=self.seg_off,
-                                    scale=self.scale if scaled else None)
+                                    scale=self.scale if scaled else None,
+                                    counts=self.layer_counts if self.lagged_codes else None)
         else:
             B.convert_encode(g, self.err, self.n, self.anchor, anchor_mode, self.gamma, self.fmt, self.codes, self.words,
                              self.chunk_syms, self.chunk_bitoff, self.total_bits, self.fused_ws, self.status,
@@ -163,12 +164,16 @@ class Co3Pipeline:
         codes of the previous call (fixed tables designed from a model)."""
         if self.lagged_codes:
             if not self.have_codes:          # first iteration: nothing is known yet, every symbol weighs the same
-                self.build(torch.ones((self.U, self.fmt.K), dtype=torch.int32, device=self.device)
+                rows = self.ncodes if self.code_mode == "layer" else self.U
+                self.build(torch.ones((rows, self.fmt.K), dtype=torch.int32, device=self.device)
                            if weights is None else weights)
                 self.have_codes = True
+            if self.bias == "moments":
+                self.fit_bias(g)
             self.convert_encode(g)
             self.aggregate()                 # the server decodes with the codes this iteration was coded with
-            self.build()                     # ... and the counts of this iteration code the next one
+            # ... and the counts of this iteration code the next one
+            self.build(self.layer_counts if self.code_mode == "layer" else None)
             return
         if self.single_pass and not rebuild:
             if self.bias == "moments":

@@ -82,8 +82,8 @@ def test_host_argument_checks_launch_nothing():
                                      None, None) == B.EINVAL
     assert L.co3_convert_encode(None, None, 10, 1, 16, None, 1, None, 0, 1.0, ok, None, None, None, 2, 256, None, None, None,
                                 0, None, None) == B.EINVAL
-    assert L.co3_convert_encode_layers(None, None, 10, 1, 16, None, 1, None, 0, None, 1.0, ok, None, None, 1, None, 2, 256,
-                                       None, None, None, 0, None, None) == B.EINVAL
+    assert L.co3_convert_encode_layers(None, None, 10, 1, 16, None, 1, None, 0, None, 1.0, ok, None, None, 1, None, None, 2,
+                                       256, None, None, None, 0, None, None) == B.EINVAL
     assert B.convert_encode_workspace_bytes(0, 1, 256) > 0 and B.convert_encode_workspace_bytes(10, 1, 100) == 0
     # sizes at and beyond the interface's limit (n < 2^32), with plausible non-null pointers: rejected before
     # anything is launched

@@ -292,3 +292,64 @@ def test_codes_from_the_previous_iterations_counts(co3, E, M, n, C):
             anchors.append(A)
         want = oracle.aggregate(np.stack(syms), np.stack(anchors), f)
         assert np.array_equal(pipe.avg[:n].cpu().numpy().view(np.uint32), want.view(np.uint32)), "average"
+
+
+@pytest.mark.parametrize("shape,E,M,scaled", [("resnet_head", 4, 3, False), ("odd", 3, 1, True), ("tiny_many", 3, 0, False),
+                                              ("single", 1, 2, True)])
+def test_shared_codes_from_the_previous_iterations_pooled_counts(co3, shape, E, M, scaled):
+    """One code per group of tensors shared by the users, built from 1 + the counts of the previous iteration
+    added up over the users (the first iteration: the flat code), the user side in one pass."""
+    fmt, f = co3.Fmt(E, M), oracle.Fmt(E, M)
+    sizes = LAYER_SHAPES[shape]
+    U, C = 3, 128
+    seg = inp.seg_offsets(sizes)
+    nseg, n = len(sizes), int(seg[-1])
+    code_seg = inp.seg_offsets(inp.group_small_tensors(sizes, 3000))
+    ncodes = len(code_seg) - 1
+    pipe = co3.Co3Pipeline(U, n, fmt, chunk_syms=C, seg_off=seg, codes="layer", code_seg_off=code_seg, single_pass=True,
+                           lagged_codes=True, bias="moments" if scaled else "absmax",
+                           cap_words=2 * ((n * 57 + 127) // 128 + 1))
+    g = pipe.new_gradient_buffer()
+    alphas = 10.0 ** inp.rng_for(95).uniform(-4, -2, nseg)
+    errs = [np.zeros(n, np.float32) for _ in range(U)]
+    weights = np.ones((ncodes, fmt.K), np.uint32)
+    for t in range(1, 4):
+        gh = [np.concatenate([inp.gennorm(inp.rng_for(95, u, t, k), m, 0.9, a * (1 + 0.2 * t))
+                              for k, (m, a) in enumerate(zip(sizes, alphas))]).astype(np.float32) for u in range(U)]
+        g[:, :n] = torch.from_numpy(np.stack(gh)).cuda()
+        scale = None
+        if scaled:
+            # the oracle's multipliers on both sides: the step is taken apart as Co3Pipeline.step does it
+            scale = np.stack([oracle.bias_scales(gh[u], errs[u], 1.0, seg) for u in range(U)])
+            if not pipe.have_codes:
+                pipe.build(torch.ones((ncodes, fmt.K), dtype=torch.int32, device="cuda"))
+                pipe.have_codes = True
+            pipe.scale.copy_(torch.from_numpy(scale).cuda())
+            pipe.convert_encode(g)
+            pipe.aggregate()
+            pipe.build(pipe.layer_counts)
+        else:
+            pipe.step(g)
+        assert pipe.poll() == 0
+        lens = np.stack([oracle.huffman_lengths(weights[k]) for k in range(ncodes)])
+        cods = np.stack([oracle.canonical_codes(lens[k]) for k in range(ncodes)])
+        pooled = np.zeros((ncodes, fmt.K), np.int64)
+        syms, anchors = [], []
+        for u in range(U):
+            A = pipe.anchor[u].cpu().numpy() if scaled else oracle.anchor(gh[u], f, seg)
+            s, errs[u] = oracle.convert_ef(gh[u], errs[u], A, 1.0, f, seg, scale=None if scale is None else scale[u])
+            words, off, total = oracle.encode_layers(s, lens, cods, code_seg, C)
+            pooled += oracle.histogram_layers(s, f, code_seg)
+            assert np.array_equal(pipe.err[u, :n].cpu().numpy().view(np.uint32), errs[u].view(np.uint32)), "memory"
+            assert int(pipe.total_bits[u].item()) == total, (t, "total bits")
+            assert np.array_equal(u64(pipe.chunk_bitoff[u]), off), "chunk offsets"
+            nw = (total + 63) // 64
+            assert np.array_equal(u64(pipe.words[u, :nw]), words[:nw]), "stream words"
+            syms.append(s)
+            anchors.append(A)
+        assert np.array_equal(pipe.layer_counts.cpu().numpy().view(np.uint32).astype(np.int64), pooled + 1), "pooled counts + 1"
+        weights = (pooled + 1).astype(np.uint32)
+        assert np.array_equal(pipe.codes[:, :fmt.K].cpu().numpy(),
+                              np.stack([oracle.huffman_lengths(weights[k]) for k in range(ncodes)])), "next codes"
+        want = oracle.aggregate(np.stack(syms), np.stack(anchors), f, seg, scale=scale)
+        assert np.array_equal(pipe.avg[:n].cpu().numpy().view(np.uint32), want.view(np.uint32)), "average"
