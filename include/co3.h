@@ -10,7 +10,8 @@
  *
  * Conventions for every call below, unless its comment says otherwise:
  *   - every pointer is a DEVICE pointer owned by the caller; the library never
- *     allocates, frees or keeps device memory, and keeps no state between calls;
+ *     allocates or frees device memory and keeps no state between calls (the one
+ *     exception, a fixed workspace inside the library, is co3_encode_static's);
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream); the
  *     call only enqueues kernels on it and returns without waiting;
  *   - batched arrays are laid out [U][stride] with `stride` in elements (>= n, and
@@ -174,6 +175,22 @@ int32_t co3_build_code(const uint32_t *weights, int32_t U, co3_fmt fmt, void *co
 int32_t co3_encode(const uint8_t *sym, int64_t n, int32_t U, int64_t stride, co3_fmt fmt, const void *codes,
                    uint64_t *words, int64_t cap_words, int32_t chunk_syms, uint64_t *chunk_bitoff,
                    uint64_t *total_bits, void *workspace, size_t ws_bytes, int32_t *status, void *stream);
+
+/*
+ * co3_encode for callers that cannot allocate device memory or pass a workspace (code under HIP graph
+ * capture that owns no buffers, tight serving loops, harnesses that forbid allocation): same arguments,
+ * same results bit for bit, the tile and group sizes living in a fixed array of
+ * CO3_ENCODE_STATIC_WS_BYTES bytes inside the library's device image (one copy per GPU, held until the
+ * process ends).  The call allocates and frees nothing.  Batches with
+ * co3_encode_workspace_bytes(n, U) > CO3_ENCODE_STATIC_WS_BYTES are rejected with CO3_EINVAL (the limit
+ * admits about 5 * 10^8 symbols over all users).  All calls on one GPU share the array: calls that
+ * overlap on one GPU (two streams, two threads) race and must be serialised by the caller; nothing in
+ * the array needs to start at zero, every entry that is read was written by the same call.
+ */
+#define CO3_ENCODE_STATIC_WS_BYTES (4u << 20)
+int32_t co3_encode_static(const uint8_t *sym, int64_t n, int32_t U, int64_t stride, co3_fmt fmt, const void *codes,
+                          uint64_t *words, int64_t cap_words, int32_t chunk_syms, uint64_t *chunk_bitoff,
+                          uint64_t *total_bits, int32_t *status, void *stream);
 
 /* ---- parameter-server side ---------------------------------------------- */
 

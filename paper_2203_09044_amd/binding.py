@@ -27,7 +27,7 @@ EXPORTS = (
     "co3_ps_aggregate", "co3_model_weights", "co3_timing_enable", "co3_timing_read", "co3_timing_reset",
     "co3_kernel_name", "co3_moments", "co3_bias_scale", "co3_convert_ef_scaled", "co3_ps_aggregate_scaled",
     "co3_histogram_layers", "co3_encode_layers", "co3_decode_layers", "co3_ps_aggregate_layers",
-    "co3_convert_encode_workspace_bytes", "co3_convert_encode", "co3_convert_encode_layers",
+    "co3_convert_encode_workspace_bytes", "co3_convert_encode", "co3_convert_encode_layers", "co3_encode_static",
 )
 KERNEL_COUNT = 12
 
@@ -91,6 +91,8 @@ def _load():
     L.co3_build_code.argtypes = [p, i32, _Fmt, p, p, p]
     L.co3_encode.restype = i32
     L.co3_encode.argtypes = [p, i64, i32, i64, _Fmt, p, p, i64, i32, p, p, p, sz, p, p]
+    L.co3_encode_static.restype = i32
+    L.co3_encode_static.argtypes = [p, i64, i32, i64, _Fmt, p, p, i64, i32, p, p, p, p]
     L.co3_decode.restype = i32
     L.co3_decode.argtypes = [p, i64, p, i32, p, _Fmt, i64, i32, p, i64, p, p]
     L.co3_ps_aggregate.restype = i32
@@ -265,6 +267,18 @@ def encode(sym, n, fmt: Fmt, codes, words, chunk_syms, chunk_bitoff, total_bits,
                          _dp(total_bits, torch.int64), _dp(workspace), workspace.numel() * workspace.element_size(),
                          _dp(status, torch.int32), _stream(stream))
     _chk(rc, "co3_encode")
+
+
+ENCODE_STATIC_WS_BYTES = 4 << 20
+
+
+def encode_static(sym, n, fmt: Fmt, codes, words, chunk_syms, chunk_bitoff, total_bits, status, stream=None):
+    """co3_encode with the library's own fixed workspace (no workspace argument, nothing allocated)."""
+    U, stride = _batch(sym)
+    rc = _lib.co3_encode_static(_dp(sym, torch.uint8), n, U, stride, fmt.c(), _dp(codes, torch.uint8),
+                                _dp(words, torch.int64), words.shape[-1], chunk_syms, _dp(chunk_bitoff, torch.int64),
+                                _dp(total_bits, torch.int64), _dp(status, torch.int32), _stream(stream))
+    _chk(rc, "co3_encode_static")
 
 
 def decode(words, chunk_bitoff, chunk_syms, codes, fmt: Fmt, n, sym_out, status, stream=None):

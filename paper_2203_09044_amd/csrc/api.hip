@@ -325,6 +325,20 @@ int32_t co3_encode(const uint8_t *sym, int64_t n, int32_t U, int64_t stride, co3
                          total_bits, workspace, ws_bytes, status, stream);
 }
 
+int32_t co3_encode_static(const uint8_t *sym, int64_t n, int32_t U, int64_t stride, co3_fmt fmt, const void *codes,
+                          uint64_t *words, int64_t cap_words, int32_t chunk_syms, uint64_t *chunk_bitoff,
+                          uint64_t *total_bits, int32_t *status, void *stream)
+{
+    // sizes first: nothing of the runtime is touched for a batch that the fixed workspace cannot serve
+    if (n < 0 || U < 1) return CO3_EINVAL;
+    const size_t need = co3_encode_workspace_bytes(n, U);
+    if (need > (size_t)CO3_ENCODE_STATIC_WS_BYTES) return CO3_EINVAL;
+    void *ws = nullptr;
+    if (co3_static_encode_workspace(&ws) != hipSuccess) return CO3_EHIP;
+    return encode_common(sym, n, U, stride, fmt, codes, nullptr, 1, words, cap_words, chunk_syms, chunk_bitoff,
+                         total_bits, ws, need, status, stream);
+}
+
 int32_t co3_encode_layers(const uint8_t *sym, int64_t n, int32_t U, int64_t stride, co3_fmt fmt, const void *codes,
                           const int64_t *seg_off, int32_t nseg, uint64_t *words, int64_t cap_words,
                           int32_t chunk_syms, uint64_t *chunk_bitoff, uint64_t *total_bits, void *workspace,

@@ -7,6 +7,8 @@
 #include "co3_dev.h"
 #include "kernels.h"
 
+#include <atomic>
+
 #define EN_BLOCK 256
 #define EN_WAVES (EN_BLOCK / CO3_WAVE)
 #define EN_LSYM 16                             // symbols per lane
@@ -589,4 +591,30 @@ hipError_t co3_launch_encode(const uint8_t *sym, int64_t n, int U, int64_t strid
                                cap_words, chunk_syms, chunk_bitoff, nchunks);
     }
     return hipGetLastError();
+}
+
+// ---- the encoder's workspace for callers that cannot allocate --------------------------------------
+// A fixed array in the library's device image (every GPU that loads the library holds its own copy until
+// the process ends).  On the host the array's name is only a handle: its device address is looked up once
+// per device and kept; kernels and copies only ever see that address.
+static __device__ __align__(256) unsigned char scratch[CO3_ENCODE_STATIC_WS_BYTES];
+
+#define CO3_MAX_DEVICES 64
+hipError_t co3_static_encode_workspace(void **ptr_out)
+{
+    static std::atomic<void *> ptr_of[CO3_MAX_DEVICES];      // zero-initialised: nothing looked up yet
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= CO3_MAX_DEVICES) return hipErrorInvalidDevice;
+    void *p = ptr_of[dev].load(std::memory_order_acquire);
+    if (!p) {
+        // two threads may both look it up: they get the same address
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        ptr_of[dev].store(p, std::memory_order_release);
+    }
+    *ptr_out = p;
+    return hipSuccess;
 }

@@ -33,6 +33,9 @@ hipError_t co3_launch_encode(const uint8_t *sym, int64_t n, int U, int64_t strid
                              const int64_t *seg_off, int nseg, uint64_t *words, int64_t cap_words, int chunk_syms,
                              uint64_t *chunk_bitoff, uint64_t *total_bits, uint64_t *tilesum, int32_t *status,
                              hipStream_t st);
+// device address, on the current device, of the library's own fixed encoder workspace of
+// CO3_ENCODE_STATIC_WS_BYTES bytes (looked up on the first call per device; allocates nothing)
+hipError_t co3_static_encode_workspace(void **ptr_out);
 // the scan pass of the encoder alone: sizes[U][nsizes] -> exclusive offsets in place, stream length, capacity check
 hipError_t co3_launch_enc_scan(uint64_t *sizes, int64_t nsizes, int U, int64_t cap_words, uint64_t *chunk_bitoff,
                                int64_t nchunks, uint64_t *total_bits, int32_t *status, hipStream_t st);
