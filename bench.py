@@ -132,6 +132,8 @@ def main():
     ap.add_argument("--sweep-c5", action="store_true",
                     help="run the 12 points of C5 (4 formats x 3 shapes) one after the other, each in a child process, "
                          "and print one line with elements/s and bits/element per point")
+    ap.add_argument("--one-call", action="store_true",
+                    help="the user's steps through co3_user_encode (resident grid: every gradient read once)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--breakdown", action="store_true", help="extra untimed pass timing every kernel (stderr)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -201,6 +203,7 @@ def main():
                        bias=args.bias, gamma=args.gamma, codes="user" if args.codes.startswith("user") else "layer",
                        code_seg_off=code_seg_off, statistics=not fixed_user_tables,
                        single_pass=args.single_pass or lagged, lagged_codes=lagged,
+                       one_call=args.one_call, keep_symbols=not args.one_call,
                        cap_words=2 * B.cap_words_empirical(w.n, fmt) if fixed_user_tables or lagged else None)
     log(f"[bench] {desc}; generating {args.pool} device batches")
     batches = device_batches(w, betas, alpha, args.pool, pipe)

@@ -61,6 +61,7 @@ typedef struct {
 #define CO3_ENOCODE (-3)    /* a symbol to encode has no codeword (possible with model tables) */
 #define CO3_EBADSTREAM (-4) /* decoder: a chunk did not end where the index says, or an invalid prefix */
 #define CO3_EHIP (-5)       /* a HIP runtime call failed */
+#define CO3_ETIMEOUT (-6)   /* a bounded wait inside a kernel ran out (co3_user_encode); results unspecified */
 
 #define CO3_ANCHOR_GIVEN 0         /* anchor[] is an input */
 #define CO3_ANCHOR_FROM_ABSMAX_G 1 /* anchor[] is an output: binade of max|g| per (user, segment) */
@@ -309,6 +310,49 @@ int32_t co3_convert_encode_layers(const float *g, float *err, int64_t n, int32_t
                                   int64_t cap_words, int32_t chunk_syms, uint64_t *chunk_bitoff, uint64_t *total_bits,
                                   void *workspace, size_t ws_bytes, int32_t *status, void *stream);
 
+/* ---- the user's steps of Algorithm 1 in one call ------------------------------ */
+
+/*
+ * Conversion with error correction, memory update, symbol statistics, Huffman code and compression
+ * (Algorithm 1, every step of a user between the local gradient and the uplink; Sec. III (i)-(iii)) for
+ * all users, with the anchor from max|g| and one empirical code per user: the results of
+ *     co3_convert_ef(..., CO3_ANCHOR_FROM_ABSMAX_G, ..., counts) -> co3_build_code(counts) -> co3_encode
+ * bit for bit -- err, anchor, counts, codes, words, chunk_bitoff, total_bits (and sym, if asked for).
+ * What the one call adds is that it may keep data on the chip between the steps: where one anchor per
+ * user is asked for (nseg = 1) and a user's gradient fits the register files of the device (n up to
+ * 45,056 elements per compute unit: 11.5 M on 256 units), a single resident grid reads every gradient
+ * once, taking the largest magnitude and converting from registers, the workgroups exchanging their
+ * maxima through one word each in the workspace; other batches run the separate kernels of the three
+ * calls.
+ *
+ *   arguments  as in co3_convert_ef (g, err, n, U, stride, seg_off, nseg, anchor [out], gamma, fmt,
+ *              counts [out, required]), co3_build_code (codes [out]) and co3_encode (words, cap_words,
+ *              chunk_syms, chunk_bitoff, total_bits, status)
+ *   sym        [U][stride] u8 out, or NULL when the caller has no use for the symbols (the workspace
+ *              then holds them where the path needs them)
+ *   workspace  co3_user_encode_workspace_bytes(n, U, stride, sym != NULL) bytes, 256-byte aligned,
+ *              contents unspecified
+ *   errors     as the three calls; CO3_ETIMEOUT through status when a wait of the resident grid ran
+ *              out (every such wait is bounded, see co3_set_exchange_spin_limit); the outputs are
+ *              then unspecified
+ * The resident grid assumes that its workgroups (one per compute unit at most) can all be on the device
+ * at once.  Kernels of other streams that share the device only delay that; they cannot prevent it.
+ */
+size_t co3_user_encode_workspace_bytes(int64_t n, int32_t U, int64_t stride, int32_t caller_has_sym);
+int32_t co3_user_encode(const float *g, float *err, int64_t n, int32_t U, int64_t stride, const int64_t *seg_off,
+                        int32_t nseg, int32_t *anchor, float gamma, co3_fmt fmt, uint32_t *counts, void *codes,
+                        uint64_t *words, int64_t cap_words, int32_t chunk_syms, uint64_t *chunk_bitoff,
+                        uint64_t *total_bits, uint8_t *sym, void *workspace, size_t ws_bytes, int32_t *status,
+                        void *stream);
+
+/*
+ * Bound on the number of polls of one wait inside the resident grid of co3_user_encode (process-wide;
+ * default 2^18, each poll takes on the order of a microsecond; a negative value restores the default).
+ * A wait that runs out raises CO3_ETIMEOUT and the kernel goes on to its end.  With 0 no wait ever
+ * polls, so every wait runs out at once: how a test forces that path from the host.
+ */
+void co3_set_exchange_spin_limit(int64_t polls);
+
 /* ---- launch timing (diagnostic) ------------------------------------------ */
 
 /*
@@ -316,14 +360,14 @@ int32_t co3_convert_encode_layers(const float *g, float *err, int64_t n, int32_t
  * that must report one kernel's average duration.  Process-global and not thread-safe: the
  * only state the library keeps, and only while enabled.  kernel ids: 0 k_fill_i32, 1 k_absmax,
  * 2 k_convert_ef, 3 k_histogram, 4 k_build_code, 5 k_enc_sizes, 6 k_enc_scan, 7 k_enc_pack,
- * 8 k_decode, 9 k_ps_sum, 10 k_moments, 11 k_bias_scale (co3_kernel_name returns these names, ""
- * for other ids).
+ * 8 k_decode, 9 k_ps_sum, 10 k_moments, 11 k_bias_scale, 12 k_coop_convert (co3_kernel_name returns
+ * these names, "" for other ids).
  *   co3_timing_enable(mask): bracket every later launch of kernel k with events iff bit k is set.
  *   co3_timing_read(k, &ms, &count): waits for the recorded events, then returns the summed
  *       duration and launch count of kernel k since the last reset.
  *   co3_timing_reset(): waits likewise and clears all sums.
  */
-#define CO3_KERNEL_COUNT 12
+#define CO3_KERNEL_COUNT 13
 int32_t co3_timing_enable(uint32_t kernel_mask);
 int32_t co3_timing_read(int32_t kernel, double *total_ms, int64_t *launches);
 int32_t co3_timing_reset(void);

@@ -16,7 +16,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libco3.so")
 
-OK, EINVAL, ECAP, ENOCODE, EBADSTREAM, EHIP = 0, -1, -2, -3, -4, -5
+OK, EINVAL, ECAP, ENOCODE, EBADSTREAM, EHIP, ETIMEOUT = 0, -1, -2, -3, -4, -5, -6
 ANCHOR_GIVEN, ANCHOR_FROM_ABSMAX_G = 0, 1
 CODE_BYTES = 12288
 PACK_SYMS = 1024
@@ -28,8 +28,9 @@ EXPORTS = (
     "co3_kernel_name", "co3_moments", "co3_bias_scale", "co3_convert_ef_scaled", "co3_ps_aggregate_scaled",
     "co3_histogram_layers", "co3_encode_layers", "co3_decode_layers", "co3_ps_aggregate_layers",
     "co3_convert_encode_workspace_bytes", "co3_convert_encode", "co3_convert_encode_layers", "co3_encode_static",
+    "co3_user_encode_workspace_bytes", "co3_user_encode", "co3_set_exchange_spin_limit",
 )
-KERNEL_COUNT = 12
+KERNEL_COUNT = 13
 
 
 class _Fmt(C.Structure):
@@ -93,6 +94,12 @@ def _load():
     L.co3_encode.argtypes = [p, i64, i32, i64, _Fmt, p, p, i64, i32, p, p, p, sz, p, p]
     L.co3_encode_static.restype = i32
     L.co3_encode_static.argtypes = [p, i64, i32, i64, _Fmt, p, p, i64, i32, p, p, p, p]
+    L.co3_user_encode_workspace_bytes.restype = sz
+    L.co3_user_encode_workspace_bytes.argtypes = [i64, i32, i64, i32]
+    L.co3_user_encode.restype = i32
+    L.co3_user_encode.argtypes = [p, p, i64, i32, i64, p, i32, p, C.c_float, _Fmt, p, p, p, i64, i32, p, p, p, p, sz, p, p]
+    L.co3_set_exchange_spin_limit.restype = None
+    L.co3_set_exchange_spin_limit.argtypes = [C.c_int64]
     L.co3_decode.restype = i32
     L.co3_decode.argtypes = [p, i64, p, i32, p, _Fmt, i64, i32, p, i64, p, p]
     L.co3_ps_aggregate.restype = i32
@@ -270,6 +277,29 @@ def encode(sym, n, fmt: Fmt, codes, words, chunk_syms, chunk_bitoff, total_bits,
 
 
 ENCODE_STATIC_WS_BYTES = 4 << 20
+
+
+def user_encode_workspace_bytes(n: int, U: int, stride: int, caller_has_sym: bool) -> int:
+    return _lib.co3_user_encode_workspace_bytes(n, U, stride, int(bool(caller_has_sym)))
+
+
+def user_encode(g, err, n, anchor, gamma, fmt: Fmt, counts, codes, words, chunk_syms, chunk_bitoff, total_bits, workspace,
+                status, sym=None, seg_off=None, stream=None):
+    """The user's steps of one iteration in one call (co3_convert_ef with the anchor from max|g| and counts,
+    co3_build_code, co3_encode); sym: None, or the [U][stride] uint8 array that receives the symbols."""
+    U, stride = _batch(g)
+    nseg = 1 if seg_off is None else seg_off.numel() - 1
+    rc = _lib.co3_user_encode(_dp(g, torch.float32), _dp(err, torch.float32), n, U, stride, _dp(seg_off, torch.int64),
+                              nseg, _dp(anchor, torch.int32), C.c_float(gamma), fmt.c(), _dp(counts, torch.int32),
+                              _dp(codes, torch.uint8), _dp(words, torch.int64), words.shape[-1], chunk_syms,
+                              _dp(chunk_bitoff, torch.int64), _dp(total_bits, torch.int64), _dp(sym, torch.uint8),
+                              _dp(workspace), workspace.numel() * workspace.element_size(), _dp(status, torch.int32),
+                              _stream(stream))
+    _chk(rc, "co3_user_encode")
+
+
+def set_exchange_spin_limit(polls: int):
+    _lib.co3_set_exchange_spin_limit(polls)
 
 
 def encode_static(sym, n, fmt: Fmt, codes, words, chunk_syms, chunk_bitoff, total_bits, status, stream=None):

@@ -4,9 +4,28 @@
 #include "co3_dev.h"
 #include "kernels.h"
 
+#include <atomic>
 #include <vector>
 
 namespace {
+
+// ---- compute units of each device, looked up once -------------------------------------------
+int device_cus()
+{
+    static std::atomic<int> cus_of[64];
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+    int c = cus_of[dev].load(std::memory_order_relaxed);
+    if (c == 0) {
+        if (hipDeviceGetAttribute(&c, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || c < 1) return 0;
+        cus_of[dev].store(c, std::memory_order_relaxed);
+    }
+    return c;
+}
+
+std::atomic<uint32_t> g_spin_limit{1u << 18};
+
+size_t round_up_256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // ---- optional launch timing (diagnostic, process-global, not thread-safe) ------------------
 struct TimedLaunch {
@@ -112,7 +131,7 @@ const char *co3_kernel_name(int32_t kernel)
 {
     static const char *names[CO3_K_COUNT] = {"k_fill_i32", "k_absmax",    "k_convert_ef", "k_histogram", "k_build_code",
                                              "k_enc_sizes", "k_enc_scan", "k_enc_pack",   "k_decode",    "k_ps_sum",
-                                             "k_moments",  "k_bias_scale"};
+                                             "k_moments",  "k_bias_scale", "k_coop_convert"};
     return (kernel >= 0 && kernel < CO3_K_COUNT) ? names[kernel] : "";
 }
 
@@ -125,6 +144,7 @@ const char *co3_strerror(int32_t status)
     case CO3_ENOCODE: return "symbol without a codeword";
     case CO3_EBADSTREAM: return "inconsistent stream";
     case CO3_EHIP: return "HIP runtime error";
+    case CO3_ETIMEOUT: return "bounded wait inside a kernel ran out";
     default: return "unknown status";
     }
 }
@@ -262,6 +282,78 @@ int32_t co3_convert_encode_layers(const float *g, float *err, int64_t n, int32_t
     return convert_encode_common(g, err, n, U, stride, seg_off, nseg, anchor, anchor_mode, scale, gamma, fmt, codes,
                                  code_seg_off, code_nseg, counts, words, cap_words, chunk_syms, chunk_bitoff, total_bits,
                                  workspace, ws_bytes, status, stream);
+}
+
+void co3_set_exchange_spin_limit(int64_t polls)
+{
+    g_spin_limit.store(polls < 0 ? (1u << 18) : polls > 0xffffffffll ? 0xffffffffu : (uint32_t)polls);
+}
+
+// layout of the workspace of co3_user_encode: exchange words [U][compute units] u32, partial count tables
+// [CO3_COOP_COUNT_REPS][U][K] u32, the encoder's workspace, then (where the caller passes no symbol array)
+// the symbols [U][stride]
+size_t co3_user_encode_workspace_bytes(int64_t n, int32_t U, int64_t stride, int32_t caller_has_sym)
+{
+    if (n < 0 || U < 1 || stride < 0) return 0;
+    const int cus = device_cus();
+    size_t b = round_up_256((size_t)U * (size_t)(cus > 0 ? cus : 1024) * sizeof(uint32_t));
+    b += round_up_256((size_t)CO3_COOP_COUNT_REPS * (size_t)U * 256 * sizeof(uint32_t));
+    b += round_up_256(co3_encode_workspace_bytes(n, U));
+    if (!caller_has_sym) b += round_up_256((size_t)U * (size_t)(stride > n ? stride : n) + 16);
+    return b;
+}
+
+int32_t co3_user_encode(const float *g, float *err, int64_t n, int32_t U, int64_t stride, const int64_t *seg_off,
+                        int32_t nseg, int32_t *anchor, float gamma, co3_fmt fmt, uint32_t *counts, void *codes,
+                        uint64_t *words, int64_t cap_words, int32_t chunk_syms, uint64_t *chunk_bitoff,
+                        uint64_t *total_bits, uint8_t *sym, void *workspace, size_t ws_bytes, int32_t *status,
+                        void *stream)
+{
+    if (!fmt_ok(fmt) || !batch_ok(n, U, stride) || nseg < 1 || (seg_off == nullptr && nseg != 1)) return CO3_EINVAL;
+    if (!chunk_ok(chunk_syms) || cap_words < 0 || cap_words % 2 != 0) return CO3_EINVAL;
+    if (!g || !err || !anchor || !counts || !codes || !words || !chunk_bitoff || !total_bits || !workspace)
+        return CO3_EINVAL;
+    if (!aligned(g, 16) || !aligned(err, 16) || !aligned(words, 16) || !aligned(codes, 8) || !aligned(workspace, 256))
+        return CO3_EINVAL;
+    if (sym && !aligned(sym, 16)) return CO3_EINVAL;
+    if (ws_bytes < co3_user_encode_workspace_bytes(n, U, stride, sym != nullptr)) return CO3_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const FmtC fc(fmt);
+    const int cus = device_cus();
+    char *ws = static_cast<char *>(workspace);
+    uint32_t *slots = reinterpret_cast<uint32_t *>(ws);
+    const size_t slot_words = (size_t)U * (size_t)(cus > 0 ? cus : 1024);
+    ws += round_up_256(slot_words * sizeof(uint32_t));
+    uint32_t *counts_rep = reinterpret_cast<uint32_t *>(ws);
+    ws += round_up_256((size_t)CO3_COOP_COUNT_REPS * (size_t)U * 256 * sizeof(uint32_t));
+    void *enc_ws = ws;
+    const size_t enc_bytes = co3_encode_workspace_bytes(n, U);
+    ws += round_up_256(enc_bytes);
+    uint8_t *symbuf = sym ? sym : reinterpret_cast<uint8_t *>(ws);
+
+    int kpt = 0, grid = 0;
+    const bool coop = nseg == 1 && cus > 0 && co3_coop_fits(n, cus, &kpt, &grid);
+    if (coop) {
+        // exchange words and partial counters start at zero
+        hipError_t e = co3_launch_fill(reinterpret_cast<int32_t *>(slots), (int64_t)U * grid, 0, counts_rep,
+                                       (int64_t)CO3_COOP_COUNT_REPS * U * fc.K, st);
+        if (e != hipSuccess) return CO3_EHIP;
+        e = co3_launch_coop_convert(g, err, symbuf, n, U, stride, kpt, grid, anchor, gamma, fmt, counts_rep, slots,
+                                    g_spin_limit.load(), status, st);
+        if (e != hipSuccess) return CO3_EHIP;
+        // the code build adds the partial tables up and leaves the sums in counts
+        if (co3_launch_build_code(counts_rep, U, fc.K, codes, status, st, CO3_COOP_COUNT_REPS, counts) != hipSuccess)
+            return CO3_EHIP;
+        return hip_rc(co3_launch_encode(symbuf, n, U, stride, codes, fc.K, nullptr, 1, words, cap_words, chunk_syms,
+                                        chunk_bitoff, total_bits, static_cast<uint64_t *>(enc_ws), status, st));
+    } else {
+        const int32_t rc = convert_common(g, err, symbuf, n, U, stride, seg_off, nseg, anchor,
+                                          CO3_ANCHOR_FROM_ABSMAX_G, nullptr, gamma, fmt, counts, stream);
+        if (rc != CO3_OK) return rc;
+    }
+    if (co3_launch_build_code(counts, U, fc.K, codes, status, st) != hipSuccess) return CO3_EHIP;
+    return hip_rc(co3_launch_encode(symbuf, n, U, stride, codes, fc.K, nullptr, 1, words, cap_words, chunk_syms,
+                                    chunk_bitoff, total_bits, static_cast<uint64_t *>(enc_ws), status, st));
 }
 
 int32_t co3_moments(const float *g, const float *err, int64_t n, int32_t U, int64_t stride, const int64_t *seg_off,

@@ -5,8 +5,10 @@
 
 #define HB_BLOCK 256
 
+// nrep > 1: the weights of a user arrive as nrep partial tables [nrep][U][K] (partial counts of groups of
+// workgroups); they are added up here and the sums also go to sums_out [U][K].
 __global__ __launch_bounds__(HB_BLOCK) void k_build_code(const uint32_t *__restrict__ weights, int K, char *codes,
-                                                          int32_t *status)
+                                                          int32_t *status, int nrep, uint32_t *__restrict__ sums_out)
 {
     const int u = blockIdx.x;
     const int tid = threadIdx.x;
@@ -22,7 +24,12 @@ __global__ __launch_bounds__(HB_BLOCK) void k_build_code(const uint32_t *__restr
     __shared__ uint8_t sorted_s[HB_BLOCK];
     __shared__ uint32_t maxlen_s;
 
-    uint32_t wt = tid < K ? weights[(size_t)u * K + tid] : 0u;
+    uint32_t wt = 0u;
+    if (tid < K) {
+        const size_t rep_stride = (size_t)gridDim.x * K;
+        for (int r = 0; r < nrep; ++r) wt += weights[r * rep_stride + (size_t)u * K + tid];
+        if (sums_out) sums_out[(size_t)u * K + tid] = wt;
+    }
     const uint64_t mykey = wt ? (((uint64_t)wt << 8) | (uint64_t)tid) : ~0ull;
     key[tid] = mykey;
     len_s[tid] = 0;
@@ -190,11 +197,12 @@ __global__ __launch_bounds__(HB_BLOCK) void k_build_code(const uint32_t *__restr
     }
 }
 
-hipError_t co3_launch_build_code(const uint32_t *weights, int U, int K, void *codes, int32_t *status, hipStream_t st)
+hipError_t co3_launch_build_code(const uint32_t *weights, int U, int K, void *codes, int32_t *status, hipStream_t st,
+                                 int nrep, uint32_t *sums_out)
 {
     if (U <= 0) return hipSuccess;
     Co3LaunchTimer tm(CO3_K_BUILD, st);
     hipLaunchKernelGGL(k_build_code, dim3(U), dim3(HB_BLOCK), 0, st, weights, K, reinterpret_cast<char *>(codes),
-                       status);
+                       status, nrep, sums_out);
     return hipGetLastError();
 }

@@ -8,7 +8,7 @@
 // Kernel ids for the optional launch timing (co3_timing_* in the public header).
 enum Co3Kernel {
     CO3_K_FILL = 0, CO3_K_ABSMAX, CO3_K_CONVERT, CO3_K_HISTOGRAM, CO3_K_BUILD, CO3_K_ENC_SIZES, CO3_K_ENC_SCAN,
-    CO3_K_ENC_PACK, CO3_K_DECODE, CO3_K_PS_SUM, CO3_K_MOMENTS, CO3_K_BIAS_SCALE, CO3_K_COUNT
+    CO3_K_ENC_PACK, CO3_K_DECODE, CO3_K_PS_SUM, CO3_K_MOMENTS, CO3_K_BIAS_SCALE, CO3_K_COOP, CO3_K_COUNT
 };
 
 // Brackets one kernel launch with a pair of HIP events on the launch stream when timing of that
@@ -26,9 +26,17 @@ hipError_t co3_launch_absmax(const float *g, int64_t n, int U, int64_t stride, c
 hipError_t co3_launch_convert(const float *g, float *err, uint8_t *sym, int64_t n, int U, int64_t stride,
                               const int64_t *seg_off, int nseg, const int32_t *anchor, const float *scale, float gamma,
                               co3_fmt fmt, uint32_t *counts, hipStream_t st);
+// resident-grid conversion (anchor from max|g| and conversion with one read of g; one anchor per user)
+bool co3_coop_fits(int64_t n, int cus, int *kpt_out, int *grid_out);
+hipError_t co3_launch_coop_convert(const float *g, float *err, uint8_t *sym, int64_t n, int U, int64_t stride, int kpt,
+                                   int grid, int32_t *anchor, float gamma, co3_fmt fmt, uint32_t *counts_rep,
+                                   uint32_t *slots, uint32_t spin_limit, int32_t *status, hipStream_t st);
 hipError_t co3_launch_histogram(const uint8_t *sym, int64_t n, int U, int64_t stride, int K, uint32_t *counts,
                                 hipStream_t st);
-hipError_t co3_launch_build_code(const uint32_t *weights, int U, int K, void *codes, int32_t *status, hipStream_t st);
+// nrep > 1: weights is [nrep][U][K] partial tables that the kernel adds up (the sums also go to sums_out [U][K])
+hipError_t co3_launch_build_code(const uint32_t *weights, int U, int K, void *codes, int32_t *status, hipStream_t st,
+                                 int nrep = 1, uint32_t *sums_out = nullptr);
+#define CO3_COOP_COUNT_REPS 32   // partial count tables of the resident-grid user side (workgroup w adds to table w mod 32)
 hipError_t co3_launch_encode(const uint8_t *sym, int64_t n, int U, int64_t stride, const void *codes, int K,
                              const int64_t *seg_off, int nseg, uint64_t *words, int64_t cap_words, int chunk_syms,
                              uint64_t *chunk_bitoff, uint64_t *total_bits, uint64_t *tilesum, int32_t *status,

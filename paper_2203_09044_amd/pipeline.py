@@ -26,7 +26,8 @@ class Co3Pipeline:
     def __init__(self, U: int, n: int, fmt: Fmt, chunk_syms: int = 256, seg_off=None, gamma: float = 1.0,
                  cap_words: Optional[int] = None, device="cuda:0", fused_histogram: bool = True,
                  bias: str = "absmax", grid_anchor: Optional[int] = None, codes: str = "user", code_seg_off=None,
-                 statistics: bool = True, single_pass: bool = False, lagged_codes: bool = False):
+                 statistics: bool = True, single_pass: bool = False, lagged_codes: bool = False,
+                 one_call: bool = False, keep_symbols: bool = True):
         if bias not in ("absmax", "moments"):
             raise ValueError("bias must be 'absmax' or 'moments'")
         if codes not in ("user", "layer"):
@@ -44,6 +45,11 @@ class Co3Pipeline:
         self.lagged_codes = lagged_codes
         if lagged_codes and not single_pass:
             raise ValueError("lagged_codes needs single_pass")
+        # the user's steps of an iteration through co3_user_encode (anchor from max|g|, one empirical code per user)
+        self.one_call = one_call
+        if one_call and (bias != "absmax" or codes != "user" or single_pass):
+            raise ValueError("one_call is the path with the anchor from max|g| and per-user empirical codes")
+        self.keep_symbols = keep_symbols  # one_call only: whether the symbol array is asked for
         self.have_codes = False
         self.bias = bias
         dev = torch.device(device)
@@ -69,6 +75,8 @@ class Co3Pipeline:
         self.agg_ws = torch.zeros((max(B.ps_aggregate_workspace_bytes(n, U, chunk_syms), 16),), dtype=torch.uint8, **z)
         self.fused_ws = (torch.empty((B.convert_encode_workspace_bytes(n, U, chunk_syms),), dtype=torch.uint8, **z)
                          if single_pass else None)
+        self.user_ws = (torch.empty((B.user_encode_workspace_bytes(n, U, self.stride, keep_symbols),), dtype=torch.uint8, **z)
+                        if one_call else None)
         self.avg = torch.zeros((self.stride,), dtype=torch.float32, **z)
         self.sym_dec = torch.zeros((U, self.stride), dtype=torch.uint8, **z)
         self.status = torch.zeros((1,), dtype=torch.int32, **z)
@@ -117,6 +125,12 @@ class Co3Pipeline:
             B.convert_encode(g, self.err, self.n, self.anchor, anchor_mode, self.gamma, self.fmt, self.codes, self.words,
                              self.chunk_syms, self.chunk_bitoff, self.total_bits, self.fused_ws, self.status,
                              seg_off=self.seg_off, counts=self.counts if self.lagged_codes else None)
+
+    def user_encode(self, g: torch.Tensor):
+        """Conversion, statistics, code and compression of all users in one library call (one_call)."""
+        B.user_encode(g, self.err, self.n, self.anchor, self.gamma, self.fmt, self.counts, self.codes, self.words,
+                      self.chunk_syms, self.chunk_bitoff, self.total_bits, self.user_ws, self.status,
+                      sym=self.sym if self.keep_symbols else None, seg_off=self.seg_off)
 
     def build(self, weights: Optional[torch.Tensor] = None):
         """Per-user codes from the users' counts (or given weights [U][K]); per-tensor codes from the pooled
@@ -179,6 +193,10 @@ class Co3Pipeline:
             if self.bias == "moments":
                 self.fit_bias(g)
             self.convert_encode(g)
+            self.aggregate()
+            return
+        if self.one_call and rebuild and weights is None:
+            self.user_encode(g)
             self.aggregate()
             return
         if self.bias == "moments":

@@ -1,0 +1,133 @@
+"""co3_user_encode (the user's steps of an iteration in one call; where the batch fits, a resident grid
+that reads every gradient once) against the CPU oracle, through the C ABI: anchors, symbols, memory,
+counts, code lengths, streams, chunk offsets and the average, bit for bit."""
+import numpy as np
+import pytest
+
+import oracle
+import co3_inputs as inp
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from test_gpu_parity import oracle_user_side, check_user_side, ofmt, host_u32, host_u64   # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def co3():
+    import paper_2203_09044_amd as pkg
+    return pkg
+
+
+def run_one_call(co3, U, n, fmt, C, betas, alpha=1e-3, T=2, gamma=1.0, sizes=None, seed=0, keep_symbols=True,
+                 adversarial=None):
+    seg_off = None if sizes is None else inp.seg_offsets(sizes)
+    pipe = co3.Co3Pipeline(U, n, fmt, chunk_syms=C, seg_off=seg_off, gamma=gamma, one_call=True,
+                           keep_symbols=keep_symbols)
+    errs = [np.zeros(n, np.float32) for _ in range(U)]
+    g = pipe.new_gradient_buffer()
+    for t in range(1, T + 1):
+        g_host = []
+        for u in range(U):
+            r = inp.rng_for(98, seed, u, t)
+            x = inp.gennorm(r, n, betas[u % len(betas)], alpha * (1.0 + 3.0 * ((u + t) % 3)))
+            if adversarial is not None:
+                x = adversarial(x, u, t)
+            g_host.append(x)
+        if n:
+            g[:, :n] = torch.from_numpy(np.stack(g_host)).cuda()
+        pipe.step(g)
+        assert pipe.poll() == 0
+        refs = []
+        for u in range(U):
+            ref = oracle_user_side(g_host[u], errs[u], fmt, seg_off, gamma, C)
+            if keep_symbols:
+                check_user_side(pipe, u, ref, n)
+            else:
+                assert np.array_equal(pipe.anchor[u].cpu().numpy(), ref["A"]), "anchor"
+                assert np.array_equal(host_u32(pipe.err[u, :n]), ref["err"].view(np.uint32)), "error vector"
+                assert np.array_equal(host_u32(pipe.counts[u]), ref["cnt"]), "histogram"
+                assert np.array_equal(pipe.codes[u, :fmt.K].cpu().numpy(), ref["len"]), "code lengths"
+                assert int(pipe.total_bits[u].item()) == ref["total"], "total bits"
+                assert np.array_equal(host_u64(pipe.chunk_bitoff[u]), ref["off"]), "chunk offsets"
+                nw = (ref["total"] + 63) // 64
+                assert np.array_equal(host_u64(pipe.words[u, :nw]), ref["words"][:nw]), "stream words"
+            errs[u] = ref["err"]
+            refs.append(ref)
+        want = oracle.aggregate(np.stack([r["sym"] for r in refs]) if n else np.zeros((U, 0), np.uint8),
+                                np.stack([r["A"] for r in refs]), ofmt(fmt), seg_off)
+        got = pipe.avg[:n].cpu().numpy()
+        assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), "average"
+    return pipe
+
+
+@pytest.mark.parametrize("E,M", [(3, 0), (3, 1), (2, 0), (4, 3), (5, 2), (1, 2)])
+def test_one_call_formats(co3, E, M):
+    # more than one run of 256 per wavefront on 256 compute units, ragged end, users of different shape and scale
+    run_one_call(co3, 3, 256 * 2048 * 2 + 1237, co3.Fmt(E, M), 256, betas=[0.6, 1.0, 1.4], T=3)
+
+
+@pytest.mark.parametrize("n", [0, 1, 3, 4, 5, 255, 256, 257, 2047, 2048, 2049, 65_536, 65_541, 524_288, 524_289,
+                               1_048_576 + 2048 + 7])
+@pytest.mark.parametrize("keep", [True, False])
+def test_one_call_sizes(co3, n, keep):
+    run_one_call(co3, 2, n, co3.Fmt(3, 1), 64, betas=[1.0, 0.7], T=2, keep_symbols=keep)
+
+
+def test_one_call_single_user_and_many_users(co3):
+    run_one_call(co3, 1, 700_001, co3.Fmt(3, 0), 256, betas=[1.0], T=3)
+    run_one_call(co3, 16, 70_001, co3.Fmt(3, 0), 128, betas=[0.5, 1.5], T=2)
+
+
+def test_one_call_gamma_and_adversarial_values(co3):
+    def adv(x, u, t):
+        x = x.copy()
+        # the largest magnitude sits in different workgroups' ranges, at both ends, and changes binade per user
+        x[0 if (u + t) % 2 else -1] = np.float32(3.9 * 2.0 ** (u - t))
+        x[len(x) // 2] = np.float32(-1e-30)        # far below every level
+        x[len(x) // 3] = np.float32(0.0)
+        return x
+    run_one_call(co3, 4, 300_007, co3.Fmt(3, 1), 256, betas=[0.8], T=4, gamma=0.9, adversarial=adv)
+    run_one_call(co3, 2, 300_007, co3.Fmt(1, 2), 256, betas=[1.2], T=3, gamma=0.0, adversarial=adv)
+
+
+def test_one_call_zero_gradients_and_subnormal_maxima(co3):
+    def zeros(x, u, t):
+        return np.zeros_like(x) if u == 0 else (x * np.float32(1e-38)).astype(np.float32)
+    run_one_call(co3, 2, 100_000, co3.Fmt(3, 1), 256, betas=[1.0], T=2, adversarial=zeros)
+
+
+def test_one_call_with_tensors_takes_the_separate_kernels(co3):
+    sizes = [10, 1, 4097, 64, 3, 20_000, 7, 128, 0, 5, 12_345]
+    run_one_call(co3, 2, sum(sizes), co3.Fmt(4, 3), 256, betas=[0.8], T=2, sizes=sizes)
+    run_one_call(co3, 2, sum(sizes), co3.Fmt(4, 3), 256, betas=[0.8], T=2, sizes=sizes, keep_symbols=False)
+
+
+def test_one_call_deterministic(co3):
+    a = run_one_call(co3, 3, 400_003, co3.Fmt(3, 0), 256, betas=[0.5, 1.0, 1.5], T=2)
+    b = run_one_call(co3, 3, 400_003, co3.Fmt(3, 0), 256, betas=[0.5, 1.0, 1.5], T=2)
+    assert torch.equal(a.words, b.words) and torch.equal(a.err, b.err) and torch.equal(a.avg, b.avg)
+
+
+def test_a_wait_that_runs_out_is_reported_and_the_kernel_ends(co3):
+    """No poll allowed: every exchange of the resident grid runs out at once.  The call must come back with
+    CO3_ETIMEOUT in the status word, having written nothing out of bounds (canaries), and the next call works."""
+    B = co3.binding
+    fmt = co3.Fmt(3, 0)
+    U, n = 2, 300_000
+    pipe = co3.Co3Pipeline(U, n, fmt, chunk_syms=256, one_call=True)
+    g = pipe.new_gradient_buffer()
+    g[:, :n] = torch.from_numpy(np.stack([inp.gennorm(inp.rng_for(97, 0, u, 1), n, 1.0, 1e-3) for u in range(U)])).cuda()
+    pad = pipe.err[:, n:].clone()
+    try:
+        B.set_exchange_spin_limit(0)
+        pipe.user_encode(g)
+        assert pipe.poll() == B.ETIMEOUT
+    finally:
+        B.set_exchange_spin_limit(-1)
+    assert torch.equal(pipe.err[:, n:], pad)
+    pipe.status.zero_()
+    pipe.err.zero_()
+    pipe.step(g)
+    assert pipe.poll() == 0
