@@ -95,7 +95,7 @@ def _load():
     L.co3_encode_static.restype = i32
     L.co3_encode_static.argtypes = [p, i64, i32, i64, _Fmt, p, p, i64, i32, p, p, p, p]
     L.co3_user_encode_workspace_bytes.restype = sz
-    L.co3_user_encode_workspace_bytes.argtypes = [i64, i32, i64, i32]
+    L.co3_user_encode_workspace_bytes.argtypes = [i64, i32, i64, i32, i32]
     L.co3_user_encode.restype = i32
     L.co3_user_encode.argtypes = [p, p, i64, i32, i64, p, i32, p, C.c_float, _Fmt, p, p, p, i64, i32, p, p, p, p, sz, p, p]
     L.co3_set_exchange_spin_limit.restype = None
@@ -279,8 +279,8 @@ def encode(sym, n, fmt: Fmt, codes, words, chunk_syms, chunk_bitoff, total_bits,
 ENCODE_STATIC_WS_BYTES = 4 << 20
 
 
-def user_encode_workspace_bytes(n: int, U: int, stride: int, caller_has_sym: bool) -> int:
-    return _lib.co3_user_encode_workspace_bytes(n, U, stride, int(bool(caller_has_sym)))
+def user_encode_workspace_bytes(n: int, U: int, stride: int, nseg: int, caller_has_sym: bool) -> int:
+    return _lib.co3_user_encode_workspace_bytes(n, U, stride, nseg, int(bool(caller_has_sym)))
 
 
 def user_encode(g, err, n, anchor, gamma, fmt: Fmt, counts, codes, words, chunk_syms, chunk_bitoff, total_bits, workspace,

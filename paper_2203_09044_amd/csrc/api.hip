@@ -131,7 +131,7 @@ const char *co3_kernel_name(int32_t kernel)
 {
     static const char *names[CO3_K_COUNT] = {"k_fill_i32", "k_absmax",    "k_convert_ef", "k_histogram", "k_build_code",
                                              "k_enc_sizes", "k_enc_scan", "k_enc_pack",   "k_decode",    "k_ps_sum",
-                                             "k_moments",  "k_bias_scale", "k_coop_convert"};
+                                             "k_moments",  "k_bias_scale", "k_coop_user"};
     return (kernel >= 0 && kernel < CO3_K_COUNT) ? names[kernel] : "";
 }
 
@@ -289,16 +289,20 @@ void co3_set_exchange_spin_limit(int64_t polls)
     g_spin_limit.store(polls < 0 ? (1u << 18) : polls > 0xffffffffll ? 0xffffffffu : (uint32_t)polls);
 }
 
-// layout of the workspace of co3_user_encode: exchange words [U][compute units] u32, partial count tables
-// [CO3_COOP_COUNT_REPS][U][K] u32, the encoder's workspace, then (where the caller passes no symbol array)
-// the symbols [U][stride]
-size_t co3_user_encode_workspace_bytes(int64_t n, int32_t U, int64_t stride, int32_t caller_has_sym)
+// workspace of co3_user_encode: the exchange words of the resident grid where it serves the batch; else the
+// encoder's workspace and (where the caller passes no symbol array) the symbols [U][stride]
+static bool user_encode_coop(int64_t n, int32_t nseg, int *kpt, int *grid)
 {
-    if (n < 0 || U < 1 || stride < 0) return 0;
     const int cus = device_cus();
-    size_t b = round_up_256((size_t)U * (size_t)(cus > 0 ? cus : 1024) * sizeof(uint32_t));
-    b += round_up_256((size_t)CO3_COOP_COUNT_REPS * (size_t)U * 256 * sizeof(uint32_t));
-    b += round_up_256(co3_encode_workspace_bytes(n, U));
+    return nseg == 1 && cus > 0 && co3_coop_fits(n, cus, kpt, grid);
+}
+
+size_t co3_user_encode_workspace_bytes(int64_t n, int32_t U, int64_t stride, int32_t nseg, int32_t caller_has_sym)
+{
+    if (n < 0 || U < 1 || stride < 0 || nseg < 1) return 0;
+    int kpt = 0, grid = 0;
+    if (user_encode_coop(n, nseg, &kpt, &grid)) return round_up_256(co3_coop_exchange_bytes(U, grid, 256));
+    size_t b = round_up_256(co3_encode_workspace_bytes(n, U));
     if (!caller_has_sym) b += round_up_256((size_t)U * (size_t)(stride > n ? stride : n) + 16);
     return b;
 }
@@ -316,41 +320,21 @@ int32_t co3_user_encode(const float *g, float *err, int64_t n, int32_t U, int64_
     if (!aligned(g, 16) || !aligned(err, 16) || !aligned(words, 16) || !aligned(codes, 8) || !aligned(workspace, 256))
         return CO3_EINVAL;
     if (sym && !aligned(sym, 16)) return CO3_EINVAL;
-    if (ws_bytes < co3_user_encode_workspace_bytes(n, U, stride, sym != nullptr)) return CO3_EINVAL;
+    if (ws_bytes < co3_user_encode_workspace_bytes(n, U, stride, nseg, sym != nullptr)) return CO3_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const FmtC fc(fmt);
-    const int cus = device_cus();
-    char *ws = static_cast<char *>(workspace);
-    uint32_t *slots = reinterpret_cast<uint32_t *>(ws);
-    const size_t slot_words = (size_t)U * (size_t)(cus > 0 ? cus : 1024);
-    ws += round_up_256(slot_words * sizeof(uint32_t));
-    uint32_t *counts_rep = reinterpret_cast<uint32_t *>(ws);
-    ws += round_up_256((size_t)CO3_COOP_COUNT_REPS * (size_t)U * 256 * sizeof(uint32_t));
-    void *enc_ws = ws;
-    const size_t enc_bytes = co3_encode_workspace_bytes(n, U);
-    ws += round_up_256(enc_bytes);
-    uint8_t *symbuf = sym ? sym : reinterpret_cast<uint8_t *>(ws);
-
     int kpt = 0, grid = 0;
-    const bool coop = nseg == 1 && cus > 0 && co3_coop_fits(n, cus, &kpt, &grid);
-    if (coop) {
-        // exchange words and partial counters start at zero
-        hipError_t e = co3_launch_fill(reinterpret_cast<int32_t *>(slots), (int64_t)U * grid, 0, counts_rep,
-                                       (int64_t)CO3_COOP_COUNT_REPS * U * fc.K, st);
-        if (e != hipSuccess) return CO3_EHIP;
-        e = co3_launch_coop_convert(g, err, symbuf, n, U, stride, kpt, grid, anchor, gamma, fmt, counts_rep, slots,
-                                    g_spin_limit.load(), status, st);
-        if (e != hipSuccess) return CO3_EHIP;
-        // the code build adds the partial tables up and leaves the sums in counts
-        if (co3_launch_build_code(counts_rep, U, fc.K, codes, status, st, CO3_COOP_COUNT_REPS, counts) != hipSuccess)
-            return CO3_EHIP;
-        return hip_rc(co3_launch_encode(symbuf, n, U, stride, codes, fc.K, nullptr, 1, words, cap_words, chunk_syms,
-                                        chunk_bitoff, total_bits, static_cast<uint64_t *>(enc_ws), status, st));
-    } else {
-        const int32_t rc = convert_common(g, err, symbuf, n, U, stride, seg_off, nseg, anchor,
-                                          CO3_ANCHOR_FROM_ABSMAX_G, nullptr, gamma, fmt, counts, stream);
-        if (rc != CO3_OK) return rc;
-    }
+    if (user_encode_coop(n, nseg, &kpt, &grid))
+        return hip_rc(co3_launch_coop_user(g, err, sym, n, U, stride, kpt, grid, anchor, gamma, fmt, counts, codes, words,
+                                           cap_words, chunk_syms, chunk_bitoff, total_bits, workspace, g_spin_limit.load(),
+                                           status, st));
+    char *ws = static_cast<char *>(workspace);
+    void *enc_ws = ws;
+    ws += round_up_256(co3_encode_workspace_bytes(n, U));
+    uint8_t *symbuf = sym ? sym : reinterpret_cast<uint8_t *>(ws);
+    const int32_t rc = convert_common(g, err, symbuf, n, U, stride, seg_off, nseg, anchor, CO3_ANCHOR_FROM_ABSMAX_G,
+                                      nullptr, gamma, fmt, counts, stream);
+    if (rc != CO3_OK) return rc;
     if (co3_launch_build_code(counts, U, fc.K, codes, status, st) != hipSuccess) return CO3_EHIP;
     return hip_rc(co3_launch_encode(symbuf, n, U, stride, codes, fc.K, nullptr, 1, words, cap_words, chunk_syms,
                                     chunk_bitoff, total_bits, static_cast<uint64_t *>(enc_ws), status, st));

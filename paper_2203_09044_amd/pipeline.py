@@ -75,7 +75,7 @@ class Co3Pipeline:
         self.agg_ws = torch.zeros((max(B.ps_aggregate_workspace_bytes(n, U, chunk_syms), 16),), dtype=torch.uint8, **z)
         self.fused_ws = (torch.empty((B.convert_encode_workspace_bytes(n, U, chunk_syms),), dtype=torch.uint8, **z)
                          if single_pass else None)
-        self.user_ws = (torch.empty((B.user_encode_workspace_bytes(n, U, self.stride, keep_symbols),), dtype=torch.uint8, **z)
+        self.user_ws = (torch.empty((max(B.user_encode_workspace_bytes(n, U, self.stride, self.nseg, keep_symbols), 256),), dtype=torch.uint8, **z)
                         if one_call else None)
         self.avg = torch.zeros((self.stride,), dtype=torch.float32, **z)
         self.sym_dec = torch.zeros((U, self.stride), dtype=torch.uint8, **z)
