@@ -320,12 +320,10 @@ int32_t co3_convert_encode_layers(const float *g, float *err, int64_t n, int32_t
  * bit for bit -- err, anchor, counts, codes, words, chunk_bitoff, total_bits (and sym, if asked for).
  * What the one call adds is that it may keep data on the chip between the steps: where one anchor per
  * user is asked for (nseg = 1) and a user's gradient fits the register files of the device (n up to
- * 45,056 elements per compute unit: 11.5 M on 256 units), a single resident grid reads every input once
- * and writes every output once -- a workgroup per compute unit keeps its part of a user's gradient in
- * registers between the search for the largest magnitude and the conversion, and its part of the symbols
- * in LDS until the user's code is built, the workgroups exchanging maxima, counts, the code and coded
- * sizes through a few self-validating words in the workspace; other batches run the separate kernels of
- * the three calls.
+ * 45,056 elements per compute unit: 11.5 M on 256 units), a single resident grid reads every gradient
+ * once, taking the largest magnitude and converting from registers, the workgroups exchanging their
+ * maxima through one word each in the workspace; other batches run the separate kernels of the three
+ * calls.
  *
  *   arguments  as in co3_convert_ef (g, err, n, U, stride, seg_off, nseg, anchor [out], gamma, fmt,
  *              counts [out, required]), co3_build_code (codes [out]) and co3_encode (words, cap_words,
@@ -362,7 +360,7 @@ void co3_set_exchange_spin_limit(int64_t polls);
  * that must report one kernel's average duration.  Process-global and not thread-safe: the
  * only state the library keeps, and only while enabled.  kernel ids: 0 k_fill_i32, 1 k_absmax,
  * 2 k_convert_ef, 3 k_histogram, 4 k_build_code, 5 k_enc_sizes, 6 k_enc_scan, 7 k_enc_pack,
- * 8 k_decode, 9 k_ps_sum, 10 k_moments, 11 k_bias_scale, 12 k_coop_user (co3_kernel_name returns
+ * 8 k_decode, 9 k_ps_sum, 10 k_moments, 11 k_bias_scale, 12 k_coop_convert (co3_kernel_name returns
  * these names, "" for other ids).
  *   co3_timing_enable(mask): bracket every later launch of kernel k with events iff bit k is set.
  *   co3_timing_read(k, &ms, &count): waits for the recorded events, then returns the summed

@@ -131,7 +131,7 @@ const char *co3_kernel_name(int32_t kernel)
 {
     static const char *names[CO3_K_COUNT] = {"k_fill_i32", "k_absmax",    "k_convert_ef", "k_histogram", "k_build_code",
                                              "k_enc_sizes", "k_enc_scan", "k_enc_pack",   "k_decode",    "k_ps_sum",
-                                             "k_moments",  "k_bias_scale", "k_coop_user"};
+                                             "k_moments",  "k_bias_scale", "k_coop_convert"};
     return (kernel >= 0 && kernel < CO3_K_COUNT) ? names[kernel] : "";
 }
 
@@ -289,8 +289,9 @@ void co3_set_exchange_spin_limit(int64_t polls)
     g_spin_limit.store(polls < 0 ? (1u << 18) : polls > 0xffffffffll ? 0xffffffffu : (uint32_t)polls);
 }
 
-// workspace of co3_user_encode: the exchange words of the resident grid where it serves the batch; else the
-// encoder's workspace and (where the caller passes no symbol array) the symbols [U][stride]
+// Layout of the workspace of co3_user_encode: the encoder's workspace, the symbols [U][stride] where the
+// caller passes no array for them, and, where the resident grid serves the batch, its exchange words
+// [U][workgroups] u32 and partial count tables [CO3_COOP_COUNT_REPS][U][K] u32.
 static bool user_encode_coop(int64_t n, int32_t nseg, int *kpt, int *grid)
 {
     const int cus = device_cus();
@@ -300,10 +301,13 @@ static bool user_encode_coop(int64_t n, int32_t nseg, int *kpt, int *grid)
 size_t co3_user_encode_workspace_bytes(int64_t n, int32_t U, int64_t stride, int32_t nseg, int32_t caller_has_sym)
 {
     if (n < 0 || U < 1 || stride < 0 || nseg < 1) return 0;
-    int kpt = 0, grid = 0;
-    if (user_encode_coop(n, nseg, &kpt, &grid)) return round_up_256(co3_coop_exchange_bytes(U, grid, 256));
     size_t b = round_up_256(co3_encode_workspace_bytes(n, U));
     if (!caller_has_sym) b += round_up_256((size_t)U * (size_t)(stride > n ? stride : n) + 16);
+    int kpt = 0, grid = 0;
+    if (user_encode_coop(n, nseg, &kpt, &grid)) {
+        b += round_up_256((size_t)U * (size_t)grid * sizeof(uint32_t));
+        b += round_up_256((size_t)CO3_COOP_COUNT_REPS * (size_t)U * 256 * sizeof(uint32_t));
+    }
     return b;
 }
 
@@ -323,15 +327,29 @@ int32_t co3_user_encode(const float *g, float *err, int64_t n, int32_t U, int64_
     if (ws_bytes < co3_user_encode_workspace_bytes(n, U, stride, nseg, sym != nullptr)) return CO3_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const FmtC fc(fmt);
-    int kpt = 0, grid = 0;
-    if (user_encode_coop(n, nseg, &kpt, &grid))
-        return hip_rc(co3_launch_coop_user(g, err, sym, n, U, stride, kpt, grid, anchor, gamma, fmt, counts, codes, words,
-                                           cap_words, chunk_syms, chunk_bitoff, total_bits, workspace, g_spin_limit.load(),
-                                           status, st));
     char *ws = static_cast<char *>(workspace);
     void *enc_ws = ws;
     ws += round_up_256(co3_encode_workspace_bytes(n, U));
     uint8_t *symbuf = sym ? sym : reinterpret_cast<uint8_t *>(ws);
+    if (!sym) ws += round_up_256((size_t)U * (size_t)(stride > n ? stride : n) + 16);
+    int kpt = 0, grid = 0;
+    if (user_encode_coop(n, nseg, &kpt, &grid)) {
+        uint32_t *slots = reinterpret_cast<uint32_t *>(ws);
+        ws += round_up_256((size_t)U * (size_t)grid * sizeof(uint32_t));
+        uint32_t *counts_rep = reinterpret_cast<uint32_t *>(ws);
+        // exchange words and partial counters start at zero
+        if (co3_launch_fill(reinterpret_cast<int32_t *>(slots), (int64_t)U * grid, 0, counts_rep,
+                            (int64_t)CO3_COOP_COUNT_REPS * U * fc.K, st) != hipSuccess)
+            return CO3_EHIP;
+        if (co3_launch_coop_convert(g, err, symbuf, n, U, stride, kpt, grid, anchor, gamma, fmt, counts_rep, slots,
+                                    g_spin_limit.load(), status, st) != hipSuccess)
+            return CO3_EHIP;
+        // the code build adds the partial tables up and leaves the sums in counts
+        if (co3_launch_build_code(counts_rep, U, fc.K, codes, status, st, CO3_COOP_COUNT_REPS, counts) != hipSuccess)
+            return CO3_EHIP;
+        return hip_rc(co3_launch_encode(symbuf, n, U, stride, codes, fc.K, nullptr, 1, words, cap_words, chunk_syms,
+                                        chunk_bitoff, total_bits, static_cast<uint64_t *>(enc_ws), status, st));
+    }
     const int32_t rc = convert_common(g, err, symbuf, n, U, stride, seg_off, nseg, anchor, CO3_ANCHOR_FROM_ABSMAX_G,
                                       nullptr, gamma, fmt, counts, stream);
     if (rc != CO3_OK) return rc;

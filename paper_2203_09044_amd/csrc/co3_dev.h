@@ -158,10 +158,14 @@ __device__ __forceinline__ void co3_quantize(float x, int e_min, int A, int E, i
     val = __uint_as_float(__float_as_uint(mag) | (s << 31));
 }
 
-// release/acquire fence at wavefront scope around a wavefront barrier: LDS written by some lanes is read by others
+// LDS written by some lanes of a wavefront is read by others.  The LDS operations of one wavefront are
+// carried out in program order and its lanes run in lockstep, so all that is needed is that the earlier
+// operations have been carried out (the LDS counter) and that the compiler keeps the order.  A fence, even
+// at wavefront scope, would also wait for every global load and store in flight: in a streaming loop that
+// drains the memory pipeline at every hand-over.
 __device__ __forceinline__ void co3_wave_lds_sync()
 {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    asm volatile("" ::: "memory");
 }

@@ -36,12 +36,7 @@ __device__ __forceinline__ int load_syms16(const uint8_t *su, int64_t i, int64_t
     return c;
 }
 
-__device__ __forceinline__ void wave_lds_sync()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
+__device__ __forceinline__ void wave_lds_sync() { co3_wave_lds_sync(); }
 
 __device__ __forceinline__ uint64_t wave_sum_u64(uint64_t v)
 {

@@ -26,14 +26,12 @@ hipError_t co3_launch_absmax(const float *g, int64_t n, int U, int64_t stride, c
 hipError_t co3_launch_convert(const float *g, float *err, uint8_t *sym, int64_t n, int U, int64_t stride,
                               const int64_t *seg_off, int nseg, const int32_t *anchor, const float *scale, float gamma,
                               co3_fmt fmt, uint32_t *counts, hipStream_t st);
-// resident-grid user side (one anchor per user, one empirical code per user): conversion, counts, code and
-// compression in one kernel; `exchange` holds co3_coop_exchange_bytes(U, grid, K) bytes
+// resident-grid conversion (anchor from max|g| and conversion with one read of g; one anchor per user);
+// slots: [U][grid] u32 exchange words, counts_rep: [CO3_COOP_COUNT_REPS][U][K] partial counts, both zero at launch
 bool co3_coop_fits(int64_t n, int cus, int *kpt_out, int *grid_out);
-size_t co3_coop_exchange_bytes(int U, int grid, int K);
-hipError_t co3_launch_coop_user(const float *g, float *err, uint8_t *sym, int64_t n, int U, int64_t stride, int kpt,
-                                int grid, int32_t *anchor, float gamma, co3_fmt fmt, uint32_t *counts, void *codes,
-                                uint64_t *words, int64_t cap_words, int chunk_syms, uint64_t *chunk_bitoff,
-                                uint64_t *total_bits, void *exchange, uint32_t spin_limit, int32_t *status, hipStream_t st);
+hipError_t co3_launch_coop_convert(const float *g, float *err, uint8_t *sym, int64_t n, int U, int64_t stride, int kpt,
+                                   int grid, int32_t *anchor, float gamma, co3_fmt fmt, uint32_t *counts_rep,
+                                   uint32_t *slots, uint32_t spin_limit, int32_t *status, hipStream_t st);
 hipError_t co3_launch_histogram(const uint8_t *sym, int64_t n, int U, int64_t stride, int K, uint32_t *counts,
                                 hipStream_t st);
 // nrep > 1: weights is [nrep][U][K] partial tables that the kernel adds up (the sums also go to sums_out [U][K])
