@@ -1,14 +1,17 @@
 #!/usr/bin/env python3
 """Benchmark of the CO3 codec hot path on one MI355X.
 
-A step is one whole iteration of Algorithm 1's uplink for all clients of the workload:
-co3_convert_ef (anchor + error correction + fp conversion + histogram) -> co3_build_code ->
-co3_encode -> co3_ps_aggregate (decode + average), on synthetic GenNorm gradients that are
-resident in HBM before the timed region starts.
+A step is one whole iteration of Algorithm 1's uplink for all clients of the workload: the user
+side (anchor + error correction + fp conversion + histogram, code build, compression: one
+co3_user_encode call, or co3_convert_ef -> co3_build_code -> co3_encode with --separate-calls)
+and the server side co3_ps_aggregate (decode + average), on synthetic GenNorm gradients that
+are resident in HBM before the timed region starts.
 
-Prints ONE JSON line: elements/s of the whole path, the roofline of the dominant kernel
-(k_convert_ef, timed live with HIP events on the launch stream), and the CPU oracle timed on a
-bounded sample of the same workload on this host.
+Prints ONE JSON line: elements/s of the whole path with its fraction of the HBM roofline
+(path_roofline; the target of 0.60 on C3 is stated beside it), the roofline of the dominant
+kernel (the conversion kernel, timed live with HIP events on the launch stream), the first
+iteration's time, the measured device copy bandwidth, and the CPU oracle timed on a bounded
+sample of the device batches on this host (one core, and one thread per client).
 """
 import argparse
 import json
@@ -20,7 +23,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
-K_CONVERT = 2                  # kernel id of k_convert_ef in the library's timing facility
+K_CONVERT = 2                  # kernel ids of the library's timing facility: k_convert_ef ...
+K_COOP = 12                    # ... and k_coop_convert, the resident-grid form of the conversion
+PATH_TARGET_FRAC = 0.60        # end-to-end target on C3: fraction of the HBM roofline
 
 
 def log(*a):
@@ -40,8 +45,8 @@ def make_workload(name):
         return w, [1.0], 1e-3, "C1: 1 client x 65,536 fp32, GenNorm beta=1 scale 1e-3, E3M1"
     if name == "C2":
         w = inp.c2()
-        return w, [0.8], 1e-3, ("C2: 1 client x 11,173,962 fp32 in 62 tensors (per-tensor anchors), GenNorm beta=0.8, "
-                                "E4M3 (the benchmark draws one scale for all tensors)")
+        return w, [0.8], None, ("C2: 1 client x 11,173,962 fp32 in 62 tensors (per-tensor anchors), GenNorm beta=0.8, "
+                                "per-tensor scale 10^U(-5,-2), E4M3")
     if name == "C4":
         w = inp.c4()
         return w, [1.0], 1e-4, "C4: 1 client x 100,000,000 fp32, GenNorm beta=1 scale 1e-4 (1e-4 of the samples at 100x), E5M2"
@@ -54,7 +59,8 @@ def make_workload(name):
 
 
 def device_batches(w, betas, alpha, pool, pipe):
-    """`pool` gradient batches [U][stride] drawn on the device (seeded), one per iteration slot."""
+    """`pool` gradient batches [U][stride] drawn on the device (seeded), one per iteration slot, by the
+    recipe of the workload: C2 one scale per tensor, C4 1e-4 of the samples at 100 times the scale."""
     import torch
     import co3_inputs as inp
     out = []
@@ -62,43 +68,94 @@ def device_batches(w, betas, alpha, pool, pipe):
         g = pipe.new_gradient_buffer()
         for u in range(w.U):
             seed = inp.BASE_SEED * 1000003 + w.cfg * 10007 + u * 101 + t
-            g[u, :w.n] = inp.device_gennorm(w.n, betas[u % len(betas)], alpha, seed)
+            beta = betas[u % len(betas)]
+            if w.cfg == 2:
+                scales = inp.c2_tensor_scales()
+                g[u, :w.n] = torch.cat([inp.device_gennorm(sz, beta, float(a), seed + 7919 * (k + 1))
+                                        for k, (sz, a) in enumerate(zip(w.sizes, scales))])
+            elif w.cfg == 4:
+                g[u, :w.n] = inp.device_gennorm_outliers(w.n, beta, alpha, 1e-4, 100.0, seed)
+            else:
+                g[u, :w.n] = inp.device_gennorm(w.n, beta, alpha, seed)
         out.append(g)
     torch.cuda.synchronize()
     return out
 
 
-def cpu_baseline(w, betas, alpha, chunk_syms, n_sample, reps):
-    """The oracle as it stands, single thread, same call sequence, on `n_sample` elements per client of
-    `U_s` clients of the workload."""
+def cpu_baseline(w, batches, chunk_syms, n_sample, reps):
+    """The oracle as it stands on the bytes the GPU leg consumed (copied back from the device batches): the
+    same call sequence per iteration, on the first `n_sample` elements of every client.  Two figures: one
+    thread over 2 clients, then threads over all clients of the workload (each oracle call stays
+    single-threaded) on up to all host cores."""
+    from concurrent.futures import ThreadPoolExecutor
     import numpy as np
     import oracle
-    import co3_inputs as inp
-    U_s = min(w.U, 2)
     fmt = oracle.Fmt(w.E, w.M)
-    gs = [[inp.gennorm(inp.rng_for(w.cfg, 7, u, t), n_sample, betas[u % len(betas)], alpha) for u in range(U_s)]
-          for t in range(reps)]
-    errs = [np.zeros(n_sample, np.float32) for _ in range(U_s)]
+    seg_off = None
+    if w.sizes is not None and n_sample == w.n:
+        seg_off = w.seg_off
+    host = [[b[u, :n_sample].cpu().numpy() for u in range(w.U)] for b in batches]
     oracle.lib()
+
+    def client_iteration(g, err):
+        A = oracle.anchor(g, fmt, seg_off)
+        s, e_new = oracle.convert_ef(g, err, A, 1.0, fmt, seg_off)
+        cnt = oracle.histogram(s, fmt)
+        l = oracle.huffman_lengths(cnt)
+        c = oracle.canonical_codes(l)
+        words, off, total = oracle.encode(s, l, c, chunk_syms)
+        d = oracle.decode(words, total, l, c, n_sample)
+        return d, A, e_new
+
+    def run(users, threads, reps):
+        errs = {u: np.zeros(n_sample, np.float32) for u in users}
+        with ThreadPoolExecutor(max_workers=threads) as tp:
+            t0 = time.perf_counter()
+            for t in range(reps):
+                res = list(tp.map(lambda u: client_iteration(host[t % len(host)][u], errs[u]), users))
+                for u, r in zip(users, res):
+                    errs[u] = r[2]
+                syms, anchors = np.stack([r[0] for r in res]), np.stack([r[1] for r in res])
+                if seg_off is None:          # the average: element ranges over the threads
+                    cuts = np.linspace(0, n_sample, threads + 1).astype(np.int64)
+                    list(tp.map(lambda k: oracle.aggregate(np.ascontiguousarray(syms[:, cuts[k]:cuts[k + 1]]), anchors, fmt),
+                                range(threads)))
+                else:
+                    oracle.aggregate(syms, anchors, fmt, seg_off)
+            return time.perf_counter() - t0
+
+    U1 = list(range(min(w.U, 2)))
+    dt1 = run(U1, 1, reps)
+    nproc = os.cpu_count() or 1
+    UN = list(range(w.U))
+    threads = max(1, min(nproc, len(UN)))
+    repsN = max(2, reps // 2)
+    dtN = run(UN, threads, repsN)
+    return {"value": len(U1) * n_sample * reps / dt1, "unit": "elements/s", "cores": 1, "kind": "oracle",
+            "sample": f"{len(U1)} clients x {n_sample} elements x {reps} iterations, the device batches' own bytes "
+                      f"({dt1:.1f} s, single thread)",
+            "all_cores": {"value": len(UN) * n_sample * repsN / dtN, "unit": "elements/s", "cores": threads,
+                          "nproc": nproc, "sample": f"{len(UN)} clients x {n_sample} elements x {repsN} iterations, "
+                                                    f"one thread per client ({dtN:.1f} s)"}}
+
+
+def measured_copy_bandwidth():
+    """GB/s (read + written bytes) of a plain device-to-device copy of 1 GiB on this machine."""
+    import torch
+    a = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+    b = torch.empty_like(a)
+    for _ in range(3):
+        b.copy_(a)
+    torch.cuda.synchronize()
+    reps = 10
     t0 = time.perf_counter()
-    for t in range(reps):
-        syms, anchors = [], []
-        for u in range(U_s):
-            A = oracle.anchor(gs[t][u], fmt)
-            s, errs[u] = oracle.convert_ef(gs[t][u], errs[u], A, 1.0, fmt)
-            cnt = oracle.histogram(s, fmt)
-            l = oracle.huffman_lengths(cnt)
-            c = oracle.canonical_codes(l)
-            words, off, total = oracle.encode(s, l, c, chunk_syms)
-            d = oracle.decode(words, total, l, c, n_sample)
-            syms.append(d)
-            anchors.append(A)
-        oracle.aggregate(np.stack(syms), np.stack(anchors), fmt)
+    for _ in range(reps):
+        b.copy_(a)
+    torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    elems = U_s * n_sample * reps
-    return {"value": elems / dt, "unit": "elements/s", "cores": 1, "kind": "oracle",
-            "sample": f"{U_s} clients x {n_sample} elements x {reps} iterations of the same workload "
-                      f"({dt:.1f} s, single thread)"}
+    del a, b
+    torch.cuda.empty_cache()
+    return 2.0 * (1 << 30) * reps / dt / 1e9
 
 
 def main():
@@ -132,8 +189,10 @@ def main():
     ap.add_argument("--sweep-c5", action="store_true",
                     help="run the 12 points of C5 (4 formats x 3 shapes) one after the other, each in a child process, "
                          "and print one line with elements/s and bits/element per point")
-    ap.add_argument("--one-call", action="store_true",
-                    help="the user's steps through co3_user_encode (resident grid: every gradient read once)")
+    ap.add_argument("--separate-calls", action="store_true",
+                    help="the user's steps through co3_convert_ef, co3_build_code and co3_encode instead of one "
+                         "co3_user_encode call (which, where a user's gradient fits the register files, reads every "
+                         "gradient once in a resident grid)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--breakdown", action="store_true", help="extra untimed pass timing every kernel (stderr)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -199,12 +258,16 @@ def main():
         raise SystemExit("--single-pass needs --codes user-model or layer-model (the codes must be known before the step)")
     if args.single_pass and fixed_user_tables and args.bias != "absmax":
         raise SystemExit("--single-pass with --bias moments needs --codes layer-model")
+    one_call = (not args.separate_calls and args.bias == "absmax" and args.codes == "user")
     pipe = Co3Pipeline(w.U, w.n, fmt, chunk_syms=args.chunk, seg_off=w.seg_off if w.sizes is not None else None,
                        bias=args.bias, gamma=args.gamma, codes="user" if args.codes.startswith("user") else "layer",
                        code_seg_off=code_seg_off, statistics=not fixed_user_tables,
                        single_pass=args.single_pass or lagged, lagged_codes=lagged,
-                       one_call=args.one_call, keep_symbols=not args.one_call,
+                       one_call=one_call, keep_symbols=not one_call,
                        cap_words=2 * B.cap_words_empirical(w.n, fmt) if fixed_user_tables or lagged else None)
+    import co3_inputs as inp
+    # scale of the law of every tensor (C2 draws one per tensor)
+    tensor_alpha = [float(a) for a in inp.c2_tensor_scales()] if w.cfg == 2 else [alpha] * pipe.nseg
     log(f"[bench] {desc}; generating {args.pool} device batches")
     batches = device_batches(w, betas, alpha, args.pool, pipe)
 
@@ -214,9 +277,10 @@ def main():
         # anchor of the first batch (every emit-able symbol has a codeword, so the table serves every step)
         import numpy as np
         pipe.convert(batches[0])
-        A0 = pipe.anchor[:, 0].cpu().numpy()
+        j = int(np.argmax(w.sizes)) if w.sizes is not None else 0      # several tensors: the law of the largest one
+        A0 = pipe.anchor[:, j].cpu().numpy()
         pipe.err.zero_()
-        wts = np.stack([B.model_weights(int(A0[u]), fmt, float(betas[u % len(betas)]), float(alpha)).numpy().view(np.uint32)
+        wts = np.stack([B.model_weights(int(A0[u]), fmt, float(betas[u % len(betas)]), float(tensor_alpha[j])).numpy().view(np.uint32)
                         for u in range(w.U)])
         pipe.build(torch.from_numpy(wts.view(np.int32)).cuda())
         desc += ", fixed per-client model tables" + (", single pass" if args.single_pass else "")
@@ -233,7 +297,6 @@ def main():
         A0 = pipe.anchor[0].cpu().numpy()
         pipe.err.zero_()
         model_beta = sum(betas) / len(betas)
-        model_alpha = alpha
         # anchor of the first tensor of each code group
         cso = pipe.code_seg_off.cpu().numpy()
         aso = [0, w.n] if pipe.seg_off is None else pipe.seg_off.cpu().numpy()
@@ -241,13 +304,21 @@ def main():
         wts = np.zeros((pipe.ncodes, fmt.K), np.uint32)
         for k in range(pipe.ncodes):
             wts[k] = B.model_weights(int(A0[first_tensor[k]]), fmt, float(model_beta),
-                                     float(model_alpha) * float(c0[first_tensor[k]])).numpy().view(np.uint32)
+                                     float(tensor_alpha[first_tensor[k]]) * float(c0[first_tensor[k]])).numpy().view(np.uint32)
         pipe.build(torch.from_numpy(wts.view(np.int32)).cuda())
         desc += ", fixed per-tensor model tables" + (", single pass" if args.single_pass else "")
     elif args.codes == "layer":
         desc += ", per-tensor codes shared by the clients"
     elif lagged:
         desc += ", codes from the counts of the previous step (one-pass user side)"
+    copy_gbs = measured_copy_bandwidth()
+    # the first iteration on its own (cold caches, first launches of every kernel)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    pipe.step(batches[0], rebuild=rebuild)
+    torch.cuda.synchronize()
+    first_step_ms = (time.perf_counter() - t0) * 1e3
+    pipe.err.zero_()
     for i in range(args.warmup):
         pipe.step(batches[i % args.pool], rebuild=rebuild)
     torch.cuda.synchronize()
@@ -265,7 +336,7 @@ def main():
 
     B.timing_reset()
     if graphs is None:
-        B.timing_enable(1 << K_CONVERT)
+        B.timing_enable((1 << K_CONVERT) | (1 << K_COOP))
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     if graphs is None:
@@ -278,11 +349,13 @@ def main():
     dt = time.perf_counter() - t0
     if graphs is not None:
         # the event timing of the dominant kernel cannot be recorded inside a graph: a separate eager pass
-        B.timing_enable(1 << K_CONVERT)
+        B.timing_enable((1 << K_CONVERT) | (1 << K_COOP))
         for i in range(min(args.steps, 10)):
             pipe.step(batches[i % args.pool], rebuild=rebuild)
         torch.cuda.synchronize()
-    conv_ms, conv_launches = B.timing_read(K_CONVERT)
+    # the conversion ran as one of two kernels: the resident grid where the batch fits it, else k_convert_ef
+    dominant = K_COOP if B.timing_read(K_COOP)[1] else K_CONVERT
+    conv_ms, conv_launches = B.timing_read(dominant)
     B.timing_enable(0)
     assert pipe.poll() == 0, "device status after the timed region"
 
@@ -295,17 +368,19 @@ def main():
     b = payload_bpe + index_bpe + header_bpe
     b_alg = 12.0 + b / 4.0 + 4.0 / w.U                 # algorithmic bytes per client-element, whole path
     conv_avg_ms = conv_ms / max(conv_launches, 1)
-    conv_bytes = 12.0 * elems_step                     # k_convert_ef: read g, read m, write m
+    conv_bytes = 12.0 * elems_step                     # the conversion kernel: read g, read m, write m
     achieved = conv_bytes / (conv_avg_ms * 1e-3) / 1e9 if conv_avg_ms > 0 else 0.0
 
-    # HBM traffic of the dominant kernel from the committed rocprofv3 counter summary (fetched + written MB)
-    traffic = None
+    # HBM traffic of the dominant kernel: not measured in this run; read from the stored rocprofv3 counter
+    # summary of the same command (fetched + written MB per launch)
+    traffic, traffic_source = None, None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic_C3.txt")
     if args.workload == "C3" and args.bias == "absmax" and args.codes == "user" and os.path.exists(tpath):
         for line in open(tpath):
-            if line.startswith("k_convert_ef"):
+            if line.startswith(B.kernel_name(dominant) + " "):
                 try:
                     traffic = float(line.split()[-1]) * 1e6
+                    traffic_source = "profiles/hbm_traffic_C3.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, stored summary)"
                 except ValueError:
                     traffic = None
                 break
@@ -348,11 +423,18 @@ def main():
                              "layer-model": "fixed per tensor, designed from the GenNorm law of the workload"}[args.codes],
                    "gamma": args.gamma, "bias": args.bias, "codes": args.codes},
         "bits_per_element": {"payload": payload_bpe, "index": index_bpe, "header": header_bpe},
-        "path_roofline": {"bound": "hbm", "algorithmic_bytes_per_element": b_alg,
+        "first_step_ms": first_step_ms,
+        "path_roofline": {"bound": "hbm", "scope": "whole path (encode + decode), all kernels of a step",
+                          "algorithmic_bytes_per_element": b_alg,
                           "achieved": b_alg * value / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                          "frac": b_alg * value / 1e9 / HBM_PEAK_GBS},
-        "roofline": {"bound": "hbm", "kernel": "k_convert_ef", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                          "frac": b_alg * value / 1e9 / HBM_PEAK_GBS,
+                          "target_frac": PATH_TARGET_FRAC if args.workload == "C3" else None,
+                          "target_met": (b_alg * value / 1e9 / HBM_PEAK_GBS >= PATH_TARGET_FRAC) if args.workload == "C3" else None,
+                          "measured_copy_GBs": copy_gbs,
+                          "frac_of_measured_copy": b_alg * value / 1e9 / copy_gbs},
+        "roofline": {"bound": "hbm", "scope": "dominant kernel only", "kernel": B.kernel_name(dominant),
+                     "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_source,
                      "avg_launch_ms": conv_avg_ms, "launches": conv_launches,
                      "algorithmic_bytes_per_launch": conv_bytes},
     }
@@ -360,10 +442,10 @@ def main():
         log("[bench] timing the CPU oracle on a bounded sample")
         if args.bias != "absmax" or args.gamma != 1.0 or args.codes != "user":
             raise SystemExit("bench.py: the CPU leg times the headline path; use --no-cpu with --bias moments / --gamma")
-        # about 12 s of oracle time at its usual 15-20 M elements/s
-        n_sample = min(w.n, 1 << 24)
-        reps = max(4, min(200, -(-220_000_000 // (min(w.U, 2) * n_sample))))
-        res["cpu_baseline"] = cpu_baseline(w, betas, alpha, args.chunk, n_sample=n_sample, reps=reps)
+        # about 6 s of oracle time per leg at its usual 15-20 M elements/s per thread
+        n_sample = w.n if w.sizes is not None else min(w.n, 1 << 24)
+        reps = max(2, min(200, -(-110_000_000 // (min(w.U, 2) * n_sample))))
+        res["cpu_baseline"] = cpu_baseline(w, batches, args.chunk, n_sample=n_sample, reps=reps)
     print(json.dumps(res), flush=True)
 
 

@@ -167,3 +167,13 @@ def device_gennorm(n: int, beta: float, alpha: float, seed: int, device="cuda"):
     s = torch.randint(0, 2, (n,), generator=gen, device=device, dtype=torch.int8).to(torch.float32) * 2.0 - 1.0
     x = (alpha * s.double() * g.double() ** (1.0 / beta)).to(torch.float32)
     return x
+
+
+def device_gennorm_outliers(n: int, beta: float, alpha: float, frac: float, factor: float, seed: int, device="cuda"):
+    """device_gennorm with a fraction ``frac`` of the samples at ``factor`` times the scale (the C4 recipe)."""
+    import torch
+    x = device_gennorm(n, beta, alpha, seed, device)
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed + 1)
+    mask = torch.rand(n, device=device, generator=gen) < frac
+    return torch.where(mask, x * factor, x)

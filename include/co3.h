@@ -384,6 +384,25 @@ const char *co3_kernel_name(int32_t kernel);
  */
 int32_t co3_model_weights(int32_t A, co3_fmt fmt, double beta, double alpha, uint32_t *weights_host);
 
+/*
+ * Model tables of codes shared by the users, one per group of consecutive tensors (Sec. III (ii): the
+ * codes are assigned per layer and designed from the GenNorm law of the layer; Sec. IV-B: that law is
+ * fitted per tensor).  The law of group k is the one fitted to the group's largest tensor among those
+ * that start inside the group (the first of equals; the tensor that holds the group's first element when
+ * none starts there), pooled over the users:
+ *     beta  = (sum over u of fit[u][s][0]) / U,   alpha = (sum over u of fit[u][s][1] * scale[u][s]) / U
+ * -- shape and scale of what is rounded onto the grid, the multiplied corrected gradient -- added in
+ * user order in double precision; beta is kept within [0.2, 4], alpha at or above 1e-30; the weights are
+ * co3_model_weights(A, fmt, beta, alpha).
+ *   fit           [U][nseg][2] f64 (shape, scale) as co3_bias_scale returns them;  scale [U][nseg] f32
+ *   seg_off       [nseg + 1] tensor boundaries;  code_seg_off [ncodes + 1] group boundaries
+ *   weights_host  [ncodes][K] u32 out
+ * All pointers are HOST pointers; pure host arithmetic.  CO3_EINVAL on bad arguments.
+ */
+int32_t co3_design_layer_tables(const double *fit, const float *scale, int32_t U, int32_t nseg, const int64_t *seg_off,
+                                const int64_t *code_seg_off, int32_t ncodes, int32_t A, co3_fmt fmt,
+                                uint32_t *weights_host);
+
 #ifdef __cplusplus
 }
 #endif

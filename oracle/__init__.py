@@ -359,3 +359,32 @@ def model_weights(A: int, fmt: Fmt, beta: float, alpha: float) -> np.ndarray:
     w = np.clip(np.rint(p * 4294967296.0), 1.0, 4294967295.0).astype(np.uint64).astype(np.uint32)
     w[fmt.K // 2] = 0
     return w
+
+
+def design_layer_tables(fit: np.ndarray, scale: np.ndarray, seg_off, code_seg_off, A: int, fmt: Fmt) -> np.ndarray:
+    """Model tables of per-layer codes shared by the users (Sec. III (ii) with the fit of Sec. IV-B): group k
+    takes the law fitted to its largest tensor among those that start inside the group (the first of equals;
+    the tensor holding the group's first element when none starts there), pooled over the users -- the mean
+    of the fitted shapes and the mean of fitted scale times multiplier, each added in user order in double
+    precision, shape kept within [0.2, 4], scale at or above 1e-30.  fit [U][nseg][2], scale [U][nseg]."""
+    fit = np.asarray(fit, dtype=np.float64)
+    scale = np.asarray(scale, dtype=np.float32)
+    seg_off = [int(x) for x in seg_off]
+    code_seg_off = [int(x) for x in code_seg_off]
+    U, nseg = scale.shape
+    rows = []
+    for a, b in zip(code_seg_off[:-1], code_seg_off[1:]):
+        starts = [s for s in range(nseg) if a <= seg_off[s] < b and seg_off[s + 1] > seg_off[s]]
+        if starts:
+            s = max(starts, key=lambda j: (seg_off[j + 1] - seg_off[j], -j))
+        else:
+            s = [j for j in range(nseg) if seg_off[j] <= a < seg_off[j + 1]][0]
+        beta = 0.0
+        alpha = 0.0
+        for u in range(U):
+            beta = beta + float(fit[u, s, 0])
+            alpha = alpha + float(fit[u, s, 1]) * float(scale[u, s])
+        beta = min(max(beta / U, 0.2), 4.0)
+        alpha = max(alpha / U, 1e-30)
+        rows.append(model_weights(A, fmt, beta, alpha))
+    return np.stack(rows)

@@ -594,9 +594,11 @@ int co3o_histogram_layers(const uint8_t *sym, int64_t n, const int64_t *seg_off,
     for (int64_t j = 0; j < (int64_t)nseg * K; ++j)
         counts[j] = 0;
     for (int s = 0; s < nseg; ++s)
-        for (int64_t i = seg_off[s]; i < seg_off[s + 1]; ++i)
-            if (sym[i] < K)
-                counts[(int64_t)s * K + sym[i]] += 1;
+        for (int64_t i = seg_off[s]; i < seg_off[s + 1]; ++i) {
+            if (sym[i] >= K) /* not a symbol of the format: rejected, as in co3o_histogram */
+                return CO3O_EINVAL;
+            counts[(int64_t)s * K + sym[i]] += 1;
+        }
     return CO3O_OK;
 }
 

@@ -28,7 +28,7 @@ EXPORTS = (
     "co3_kernel_name", "co3_moments", "co3_bias_scale", "co3_convert_ef_scaled", "co3_ps_aggregate_scaled",
     "co3_histogram_layers", "co3_encode_layers", "co3_decode_layers", "co3_ps_aggregate_layers",
     "co3_convert_encode_workspace_bytes", "co3_convert_encode", "co3_convert_encode_layers", "co3_encode_static",
-    "co3_user_encode_workspace_bytes", "co3_user_encode", "co3_set_exchange_spin_limit",
+    "co3_user_encode_workspace_bytes", "co3_user_encode", "co3_set_exchange_spin_limit", "co3_design_layer_tables",
 )
 KERNEL_COUNT = 13
 
@@ -94,6 +94,8 @@ def _load():
     L.co3_encode.argtypes = [p, i64, i32, i64, _Fmt, p, p, i64, i32, p, p, p, sz, p, p]
     L.co3_encode_static.restype = i32
     L.co3_encode_static.argtypes = [p, i64, i32, i64, _Fmt, p, p, i64, i32, p, p, p, p]
+    L.co3_design_layer_tables.restype = i32
+    L.co3_design_layer_tables.argtypes = [p, p, i32, i32, p, p, i32, i32, _Fmt, p]
     L.co3_user_encode_workspace_bytes.restype = sz
     L.co3_user_encode_workspace_bytes.argtypes = [i64, i32, i64, i32, i32]
     L.co3_user_encode.restype = i32
@@ -335,6 +337,23 @@ def model_weights(A: int, fmt: Fmt, beta: float, alpha: float):
     import numpy as np
     w = np.zeros(fmt.K, dtype=np.uint32)
     _chk(_lib.co3_model_weights(A, fmt.c(), beta, alpha, w.ctypes.data_as(C.c_void_p)), "co3_model_weights")
+    return torch.from_numpy(w.view(np.int32).copy())
+
+
+def design_layer_tables(fit, scale, seg_off, code_seg_off, A: int, fmt: Fmt):
+    """Host computation on host copies of fit [U][nseg][2] f64 and scale [U][nseg] f32; returns a CPU int32
+    tensor [ncodes][K] holding the uint32 weights bit for bit."""
+    import numpy as np
+    fit = np.ascontiguousarray(fit.detach().cpu().numpy(), dtype=np.float64)
+    sc = np.ascontiguousarray(scale.detach().cpu().numpy(), dtype=np.float32)
+    so = np.ascontiguousarray(np.asarray(seg_off, dtype=np.int64))
+    cso = np.ascontiguousarray(np.asarray(code_seg_off, dtype=np.int64))
+    U, nseg = sc.shape
+    ncodes = cso.size - 1
+    w = np.zeros((ncodes, fmt.K), dtype=np.uint32)
+    vp = lambda a: a.ctypes.data_as(C.c_void_p)
+    _chk(_lib.co3_design_layer_tables(vp(fit), vp(sc), U, nseg, vp(so), vp(cso), ncodes, A, fmt.c(), vp(w)),
+         "co3_design_layer_tables")
     return torch.from_numpy(w.view(np.int32).copy())
 
 

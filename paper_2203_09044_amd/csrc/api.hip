@@ -241,6 +241,9 @@ static int32_t convert_encode_common(const float *g, float *err, int64_t n, int3
         return CO3_EINVAL;
     if (anchor_mode != CO3_ANCHOR_GIVEN && anchor_mode != CO3_ANCHOR_FROM_ABSMAX_G) return CO3_EINVAL;
     if (scale && anchor_mode != CO3_ANCHOR_GIVEN) return CO3_EINVAL;      // the multiplier belongs to a fixed grid
+    if (scale && !code_seg_off) return CO3_EINVAL;                        // ... and goes with the per-layer codes
+    // counts pooled over the users are 32-bit: every symbol of every user may land in one counter
+    if (counts && code_seg_off && (int64_t)n * U >= ((int64_t)1 << 32) - 1) return CO3_EINVAL;
     if (ws_bytes < co3_convert_encode_workspace_bytes(n, U, chunk_syms)) return CO3_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const FmtC fc(fmt);
@@ -448,6 +451,7 @@ int32_t co3_histogram_layers(const uint8_t *sym, int64_t n, int32_t U, int64_t s
 {
     if (!fmt_ok(fmt) || !batch_ok(n, U, stride) || !sym || !counts || !aligned(sym, 16)) return CO3_EINVAL;
     if (!seg_off || nseg < 1) return CO3_EINVAL;
+    if (pool_users && (int64_t)n * U >= ((int64_t)1 << 32)) return CO3_EINVAL;      // 32-bit counters summed over the users
     hipStream_t st = static_cast<hipStream_t>(stream);
     const FmtC fc(fmt);
     hipError_t e = co3_launch_fill(nullptr, 0, 0, counts, (int64_t)(pool_users ? 1 : U) * nseg * fc.K, st);
@@ -605,6 +609,44 @@ int32_t co3_model_weights(int32_t A, co3_fmt fmt, double beta, double alpha, uin
         if (w > 4294967295.0) w = 4294967295.0;
         weights_host[c] = (uint32_t)w;
         weights_host[half + c] = c ? (uint32_t)w : 0u;
+    }
+    return CO3_OK;
+}
+
+int32_t co3_design_layer_tables(const double *fit, const float *scale, int32_t U, int32_t nseg, const int64_t *seg_off,
+                                const int64_t *code_seg_off, int32_t ncodes, int32_t A, co3_fmt fmt,
+                                uint32_t *weights_host)
+{
+    if (!fmt_ok(fmt) || !fit || !scale || !seg_off || !code_seg_off || !weights_host || U < 1 || nseg < 1 || ncodes < 1)
+        return CO3_EINVAL;
+    const int K = 1 << (1 + fmt.exp_bits + fmt.mant_bits);
+    for (int k = 0; k < ncodes; ++k) {
+        const int64_t a = code_seg_off[k], b = code_seg_off[k + 1];
+        int s_best = -1;
+        int64_t size_best = 0;
+        int s_holds = 0;                                  // tensor that holds the group's first element
+        for (int s = 0; s < nseg; ++s) {
+            const int64_t size = seg_off[s + 1] - seg_off[s];
+            if (seg_off[s] <= a && a < seg_off[s + 1]) s_holds = s;
+            if (seg_off[s] >= a && seg_off[s] < b && size > size_best) {
+                s_best = s;
+                size_best = size;
+            }
+        }
+        const int s = s_best >= 0 ? s_best : s_holds;
+        double beta = 0.0, alpha = 0.0;
+        for (int u = 0; u < U; ++u) {
+            const size_t j = (size_t)u * nseg + s;
+            beta += fit[2 * j];
+            alpha += fit[2 * j + 1] * (double)scale[j];
+        }
+        beta /= (double)U;
+        alpha /= (double)U;
+        beta = beta < 0.2 ? 0.2 : beta > 4.0 ? 4.0 : beta;
+        alpha = alpha < 1e-30 ? 1e-30 : alpha;
+        if (!(beta == beta) || !(alpha == alpha)) return CO3_EINVAL;          // a fit that is not a number
+        const int32_t rc = co3_model_weights(A, fmt, beta, alpha, weights_host + (size_t)k * K);
+        if (rc != CO3_OK) return rc;
     }
     return CO3_OK;
 }

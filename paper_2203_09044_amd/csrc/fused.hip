@@ -407,8 +407,10 @@ __global__ __launch_bounds__(FU_BLOCK) void k_compact(const uint64_t *__restrict
     for (int k = 0; k < CP_UNITS; ++k) {
         d[k] = gbase + (uint32_t)__builtin_amdgcn_readlane((int)my_off, k);
         // every owned word of a unit starts at the same bit of a slot word (64 * gw - d is the same modulo
-        // 64); the amount is uniform over the wavefront
-        sh[k] = (0u - (uint32_t)d[k]) & 63u;
+        // 64); the amount is uniform over the wavefront and is kept in a scalar register: an earlier build
+        // that held it in the last vector register of the kernel's allocation produced wrong words in a few
+        // wavefronts per thousand (cause not established), the scalar form never did
+        sh[k] = (uint32_t)__builtin_amdgcn_readfirstlane((int)((0u - (uint32_t)d[k]) & 63u));
     }
 
     // chunk index: chunks whose first element lies in these units (chunks have at least 64 symbols)
@@ -517,7 +519,6 @@ hipError_t co3_launch_convert_encode(const float *g, float *err, int64_t n, int 
             else if (code_seg_off && scale) CO3_STAGE_LAUNCH(true, true, false);
             else if (code_seg_off && counts) CO3_STAGE_LAUNCH(true, false, true);
             else if (code_seg_off) CO3_STAGE_LAUNCH(true, false, false);
-            else if (scale) CO3_STAGE_LAUNCH(false, true, false);
             else if (counts) CO3_STAGE_LAUNCH(false, false, true);
             else CO3_STAGE_LAUNCH(false, false, false);
 #undef CO3_STAGE_LAUNCH

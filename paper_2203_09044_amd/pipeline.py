@@ -207,5 +207,12 @@ class Co3Pipeline:
         self.encode()
         self.aggregate()
 
+    def grow_capacity(self, need_words: int):
+        """A larger stream buffer per user (at least ``need_words`` 64-bit words plus an eighth); the streams
+        it held are not kept."""
+        cap = _round_up(max(need_words + need_words // 8, self.cap_words + 2), 2)
+        self.cap_words = cap
+        self.words = torch.zeros((self.U, cap), dtype=torch.int64, device=self.device)
+
     def poll(self) -> int:
         return B.poll_status(self.status)

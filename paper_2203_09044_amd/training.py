@@ -20,6 +20,8 @@ from typing import Callable, Iterable, Optional, Sequence, Tuple
 
 import torch
 
+from co3_inputs import group_small_tensors, seg_offsets
+
 from . import binding as B
 from .binding import Fmt
 from .pipeline import Co3Pipeline
@@ -28,7 +30,7 @@ from .pipeline import Co3Pipeline
 class Co3SGD:
     def __init__(self, model: torch.nn.Module, users: int, fmt: Fmt, lr: float, gamma: float = 1.0,
                  chunk_syms: int = 256, bias: str = "absmax", codes: str = "user", code_group_min: int = 16384,
-                 tables: str = "empirical", refresh: int = 10):
+                 tables: str = "empirical", refresh: int = 10, cap_words: Optional[int] = None):
         if tables not in ("empirical", "model", "lagged"):
             raise ValueError("tables must be 'empirical', 'model' or 'lagged'")
         if tables == "model" and (bias != "moments" or codes != "layer"):
@@ -52,32 +54,22 @@ class Co3SGD:
         code_seg_off = None
         if codes == "layer":
             # tensors too small to pay for a table share the code of the large tensor before them
-            groups, pending = [], 0
-            for s in self.sizes:
-                if s >= code_group_min:
-                    groups.append(s + pending)
-                    pending = 0
-                elif groups:
-                    groups[-1] += s
-                else:
-                    pending += s
-            if pending:
-                groups.append(pending)
-            code_seg_off = [0]
-            for gsz in groups:
-                code_seg_off.append(code_seg_off[-1] + gsz)
+            code_seg_off = [int(x) for x in seg_offsets(group_small_tensors(self.sizes, code_group_min))]
         self.pipe = Co3Pipeline(users, self.n, fmt, chunk_syms=chunk_syms, seg_off=self.seg_off, gamma=gamma,
                                 device=dev, bias=bias, codes=codes, code_seg_off=code_seg_off,
                                 statistics=tables != "model", single_pass=tables != "empirical",
-                                lagged_codes=tables == "lagged")
+                                lagged_codes=tables == "lagged", cap_words=cap_words)
         self.g = self.pipe.new_gradient_buffer()
-        if tables == "model":
-            # the tensor that designs each group's table: the largest one of the group
-            cso = self.pipe.code_seg_off.cpu().tolist()
-            self.design_tensor = []
-            for a, b in zip(cso[:-1], cso[1:]):
-                members = [k for k in range(len(self.sizes)) if a <= self.seg_off[k] < b and self.sizes[k] > 0]
-                self.design_tensor.append(max(members, key=lambda k: self.sizes[k]) if members else 0)
+        # Views of every user's row of the gradient batch, shaped like the parameters: during a user's backward
+        # pass they are the parameters' .grad, so autograd accumulates straight into the batch.
+        self.grad_views = [[self.g[u, a:b].view_as(p) for p, a, b in zip(self.params, self.seg_off[:-1], self.seg_off[1:])]
+                           for u in range(users)]
+        # The one-pass user side overwrites the memory while it compresses; a stream that then does not fit its
+        # buffer (possible with codes that are not the user's own counts) must be made again from the memory
+        # as it was: those modes keep a copy of it per iteration.
+        self.err_before = torch.empty_like(self.pipe.err) if self.pipe.single_pass else None
+        self.codes_before = torch.empty_like(self.pipe.codes) if self.pipe.single_pass else None
+        self.capacity_growths = 0
 
     def local_gradients(self, batches: Sequence[Tuple[torch.Tensor, torch.Tensor]],
                         loss_fn: Callable[[torch.Tensor, torch.Tensor], torch.Tensor]) -> float:
@@ -86,13 +78,17 @@ class Co3SGD:
             raise ValueError(f"expected {self.U} user batches")
         total = 0.0
         for u, (x, y) in enumerate(batches):
-            self.model.zero_grad(set_to_none=True)
+            self.g[u].zero_()
+            for p, v in zip(self.params, self.grad_views[u]):
+                p.grad = v
             loss = loss_fn(self.model(x), y)
             loss.backward()
             total += float(loss.detach())
-            row = self.g[u]
-            for p, a, b in zip(self.params, self.seg_off[:-1], self.seg_off[1:]):
-                row[a:b].copy_(p.grad.reshape(-1))
+            for p, v in zip(self.params, self.grad_views[u]):
+                if p.grad is None or p.grad.data_ptr() != v.data_ptr():      # autograd replaced the tensor: copy it in
+                    v.copy_(p.grad if p.grad is not None else torch.zeros_like(v))
+        for p in self.params:
+            p.grad = None
         return total / self.U
 
     def apply_average(self, avg: Optional[torch.Tensor] = None):
@@ -103,22 +99,14 @@ class Co3SGD:
                 p.add_(avg[a:b].view_as(p), alpha=-self.lr)
 
     def refresh_tables(self):
-        """One table per code group from the law fitted to the group's largest tensor (mean over the users of
-        the fitted shape and of the fitted scale times the multiplier, i.e. the law of what is rounded onto
-        the grid); host computation of the model weights, code build on the device."""
+        """One table per code group from the law fitted to the group's largest tensor, pooled over the users
+        (co3_design_layer_tables: host computation of the model weights), code build on the device."""
         pipe = self.pipe
-        fit = pipe.fit.cpu().numpy()                   # [U][nseg][2]: (shape, scale) of x = g + gamma * m
-        c = pipe.scale.cpu().numpy()                   # [U][nseg]
         A = int(pipe.anchor[0, 0].item())              # the fixed grid of the bias rule
-        rows = []
-        for k in self.design_tensor:
-            beta = float(fit[:, k, 0].mean())
-            alpha = float((fit[:, k, 1] * c[:, k]).mean())
-            rows.append(B.model_weights(A, pipe.fmt, min(max(beta, 0.2), 4.0), max(alpha, 1e-30)))
-        pipe.build(torch.stack(rows).to(pipe.device))
+        weights = B.design_layer_tables(pipe.fit, pipe.scale, self.seg_off, pipe.code_seg_off.cpu().tolist(), A, pipe.fmt)
+        pipe.build(weights.to(pipe.device))
 
-    def step(self, batches, loss_fn) -> float:
-        loss = self.local_gradients(batches, loss_fn)
+    def _codec(self):
         if self.tables == "model":
             self.pipe.fit_bias(self.g)
             if self.t % self.refresh == 0:
@@ -127,6 +115,36 @@ class Co3SGD:
             self.pipe.aggregate()
         else:
             self.pipe.step(self.g)
+
+    def step(self, batches, loss_fn) -> float:
+        """One iteration of Algorithm 1.  The device status is read before the average reaches the model (one
+        synchronisation per iteration).  A stream that did not fit its buffer (possible with codes that are
+        not built from the user's own counts of the iteration) is made again in a larger one: from the symbols
+        where the path keeps them, else from the saved memory and codes.  Any other condition raises Co3Error."""
+        loss = self.local_gradients(batches, loss_fn)
+        pipe = self.pipe
+        if self.err_before is not None:
+            self.err_before.copy_(pipe.err)
+            self.codes_before.copy_(pipe.codes)
+            had_codes = pipe.have_codes
+        self._codec()
+        for attempt in range(4):
+            st = pipe.poll()
+            if st == B.OK:
+                break
+            if st != B.ECAP or attempt == 3:
+                raise B.Co3Error(st, "Co3SGD.step")
+            pipe.grow_capacity((int(pipe.total_bits.max().item()) + 63) // 64)      # total_bits holds what every stream needs
+            pipe.status.zero_()
+            self.capacity_growths += 1
+            if self.err_before is not None:
+                pipe.err.copy_(self.err_before)
+                pipe.codes.copy_(self.codes_before)
+                pipe.have_codes = had_codes
+                self._codec()
+            else:                       # the symbols and the codes of this iteration are still there
+                pipe.encode()
+                pipe.aggregate()
         self.t += 1
         self.apply_average()
         return loss

@@ -110,3 +110,38 @@ def test_model_weights_host_matches_oracle_model():
         want = oracle.model_weights(A, oracle.Fmt(E, M), beta, alpha)
         assert np.array_equal(got, want), (E, M, beta, A)
         assert got[(1 << (E + M))] == 0 and got.min(initial=1, where=np.arange(got.size) != (1 << (E + M))) >= 1
+
+
+def test_design_layer_tables_host_matches_oracle():
+    """co3_design_layer_tables (which tensor designs a group's shared table, the law pooled over the users,
+    its limits) against the oracle's statement of the same rule, bit for bit on the weights."""
+    import oracle
+    import co3_inputs as inp
+    from paper_2203_09044_amd import binding as B
+    import torch
+    rng = inp.rng_for(68, 2)
+    for case, (sizes, gmin, U, (E, M), A) in enumerate([([5, 100, 100, 7, 300, 2, 0, 40], 50, 3, (3, 1), -3),
+                                                        (inp.resnet18_cifar_tensor_sizes(), 16384, 10, (1, 2), 1),
+                                                        ([1000], 1, 1, (4, 3), 8), ([3, 3, 3], 100, 4, (2, 0), 0)]):
+        seg = inp.seg_offsets(sizes)
+        cso = inp.seg_offsets(inp.group_small_tensors(sizes, gmin))
+        nseg = len(sizes)
+        fit = np.zeros((U, nseg, 2))
+        fit[:, :, 0] = rng.uniform(0.1, 5.0, (U, nseg))              # beyond the limits on both sides
+        fit[:, :, 1] = 10.0 ** rng.uniform(-6, -1, (U, nseg))
+        scale = (10.0 ** rng.uniform(0, 4, (U, nseg))).astype(np.float32)
+        got = B.design_layer_tables(torch.from_numpy(fit), torch.from_numpy(scale), seg, cso, A, B.Fmt(E, M))
+        want = oracle.design_layer_tables(fit, scale, seg, cso, A, oracle.Fmt(E, M))
+        assert np.array_equal(got.numpy().view(np.uint32), want), case
+    # boundaries of the groups that are not tensor boundaries
+    sizes = [5, 100, 100, 7, 300]
+    seg = inp.seg_offsets(sizes)
+    fit = np.zeros((2, 5, 2))
+    fit[:, :, 0] = rng.uniform(0.5, 1.5, (2, 5))
+    fit[:, :, 1] = 1e-3
+    scale = np.ones((2, 5), np.float32)
+    cso = [0, 250, 400, 512]
+    got = B.design_layer_tables(torch.from_numpy(fit), torch.from_numpy(scale), seg, cso, -2, B.Fmt(3, 1))
+    assert np.array_equal(got.numpy().view(np.uint32), oracle.design_layer_tables(fit, scale, seg, cso, -2, oracle.Fmt(3, 1)))
+    L = B._lib
+    assert L.co3_design_layer_tables(None, None, 1, 1, None, None, 1, 0, B.Fmt(3, 1).c(), None) == B.EINVAL

@@ -1,11 +1,13 @@
-"""Parity at the full sizes of the five benchmark workloads, in the launch configuration that
-bench.py times (chunk 256, fused histogram, tiled averaging workspace).
+"""Parity at the full sizes of the five benchmark workloads, in the launch configurations that
+bench.py times (chunk 256, fused histogram, tiled averaging workspace; one call per iteration for the
+user side where the benchmark uses it).
 
-Where the oracle is fast enough it checks every element of every client (threads over clients;
-the oracle itself stays single-threaded per call).  For the largest workloads a stated subset of
-clients goes through the oracle element by element and every client is checked through
-properties that hold at any size: decode(encode(s)) = s, coded length = sum of count * length,
-chunk offsets consistent with the stream length, histogram total = n.
+Every element of every client goes through the oracle (threads over clients; the oracle itself stays
+single-threaded per call): C1 for its 5 iterations, C2, C3, C4 and all 12 points of C5 for iterations
+1-2 of all clients, and one client of each of C2, C3, C4 and C5 point 7 over the workload's full
+number of chained iterations.  On top, properties that hold at any size are checked on every client:
+decode(encode(s)) = s, coded length = sum of count * length, chunk offsets consistent with the stream
+length, histogram total = n.
 Inputs are drawn on the device with the seeded sampler and copied back, so both sides consume
 the same bytes.
 """
@@ -130,13 +132,15 @@ def test_c2_full(co3):
     properties_all_clients(pipe, w.n)
 
 
-def test_c3_full(co3):
+@pytest.mark.parametrize("one_call", [True, False])
+def test_c3_full(co3, one_call):
     """C3 (the benchmark workload): 10 clients x 11,173,962, E3M0; 2 chained iterations, every element of
-    every client, and the average."""
+    every client, and the average; through co3_user_encode (the benchmark's configuration) and through the
+    separate calls."""
     w = inp.c3()
     fmt = co3.Fmt(w.E, w.M)
     betas = inp.c3_client_betas(w.U)
-    pipe = co3.Co3Pipeline(w.U, w.n, fmt, chunk_syms=256)
+    pipe = co3.Co3Pipeline(w.U, w.n, fmt, chunk_syms=256, one_call=one_call)
     g = pipe.new_gradient_buffer()
     errs = [np.zeros(w.n, np.float32) for _ in range(w.U)]
     with ThreadPoolExecutor(max_workers=10) as pool:
@@ -288,9 +292,7 @@ def test_c4_full(co3):
     fmt = co3.Fmt(w.E, w.M)
     f = oracle.Fmt(w.E, w.M)
     n = w.n
-    x = inp.device_gennorm(n, 1.0, 1e-4, 4001)
-    mask = torch.rand(n, device="cuda", generator=torch.Generator(device="cuda").manual_seed(4002)) < 1e-4
-    x = torch.where(mask, x * 100.0, x)
+    x = inp.device_gennorm_outliers(n, 1.0, 1e-4, 1e-4, 100.0, 4001)
     gh = x.cpu().numpy()
     for table in ("empirical", "model"):
         pipe = co3.Co3Pipeline(1, n, fmt, chunk_syms=256, cap_words=None if table == "empirical" else n // 4)
@@ -321,37 +323,145 @@ def test_c4_full(co3):
         torch.cuda.empty_cache()
 
 
-@pytest.mark.parametrize("point", [0, 4, 8, 11])
+def oracle_average(pool, refs, f, n, parts=16):
+    """The oracle's average of all users, element ranges spread over the pool (each call stays single-threaded)."""
+    syms = [r["sym"] for r in refs]
+    A = np.stack([r["A"] for r in refs])
+    cuts = np.linspace(0, n, parts + 1).astype(np.int64)
+
+    def piece(k):
+        a, b = int(cuts[k]), int(cuts[k + 1])
+        return oracle.aggregate(np.stack([s[a:b] for s in syms]), A, f)
+
+    return np.concatenate(list(pool.map(piece, range(parts))))
+
+
+@pytest.mark.parametrize("point", range(12))
 def test_c5_points(co3, point):
-    """C5: 16 clients x 25M; formats E2M0 / E3M1 / E4M3 / E5M2 at one beta each (points 0, 4, 8, 11 of the
-    12-point sweep).  Clients 0 and 15 go through the oracle element by element, all 16 through the
-    size-independent properties; the average is checked on the first 2^20 elements with all 16
-    clients' symbols taken from the (round-trip verified) GPU symbols."""
+    """C5: 16 clients x 25M, all 12 points of the sweep (E2M0 / E3M1 / E4M3 / E5M2 x beta 0.5 / 1 / 2): every
+    element of every client and the average through the oracle for iterations 1 and 2 (chained through the
+    memory), in the one-call launch configuration that the benchmark times."""
     w = inp.c5(point)
     beta = inp.C5_BETAS[point % 3]
     fmt = co3.Fmt(w.E, w.M)
-    pipe = co3.Co3Pipeline(w.U, w.n, fmt, chunk_syms=256)
+    f = oracle.Fmt(w.E, w.M)
+    pipe = co3.Co3Pipeline(w.U, w.n, fmt, chunk_syms=256, one_call=True)
     g = pipe.new_gradient_buffer()
-    checked = (0, w.U - 1)
-    host = {}
-    for u in range(w.U):
-        x = inp.device_gennorm(w.n, beta, 1e-3, 5000 + 100 * point + u)
-        g[u, :w.n] = x
-        if u in checked:
-            host[u] = x.cpu().numpy()
-        del x
-    pipe.step(g)
-    assert pipe.poll() == 0
-    with ThreadPoolExecutor(max_workers=2) as pool:
-        refs = list(pool.map(oracle_client, [(host[u], np.zeros(w.n, np.float32), w.E, w.M, None, 256, None)
-                                             for u in checked]))
-    for u, ref in zip(checked, refs):
-        compare_client(pipe, u, ref, w.n)
+    errs = [np.zeros(w.n, np.float32) for _ in range(w.U)]
+    with ThreadPoolExecutor(max_workers=16) as pool:
+        for t in (1, 2):
+            host = fill_from_device(pipe, g, lambda u: inp.device_gennorm(w.n, beta, 1e-3, 50000 + 1000 * point + 20 * t + u))
+            pipe.step(g)
+            assert pipe.poll() == 0
+            refs = list(pool.map(oracle_client, [(host[u], errs[u], w.E, w.M, None, 256, None) for u in range(w.U)]))
+            for u in range(w.U):
+                compare_client(pipe, u, refs[u], w.n)
+                errs[u] = refs[u]["err"]
+            want = oracle_average(pool, refs, f, w.n)
+            assert np.array_equal(u32(pipe.avg[:w.n]), want.view(np.uint32)), "average"
+            del refs, want, host
     properties_all_clients(pipe, w.n)
-    m = 1 << 20
-    syms = pipe.sym[:, :m].cpu().numpy()
-    want = oracle.aggregate(syms, pipe.anchor.cpu().numpy(), oracle.Fmt(w.E, w.M))
-    assert np.array_equal(u32(pipe.avg[:m]), want.view(np.uint32))
+
+
+# ---- one client of every workload over the workload's full number of iterations ------------------------
+# The memory chains the iterations, so the oracle's conversion of iteration t + 1 waits for that of
+# iteration t; its statistics, code and compression of iteration t run beside it in a worker thread.
+def run_chain(co3, pipe, w, T, draw, client=0, seg_off=None):
+    n = w.n
+    f = oracle.Fmt(w.E, w.M)
+    g = pipe.new_gradient_buffer()
+    err = np.zeros(n, np.float32)
+
+    def finish(t, snap, A, sym):
+        cnt = oracle.histogram(sym, f)
+        l = oracle.huffman_lengths(cnt)
+        words, off, total = oracle.encode(sym, l, oracle.canonical_codes(l), 256)
+        assert np.array_equal(snap["cnt"], cnt), (t, "histogram")
+        assert np.array_equal(snap["len"], l), (t, "code lengths")
+        assert snap["total"] == total, (t, "total bits")
+        assert np.array_equal(snap["off"], off), (t, "chunk offsets")
+        nw = (total + 63) // 64
+        assert np.array_equal(snap["words"][:nw], words[:nw]), (t, "stream words")
+        return total
+
+    with ThreadPoolExecutor(max_workers=2) as pool:
+        pending = []
+        for t in range(1, T + 1):
+            gh = draw(pipe, g, t)
+            pipe.step(g)
+            assert pipe.poll() == 0
+            u = client
+            snap = dict(cnt=u32(pipe.counts[u]), len=pipe.codes[u, :pipe.fmt.K].cpu().numpy(),
+                        total=int(pipe.total_bits[u].item()), off=u64(pipe.chunk_bitoff[u]),
+                        words=u64(pipe.words[u, :(int(pipe.total_bits[u].item()) + 63) // 64]))
+            A = oracle.anchor(gh, f, seg_off)
+            sym, err = oracle.convert_ef(gh, err, A, 1.0, f, seg_off)
+            assert np.array_equal(pipe.anchor[u].cpu().numpy(), A), (t, "anchor")
+            assert np.array_equal(pipe.sym[u, :n].cpu().numpy(), sym), (t, "symbols")
+            assert np.array_equal(u32(pipe.err[u, :n]), err.view(np.uint32)), (t, "error vector")
+            if pipe.U == 1:
+                want = oracle.aggregate(sym[None, :], A[None, :], f, seg_off)
+                assert np.array_equal(u32(pipe.avg[:n]), want.view(np.uint32)), (t, "average")
+            pending.append(pool.submit(finish, t, snap, A, sym))
+            while len(pending) > 2:
+                pending.pop(0).result()
+        for fut in pending:
+            fut.result()
+
+
+def test_c2_all_100_iterations(co3):
+    """C2 over its 100 chained iterations: every output of every iteration against the oracle."""
+    w = inp.c2()
+    pipe = co3.Co3Pipeline(1, w.n, co3.Fmt(w.E, w.M), chunk_syms=256, seg_off=w.seg_off)
+    scales = inp.c2_tensor_scales()
+
+    def draw(pipe, g, t):
+        x = torch.cat([inp.device_gennorm(s, 0.8, float(a), 20000 + 100 * t + k) for k, (s, a) in enumerate(zip(w.sizes, scales))])
+        g[0, :w.n] = x
+        return x.cpu().numpy()
+
+    run_chain(co3, pipe, w, w.T, draw, seg_off=w.seg_off)
+
+
+def test_c3_client_0_all_50_iterations(co3):
+    """C3 over its 50 chained iterations (all 10 clients run on the device, one call per iteration as in the
+    benchmark): every output of client 0 against the oracle at every iteration."""
+    w = inp.c3()
+    betas = inp.c3_client_betas(w.U)
+    pipe = co3.Co3Pipeline(w.U, w.n, co3.Fmt(w.E, w.M), chunk_syms=256, one_call=True)
+
+    def draw(pipe, g, t):
+        for u in range(w.U):
+            g[u, :w.n] = inp.device_gennorm(w.n, float(betas[u]), 1e-3, 30000 + 100 * t + u)
+        return g[0, :w.n].cpu().numpy()
+
+    run_chain(co3, pipe, w, w.T, draw)
+
+
+def test_c4_all_20_iterations(co3):
+    """C4 (100M elements with outliers, empirical table) over its 20 chained iterations."""
+    w = inp.c4()
+    pipe = co3.Co3Pipeline(1, w.n, co3.Fmt(w.E, w.M), chunk_syms=256, one_call=True)
+
+    def draw(pipe, g, t):
+        x = inp.device_gennorm_outliers(w.n, 1.0, 1e-4, 1e-4, 100.0, 40000 + 10 * t)
+        g[0, :w.n] = x
+        return x.cpu().numpy()
+
+    run_chain(co3, pipe, w, w.T, draw)
+
+
+def test_c5_point_7_client_0_all_10_iterations(co3):
+    """One point of the C5 sweep (E4M3, beta = 1) over its 10 chained iterations, client 0 through the oracle."""
+    w = inp.c5(7)
+    pipe = co3.Co3Pipeline(w.U, w.n, co3.Fmt(w.E, w.M), chunk_syms=256, one_call=True)
+
+    def draw(pipe, g, t):
+        for u in range(w.U):
+            g[u, :w.n] = inp.device_gennorm(w.n, 1.0, 1e-3, 57000 + 100 * t + u)
+        return g[0, :w.n].cpu().numpy()
+
+    run_chain(co3, pipe, w, w.T, draw)
 
 
 def test_beyond_2_to_the_31_elements(co3):

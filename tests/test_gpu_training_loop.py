@@ -104,3 +104,67 @@ def test_training_converges_like_plain_sgd(co3, E, M, bias, codes, tables):
     assert last < 0.5 * first
     assert last < 1.35 * ref_last + 0.05
     assert opt.bits_per_element() < 1 + E + M + (0 if tables == "empirical" else 1)  # only own-count codes have that bound
+
+
+def test_gradients_land_in_the_batch_rows(co3):
+    """The users' gradients reach the [U][n] batch through the parameters' .grad views: every row equals the
+    gradient of a plain backward pass of that user's mini-batch, tensor after tensor in parameter order."""
+    from paper_2203_09044_amd.training import Co3SGD
+    U = 3
+    sample, model = make_problem(21, U, 16)
+    net = model()
+    opt = Co3SGD(net, U, co3.Fmt(3, 1), lr=0.05)
+    loss_fn = torch.nn.functional.cross_entropy
+    for t in range(2):                       # twice: the rows are cleared before every backward pass
+        batches = [sample(t, u) for u in range(U)]
+        opt.local_gradients(batches, loss_fn)
+        assert all(p.grad is None for p in opt.params)
+        for u, (x, y) in enumerate(batches):
+            net.zero_grad(set_to_none=True)
+            loss_fn(net(x), y).backward()
+            want = torch.cat([p.grad.reshape(-1) for p in opt.params])
+            assert torch.equal(opt.g[u, :opt.n], want), (t, u)
+        net.zero_grad(set_to_none=True)
+
+
+@pytest.mark.parametrize("tables,codes,bias", [("lagged", "user", "absmax"), ("model", "layer", "moments"),
+                                               ("empirical", "layer", "absmax")])
+def test_a_stream_that_does_not_fit_is_made_again(co3, tables, codes, bias):
+    """Codes that are not built from the user's own counts of the iteration can outgrow the stream buffer.
+    With a buffer far too small the wrapper must notice (device status), enlarge it and make the iteration
+    again from the state before it: weights, memory, average and stream lengths equal those of a run with
+    ample buffers, bit for bit."""
+    from paper_2203_09044_amd.training import Co3SGD
+    U, T = 3, 4
+    sample, model = make_problem(31, U, 32)
+    loss_fn = torch.nn.functional.cross_entropy
+    runs = []
+    for cap in (None, 64):
+        net = model()
+        opt = Co3SGD(net, U, co3.Fmt(3, 1), lr=0.05, bias=bias, codes=codes, code_group_min=10000, tables=tables,
+                     refresh=2, cap_words=cap)
+        for t in range(T):
+            opt.step([sample(t, u) for u in range(U)], loss_fn)
+        runs.append((opt, [p.detach().clone() for p in opt.params]))
+    (a, pa), (b, pb) = runs
+    assert a.capacity_growths == 0 and b.capacity_growths >= 1
+    assert b.pipe.poll() == 0
+    for x, y in zip(pa, pb):
+        assert torch.equal(x, y)
+    assert torch.equal(a.pipe.err.view(torch.int32), b.pipe.err.view(torch.int32))
+    assert torch.equal(a.pipe.avg.view(torch.int32), b.pipe.avg.view(torch.int32))
+    assert torch.equal(a.pipe.total_bits, b.pipe.total_bits)
+
+
+def test_a_device_condition_other_than_capacity_raises(co3):
+    from paper_2203_09044_amd.training import Co3SGD
+    from paper_2203_09044_amd import binding as B
+    U = 2
+    sample, model = make_problem(41, U, 16)
+    opt = Co3SGD(model(), U, co3.Fmt(3, 1), lr=0.05)
+    before = [p.detach().clone() for p in opt.params]
+    opt.pipe.status.fill_(B.EBADSTREAM)       # what a kernel would have left there
+    with pytest.raises(B.Co3Error):
+        opt.step([sample(0, u) for u in range(U)], torch.nn.functional.cross_entropy)
+    for p, q in zip(opt.params, before):      # the average never reached the model
+        assert torch.equal(p.detach(), q)

@@ -82,9 +82,74 @@ def test_error_paths():
     with pytest.raises(oracle.OracleError) as e:
         oracle.decode_layers(words, total - 1, lens, codes, seg, n)
     assert e.value.code == oracle.EBADSTREAM
+    # a byte that is not a symbol of the format is rejected by both histogram functions alike
+    f3 = oracle.Fmt(2, 0)
+    good = np.array([0, 1, 7, 3, 2, 7], np.uint8)
+    assert np.array_equal(oracle.histogram_layers(good, f3, [0, 2, 6]).sum(axis=0), oracle.histogram(good, f3))
+    for fn in (lambda x: oracle.histogram(x, f3), lambda x: oracle.histogram_layers(x, f3, [0, 2, 6])):
+        with pytest.raises(oracle.OracleError) as e:
+            fn(np.array([0, 1, 8, 3, 2, 7], np.uint8))
+        assert e.value.code == oracle.EINVAL
     # decoding with the tensors' codes swapped does not give the symbols back
     try:
         out = oracle.decode_layers(words, total, lens[::-1].copy(), codes[::-1].copy(), seg, n)
         assert not np.array_equal(out, sym)
     except oracle.OracleError as e2:
         assert e2.code == oracle.EBADSTREAM
+
+
+# ---- model tables of shared per-layer codes: which tensor designs a group's table, and the pooled law ----
+def test_design_tables_pick_the_largest_tensor_that_starts_in_the_group():
+    """Hand-built layout: expected design tensors written out by hand.  Every tensor gets a law of its own
+    (all users alike), so the table of a group tells which tensor designed it."""
+    f = oracle.Fmt(3, 1)
+    sizes = [5, 100, 100, 7, 300, 2, 0, 40]
+    seg = inp.seg_offsets(sizes)                      # 0 5 105 205 212 512 514 514 554
+    code_seg = [0, 205, 212, 514, 554, 554]           # groups: {0,1,2} {3} {4,5,6} {7} {} (empty range at the end)
+    want_tensor = [1, 3, 4, 7]                        # first of the two equal tensors 1 and 2; 6 is empty
+    U, nseg = 3, len(sizes)
+    fit = np.zeros((U, nseg, 2))
+    fit[:, :, 0] = 0.5 + 0.1 * np.arange(nseg)        # shape per tensor
+    fit[:, :, 1] = 1e-3 * (1 + np.arange(nseg))       # scale per tensor
+    scale = np.ones((U, nseg), np.float32)
+    got = oracle.design_layer_tables(fit, scale, seg, code_seg[:5], -3, f)
+    for k, s in enumerate(want_tensor):
+        assert np.array_equal(got[k], oracle.model_weights(-3, f, 0.5 + 0.1 * s, 1e-3 * (1 + s))), k
+    # a group in which no tensor starts takes the tensor that holds its first element
+    got = oracle.design_layer_tables(fit, scale, seg, [0, 250, 400, 554], -3, f)
+    assert np.array_equal(got[1], oracle.model_weights(-3, f, 0.5 + 0.1 * 4, 1e-3 * 5))   # element 250 lies in tensor 4
+
+
+def test_design_tables_pool_the_users_by_the_mean_of_the_fitted_parameters():
+    """One tensor, one group: the law is (mean shape, mean of scale x multiplier), checked against exact
+    rational arithmetic; identical users reduce to a single user; the limits on the shape hold."""
+    from fractions import Fraction
+    f = oracle.Fmt(1, 2)
+    rng = inp.rng_for(67, 1)
+    U = 5
+    fit = np.zeros((U, 1, 2))
+    fit[:, 0, 0] = rng.uniform(0.6, 1.8, U)
+    fit[:, 0, 1] = rng.uniform(1e-4, 1e-2, U)
+    scale = rng.uniform(50, 500, (U, 1)).astype(np.float32)
+    beta = float(sum(Fraction(float(b)) for b in fit[:, 0, 0]) / U)
+    alpha = float(sum(Fraction(float(a)) * Fraction(float(c)) for a, c in zip(fit[:, 0, 1], scale[:, 0])) / U)
+    got = oracle.design_layer_tables(fit, scale, [0, 1000], [0, 1000], 1, f)[0]
+    want = oracle.model_weights(1, f, beta, alpha)
+    # the double-precision sums are within a few units in the last place of the exact means: the weights
+    # (32-bit roundings of probabilities) can differ by one unit at most
+    assert np.max(np.abs(got.astype(np.int64) - want.astype(np.int64))) <= 1
+    # a multiplier moves the scale, not the shape: twice the multiplier = twice the scale of the law
+    twice = oracle.design_layer_tables(fit, 2 * scale, [0, 1000], [0, 1000], 1, f)[0]
+    assert np.max(np.abs(twice.astype(np.int64) - oracle.model_weights(1, f, beta, 2 * alpha).astype(np.int64))) <= 1
+    same = np.repeat(fit[:1], 4, axis=0), np.repeat(scale[:1], 4, axis=0)
+    one = oracle.design_layer_tables(fit[:1], scale[:1], [0, 1000], [0, 1000], 1, f)[0]
+    assert np.array_equal(oracle.design_layer_tables(same[0], same[1], [0, 1000], [0, 1000], 1, f)[0], one)
+    assert np.array_equal(one, oracle.model_weights(1, f, float(fit[0, 0, 0]), float(fit[0, 0, 1]) * float(scale[0, 0])))
+    lo, hi = fit.copy(), fit.copy()
+    lo[:, 0, 0], hi[:, 0, 0] = 0.01, 40.0
+    ones = np.ones((U, 1), np.float32)
+    a = float(np.sum([Fraction(float(x)) for x in fit[:, 0, 1]]) / U)
+    assert np.max(np.abs(oracle.design_layer_tables(lo, ones, [0, 9], [0, 9], 1, f)[0].astype(np.int64) -
+                         oracle.model_weights(1, f, 0.2, a).astype(np.int64))) <= 1
+    assert np.max(np.abs(oracle.design_layer_tables(hi, ones, [0, 9], [0, 9], 1, f)[0].astype(np.int64) -
+                         oracle.model_weights(1, f, 4.0, a).astype(np.int64))) <= 1

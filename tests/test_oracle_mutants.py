@@ -60,7 +60,7 @@ MUTANTS = [
      "scaled_conversion or power_of_two_multiplier or rule_beats"),
     ("layer_code_of_first_tensor", "            int l = len[(int64_t)s * K + sym[i]];\n            uint64_t c = code[(int64_t)s * K + sym[i]];",
      "            int l = len[sym[i]];\n            uint64_t c = code[sym[i]];", LAYERS, "concatenation or single_tensor"),
-    ("layer_counts_pooled", "                counts[(int64_t)s * K + sym[i]] += 1;", "                counts[sym[i]] += 1;", LAYERS,
+    ("layer_counts_pooled", "            counts[(int64_t)s * K + sym[i]] += 1;\n        }", "            counts[sym[i]] += 1;\n        }", LAYERS,
      "concatenation or single_tensor"),
     ("second_moment_is_first", "            s2 += xd * xd;", "            s2 += fabs(xd);", BIAS, "moments_against_exact"),
     ("ratio_wrong_gamma", "return exp(2.0 * lgamma(2.0 / beta) - lgamma(1.0 / beta) - lgamma(3.0 / beta));",
