@@ -421,7 +421,8 @@ def main():
                              "layer-lagged": "empirical per tensor from the previous step's pooled counts (+1), rebuilt every step",
                              "layer": "empirical per tensor, pooled over the clients, rebuilt every step",
                              "layer-model": "fixed per tensor, designed from the GenNorm law of the workload"}[args.codes],
-                   "gamma": args.gamma, "bias": args.bias, "codes": args.codes},
+                   "gamma": args.gamma, "bias": args.bias, "codes": args.codes,
+                   "user_side": "co3_user_encode" if one_call else "separate calls"},
         "bits_per_element": {"payload": payload_bpe, "index": index_bpe, "header": header_bpe},
         "first_step_ms": first_step_ms,
         "path_roofline": {"bound": "hbm", "scope": "whole path (encode + decode), all kernels of a step",

@@ -220,6 +220,26 @@ int32_t co3_ps_aggregate(const uint64_t *words, int64_t cap_words, const uint64_
                          int32_t *status, void *stream);
 
 /*
+ * The aggregate of Sec. II-A taken over the users in groups: co3_ps_aggregate that continues a sum and
+ * may leave it undivided,
+ *     out[i] = fl32( ((acc_in[i] + v_0) + v_1) + ... + v_{U-1} ) [ / divide_by ]
+ * with acc_in = NULL read as zeros and no division when divide_by = 0.  Calling it for the users
+ * 0..a-1 (acc_in NULL, divide_by 0), then a..b-1 with the first result as acc_in, ..., the last group with
+ * divide_by = the number of all users, performs the additions and the one division of co3_ps_aggregate
+ * over all users in the same order: the result is the same bit for bit.  The groups' decoders can then
+ * run as soon as a group's streams are there.
+ *   acc_in    [n] f32 in or NULL; may be the same array as out
+ *   out       [n] f32 out
+ *   other arguments, workspace and errors as co3_ps_aggregate (U = users of this group, pointers at the
+ *   group's first user); CO3_EINVAL when divide_by < 0
+ */
+int32_t co3_ps_aggregate_partial(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff,
+                                 int32_t chunk_syms, const void *codes, co3_fmt fmt, int64_t n, int32_t U,
+                                 const int32_t *anchor, const int64_t *seg_off, int32_t nseg, const float *acc_in,
+                                 int32_t divide_by, float *out, void *workspace, size_t ws_bytes, int32_t *status,
+                                 void *stream);
+
+/*
  * co3_ps_aggregate for streams made with co3_convert_ef_scaled: v_u = fl32(value_{A_u}(symbol) / c_u) with
  * the multipliers scale [U][nseg] of the users (Sec. III (i): the receiver undoes the bias).
  */
@@ -336,7 +356,10 @@ int32_t co3_convert_encode_layers(const float *g, float *err, int64_t n, int32_t
  *              out (every such wait is bounded, see co3_set_exchange_spin_limit); the outputs are
  *              then unspecified
  * The resident grid assumes that its workgroups (one per compute unit at most) can all be on the device
- * at once.  Kernels of other streams that share the device only delay that; they cannot prevent it.
+ * at once.  Kernels of other streams that share the device only delay that; they cannot prevent it --
+ * except another resident grid: two of them started at the same time may each hold part of the device and
+ * wait for the rest, until both time out.  Calls that may run at the same time (on different streams) must
+ * not both take the resident-grid path.
  */
 size_t co3_user_encode_workspace_bytes(int64_t n, int32_t U, int64_t stride, int32_t nseg, int32_t caller_has_sym);
 int32_t co3_user_encode(const float *g, float *err, int64_t n, int32_t U, int64_t stride, const int64_t *seg_off,

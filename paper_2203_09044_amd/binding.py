@@ -29,6 +29,7 @@ EXPORTS = (
     "co3_histogram_layers", "co3_encode_layers", "co3_decode_layers", "co3_ps_aggregate_layers",
     "co3_convert_encode_workspace_bytes", "co3_convert_encode", "co3_convert_encode_layers", "co3_encode_static",
     "co3_user_encode_workspace_bytes", "co3_user_encode", "co3_set_exchange_spin_limit", "co3_design_layer_tables",
+    "co3_ps_aggregate_partial",
 )
 KERNEL_COUNT = 13
 
@@ -100,6 +101,8 @@ def _load():
     L.co3_user_encode_workspace_bytes.argtypes = [i64, i32, i64, i32, i32]
     L.co3_user_encode.restype = i32
     L.co3_user_encode.argtypes = [p, p, i64, i32, i64, p, i32, p, C.c_float, _Fmt, p, p, p, i64, i32, p, p, p, p, sz, p, p]
+    L.co3_ps_aggregate_partial.restype = i32
+    L.co3_ps_aggregate_partial.argtypes = [p, i64, p, i32, p, _Fmt, i64, i32, p, p, i32, p, i32, p, p, sz, p, p]
     L.co3_set_exchange_spin_limit.restype = None
     L.co3_set_exchange_spin_limit.argtypes = [C.c_int64]
     L.co3_decode.restype = i32
@@ -330,6 +333,20 @@ def ps_aggregate(words, chunk_bitoff, chunk_syms, codes, fmt: Fmt, n, U, anchor,
                                workspace.numel() * workspace.element_size(), _dp(status, torch.int32),
                                _stream(stream))
     _chk(rc, "co3_ps_aggregate")
+
+
+def ps_aggregate_partial(words, chunk_bitoff, chunk_syms, codes, fmt: Fmt, n, U, anchor, acc_in, divide_by, out, workspace,
+                         status, seg_off=None, stream=None):
+    """co3_ps_aggregate over a group of users that continues the sum ``acc_in`` (None: zeros) and divides by
+    ``divide_by`` (0: the sum is left undivided)."""
+    nseg = 1 if seg_off is None else seg_off.numel() - 1
+    rc = _lib.co3_ps_aggregate_partial(_dp(words, torch.int64), words.shape[-1], _dp(chunk_bitoff, torch.int64),
+                                       chunk_syms, _dp(codes, torch.uint8), fmt.c(), n, U, _dp(anchor, torch.int32),
+                                       _dp(seg_off, torch.int64), nseg, _dp(acc_in, torch.float32), divide_by,
+                                       _dp(out, torch.float32), _dp(workspace),
+                                       workspace.numel() * workspace.element_size(), _dp(status, torch.int32),
+                                       _stream(stream))
+    _chk(rc, "co3_ps_aggregate_partial")
 
 
 def model_weights(A: int, fmt: Fmt, beta: float, alpha: float):

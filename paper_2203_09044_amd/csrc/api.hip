@@ -191,7 +191,7 @@ int32_t co3_poll_status(const int32_t *status_dev, void *stream)
 
 static int32_t convert_common(const float *g, float *err, uint8_t *sym, int64_t n, int32_t U, int64_t stride,
                               const int64_t *seg_off, int32_t nseg, int32_t *anchor, int32_t anchor_mode,
-                              const float *scale, float gamma, co3_fmt fmt, uint32_t *counts, void *stream)
+                              const float *scale, float gamma, co3_fmt fmt, uint32_t *counts, void *stream, int sym_nib = 0)
 {
     if (!fmt_ok(fmt) || !batch_ok(n, U, stride) || nseg < 1 || (seg_off == nullptr && nseg != 1)) return CO3_EINVAL;
     if (!g || !err || !sym || !anchor) return CO3_EINVAL;
@@ -207,7 +207,8 @@ static int32_t convert_common(const float *g, float *err, uint8_t *sym, int64_t 
         e = co3_launch_absmax(g, n, U, stride, seg_off, nseg, anchor, st);
         if (e != hipSuccess) return CO3_EHIP;
     }
-    return hip_rc(co3_launch_convert(g, err, sym, n, U, stride, seg_off, nseg, anchor, scale, gamma, fmt, counts, st));
+    return hip_rc(co3_launch_convert(g, err, sym, n, U, stride, seg_off, nseg, anchor, scale, gamma, fmt, counts, st,
+                                     sym_nib));
 }
 
 int32_t co3_convert_ef(const float *g, float *err, uint8_t *sym, int64_t n, int32_t U, int64_t stride,
@@ -335,6 +336,8 @@ int32_t co3_user_encode(const float *g, float *err, int64_t n, int32_t U, int64_
     ws += round_up_256(co3_encode_workspace_bytes(n, U));
     uint8_t *symbuf = sym ? sym : reinterpret_cast<uint8_t *>(ws);
     if (!sym) ws += round_up_256((size_t)U * (size_t)(stride > n ? stride : n) + 16);
+    // symbols that stay inside the call take four bits each where the alphabet allows
+    const int nib = !sym && fc.K <= 16 && (U == 1 || stride % 2 == 0) ? 1 : 0;
     int kpt = 0, grid = 0;
     if (user_encode_coop(n, nseg, &kpt, &grid)) {
         uint32_t *slots = reinterpret_cast<uint32_t *>(ws);
@@ -345,20 +348,21 @@ int32_t co3_user_encode(const float *g, float *err, int64_t n, int32_t U, int64_
                             (int64_t)CO3_COOP_COUNT_REPS * U * fc.K, st) != hipSuccess)
             return CO3_EHIP;
         if (co3_launch_coop_convert(g, err, symbuf, n, U, stride, kpt, grid, anchor, gamma, fmt, counts_rep, slots,
-                                    g_spin_limit.load(), status, st) != hipSuccess)
+                                    g_spin_limit.load(), status, nib, st) != hipSuccess)
             return CO3_EHIP;
-        // the code build adds the partial tables up and leaves the sums in counts
-        if (co3_launch_build_code(counts_rep, U, fc.K, codes, status, st, CO3_COOP_COUNT_REPS, counts) != hipSuccess)
+        // the ragged end of the vector, the counts (partial tables added up) and the code of every user: one launch
+        if (co3_launch_user_finish(g, err, symbuf, n, co3_coop_full_elements(n, kpt), stride, U, anchor, gamma, fmt, nib,
+                                   counts_rep, CO3_COOP_COUNT_REPS, counts, codes, status, st) != hipSuccess)
             return CO3_EHIP;
         return hip_rc(co3_launch_encode(symbuf, n, U, stride, codes, fc.K, nullptr, 1, words, cap_words, chunk_syms,
-                                        chunk_bitoff, total_bits, static_cast<uint64_t *>(enc_ws), status, st));
+                                        chunk_bitoff, total_bits, static_cast<uint64_t *>(enc_ws), status, st, nib));
     }
     const int32_t rc = convert_common(g, err, symbuf, n, U, stride, seg_off, nseg, anchor, CO3_ANCHOR_FROM_ABSMAX_G,
-                                      nullptr, gamma, fmt, counts, stream);
+                                      nullptr, gamma, fmt, counts, stream, nib);
     if (rc != CO3_OK) return rc;
     if (co3_launch_build_code(counts, U, fc.K, codes, status, st) != hipSuccess) return CO3_EHIP;
     return hip_rc(co3_launch_encode(symbuf, n, U, stride, codes, fc.K, nullptr, 1, words, cap_words, chunk_syms,
-                                    chunk_bitoff, total_bits, static_cast<uint64_t *>(enc_ws), status, st));
+                                    chunk_bitoff, total_bits, static_cast<uint64_t *>(enc_ws), status, st, nib));
 }
 
 int32_t co3_moments(const float *g, const float *err, int64_t n, int32_t U, int64_t stride, const int64_t *seg_off,
@@ -493,10 +497,12 @@ static int32_t aggregate_common(const uint64_t *words, int64_t cap_words, const 
                                 int32_t chunk_syms, const void *codes, const int64_t *code_seg_off, int32_t code_nseg,
                                 co3_fmt fmt, int64_t n, int32_t U, const int32_t *anchor, const float *scale,
                                 const int64_t *seg_off, int32_t nseg, float *avg_out, void *workspace, size_t ws_bytes,
-                                int32_t *status, void *stream)
+                                int32_t *status, void *stream, const float *acc_in = nullptr, int32_t divide_by = -1)
 {
     if (!fmt_ok(fmt) || n < 0 || n >= ((int64_t)1 << 32) || U < 1 || !chunk_ok(chunk_syms) || cap_words < 0)
         return CO3_EINVAL;
+    if (acc_in && !aligned(acc_in, 16)) return CO3_EINVAL;
+    const float divisor = divide_by < 0 ? (float)U : (float)divide_by;      // 0: the sum is left undivided
     if (nseg < 1 || (seg_off == nullptr && nseg != 1) || code_nseg < 1) return CO3_EINVAL;
     if (!words || !chunk_bitoff || !codes || !anchor || !avg_out || !workspace) return CO3_EINVAL;
     if (!aligned(avg_out, 16) || !aligned(workspace, 16) || !aligned(words, 16) || !aligned(codes, 8)) return CO3_EINVAL;
@@ -511,7 +517,7 @@ static int32_t aggregate_common(const uint64_t *words, int64_t cap_words, const 
     if (e != hipSuccess) return CO3_EHIP;
     const int packed = co3_ws_packed(FmtC(fmt).K, chunk_syms, code_seg_off ? code_nseg : 0) ? 1 : 0;
     return hip_rc(co3_launch_ps_sum_tiled(symws, n, U, ws_stride, chunk_syms, anchor, scale, seg_off, nseg, fmt, packed,
-                                          avg_out, st));
+                                          acc_in, divisor, avg_out, st));
 }
 
 int32_t co3_ps_aggregate(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff, int32_t chunk_syms,
@@ -521,6 +527,17 @@ int32_t co3_ps_aggregate(const uint64_t *words, int64_t cap_words, const uint64_
 {
     return aggregate_common(words, cap_words, chunk_bitoff, chunk_syms, codes, nullptr, 1, fmt, n, U, anchor, nullptr,
                             seg_off, nseg, avg_out, workspace, ws_bytes, status, stream);
+}
+
+int32_t co3_ps_aggregate_partial(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff,
+                                 int32_t chunk_syms, const void *codes, co3_fmt fmt, int64_t n, int32_t U,
+                                 const int32_t *anchor, const int64_t *seg_off, int32_t nseg, const float *acc_in,
+                                 int32_t divide_by, float *out, void *workspace, size_t ws_bytes, int32_t *status,
+                                 void *stream)
+{
+    if (divide_by < 0) return CO3_EINVAL;
+    return aggregate_common(words, cap_words, chunk_bitoff, chunk_syms, codes, nullptr, 1, fmt, n, U, anchor, nullptr,
+                            seg_off, nseg, out, workspace, ws_bytes, status, stream, acc_in, divide_by);
 }
 
 int32_t co3_ps_aggregate_scaled(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff,

@@ -163,7 +163,10 @@ __global__ __launch_bounds__(CV_BLOCK) void k_absmax(const float *__restrict__ g
 // SCALED: the bias in its multiplier form (Sec. III (i) with the approximation of Sec. IV-B): the corrected
 // gradient is multiplied by c before it is rounded onto the grid of the given anchor, and the level
 // is divided by c again; one fp32 rounding per operation.
-template <bool HIST, bool SCALED>
+// NIB (alphabets of at most 16 symbols): the symbols leave two per byte, the earlier one in the low half, a
+// user's row taking stride / 2 bytes.  A thread's elements start at a multiple of four, so the bytes it
+// writes are its own.
+template <bool HIST, bool SCALED, bool NIB = false>
 __global__ __launch_bounds__(CV_BLOCK) void k_convert_ef(const float *__restrict__ g, float *__restrict__ err,
                                                           uint8_t *__restrict__ sym, int64_t n, int64_t stride,
                                                           const int64_t *__restrict__ seg_off_g, int nseg,
@@ -181,11 +184,21 @@ __global__ __launch_bounds__(CV_BLOCK) void k_convert_ef(const float *__restrict
     const int64_t range = gridDim.x - 1 - blockIdx.x;
     const float *gu = g + (int64_t)u * stride;
     float *eu = err + (int64_t)u * stride;
-    uint8_t *su = sym + (int64_t)u * stride;
+    uint8_t *su = sym + (int64_t)u * (NIB ? stride / 2 : stride);
     const int32_t *anchor_u = anchor + (int64_t)u * nseg;
     const float *scale_u = SCALED ? scale + (int64_t)u * nseg : nullptr;
     const int lane = threadIdx.x & (CO3_WAVE - 1);
     const int wave = threadIdx.x / CO3_WAVE;
+    // symbols of four consecutive elements from i (a multiple of four) on; one symbol of element j
+    auto store_sym4 = [&](int64_t i, uint32_t q0, uint32_t q1, uint32_t q2, uint32_t q3) {
+        if (NIB) *reinterpret_cast<uint16_t *>(su + (i >> 1)) = (uint16_t)(q0 | (q1 << 4) | (q2 << 8) | (q3 << 12));
+        else *reinterpret_cast<uint32_t *>(su + i) = q0 | (q1 << 8) | (q2 << 16) | (q3 << 24);
+    };
+    auto store_sym1 = [&](int64_t j, uint32_t q) {
+        if (!NIB) su[j] = (uint8_t)q;
+        else if ((j & 1) == 0) su[j >> 1] = (uint8_t)q;              // the even element writes the byte ...
+        else su[j >> 1] = (uint8_t)(su[j >> 1] | (q << 4));          // ... the odd one, the same thread after it, joins
+    };
 
     // per-wavefront private histogram: `copies` interleaved replicas of the K counters so that
     // lanes hitting one popular symbol spread over banks
@@ -219,7 +232,7 @@ __global__ __launch_bounds__(CV_BLOCK) void k_convert_ef(const float *__restrict
         en.z = convert1(gv.z, ev.z, A, e_min, c, q2);
         en.w = convert1(gv.w, ev.w, A, e_min, c, q3);
         st_stream_f4(eu + i, en);
-        *reinterpret_cast<uint32_t *>(su + i) = q0 | (q1 << 8) | (q2 << 16) | (q3 << 24);
+        store_sym4(i, q0, q1, q2, q3);
         if (HIST) {
             atomicAdd(&myhist[q0 * copies + mycopy], 1u);
             atomicAdd(&myhist[q1 * copies + mycopy], 1u);
@@ -234,7 +247,7 @@ __global__ __launch_bounds__(CV_BLOCK) void k_convert_ef(const float *__restrict
         for (int64_t j = a0; j < a1; j += step) {
             uint32_t q;
             eu[j] = convert1(gu[j], eu[j], A, A - F + 1, c, q);
-            su[j] = (uint8_t)q;
+            store_sym1(j, q);
             if (HIST) atomicAdd(&myhist[q * copies + mycopy], 1u);
         }
     };
@@ -284,7 +297,7 @@ __global__ __launch_bounds__(CV_BLOCK) void k_convert_ef(const float *__restrict
                     if (HIST) atomicAdd(&myhist[q[k] * copies + mycopy], 1u);
                 }
                 st_stream_f4(eu + i, make_float4(en[0], en[1], en[2], en[3]));
-                *reinterpret_cast<uint32_t *>(su + i) = q[0] | (q[1] << 8) | (q[2] << 16) | (q[3] << 24);
+                store_sym4(i, q[0], q[1], q[2], q[3]);
             }
         } else {                         // its ragged end, element by element
             for (int64_t j = i; j < t1; ++j) convert_part(j, j + 1, 1, co3_find_seg(seg_off, nseg, j));
@@ -477,13 +490,19 @@ hipError_t co3_launch_absmax(const float *g, int64_t n, int U, int64_t stride, c
 
 hipError_t co3_launch_convert(const float *g, float *err, uint8_t *sym, int64_t n, int U, int64_t stride,
                               const int64_t *seg_off, int nseg, const int32_t *anchor, const float *scale, float gamma,
-                              co3_fmt fmt, uint32_t *counts, hipStream_t st)
+                              co3_fmt fmt, uint32_t *counts, hipStream_t st, int sym_nib)
 {
     if (n <= 0) return hipSuccess;
+    if (sym_nib && (!counts || scale || (1 << (1 + fmt.exp_bits + fmt.mant_bits)) > 16)) return hipErrorInvalidValue;
     int blocks;
     int64_t pb = per_block_for(n, U, CV_TILE, &blocks, counts ? 1 << (1 + fmt.exp_bits + fmt.mant_bits) : 0);
     Co3LaunchTimer tm(CO3_K_CONVERT, st);
     const dim3 grid(blocks, U), block(CV_BLOCK);
+    if (sym_nib) {
+        hipLaunchKernelGGL((k_convert_ef<true, false, true>), grid, block, 0, st, g, err, sym, n, stride, seg_off, nseg, anchor,
+                           scale, gamma, fmt, counts, pb);
+        return hipGetLastError();
+    }
 #define CO3_CONVERT_LAUNCH(H, S)                                                                                     \
     hipLaunchKernelGGL((k_convert_ef<H, S>), grid, block, 0, st, g, err, sym, n, stride, seg_off, nseg, anchor, scale, \
                        gamma, fmt, counts, pb)

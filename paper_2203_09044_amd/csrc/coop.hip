@@ -24,12 +24,14 @@
 #ifndef CP_AHEAD
 #define CP_AHEAD 6                           // memory loads in flight per lane ahead of the conversion
 #endif
-#ifdef CP_MAP_BLOCK
-#define CP_RUN_STRIDE (CP_WAVES * CP_STEP)
-#else
-#define CP_RUN_STRIDE CP_STEP
-#endif
 #define CP_HIST_SLOTS 1024                   // LDS counters per wavefront
+// Registers: the kernel is compiled for this many wavefronts per SIMD (168 vector registers each) although a
+// workgroup brings only two.  With all 256 registers a wavefront could have, the resident grid would fill
+// every register file of the device, and kernels of other streams (the code build, compression and
+// decoding of another group of users) could not start before it ends.
+#ifndef CP_WAVES_PER_SIMD
+#define CP_WAVES_PER_SIMD 3
+#endif
 #define CP_VALID 0x80000000u
 
 __device__ __forceinline__ uint32_t ld_relaxed_agent(const uint32_t *p)
@@ -116,16 +118,15 @@ __device__ __forceinline__ uint32_t coop_collect_max(const uint32_t *row, int G,
     return r;
 }
 
-// One user's conversion by one wavefront: KPT runs of 256 elements, the gradient from registers, the memory
-// streamed CP_AHEAD runs ahead; as soon as a run is converted its registers take the next user's gradient.
-// FULL: all KPT runs lie below n (straight-line code: the compiler can count the memory operations in
-// flight exactly); else every access is guarded.  `left` = n - (first element of the wavefront's run 0).
+// One user's conversion by one wavefront whose KPT runs of 256 elements all lie below n: the gradient from
+// registers, the memory streamed CP_AHEAD runs ahead; as soon as a run is converted its registers take the
+// next user's gradient.  Straight-line code: the compiler can count the memory operations in flight exactly.
 struct CoopWave {
-    float *eu;                 // the user's memory at the wavefront's run 0
-    uint8_t *su;               // its symbols there, or NULL
+    float *eu;                 // the user's memory there
+    uint8_t *su;               // its symbols there
     const float *gnext;        // the next user's gradient there (read when `more`)
     bool more;
-    int64_t left;
+    int64_t left;              // n - (first element of the wavefront's run 0)
     uint32_t lane4;
     int A, e_min, E, M, codemax;
     float gamma;
@@ -133,17 +134,14 @@ struct CoopWave {
     int copies, mycopy;
 };
 
-template <int KPT, bool HIST, bool FULL>
+template <int KPT, bool NIB>
 __device__ __forceinline__ void coop_convert_user(const CoopWave &w, float4 (&gr)[KPT], float4 (&ev)[CP_AHEAD])
 {
 #pragma unroll
     for (int k = 0; k < KPT; ++k) {
-        const int64_t rem = w.left - (int64_t)k * CP_RUN_STRIDE;            // uniform: elements of this run below n
-        float *ek = w.eu + k * CP_RUN_STRIDE;
+        float *ek = w.eu + k * CP_STEP;
         const float4 gv = gr[k], e4 = ev[k % CP_AHEAD];
-        if (k + CP_AHEAD < KPT)
-            ev[k % CP_AHEAD] = FULL ? ld_stream_f4(ek + CP_AHEAD * CP_RUN_STRIDE + w.lane4)
-                                    : ld4_run(ek + CP_AHEAD * CP_RUN_STRIDE, rem - CP_AHEAD * CP_RUN_STRIDE, w.lane4);
+        if (k + CP_AHEAD < KPT) ev[k % CP_AHEAD] = ld_stream_f4(ek + CP_AHEAD * CP_STEP + w.lane4);
         const float ga[CP_VEC] = {gv.x, gv.y, gv.z, gv.w}, ea[CP_VEC] = {e4.x, e4.y, e4.z, e4.w};
         float en[CP_VEC];
         uint32_t q[CP_VEC];
@@ -151,49 +149,44 @@ __device__ __forceinline__ void coop_convert_user(const CoopWave &w, float4 (&gr
         for (int c = 0; c < CP_VEC; ++c) {
             const float x = ga[c] + w.gamma * ea[c];              // no contraction (build flag): one rounding per operation
             float v;
-#ifdef CP_NO_QUANT
-            q[c] = __float_as_uint(x) >> 28; v = x * 0.5f;
-#else
             co3_quantize(x, w.e_min, w.A, w.E, w.M, w.codemax, q[c], v);
-#endif
             en[c] = x - v;
         }
-        if (FULL || rem >= CP_STEP) {                             // uniform: the whole run exists
-            st_stream_f4(ek + w.lane4, make_float4(en[0], en[1], en[2], en[3]));
-#ifndef CP_NO_SYM
-            if (w.su)
-                *reinterpret_cast<uint32_t *>(w.su + k * CP_RUN_STRIDE + w.lane4) = q[0] | (q[1] << 8) | (q[2] << 16) | (q[3] << 24);
-#endif
-#ifndef CP_NO_HIST_ATOMICS
-            if (HIST) {
+        st_stream_f4(ek + w.lane4, make_float4(en[0], en[1], en[2], en[3]));
+        if (NIB)         // two symbols per byte, the earlier one in the low half
+            *reinterpret_cast<uint16_t *>(w.su + k * (CP_STEP / 2) + w.lane4 / 2) =
+                (uint16_t)(q[0] | (q[1] << 4) | (q[2] << 8) | (q[3] << 12));
+        else
+            *reinterpret_cast<uint32_t *>(w.su + k * CP_STEP + w.lane4) = q[0] | (q[1] << 8) | (q[2] << 16) | (q[3] << 24);
 #pragma unroll
-                for (int c = 0; c < CP_VEC; ++c) atomicAdd(&w.myhist[q[c] * w.copies + w.mycopy], 1u);
-            }
-#endif
-        } else {
-#pragma unroll
-            for (int c = 0; c < CP_VEC; ++c)
-                if ((int64_t)(w.lane4 + c) < rem) {
-                    ek[w.lane4 + c] = en[c];
-                    if (w.su) w.su[k * CP_RUN_STRIDE + w.lane4 + c] = (uint8_t)q[c];
-                    if (HIST) atomicAdd(&w.myhist[q[c] * w.copies + w.mycopy], 1u);
-                }
-        }
+        for (int c = 0; c < CP_VEC; ++c) atomicAdd(&w.myhist[q[c] * w.copies + w.mycopy], 1u);
         // the registers are free: the next user's gradient moves in
-#ifndef CP_NO_REFILL
-        if (w.more)
-#else
-        if (false)
-#endif
-            gr[k] = FULL ? ld_stream_f4(w.gnext + k * CP_RUN_STRIDE + w.lane4) : ld4_run(w.gnext + k * CP_RUN_STRIDE, rem, w.lane4);
+        if (w.more) gr[k] = ld_stream_f4(w.gnext + k * CP_STEP + w.lane4);
     }
+}
+
+// The one wavefront that holds the ragged end of the vector (fewer than KPT whole runs) and those after it,
+// which hold nothing, only take part in the search for the largest magnitude, run by run with every access
+// guarded; the ragged end is converted after the kernel by the plain conversion kernel, with the anchors
+// that this kernel leaves.  (A guarded copy of the conversion in here would add its registers to those of
+// the path above, which every other wavefront of the device runs.)
+__device__ __forceinline__ uint32_t coop_ragged_max(const float *gu, int64_t left, int kpt, uint32_t lane4)
+{
+    uint32_t m = 0;
+#pragma unroll 1
+    for (int k = 0; k < kpt; ++k) {
+        const int64_t rem = left - (int64_t)k * CP_STEP;
+        if (rem <= 0) break;
+        m = absbits4(ld4_run(gu + k * CP_STEP, rem, lane4), m);
+    }
+    return m;
 }
 
 // grid: G workgroups (at most one per compute unit, all resident); workgroup w owns elements
 // [w * KPT * 2048, (w + 1) * KPT * 2048) of every user, wavefront v of it the v-th eighth, lane l of the
 // wavefront elements 4l .. 4l+3 of each of the wavefront's KPT runs of 256.
-template <int KPT, bool HIST>
-__global__ __launch_bounds__(CP_BLOCK) void k_coop_convert(const float *__restrict__ g, float *__restrict__ err,
+template <int KPT, bool NIB>
+__global__ __launch_bounds__(CP_BLOCK) __attribute__((amdgpu_waves_per_eu(CP_WAVES_PER_SIMD, CP_WAVES_PER_SIMD))) void k_coop_convert(const float *__restrict__ g, float *__restrict__ err,
                                                             uint8_t *__restrict__ sym, int64_t n, int64_t stride, int U,
                                                             int32_t *__restrict__ anchor, float gamma,
                                                             co3_fmt fmt, uint32_t *__restrict__ counts,
@@ -206,34 +199,30 @@ __global__ __launch_bounds__(CP_BLOCK) void k_coop_convert(const float *__restri
     const int lane = threadIdx.x & (CO3_WAVE - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / CO3_WAVE);     // uniform: addresses of a run are scalar
     __shared__ uint32_t red[CP_WAVES + 1];
-    __shared__ uint32_t hist[HIST ? CP_WAVES * CP_HIST_SLOTS : 1];
+    __shared__ uint32_t hist[CP_WAVES * CP_HIST_SLOTS];
+    __shared__ uint32_t wavecnt[CP_WAVES * 256];               // symbol counts of every wavefront's part of a user
     const int copies = CP_HIST_SLOTS / K > 32 ? 32 : CP_HIST_SLOTS / K;
-    if (HIST) {
-        for (int j = threadIdx.x; j < CP_WAVES * CP_HIST_SLOTS; j += CP_BLOCK) hist[j] = 0u;
-    }
+    for (int j = threadIdx.x; j < CP_WAVES * CP_HIST_SLOTS; j += CP_BLOCK) hist[j] = 0u;
 
-    // first element of the wavefront's run 0 (uniform); run k lies k * CP_RUN_STRIDE further
-#ifdef CP_MAP_BLOCK
-    const int64_t first = ((int64_t)blockIdx.x * KPT) * CP_RUN_STRIDE + wave * CP_STEP;
-#else
+    // first element of the wavefront's run 0 (uniform); run k lies k * CP_STEP further
     const int64_t first = (((int64_t)blockIdx.x * CP_WAVES + wave) * KPT) * CP_STEP;
-#endif
     const uint32_t lane4 = (uint32_t)lane * CP_VEC;
-    const bool full = first + (int64_t)(KPT - 1) * CP_RUN_STRIDE + CP_STEP <= n;      // uniform: every run of the wavefront is whole
+    const bool full = first + (int64_t)KPT * CP_STEP <= n;      // uniform: every run of the wavefront is whole
 
     // user 0's gradient: every load of the lane in flight at once
     float4 gr[KPT];
-    if (full) {
-#pragma unroll
-        for (int k = 0; k < KPT; ++k) gr[k] = ld_stream_f4(g + first + k * CP_RUN_STRIDE + lane4);
-    } else {
-#pragma unroll
-        for (int k = 0; k < KPT; ++k) gr[k] = ld4_run(g + first + k * CP_RUN_STRIDE, n - first - k * CP_RUN_STRIDE, lane4);
-    }
     {
         uint32_t m = 0;
+        if (full) {
 #pragma unroll
-        for (int k = 0; k < KPT; ++k) m = absbits4(gr[k], m);
+            for (int k = 0; k < KPT; ++k) gr[k] = ld_stream_f4(g + first + k * CP_STEP + lane4);
+#pragma unroll
+            for (int k = 0; k < KPT; ++k) m = absbits4(gr[k], m);
+        } else {
+#pragma unroll
+            for (int k = 0; k < KPT; ++k) gr[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+            m = coop_ragged_max(g + first, n - first, KPT, lane4);
+        }
         coop_publish_max(m, slots, red);
     }
 
@@ -250,20 +239,14 @@ __global__ __launch_bounds__(CP_BLOCK) void k_coop_convert(const float *__restri
     for (int u = 0; u < U; ++u) {
         w.gnext = g + (int64_t)(u + 1) * stride + first;          // only read when u + 1 < U
         w.eu = err + (int64_t)u * stride + first;
-        w.su = sym ? sym + (int64_t)u * stride + first : nullptr;
+        w.su = NIB ? sym + (int64_t)u * (stride / 2) + first / 2 : sym + (int64_t)u * stride + first;
         w.more = u + 1 < U;
 
         // the memory of this user does not wait for the anchor: the first loads go out before the exchange ends
         float4 ev[CP_AHEAD];
-        if (full) {
 #pragma unroll
-            for (int k = 0; k < CP_AHEAD; ++k)
-                ev[k] = k < KPT ? ld_stream_f4(w.eu + k * CP_RUN_STRIDE + lane4) : make_float4(0.f, 0.f, 0.f, 0.f);
-        } else {
-#pragma unroll
-            for (int k = 0; k < CP_AHEAD; ++k)
-                ev[k] = k < KPT ? ld4_run(w.eu + k * CP_RUN_STRIDE, w.left - k * CP_RUN_STRIDE, lane4) : make_float4(0.f, 0.f, 0.f, 0.f);
-        }
+        for (int k = 0; k < CP_AHEAD; ++k)
+            ev[k] = full && k < KPT ? ld_stream_f4(w.eu + k * CP_STEP + lane4) : make_float4(0.f, 0.f, 0.f, 0.f);
 
         const uint32_t mm = coop_collect_max(slots + (int64_t)u * G, G, spin_limit, red, status);
         int A = (int)(mm >> 23) - 127;
@@ -273,33 +256,46 @@ __global__ __launch_bounds__(CP_BLOCK) void k_coop_convert(const float *__restri
         w.A = A;
         w.e_min = A - F + 1;
 
-        if (full) coop_convert_user<KPT, HIST, true>(w, gr, ev);
-        else coop_convert_user<KPT, HIST, false>(w, gr, ev);
+        if (full) coop_convert_user<KPT, NIB>(w, gr, ev);
 
         if (w.more) {
             uint32_t m = 0;
+            if (full) {
 #pragma unroll
-            for (int k = 0; k < KPT; ++k) m = absbits4(gr[k], m);
+                for (int k = 0; k < KPT; ++k) m = absbits4(gr[k], m);
+            } else {
+                m = coop_ragged_max(w.gnext, w.left, KPT, lane4);
+            }
             coop_publish_max(m, slots + (int64_t)(u + 1) * G, red);
         }
-        if (HIST) {
-            // the workgroup's counts of this user -> global counters: entry j = symbol * copies + replica; a lane
-            // adds the eight wavefronts' entry j, the lanes of one symbol (consecutive) are summed by exchange
-            __syncthreads();
-            for (int j = threadIdx.x; j < K * copies; j += CP_BLOCK) {       // whole wavefronts take part or not
-                uint32_t c = 0;
-#pragma unroll
-                for (int wv = 0; wv < CP_WAVES; ++wv) {
-                    c += hist[wv * CP_HIST_SLOTS + j];
-                    hist[wv * CP_HIST_SLOTS + j] = 0u;
+        {
+            // The counts of this user.  Entry j of a wavefront's counters = symbol * copies + replica.  Every
+            // wavefront adds up its own counters: a lane takes consecutive entries (all of one symbol, or whole
+            // symbols), lanes that share a symbol finish by exchange.  The wavefronts' sums are added up and go to
+            // one of several partial tables (every workgroup adding to the same K words at the same moment
+            // serialises chip-wide, and the loads behind the atomics wait).  (A wavefront's counters are its
+            // own, and the sums of the user before this one were read before the barriers of this user's exchange.)
+            const int per = K * copies / CO3_WAVE;                 // entries per lane: a power of two, 2 .. 16
+            const int grp = per < copies ? per : copies;           // entries of one symbol that a lane holds together
+            uint32_t *h = hist + wave * CP_HIST_SLOTS;
+            for (int c0 = 0; c0 < per; c0 += grp) {
+                const int base = lane * per + c0;
+                uint32_t sum = 0;
+                for (int i = 0; i < grp; ++i) {
+                    sum += h[base + i];
+                    h[base + i] = 0u;
                 }
-                for (int o = copies >> 1; o >= 1; o >>= 1) c += (uint32_t)__shfl_xor((int)c, o, CO3_WAVE);
-                // (every workgroup adding to the same K words at the same moment serialises chip-wide, and the
-                // loads behind the atomics wait: the counts go to one of several partial tables)
-                if ((j & (copies - 1)) == 0 && c)
-                    atomicAdd(&counts[((int64_t)(blockIdx.x % CO3_COOP_COUNT_REPS) * U + u) * K + j / copies], c);
+                for (int o = 1; o * grp < copies; o <<= 1) sum += (uint32_t)__shfl_xor((int)sum, o, CO3_WAVE);
+                if (base % copies == 0) wavecnt[wave * 256 + base / copies] = sum;
             }
             __syncthreads();
+            if ((int)threadIdx.x < K) {
+                uint32_t c = 0;
+#pragma unroll
+                for (int wv = 0; wv < CP_WAVES; ++wv) c += wavecnt[wv * 256 + threadIdx.x];
+                if (c) atomicAdd(&counts[((int64_t)(blockIdx.x % CO3_COOP_COUNT_REPS) * U + u) * K + threadIdx.x], c);
+            }
+            // (the next user's counters are not read before the next pair of barriers)
         }
     }
 }
@@ -324,12 +320,19 @@ bool co3_coop_fits(int64_t n, int cus, int *kpt_out, int *grid_out)
     return true;
 }
 
+int64_t co3_coop_full_elements(int64_t n, int kpt)
+{
+    const int64_t part = (int64_t)kpt * CP_STEP;
+    return n / part * part;
+}
+
+
 template <int KPT>
 static void coop_launch_kpt(const float *g, float *err, uint8_t *sym, int64_t n, int U, int64_t stride, int grid,
                             int32_t *anchor, float gamma, co3_fmt fmt, uint32_t *counts, uint32_t *slots,
-                            uint32_t spin_limit, int32_t *status, hipStream_t st)
+                            uint32_t spin_limit, int32_t *status, int sym_nib, hipStream_t st)
 {
-    if (counts)
+    if (sym_nib)
         hipLaunchKernelGGL((k_coop_convert<KPT, true>), dim3(grid), dim3(CP_BLOCK), 0, st, g, err, sym, n, stride, U, anchor,
                            gamma, fmt, counts, slots, spin_limit, status);
     else
@@ -339,12 +342,14 @@ static void coop_launch_kpt(const float *g, float *err, uint8_t *sym, int64_t n,
 
 hipError_t co3_launch_coop_convert(const float *g, float *err, uint8_t *sym, int64_t n, int U, int64_t stride, int kpt,
                                    int grid, int32_t *anchor, float gamma, co3_fmt fmt, uint32_t *counts,
-                                   uint32_t *slots, uint32_t spin_limit, int32_t *status, hipStream_t st)
+                                   uint32_t *slots, uint32_t spin_limit, int32_t *status, int sym_nib, hipStream_t st)
 {
+    {
     Co3LaunchTimer tm(CO3_K_COOP, st);
 #define CO3_COOP_CASE(KPT)                                                                                         \
     case KPT:                                                                                                      \
-        coop_launch_kpt<KPT>(g, err, sym, n, U, stride, grid, anchor, gamma, fmt, counts, slots, spin_limit, status, st); \
+        coop_launch_kpt<KPT>(g, err, sym, n, U, stride, grid, anchor, gamma, fmt, counts, slots, spin_limit, status, sym_nib, \
+                             st);                                                                                  \
         break
     switch (kpt) {
         CO3_COOP_CASE(1);
@@ -357,5 +362,8 @@ hipError_t co3_launch_coop_convert(const float *g, float *err, uint8_t *sym, int
     default: return hipErrorInvalidValue;
     }
 #undef CO3_COOP_CASE
+    }
+    // (the ragged end of the vector -- what the last wavefront with elements holds when these are fewer than
+    // its kpt runs -- is left to the kernel that finishes the users, co3_launch_user_finish)
     return hipGetLastError();
 }

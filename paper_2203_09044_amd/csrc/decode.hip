@@ -643,14 +643,14 @@ __global__ __launch_bounds__(PT_WAVES(NIB) * CO3_WAVE) void k_ps_sum_tiled(const
                                                             const int32_t *__restrict__ anchor,
                                                             const float *__restrict__ scale,
                                                             const int64_t *__restrict__ seg_off_g, int nseg,
-                                                            co3_fmt fmt, float *__restrict__ avg_out)
+                                                            co3_fmt fmt, const float *acc_in, float divisor,
+                                                            float *avg_out)
 {
     constexpr int EPT = NIB ? 32 : 16;     // elements per thread
     constexpr int WAVES = PT_WAVES(NIB), PT_BLOCK = WAVES * CO3_WAVE;
     const FmtC fc(fmt);
     const int EM = fc.E + fc.M, M = fc.M, F = fc.F;
     const uint32_t cmask = (uint32_t)fc.codemax;
-    const float fU = (float)U;
     const int runs_per_chunk = chunk_syms / EPT;
     // value of symbol s of user u in tensor sg; with multipliers (scale != NULL) the level is divided by
     // the user's multiplier, one fp32 rounding
@@ -691,9 +691,24 @@ __global__ __launch_bounds__(PT_WAVES(NIB) * CO3_WAVE) void k_ps_sum_tiled(const
         const int64_t tile = q / runs_per_chunk;
         const int64_t i0 = (tile * CO3_WAVE + lane) * chunk_syms + (int64_t)run * EPT;
         const uint8_t *src = symt + r * 16;
+        // the sum starts at zero, or continues a sum over users before these (acc_in may be avg_out: every
+        // element is read and written by the same workgroup, the reads first)
         float acc[EPT];
 #pragma unroll
         for (int k = 0; k < EPT; ++k) acc[k] = 0.f;
+        if (acc_in && i0 < n) {
+            if (i0 + EPT <= n) {
+#pragma unroll
+                for (int k = 0; k < EPT; k += 4) {
+                    const float4 a = *reinterpret_cast<const float4 *>(acc_in + i0 + k);
+                    acc[k] = a.x, acc[k + 1] = a.y, acc[k + 2] = a.z, acc[k + 3] = a.w;
+                }
+            } else {
+#pragma unroll
+                for (int k = 0; k < EPT; ++k)
+                    if (i0 + k < n) acc[k] = acc_in[i0 + k];
+            }
+        }
         const int64_t i_first = i0 < n ? i0 : n - 1;       // lanes past the end compute on the last element's
         const int s_lo = co3_find_seg(seg_off, nseg, i_first);   // tensor and store nothing
         const int64_t i_last = i0 + EPT - 1 < n ? i0 + EPT - 1 : n - 1;
@@ -737,7 +752,7 @@ __global__ __launch_bounds__(PT_WAVES(NIB) * CO3_WAVE) void k_ps_sum_tiled(const
             }
         }
 #pragma unroll
-        for (int k = 0; k < EPT; ++k) out_s[lane][wr * EPT + k] = acc[k] / fU;
+        for (int k = 0; k < EPT; ++k) out_s[lane][wr * EPT + k] = divisor > 0.f ? acc[k] / divisor : acc[k];
         __syncthreads();
         const int64_t run0 = (int64_t)(run - wr) * EPT;      // first element (within a chunk) of the block's runs
 #pragma unroll 4
@@ -786,7 +801,8 @@ hipError_t co3_launch_decode(const uint64_t *words, int64_t cap_words, const uin
 
 hipError_t co3_launch_ps_sum_tiled(const uint8_t *symt, int64_t n, int U, int64_t ws_stride, int chunk_syms,
                                    const int32_t *anchor, const float *scale, const int64_t *seg_off, int nseg,
-                                   co3_fmt fmt, int packed, float *avg_out, hipStream_t st)
+                                   co3_fmt fmt, int packed, const float *acc_in, float divisor, float *avg_out,
+                                   hipStream_t st)
 {
     if (n <= 0) return hipSuccess;
     const int64_t nchunks = (n + chunk_syms - 1) / chunk_syms;
@@ -799,7 +815,7 @@ hipError_t co3_launch_ps_sum_tiled(const uint8_t *symt, int64_t n, int U, int64_
     const size_t full_bytes = (size_t)U * (size_t)(1 << (1 + fmt.exp_bits + fmt.mant_bits)) * sizeof(float);
 #define CO3_SUM_LAUNCH(T, P, BYTES)                                                                                \
     hipLaunchKernelGGL((k_ps_sum_tiled<T, P>), dim3(blocks), dim3(threads), BYTES, st, symt, n, U, ws_stride,     \
-                       chunk_syms, nruns, anchor, scale, seg_off, nseg, fmt, avg_out)
+                       chunk_syms, nruns, anchor, scale, seg_off, nseg, fmt, acc_in, divisor, avg_out)
     if (packed) {       // alphabets of at most 16 symbols: the full table is 64 bytes per user
         if (nseg == 1 && full_bytes <= 4096) CO3_SUM_LAUNCH(1, true, full_bytes);
         else CO3_SUM_LAUNCH(0, true, 0);

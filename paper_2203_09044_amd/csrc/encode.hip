@@ -20,19 +20,44 @@ __device__ __forceinline__ const Co3Code *code_of(const void *codes, int u)
     return reinterpret_cast<const Co3Code *>(reinterpret_cast<const char *>(codes) + (size_t)u * CO3_CODE_BYTES);
 }
 
+// Eight symbols stored two per byte (the earlier one in the low half) -> two words of four symbol bytes.
+__device__ __forceinline__ void unpack_nib8(uint32_t w, uint32_t &b0, uint32_t &b1)
+{
+    const uint32_t lo = w & 0x0f0f0f0fu, hi = (w >> 4) & 0x0f0f0f0fu;      // symbols 0 2 4 6 / 1 3 5 7, one per byte
+    b0 = (lo & 0xffu) | ((hi & 0xffu) << 8) | ((lo & 0xff00u) << 8) | ((hi & 0xff00u) << 16);
+    b1 = ((lo >> 16) & 0xffu) | (((hi >> 16) & 0xffu) << 8) | ((lo >> 24) << 16) | ((hi >> 24) << 24);
+}
+
+// The 16 symbols from element i (a multiple of 16) on, all below n; NIB: the array holds two symbols per byte.
+__device__ __forceinline__ void load_syms16_full(const uint8_t *su, int64_t i, bool nib, uint32_t s[4])
+{
+    if (nib) {
+        const uint2 a = *reinterpret_cast<const uint2 *>(su + (i >> 1));
+        unpack_nib8(a.x, s[0], s[1]);
+        unpack_nib8(a.y, s[2], s[3]);
+    } else {
+        const uint4 a = *reinterpret_cast<const uint4 *>(su + i);
+        s[0] = a.x; s[1] = a.y; s[2] = a.z; s[3] = a.w;
+    }
+}
+
+__device__ __forceinline__ uint32_t load_sym1(const uint8_t *su, int64_t j, bool nib)
+{
+    return nib ? ((uint32_t)su[j >> 1] >> (4 * (int)(j & 1))) & 0xfu : (uint32_t)su[j];
+}
+
 // Loads the 16 symbols of this lane into s[0..4) (4 per word, first symbol in the low byte);
 // returns how many lie below n.
-__device__ __forceinline__ int load_syms16(const uint8_t *su, int64_t i, int64_t n, uint32_t s[4])
+__device__ __forceinline__ int load_syms16(const uint8_t *su, int64_t i, int64_t n, uint32_t s[4], bool nib = false)
 {
     if (i + EN_LSYM <= n) {
-        uint4 a = *reinterpret_cast<const uint4 *>(su + i);
-        s[0] = a.x; s[1] = a.y; s[2] = a.z; s[3] = a.w;
+        load_syms16_full(su, i, nib, s);
         return EN_LSYM;
     }
 #pragma unroll
     for (int k = 0; k < 4; ++k) s[k] = 0;
     int c = 0;
-    for (int64_t j = i; j < n; ++j, ++c) s[c >> 2] |= (uint32_t)su[j] << (8 * (c & 3));
+    for (int64_t j = i; j < n; ++j, ++c) s[c >> 2] |= load_sym1(su, j, nib) << (8 * (c & 3));
     return c;
 }
 
@@ -56,29 +81,53 @@ __global__ __launch_bounds__(EN_BLOCK) void k_enc_sizes(const uint8_t *__restric
                                                          const void *__restrict__ codes, int K,
                                                          uint64_t *__restrict__ tilesum, int64_t nblk,
                                                          uint64_t *__restrict__ groupsum, int64_t ngrp,
-                                                         int32_t *status)
+                                                         int32_t *status, int sym_nib)
 {
     const int u = blockIdx.y;
     const Co3Code *cd = code_of(codes, u);
     __shared__ uint8_t len_s[256];
+    __shared__ uint8_t pairlen_s[256];     // symbols two per byte: both lengths together, bit 7 set when one of them is 0
     __shared__ uint32_t tile_bits[SZ_GROUP];
     len_s[threadIdx.x] = (int)threadIdx.x < K ? cd->len[threadIdx.x] : (uint8_t)0;
     if (threadIdx.x < SZ_GROUP) tile_bits[threadIdx.x] = 0;
+    if (sym_nib) {
+        const int lo = threadIdx.x & 15, hi = threadIdx.x >> 4;
+        const uint32_t l0 = lo < K ? cd->len[lo] : 0u, l1 = hi < K ? cd->len[hi] : 0u;
+        pairlen_s[threadIdx.x] = (uint8_t)((l0 + l1) | (l0 == 0u || l1 == 0u ? 0x80u : 0u));
+    }
     __syncthreads();
 
     const int lane = threadIdx.x & (CO3_WAVE - 1);
     const int wave = threadIdx.x / CO3_WAVE;
     const int64_t tb0 = ((int64_t)blockIdx.x * EN_WAVES + wave) * SZ_TILES;
-    const uint8_t *su = sym + (int64_t)u * stride;
+    const bool nib = sym_nib != 0;
+    const uint8_t *su = sym + (int64_t)u * (nib ? stride / 2 : stride);
     uint32_t s[SZ_TILES][4];
     bool nocode = false;
     if (tb0 >= nblk) {                                // uniform: nothing for this wavefront
+    } else if (nib && (tb0 + SZ_TILES) * CO3_PACK_SYMS <= n) {     // uniform: four complete tiles, two symbols per byte
+        uint2 raw[SZ_TILES];
+#pragma unroll
+        for (int t = 0; t < SZ_TILES; ++t)
+            raw[t] = *reinterpret_cast<const uint2 *>(su + (((tb0 + t) * CO3_PACK_SYMS + (int64_t)lane * EN_LSYM) >> 1));
+#pragma unroll
+        for (int t = 0; t < SZ_TILES; ++t) {
+            uint32_t bits = 0, flags = 0;    // one lookup per byte
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                const uint32_t e = pairlen_s[((c < 4 ? raw[t].x : raw[t].y) >> (8 * (c & 3))) & 0xffu];
+                bits += e & 0x7fu;
+                flags |= e;
+            }
+            nocode |= (flags & 0x80u) != 0u;
+            bits = wave_sum_u32(bits);
+            if (lane == 0) tile_bits[wave * SZ_TILES + t] = bits;
+        }
     } else if ((tb0 + SZ_TILES) * CO3_PACK_SYMS <= n) {     // uniform: all four tiles are complete
 #pragma unroll
         for (int t = 0; t < SZ_TILES; ++t) {
             // ordinary (cached) loads: the packing pass reads the same symbols next
-            uint4 a = *reinterpret_cast<const uint4 *>(su + (tb0 + t) * CO3_PACK_SYMS + (int64_t)lane * EN_LSYM);
-            s[t][0] = a.x; s[t][1] = a.y; s[t][2] = a.z; s[t][3] = a.w;
+            load_syms16_full(su, (tb0 + t) * CO3_PACK_SYMS + (int64_t)lane * EN_LSYM, nib, s[t]);
         }
 #pragma unroll
         for (int t = 0; t < SZ_TILES; ++t) {
@@ -96,7 +145,7 @@ __global__ __launch_bounds__(EN_BLOCK) void k_enc_sizes(const uint8_t *__restric
     } else {                                          // the end of the vector
         for (int t = 0; t < SZ_TILES && tb0 + t < nblk; ++t) {
             const int64_t i = (tb0 + t) * CO3_PACK_SYMS + (int64_t)lane * EN_LSYM;
-            const int nvalid = i < n ? load_syms16(su, i, n, s[0]) : 0;
+            const int nvalid = i < n ? load_syms16(su, i, n, s[0], nib) : 0;
             uint32_t bits = 0;
 #pragma unroll
             for (int c = 0; c < EN_LSYM; ++c) {
@@ -326,6 +375,24 @@ __device__ __forceinline__ void lookup_runs_short(const uint64_t *enc_s, const u
     }
 }
 
+// Symbols stored two per byte (alphabets of at most 16 symbols: no codeword exceeds 15 bits): one lookup per
+// byte in a table of codeword pairs, (both codewords joined << 6 | both lengths), the earlier symbol's
+// codeword on top; the two pairs of four consecutive symbols make a run of at most 60 bits.
+__device__ __forceinline__ void lookup_runs_pairs(const uint64_t *penc_s, uint2 raw, uint64_t run[EN_LSYM / 4],
+                                                  uint32_t runbits[EN_LSYM / 4], uint32_t &mybits)
+{
+#pragma unroll
+    for (int g = 0; g < EN_LSYM / 4; ++g) {
+        const uint32_t w = (g < 2 ? raw.x : raw.y) >> (16 * (g & 1));
+        const uint64_t p0 = penc_s[w & 0xffu], p1 = penc_s[(w >> 8) & 0xffu];
+        const uint32_t l1 = (uint32_t)(p1 & 63u);
+        const uint32_t nb = (uint32_t)(p0 & 63u) + l1;
+        run[g] = ((p0 >> 6) << l1) | (p1 >> 6);
+        runbits[g] = nb;
+        mybits += nb;
+    }
+}
+
 // ORs `nb` bits (right-aligned in `acc`, 1 <= nb <= 64) into the staging window at stream position
 // `pos` (bits, relative to the first word of the tile); only words inside the window are touched.
 __device__ __forceinline__ void stage_bits(unsigned long long *stage, int64_t win_w0, uint64_t acc, int nb,
@@ -343,28 +410,60 @@ __device__ __forceinline__ void stage_bits(unsigned long long *stage, int64_t wi
 // tensor, and a tile that straddles tensors (look-ahead included) reads its entries from the code
 // blobs, tensor by element.
 template <bool LAYERS>
-__global__ __launch_bounds__(EN_BLOCK) void k_enc_pack(const uint8_t *__restrict__ sym, int64_t n, int64_t stride,
-                                                        const void *__restrict__ codes, int K,
-                                                        const int64_t *__restrict__ seg_off_g, int nseg,
-                                                        const uint64_t *__restrict__ tileoff, int64_t nblk,
-                                                        const uint64_t *__restrict__ groupoff, int64_t ngrp,
-                                                        uint64_t *__restrict__ words, int64_t cap_words, int chunk_syms,
-                                                        uint64_t *__restrict__ chunk_bitoff, int64_t nchunks)
+__global__ __launch_bounds__(EN_BLOCK)
+void k_enc_pack(const uint8_t *__restrict__ sym, int64_t n, int64_t stride, const void *__restrict__ codes, int K,
+                const int64_t *__restrict__ seg_off_g, int nseg, const uint64_t *__restrict__ tileoff, int64_t nblk,
+                const uint64_t *__restrict__ groupoff, int64_t ngrp, uint64_t *__restrict__ words, int64_t cap_words,
+                int chunk_syms, uint64_t *__restrict__ chunk_bitoff, int64_t nchunks, int sym_nib)
 {
     const int u = blockIdx.y;
+    const bool nib = !LAYERS && sym_nib != 0;
     __shared__ uint64_t enc_all[LAYERS ? EN_WAVES * 256 : 256];
+    __shared__ uint64_t penc_s[LAYERS ? 1 : 256];        // codeword pairs, symbols two per byte
     __shared__ unsigned long long stage_all[EN_WAVES][EN_STAGE_WORDS];
     __shared__ int64_t seg_cache[LAYERS ? CO3_SEG_CACHE : 1];
     const int lane = threadIdx.x & (CO3_WAVE - 1);
     const int wave = threadIdx.x / CO3_WAVE;
-    const int64_t tb = (int64_t)blockIdx.x * EN_WAVES + wave;
+    const int64_t tb = (int64_t)blockIdx.x * EN_WAVES + wave;      // the wavefront's tile: elements [t0, t1)
+    const int64_t t0 = tb * CO3_PACK_SYMS;
+    const int64_t t1 = t0 + CO3_PACK_SYMS < n ? t0 + CO3_PACK_SYMS : n;
+    const bool whole_tile = t1 - t0 == CO3_PACK_SYMS;
+    // Everything the wavefront reads from memory apart from the tables is requested first, so that its latency
+    // and that of the table load below (with its barrier) overlap.
+    const uint8_t *su = sym + (int64_t)u * (nib ? stride / 2 : stride);
+    uint64_t *wu = words + (int64_t)u * cap_words;
+    const int64_t i = t0 + (int64_t)lane * EN_LSYM;
+    const bool live = tb < nblk;                     // uniform: the wavefront has a tile
+    // a complete tile of symbols stored two per byte stays in that form: one lookup per byte below
+    const bool raw_tile = nib && whole_tile;
+    uint32_t s[4] = {0u, 0u, 0u, 0u};
+    uint2 raw = make_uint2(0u, 0u);
+    int nvalid = EN_LSYM;
+    if (raw_tile) raw = *reinterpret_cast<const uint2 *>(su + (i >> 1));
+    else if (whole_tile) load_syms16_full(su, i, nib, s);
+    else nvalid = live && i < t1 ? load_syms16(su, i, t1, s, nib) : 0;
+    // the symbols that follow the tile (their codewords complete its last word): used at the end
+    const int64_t i2 = t1 + lane;
+    const bool has_next = live && t1 > t0 && lane < CO3_WAVE - 1 && i2 < n;
+    const uint32_t next_sym = has_next ? load_sym1(su, i2, nib) : 0u;
+    const uint64_t group_base = live ? groupoff[(int64_t)u * ngrp + tb / CO3_PACK_GROUP] : 0ull;
+    const uint64_t tile_base = live ? tileoff[(int64_t)u * nblk + tb] : 0ull;
+
     const uint64_t *enc_s = LAYERS ? enc_all + wave * 256 : enc_all;
     const int64_t *seg_off = seg_off_g;
     uint32_t maxlen;
     bool one_tensor = true;
     if (!LAYERS) {
         const Co3Code *cd = code_of(codes, u);
-        enc_all[threadIdx.x] = (int)threadIdx.x < K ? cd->enc[threadIdx.x] : 0ull;
+        for (int j = threadIdx.x; j < 256; j += blockDim.x) {
+            enc_all[j] = j < K ? cd->enc[j] : 0ull;
+            if (nib) {
+                const int lo = j & 15, hi = j >> 4;
+                const uint64_t e0 = lo < K ? cd->enc[lo] : 0ull, e1 = hi < K ? cd->enc[hi] : 0ull;
+                const uint32_t l1 = (uint32_t)(e1 & 63u);
+                penc_s[j] = ((((e0 >> 6) << l1) | (e1 >> 6)) << 6) | (uint64_t)((uint32_t)(e0 & 63u) + l1);
+            }
+        }
         maxlen = cd->maxlen;
         __syncthreads();
         if (tb >= nblk) return;
@@ -373,7 +472,7 @@ __global__ __launch_bounds__(EN_BLOCK) void k_enc_pack(const uint8_t *__restrict
         __syncthreads();
         if (tb >= nblk) return;
         // tensors of the tile and of the at most 63 following symbols whose codewords complete its last word
-        const int64_t t_lo = tb * CO3_PACK_SYMS;
+        const int64_t t_lo = t0;
         int64_t t_hi = t_lo + CO3_PACK_SYMS + CO3_WAVE - 1;
         t_hi = (t_hi < n ? t_hi : n) - 1;
         const int s_lo = co3_find_seg(seg_off, nseg, t_lo), s_hi = co3_find_seg(seg_off, nseg, t_hi);
@@ -392,17 +491,6 @@ __global__ __launch_bounds__(EN_BLOCK) void k_enc_pack(const uint8_t *__restrict
     }
     unsigned long long *stage = stage_all[wave];
 
-    const uint8_t *su = sym + (int64_t)u * stride;
-    uint64_t *wu = words + (int64_t)u * cap_words;
-    const int64_t i = tb * CO3_PACK_SYMS + (int64_t)lane * EN_LSYM;
-    uint32_t s[4];
-    const int nvalid = i < n ? load_syms16(su, i, n, s) : 0;
-    // the symbols that follow the tile (their codewords complete its last word): requested now, used at the end
-    const int64_t i2 = (tb + 1) * CO3_PACK_SYMS + lane;
-    const bool has_next = lane < CO3_WAVE - 1 && i2 < n;
-    const uint32_t next_sym = has_next ? su[i2] : 0u;
-    const uint64_t group_base = groupoff[(int64_t)u * ngrp + tb / CO3_PACK_GROUP];     // likewise
-    const uint64_t tile_base = tileoff[(int64_t)u * nblk + tb];
     // packed (codeword << 6 | length) of symbol sy at element idx
     auto entry_at = [&](uint32_t sy, int64_t idx) -> uint64_t {
         if (!LAYERS || one_tensor) return enc_s[sy];
@@ -429,7 +517,9 @@ __global__ __launch_bounds__(EN_BLOCK) void k_enc_pack(const uint8_t *__restrict
     uint32_t runbits[EN_LSYM / 4];
     uint32_t mybits = 0;
     bool wide = false;
-    if ((tb + 1) * CO3_PACK_SYMS <= n) {    // uniform: every symbol of the tile exists
+    if (raw_tile) {
+        lookup_runs_pairs(penc_s, raw, run, runbits, mybits);
+    } else if (whole_tile) {    // uniform: every symbol of the tile exists
         if (maxlen <= 16u)
             lookup_runs_short(enc_s, s, run, runbits, mybits);
         else
@@ -555,8 +645,9 @@ hipError_t co3_launch_enc_scan(uint64_t *sizes, int64_t nsizes, int U, int64_t c
 hipError_t co3_launch_encode(const uint8_t *sym, int64_t n, int U, int64_t stride, const void *codes, int K,
                              const int64_t *seg_off, int nseg, uint64_t *words, int64_t cap_words, int chunk_syms,
                              uint64_t *chunk_bitoff, uint64_t *total_bits, uint64_t *tilesum, int32_t *status,
-                             hipStream_t st)
+                             hipStream_t st, int sym_nib)
 {
+    if (sym_nib && (seg_off || K > 16)) return hipErrorInvalidValue;
     static_assert(SZ_GROUP == CO3_PACK_GROUP, "group size of the sizes pass");
     const int64_t nblk = (n + CO3_PACK_SYMS - 1) / CO3_PACK_SYMS;
     const int64_t ngrp = (nblk + CO3_PACK_GROUP - 1) / CO3_PACK_GROUP;
@@ -569,7 +660,7 @@ hipError_t co3_launch_encode(const uint8_t *sym, int64_t n, int U, int64_t strid
                                K, seg_off, nseg, tilesum, nblk, groupsum, ngrp, status);
         else
             hipLaunchKernelGGL(k_enc_sizes, dim3((unsigned)ngrp, U), dim3(EN_BLOCK), 0, st, sym, n, stride, codes, K,
-                               tilesum, nblk, groupsum, ngrp, status);
+                               tilesum, nblk, groupsum, ngrp, status, sym_nib);
     }
     if (co3_launch_enc_scan(groupsum, ngrp, U, cap_words, chunk_bitoff, nchunks, total_bits, status, st) != hipSuccess)
         return hipGetLastError();
@@ -579,11 +670,11 @@ hipError_t co3_launch_encode(const uint8_t *sym, int64_t n, int U, int64_t strid
         if (seg_off)
             hipLaunchKernelGGL(k_enc_pack<true>, dim3(gx, U), dim3(EN_BLOCK), 0, st, sym, n, stride, codes, K, seg_off,
                                nseg, (const uint64_t *)tilesum, nblk, (const uint64_t *)groupsum, ngrp, words,
-                               cap_words, chunk_syms, chunk_bitoff, nchunks);
+                               cap_words, chunk_syms, chunk_bitoff, nchunks, 0);
         else
             hipLaunchKernelGGL(k_enc_pack<false>, dim3(gx, U), dim3(EN_BLOCK), 0, st, sym, n, stride, codes, K, seg_off,
                                nseg, (const uint64_t *)tilesum, nblk, (const uint64_t *)groupsum, ngrp, words,
-                               cap_words, chunk_syms, chunk_bitoff, nchunks);
+                               cap_words, chunk_syms, chunk_bitoff, nchunks, sym_nib);
     }
     return hipGetLastError();
 }

@@ -132,9 +132,12 @@ class Co3SGD:
             st = pipe.poll()
             if st == B.OK:
                 break
-            if st != B.ECAP or attempt == 3:
+            # total_bits holds what every stream needs, also after an overrun (the server's decoder then met a
+            # truncated stream and may have reported that on top: the status word keeps the lowest code)
+            need = (int(pipe.total_bits.max().item()) + 63) // 64
+            if need <= pipe.cap_words or attempt == 3:
                 raise B.Co3Error(st, "Co3SGD.step")
-            pipe.grow_capacity((int(pipe.total_bits.max().item()) + 63) // 64)      # total_bits holds what every stream needs
+            pipe.grow_capacity(need)
             pipe.status.zero_()
             self.capacity_growths += 1
             if self.err_before is not None:

@@ -131,3 +131,66 @@ def test_a_wait_that_runs_out_is_reported_and_the_kernel_ends(co3):
     pipe.err.zero_()
     pipe.step(g)
     assert pipe.poll() == 0
+
+
+@pytest.mark.parametrize("n", [1, 255, 256, 1023, 5631, 5632, 5633, 256 * 2048 * 3 + 17])
+def test_ragged_ends_of_the_resident_grid(co3, n):
+    """Sizes around the boundaries of the resident grid's parts (whole parts in the grid, the ragged end in
+    the kernel that finishes the users, parts with no element at all)."""
+    run_one_call(co3, 4, n, co3.Fmt(3, 1), 64, betas=[0.7, 1.2], T=2, seed=n)
+    run_one_call(co3, 4, n, co3.Fmt(3, 0), 64, betas=[0.7, 1.2], T=2, seed=n + 1, keep_symbols=False)
+
+
+def test_ten_chained_iterations_at_a_size_that_fills_the_device(co3):
+    run_one_call(co3, 6, 256 * 2048 * 8 + 999, co3.Fmt(3, 0), 256, betas=[0.5, 1.5, 1.0], T=10, keep_symbols=False)
+    run_one_call(co3, 2, 256 * 2048 * 12 + 1, co3.Fmt(4, 3), 256, betas=[0.8], T=2)
+
+
+def test_average_continued_over_groups_of_users(co3):
+    """co3_ps_aggregate_partial: sums over groups of users chained through acc_in, one division at the end =
+    co3_ps_aggregate over all users = the oracle's average, bit for bit; acc_in may be the output array; an
+    undivided partial sum is the plain fp32 sum of the group's values."""
+    B = co3.binding
+    fmt = co3.Fmt(3, 1)
+    U, n, C = 7, 200_003, 256
+    pipe = run_one_call(co3, U, n, fmt, C, betas=[0.6, 1.0, 1.5], T=1)
+    want = pipe.avg.clone()
+    for cuts in ([0, 3, 7], [0, 1, 2, 7], [0, 7], [0, 2, 4, 6, 7]):
+        acc = torch.zeros_like(pipe.avg)
+        out = torch.full_like(pipe.avg, float("nan"))
+        for j, (a, b) in enumerate(zip(cuts[:-1], cuts[1:])):
+            last = b == U
+            ws = torch.zeros((B.ps_aggregate_workspace_bytes(n, b - a, C),), dtype=torch.uint8, device="cuda")
+            B.ps_aggregate_partial(pipe.words[a:b], pipe.chunk_bitoff[a:b], C, pipe.codes[a:b], fmt, n, b - a,
+                                   pipe.anchor[a:b], None if j == 0 else acc, U if last else 0, out if last else acc,
+                                   ws, pipe.status)
+        assert pipe.poll() == 0
+        assert torch.equal(out[:n].view(torch.int32), want[:n].view(torch.int32)), cuts
+    # an undivided sum of users 2..4 against the oracle's values added in order
+    f = ofmt(fmt)
+    ws = torch.zeros((B.ps_aggregate_workspace_bytes(n, 3, C),), dtype=torch.uint8, device="cuda")
+    part = torch.zeros_like(pipe.avg)
+    B.ps_aggregate_partial(pipe.words[2:5], pipe.chunk_bitoff[2:5], C, pipe.codes[2:5], fmt, n, 3, pipe.anchor[2:5], None, 0,
+                           part, ws, pipe.status)
+    s = np.zeros(n, np.float32)
+    for u in range(2, 5):
+        s = s + oracle.aggregate(pipe.sym[u:u + 1, :n].cpu().numpy(), pipe.anchor[u:u + 1].cpu().numpy(), f)
+    assert np.array_equal(part[:n].cpu().numpy().view(np.uint32), s.view(np.uint32))
+    assert B._lib.co3_ps_aggregate_partial(None, 2, None, 256, None, fmt.c(), 10, 1, None, None, 1, None, -1, None, None, 0,
+                                           None, None) == B.EINVAL
+
+
+@pytest.mark.parametrize("E,M", [(3, 0), (2, 0), (1, 2)])
+@pytest.mark.parametrize("n", [1, 3, 5, 255, 1023, 1025, 5631, 5633, 65_541, 256 * 2048 + 4097])
+def test_symbols_kept_inside_the_call_take_four_bits(co3, E, M, n):
+    """Alphabets of at most 16 symbols with no symbol array asked for: between conversion and compression
+    the symbols are held two per byte.  Everything that leaves the call must be what the oracle says."""
+    run_one_call(co3, 3, n, co3.Fmt(E, M), 64, betas=[0.6, 1.0, 1.6], T=2, keep_symbols=False, seed=n)
+
+
+def test_symbols_kept_inside_the_call_with_tensors(co3):
+    """The same on the path of the separate kernels (several tensors per user: anchors per tensor, tiles that
+    straddle tensors, one-element and empty tensors, a ragged end)."""
+    for sizes in ([70_000, 13, 300_001, 1, 0, 50_000], [3, 3, 3, 2], [1024, 1, 1023, 2048 + 7]):
+        run_one_call(co3, 2, sum(sizes), co3.Fmt(3, 0), 256, betas=[0.8, 1.3], T=2, sizes=sizes, keep_symbols=False)
+        run_one_call(co3, 3, sum(sizes), co3.Fmt(1, 2), 64, betas=[1.0], T=2, sizes=sizes, keep_symbols=False, gamma=0.9)
