@@ -377,7 +377,7 @@ def main():
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic_C3.txt")
     if args.workload == "C3" and args.bias == "absmax" and args.codes == "user" and os.path.exists(tpath):
         for line in open(tpath):
-            if line.startswith(B.kernel_name(dominant) + " "):
+            if line.startswith(B.kernel_name(dominant)):
                 try:
                     traffic = float(line.split()[-1]) * 1e6
                     traffic_source = "profiles/hbm_traffic_C3.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, stored summary)"

@@ -409,8 +409,11 @@ __device__ __forceinline__ void stage_bits(unsigned long long *stage, int64_t wi
 // code per tensor shared by all users (codes[tensor]); each wavefront keeps the table of its tile's
 // tensor, and a tile that straddles tensors (look-ahead included) reads its entries from the code
 // blobs, tensor by element.
+// The per-user form is compiled for eight wavefronts per SIMD (64 registers; a few spills on the rarely taken
+// paths): the kernel is bound by the latency of its per-tile chain, and residency is what hides it (C3:
+// 61 -> 55 us against six wavefronts per SIMD).
 template <bool LAYERS>
-__global__ __launch_bounds__(EN_BLOCK)
+__global__ __launch_bounds__(EN_BLOCK) __attribute__((amdgpu_waves_per_eu(LAYERS ? 5 : 8, LAYERS ? 5 : 8)))
 void k_enc_pack(const uint8_t *__restrict__ sym, int64_t n, int64_t stride, const void *__restrict__ codes, int K,
                 const int64_t *__restrict__ seg_off_g, int nseg, const uint64_t *__restrict__ tileoff, int64_t nblk,
                 const uint64_t *__restrict__ groupoff, int64_t ngrp, uint64_t *__restrict__ words, int64_t cap_words,
