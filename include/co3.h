@@ -240,6 +240,23 @@ int32_t co3_ps_aggregate_partial(const uint64_t *words, int64_t cap_words, const
                                  void *stream);
 
 /*
+ * The two halves of co3_ps_aggregate (Alg. 1, PS decompression step; Sec. II-A aggregate) as calls of their
+ * own, for a server that decompresses the users' streams in groups -- as they arrive, or on several HIP
+ * streams at once -- and averages when all are there:
+ *   co3_ps_decode_users  decompresses the streams of U consecutive users (pointers at the first of them) into
+ *                        their places first_user .. first_user + U - 1 of the averaging workspace of U_total
+ *                        users (co3_ps_aggregate_workspace_bytes(n, U_total, chunk_syms) bytes)
+ *   co3_ps_average       the average of all U users from a workspace that every user has been decompressed
+ *                        into: exactly co3_ps_aggregate's second half (same additions, same order)
+ * Arguments and errors as co3_ps_aggregate.
+ */
+int32_t co3_ps_decode_users(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff, int32_t chunk_syms,
+                            const void *codes, co3_fmt fmt, int64_t n, int32_t U, int32_t first_user, int32_t U_total,
+                            void *workspace, size_t ws_bytes, int32_t *status, void *stream);
+int32_t co3_ps_average(const void *workspace, size_t ws_bytes, int32_t chunk_syms, co3_fmt fmt, int64_t n, int32_t U,
+                       const int32_t *anchor, const int64_t *seg_off, int32_t nseg, float *avg_out, void *stream);
+
+/*
  * co3_ps_aggregate for streams made with co3_convert_ef_scaled: v_u = fl32(value_{A_u}(symbol) / c_u) with
  * the multipliers scale [U][nseg] of the users (Sec. III (i): the receiver undoes the bias).
  */

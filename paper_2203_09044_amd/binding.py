@@ -29,7 +29,7 @@ EXPORTS = (
     "co3_histogram_layers", "co3_encode_layers", "co3_decode_layers", "co3_ps_aggregate_layers",
     "co3_convert_encode_workspace_bytes", "co3_convert_encode", "co3_convert_encode_layers", "co3_encode_static",
     "co3_user_encode_workspace_bytes", "co3_user_encode", "co3_set_exchange_spin_limit", "co3_design_layer_tables",
-    "co3_ps_aggregate_partial",
+    "co3_ps_aggregate_partial", "co3_ps_decode_users", "co3_ps_average",
 )
 KERNEL_COUNT = 13
 
@@ -101,6 +101,10 @@ def _load():
     L.co3_user_encode_workspace_bytes.argtypes = [i64, i32, i64, i32, i32]
     L.co3_user_encode.restype = i32
     L.co3_user_encode.argtypes = [p, p, i64, i32, i64, p, i32, p, C.c_float, _Fmt, p, p, p, i64, i32, p, p, p, p, sz, p, p]
+    L.co3_ps_decode_users.restype = i32
+    L.co3_ps_decode_users.argtypes = [p, i64, p, i32, p, _Fmt, i64, i32, i32, i32, p, sz, p, p]
+    L.co3_ps_average.restype = i32
+    L.co3_ps_average.argtypes = [p, sz, i32, _Fmt, i64, i32, p, p, i32, p, p]
     L.co3_ps_aggregate_partial.restype = i32
     L.co3_ps_aggregate_partial.argtypes = [p, i64, p, i32, p, _Fmt, i64, i32, p, p, i32, p, i32, p, p, sz, p, p]
     L.co3_set_exchange_spin_limit.restype = None
@@ -347,6 +351,22 @@ def ps_aggregate_partial(words, chunk_bitoff, chunk_syms, codes, fmt: Fmt, n, U,
                                        workspace.numel() * workspace.element_size(), _dp(status, torch.int32),
                                        _stream(stream))
     _chk(rc, "co3_ps_aggregate_partial")
+
+
+def ps_decode_users(words, chunk_bitoff, chunk_syms, codes, fmt: Fmt, n, U, first_user, U_total, workspace, status, stream=None):
+    """Decompresses U users (tensors sliced to them) into their places of the averaging workspace of U_total users."""
+    rc = _lib.co3_ps_decode_users(_dp(words, torch.int64), words.shape[-1], _dp(chunk_bitoff, torch.int64), chunk_syms,
+                                  _dp(codes, torch.uint8), fmt.c(), n, U, first_user, U_total, _dp(workspace),
+                                  workspace.numel() * workspace.element_size(), _dp(status, torch.int32), _stream(stream))
+    _chk(rc, "co3_ps_decode_users")
+
+
+def ps_average(workspace, chunk_syms, fmt: Fmt, n, U, anchor, avg_out, seg_off=None, stream=None):
+    nseg = 1 if seg_off is None else seg_off.numel() - 1
+    rc = _lib.co3_ps_average(_dp(workspace), workspace.numel() * workspace.element_size(), chunk_syms, fmt.c(), n, U,
+                             _dp(anchor, torch.int32), _dp(seg_off, torch.int64), nseg, _dp(avg_out, torch.float32),
+                             _stream(stream))
+    _chk(rc, "co3_ps_average")
 
 
 def model_weights(A: int, fmt: Fmt, beta: float, alpha: float):

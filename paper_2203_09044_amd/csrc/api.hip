@@ -339,10 +339,12 @@ int32_t co3_user_encode(const float *g, float *err, int64_t n, int32_t U, int64_
     // symbols that stay inside the call take four bits each where the alphabet allows
     const int nib = !sym && fc.K <= 16 && (U == 1 || stride % 2 == 0) ? 1 : 0;
     int kpt = 0, grid = 0;
-    if (user_encode_coop(n, nseg, &kpt, &grid)) {
+    const bool coop = user_encode_coop(n, nseg, &kpt, &grid);
+    uint32_t *counts_rep = nullptr;
+    if (coop) {
         uint32_t *slots = reinterpret_cast<uint32_t *>(ws);
         ws += round_up_256((size_t)U * (size_t)grid * sizeof(uint32_t));
-        uint32_t *counts_rep = reinterpret_cast<uint32_t *>(ws);
+        counts_rep = reinterpret_cast<uint32_t *>(ws);
         // exchange words and partial counters start at zero
         if (co3_launch_fill(reinterpret_cast<int32_t *>(slots), (int64_t)U * grid, 0, counts_rep,
                             (int64_t)CO3_COOP_COUNT_REPS * U * fc.K, st) != hipSuccess)
@@ -350,19 +352,19 @@ int32_t co3_user_encode(const float *g, float *err, int64_t n, int32_t U, int64_
         if (co3_launch_coop_convert(g, err, symbuf, n, U, stride, kpt, grid, anchor, gamma, fmt, counts_rep, slots,
                                     g_spin_limit.load(), status, nib, st) != hipSuccess)
             return CO3_EHIP;
-        // the ragged end of the vector, the counts (partial tables added up) and the code of every user: one launch
-        if (co3_launch_user_finish(g, err, symbuf, n, co3_coop_full_elements(n, kpt), stride, U, anchor, gamma, fmt, nib,
-                                   counts_rep, CO3_COOP_COUNT_REPS, counts, codes, status, st) != hipSuccess)
-            return CO3_EHIP;
-        return hip_rc(co3_launch_encode(symbuf, n, U, stride, codes, fc.K, nullptr, 1, words, cap_words, chunk_syms,
-                                        chunk_bitoff, total_bits, static_cast<uint64_t *>(enc_ws), status, st, nib));
+    } else {
+        const int32_t rc = convert_common(g, err, symbuf, n, U, stride, seg_off, nseg, anchor, CO3_ANCHOR_FROM_ABSMAX_G,
+                                          nullptr, gamma, fmt, counts, stream, nib);
+        if (rc != CO3_OK) return rc;
     }
-    const int32_t rc = convert_common(g, err, symbuf, n, U, stride, seg_off, nseg, anchor, CO3_ANCHOR_FROM_ABSMAX_G,
-                                      nullptr, gamma, fmt, counts, stream, nib);
-    if (rc != CO3_OK) return rc;
-    if (co3_launch_build_code(counts, U, fc.K, codes, status, st) != hipSuccess) return CO3_EHIP;
-    return hip_rc(co3_launch_encode(symbuf, n, U, stride, codes, fc.K, nullptr, 1, words, cap_words, chunk_syms,
-                                    chunk_bitoff, total_bits, static_cast<uint64_t *>(enc_ws), status, st, nib));
+    // the codes (after a resident grid: with the ragged end of the vector and the partial count tables added
+    // up, in the same launch), then the compression
+    const hipError_t e = coop ? co3_launch_user_finish(g, err, symbuf, n, co3_coop_full_elements(n, kpt), stride, U, anchor, gamma,
+                                                       fmt, nib, counts_rep, CO3_COOP_COUNT_REPS, counts, codes, status, st, 0, U)
+                              : co3_launch_build_code(counts, U, fc.K, codes, status, st);
+    if (e != hipSuccess) return CO3_EHIP;
+    return hip_rc(co3_launch_encode(symbuf, n, U, stride, codes, fc.K, nullptr, 1, words, cap_words, chunk_syms, chunk_bitoff,
+                                    total_bits, static_cast<uint64_t *>(enc_ws), status, st, nib));
 }
 
 int32_t co3_moments(const float *g, const float *err, int64_t n, int32_t U, int64_t stride, const int64_t *seg_off,
@@ -538,6 +540,37 @@ int32_t co3_ps_aggregate_partial(const uint64_t *words, int64_t cap_words, const
     if (divide_by < 0) return CO3_EINVAL;
     return aggregate_common(words, cap_words, chunk_bitoff, chunk_syms, codes, nullptr, 1, fmt, n, U, anchor, nullptr,
                             seg_off, nseg, out, workspace, ws_bytes, status, stream, acc_in, divide_by);
+}
+
+int32_t co3_ps_decode_users(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff, int32_t chunk_syms,
+                            const void *codes, co3_fmt fmt, int64_t n, int32_t U, int32_t first_user, int32_t U_total,
+                            void *workspace, size_t ws_bytes, int32_t *status, void *stream)
+{
+    if (!fmt_ok(fmt) || n < 0 || n >= ((int64_t)1 << 32) || U < 1 || !chunk_ok(chunk_syms) || cap_words < 0 || cap_words % 2)
+        return CO3_EINVAL;
+    if (first_user < 0 || U_total < 1 || first_user + U > U_total) return CO3_EINVAL;
+    if (!words || !chunk_bitoff || !codes || !workspace) return CO3_EINVAL;
+    if (!aligned(workspace, 16) || !aligned(words, 16) || !aligned(codes, 8)) return CO3_EINVAL;
+    const size_t need = co3_ps_aggregate_workspace_bytes(n, U_total, chunk_syms);
+    if (ws_bytes < need) return CO3_EINVAL;
+    const int64_t ws_stride = (int64_t)(need / (size_t)U_total);
+    uint8_t *symws = static_cast<uint8_t *>(workspace) + (size_t)first_user * (size_t)ws_stride;
+    return hip_rc(co3_launch_decode(words, cap_words, chunk_bitoff, chunk_syms, codes, nullptr, 1, FmtC(fmt).K, n, U, symws,
+                                    ws_stride, 1, status, static_cast<hipStream_t>(stream)));
+}
+
+int32_t co3_ps_average(const void *workspace, size_t ws_bytes, int32_t chunk_syms, co3_fmt fmt, int64_t n, int32_t U,
+                       const int32_t *anchor, const int64_t *seg_off, int32_t nseg, float *avg_out, void *stream)
+{
+    if (!fmt_ok(fmt) || n < 0 || n >= ((int64_t)1 << 32) || U < 1 || !chunk_ok(chunk_syms)) return CO3_EINVAL;
+    if (nseg < 1 || (seg_off == nullptr && nseg != 1)) return CO3_EINVAL;
+    if (!workspace || !anchor || !avg_out || !aligned(workspace, 16) || !aligned(avg_out, 16)) return CO3_EINVAL;
+    const size_t need = co3_ps_aggregate_workspace_bytes(n, U, chunk_syms);
+    if (ws_bytes < need) return CO3_EINVAL;
+    const int packed = co3_ws_packed(FmtC(fmt).K, chunk_syms, 0) ? 1 : 0;
+    return hip_rc(co3_launch_ps_sum_tiled(static_cast<const uint8_t *>(workspace), n, U, (int64_t)(need / (size_t)U), chunk_syms,
+                                          anchor, nullptr, seg_off, nseg, fmt, packed, nullptr, (float)U, avg_out,
+                                          static_cast<hipStream_t>(stream)));
 }
 
 int32_t co3_ps_aggregate_scaled(const uint64_t *words, int64_t cap_words, const uint64_t *chunk_bitoff,

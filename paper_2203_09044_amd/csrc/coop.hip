@@ -182,6 +182,19 @@ __device__ __forceinline__ uint32_t coop_ragged_max(const float *gu, int64_t lef
     return m;
 }
 
+#ifdef CO3_COOP_TRACE
+__device__ unsigned long long co3_coop_trace[4 * 64 * 8];
+#define CP_TRACE(i)                                                                                   \
+    if (threadIdx.x == 0 && (blockIdx.x & 63) == 0 && u < 64)                                         \
+        co3_coop_trace[((blockIdx.x >> 6) * 64 + u) * 8 + (i)] = wall_clock64();
+extern "C" int co3_debug_coop_trace(unsigned long long *host)
+{
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(co3_coop_trace), sizeof(co3_coop_trace));
+}
+#else
+#define CP_TRACE(i)
+#endif
+
 // grid: G workgroups (at most one per compute unit, all resident); workgroup w owns elements
 // [w * KPT * 2048, (w + 1) * KPT * 2048) of every user, wavefront v of it the v-th eighth, lane l of the
 // wavefront elements 4l .. 4l+3 of each of the wavefront's KPT runs of 256.
@@ -244,6 +257,7 @@ __global__ __launch_bounds__(CP_BLOCK) __attribute__((amdgpu_waves_per_eu(CP_WAV
 
         // the memory of this user does not wait for the anchor: the first loads go out before the exchange ends
         float4 ev[CP_AHEAD];
+        CP_TRACE(0)
 #pragma unroll
         for (int k = 0; k < CP_AHEAD; ++k)
             ev[k] = full && k < KPT ? ld_stream_f4(w.eu + k * CP_STEP + lane4) : make_float4(0.f, 0.f, 0.f, 0.f);
@@ -255,8 +269,10 @@ __global__ __launch_bounds__(CP_BLOCK) __attribute__((amdgpu_waves_per_eu(CP_WAV
         if (blockIdx.x == 0 && threadIdx.x == 0) anchor[u] = A;
         w.A = A;
         w.e_min = A - F + 1;
+        CP_TRACE(1)
 
         if (full) coop_convert_user<KPT, NIB>(w, gr, ev);
+        CP_TRACE(2)
 
         if (w.more) {
             uint32_t m = 0;
@@ -266,7 +282,12 @@ __global__ __launch_bounds__(CP_BLOCK) __attribute__((amdgpu_waves_per_eu(CP_WAV
             } else {
                 m = coop_ragged_max(w.gnext, w.left, KPT, lane4);
             }
+#ifdef CO3_COOP_TRACE
+            asm volatile("" ::"v"(m));                // the time stamp comes after the loads have landed
+#endif
+            CP_TRACE(3)
             coop_publish_max(m, slots + (int64_t)(u + 1) * G, red);
+            CP_TRACE(4)
         }
         {
             // The counts of this user.  Entry j of a wavefront's counters = symbol * copies + replica.  Every
@@ -297,6 +318,7 @@ __global__ __launch_bounds__(CP_BLOCK) __attribute__((amdgpu_waves_per_eu(CP_WAV
             }
             // (the next user's counters are not read before the next pair of barriers)
         }
+        CP_TRACE(5)
     }
 }
 

@@ -687,8 +687,8 @@ __global__ __launch_bounds__(PT_WAVES(NIB) * CO3_WAVE) void k_ps_sum_tiled(const
         const int lane = (int)(r & 63);
         const int wr = threadIdx.x >> 6;
         const int64_t q = r >> 6;
-        const int run = (int)(q % runs_per_chunk);
-        const int64_t tile = q / runs_per_chunk;
+        const int run = (int)(q & (runs_per_chunk - 1));             // runs per chunk: a power of two
+        const int64_t tile = q >> __builtin_ctz((unsigned)runs_per_chunk);
         const int64_t i0 = (tile * CO3_WAVE + lane) * chunk_syms + (int64_t)run * EPT;
         const uint8_t *src = symt + r * 16;
         // the sum starts at zero, or continues a sum over users before these (acc_in may be avg_out: every
@@ -710,9 +710,9 @@ __global__ __launch_bounds__(PT_WAVES(NIB) * CO3_WAVE) void k_ps_sum_tiled(const
             }
         }
         const int64_t i_first = i0 < n ? i0 : n - 1;       // lanes past the end compute on the last element's
-        const int s_lo = co3_find_seg(seg_off, nseg, i_first);   // tensor and store nothing
+        const int s_lo = TABLE ? 0 : co3_find_seg(seg_off, nseg, i_first);   // tensor and store nothing
         const int64_t i_last = i0 + EPT - 1 < n ? i0 + EPT - 1 : n - 1;
-        const int s_hi = co3_find_seg(seg_off, nseg, i_last);
+        const int s_hi = TABLE ? 0 : co3_find_seg(seg_off, nseg, i_last);
         if (i0 >= n) {
         } else if (TABLE) {
             for (int u = 0; u < U; ++u) {

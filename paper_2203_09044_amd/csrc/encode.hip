@@ -537,8 +537,9 @@ void k_enc_pack(const uint8_t *__restrict__ sym, int64_t n, int64_t stride, cons
     const uint64_t B1 = B0 + tilebits;
 
     // chunk index: stream position of every chunk that starts at this lane's first symbol
+    // (chunk sizes are powers of two: a shift, not a 64-bit division that every lane of the wavefront would sit through)
     if (nvalid > 0 && (i & (int64_t)(chunk_syms - 1)) == 0)
-        chunk_bitoff[(int64_t)u * (nchunks + 1) + i / chunk_syms] = B0 + excl;
+        chunk_bitoff[(int64_t)u * (nchunks + 1) + (i >> __builtin_ctz((unsigned)chunk_syms))] = B0 + excl;
     // beyond the capacity nothing is written (the scan pass has reported it); uniform over the wavefront
     if ((B1 + 63) / 64 > (uint64_t)cap_words || tilebits == 0) return;
 

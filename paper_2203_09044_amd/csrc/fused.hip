@@ -284,7 +284,7 @@ __global__ __launch_bounds__(FU_BLOCK) void k_convert_stage(const float *__restr
 #pragma unroll
         for (int r = 0; r < FU_SUB; ++r) {
             const int64_t i = u0 + r * FU_RUN + lane * FU_VEC;
-            if (i < n && (i & (int64_t)(chunk_syms - 1)) == 0) chunk_local_u[i / chunk_syms] = pos[r];
+            if (i < n && (i & (int64_t)(chunk_syms - 1)) == 0) chunk_local_u[i >> __builtin_ctz((unsigned)chunk_syms)] = pos[r];
         }
 
         // the unit's bits, packed from bit 0 of the wavefront's LDS window, then copied to the unit's slot
@@ -416,7 +416,7 @@ __global__ __launch_bounds__(FU_BLOCK) void k_compact(const uint64_t *__restrict
     // chunk index: chunks whose first element lies in these units (chunks have at least 64 symbols)
     {
         const int64_t e0 = unit0 * CO3_FUSED_UNIT;
-        const int64_t c = (e0 + chunk_syms - 1) / chunk_syms + lane;
+        const int64_t c = ((e0 + chunk_syms - 1) >> __builtin_ctz((unsigned)chunk_syms)) + lane;      // a power of two
         const int64_t e = c * chunk_syms;
         if (e < n && e < e0 + (int64_t)CP_UNITS * CO3_FUSED_UNIT) {
             const int k = (int)((e - e0) / CO3_FUSED_UNIT);

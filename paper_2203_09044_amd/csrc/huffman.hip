@@ -42,12 +42,12 @@ __global__ __launch_bounds__(HB_BLOCK) void k_user_finish(const float *__restric
                                                            int64_t stride, const int32_t *__restrict__ anchor, float gamma,
                                                            co3_fmt fmt, int sym_nib, const uint32_t *__restrict__ counts_rep,
                                                            int nrep, uint32_t *__restrict__ counts, char *codes,
-                                                           int32_t *status)
+                                                           int32_t *status, int first_user, int U)
 {
     const FmtC fc(fmt);
     const int K = fc.K;
     const int tid = threadIdx.x;
-    const int u = blockIdx.x, U = gridDim.x;
+    const int u = first_user + blockIdx.x;       // users first_user .. first_user + gridDim.x - 1 of the batch of U
     __shared__ Co3BuildLds lds;
     __shared__ uint32_t hist[256];
     hist[tid] = 0u;
@@ -99,12 +99,13 @@ __global__ __launch_bounds__(HB_BLOCK) void k_user_finish(const float *__restric
 
 hipError_t co3_launch_user_finish(const float *g, float *err, uint8_t *sym, int64_t n, int64_t n_full, int64_t stride, int U,
                                   const int32_t *anchor, float gamma, co3_fmt fmt, int sym_nib, const uint32_t *counts_rep,
-                                  int nrep, uint32_t *counts, void *codes, int32_t *status, hipStream_t st)
+                                  int nrep, uint32_t *counts, void *codes, int32_t *status, hipStream_t st, int first_user,
+                                  int users)
 {
-    if (U <= 0) return hipSuccess;
+    if (U <= 0 || users <= 0) return hipSuccess;
     Co3LaunchTimer tm(CO3_K_BUILD, st);
-    hipLaunchKernelGGL(k_user_finish, dim3(U), dim3(HB_BLOCK), 0, st, g, err, sym, n, n_full, stride, anchor, gamma, fmt,
-                       sym_nib, counts_rep, nrep, counts, reinterpret_cast<char *>(codes), status);
+    hipLaunchKernelGGL(k_user_finish, dim3(users), dim3(HB_BLOCK), 0, st, g, err, sym, n, n_full, stride, anchor, gamma, fmt,
+                       sym_nib, counts_rep, nrep, counts, reinterpret_cast<char *>(codes), status, first_user, U);
     return hipGetLastError();
 }
 

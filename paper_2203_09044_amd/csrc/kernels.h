@@ -40,10 +40,12 @@ hipError_t co3_launch_histogram(const uint8_t *sym, int64_t n, int U, int64_t st
 hipError_t co3_launch_build_code(const uint32_t *weights, int U, int K, void *codes, int32_t *status, hipStream_t st,
                                  int nrep = 1, uint32_t *sums_out = nullptr);
 // After a resident-grid conversion that left the ragged end [n_full, n) of every user unconverted: that end,
-// the user's counts (its own + the nrep partial tables [nrep][U][K]) and the user's code
+// the user's counts (its own + the nrep partial tables [nrep][U][K]) and the user's code; all pointers at user 0
+// of the batch of U, the launch serving users first_user .. first_user + users - 1
 hipError_t co3_launch_user_finish(const float *g, float *err, uint8_t *sym, int64_t n, int64_t n_full, int64_t stride, int U,
                                   const int32_t *anchor, float gamma, co3_fmt fmt, int sym_nib, const uint32_t *counts_rep,
-                                  int nrep, uint32_t *counts, void *codes, int32_t *status, hipStream_t st);
+                                  int nrep, uint32_t *counts, void *codes, int32_t *status, hipStream_t st, int first_user,
+                                  int users);
 // elements of a user that the resident grid converts itself (a whole number of wavefront parts)
 int64_t co3_coop_full_elements(int64_t n, int kpt);
 #define CO3_COOP_COUNT_REPS 32   // partial count tables of the resident-grid user side (workgroup w adds to table w mod 32)

@@ -146,6 +146,26 @@ def test_ten_chained_iterations_at_a_size_that_fills_the_device(co3):
     run_one_call(co3, 2, 256 * 2048 * 12 + 1, co3.Fmt(4, 3), 256, betas=[0.8], T=2)
 
 
+def test_the_two_halves_of_the_aggregate(co3):
+    """co3_ps_decode_users for groups of users followed by co3_ps_average = co3_ps_aggregate, bit for bit."""
+    B = co3.binding
+    fmt = co3.Fmt(3, 1)
+    U, n, C = 7, 200_003, 256
+    pipe = run_one_call(co3, U, n, fmt, C, betas=[0.6, 1.0, 1.5], T=1)
+    want = pipe.avg.clone()
+    for cuts in ([0, 3, 7], [0, 1, 2, 7], [0, 7]):
+        ws = torch.zeros((B.ps_aggregate_workspace_bytes(n, U, C),), dtype=torch.uint8, device="cuda")
+        for a, b in reversed(list(zip(cuts[:-1], cuts[1:]))):         # any order of the groups
+            B.ps_decode_users(pipe.words[a:b], pipe.chunk_bitoff[a:b], C, pipe.codes[a:b], fmt, n, b - a, a, U, ws, pipe.status)
+        out = torch.full_like(pipe.avg, float("nan"))
+        B.ps_average(ws, C, fmt, n, U, pipe.anchor, out)
+        assert pipe.poll() == 0
+        assert torch.equal(out[:n].view(torch.int32), want[:n].view(torch.int32)), cuts
+    L = B._lib
+    assert L.co3_ps_decode_users(None, 2, None, 256, None, fmt.c(), 10, 1, 0, 1, None, 0, None, None) == B.EINVAL
+    assert L.co3_ps_average(None, 0, 256, fmt.c(), 10, 1, None, None, 1, None, None) == B.EINVAL
+
+
 def test_average_continued_over_groups_of_users(co3):
     """co3_ps_aggregate_partial: sums over groups of users chained through acc_in, one division at the end =
     co3_ps_aggregate over all users = the oracle's average, bit for bit; acc_in may be the output array; an
