@@ -5,7 +5,8 @@
 // uses: every workgroup owns the same contiguous 1/G of each user's vector, loads its part of g, takes
 // the largest magnitude, exchanges it with the other workgroups through one word per workgroup in
 // global memory, and converts from registers.  While user u is converted, each register that has been
-// consumed is refilled with user u+1's gradient, so the exchange for u+1 starts when u ends.
+// consumed is refilled with user u+1's gradient (the last few runs of u+1 have registers of their own and are
+// requested first), so the exchange for u+1 starts when u ends.
 //
 // The exchange uses no fences: a workgroup publishes one self-validating 32-bit word (valid bit |
 // magnitude bits) with a relaxed device-scope store, and one wavefront of every workgroup polls the G
@@ -24,13 +25,15 @@
 #ifndef CP_AHEAD
 #define CP_AHEAD 6                           // memory loads in flight per lane ahead of the conversion
 #endif
+#ifndef CP_SPARE
+#define CP_SPARE 4                           // runs of the next user's gradient that have registers of their own
+#endif
 #define CP_HIST_SLOTS 1024                   // LDS counters per wavefront
-// Registers: the kernel is compiled for this many wavefronts per SIMD (168 vector registers each) although a
-// workgroup brings only two.  With all 256 registers a wavefront could have, the resident grid would fill
-// every register file of the device, and kernels of other streams (the code build, compression and
-// decoding of another group of users) could not start before it ends.
+// Registers: a workgroup brings two wavefronts per SIMD, and the kernel is compiled for that (191 vector
+// registers with CP_SPARE 4).  While it runs, a kernel of another stream finds little room beside it; with 3 the
+// kernel keeps to 168 registers and needs CP_SPARE 1 to stay free of spills (5 us slower on 10 users x 11M).
 #ifndef CP_WAVES_PER_SIMD
-#define CP_WAVES_PER_SIMD 3
+#define CP_WAVES_PER_SIMD 2
 #endif
 #define CP_VALID 0x80000000u
 
@@ -135,8 +138,10 @@ struct CoopWave {
 };
 
 template <int KPT, bool NIB>
-__device__ __forceinline__ void coop_convert_user(const CoopWave &w, float4 (&gr)[KPT], float4 (&ev)[CP_AHEAD])
+__device__ __forceinline__ void coop_convert_user(const CoopWave &w, float4 (&gr)[KPT], float4 (&ev)[CP_AHEAD],
+                                                  float4 (&sp)[CP_SPARE])
 {
+    constexpr int S = KPT > CP_SPARE ? CP_SPARE : 0;     // the next user's last S runs were requested before this call
 #pragma unroll
     for (int k = 0; k < KPT; ++k) {
         float *ek = w.eu + k * CP_STEP;
@@ -161,7 +166,10 @@ __device__ __forceinline__ void coop_convert_user(const CoopWave &w, float4 (&gr
 #pragma unroll
         for (int c = 0; c < CP_VEC; ++c) atomicAdd(&w.myhist[q[c] * w.copies + w.mycopy], 1u);
         // the registers are free: the next user's gradient moves in
-        if (w.more) gr[k] = ld_stream_f4(w.gnext + k * CP_STEP + w.lane4);
+        if (k >= KPT - S)
+            gr[k] = sp[k - (KPT - S)];
+        else if (w.more)
+            gr[k] = ld_stream_f4(w.gnext + k * CP_STEP + w.lane4);
     }
 }
 
@@ -180,6 +188,37 @@ __device__ __forceinline__ uint32_t coop_ragged_max(const float *gu, int64_t lef
         m = absbits4(ld4_run(gu + k * CP_STEP, rem, lane4), m);
     }
     return m;
+}
+
+// The symbol counts of the user just converted.  Entry j of a wavefront's counters = symbol * copies + replica.
+// Every wavefront adds up its own counters: a lane takes consecutive entries (all of one symbol, or whole
+// symbols), lanes that share a symbol finish by exchange.  The wavefronts' sums are added up and go to one of
+// several partial tables (every workgroup adding to the same K words at the same moment serialises chip-wide,
+// and the loads behind the atomics wait).  Called by all threads of the workgroup; the counters are zero
+// afterwards.  (`wavecnt` is not written again before the barriers of the next exchange.)
+__device__ __forceinline__ void coop_flush_counts(uint32_t *hist, uint32_t *wavecnt, int wave, int lane, int K, int copies,
+                                                  uint32_t *__restrict__ counts_row)
+{
+    const int per = K * copies / CO3_WAVE;                 // entries per lane: a power of two, 2 .. 16
+    const int grp = per < copies ? per : copies;           // entries of one symbol that a lane holds together
+    uint32_t *h = hist + wave * CP_HIST_SLOTS;
+    for (int c0 = 0; c0 < per; c0 += grp) {
+        const int base = lane * per + c0;
+        uint32_t sum = 0;
+        for (int i = 0; i < grp; ++i) {
+            sum += h[base + i];
+            h[base + i] = 0u;
+        }
+        for (int o = 1; o * grp < copies; o <<= 1) sum += (uint32_t)__shfl_xor((int)sum, o, CO3_WAVE);
+        if (base % copies == 0) wavecnt[wave * 256 + base / copies] = sum;
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < K) {
+        uint32_t c = 0;
+#pragma unroll
+        for (int wv = 0; wv < CP_WAVES; ++wv) c += wavecnt[wv * 256 + threadIdx.x];
+        if (c) atomicAdd(&counts_row[threadIdx.x], c);
+    }
 }
 
 #ifdef CO3_COOP_TRACE
@@ -262,6 +301,17 @@ __global__ __launch_bounds__(CP_BLOCK) __attribute__((amdgpu_waves_per_eu(CP_WAV
         for (int k = 0; k < CP_AHEAD; ++k)
             ev[k] = full && k < KPT ? ld_stream_f4(w.eu + k * CP_STEP + lane4) : make_float4(0.f, 0.f, 0.f, 0.f);
 
+        // the next user's last runs have registers of their own and are requested now: when this user's
+        // conversion ends, all of the next user's gradient has been on its way for CP_SPARE runs' time
+        constexpr int S = KPT > CP_SPARE ? CP_SPARE : 0;
+        float4 sp[CP_SPARE];
+#pragma unroll
+        for (int i = 0; i < CP_SPARE; ++i)
+            sp[i] = (i < S && full && w.more) ? ld_stream_f4(w.gnext + (KPT - S + i) * CP_STEP + lane4) : make_float4(0.f, 0.f, 0.f, 0.f);
+
+        // the counts of the user before this one leave the workgroup while the exchange is on its way
+        if (u > 0) coop_flush_counts(hist, wavecnt, wave, lane, K, copies, counts + ((int64_t)(blockIdx.x % CO3_COOP_COUNT_REPS) * U + u - 1) * K);
+        CP_TRACE(5)
         const uint32_t mm = coop_collect_max(slots + (int64_t)u * G, G, spin_limit, red, status);
         int A = (int)(mm >> 23) - 127;
         A = A > 127 ? 127 : A;
@@ -271,7 +321,7 @@ __global__ __launch_bounds__(CP_BLOCK) __attribute__((amdgpu_waves_per_eu(CP_WAV
         w.e_min = A - F + 1;
         CP_TRACE(1)
 
-        if (full) coop_convert_user<KPT, NIB>(w, gr, ev);
+        if (full) coop_convert_user<KPT, NIB>(w, gr, ev, sp);
         CP_TRACE(2)
 
         if (w.more) {
@@ -289,37 +339,8 @@ __global__ __launch_bounds__(CP_BLOCK) __attribute__((amdgpu_waves_per_eu(CP_WAV
             coop_publish_max(m, slots + (int64_t)(u + 1) * G, red);
             CP_TRACE(4)
         }
-        {
-            // The counts of this user.  Entry j of a wavefront's counters = symbol * copies + replica.  Every
-            // wavefront adds up its own counters: a lane takes consecutive entries (all of one symbol, or whole
-            // symbols), lanes that share a symbol finish by exchange.  The wavefronts' sums are added up and go to
-            // one of several partial tables (every workgroup adding to the same K words at the same moment
-            // serialises chip-wide, and the loads behind the atomics wait).  (A wavefront's counters are its
-            // own, and the sums of the user before this one were read before the barriers of this user's exchange.)
-            const int per = K * copies / CO3_WAVE;                 // entries per lane: a power of two, 2 .. 16
-            const int grp = per < copies ? per : copies;           // entries of one symbol that a lane holds together
-            uint32_t *h = hist + wave * CP_HIST_SLOTS;
-            for (int c0 = 0; c0 < per; c0 += grp) {
-                const int base = lane * per + c0;
-                uint32_t sum = 0;
-                for (int i = 0; i < grp; ++i) {
-                    sum += h[base + i];
-                    h[base + i] = 0u;
-                }
-                for (int o = 1; o * grp < copies; o <<= 1) sum += (uint32_t)__shfl_xor((int)sum, o, CO3_WAVE);
-                if (base % copies == 0) wavecnt[wave * 256 + base / copies] = sum;
-            }
-            __syncthreads();
-            if ((int)threadIdx.x < K) {
-                uint32_t c = 0;
-#pragma unroll
-                for (int wv = 0; wv < CP_WAVES; ++wv) c += wavecnt[wv * 256 + threadIdx.x];
-                if (c) atomicAdd(&counts[((int64_t)(blockIdx.x % CO3_COOP_COUNT_REPS) * U + u) * K + threadIdx.x], c);
-            }
-            // (the next user's counters are not read before the next pair of barriers)
-        }
-        CP_TRACE(5)
     }
+    coop_flush_counts(hist, wavecnt, wave, lane, K, copies, counts + ((int64_t)(blockIdx.x % CO3_COOP_COUNT_REPS) * U + U - 1) * K);
 }
 
 // Runs per lane that the kernel is built for; a batch takes the smallest one that covers it.
