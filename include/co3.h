@@ -10,8 +10,11 @@
  *
  * Conventions for every call below, unless its comment says otherwise:
  *   - every pointer is a DEVICE pointer owned by the caller; the library never
- *     allocates or frees device memory and keeps no state between calls (the one
- *     exception, a fixed workspace inside the library, is co3_encode_static's);
+ *     allocates or frees device memory and keeps no state between calls.  The
+ *     exceptions, all process-wide: the fixed workspace of co3_encode_static, the
+ *     poll limit set by co3_set_exchange_spin_limit (an atomic word), and, only
+ *     while co3_timing_enable has switched it on, a pool of events for the
+ *     per-kernel timer (not thread-safe: a diagnostic for single-threaded use);
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream); the
  *     call only enqueues kernels on it and returns without waiting;
  *   - batched arrays are laid out [U][stride] with `stride` in elements (>= n, and
