@@ -14,6 +14,7 @@
 #define CO3_FUSED_SLOT_WORDS 1024 // 64-bit words of workspace per unit: room for 1024 codewords of any length
 #define CO3_FUSED_GROUP 64       // units per group of the offset scan (= lanes of a wavefront)
 #define CO3_COOP_KPT_MAX 22      // resident-grid user side: 16-byte pieces of a gradient that a lane keeps in registers
+#define CO3_COOP_KPT_BIG 48      // the same with part of the pieces in LDS
 
 // Per-user code blob.  Bytes 0..K-1 (len) are the public wire header; the rest is private.
 struct Co3Code {

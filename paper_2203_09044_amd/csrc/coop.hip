@@ -17,11 +17,14 @@
 #include "co3_dev.h"
 #include "kernels.h"
 
+#include <atomic>
+
 #define CP_BLOCK 512
 #define CP_WAVES (CP_BLOCK / CO3_WAVE)
 #define CP_VEC 4
 #define CP_STEP (CO3_WAVE * CP_VEC)          // elements that one load of a wavefront covers: one KiB
 #define CP_KPT_MAX CO3_COOP_KPT_MAX          // steps per lane: 16-byte pieces of g that a lane keeps in registers
+#define CP_KPT_REG_MAX 32                    // the most that the all-register form is built for
 #ifndef CP_AHEAD
 #define CP_AHEAD 6                           // memory loads in flight per lane ahead of the conversion
 #endif
@@ -137,6 +140,30 @@ struct CoopWave {
     int copies, mycopy;
 };
 
+// Run k of the wavefront (gradient gv, memory e4): conversion, new memory and symbols out, counts.
+template <bool NIB>
+__device__ __forceinline__ void coop_convert_run(const CoopWave &w, int k, const float4 gv, const float4 e4)
+{
+    const float ga[CP_VEC] = {gv.x, gv.y, gv.z, gv.w}, ea[CP_VEC] = {e4.x, e4.y, e4.z, e4.w};
+    float en[CP_VEC];
+    uint32_t q[CP_VEC];
+#pragma unroll
+    for (int c = 0; c < CP_VEC; ++c) {
+        const float x = ga[c] + w.gamma * ea[c];              // no contraction (build flag): one rounding per operation
+        float v;
+        co3_quantize(x, w.e_min, w.A, w.E, w.M, w.codemax, q[c], v);
+        en[c] = x - v;
+    }
+    st_stream_f4(w.eu + k * CP_STEP + w.lane4, make_float4(en[0], en[1], en[2], en[3]));
+    if (NIB)         // two symbols per byte, the earlier one in the low half
+        *reinterpret_cast<uint16_t *>(w.su + k * (CP_STEP / 2) + w.lane4 / 2) =
+            (uint16_t)(q[0] | (q[1] << 4) | (q[2] << 8) | (q[3] << 12));
+    else
+        *reinterpret_cast<uint32_t *>(w.su + k * CP_STEP + w.lane4) = q[0] | (q[1] << 8) | (q[2] << 16) | (q[3] << 24);
+#pragma unroll
+    for (int c = 0; c < CP_VEC; ++c) atomicAdd(&w.myhist[q[c] * w.copies + w.mycopy], 1u);
+}
+
 template <int KPT, bool NIB>
 __device__ __forceinline__ void coop_convert_user(const CoopWave &w, float4 (&gr)[KPT], float4 (&ev)[CP_AHEAD],
                                                   float4 (&sp)[CP_SPARE])
@@ -147,24 +174,7 @@ __device__ __forceinline__ void coop_convert_user(const CoopWave &w, float4 (&gr
         float *ek = w.eu + k * CP_STEP;
         const float4 gv = gr[k], e4 = ev[k % CP_AHEAD];
         if (k + CP_AHEAD < KPT) ev[k % CP_AHEAD] = ld_stream_f4(ek + CP_AHEAD * CP_STEP + w.lane4);
-        const float ga[CP_VEC] = {gv.x, gv.y, gv.z, gv.w}, ea[CP_VEC] = {e4.x, e4.y, e4.z, e4.w};
-        float en[CP_VEC];
-        uint32_t q[CP_VEC];
-#pragma unroll
-        for (int c = 0; c < CP_VEC; ++c) {
-            const float x = ga[c] + w.gamma * ea[c];              // no contraction (build flag): one rounding per operation
-            float v;
-            co3_quantize(x, w.e_min, w.A, w.E, w.M, w.codemax, q[c], v);
-            en[c] = x - v;
-        }
-        st_stream_f4(ek + w.lane4, make_float4(en[0], en[1], en[2], en[3]));
-        if (NIB)         // two symbols per byte, the earlier one in the low half
-            *reinterpret_cast<uint16_t *>(w.su + k * (CP_STEP / 2) + w.lane4 / 2) =
-                (uint16_t)(q[0] | (q[1] << 4) | (q[2] << 8) | (q[3] << 12));
-        else
-            *reinterpret_cast<uint32_t *>(w.su + k * CP_STEP + w.lane4) = q[0] | (q[1] << 8) | (q[2] << 16) | (q[3] << 24);
-#pragma unroll
-        for (int c = 0; c < CP_VEC; ++c) atomicAdd(&w.myhist[q[c] * w.copies + w.mycopy], 1u);
+        coop_convert_run<NIB>(w, k, gv, e4);
         // the registers are free: the next user's gradient moves in
         if (k >= KPT - S)
             gr[k] = sp[k - (KPT - S)];
@@ -343,8 +353,156 @@ __global__ __launch_bounds__(CP_BLOCK) __attribute__((amdgpu_waves_per_eu(CP_WAV
     coop_flush_counts(hist, wavecnt, wave, lane, K, copies, counts + ((int64_t)(blockIdx.x % CO3_COOP_COUNT_REPS) * U + U - 1) * K);
 }
 
+// ---- vectors beyond what the registers hold: part of a wavefront's runs in LDS ------------------------
+// The same kernel for up to CP_BIG_KPT runs per lane: the first CP_BIG_KL runs of a wavefront wait in LDS
+// (one KiB per run and wavefront), the other CP_BIG_KR in registers.  A user's conversion takes the LDS runs
+// first; the next user's gradient for an LDS run is requested into one of CP_BIG_D registers when the run has
+// been converted and moves to LDS that many runs later.
+#define CP_BIG_KR 34
+#define CP_BIG_KL 14                         // at most; the kernel is also built for CP_BIG_KL_SMALL
+#define CP_BIG_KL_SMALL 6
+#define CP_BIG_KPT (CP_BIG_KR + CP_BIG_KL)
+#define CP_BIG_KPT_SMALL (CP_BIG_KR + CP_BIG_KL_SMALL)
+#ifndef CP_BIG_AHEAD
+#define CP_BIG_AHEAD 4
+#endif
+#ifndef CP_BIG_D
+#define CP_BIG_D 4
+#endif
+#define CP_BIG_LDS_BYTES(KL) (CP_WAVES * (KL) * CP_STEP * 4)
+static_assert(CP_BIG_KR >= CP_BIG_D && CP_BIG_KL_SMALL >= CP_BIG_D, "the last LDS runs of the next user move in during the register runs");
+static_assert(CP_BIG_KPT == CO3_COOP_KPT_BIG, "runs per lane of the large form");
+
+// Returns the largest magnitude pattern of the next user's LDS runs (0 without a next user).
+template <int KL, bool NIB>
+__device__ __forceinline__ uint32_t coop_convert_user_big(const CoopWave &w, float4 (&gr)[CP_BIG_KR], float4 (&ev)[CP_BIG_AHEAD],
+                                                          float4 *lg, int lane)
+{
+    constexpr int KR = CP_BIG_KR, KPT = KR + KL, A = CP_BIG_AHEAD, D = CP_BIG_D;
+    float4 tmp[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d) tmp[d] = make_float4(0.f, 0.f, 0.f, 0.f);
+    uint32_t mnext = 0;
+    float4 gl = lg[lane];                       // LDS run 0
+#pragma unroll
+    for (int k = 0; k < KPT; ++k) {
+        const float4 e4 = ev[k % A];
+        if (k + A < KPT) ev[k % A] = ld_stream_f4(w.eu + (k + A) * CP_STEP + w.lane4);
+        float4 gv;
+        if (k < KL) {
+            gv = gl;
+            if (k + 1 < KL) gl = lg[(k + 1) * CO3_WAVE + lane];
+        } else
+            gv = gr[k - KL];
+        coop_convert_run<NIB>(w, k, gv, e4);
+        if (w.more) {
+            if (k >= D && k - D < KL) {         // the request of D runs ago has had its time: to LDS
+                mnext = absbits4(tmp[(k - D) % D], mnext);
+                lg[(k - D) * CO3_WAVE + lane] = tmp[(k - D) % D];
+            }
+            if (k < KL)
+                tmp[k % D] = ld_stream_f4(w.gnext + k * CP_STEP + w.lane4);
+            else
+                gr[k - KL] = ld_stream_f4(w.gnext + k * CP_STEP + w.lane4);
+        }
+    }
+    return mnext;
+}
+
+template <int KL, bool NIB>
+__global__ __launch_bounds__(CP_BLOCK) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_coop_convert_big(
+    const float *__restrict__ g, float *__restrict__ err, uint8_t *__restrict__ sym, int64_t n, int64_t stride, int U,
+    int32_t *__restrict__ anchor, float gamma, co3_fmt fmt, uint32_t *__restrict__ counts, uint32_t *__restrict__ slots,
+    uint32_t spin_limit, int32_t *status)
+{
+    constexpr int KR = CP_BIG_KR, KPT = KR + KL;
+    const FmtC fc(fmt);
+    const int F = fc.F, K = fc.K;
+    const int G = gridDim.x;
+    const int lane = threadIdx.x & (CO3_WAVE - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / CO3_WAVE);
+    __shared__ uint32_t red[CP_WAVES + 1];
+    __shared__ uint32_t hist[CP_WAVES * CP_HIST_SLOTS];
+    __shared__ uint32_t wavecnt[CP_WAVES * 256];
+    extern __shared__ __align__(16) unsigned char coop_big_lds[];
+    float4 *lg = reinterpret_cast<float4 *>(coop_big_lds) + (size_t)wave * KL * CO3_WAVE;   // the wavefront's LDS runs
+    const int copies = CP_HIST_SLOTS / K > 32 ? 32 : CP_HIST_SLOTS / K;
+    for (int j = threadIdx.x; j < CP_WAVES * CP_HIST_SLOTS; j += CP_BLOCK) hist[j] = 0u;
+
+    const int64_t first = (((int64_t)blockIdx.x * CP_WAVES + wave) * KPT) * CP_STEP;
+    const uint32_t lane4 = (uint32_t)lane * CP_VEC;
+    const bool full = first + (int64_t)KPT * CP_STEP <= n;
+
+    // user 0: the LDS runs pass through the registers of the register runs
+    float4 gr[KR];
+    {
+        uint32_t m = 0;
+        if (full) {
+#pragma unroll
+            for (int k = 0; k < KL; ++k) gr[k] = ld_stream_f4(g + first + k * CP_STEP + lane4);
+#pragma unroll
+            for (int k = 0; k < KL; ++k) {
+                m = absbits4(gr[k], m);
+                lg[k * CO3_WAVE + lane] = gr[k];
+            }
+#pragma unroll
+            for (int k = 0; k < KR; ++k) gr[k] = ld_stream_f4(g + first + (KL + k) * CP_STEP + lane4);
+#pragma unroll
+            for (int k = 0; k < KR; ++k) m = absbits4(gr[k], m);
+        } else {
+#pragma unroll
+            for (int k = 0; k < KR; ++k) gr[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+            m = coop_ragged_max(g + first, n - first, KPT, lane4);
+        }
+        coop_publish_max(m, slots, red);
+    }
+
+    CoopWave w;
+    w.left = n - first;
+    w.lane4 = lane4;
+    w.E = fc.E;
+    w.M = fc.M;
+    w.codemax = fc.codemax;
+    w.gamma = gamma;
+    w.myhist = hist + wave * CP_HIST_SLOTS;
+    w.copies = copies;
+    w.mycopy = lane & (copies - 1);
+    for (int u = 0; u < U; ++u) {
+        w.gnext = g + (int64_t)(u + 1) * stride + first;
+        w.eu = err + (int64_t)u * stride + first;
+        w.su = NIB ? sym + (int64_t)u * (stride / 2) + first / 2 : sym + (int64_t)u * stride + first;
+        w.more = u + 1 < U;
+
+        float4 ev[CP_BIG_AHEAD];
+#pragma unroll
+        for (int k = 0; k < CP_BIG_AHEAD; ++k)
+            ev[k] = full ? ld_stream_f4(w.eu + k * CP_STEP + lane4) : make_float4(0.f, 0.f, 0.f, 0.f);
+        if (u > 0) coop_flush_counts(hist, wavecnt, wave, lane, K, copies, counts + ((int64_t)(blockIdx.x % CO3_COOP_COUNT_REPS) * U + u - 1) * K);
+        const uint32_t mm = coop_collect_max(slots + (int64_t)u * G, G, spin_limit, red, status);
+        int A = (int)(mm >> 23) - 127;
+        A = A > 127 ? 127 : A;
+        A = A < F - 126 ? F - 126 : A;
+        if (blockIdx.x == 0 && threadIdx.x == 0) anchor[u] = A;
+        w.A = A;
+        w.e_min = A - F + 1;
+
+        uint32_t m = 0;
+        if (full) m = coop_convert_user_big<KL, NIB>(w, gr, ev, lg, lane);
+        if (w.more) {
+            if (full) {
+#pragma unroll
+                for (int k = 0; k < KR; ++k) m = absbits4(gr[k], m);
+            } else {
+                m = coop_ragged_max(w.gnext, w.left, KPT, lane4);
+            }
+            coop_publish_max(m, slots + (int64_t)(u + 1) * G, red);
+        }
+    }
+    coop_flush_counts(hist, wavecnt, wave, lane, K, copies, counts + ((int64_t)(blockIdx.x % CO3_COOP_COUNT_REPS) * U + U - 1) * K);
+}
+
 // Runs per lane that the kernel is built for; a batch takes the smallest one that covers it.
-static const int kCoopKpt[] = {1, 2, 4, 8, 12, 16, CP_KPT_MAX};
+static const int kCoopKpt[] = {1, 2, 4, 8, 12, 16, CP_KPT_MAX, CP_KPT_REG_MAX, CP_BIG_KPT_SMALL, CP_BIG_KPT};
 
 // Whether the resident-grid form serves this batch on a device with `cus` compute units; *kpt_out and
 // *grid_out then hold the launch shape.
@@ -353,8 +511,8 @@ bool co3_coop_fits(int64_t n, int cus, int *kpt_out, int *grid_out)
     if (cus < 1 || n < 1) return false;
     const int64_t per_wg_step = (int64_t)CP_WAVES * CP_STEP;                       // 2048 elements
     const int64_t need = (n + (int64_t)cus * per_wg_step - 1) / ((int64_t)cus * per_wg_step);
-    if (need > CP_KPT_MAX) return false;
-    int kpt = CP_KPT_MAX;
+    if (need > CP_BIG_KPT) return false;
+    int kpt = CP_BIG_KPT;
     for (int i = (int)(sizeof(kCoopKpt) / sizeof(kCoopKpt[0])) - 1; i >= 0; --i)
         if (kCoopKpt[i] >= need) kpt = kCoopKpt[i];
     const int64_t grid = (n + kpt * per_wg_step - 1) / (kpt * per_wg_step);         // <= cus
@@ -383,6 +541,31 @@ static void coop_launch_kpt(const float *g, float *err, uint8_t *sym, int64_t n,
                            gamma, fmt, counts, slots, spin_limit, status);
 }
 
+// The form with KL runs per wavefront in LDS (more than the 64 KiB a kernel gets without asking).
+template <int KL>
+static hipError_t coop_launch_big(const float *g, float *err, uint8_t *sym, int64_t n, int U, int64_t stride, int grid,
+                                  int32_t *anchor, float gamma, co3_fmt fmt, uint32_t *counts, uint32_t *slots,
+                                  uint32_t spin_limit, int32_t *status, int sym_nib, hipStream_t st)
+{
+    static std::atomic<int> lds_set{0};
+    if (!lds_set.load(std::memory_order_acquire)) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_coop_convert_big<KL, true>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, CP_BIG_LDS_BYTES(KL));
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_coop_convert_big<KL, false>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, CP_BIG_LDS_BYTES(KL));
+        if (e != hipSuccess) return e;
+        lds_set.store(1, std::memory_order_release);
+    }
+    if (sym_nib)
+        hipLaunchKernelGGL((k_coop_convert_big<KL, true>), dim3(grid), dim3(CP_BLOCK), CP_BIG_LDS_BYTES(KL), st, g, err, sym, n,
+                           stride, U, anchor, gamma, fmt, counts, slots, spin_limit, status);
+    else
+        hipLaunchKernelGGL((k_coop_convert_big<KL, false>), dim3(grid), dim3(CP_BLOCK), CP_BIG_LDS_BYTES(KL), st, g, err, sym, n,
+                           stride, U, anchor, gamma, fmt, counts, slots, spin_limit, status);
+    return hipGetLastError();
+}
+
 hipError_t co3_launch_coop_convert(const float *g, float *err, uint8_t *sym, int64_t n, int U, int64_t stride, int kpt,
                                    int grid, int32_t *anchor, float gamma, co3_fmt fmt, uint32_t *counts,
                                    uint32_t *slots, uint32_t spin_limit, int32_t *status, int sym_nib, hipStream_t st)
@@ -402,6 +585,17 @@ hipError_t co3_launch_coop_convert(const float *g, float *err, uint8_t *sym, int
         CO3_COOP_CASE(12);
         CO3_COOP_CASE(16);
         CO3_COOP_CASE(CP_KPT_MAX);
+        CO3_COOP_CASE(CP_KPT_REG_MAX);
+    case CP_BIG_KPT_SMALL:
+        if (coop_launch_big<CP_BIG_KL_SMALL>(g, err, sym, n, U, stride, grid, anchor, gamma, fmt, counts, slots, spin_limit,
+                                              status, sym_nib, st) != hipSuccess)
+            return hipGetLastError();
+        break;
+    case CP_BIG_KPT:
+        if (coop_launch_big<CP_BIG_KL>(g, err, sym, n, U, stride, grid, anchor, gamma, fmt, counts, slots, spin_limit, status,
+                                        sym_nib, st) != hipSuccess)
+            return hipGetLastError();
+        break;
     default: return hipErrorInvalidValue;
     }
 #undef CO3_COOP_CASE

@@ -141,6 +141,14 @@ def test_ragged_ends_of_the_resident_grid(co3, n):
     run_one_call(co3, 4, n, co3.Fmt(3, 0), 64, betas=[0.7, 1.2], T=2, seed=n + 1, keep_symbols=False)
 
 
+@pytest.mark.parametrize("n,E,M,keep", [(12_000_037, 3, 0, False), (16_777_216 + 333, 4, 3, True), (17_000_003, 2, 0, False),
+                                        (20_900_001, 3, 1, True), (24_000_005, 3, 0, False), (25_165_824, 4, 3, False)])
+def test_vectors_beyond_the_registers_of_the_device(co3, n, E, M, keep):
+    """On 256 compute units these sizes select the forms of the resident grid with 32 runs of 256 elements per
+    lane in registers, and with 34 in registers plus 6 or 14 in LDS (the last size fills that form exactly)."""
+    run_one_call(co3, 2, n, co3.Fmt(E, M), 256, betas=[0.8, 1.3], T=2, keep_symbols=keep)
+
+
 def test_ten_chained_iterations_at_a_size_that_fills_the_device(co3):
     run_one_call(co3, 6, 256 * 2048 * 8 + 999, co3.Fmt(3, 0), 256, betas=[0.5, 1.5, 1.0], T=10, keep_symbols=False)
     run_one_call(co3, 2, 256 * 2048 * 12 + 1, co3.Fmt(4, 3), 256, betas=[0.8], T=2)
