@@ -164,6 +164,32 @@ __device__ __forceinline__ void coop_convert_run(const CoopWave &w, int k, const
     for (int c = 0; c < CP_VEC; ++c) atomicAdd(&w.myhist[q[c] * w.copies + w.mycopy], 1u);
 }
 
+// The same with an anchor per element (a4: the four anchors of the lane's elements, a byte each).
+template <bool NIB>
+__device__ __forceinline__ void coop_convert_run_a4(const CoopWave &w, int k, const float4 gv, const float4 e4, uint32_t a4,
+                                                    int F)
+{
+    const float ga[CP_VEC] = {gv.x, gv.y, gv.z, gv.w}, ea[CP_VEC] = {e4.x, e4.y, e4.z, e4.w};
+    float en[CP_VEC];
+    uint32_t q[CP_VEC];
+#pragma unroll
+    for (int c = 0; c < CP_VEC; ++c) {
+        const int A = (int)(int8_t)(a4 >> (8 * c));
+        const float x = ga[c] + w.gamma * ea[c];
+        float v;
+        co3_quantize(x, A - F + 1, A, w.E, w.M, w.codemax, q[c], v);
+        en[c] = x - v;
+    }
+    st_stream_f4(w.eu + k * CP_STEP + w.lane4, make_float4(en[0], en[1], en[2], en[3]));
+    if (NIB)
+        *reinterpret_cast<uint16_t *>(w.su + k * (CP_STEP / 2) + w.lane4 / 2) =
+            (uint16_t)(q[0] | (q[1] << 4) | (q[2] << 8) | (q[3] << 12));
+    else
+        *reinterpret_cast<uint32_t *>(w.su + k * CP_STEP + w.lane4) = q[0] | (q[1] << 8) | (q[2] << 16) | (q[3] << 24);
+#pragma unroll
+    for (int c = 0; c < CP_VEC; ++c) atomicAdd(&w.myhist[q[c] * w.copies + w.mycopy], 1u);
+}
+
 template <int KPT, bool NIB>
 __device__ __forceinline__ void coop_convert_user(const CoopWave &w, float4 (&gr)[KPT], float4 (&ev)[CP_AHEAD],
                                                   float4 (&sp)[CP_SPARE])
@@ -353,6 +379,274 @@ __global__ __launch_bounds__(CP_BLOCK) __attribute__((amdgpu_waves_per_eu(CP_WAV
     coop_flush_counts(hist, wavecnt, wave, lane, K, copies, counts + ((int64_t)(blockIdx.x % CO3_COOP_COUNT_REPS) * U + U - 1) * K);
 }
 
+// ---- several tensors per user: one anchor per (user, tensor) ------------------------------------------
+// The same resident grid when a user's vector is a concatenation of tensors, each with its own anchor.  The
+// workgroups do not exchange one maximum but add their tensors' maxima into a table [U][nseg] in global memory
+// (device-scope atomic max, the returned values awaited), then publish a word that only says "done"; a
+// workgroup that has seen every word reads the maxima of the tensors it holds.  A run of 256 elements that
+// lies in one tensor is converted from registers with that tensor's anchor; the few runs that hold a tensor
+// boundary are converted after the others, element by element, from memory.
+__device__ __forceinline__ void wave_lds_sync_coop() { co3_wave_lds_sync(); }
+
+#define CP_SEGS_STASH 3                      // runs with a tensor boundary per wavefront that wait in LDS (more: read again)
+#define CP_SEGS_LDS_BYTES(KPT) (CP_WAVES * CP_SEGS_STASH * CP_STEP * 4 + CP_WAVES * (KPT) * CO3_WAVE * 4)
+
+__device__ __forceinline__ void coop_max_agent(uint32_t *p, uint32_t v)
+{
+    (void)__hip_atomic_fetch_max(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ int coop_anchor_of(uint32_t maxbits, int F)
+{
+    int A = (int)(maxbits >> 23) - 127;
+    A = A > 127 ? 127 : A;
+    return A < F - 126 ? F - 126 : A;
+}
+
+// Tensor of element e, searched upwards from tensor s (which starts at or before e).
+__device__ __forceinline__ int coop_seg_from(const int64_t *seg_off, int nseg, int s, int64_t e)
+{
+    while (s + 1 < nseg && seg_off[s + 1] <= e) ++s;
+    return s;
+}
+
+// Maxima found by a wavefront wait in its lanes (entry i in lane i) and go out together, one atomic each: an
+// atomic that is waited for costs a trip to memory, and the waits the compiler puts at the end of a loop body
+// would line these trips up one after the other.
+struct CoopPending {
+    int count;          // uniform
+    int seg;            // lane i: tensor of entry i
+    uint32_t max;
+};
+__device__ __forceinline__ void coop_pending_flush(CoopPending &p, uint32_t *tmax_u)
+{
+    if ((int)(threadIdx.x & (CO3_WAVE - 1)) < p.count && p.max) coop_max_agent(tmax_u + p.seg, p.max);
+    p.count = 0;
+}
+__device__ __forceinline__ void coop_pending_add(CoopPending &p, int seg, uint32_t m, uint32_t *tmax_u)
+{
+    if ((int)(threadIdx.x & (CO3_WAVE - 1)) == p.count) {
+        p.seg = seg;
+        p.max = m;
+    }
+    if (++p.count == CO3_WAVE) coop_pending_flush(p, tmax_u);
+}
+
+// Maxima of a run of 256 elements that holds tensor boundaries: tensor by tensor (a uniform loop over the
+// tensors that the run touches), the wavefront's maximum over the tensor's elements as one entry.  v: the
+// lane's four elements from element e_run + 4 * lane on; s_first: the tensor of element e_run.
+__device__ __forceinline__ void coop_segmax_run(const float4 v, int64_t e_run, uint32_t lane4, int64_t n, const int64_t *seg_off,
+                                                int nseg, int s_first, uint32_t *tmax_u, CoopPending &pend)
+{
+    const uint32_t bits[4] = {__float_as_uint(v.x) & 0x7fffffffu, __float_as_uint(v.y) & 0x7fffffffu,
+                              __float_as_uint(v.z) & 0x7fffffffu, __float_as_uint(v.w) & 0x7fffffffu};
+    const int64_t end = e_run + CP_STEP < n ? e_run + CP_STEP : n;      // uniform
+    const int64_t e = e_run + lane4;
+    for (int sg = s_first; sg < nseg; ++sg) {                               // uniform
+        const int64_t a = seg_off[sg], b = seg_off[sg + 1];
+        if (a >= end) break;
+        uint32_t m = 0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            if (e + c >= a && e + c < b && e + c < end) m = m > bits[c] ? m : bits[c];
+        m = wave_max_u32(m);
+        coop_pending_add(pend, sg, m, tmax_u);
+    }
+}
+
+template <int KPT, bool NIB>
+__global__ __launch_bounds__(CP_BLOCK) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_coop_convert_segs(
+    const float *__restrict__ g, float *__restrict__ err, uint8_t *__restrict__ sym, int64_t n, int64_t stride, int U,
+    const int64_t *__restrict__ seg_off_g, int nseg, int32_t *__restrict__ anchor, float gamma, co3_fmt fmt,
+    uint32_t *__restrict__ counts, uint32_t *__restrict__ slots, uint32_t *__restrict__ tmax, uint32_t spin_limit,
+    int32_t *status)
+{
+    const FmtC fc(fmt);
+    const int F = fc.F, K = fc.K;
+    const int G = gridDim.x;
+    const int lane = threadIdx.x & (CO3_WAVE - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / CO3_WAVE);
+    __shared__ uint32_t red[CP_WAVES + 1];
+    __shared__ uint32_t hist[CP_WAVES * CP_HIST_SLOTS];
+    __shared__ uint32_t wavecnt[CP_WAVES * 256];
+    __shared__ int64_t seg_cache[CO3_SEG_CACHE];
+    const int copies = CP_HIST_SLOTS / K > 32 ? 32 : CP_HIST_SLOTS / K;
+    for (int j = threadIdx.x; j < CP_WAVES * CP_HIST_SLOTS; j += CP_BLOCK) hist[j] = 0u;
+    const int64_t *seg_off = co3_cache_segs(seg_off_g, nseg, seg_cache);     // (the launch keeps nseg + 1 within the cache)
+
+    const int64_t first = (((int64_t)blockIdx.x * CP_WAVES + wave) * KPT) * CP_STEP;
+    const uint32_t lane4 = (uint32_t)lane * CP_VEC;
+    const bool full = first + (int64_t)KPT * CP_STEP <= n;
+
+    // Tensor of every run's first element (lane k looks run k up; kept in LDS, read where a run needs it), and
+    // as bit masks over the runs: which hold a tensor boundary, which start in another tensor than the run
+    // before, after which the maximum gathered so far belongs to a tensor that ends.  The same for every user.
+    static_assert(KPT <= 32, "a lane per run, masks of 64 bits");
+    __shared__ int segs_s[CP_WAVES][32];
+    __shared__ int8_t anchor_s[CO3_SEG_CACHE];             // the current user's anchor of every tensor
+    __shared__ uint8_t runa_s[CP_WAVES][32];                // ... of the tensor of every run's first element
+    // runs with a tensor boundary wait here (gradient, memory) between the pass over all runs and their own loop
+    extern __shared__ __align__(16) unsigned char coop_segs_lds[];
+    float4 *stash_g = reinterpret_cast<float4 *>(coop_segs_lds);
+    // the anchors of the current user for every (run, lane): four bytes, one per element
+    uint32_t *a4_s = reinterpret_cast<uint32_t *>(stash_g + CP_WAVES * CP_SEGS_STASH * CO3_WAVE) + (size_t)wave * KPT * CO3_WAVE;
+    uint64_t strad, newm, flushm;
+    {
+        const int64_t e0 = first + (int64_t)lane * CP_STEP;
+        const bool have = lane < KPT && e0 < n;
+        const int sk = have ? co3_find_seg(seg_off, nseg, e0) : nseg - 1;
+        const int64_t last = e0 + CP_STEP - 1 < n ? e0 + CP_STEP - 1 : n - 1;
+        const bool st = have && co3_find_seg(seg_off, nseg, last) != sk;
+        if (lane < 32) segs_s[wave][lane] = sk;
+        const int prev = __shfl_up(sk, 1, CO3_WAVE);
+        strad = __ballot(st);
+        newm = __ballot(lane < KPT && (lane == 0 || prev != sk));
+        flushm = ((strad | newm) >> 1) | (1ull << (KPT - 1));
+        wave_lds_sync_coop();
+    }
+
+    // maxima of the user whose gradient the registers hold -> tmax[uu]; returns what must be awaited
+    float4 gr[KPT];
+    auto seg_maxima = [&](int uu, const float *gu) {
+        uint32_t *tm = tmax + (int64_t)uu * nseg;
+        CoopPending pend = {0, 0, 0u};
+        if (full) {
+            uint32_t acc = 0;
+            int held = 0;                                // uniform: runs with a tensor boundary met so far
+#pragma unroll
+            for (int k = 0; k < KPT; ++k) {
+                if ((strad >> k) & 1ull) {               // uniform: set aside for the loop below
+                    if (held < CP_SEGS_STASH) stash_g[(wave * CP_SEGS_STASH + held) * CO3_WAVE + lane] = gr[k];
+                    ++held;
+                } else {
+                    acc = absbits4(gr[k], acc);
+                    if ((flushm >> k) & 1ull) {          // uniform: a tensor's last whole run here
+                        coop_pending_add(pend, segs_s[wave][k], wave_max_u32(acc), tm);
+                        acc = 0;
+                    }
+                }
+            }
+            if (strad) {                                 // uniform: the runs with a tensor boundary, element by element
+                int i = 0;
+#pragma unroll 1
+                for (int k = 0; k < KPT; ++k) {
+                    if (!((strad >> k) & 1ull)) continue;
+                    const int64_t e0 = first + (int64_t)k * CP_STEP;
+                    const float4 v = i < CP_SEGS_STASH ? stash_g[(wave * CP_SEGS_STASH + i) * CO3_WAVE + lane]
+                                                       : ld_stream_f4(gu + e0 + lane4);
+                    coop_segmax_run(v, e0, lane4, n, seg_off, nseg, segs_s[wave][k], tm, pend);
+                    ++i;
+                }
+            }
+        } else {                                         // the ragged end, or nothing
+#pragma unroll 1
+            for (int k = 0; k < KPT; ++k) {
+                const int64_t e0 = first + (int64_t)k * CP_STEP;
+                if (e0 >= n) break;
+                const float4 v = ld4_run(gu + e0, n - e0, lane4);
+                coop_segmax_run(v, e0, lane4, n, seg_off, nseg, co3_find_seg(seg_off, nseg, e0), tm, pend);
+            }
+        }
+        coop_pending_flush(pend, tm);
+    };
+    // "done" of this workgroup for a user: after every wavefront's atomics have returned
+    auto publish_done = [&](uint32_t *row) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // this wavefront's atomics have been performed
+        __syncthreads();
+        if (threadIdx.x == 0) st_relaxed_agent(row + blockIdx.x, CP_VALID);
+    };
+
+    {
+        if (full) {
+#pragma unroll
+            for (int k = 0; k < KPT; ++k) gr[k] = ld_stream_f4(g + first + k * CP_STEP + lane4);
+        } else {
+#pragma unroll
+            for (int k = 0; k < KPT; ++k) gr[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        seg_maxima(0, g);
+        publish_done(slots);
+    }
+
+    CoopWave w;
+    w.left = n - first;
+    w.lane4 = lane4;
+    w.E = fc.E;
+    w.M = fc.M;
+    w.codemax = fc.codemax;
+    w.gamma = gamma;
+    w.myhist = hist + wave * CP_HIST_SLOTS;
+    w.copies = copies;
+    w.mycopy = lane & (copies - 1);
+    for (int u = 0; u < U; ++u) {
+        w.gnext = g + (int64_t)(u + 1) * stride + first;
+        w.eu = err + (int64_t)u * stride + first;
+        w.su = NIB ? sym + (int64_t)u * (stride / 2) + first / 2 : sym + (int64_t)u * stride + first;
+        w.more = u + 1 < U;
+        const uint32_t *tm = tmax + (int64_t)u * nseg;
+
+        float4 ev[CP_AHEAD];
+        CP_TRACE(0)
+#pragma unroll
+        for (int k = 0; k < CP_AHEAD; ++k)
+            ev[k] = full && k < KPT ? ld_stream_f4(w.eu + k * CP_STEP + lane4) : make_float4(0.f, 0.f, 0.f, 0.f);
+        if (u > 0) coop_flush_counts(hist, wavecnt, wave, lane, K, copies, counts + ((int64_t)(blockIdx.x % CO3_COOP_COUNT_REPS) * U + u - 1) * K);
+        (void)coop_collect_max(slots + (int64_t)u * G, G, spin_limit, red, status);    // every workgroup's maxima are in
+        CP_TRACE(1)
+
+        // anchors: of the tensors of this wavefront's runs, and (workgroup 0) of all tensors for the caller
+        for (int s = threadIdx.x; s < nseg; s += CP_BLOCK) {       // (nseg is within the cache: at most one round)
+            const int A = coop_anchor_of(ld_relaxed_agent(tm + s), F);
+            anchor_s[s] = (int8_t)A;
+            if (blockIdx.x == 0) anchor[(int64_t)u * nseg + s] = A;
+        }
+        __syncthreads();                                 // (read until this user's conversion ends; the next write
+                                                         // comes after the barriers of the next exchange)
+        CP_TRACE(2)
+
+        if (full) {
+            // anchors: a run inside one tensor takes that tensor's anchor for all its elements, a run with a tensor
+            // boundary an anchor per element (per lane in LDS); the conversion below is then the same for all
+            if (lane < KPT) runa_s[wave][lane] = (uint8_t)anchor_s[segs_s[wave][lane]];      // lane k: run k
+            wave_lds_sync_coop();
+            if (strad) {                                 // uniform
+#pragma unroll 1
+                for (int k = 0; k < KPT; ++k) {
+                    if (!((strad >> k) & 1ull)) continue;
+                    const int64_t e0 = first + (int64_t)k * CP_STEP + lane4;
+                    int sg = segs_s[wave][k];
+                    uint32_t a4 = 0;
+#pragma unroll
+                    for (int c = 0; c < CP_VEC; ++c) {
+                        sg = coop_seg_from(seg_off, nseg, sg, e0 + c);
+                        a4 |= (uint32_t)(uint8_t)anchor_s[sg] << (8 * c);
+                    }
+                    a4_s[k * CO3_WAVE + lane] = a4;
+                }
+            }
+            wave_lds_sync_coop();
+            CP_TRACE(3)
+#pragma unroll
+            for (int k = 0; k < KPT; ++k) {
+                const float4 gv = gr[k], e4 = ev[k % CP_AHEAD];
+                if (k + CP_AHEAD < KPT) ev[k % CP_AHEAD] = ld_stream_f4(w.eu + (k + CP_AHEAD) * CP_STEP + lane4);
+                // (both are read; which one counts is the same for the whole wavefront)
+                const uint32_t a4 = (strad >> k) & 1ull ? a4_s[k * CO3_WAVE + lane] : (uint32_t)runa_s[wave][k] * 0x01010101u;
+                coop_convert_run_a4<NIB>(w, k, gv, e4, a4, F);
+                if (w.more) gr[k] = ld_stream_f4(w.gnext + k * CP_STEP + lane4);
+            }
+        }
+        CP_TRACE(4)
+        if (w.more) {
+            seg_maxima(u + 1, g + (int64_t)(u + 1) * stride);
+            CP_TRACE(5)
+            publish_done(slots + (int64_t)(u + 1) * G);
+            CP_TRACE(6)
+        }
+    }
+    coop_flush_counts(hist, wavecnt, wave, lane, K, copies, counts + ((int64_t)(blockIdx.x % CO3_COOP_COUNT_REPS) * U + U - 1) * K);
+}
+
 // ---- vectors beyond what the registers hold: part of a wavefront's runs in LDS ------------------------
 // The same kernel for up to CP_BIG_KPT runs per lane: the first CP_BIG_KL runs of a wavefront wait in LDS
 // (one KiB per run and wavefront), the other CP_BIG_KR in registers.  A user's conversion takes the LDS runs
@@ -506,8 +800,23 @@ static const int kCoopKpt[] = {1, 2, 4, 8, 12, 16, CP_KPT_MAX, CP_KPT_REG_MAX, C
 
 // Whether the resident-grid form serves this batch on a device with `cus` compute units; *kpt_out and
 // *grid_out then hold the launch shape.
-bool co3_coop_fits(int64_t n, int cus, int *kpt_out, int *grid_out)
+// (the form for several tensors per user is built for fewer sizes)
+static const int kCoopKptSegs[] = {1, 4, 12, CP_KPT_MAX, CP_KPT_REG_MAX};
+
+bool co3_coop_fits(int64_t n, int nseg, int cus, int *kpt_out, int *grid_out)
 {
+    if (nseg > 1) {
+        if (cus < 1 || n < 1 || nseg + 1 > CO3_SEG_CACHE) return false;
+        const int64_t step = (int64_t)CP_WAVES * CP_STEP;
+        const int64_t need = (n + (int64_t)cus * step - 1) / ((int64_t)cus * step);
+        if (need > CP_KPT_REG_MAX) return false;
+        int kpt = CP_KPT_REG_MAX;
+        for (int i = (int)(sizeof(kCoopKptSegs) / sizeof(kCoopKptSegs[0])) - 1; i >= 0; --i)
+            if (kCoopKptSegs[i] >= need) kpt = kCoopKptSegs[i];
+        *kpt_out = kpt;
+        *grid_out = (int)((n + kpt * step - 1) / (kpt * step));
+        return true;
+    }
     if (cus < 1 || n < 1) return false;
     const int64_t per_wg_step = (int64_t)CP_WAVES * CP_STEP;                       // 2048 elements
     const int64_t need = (n + (int64_t)cus * per_wg_step - 1) / ((int64_t)cus * per_wg_step);
@@ -566,10 +875,53 @@ static hipError_t coop_launch_big(const float *g, float *err, uint8_t *sym, int6
     return hipGetLastError();
 }
 
-hipError_t co3_launch_coop_convert(const float *g, float *err, uint8_t *sym, int64_t n, int U, int64_t stride, int kpt,
-                                   int grid, int32_t *anchor, float gamma, co3_fmt fmt, uint32_t *counts,
-                                   uint32_t *slots, uint32_t spin_limit, int32_t *status, int sym_nib, hipStream_t st)
+template <int KPT>
+static void coop_launch_segs(const float *g, float *err, uint8_t *sym, int64_t n, int U, int64_t stride, int grid,
+                             const int64_t *seg_off, int nseg, int32_t *anchor, float gamma, co3_fmt fmt, uint32_t *counts,
+                             uint32_t *slots, uint32_t *tmax, uint32_t spin_limit, int32_t *status, int sym_nib, hipStream_t st)
 {
+    static std::atomic<int> lds_set{0};              // (more LDS than a kernel gets without asking)
+    if (!lds_set.load(std::memory_order_acquire)) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(k_coop_convert_segs<KPT, true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, CP_SEGS_LDS_BYTES(KPT)) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void *>(k_coop_convert_segs<KPT, false>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, CP_SEGS_LDS_BYTES(KPT)) != hipSuccess)
+            return;                                      // (the launch below then reports the error)
+        lds_set.store(1, std::memory_order_release);
+    }
+    if (sym_nib)
+        hipLaunchKernelGGL((k_coop_convert_segs<KPT, true>), dim3(grid), dim3(CP_BLOCK), CP_SEGS_LDS_BYTES(KPT), st, g, err, sym, n,
+                           stride, U, seg_off, nseg, anchor, gamma, fmt, counts, slots, tmax, spin_limit, status);
+    else
+        hipLaunchKernelGGL((k_coop_convert_segs<KPT, false>), dim3(grid), dim3(CP_BLOCK), CP_SEGS_LDS_BYTES(KPT), st, g, err, sym, n,
+                           stride, U, seg_off, nseg, anchor, gamma, fmt, counts, slots, tmax, spin_limit, status);
+}
+
+// `tmax`: U * nseg zero words (nseg > 1 only).  seg_off == nullptr or nseg == 1: one anchor per user.
+hipError_t co3_launch_coop_convert(const float *g, float *err, uint8_t *sym, int64_t n, int U, int64_t stride, int kpt,
+                                   int grid, const int64_t *seg_off, int nseg, int32_t *anchor, float gamma, co3_fmt fmt,
+                                   uint32_t *counts, uint32_t *slots, uint32_t *tmax, uint32_t spin_limit, int32_t *status,
+                                   int sym_nib, hipStream_t st)
+{
+    if (seg_off && nseg > 1) {
+        if (!tmax || nseg + 1 > CO3_SEG_CACHE) return hipErrorInvalidValue;
+        Co3LaunchTimer tm(CO3_K_COOP, st);
+#define CO3_COOP_SEGS_CASE(KPT)                                                                                    \
+    case KPT:                                                                                                      \
+        coop_launch_segs<KPT>(g, err, sym, n, U, stride, grid, seg_off, nseg, anchor, gamma, fmt, counts, slots, tmax,   \
+                              spin_limit, status, sym_nib, st);                                                    \
+        break
+        switch (kpt) {
+            CO3_COOP_SEGS_CASE(1);
+            CO3_COOP_SEGS_CASE(4);
+            CO3_COOP_SEGS_CASE(12);
+            CO3_COOP_SEGS_CASE(CP_KPT_MAX);
+            CO3_COOP_SEGS_CASE(CP_KPT_REG_MAX);
+        default: return hipErrorInvalidValue;
+        }
+#undef CO3_COOP_SEGS_CASE
+        return hipGetLastError();
+    }
     {
     Co3LaunchTimer tm(CO3_K_COOP, st);
 #define CO3_COOP_CASE(KPT)                                                                                         \

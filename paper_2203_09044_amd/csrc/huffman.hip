@@ -39,7 +39,8 @@ __global__ __launch_bounds__(HB_BLOCK) void k_build_code(const uint32_t *__restr
 // symbols, adds the grid's partial count tables to them and builds the user's code.
 __global__ __launch_bounds__(HB_BLOCK) void k_user_finish(const float *__restrict__ g, float *__restrict__ err,
                                                            uint8_t *__restrict__ sym, int64_t n, int64_t n_full,
-                                                           int64_t stride, const int32_t *__restrict__ anchor, float gamma,
+                                                           int64_t stride, const int64_t *__restrict__ seg_off, int nseg,
+                                                           const int32_t *__restrict__ anchor, float gamma,
                                                            co3_fmt fmt, int sym_nib, const uint32_t *__restrict__ counts_rep,
                                                            int nrep, uint32_t *__restrict__ counts, char *codes,
                                                            int32_t *status, int first_user, int U)
@@ -63,8 +64,7 @@ __global__ __launch_bounds__(HB_BLOCK) void k_user_finish(const float *__restric
         }
     }
     __syncthreads();
-    const int A = anchor[u];
-    const int e_min = A - fc.F + 1;
+    // one anchor per (user, tensor): anchor is [U][nseg]
     const float *gu = g + (int64_t)u * stride;
     float *eu = err + (int64_t)u * stride;
     uint8_t *su = sym + (int64_t)u * (sym_nib ? stride / 2 : stride);
@@ -75,8 +75,9 @@ __global__ __launch_bounds__(HB_BLOCK) void k_user_finish(const float *__restric
         const int cnt = n - i < 4 ? (int)(n - i) : 4;
         for (int c = 0; c < cnt; ++c) {
             const float x = gu[i + c] + gamma * eu[i + c];          // no contraction (build flag): one rounding per operation
+            const int A = anchor[(int64_t)u * nseg + co3_find_seg(seg_off, nseg, i + c)];
             float v;
-            co3_quantize(x, e_min, A, fc.E, fc.M, fc.codemax, q[c], v);
+            co3_quantize(x, A - fc.F + 1, A, fc.E, fc.M, fc.codemax, q[c], v);
             eu[i + c] = x - v;
             atomicAdd(&hist[q[c]], 1u);
         }
@@ -98,13 +99,13 @@ __global__ __launch_bounds__(HB_BLOCK) void k_user_finish(const float *__restric
 }
 
 hipError_t co3_launch_user_finish(const float *g, float *err, uint8_t *sym, int64_t n, int64_t n_full, int64_t stride, int U,
-                                  const int32_t *anchor, float gamma, co3_fmt fmt, int sym_nib, const uint32_t *counts_rep,
-                                  int nrep, uint32_t *counts, void *codes, int32_t *status, hipStream_t st, int first_user,
-                                  int users)
+                                  const int64_t *seg_off, int nseg, const int32_t *anchor, float gamma, co3_fmt fmt,
+                                  int sym_nib, const uint32_t *counts_rep, int nrep, uint32_t *counts, void *codes,
+                                  int32_t *status, hipStream_t st, int first_user, int users)
 {
     if (U <= 0 || users <= 0) return hipSuccess;
     Co3LaunchTimer tm(CO3_K_BUILD, st);
-    hipLaunchKernelGGL(k_user_finish, dim3(users), dim3(HB_BLOCK), 0, st, g, err, sym, n, n_full, stride, anchor, gamma, fmt,
+    hipLaunchKernelGGL(k_user_finish, dim3(users), dim3(HB_BLOCK), 0, st, g, err, sym, n, n_full, stride, seg_off, nseg, anchor, gamma, fmt,
                        sym_nib, counts_rep, nrep, counts, reinterpret_cast<char *>(codes), status, first_user, U);
     return hipGetLastError();
 }

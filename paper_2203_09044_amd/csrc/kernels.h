@@ -30,10 +30,12 @@ hipError_t co3_launch_convert(const float *g, float *err, uint8_t *sym, int64_t 
 // earlier one in the low half, rows of stride / 2 bytes -- the form the encoder reads with its own sym_nib
 // resident-grid conversion (anchor from max|g| and conversion with one read of g; one anchor per user);
 // slots: [U][grid] u32 exchange words, counts_rep: [CO3_COOP_COUNT_REPS][U][K] partial counts, both zero at launch
-bool co3_coop_fits(int64_t n, int cus, int *kpt_out, int *grid_out);
+// nseg > 1 (seg_off given): one anchor per (user, tensor), anchor [U][nseg], tmax: U * nseg zero words
+bool co3_coop_fits(int64_t n, int nseg, int cus, int *kpt_out, int *grid_out);
 hipError_t co3_launch_coop_convert(const float *g, float *err, uint8_t *sym, int64_t n, int U, int64_t stride, int kpt,
-                                   int grid, int32_t *anchor, float gamma, co3_fmt fmt, uint32_t *counts_rep,
-                                   uint32_t *slots, uint32_t spin_limit, int32_t *status, int sym_nib, hipStream_t st);
+                                   int grid, const int64_t *seg_off, int nseg, int32_t *anchor, float gamma, co3_fmt fmt,
+                                   uint32_t *counts_rep, uint32_t *slots, uint32_t *tmax, uint32_t spin_limit,
+                                   int32_t *status, int sym_nib, hipStream_t st);
 hipError_t co3_launch_histogram(const uint8_t *sym, int64_t n, int U, int64_t stride, int K, uint32_t *counts,
                                 hipStream_t st);
 // nrep > 1: weights is [nrep][U][K] partial tables that the kernel adds up (the sums also go to sums_out [U][K])
@@ -43,9 +45,9 @@ hipError_t co3_launch_build_code(const uint32_t *weights, int U, int K, void *co
 // the user's counts (its own + the nrep partial tables [nrep][U][K]) and the user's code; all pointers at user 0
 // of the batch of U, the launch serving users first_user .. first_user + users - 1
 hipError_t co3_launch_user_finish(const float *g, float *err, uint8_t *sym, int64_t n, int64_t n_full, int64_t stride, int U,
-                                  const int32_t *anchor, float gamma, co3_fmt fmt, int sym_nib, const uint32_t *counts_rep,
-                                  int nrep, uint32_t *counts, void *codes, int32_t *status, hipStream_t st, int first_user,
-                                  int users);
+                                  const int64_t *seg_off, int nseg, const int32_t *anchor, float gamma, co3_fmt fmt,
+                                  int sym_nib, const uint32_t *counts_rep, int nrep, uint32_t *counts, void *codes,
+                                  int32_t *status, hipStream_t st, int first_user, int users);
 // elements of a user that the resident grid converts itself (a whole number of wavefront parts)
 int64_t co3_coop_full_elements(int64_t n, int kpt);
 #define CO3_COOP_COUNT_REPS 32   // partial count tables of the resident-grid user side (workgroup w adds to table w mod 32)

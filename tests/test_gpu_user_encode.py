@@ -98,10 +98,46 @@ def test_one_call_zero_gradients_and_subnormal_maxima(co3):
     run_one_call(co3, 2, 100_000, co3.Fmt(3, 1), 256, betas=[1.0], T=2, adversarial=zeros)
 
 
-def test_one_call_with_tensors_takes_the_separate_kernels(co3):
+def test_one_call_with_tensors(co3):
+    """Several tensors per user, one anchor each: up to three users the resident grid (maxima per tensor through
+    atomics, runs with a tensor boundary converted with an anchor per element), more users the separate kernels."""
     sizes = [10, 1, 4097, 64, 3, 20_000, 7, 128, 0, 5, 12_345]
     run_one_call(co3, 2, sum(sizes), co3.Fmt(4, 3), 256, betas=[0.8], T=2, sizes=sizes)
     run_one_call(co3, 2, sum(sizes), co3.Fmt(4, 3), 256, betas=[0.8], T=2, sizes=sizes, keep_symbols=False)
+    run_one_call(co3, 5, sum(sizes), co3.Fmt(4, 3), 256, betas=[0.8], T=2, sizes=sizes)
+
+
+def tensor_sizes(total, seed):
+    """Tensors of a network-like mix: a few large ones, runs of small ones (64 ... 512), single elements and empty ones."""
+    rng = inp.rng_for(97, seed)
+    sizes = []
+    while sum(sizes) < total:
+        kind = rng.integers(0, 10)
+        if kind < 3:
+            sizes.append(int(rng.integers(total // 40, total // 8)))
+        elif kind < 8:
+            sizes.extend([int(rng.choice([64, 128, 256, 512]))] * 2)
+        elif kind == 8:
+            sizes.extend([1, 0, int(rng.integers(2, 300))])
+        else:
+            sizes.append(int(rng.integers(1000, 50_000)))
+    sizes[-1] -= sum(sizes) - total
+    if sizes[-1] < 0:
+        sizes = sizes[:-1] + [0]
+        while sum(sizes) > total:
+            sizes.pop(0)
+        sizes.append(total - sum(sizes))
+    return sizes
+
+
+@pytest.mark.parametrize("total,U,E,M,keep", [(1_200_003, 3, 3, 1, True), (2_600_017, 2, 2, 0, False), (6_000_001, 1, 4, 3, False),
+                                              (14_000_021, 2, 3, 0, False)])
+def test_tensors_in_every_form_of_the_resident_grid(co3, total, U, E, M, keep):
+    """Sizes that select, on 256 compute units, 4, 12, 22 and 32 runs per lane of the form with one anchor per tensor;
+    tensor boundaries inside runs, runs that hold several small tensors, empty and one-element tensors."""
+    sizes = tensor_sizes(total, total % 97)
+    assert sum(sizes) == total and min(sizes) >= 0
+    run_one_call(co3, U, total, co3.Fmt(E, M), 256, betas=[0.7, 1.2, 1.0], T=2, sizes=sizes, keep_symbols=keep)
 
 
 def test_one_call_deterministic(co3):
