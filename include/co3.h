@@ -358,12 +358,13 @@ int32_t co3_convert_encode_layers(const float *g, float *err, int64_t n, int32_t
  * all users, with the anchor from max|g| and one empirical code per user: the results of
  *     co3_convert_ef(..., CO3_ANCHOR_FROM_ABSMAX_G, ..., counts) -> co3_build_code(counts) -> co3_encode
  * bit for bit -- err, anchor, counts, codes, words, chunk_bitoff, total_bits (and sym, if asked for).
- * What the one call adds is that it may keep data on the chip between the steps: where one anchor per
- * user is asked for (nseg = 1) and a user's gradient fits the register files of the device, for the
- * larger vectors with a part of it in LDS (n up to 98,304 elements per compute unit: 25.1 M on 256
- * units), a single resident grid reads every gradient once, taking the largest magnitude and converting
- * from the chip, the workgroups exchanging their maxima through one word each in the workspace; other
- * batches run the separate kernels of the three calls.
+ * What the one call adds is that it may keep data on the chip between the steps: where a user's
+ * gradient fits the register files of the device (with one anchor per user, nseg = 1, for the larger
+ * vectors with a part of it in LDS: n up to 98,304 elements per compute unit, 25.1 M on 256 units;
+ * with several tensors per user up to 65,536 elements per compute unit, 511 tensors and three users),
+ * a single resident grid reads every gradient once, taking the largest magnitudes and converting from
+ * the chip, the workgroups exchanging their maxima through words in the workspace; other batches run
+ * the separate kernels of the three calls.
  *
  *   arguments  as in co3_convert_ef (g, err, n, U, stride, seg_off, nseg, anchor [out], gamma, fmt,
  *              counts [out, required]), co3_build_code (codes [out]) and co3_encode (words, cap_words,
