@@ -850,22 +850,32 @@ static void coop_launch_kpt(const float *g, float *err, uint8_t *sym, int64_t n,
                            gamma, fmt, counts, slots, spin_limit, status);
 }
 
-// The form with KL runs per wavefront in LDS (more than the 64 KiB a kernel gets without asking).
+// A kernel that wants more LDS than it gets without asking: asked for once per device (the flag array is the
+// caller's, one per kernel).
+#define CP_MAX_DEVICES 64
+static hipError_t coop_allow_lds(const void *kernel, int bytes, std::atomic<int> (&asked)[CP_MAX_DEVICES])
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= CP_MAX_DEVICES) return hipErrorInvalidDevice;
+    if (asked[dev].load(std::memory_order_acquire)) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess) asked[dev].store(1, std::memory_order_release);
+    return e;
+}
+
+// The form with KL runs per wavefront in LDS.
 template <int KL>
 static hipError_t coop_launch_big(const float *g, float *err, uint8_t *sym, int64_t n, int U, int64_t stride, int grid,
                                   int32_t *anchor, float gamma, co3_fmt fmt, uint32_t *counts, uint32_t *slots,
                                   uint32_t spin_limit, int32_t *status, int sym_nib, hipStream_t st)
 {
-    static std::atomic<int> lds_set{0};
-    if (!lds_set.load(std::memory_order_acquire)) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_coop_convert_big<KL, true>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, CP_BIG_LDS_BYTES(KL));
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_coop_convert_big<KL, false>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, CP_BIG_LDS_BYTES(KL));
-        if (e != hipSuccess) return e;
-        lds_set.store(1, std::memory_order_release);
-    }
+    static std::atomic<int> asked[2][CP_MAX_DEVICES];     // zero-initialised
+    const void *kernel = sym_nib ? reinterpret_cast<const void *>(k_coop_convert_big<KL, true>)
+                                 : reinterpret_cast<const void *>(k_coop_convert_big<KL, false>);
+    const hipError_t e = coop_allow_lds(kernel, CP_BIG_LDS_BYTES(KL), asked[sym_nib ? 1 : 0]);
+    if (e != hipSuccess) return e;
     if (sym_nib)
         hipLaunchKernelGGL((k_coop_convert_big<KL, true>), dim3(grid), dim3(CP_BLOCK), CP_BIG_LDS_BYTES(KL), st, g, err, sym, n,
                            stride, U, anchor, gamma, fmt, counts, slots, spin_limit, status);
@@ -876,25 +886,22 @@ static hipError_t coop_launch_big(const float *g, float *err, uint8_t *sym, int6
 }
 
 template <int KPT>
-static void coop_launch_segs(const float *g, float *err, uint8_t *sym, int64_t n, int U, int64_t stride, int grid,
+static hipError_t coop_launch_segs(const float *g, float *err, uint8_t *sym, int64_t n, int U, int64_t stride, int grid,
                              const int64_t *seg_off, int nseg, int32_t *anchor, float gamma, co3_fmt fmt, uint32_t *counts,
                              uint32_t *slots, uint32_t *tmax, uint32_t spin_limit, int32_t *status, int sym_nib, hipStream_t st)
 {
-    static std::atomic<int> lds_set{0};              // (more LDS than a kernel gets without asking)
-    if (!lds_set.load(std::memory_order_acquire)) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(k_coop_convert_segs<KPT, true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, CP_SEGS_LDS_BYTES(KPT)) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void *>(k_coop_convert_segs<KPT, false>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, CP_SEGS_LDS_BYTES(KPT)) != hipSuccess)
-            return;                                      // (the launch below then reports the error)
-        lds_set.store(1, std::memory_order_release);
-    }
+    static std::atomic<int> asked[2][CP_MAX_DEVICES];     // zero-initialised
+    const void *kernel = sym_nib ? reinterpret_cast<const void *>(k_coop_convert_segs<KPT, true>)
+                                 : reinterpret_cast<const void *>(k_coop_convert_segs<KPT, false>);
+    const hipError_t e = coop_allow_lds(kernel, CP_SEGS_LDS_BYTES(KPT), asked[sym_nib ? 1 : 0]);
+    if (e != hipSuccess) return e;
     if (sym_nib)
         hipLaunchKernelGGL((k_coop_convert_segs<KPT, true>), dim3(grid), dim3(CP_BLOCK), CP_SEGS_LDS_BYTES(KPT), st, g, err, sym, n,
                            stride, U, seg_off, nseg, anchor, gamma, fmt, counts, slots, tmax, spin_limit, status);
     else
         hipLaunchKernelGGL((k_coop_convert_segs<KPT, false>), dim3(grid), dim3(CP_BLOCK), CP_SEGS_LDS_BYTES(KPT), st, g, err, sym, n,
                            stride, U, seg_off, nseg, anchor, gamma, fmt, counts, slots, tmax, spin_limit, status);
+    return hipGetLastError();
 }
 
 // `tmax`: U * nseg zero words (nseg > 1 only).  seg_off == nullptr or nseg == 1: one anchor per user.
@@ -908,9 +915,8 @@ hipError_t co3_launch_coop_convert(const float *g, float *err, uint8_t *sym, int
         Co3LaunchTimer tm(CO3_K_COOP, st);
 #define CO3_COOP_SEGS_CASE(KPT)                                                                                    \
     case KPT:                                                                                                      \
-        coop_launch_segs<KPT>(g, err, sym, n, U, stride, grid, seg_off, nseg, anchor, gamma, fmt, counts, slots, tmax,   \
-                              spin_limit, status, sym_nib, st);                                                    \
-        break
+        return coop_launch_segs<KPT>(g, err, sym, n, U, stride, grid, seg_off, nseg, anchor, gamma, fmt, counts, slots,  \
+                                     tmax, spin_limit, status, sym_nib, st)
         switch (kpt) {
             CO3_COOP_SEGS_CASE(1);
             CO3_COOP_SEGS_CASE(4);
