@@ -361,7 +361,7 @@ int32_t co3_convert_encode_layers(const float *g, float *err, int64_t n, int32_t
  * What the one call adds is that it may keep data on the chip between the steps: where a user's
  * gradient fits the register files of the device (with one anchor per user, nseg = 1, for the larger
  * vectors with a part of it in LDS: n up to 98,304 elements per compute unit, 25.1 M on 256 units;
- * with several tensors per user up to 65,536 elements per compute unit, 511 tensors and three users),
+ * with several tensors per user up to 65,536 elements per compute unit, 511 tensors and six users),
  * a single resident grid reads every gradient once, taking the largest magnitudes and converting from
  * the chip, the workgroups exchanging their maxima through words in the workspace; other batches run
  * the separate kernels of the three calls.

@@ -297,9 +297,11 @@ void co3_set_exchange_spin_limit(int64_t polls)
 // caller passes no array for them, and, where the resident grid serves the batch, its exchange words
 // [U][workgroups] u32 and partial count tables [CO3_COOP_COUNT_REPS][U][K] u32.
 // Several tensors per user: the resident grid pays an exchange of the tensors' maxima per user, which the
-// separate kernels do not; measured on 62 tensors of 11.2 M elements it wins up to three users (one user:
-// 50 us against 68), beyond that the separate kernels do.
-#define CO3_COOP_SEGS_MAX_USERS 3
+// separate kernels do not; measured on 62 tensors of 11.2 M elements (us, resident | separate): one user
+// 48 | 68, four 164 | 157, ten 392 | 380: 48 + 38 per further user against 68 + 35, so it is taken up to six.
+#ifndef CO3_COOP_SEGS_MAX_USERS
+#define CO3_COOP_SEGS_MAX_USERS 6
+#endif
 static bool user_encode_coop(int64_t n, int32_t U, int32_t nseg, int *kpt, int *grid)
 {
     const int cus = device_cus();

@@ -94,12 +94,15 @@ __device__ __forceinline__ const int64_t *co3_cache_segs(const int64_t *seg_off,
 
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
 {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) {
-        uint32_t t = (uint32_t)__shfl_xor((int)v, o, CO3_WAVE);
-        v = t > v ? t : v;
-    }
-    return v;
+    // row shifts and row broadcasts as in the scan below; a lane without a source takes 0, the identity here
+    auto step = [](uint32_t x, uint32_t y) { return x > y ? x : y; };
+    v = step(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, false));   // row_shr:1
+    v = step(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, false));   // row_shr:2
+    v = step(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, false));   // row_shr:4
+    v = step(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, false));   // row_shr:8
+    v = step(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xa, 0xf, false));   // row_bcast:15 -> rows 1, 3
+    v = step(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xc, 0xf, false));   // row_bcast:31 -> rows 2, 3
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, CO3_WAVE - 1);                        // the last lane holds the maximum
 }
 
 // Inclusive prefix sum across the 64 lanes of a wavefront with data-parallel-primitive moves:

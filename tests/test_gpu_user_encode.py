@@ -99,12 +99,13 @@ def test_one_call_zero_gradients_and_subnormal_maxima(co3):
 
 
 def test_one_call_with_tensors(co3):
-    """Several tensors per user, one anchor each: up to three users the resident grid (maxima per tensor through
+    """Several tensors per user, one anchor each: up to six users the resident grid (maxima per tensor through
     atomics, runs with a tensor boundary converted with an anchor per element), more users the separate kernels."""
     sizes = [10, 1, 4097, 64, 3, 20_000, 7, 128, 0, 5, 12_345]
     run_one_call(co3, 2, sum(sizes), co3.Fmt(4, 3), 256, betas=[0.8], T=2, sizes=sizes)
     run_one_call(co3, 2, sum(sizes), co3.Fmt(4, 3), 256, betas=[0.8], T=2, sizes=sizes, keep_symbols=False)
-    run_one_call(co3, 5, sum(sizes), co3.Fmt(4, 3), 256, betas=[0.8], T=2, sizes=sizes)
+    run_one_call(co3, 6, sum(sizes), co3.Fmt(4, 3), 256, betas=[0.8], T=2, sizes=sizes)
+    run_one_call(co3, 9, sum(sizes), co3.Fmt(4, 3), 256, betas=[0.8], T=2, sizes=sizes)
 
 
 def tensor_sizes(total, seed):
