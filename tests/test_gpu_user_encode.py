@@ -147,15 +147,20 @@ def test_one_call_deterministic(co3):
     assert torch.equal(a.words, b.words) and torch.equal(a.err, b.err) and torch.equal(a.avg, b.avg)
 
 
-def test_a_wait_that_runs_out_is_reported_and_the_kernel_ends(co3):
-    """No poll allowed: every exchange of the resident grid runs out at once.  The call must come back with
-    CO3_ETIMEOUT in the status word, having written nothing out of bounds (canaries), and the next call works."""
+@pytest.mark.parametrize("kind,n,sizes", [("one tensor", 300_000, None), ("tensors", 300_000, [100_000, 7, 150_000, 0, 49_993]),
+                                          ("long vector", 17_000_003, None)])
+def test_a_wait_that_runs_out_is_reported_and_the_kernel_ends(co3, kind, n, sizes):
+    """No poll allowed: every exchange of the resident grid runs out at once (in each of its forms: one anchor per
+    user, one per tensor, part of the gradient in LDS).  The call must come back with CO3_ETIMEOUT in the status
+    word, having written nothing out of bounds (canaries), and the next call works."""
     B = co3.binding
     fmt = co3.Fmt(3, 0)
-    U, n = 2, 300_000
-    pipe = co3.Co3Pipeline(U, n, fmt, chunk_syms=256, one_call=True)
+    U = 2
+    assert sizes is None or sum(sizes) == n
+    pipe = co3.Co3Pipeline(U, n, fmt, chunk_syms=256, one_call=True, seg_off=None if sizes is None else inp.seg_offsets(sizes))
     g = pipe.new_gradient_buffer()
-    g[:, :n] = torch.from_numpy(np.stack([inp.gennorm(inp.rng_for(97, 0, u, 1), n, 1.0, 1e-3) for u in range(U)])).cuda()
+    for u in range(U):
+        g[u, :n] = inp.device_gennorm(n, 1.0, 1e-3, 40 + u)
     pad = pipe.err[:, n:].clone()
     try:
         B.set_exchange_spin_limit(0)
